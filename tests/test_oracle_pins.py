@@ -1,0 +1,407 @@
+"""Pins for the CPU oracle (no GPU needed).
+
+The paper prints no worked numeric example, so the oracle is pinned to what the
+mathematics fixes: closed forms at w = 0, finite differences, an explicitly built
+dense Hessian, a brute-force Newton minimiser written with numpy only, decoupled
+special cases with scalar closed forms, ridge normal equations, CG facts on an
+explicit SPD system, and layout (CSR vs dense) agreement.
+"""
+import numpy as np
+import pytest
+
+import oracle as orc
+from oracle import LOSS_LR, LOSS_L2SVM, Oracle
+
+
+# ----------------------------------------------------------------------------
+# small random problems (dense arrays; CSR built from them when needed)
+# ----------------------------------------------------------------------------
+def _dense_problem(rng, n, d, density=1.0):
+    X = rng.standard_normal((n, d))
+    if density < 1.0:
+        X *= rng.random((n, d)) < density
+    y = np.where(rng.random(n) < 0.5, 1.0, -1.0)
+    return X, y
+
+
+def _to_csr(X):
+    n, d = X.shape
+    rowptr = np.zeros(n + 1, dtype=np.int64)
+    cols, vals = [], []
+    for i in range(n):
+        nz = np.nonzero(X[i])[0]
+        cols.append(nz.astype(np.int32))
+        vals.append(X[i, nz])
+        rowptr[i + 1] = rowptr[i] + len(nz)
+    return rowptr, np.concatenate(cols) if cols else np.zeros(0, np.int32), \
+        np.concatenate(vals) if vals else np.zeros(0)
+
+
+def _f_numpy(X, y, w, loss, C):
+    """Objective written with library routines only (logaddexp / maximum)."""
+    t = y * (X @ w)
+    if loss == LOSS_LR:
+        return 0.5 * w @ w + C * np.sum(np.logaddexp(0.0, -t))
+    return 0.5 * w @ w + C * np.sum(np.maximum(0.0, 1.0 - t) ** 2)
+
+
+# ----------------------------------------------------------------------------
+# closed forms at w = 0  (Table 1 evaluated at z = 0)
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("layout", ["dense", "csr"])
+def test_closed_forms_at_zero(rng, layout):
+    n, d, C = 300, 17, 0.7
+    X, y = _dense_problem(rng, n, d, density=0.4 if layout == "csr" else 1.0)
+    if layout == "csr":
+        rp, col, val = _to_csr(X)
+        o = Oracle(n=n, d=d, y=y, rowptr=rp, col=col, val=val)
+    else:
+        o = Oracle(n=n, d=d, y=y, X=X)
+    w0 = np.zeros(d)
+    v = rng.standard_normal(d)
+
+    f, g, D = o.fun_grad(LOSS_LR, C, w0)
+    assert f == pytest.approx(C * n * np.log(2.0), rel=1e-14)
+    np.testing.assert_allclose(g, -(C / 2.0) * (X.T @ y), rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(D, 0.25, rtol=0, atol=0)
+    np.testing.assert_allclose(o.hv(C, D, v), v + (C / 4.0) * (X.T @ (X @ v)), rtol=1e-12, atol=1e-12)
+
+    f, g, D = o.fun_grad(LOSS_L2SVM, C, w0)
+    assert f == pytest.approx(C * n, rel=1e-15)
+    np.testing.assert_allclose(g, -2.0 * C * (X.T @ y), rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(D, 2.0, rtol=0, atol=0)
+    np.testing.assert_allclose(o.hv(C, D, v), v + 2.0 * C * (X.T @ (X @ v)), rtol=1e-12, atol=1e-12)
+
+
+# ----------------------------------------------------------------------------
+# objective against the library-routine definition, including huge margins
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("loss", [LOSS_LR, LOSS_L2SVM])
+def test_objective_matches_definition(rng, loss):
+    n, d, C = 200, 9, 1.3
+    X, y = _dense_problem(rng, n, d)
+    o = Oracle(n=n, d=d, y=y, X=X)
+    for scale in (0.0, 0.1, 1.0, 30.0):
+        w = scale * rng.standard_normal(d)
+        f, z, zhat, D = o.fun(loss, C, w)
+        np.testing.assert_allclose(z, X @ w, rtol=1e-13, atol=1e-13)
+        assert f == pytest.approx(_f_numpy(X, y, w, loss, C), rel=1e-13)
+
+
+def test_lr_terms_extreme_margins():
+    # one instance, one feature: z = w, so the margin is set directly
+    for t in (-745.0, -700.0, -40.0, -1e-300, 0.0, 1e-300, 40.0, 700.0, 745.0):
+        for yi in (1.0, -1.0):
+            o = Oracle(n=1, d=1, y=[yi], X=[[1.0]])
+            w = np.array([t * yi])
+            f, z, zhat, D = o.fun(LOSS_LR, 1.0, w)
+            assert np.isfinite([f, zhat[0], D[0]]).all()
+            h = 0.5 * (1.0 + np.tanh(0.5 * t))  # h(t) via tanh: a different route to the sigmoid
+            assert f - 0.5 * t * t == pytest.approx(np.logaddexp(0.0, -t), rel=1e-12, abs=1e-300) or t * t > 1e3
+            assert zhat[0] == pytest.approx((h - 1.0) * yi, rel=1e-9, abs=1e-300) or abs(t) > 30
+            assert 0.0 <= D[0] <= 0.25
+            if abs(t) <= 30:
+                assert D[0] == pytest.approx(h * (1.0 - h), rel=1e-9)
+    # symmetric tails: D(t) = D(-t), zhat(-t)*y + zhat(t)*y = -1
+    o = Oracle(n=2, d=1, y=[1.0, 1.0], X=[[1.0], [-1.0]])
+    _, _, zhat, D = o.fun(LOSS_LR, 1.0, np.array([37.5]))
+    assert D[0] == pytest.approx(D[1], rel=1e-14)
+    assert zhat[0] + zhat[1] == pytest.approx(-1.0, rel=1e-15)
+
+
+# ----------------------------------------------------------------------------
+# gradient: central finite differences of f
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("loss", [LOSS_LR, LOSS_L2SVM])
+def test_gradient_finite_difference(rng, loss):
+    n, d, C = 150, 12, 0.9
+    X, y = _dense_problem(rng, n, d)
+    o = Oracle(n=n, d=d, y=y, X=X)
+    w = 0.3 * rng.standard_normal(d)
+    _, g, _ = o.fun_grad(loss, C, w)
+    for _ in range(5):
+        u = rng.standard_normal(d)
+        u /= np.linalg.norm(u)
+        h = 1e-5
+        fp = _f_numpy(X, y, w + h * u, loss, C)
+        fm = _f_numpy(X, y, w - h * u, loss, C)
+        assert g @ u == pytest.approx((fp - fm) / (2 * h), rel=2e-7, abs=1e-7)
+
+
+# ----------------------------------------------------------------------------
+# Hessian-vector product: finite differences of the gradient, explicit dense H
+# ----------------------------------------------------------------------------
+def test_hv_lr_finite_difference(rng):
+    n, d, C = 120, 10, 1.1
+    X, y = _dense_problem(rng, n, d)
+    o = Oracle(n=n, d=d, y=y, X=X)
+    w = 0.4 * rng.standard_normal(d)
+    _, _, D = o.fun_grad(LOSS_LR, C, w)
+    v = rng.standard_normal(d)
+    h = 1e-5
+    gp = o.fun_grad(LOSS_LR, C, w + h * v)[1]
+    gm = o.fun_grad(LOSS_LR, C, w - h * v)[1]
+    np.testing.assert_allclose(o.hv(C, D, v), (gp - gm) / (2 * h), rtol=1e-6, atol=1e-6)
+
+
+def test_hv_svm_finite_difference_away_from_kinks(rng):
+    n, d, C = 120, 10, 0.6
+    X, y = _dense_problem(rng, n, d)
+    o = Oracle(n=n, d=d, y=y, X=X)
+    w = 0.4 * rng.standard_normal(d)
+    v = rng.standard_normal(d)
+    h = 1e-6
+    slack = np.abs(1.0 - y * (X @ w))
+    assert slack.min() > h * np.abs(X @ v).max()  # no instance crosses the hinge
+    _, _, D = o.fun_grad(LOSS_L2SVM, C, w)
+    gp = o.fun_grad(LOSS_L2SVM, C, w + h * v)[1]
+    gm = o.fun_grad(LOSS_L2SVM, C, w - h * v)[1]
+    # the objective is piecewise quadratic, so the difference quotient is exact up to rounding
+    np.testing.assert_allclose(o.hv(C, D, v), (gp - gm) / (2 * h), rtol=1e-8, atol=1e-8)
+
+
+@pytest.mark.parametrize("loss", [LOSS_LR, LOSS_L2SVM])
+def test_hv_against_explicit_hessian(rng, loss):
+    n, d, C = 180, 14, 0.8
+    X, y = _dense_problem(rng, n, d)
+    o = Oracle(n=n, d=d, y=y, X=X)
+    w = 0.5 * rng.standard_normal(d)
+    _, _, D = o.fun_grad(loss, C, w)
+    t = y * (X @ w)
+    if loss == LOSS_LR:
+        h = 1.0 / (1.0 + np.exp(-t))
+        H = np.eye(d) + C * X.T @ (X * (h * (1 - h))[:, None])
+    else:
+        act = (1.0 - t) > 0
+        assert 0 < act.sum() < n  # both active and inactive rows are present
+        H = np.eye(d) + 2.0 * C * X[act].T @ X[act]
+    u, v = rng.standard_normal(d), rng.standard_normal(d)
+    Hu, Hv = o.hv(C, D, u), o.hv(C, D, v)
+    np.testing.assert_allclose(Hv, H @ v, rtol=1e-12, atol=1e-12)
+    assert u @ Hv == pytest.approx(v @ Hu, rel=1e-13)       # symmetry
+    assert v @ Hv >= v @ v                                    # H >= I
+
+
+def test_svm_tie_is_inactive():
+    # y z = 1 exactly: strict inequality in the active-set definition -> inactive
+    o = Oracle(n=3, d=1, y=[1.0, -1.0, 1.0], X=[[1.0], [-1.0], [0.5]])
+    f, z, zhat, D = o.fun(LOSS_L2SVM, 1.0, np.array([1.0]))
+    np.testing.assert_array_equal(D, [0.0, 0.0, 2.0])
+    np.testing.assert_array_equal(zhat, [0.0, 0.0, 2.0 * (0.5 - 1.0)])
+    assert f == pytest.approx(0.5 + 0.25)
+
+
+# ----------------------------------------------------------------------------
+# layouts agree
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("loss", [LOSS_LR, LOSS_L2SVM])
+def test_csr_and_dense_agree(rng, loss):
+    n, d, C = 250, 40, 1.0
+    X, y = _dense_problem(rng, n, d, density=0.2)
+    X[7] = 0.0  # an empty row
+    X[:, 11] = 0.0  # an empty column
+    rp, col, val = _to_csr(X)
+    od = Oracle(n=n, d=d, y=y, X=X)
+    os_ = Oracle(n=n, d=d, y=y, rowptr=rp, col=col, val=val)
+    w = 0.5 * rng.standard_normal(d)
+    v = rng.standard_normal(d)
+    fd, gd, Dd = od.fun_grad(loss, C, w)
+    fs, gs, Ds = os_.fun_grad(loss, C, w)
+    assert fd == pytest.approx(fs, rel=1e-14)
+    np.testing.assert_allclose(gd, gs, rtol=1e-13, atol=1e-14)
+    np.testing.assert_allclose(Dd, Ds, rtol=1e-13, atol=0)
+    np.testing.assert_allclose(od.hv(C, Dd, v), os_.hv(C, Ds, v), rtol=1e-13, atol=1e-14)
+    rd = od.tron(loss, C, 1e-6)
+    rs = os_.tron(loss, C, 1e-6)
+    assert rd.outer_iters == rs.outer_iters and rd.cg_iters_total == rs.cg_iters_total
+    assert rd.f == pytest.approx(rs.f, rel=1e-13)
+
+
+# ----------------------------------------------------------------------------
+# CG on an explicit SPD system
+# ----------------------------------------------------------------------------
+def _explicit_system(rng, n=60, d=8, C=0.9):
+    X, y = _dense_problem(rng, n, d)
+    o = Oracle(n=n, d=d, y=y, X=X)
+    w = 0.3 * rng.standard_normal(d)
+    _, g, D = o.fun_grad(LOSS_LR, C, w)
+    H = np.eye(d) + C * X.T @ (X * D[:, None])
+    return o, C, D, g, H
+
+
+def test_cg_unconstrained_solves_newton_system(rng):
+    o, C, D, g, H = _explicit_system(rng)
+    d = len(g)
+    s, r, nhv, onb = o.cg(C, D, g, delta=1e30, xi=1e-14, max_cg=d)
+    assert not onb and nhv <= d
+    np.testing.assert_allclose(s, np.linalg.solve(H, -g), rtol=1e-9, atol=1e-12)
+    np.testing.assert_allclose(r, -g - H @ s, rtol=0, atol=1e-12)
+
+
+def test_cg_residuals_are_orthogonal(rng):
+    o, C, D, g, H = _explicit_system(rng)
+    # residual after k products, for k = 1..4, by capping max_cg
+    res = [o.cg(C, D, g, delta=1e30, xi=0.0, max_cg=k)[1] for k in range(1, 5)]
+    res = [-g] + res
+    for a in range(len(res)):
+        for b in range(a):
+            cosang = res[a] @ res[b] / (np.linalg.norm(res[a]) * np.linalg.norm(res[b]))
+            assert abs(cosang) < 1e-10
+
+
+def test_cg_boundary_step(rng):
+    o, C, D, g, H = _explicit_system(rng)
+    newton = np.linalg.solve(H, -g)
+    delta = 0.3 * np.linalg.norm(newton)
+    s, r, nhv, onb = o.cg(C, D, g, delta=delta, xi=1e-12, max_cg=50)
+    assert onb
+    assert np.linalg.norm(s) == pytest.approx(delta, rel=1e-14)
+    np.testing.assert_allclose(r, -g - H @ s, rtol=0, atol=1e-12)
+    q = lambda u: g @ u + 0.5 * u @ H @ u
+    # Cauchy point: minimiser of q along -g inside the region
+    tc = min((g @ g) / (g @ H @ g), delta / np.linalg.norm(g))
+    assert q(s) <= q(-tc * g) + 1e-14
+    # first step from s = 0 along -g: a tiny radius must give exactly -delta g/|g|
+    s1, _, n1, onb1 = o.cg(C, D, g, delta=1e-3 * np.linalg.norm(g) / np.linalg.norm(H, 2), xi=1e-12, max_cg=50)
+    assert onb1 and n1 == 1
+    np.testing.assert_allclose(s1 / np.linalg.norm(s1), -g / np.linalg.norm(g), rtol=1e-12, atol=1e-14)
+
+
+def test_cg_stops_on_relative_residual(rng):
+    o, C, D, g, H = _explicit_system(rng)
+    s, r, nhv, onb = o.cg(C, D, g, delta=1e30, xi=0.1, max_cg=100)
+    assert np.linalg.norm(r) <= 0.1 * np.linalg.norm(g)
+    if nhv > 1:  # one fewer product would not have met the test
+        r_prev = o.cg(C, D, g, delta=1e30, xi=0.0, max_cg=nhv - 1)[1]
+        assert np.linalg.norm(r_prev) > 0.1 * np.linalg.norm(g)
+
+
+# ----------------------------------------------------------------------------
+# full solves
+# ----------------------------------------------------------------------------
+def _newton_minimise(X, y, loss, C, tol=1e-12, iters=200):
+    """Brute force: explicit Hessian, linear solve, backtracking; numpy only."""
+    n, d = X.shape
+    w = np.zeros(d)
+
+    def grad_hess(w):
+        t = y * (X @ w)
+        if loss == LOSS_LR:
+            h = 0.5 * (1.0 + np.tanh(0.5 * t))
+            g = w + C * X.T @ ((h - 1.0) * y)
+            H = np.eye(d) + C * X.T @ (X * (h * (1 - h))[:, None])
+        else:
+            act = (1.0 - t) > 0
+            g = w + 2.0 * C * X[act].T @ (X[act] @ w - y[act])
+            H = np.eye(d) + 2.0 * C * X[act].T @ X[act]
+        return g, H
+
+    for _ in range(iters):
+        g, H = grad_hess(w)
+        if np.linalg.norm(g) <= tol:
+            break
+        step = np.linalg.solve(H, -g)
+        f0, a = _f_numpy(X, y, w, loss, C), 1.0
+        while _f_numpy(X, y, w + a * step, loss, C) > f0 + 1e-4 * a * (g @ step) and a > 1e-12:
+            a *= 0.5
+        w = w + a * step
+    return w, np.linalg.norm(grad_hess(w)[0])
+
+
+@pytest.mark.parametrize("loss", [LOSS_LR, LOSS_L2SVM])
+@pytest.mark.parametrize("shape", [(80, 6), (200, 20)])
+def test_tron_matches_brute_force_newton(rng, loss, shape):
+    n, d = shape
+    C = 1.0
+    X, y = _dense_problem(rng, n, d)
+    w_star, gn = _newton_minimise(X, y, loss, C)
+    assert gn <= 1e-10
+    res = Oracle(n=n, d=d, y=y, X=X).tron(loss, C, eps=1e-10)
+    assert res.converged
+    assert np.linalg.norm(res.w - w_star) <= 1e-8 * np.linalg.norm(w_star)
+    assert res.f == pytest.approx(_f_numpy(X, y, w_star, loss, C), rel=1e-12)
+
+
+def test_tron_identity_features_closed_form(rng):
+    # X = I: the problem decouples into n scalar problems
+    n, C = 25, 0.8
+    y = np.where(rng.random(n) < 0.5, 1.0, -1.0)
+    o = Oracle(n=n, d=n, y=y, X=np.eye(n))
+    res = o.tron(LOSS_L2SVM, C, eps=1e-12)
+    np.testing.assert_allclose(res.w, 2 * C * y / (1 + 2 * C), rtol=1e-10)
+    # LR: w_i = y_i a with a solving a = C (1 - h(a)); bisection on [0, C]
+    lo, hi = 0.0, C
+    for _ in range(200):
+        a = 0.5 * (lo + hi)
+        if a - C * (1.0 - 1.0 / (1.0 + np.exp(-a))) > 0:
+            hi = a
+        else:
+            lo = a
+    res = o.tron(LOSS_LR, C, eps=1e-12)
+    np.testing.assert_allclose(res.w, y * a, rtol=1e-9)
+
+
+def test_tron_all_active_svm_is_ridge(rng):
+    # small C keeps |w| small, so every margin stays below 1: ridge normal equations
+    n, d, C = 300, 10, 1e-3
+    X, y = _dense_problem(rng, n, d)
+    res = Oracle(n=n, d=d, y=y, X=X).tron(LOSS_L2SVM, C, eps=1e-12)
+    assert np.all(y * (X @ res.w) < 1.0)
+    w_ridge = np.linalg.solve(np.eye(d) + 2 * C * X.T @ X, 2 * C * X.T @ y)
+    np.testing.assert_allclose(res.w, w_ridge, rtol=1e-9, atol=1e-12)
+
+
+@pytest.mark.parametrize("loss", [LOSS_LR, LOSS_L2SVM])
+def test_tron_invariants(rng, loss):
+    n, d, C, eps = 400, 60, 2.0, 1e-2
+    X, y = _dense_problem(rng, n, d, density=0.3)
+    rp, col, val = _to_csr(X)
+    o = Oracle(n=n, d=d, y=y, rowptr=rp, col=col, val=val)
+    res = o.tron(loss, C, eps)
+    assert res.converged and res.status == 0
+    # stationarity, re-evaluated from scratch with numpy
+    t = y * (X @ res.w)
+    if loss == LOSS_LR:
+        g = res.w + C * X.T @ ((0.5 * (1 + np.tanh(0.5 * t)) - 1.0) * y)
+        g0 = -(C / 2) * X.T @ y
+    else:
+        act = (1 - t) > 0
+        g = res.w + 2 * C * X[act].T @ (X[act] @ res.w - y[act])
+        g0 = -2 * C * X.T @ y
+    assert res.gnorm0 == pytest.approx(np.linalg.norm(g0), rel=1e-12)
+    assert np.linalg.norm(g) <= eps * np.linalg.norm(g0)
+    assert res.gnorm == pytest.approx(np.linalg.norm(g), rel=1e-9)
+    assert res.f == pytest.approx(_f_numpy(X, y, res.w, loss, C), rel=1e-13)
+    # accepted steps decrease f; rejected ones leave it alone; counts are consistent
+    f_prev = _f_numpy(X, y, np.zeros(d), loss, C)
+    for rec in res.trace:
+        if rec["accepted"]:
+            assert rec["f"] < f_prev
+        else:
+            assert rec["f"] == f_prev
+        f_prev = rec["f"]
+        assert rec["pred"] > 0 and rec["snorm"] > 0
+    assert sum(r["cg_iters"] for r in res.trace) == res.cg_iters_total == res.n_hv
+    assert res.n_fun == 1 + res.outer_iters
+    assert res.n_grad == 1 + sum(r["accepted"] for r in res.trace)
+    # strong convexity (modulus 1): f(w_eps) - f* <= |g|^2 / 2
+    tight = o.tron(loss, C, 1e-9)
+    assert 0.0 <= res.f - tight.f <= 0.5 * (eps * res.gnorm0) ** 2
+
+
+def test_tron_warm_start_uses_gradient_at_zero(rng):
+    n, d, C = 150, 8, 1.0
+    X, y = _dense_problem(rng, n, d)
+    o = Oracle(n=n, d=d, y=y, X=X)
+    cold = o.tron(LOSS_LR, C, 1e-8)
+    warm = o.tron(LOSS_LR, C, 1e-8, w0=cold.w)
+    assert warm.gnorm0 == pytest.approx(cold.gnorm0, rel=1e-14)
+    assert warm.outer_iters == 0 and warm.converged
+    np.testing.assert_array_equal(warm.w, cold.w)
+
+
+def test_tron_respects_iteration_cap(rng):
+    n, d = 200, 15
+    X, y = _dense_problem(rng, n, d)
+    res = Oracle(n=n, d=d, y=y, X=X).tron(LOSS_LR, 10.0, 1e-12, max_outer=2)
+    assert res.status == 1 and not res.converged and res.outer_iters == 2
