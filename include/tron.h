@@ -1,0 +1,195 @@
+/*
+ * tron.h -- C ABI of the MI355X (gfx950) trust-region Newton hot path for
+ * L2-regularised logistic regression and the L2-loss SVM.
+ *
+ * Method: Halloran & Rocke, "GPU-Accelerated Primal Learning for Extremely Fast
+ * Large-Scale Classification" (Section 3, Table 1, Algorithm 1, Appendices B, D, E).
+ *
+ * Notation used throughout: n = instances (rows of X), d = features, X is n-by-d,
+ * y in {-1,+1}^n, z = X w.  (The paper writes l for instances and n for features.)
+ *
+ *   f(w)  = 1/2 w.w + C sum_i loss(y_i z_i)                 (Section 3, Eq. 1; Appendix B)
+ *   g(w)  = w + C X^T zhat                                  (Table 1)
+ *   H(w)v = v + C X^T ( D (X v) )                           (Table 1, Appendix B, D)
+ *
+ *   logistic: loss = log(1+exp(-y z)), zhat_i = (h(y_i z_i)-1) y_i, D_ii = h(1-h),
+ *             h(t) = 1/(1+exp(-t))                          (Appendix E)
+ *   L2-SVM:   loss = max(0, 1-y z)^2, I = {i : 1 - y_i z_i > 0} (strict),
+ *             zhat_i = 2 (z_i - y_i) on I else 0, D_ii = 2 on I else 0, which is the
+ *             paper's  w + 2C X_I^T (z_I - y_I)  and  v + 2C X_I^T X_I v.
+ *
+ * General rules
+ *   - Every function returns an int status: TRON_OK (0), a negative error, or the
+ *     positive soft status TRON_EMAXITER.  Nothing throws or aborts across the ABI.
+ *     After an error, tron_last_error() (thread-local) describes it.
+ *   - "device pointer" = HIP device memory on the handle's GPU, caller-owned, fp64,
+ *     never retained after the call returns.  "host pointer" = ordinary host memory.
+ *   - All GPU work is enqueued on the hipStream_t given at dataset creation (pass the
+ *     stream as void*; NULL = the default stream).  A call that returns a host scalar
+ *     synchronises that stream before returning; one that does not, does not.
+ *   - A handle is not thread-safe; distinct handles are independent.
+ *   - All arithmetic is fp64.  Reductions are two-stage and atomic-free, so repeated
+ *     calls with the same inputs return bit-identical results.
+ *   - There is no CPU fallback: without a usable GPU every call returns TRON_EDEVICE.
+ */
+#ifndef TRON_H_
+#define TRON_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TRON_API __attribute__((visibility("default")))
+
+typedef struct tron_dataset tron_dataset; /* opaque: device copies of X (and X^T for CSR), y, cached D, work space */
+
+enum { TRON_LOSS_LR = 0, TRON_LOSS_L2SVM = 1 };
+enum {
+    TRON_OK = 0,
+    TRON_EINVAL = -1,   /* bad argument or malformed input */
+    TRON_ENOMEM = -2,   /* host or device allocation failed */
+    TRON_EDEVICE = -3,  /* HIP runtime error / no device */
+    TRON_ESTATE = -4,   /* call order violated (e.g. tron_hv before tron_fun_grad) */
+    TRON_EMAXITER = 1   /* soft: iteration limit or stall; outputs hold the last iterate */
+};
+enum { TRON_MEM_HOST = 0, TRON_MEM_DEVICE = 1 };
+
+/* ------------------------------------------------------------------------------------------
+ * Dataset handles (the problem statement of Section 3: X = [x_1 ... x_l]^T and y).
+ * The library copies X and y (the caller may free its buffers on return) and, for CSR,
+ * builds the explicit transposed copy used by X^T products (Table 1: X^T zhat, X^T(D(Xv))).
+ * ------------------------------------------------------------------------------------------ */
+
+/*
+ * CSR input: rowptr int64[n+1] (rowptr[0] = 0, non-decreasing, rowptr[n] = nnz), col int32[nnz]
+ * (inside each row strictly increasing and in [0,d)), val fp64[nnz] (finite), y fp64[n]
+ * (exactly +1.0 or -1.0).  mem says whether the four arrays are host or device pointers (all
+ * alike).  Validation failures return TRON_EINVAL and create nothing.  n, d >= 1; nnz may be 0;
+ * empty rows and columns are allowed.
+ */
+TRON_API int tron_dataset_create_csr(int64_t n, int64_t d, const int64_t *rowptr, const int32_t *col,
+                                     const double *val, const double *y, int mem, void *hip_stream,
+                                     tron_dataset **out);
+
+/* Dense input: X row-major n*d fp64 with leading dimension d, y fp64[n] in {+1,-1}. */
+TRON_API int tron_dataset_create_dense(int64_t n, int64_t d, const double *X_rowmajor, const double *y, int mem,
+                                       void *hip_stream, tron_dataset **out);
+
+/*
+ * Dense dataset filled in row chunks (for matrices too large to stage on the host at once):
+ * create_dense_empty allocates n*d on the device with undefined contents; write_rows copies
+ * nrows rows starting at row0 (X_chunk row-major nrows*d, y_chunk nrows; host or device per mem).
+ * Every row must be written once before the first compute call; this is not checked.
+ */
+TRON_API int tron_dataset_create_dense_empty(int64_t n, int64_t d, void *hip_stream, tron_dataset **out);
+TRON_API int tron_dataset_write_rows(tron_dataset *ds, int64_t row0, int64_t nrows, const double *X_chunk,
+                                     const double *y_chunk, int mem);
+
+/* Frees the device memory.  NULL is ignored. */
+TRON_API void tron_dataset_destroy(tron_dataset *ds);
+
+/* Shape query: any output pointer may be NULL.  nnz = n*d for dense handles. */
+TRON_API int tron_dataset_shape(const tron_dataset *ds, int64_t *n, int64_t *d, int64_t *nnz, int *is_dense);
+
+/* ------------------------------------------------------------------------------------------
+ * The three callbacks of Table 1.
+ * ------------------------------------------------------------------------------------------ */
+
+/*
+ * Function value and gradient at w (Algorithm 1 lines 2, 5, 7; Section 4.2; Appendix E):
+ *   z = X w;  per-instance loss, zhat, D;  *f_host = 1/2 w.w + C sum loss;  g = w + C X^T zhat.
+ * w_dev: device pointer, d doubles.  f_host: host pointer (required).  g_dev: device pointer to d
+ * doubles, or NULL for the function value only.  Side effect: D at w is cached in the handle and
+ * is what tron_hv uses until the next tron_fun_grad / tron_solve.  Synchronises the stream.
+ */
+TRON_API int tron_fun_grad(tron_dataset *ds, int loss, double C, const double *w_dev, double *f_host,
+                           double *g_dev);
+
+/*
+ * Hessian-vector product at the w of the last tron_fun_grad (Table 1; Appendix D):
+ *   a0 = X v;  a1 = D a0;  Hv = v + C X^T a1;  optionally *vHv_host = v.Hv (Appendix D: the
+ *   curvature scalar is reduced on the device).
+ * v_dev, Hv_dev: device pointers, d doubles, must not alias.  vHv_host: host pointer or NULL; when
+ * NULL the call only enqueues work and does not synchronise.  C must be the value the cached D
+ * belongs with (D itself does not depend on C).  TRON_ESTATE if no D is cached.
+ */
+TRON_API int tron_hv(tron_dataset *ds, double C, const double *v_dev, double *Hv_dev, double *vHv_host);
+
+/* ------------------------------------------------------------------------------------------
+ * Full solve: Algorithm 1 with the conjugate-gradient inner solver, all vectors on the device;
+ * only scalars reach the host.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct {
+    int loss;       /* TRON_LOSS_* */
+    double C;       /* > 0 */
+    double eps;     /* > 0: stop when |grad f(w)| <= eps |grad f(0)| */
+    int max_outer;  /* > 0 */
+    int max_cg;     /* > 0: cap on Hessian-vector products per outer iteration */
+    double cg_xi;   /* in (0,1): CG stops when |r| <= cg_xi |g| */
+} tron_params;
+
+typedef struct {
+    int iter;         /* outer iteration, from 1 */
+    int cg_iters;     /* Hessian-vector products of this iteration */
+    int accepted;     /* step taken */
+    int on_boundary;  /* CG ended on the trust-region boundary */
+    double f;         /* objective at the current w after this iteration */
+    double gnorm;     /* |grad f| at the current w */
+    double delta;     /* radius after the update */
+    double ared;      /* f(w) - f(w+s) */
+    double pred;      /* -q(s) */
+    double snorm;     /* |s| */
+} tron_trace_rec;
+
+typedef struct {
+    double f, gnorm, gnorm0;
+    int outer_iters, cg_iters_total, n_fun, n_grad, n_hv, converged;
+    int trace_cap;          /* in: capacity of trace (0 = none) */
+    int trace_len;          /* out: records written */
+    tron_trace_rec *trace;  /* in: host array of trace_cap records, or NULL */
+} tron_result;
+
+/*
+ * w_dev: device pointer, d doubles; in: starting point w0, out: final iterate.
+ * res_host: host pointer; set trace/trace_cap before the call.
+ * Rules (the paper names sigma_0 only; these are this library's reading of Algorithm 1):
+ *   Delta_0 = |g(w0)|;  accept iff sigma = ared/pred > 1e-4;  sigma < 1/4: Delta = min(|s|,Delta)/2;
+ *   sigma < 3/4: unchanged;  else Delta = min(4 Delta, max(Delta, 4|s|));  when |ared| and pred are
+ *   both below 1e-12 |f| sigma is taken as 1;  CG is Steihaug's truncated iteration.
+ * Returns TRON_OK when converged, TRON_EMAXITER when max_outer was reached or progress stalled.
+ * On return the handle caches D at the final iterate (so tron_hv may follow).
+ */
+TRON_API int tron_solve(tron_dataset *ds, const tron_params *params, double *w_dev, tron_result *res_host);
+
+/* ------------------------------------------------------------------------------------------
+ * Diagnostics.
+ * ------------------------------------------------------------------------------------------ */
+
+/* Message for the calling thread's most recent failure ("" if none).  Static storage. */
+TRON_API const char *tron_last_error(void);
+
+/*
+ * Per-kernel timing with HIP events on the handle's stream.  While enabled, every kernel the
+ * library launches for this handle is bracketed by an event pair.  tron_profile_read synchronises,
+ * adds up the elapsed time per kernel slot since the last reset, and fills up to `cap` entries of
+ * names[] (static strings), ms[] (total milliseconds) and calls[] (launch counts); it returns the
+ * number of slots in *count and resets the totals.
+ */
+TRON_API int tron_profile_enable(tron_dataset *ds, int on);
+TRON_API int tron_profile_read(tron_dataset *ds, int cap, const char **names, double *ms, int64_t *calls,
+                               int *count);
+
+/*
+ * Streaming-read probe: sums `count` doubles at src_dev with the library's reduction kernel,
+ * `reps` launches back to back, and returns the average milliseconds per launch measured with
+ * HIP events.  Used to report the attainable HBM read rate next to the nominal peak.
+ */
+TRON_API int tron_probe_read_bandwidth(const double *src_dev, int64_t count, int reps, void *hip_stream,
+                                       double *ms_per_launch, double *checksum);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TRON_H_ */

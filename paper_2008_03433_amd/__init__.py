@@ -1,0 +1,14 @@
+"""MI355X-native TRON hot path (function/gradient, Hessian-vector product, full solve) for
+L2-regularised logistic regression and the L2-loss SVM.
+
+The arithmetic lives in ``libtron_hip.so`` (hand-written HIP for gfx950 behind the C ABI of
+``include/tron.h``); this package is argument marshalling only.  PyTorch supplies device
+memory and the stream.  There is no CPU fallback: importing works anywhere, calling needs
+the built library and a GPU.
+"""
+from .binding import (  # noqa: F401
+    LOSS_LR, LOSS_L2SVM, TronError, Dataset, SolveResult, lib_path, load_library,
+    tron_dataset_create_csr, tron_dataset_create_dense, tron_dataset_create_dense_empty,
+    tron_dataset_write_rows, tron_dataset_destroy, tron_dataset_shape, tron_fun_grad, tron_hv,
+    tron_solve, tron_last_error, tron_profile_enable, tron_profile_read, tron_probe_read_bandwidth,
+)

@@ -1,0 +1,382 @@
+// C ABI entry points: dataset handles, argument checking, profiling, error text.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "common.h"
+
+namespace tron {
+
+// ------------------------------------------------------------------ errors
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+int hip_fail(hipError_t e, const char *what, const char *file, int line)
+{
+    const char *base = strrchr(file, '/');
+    set_error("HIP error %d (%s) in %s at %s:%d", (int)e, hipGetErrorString(e), what, base ? base + 1 : file, line);
+    return (e == hipErrorOutOfMemory) ? TRON_ENOMEM : TRON_EDEVICE;
+}
+
+// ------------------------------------------------------------------ profiler
+const char *const kSlotNames[SLOT_COUNT] = {
+    "spmv_fwd_z", "spmv_fwd_a1", "spmv_bwd_g", "spmv_bwd_hv", "spmv_fixup", "loss_terms",
+    "dense_fun_grad", "dense_hv", "dense_finalize", "dot", "reduce_final", "cg_vec"};
+
+int Profiler::begin(int slot, hipStream_t st)
+{
+    if (used == pool.size()) {
+        Rec r;
+        if (hipEventCreate(&r.a) != hipSuccess) return -1;
+        if (hipEventCreate(&r.b) != hipSuccess) { hipEventDestroy(r.a); return -1; }
+        r.slot = slot;
+        pool.push_back(r);
+    }
+    Rec &r = pool[used];
+    r.slot = slot;
+    if (hipEventRecord(r.a, st) != hipSuccess) return -1;
+    return (int)used++;
+}
+
+void Profiler::end(int idx, hipStream_t st) { hipEventRecord(pool[idx].b, st); }
+
+int Profiler::drain()
+{
+    for (size_t i = 0; i < used; ++i) {
+        Rec &r = pool[i];
+        TRON_HIP(hipEventSynchronize(r.b));
+        float t = 0.f;
+        TRON_HIP(hipEventElapsedTime(&t, r.a, r.b));
+        ms[r.slot] += t;
+        calls[r.slot] += 1;
+    }
+    used = 0;
+    return TRON_OK;
+}
+
+void Profiler::destroy()
+{
+    for (auto &r : pool) { hipEventDestroy(r.a); hipEventDestroy(r.b); }
+    pool.clear();
+    used = 0;
+}
+
+// ------------------------------------------------------------------ helpers
+static int check_device()
+{
+    int count = 0;
+    hipError_t e = hipGetDeviceCount(&count);
+    if (e != hipSuccess || count < 1) {
+        set_error("no usable HIP device (%s); this library has no CPU fallback", hipGetErrorString(e));
+        (void)hipGetLastError();
+        return TRON_EDEVICE;
+    }
+    return TRON_OK;
+}
+
+static int vec_grid_for(int64_t m)
+{
+    int64_t g = (m + kBlock * 4 - 1) / (kBlock * 4);
+    if (g < 1) g = 1;
+    if (g > kMaxGrid) g = kMaxGrid;
+    return (int)g;
+}
+
+static int alloc_common(tron_dataset *ds)
+{
+    const int64_t n = ds->n;
+    TRON_HIP(hipGetDevice(&ds->device));
+    TRON_HIP(hipMalloc(reinterpret_cast<void **>(&ds->y), sizeof(double) * n));
+    TRON_HIP(hipMalloc(reinterpret_cast<void **>(&ds->Dbuf[0]), sizeof(double) * n));
+    TRON_HIP(hipMalloc(reinterpret_cast<void **>(&ds->Dbuf[1]), sizeof(double) * n));
+    if (!ds->dense) {
+        TRON_HIP(hipMalloc(reinterpret_cast<void **>(&ds->z), sizeof(double) * n));
+        TRON_HIP(hipMalloc(reinterpret_cast<void **>(&ds->zhat), sizeof(double) * n));
+    }
+    int64_t need = 4 * (int64_t)kMaxGrid;
+    if (ds->dense) {
+        ds->dense_grid = dense_grid_for(ds->n, ds->d);
+        const int64_t dn = dense_partials_needed(ds->n, ds->d);
+        if (dn > need) need = dn;
+    }
+    ds->partials_len = need;
+    TRON_HIP(hipMalloc(reinterpret_cast<void **>(&ds->partials), sizeof(double) * need));
+    TRON_HIP(hipMalloc(reinterpret_cast<void **>(&ds->scal_dev), sizeof(double) * kScalars));
+    TRON_HIP(hipHostMalloc(reinterpret_cast<void **>(&ds->scal_host), sizeof(double) * kScalars, hipHostMallocDefault));
+    ds->vec_grid_n = vec_grid_for(ds->n);
+    ds->vec_grid_d = vec_grid_for(ds->d);
+    return TRON_OK;
+}
+
+static int check_labels(const double *y, int64_t n)
+{
+    for (int64_t i = 0; i < n; ++i)
+        if (!(y[i] == 1.0 || y[i] == -1.0)) {
+            set_error("y[%lld] = %g is not +1 or -1", (long long)i, y[i]);
+            return TRON_EINVAL;
+        }
+    return TRON_OK;
+}
+
+// host copies of caller arrays (from host or device memory)
+template <typename T>
+static int fetch(std::vector<T> &dst, const T *src, size_t count, int mem)
+{
+    try {
+        dst.resize(count);
+    } catch (const std::bad_alloc &) {
+        set_error("out of host memory staging %zu elements", count);
+        return TRON_ENOMEM;
+    }
+    if (!count) return TRON_OK;
+    if (mem == TRON_MEM_DEVICE)
+        TRON_HIP(hipMemcpy(dst.data(), src, sizeof(T) * count, hipMemcpyDeviceToHost));
+    else
+        memcpy(dst.data(), src, sizeof(T) * count);
+    return TRON_OK;
+}
+
+}  // namespace tron
+
+using namespace tron;
+
+// =================================================================== ABI
+extern "C" {
+
+const char *tron_last_error(void) { return g_err; }
+
+void tron_dataset_destroy(tron_dataset *ds)
+{
+    if (!ds) return;
+    hipStreamSynchronize(ds->stream);
+    hipFree(ds->X);
+    ds->fwd.release();
+    ds->bwd.release();
+    hipFree(ds->y); hipFree(ds->z); hipFree(ds->zhat); hipFree(ds->Dbuf[0]); hipFree(ds->Dbuf[1]);
+    hipFree(ds->partials); hipFree(ds->scal_dev);
+    if (ds->scal_host) hipHostFree(ds->scal_host);
+    for (double *p : ds->sv) hipFree(p);
+    ds->prof.destroy();
+    delete ds;
+}
+
+int tron_dataset_create_csr(int64_t n, int64_t d, const int64_t *rowptr, const int32_t *col, const double *val,
+                            const double *y, int mem, void *hip_stream, tron_dataset **out)
+{
+    if (out) *out = nullptr;
+    if (!out || !rowptr || !y || n < 1 || d < 1 || n > 0x7ffffff0 || d > 0x7ffffff0 ||
+        (mem != TRON_MEM_HOST && mem != TRON_MEM_DEVICE)) {
+        set_error("tron_dataset_create_csr: bad argument (need 1 <= n,d < 2^31, non-null rowptr/y/out, mem in {0,1})");
+        return TRON_EINVAL;
+    }
+    TRON_TRY(check_device());
+    std::vector<int64_t> h_rowptr;
+    TRON_TRY(fetch(h_rowptr, rowptr, (size_t)n + 1, mem));
+    if (h_rowptr[0] != 0) { set_error("rowptr[0] = %lld, expected 0", (long long)h_rowptr[0]); return TRON_EINVAL; }
+    for (int64_t i = 0; i < n; ++i)
+        if (h_rowptr[i + 1] < h_rowptr[i]) { set_error("rowptr decreases at row %lld", (long long)i); return TRON_EINVAL; }
+    const int64_t nnz = h_rowptr[n];
+    if (nnz > 0 && (!col || !val)) { set_error("col/val are null but nnz = %lld", (long long)nnz); return TRON_EINVAL; }
+    std::vector<int32_t> h_col;
+    std::vector<double> h_val, h_y;
+    TRON_TRY(fetch(h_col, col, (size_t)nnz, mem));
+    TRON_TRY(fetch(h_val, val, (size_t)nnz, mem));
+    TRON_TRY(fetch(h_y, y, (size_t)n, mem));
+    TRON_TRY(check_labels(h_y.data(), n));
+    // columns strictly increasing inside each row and in range; values finite; count per column
+    std::vector<int64_t> t_rowptr;
+    try {
+        t_rowptr.assign((size_t)d + 1, 0);
+    } catch (const std::bad_alloc &) { set_error("out of host memory"); return TRON_ENOMEM; }
+    for (int64_t i = 0; i < n; ++i) {
+        int64_t prev = -1;
+        for (int64_t k = h_rowptr[i]; k < h_rowptr[i + 1]; ++k) {
+            const int64_t c = h_col[k];
+            if (c <= prev || c >= d) {
+                set_error("row %lld: column index %lld out of order or out of range [0,%lld)", (long long)i, (long long)c, (long long)d);
+                return TRON_EINVAL;
+            }
+            if (!std::isfinite(h_val[k])) { set_error("row %lld: non-finite value", (long long)i); return TRON_EINVAL; }
+            prev = c;
+            t_rowptr[c + 1] += 1;
+        }
+    }
+    // explicit transposed copy (d x n): counting sort by column keeps rows ascending inside each column
+    for (int64_t j = 0; j < d; ++j) t_rowptr[j + 1] += t_rowptr[j];
+    std::vector<int32_t> t_col;
+    std::vector<double> t_val;
+    std::vector<int64_t> cursor;
+    try {
+        t_col.resize((size_t)nnz);
+        t_val.resize((size_t)nnz);
+        cursor.assign(t_rowptr.begin(), t_rowptr.end() - 1);
+    } catch (const std::bad_alloc &) { set_error("out of host memory building the transposed copy"); return TRON_ENOMEM; }
+    for (int64_t i = 0; i < n; ++i)
+        for (int64_t k = h_rowptr[i]; k < h_rowptr[i + 1]; ++k) {
+            const int64_t pos = cursor[h_col[k]]++;
+            t_col[pos] = (int32_t)i;
+            t_val[pos] = h_val[k];
+        }
+
+    tron_dataset *ds = new (std::nothrow) tron_dataset();
+    if (!ds) { set_error("out of host memory"); return TRON_ENOMEM; }
+    ds->n = n; ds->d = d; ds->dense = false; ds->stream = reinterpret_cast<hipStream_t>(hip_stream);
+    int rc = alloc_common(ds);
+    if (rc >= 0) rc = csr_plan_build(ds->fwd, n, d, h_rowptr.data(), h_col.data(), h_val.data(), ds->stream);
+    if (rc >= 0) rc = csr_plan_build(ds->bwd, d, n, t_rowptr.data(), t_col.data(), t_val.data(), ds->stream);
+    if (rc >= 0) {
+        hipError_t e = hipMemcpyAsync(ds->y, h_y.data(), sizeof(double) * n, hipMemcpyHostToDevice, ds->stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(ds->stream);
+        if (e != hipSuccess) rc = hip_fail(e, "copy y", __FILE__, __LINE__);
+    }
+    if (rc < 0) { tron_dataset_destroy(ds); return rc; }
+    *out = ds;
+    return TRON_OK;
+}
+
+int tron_dataset_create_dense_empty(int64_t n, int64_t d, void *hip_stream, tron_dataset **out)
+{
+    if (out) *out = nullptr;
+    if (!out || n < 1 || d < 1 || n > 0x7ffffff0) {
+        set_error("tron_dataset_create_dense_empty: bad argument (need 1 <= n < 2^31, d >= 1, non-null out)");
+        return TRON_EINVAL;
+    }
+    if (!dense_supported(d)) { set_error("dense d = %lld not supported (1 <= d <= 512)", (long long)d); return TRON_EINVAL; }
+    TRON_TRY(check_device());
+    tron_dataset *ds = new (std::nothrow) tron_dataset();
+    if (!ds) { set_error("out of host memory"); return TRON_ENOMEM; }
+    ds->n = n; ds->d = d; ds->dense = true; ds->stream = reinterpret_cast<hipStream_t>(hip_stream);
+    int rc = alloc_common(ds);
+    if (rc >= 0) {
+        hipError_t e = hipMalloc(reinterpret_cast<void **>(&ds->X), sizeof(double) * (size_t)n * (size_t)d);
+        if (e != hipSuccess) rc = hip_fail(e, "allocate X", __FILE__, __LINE__);
+    }
+    if (rc < 0) { tron_dataset_destroy(ds); return rc; }
+    *out = ds;
+    return TRON_OK;
+}
+
+int tron_dataset_write_rows(tron_dataset *ds, int64_t row0, int64_t nrows, const double *X_chunk, const double *y_chunk, int mem)
+{
+    if (!ds || !ds->dense || !X_chunk || !y_chunk || row0 < 0 || nrows < 0 || row0 + nrows > ds->n ||
+        (mem != TRON_MEM_HOST && mem != TRON_MEM_DEVICE)) {
+        set_error("tron_dataset_write_rows: bad argument");
+        return TRON_EINVAL;
+    }
+    if (nrows == 0) return TRON_OK;
+    if (mem == TRON_MEM_HOST) {
+        TRON_TRY(check_labels(y_chunk, nrows));
+        for (int64_t k = 0; k < nrows * ds->d; ++k)
+            if (!std::isfinite(X_chunk[k])) { set_error("X has a non-finite entry in row %lld", (long long)(row0 + k / ds->d)); return TRON_EINVAL; }
+    }
+    const hipMemcpyKind kind = (mem == TRON_MEM_HOST) ? hipMemcpyHostToDevice : hipMemcpyDeviceToDevice;
+    TRON_HIP(hipMemcpyAsync(ds->X + row0 * ds->d, X_chunk, sizeof(double) * (size_t)nrows * (size_t)ds->d, kind, ds->stream));
+    TRON_HIP(hipMemcpyAsync(ds->y + row0, y_chunk, sizeof(double) * (size_t)nrows, kind, ds->stream));
+    TRON_HIP(hipStreamSynchronize(ds->stream));  // the caller may reuse its buffers on return
+    ds->have_D = false;
+    return TRON_OK;
+}
+
+int tron_dataset_create_dense(int64_t n, int64_t d, const double *X_rowmajor, const double *y, int mem, void *hip_stream,
+                              tron_dataset **out)
+{
+    if (out) *out = nullptr;
+    if (!out || !X_rowmajor || !y) { set_error("tron_dataset_create_dense: null argument"); return TRON_EINVAL; }
+    tron_dataset *ds = nullptr;
+    TRON_TRY(tron_dataset_create_dense_empty(n, d, hip_stream, &ds));
+    int rc = tron_dataset_write_rows(ds, 0, n, X_rowmajor, y, mem);
+    if (rc < 0) { tron_dataset_destroy(ds); return rc; }
+    *out = ds;
+    return TRON_OK;
+}
+
+int tron_dataset_shape(const tron_dataset *ds, int64_t *n, int64_t *d, int64_t *nnz, int *is_dense)
+{
+    if (!ds) { set_error("tron_dataset_shape: null handle"); return TRON_EINVAL; }
+    if (n) *n = ds->n;
+    if (d) *d = ds->d;
+    if (nnz) *nnz = ds->dense ? ds->n * ds->d : ds->fwd.nnz;
+    if (is_dense) *is_dense = ds->dense ? 1 : 0;
+    return TRON_OK;
+}
+
+int tron_fun_grad(tron_dataset *ds, int loss, double C, const double *w_dev, double *f_host, double *g_dev)
+{
+    if (!ds || !w_dev || !f_host || (loss != TRON_LOSS_LR && loss != TRON_LOSS_L2SVM) || !(C > 0.0) || !std::isfinite(C)) {
+        set_error("tron_fun_grad: bad argument (null handle/w/f, unknown loss, or C <= 0)");
+        return TRON_EINVAL;
+    }
+    const int slot = ds->have_D ? 1 - ds->Dcur : ds->Dcur;
+    if (ds->dense) {
+        TRON_TRY(dense_fun_grad(ds, loss, C, w_dev, ds->Dbuf[slot], g_dev));
+        TRON_TRY(read_scalars(ds, 3));
+        *f_host = 0.5 * ds->scal_host[1] + C * ds->scal_host[0];
+    } else {
+        TRON_TRY(fun_eval(ds, loss, C, w_dev, slot, f_host));
+        if (g_dev) {
+            double gn;
+            TRON_TRY(grad_eval(ds, C, w_dev, g_dev, &gn));
+        }
+    }
+    ds->Dcur = slot;
+    ds->have_D = true;
+    return TRON_OK;
+}
+
+int tron_hv(tron_dataset *ds, double C, const double *v_dev, double *Hv_dev, double *vHv_host)
+{
+    if (!ds || !v_dev || !Hv_dev || v_dev == Hv_dev || !(C > 0.0) || !std::isfinite(C)) {
+        set_error("tron_hv: bad argument (null handle/v/Hv, v aliases Hv, or C <= 0)");
+        return TRON_EINVAL;
+    }
+    if (!ds->have_D) { set_error("tron_hv: no cached D; call tron_fun_grad first"); return TRON_ESTATE; }
+    TRON_TRY(hv_enqueue(ds, C, v_dev, Hv_dev));
+    if (vHv_host) {
+        TRON_TRY(read_scalars(ds, 1));
+        *vHv_host = ds->scal_host[0];
+    }
+    return TRON_OK;
+}
+
+int tron_profile_enable(tron_dataset *ds, int on)
+{
+    if (!ds) { set_error("tron_profile_enable: null handle"); return TRON_EINVAL; }
+    TRON_HIP(hipStreamSynchronize(ds->stream));
+    TRON_TRY(ds->prof.drain());
+    ds->prof.on = on != 0;
+    for (int s = 0; s < SLOT_COUNT; ++s) { ds->prof.ms[s] = 0; ds->prof.calls[s] = 0; }
+    return TRON_OK;
+}
+
+int tron_profile_read(tron_dataset *ds, int cap, const char **names, double *ms, int64_t *calls, int *count)
+{
+    if (!ds || cap < 0) { set_error("tron_profile_read: bad argument"); return TRON_EINVAL; }
+    TRON_HIP(hipStreamSynchronize(ds->stream));
+    TRON_TRY(ds->prof.drain());
+    for (int s = 0; s < SLOT_COUNT && s < cap; ++s) {
+        if (names) names[s] = kSlotNames[s];
+        if (ms) ms[s] = ds->prof.ms[s];
+        if (calls) calls[s] = ds->prof.calls[s];
+    }
+    if (count) *count = SLOT_COUNT;
+    for (int s = 0; s < SLOT_COUNT; ++s) { ds->prof.ms[s] = 0; ds->prof.calls[s] = 0; }
+    return TRON_OK;
+}
+
+int tron_probe_read_bandwidth(const double *src_dev, int64_t count, int reps, void *hip_stream, double *ms_per_launch,
+                              double *checksum)
+{
+    TRON_TRY(check_device());
+    return probe_read(src_dev, count, reps, reinterpret_cast<hipStream_t>(hip_stream), ms_per_launch, checksum);
+}
+
+}  // extern "C"

@@ -1,0 +1,394 @@
+// Dense row-major kernels: one pass over X computes both products of Table 1 of the paper,
+//   Hessian-vector:  X^T ( D (X v) )        (written there as 2C X_I^T (X_I v) for the L2-SVM; the
+//                                            active set enters through D_ii in {0, 2})
+//   function/gradient:  z = X w, the per-instance loss, zhat and D, and X^T zhat
+// so each element of X is read from HBM exactly once per call.
+//
+// Layout of the work inside a wavefront (64 lanes): a row is covered by L consecutive lanes, each
+// holding E consecutive columns (E*L >= d); one "step" therefore covers 64/L rows and a wave tile of
+// U steps covers RT = U*64/L consecutive rows.  For d = 24: E = 6, L = 4, U = 4 -- 64 rows = 12 KiB per
+// tile, each lane issuing three 16-byte loads per step, twelve per tile, all in flight together.
+//   1. partial dot products x.v per lane, butterfly over the L lanes of the row;
+//   2. the RT row results are moved so that lane i owns row i of the tile: the per-row scalar work
+//      (sigmoid / log1p for the logistic loss, D scaling) runs once per row, and D, y are read/written
+//      as one coalesced 8-byte-per-lane access;
+//   3. the per-row coefficient is broadcast back to the row's lanes and accumulated into E private
+//      column accumulators, which are reduced over the wavefront / workgroup once, at the end.
+// Workgroup partial column sums go to `partials[col * grid + block]`; a second kernel adds them in a
+// fixed order (no atomics) and applies  out = add + C * sum  together with the dot products the
+// trust-region driver needs.
+#include "device_util.h"
+
+namespace tron {
+
+namespace {
+
+constexpr int ilog2(int x) { return x <= 1 ? 0 : 1 + ilog2(x / 2); }
+
+template <int E, int L, int U, bool VEC>
+struct Tile {
+    static constexpr int RW = kWave / L;     // rows per step
+    static constexpr int RT = U * RW;        // rows per wave tile
+
+    // load the U x E block of this lane; out-of-range rows / columns read as zero
+    __device__ static __forceinline__ void load(const double *__restrict__ X, int64_t n, int64_t d, int64_t row0,
+                                                int lane, double (&x)[U][E])
+    {
+        const int q = lane % L, rl = lane / L;
+        const int c0 = q * E;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t row = row0 + u * RW + rl;
+            const bool rok = row < n;
+            const double *p = X + row * d + c0;
+            if (VEC) {
+#pragma unroll
+                for (int e = 0; e < E; e += 2) {
+                    double2 t = make_double2(0.0, 0.0);
+                    if (rok && c0 + e < d) t = *reinterpret_cast<const double2 *>(p + e);
+                    x[u][e] = t.x;
+                    x[u][e + 1] = t.y;
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < E; ++e) x[u][e] = (rok && c0 + e < d) ? p[e] : 0.0;
+            }
+        }
+    }
+
+    // t[u] = x_row . vec for the row this lane helps with in step u (all L lanes of the row get it)
+    __device__ static __forceinline__ void row_dots(const double (&x)[U][E], const double (&vec)[E], double (&t)[U])
+    {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            double s = 0.0;
+#pragma unroll
+            for (int e = 0; e < E; ++e) s = fma(x[u][e], vec[e], s);
+#pragma unroll
+            for (int m = 1; m < L; m <<= 1) s += __shfl_xor(s, m, kWave);
+            t[u] = s;
+        }
+    }
+
+    // lane i (< RT) receives the value of tile row i
+    __device__ static __forceinline__ double to_row_owner(const double (&t)[U], int lane)
+    {
+        double mine = 0.0;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const double got = __shfl(t[u], (lane % RW) * L, kWave);
+            if (lane / RW == u) mine = got;
+        }
+        return mine;
+    }
+
+    // every lane receives, for step u, the value owned by the lane of its row
+    __device__ static __forceinline__ void from_row_owner(double mine, int lane, double (&c)[U])
+    {
+#pragma unroll
+        for (int u = 0; u < U; ++u) c[u] = __shfl(mine, u * RW + lane / L, kWave);
+    }
+
+    // acc[e] summed over the lanes that hold the same columns, then over the workgroup's wavefronts,
+    // written to partials[(col) * grid + block]
+    __device__ static __forceinline__ void flush(double (&acc)[E], int64_t d, int lane, int wv, double *lds /*4*E*L*/,
+                                                 double *__restrict__ partials)
+    {
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+#pragma unroll
+            for (int m = L; m < kWave; m <<= 1) acc[e] += __shfl_xor(acc[e], m, kWave);
+        }
+        if (lane < L) {
+#pragma unroll
+            for (int e = 0; e < E; ++e) lds[wv * (E * L) + lane * E + e] = acc[e];
+        }
+        __syncthreads();
+        for (int c = threadIdx.x; c < d; c += kBlock) {
+            double s = 0.0;
+#pragma unroll
+            for (int k = 0; k < kWavesPerBlock; ++k) s += lds[k * (E * L) + c];
+            partials[(int64_t)c * gridDim.x + blockIdx.x] = s;
+        }
+    }
+};
+
+// ------------------------------------------------------------------ Hessian-vector pass
+template <int E, int L, int U, bool VEC>
+__global__ __launch_bounds__(kBlock) void k_dense_hv(int64_t n, int64_t d, const double *__restrict__ X,
+                                                     const double *__restrict__ D, const double *__restrict__ v,
+                                                     double *__restrict__ partials)
+{
+    using T = Tile<E, L, U, VEC>;
+    __shared__ double lds[kWavesPerBlock * E * L];
+    const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave;
+    const int q = lane % L;
+    double vreg[E], acc[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        vreg[e] = (q * E + e < d) ? v[q * E + e] : 0.0;
+        acc[e] = 0.0;
+    }
+    const int64_t ntiles = (n + T::RT - 1) / T::RT;
+    const int64_t nwaves = (int64_t)gridDim.x * kWavesPerBlock;
+    for (int64_t tile = (int64_t)blockIdx.x * kWavesPerBlock + wv; tile < ntiles; tile += nwaves) {
+        const int64_t row0 = tile * T::RT;
+        double x[U][E], t[U], c[U];
+        T::load(X, n, d, row0, lane, x);
+        const double Drow = (lane < T::RT && row0 + lane < n) ? D[row0 + lane] : 0.0;
+        T::row_dots(x, vreg, t);
+        const double a1 = Drow * T::to_row_owner(t, lane);   // a1 = D (X v)
+        T::from_row_owner(a1, lane, c);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+#pragma unroll
+            for (int e = 0; e < E; ++e) acc[e] = fma(c[u], x[u][e], acc[e]);
+        }
+    }
+    T::flush(acc, d, lane, wv, lds, partials);
+}
+
+// ------------------------------------------------------------------ function / gradient pass
+template <int E, int L, int U, bool VEC, int LOSS>
+__global__ __launch_bounds__(kBlock) void k_dense_fun_grad(int64_t n, int64_t d, const double *__restrict__ X,
+                                                           const double *__restrict__ y, const double *__restrict__ w,
+                                                           double *__restrict__ Dout, double *__restrict__ partials,
+                                                           double *__restrict__ loss_partials)
+{
+    using T = Tile<E, L, U, VEC>;
+    __shared__ double lds[kWavesPerBlock * E * L];
+    __shared__ double lds_red[kWavesPerBlock];
+    const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave;
+    const int q = lane % L;
+    double wreg[E], acc[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        wreg[e] = (q * E + e < d) ? w[q * E + e] : 0.0;
+        acc[e] = 0.0;
+    }
+    double loss_acc = 0.0;
+    const int64_t ntiles = (n + T::RT - 1) / T::RT;
+    const int64_t nwaves = (int64_t)gridDim.x * kWavesPerBlock;
+    for (int64_t tile = (int64_t)blockIdx.x * kWavesPerBlock + wv; tile < ntiles; tile += nwaves) {
+        const int64_t row0 = tile * T::RT;
+        double x[U][E], t[U], c[U];
+        T::load(X, n, d, row0, lane, x);
+        const bool mine = lane < T::RT && row0 + lane < n;
+        const double yrow = mine ? y[row0 + lane] : 1.0;
+        T::row_dots(x, wreg, t);
+        const double z = T::to_row_owner(t, lane);            // z = X w
+        double alpha, zhat, Di;
+        loss_terms_dev<LOSS>(z, yrow, alpha, zhat, Di);
+        if (mine) {
+            Dout[row0 + lane] = Di;
+            loss_acc += alpha;
+        } else {
+            zhat = 0.0;
+        }
+        T::from_row_owner(zhat, lane, c);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+#pragma unroll
+            for (int e = 0; e < E; ++e) acc[e] = fma(c[u], x[u][e], acc[e]);
+        }
+    }
+    T::flush(acc, d, lane, wv, lds, partials);
+    loss_acc = block_sum(loss_acc, lds_red);
+    if (threadIdx.x == 0) loss_partials[blockIdx.x] = loss_acc;
+}
+
+// ------------------------------------------------------------------ second stage
+// One wavefront per column: out[c] = add[c] + C * sum_b partials[c*grid + b]; colprod[c] = out[c]*dotw[c]
+// (dotw = v for the Hessian-vector product, out itself for the gradient norm).
+__global__ __launch_bounds__(kBlock) void k_dense_columns(int64_t d, int grid, const double *__restrict__ partials,
+                                                          const double *__restrict__ add, double C, double *__restrict__ out,
+                                                          const double *__restrict__ dotw, double *__restrict__ colprod)
+{
+    const int c = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+    if (c >= d) return;
+    const int lane = threadIdx.x & (kWave - 1);
+    const double *p = partials + (int64_t)c * grid;
+    double s = 0.0;
+    for (int b = lane; b < grid; b += kWave) s += p[b];
+    s = wave_sum(s);
+    if (lane == 0) {
+        const double o = fma(C, s, add[c]);
+        if (out) out[c] = o;
+        colprod[c] = o * (dotw ? dotw[c] : o);
+    }
+}
+
+// scal[0] = sum loss partials (or v.Hv when nloss == 0: then scal[0] = sum colprod), scal[1] = w.w, scal[2] = sum colprod
+__global__ __launch_bounds__(kBlock) void k_dense_scalars(int64_t d, int nloss, const double *__restrict__ loss_partials,
+                                                          const double *__restrict__ w, const double *__restrict__ colprod,
+                                                          double *__restrict__ scal)
+{
+    __shared__ double lds[kWavesPerBlock];
+    double a = 0.0, b = 0.0, c = 0.0;
+    for (int i = threadIdx.x; i < nloss; i += kBlock) a += loss_partials[i];
+    for (int64_t j = threadIdx.x; j < d; j += kBlock) {
+        if (w) b += w[j] * w[j];
+        c += colprod[j];
+    }
+    a = block_sum(a, lds);
+    b = block_sum(b, lds);
+    c = block_sum(c, lds);
+    if (threadIdx.x == 0) {
+        if (nloss > 0) {
+            scal[0] = a;
+            scal[1] = b;
+            scal[2] = c;
+        } else {
+            scal[0] = c;
+        }
+    }
+}
+
+// ------------------------------------------------------------------ dispatch
+struct Shape { int E, L; };
+
+// smallest L in {1,2,4,...,64} with ceil(d/L) <= 8
+bool pick_shape(int64_t d, Shape &s)
+{
+    for (int L = 1; L <= kWave; L *= 2) {
+        const int64_t E = (d + L - 1) / L;
+        if (E <= 8) { s.E = (int)E; s.L = L; return true; }
+    }
+    return false;
+}
+
+constexpr int pick_U(int E, int L) { return (L < 4 ? L : 4); }
+
+template <int E, int L>
+int launch_hv(tron_dataset *ds, const double *D, const double *v)
+{
+    constexpr int U = pick_U(E, L);
+    const bool vec = (E % 2 == 0) && (ds->d % 2 == 0);
+    const int grid = ds->dense_grid;
+    if (vec)
+        hipLaunchKernelGGL((k_dense_hv<E, L, U, (E % 2 == 0)>), dim3(grid), dim3(kBlock), 0, ds->stream, ds->n, ds->d, ds->X, D, v, ds->partials);
+    else
+        hipLaunchKernelGGL((k_dense_hv<E, L, U, false>), dim3(grid), dim3(kBlock), 0, ds->stream, ds->n, ds->d, ds->X, D, v, ds->partials);
+    return TRON_OK;
+}
+
+template <int E, int L>
+int launch_fg(tron_dataset *ds, int loss, const double *w, double *Dout, double *loss_partials)
+{
+    constexpr int U = pick_U(E, L);
+    const bool vec = (E % 2 == 0) && (ds->d % 2 == 0);
+    const int grid = ds->dense_grid;
+#define TRON_FG(V, LS) \
+    hipLaunchKernelGGL((k_dense_fun_grad<E, L, U, V, LS>), dim3(grid), dim3(kBlock), 0, ds->stream, ds->n, ds->d, ds->X, ds->y, w, Dout, ds->partials, loss_partials)
+    if (loss == TRON_LOSS_LR) {
+        if (vec) TRON_FG((E % 2 == 0), TRON_LOSS_LR); else TRON_FG(false, TRON_LOSS_LR);
+    } else {
+        if (vec) TRON_FG((E % 2 == 0), TRON_LOSS_L2SVM); else TRON_FG(false, TRON_LOSS_L2SVM);
+    }
+#undef TRON_FG
+    return TRON_OK;
+}
+
+// E in 1..8 for L = 1, E in 5..8 for L >= 2 (smaller d picks a smaller L)
+#define TRON_DISPATCH_E(L_, FN, ...)                         \
+    switch (s.E) {                                           \
+    case 5: return FN<5, L_>(__VA_ARGS__);                   \
+    case 6: return FN<6, L_>(__VA_ARGS__);                   \
+    case 7: return FN<7, L_>(__VA_ARGS__);                   \
+    case 8: return FN<8, L_>(__VA_ARGS__);                   \
+    default: break;                                          \
+    }
+
+#define TRON_DISPATCH(FN, ...)                                                   \
+    Shape s;                                                                     \
+    if (!pick_shape(ds->d, s)) { set_error("dense d = %lld not supported (max 512)", (long long)ds->d); return TRON_EINVAL; } \
+    switch (s.L) {                                                               \
+    case 1:                                                                      \
+        switch (s.E) {                                                           \
+        case 1: return FN<1, 1>(__VA_ARGS__);                                    \
+        case 2: return FN<2, 1>(__VA_ARGS__);                                    \
+        case 3: return FN<3, 1>(__VA_ARGS__);                                    \
+        case 4: return FN<4, 1>(__VA_ARGS__);                                    \
+        default: break;                                                          \
+        }                                                                        \
+        TRON_DISPATCH_E(1, FN, __VA_ARGS__) break;                               \
+    case 2: TRON_DISPATCH_E(2, FN, __VA_ARGS__) break;                           \
+    case 4: TRON_DISPATCH_E(4, FN, __VA_ARGS__) break;                           \
+    case 8: TRON_DISPATCH_E(8, FN, __VA_ARGS__) break;                           \
+    case 16: TRON_DISPATCH_E(16, FN, __VA_ARGS__) break;                         \
+    case 32: TRON_DISPATCH_E(32, FN, __VA_ARGS__) break;                         \
+    case 64: TRON_DISPATCH_E(64, FN, __VA_ARGS__) break;                         \
+    default: break;                                                              \
+    }                                                                            \
+    set_error("internal: no dense kernel for E=%d L=%d", s.E, s.L);              \
+    return TRON_EINVAL;
+
+int dispatch_hv(tron_dataset *ds, const double *D, const double *v) { TRON_DISPATCH(launch_hv, ds, D, v) }
+int dispatch_fg(tron_dataset *ds, int loss, const double *w, double *Dout, double *lp) { TRON_DISPATCH(launch_fg, ds, loss, w, Dout, lp) }
+
+}  // namespace
+
+bool dense_supported(int64_t d)
+{
+    Shape s;
+    return d >= 1 && pick_shape(d, s);
+}
+
+int dense_grid_for(int64_t n, int64_t d)
+{
+    Shape s;
+    if (!pick_shape(d, s)) return 1;
+    const int U = pick_U(s.E, s.L);
+    const int64_t RT = (int64_t)U * (kWave / s.L);
+    const int64_t tiles = (n + RT - 1) / RT;
+    int64_t g = (tiles + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (g < 1) g = 1;
+    if (g > kMaxGrid) g = kMaxGrid;
+    return (int)g;
+}
+
+// column partials (d * grid) followed by loss partials (grid) and column products (d)
+int64_t dense_partials_needed(int64_t n, int64_t d)
+{
+    const int64_t g = dense_grid_for(n, d);
+    return d * g + g + d;
+}
+
+int dense_hv(tron_dataset *ds, double C, const double *D, const double *v, double *Hv)
+{
+    const int grid = ds->dense_grid;
+    double *colprod = ds->partials + ds->d * grid + grid;
+    {
+        ProfScope ps(ds, SLOT_DENSE_HV);
+        TRON_TRY(dispatch_hv(ds, D, v));
+        TRON_HIP(hipGetLastError());
+    }
+    ProfScope ps(ds, SLOT_DENSE_FINALIZE);
+    const int cg = (int)((ds->d + kWavesPerBlock - 1) / kWavesPerBlock);
+    hipLaunchKernelGGL(k_dense_columns, dim3(cg), dim3(kBlock), 0, ds->stream, ds->d, grid, ds->partials, v, C, Hv, v, colprod);
+    hipLaunchKernelGGL(k_dense_scalars, dim3(1), dim3(kBlock), 0, ds->stream, ds->d, 0, (const double *)nullptr,
+                       (const double *)nullptr, colprod, ds->scal_dev);
+    TRON_HIP(hipGetLastError());
+    return TRON_OK;
+}
+
+int dense_fun_grad(tron_dataset *ds, int loss, double C, const double *w, double *Dout, double *g)
+{
+    const int grid = ds->dense_grid;
+    double *loss_partials = ds->partials + ds->d * grid;
+    double *colprod = loss_partials + grid;
+    {
+        ProfScope ps(ds, SLOT_DENSE_FUN_GRAD);
+        TRON_TRY(dispatch_fg(ds, loss, w, Dout, loss_partials));
+        TRON_HIP(hipGetLastError());
+    }
+    ProfScope ps(ds, SLOT_DENSE_FINALIZE);
+    const int cg = (int)((ds->d + kWavesPerBlock - 1) / kWavesPerBlock);
+    hipLaunchKernelGGL(k_dense_columns, dim3(cg), dim3(kBlock), 0, ds->stream, ds->d, grid, ds->partials, w, C, g,
+                       (const double *)nullptr, colprod);
+    hipLaunchKernelGGL(k_dense_scalars, dim3(1), dim3(kBlock), 0, ds->stream, ds->d, grid, loss_partials, w, colprod, ds->scal_dev);
+    TRON_HIP(hipGetLastError());
+    return TRON_OK;
+}
+
+}  // namespace tron

@@ -1,0 +1,283 @@
+// Elementwise and reduction kernels over the length-n and length-d vectors: per-instance loss
+// terms (Appendix E of the paper), dot products / norms, the conjugate-gradient vector updates
+// and the second reduction stage.  All reductions are two-stage: each workgroup writes one partial
+// per quantity, a single workgroup then adds the partials in a fixed order (no atomics).
+#include "device_util.h"
+
+namespace tron {
+
+// ------------------------------------------------------------------ second stage
+// scal[first + s] = sum_{b < count} partials[s*stride + b]
+__global__ __launch_bounds__(kBlock) void k_reduce_final(const double *__restrict__ partials, int count, int stride,
+                                                         double *__restrict__ scal, int first)
+{
+    __shared__ double lds[kWavesPerBlock];
+    const int s = blockIdx.x;
+    const double *p = partials + (int64_t)s * stride;
+    double acc = 0.0;
+    for (int b = threadIdx.x; b < count; b += kBlock) acc += p[b];
+    acc = block_sum(acc, lds);
+    if (threadIdx.x == 0) scal[first + s] = acc;
+}
+
+int reduce_final(tron_dataset *ds, int nslots, int count, int stride, int first_scalar)
+{
+    ProfScope ps(ds, SLOT_REDUCE_FINAL);
+    hipLaunchKernelGGL(k_reduce_final, dim3(nslots), dim3(kBlock), 0, ds->stream, ds->partials, count, stride,
+                       ds->scal_dev, first_scalar);
+    TRON_HIP(hipGetLastError());
+    return TRON_OK;
+}
+
+int read_scalars(tron_dataset *ds, int count)
+{
+    TRON_HIP(hipMemcpyAsync(ds->scal_host, ds->scal_dev, sizeof(double) * count, hipMemcpyDeviceToHost, ds->stream));
+    TRON_HIP(hipStreamSynchronize(ds->stream));
+    return TRON_OK;
+}
+
+static inline int vec_grid(int64_t m)
+{
+    int64_t g = (m + kBlock * 4 - 1) / (kBlock * 4);
+    if (g < 1) g = 1;
+    if (g > kMaxGrid) g = kMaxGrid;
+    return (int)g;
+}
+
+// ------------------------------------------------------------------ dots
+template <int K>
+__global__ __launch_bounds__(kBlock) void k_dots(int64_t m, const double *__restrict__ a0, const double *__restrict__ b0,
+                                                 const double *__restrict__ a1, const double *__restrict__ b1,
+                                                 const double *__restrict__ a2, const double *__restrict__ b2,
+                                                 double *__restrict__ partials, int stride)
+{
+    __shared__ double lds[kWavesPerBlock];
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < m; i += (int64_t)gridDim.x * kBlock) {
+        s0 += a0[i] * b0[i];
+        if (K > 1) s1 += a1[i] * b1[i];
+        if (K > 2) s2 += a2[i] * b2[i];
+    }
+    s0 = block_sum(s0, lds);
+    if (threadIdx.x == 0) partials[blockIdx.x] = s0;
+    if (K > 1) {
+        s1 = block_sum(s1, lds);
+        if (threadIdx.x == 0) partials[stride + blockIdx.x] = s1;
+    }
+    if (K > 2) {
+        s2 = block_sum(s2, lds);
+        if (threadIdx.x == 0) partials[2 * stride + blockIdx.x] = s2;
+    }
+}
+
+int dot_partials(tron_dataset *ds, int64_t m, const double *a0, const double *b0, const double *a1, const double *b1,
+                 const double *a2, const double *b2)
+{
+    ProfScope ps(ds, SLOT_DOT);
+    const int g = vec_grid(m);
+    if (a2)
+        hipLaunchKernelGGL(k_dots<3>, dim3(g), dim3(kBlock), 0, ds->stream, m, a0, b0, a1, b1, a2, b2, ds->partials, kMaxGrid);
+    else if (a1)
+        hipLaunchKernelGGL(k_dots<2>, dim3(g), dim3(kBlock), 0, ds->stream, m, a0, b0, a1, b1, a2, b2, ds->partials, kMaxGrid);
+    else
+        hipLaunchKernelGGL(k_dots<1>, dim3(g), dim3(kBlock), 0, ds->stream, m, a0, b0, a1, b1, a2, b2, ds->partials, kMaxGrid);
+    TRON_HIP(hipGetLastError());
+    return g;
+}
+
+// ------------------------------------------------------------------ per-instance loss terms
+// z -> zhat, D and the partial loss sums (partial slot 0).
+template <int LOSS>
+__global__ __launch_bounds__(kBlock) void k_loss_terms(int64_t n, const double *__restrict__ z, const double *__restrict__ y,
+                                                       double *__restrict__ zhat, double *__restrict__ D,
+                                                       double *__restrict__ partials)
+{
+    __shared__ double lds[kWavesPerBlock];
+    double acc = 0.0;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (int64_t)gridDim.x * kBlock) {
+        double a, zh, Di;
+        loss_terms_dev<LOSS>(z[i], y[i], a, zh, Di);
+        zhat[i] = zh;
+        D[i] = Di;
+        acc += a;
+    }
+    acc = block_sum(acc, lds);
+    if (threadIdx.x == 0) partials[blockIdx.x] = acc;
+}
+
+int loss_terms(tron_dataset *ds, int loss, const double *z, double *zhat, double *D)
+{
+    ProfScope ps(ds, SLOT_LOSS_TERMS);
+    const int g = vec_grid(ds->n);
+    if (loss == TRON_LOSS_LR)
+        hipLaunchKernelGGL(k_loss_terms<TRON_LOSS_LR>, dim3(g), dim3(kBlock), 0, ds->stream, ds->n, z, ds->y, zhat, D, ds->partials);
+    else
+        hipLaunchKernelGGL(k_loss_terms<TRON_LOSS_L2SVM>, dim3(g), dim3(kBlock), 0, ds->stream, ds->n, z, ds->y, zhat, D, ds->partials);
+    TRON_HIP(hipGetLastError());
+    return g;
+}
+
+// ------------------------------------------------------------------ conjugate-gradient vector updates
+// s = 0, r = p = -g
+__global__ __launch_bounds__(kBlock) void k_cg_init(int64_t d, const double *__restrict__ g, double *__restrict__ s,
+                                                    double *__restrict__ r, double *__restrict__ p)
+{
+    for (int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x; j < d; j += (int64_t)gridDim.x * kBlock) {
+        const double t = -g[j];
+        s[j] = 0.0;
+        r[j] = t;
+        p[j] = t;
+    }
+}
+
+int cg_init(tron_dataset *ds, const double *g, double *s, double *r, double *p)
+{
+    ProfScope ps(ds, SLOT_CG_VEC);
+    hipLaunchKernelGGL(k_cg_init, dim3(vec_grid(ds->d)), dim3(kBlock), 0, ds->stream, ds->d, g, s, r, p);
+    TRON_HIP(hipGetLastError());
+    return TRON_OK;
+}
+
+// s += alpha p;  r -= alpha Hp;  partial slot 0 = r.r
+__global__ __launch_bounds__(kBlock) void k_cg_step(int64_t d, double alpha, const double *__restrict__ p,
+                                                    const double *__restrict__ Hp, double *__restrict__ s,
+                                                    double *__restrict__ r, double *__restrict__ partials)
+{
+    __shared__ double lds[kWavesPerBlock];
+    double acc = 0.0;
+    for (int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x; j < d; j += (int64_t)gridDim.x * kBlock) {
+        s[j] = fma(alpha, p[j], s[j]);
+        const double rj = fma(-alpha, Hp[j], r[j]);
+        r[j] = rj;
+        acc += rj * rj;
+    }
+    acc = block_sum(acc, lds);
+    if (threadIdx.x == 0) partials[blockIdx.x] = acc;
+}
+
+int cg_step(tron_dataset *ds, double alpha, const double *p, const double *Hp, double *s, double *r)
+{
+    ProfScope ps(ds, SLOT_CG_VEC);
+    const int g = vec_grid(ds->d);
+    hipLaunchKernelGGL(k_cg_step, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, alpha, p, Hp, s, r, ds->partials);
+    TRON_HIP(hipGetLastError());
+    return g;
+}
+
+// p = r + beta p;  partial slots: 0 = p.p, 1 = s.p, 2 = s.s
+__global__ __launch_bounds__(kBlock) void k_cg_dir(int64_t d, double beta, const double *__restrict__ r,
+                                                   const double *__restrict__ s, double *__restrict__ p,
+                                                   double *__restrict__ partials, int stride)
+{
+    __shared__ double lds[kWavesPerBlock];
+    double pp = 0.0, sp = 0.0, ss = 0.0;
+    for (int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x; j < d; j += (int64_t)gridDim.x * kBlock) {
+        const double pj = fma(beta, p[j], r[j]);
+        const double sj = s[j];
+        p[j] = pj;
+        pp += pj * pj;
+        sp += sj * pj;
+        ss += sj * sj;
+    }
+    pp = block_sum(pp, lds);
+    if (threadIdx.x == 0) partials[blockIdx.x] = pp;
+    sp = block_sum(sp, lds);
+    if (threadIdx.x == 0) partials[stride + blockIdx.x] = sp;
+    ss = block_sum(ss, lds);
+    if (threadIdx.x == 0) partials[2 * stride + blockIdx.x] = ss;
+}
+
+int cg_dir(tron_dataset *ds, double beta, const double *r, const double *s, double *p)
+{
+    ProfScope ps(ds, SLOT_CG_VEC);
+    const int g = vec_grid(ds->d);
+    hipLaunchKernelGGL(k_cg_dir, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, beta, r, s, p, ds->partials, kMaxGrid);
+    TRON_HIP(hipGetLastError());
+    return g;
+}
+
+// wnew = w + s;  partial slots: 0 = g.s, 1 = s.r, 2 = s.s
+__global__ __launch_bounds__(kBlock) void k_trial_point(int64_t d, const double *__restrict__ w, const double *__restrict__ s,
+                                                        const double *__restrict__ g, const double *__restrict__ r,
+                                                        double *__restrict__ wnew, double *__restrict__ partials, int stride)
+{
+    __shared__ double lds[kWavesPerBlock];
+    double gs = 0.0, sr = 0.0, ss = 0.0;
+    for (int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x; j < d; j += (int64_t)gridDim.x * kBlock) {
+        const double sj = s[j];
+        wnew[j] = w[j] + sj;
+        gs += g[j] * sj;
+        sr += sj * r[j];
+        ss += sj * sj;
+    }
+    gs = block_sum(gs, lds);
+    if (threadIdx.x == 0) partials[blockIdx.x] = gs;
+    sr = block_sum(sr, lds);
+    if (threadIdx.x == 0) partials[stride + blockIdx.x] = sr;
+    ss = block_sum(ss, lds);
+    if (threadIdx.x == 0) partials[2 * stride + blockIdx.x] = ss;
+}
+
+int trial_point(tron_dataset *ds, const double *w, const double *s, const double *g, const double *r, double *wnew)
+{
+    ProfScope ps(ds, SLOT_CG_VEC);
+    const int gr = vec_grid(ds->d);
+    hipLaunchKernelGGL(k_trial_point, dim3(gr), dim3(kBlock), 0, ds->stream, ds->d, w, s, g, r, wnew, ds->partials, kMaxGrid);
+    TRON_HIP(hipGetLastError());
+    return gr;
+}
+
+// ------------------------------------------------------------------ streaming-read probe
+__global__ __launch_bounds__(kBlock) void k_probe_sum(const double2 *__restrict__ src, int64_t count2, double *__restrict__ out)
+{
+    __shared__ double lds[kWavesPerBlock];
+    double a = 0.0, b = 0.0;
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    for (; i + 3 * stride < count2; i += 4 * stride) {
+        const double2 x0 = src[i], x1 = src[i + stride], x2 = src[i + 2 * stride], x3 = src[i + 3 * stride];
+        a += (x0.x + x1.x) + (x2.x + x3.x);
+        b += (x0.y + x1.y) + (x2.y + x3.y);
+    }
+    for (; i < count2; i += stride) {
+        const double2 x0 = src[i];
+        a += x0.x;
+        b += x0.y;
+    }
+    a = block_sum(a + b, lds);
+    if (threadIdx.x == 0) out[blockIdx.x] = a;
+}
+
+int probe_read(const double *src, int64_t count, int reps, hipStream_t st, double *ms, double *checksum)
+{
+    if (!src || count < 2 || reps < 1 || (reinterpret_cast<uintptr_t>(src) & 15)) {
+        set_error("tron_probe_read_bandwidth: need a 16-byte aligned device pointer, count >= 2, reps >= 1");
+        return TRON_EINVAL;
+    }
+    const int grid = kMaxGrid;
+    double *out = nullptr;
+    TRON_HIP(hipMalloc(&out, sizeof(double) * grid));
+    hipEvent_t e0, e1;
+    TRON_HIP(hipEventCreate(&e0));
+    TRON_HIP(hipEventCreate(&e1));
+    hipLaunchKernelGGL(k_probe_sum, dim3(grid), dim3(kBlock), 0, st, reinterpret_cast<const double2 *>(src), count / 2, out);
+    TRON_HIP(hipEventRecord(e0, st));
+    for (int r = 0; r < reps; ++r)
+        hipLaunchKernelGGL(k_probe_sum, dim3(grid), dim3(kBlock), 0, st, reinterpret_cast<const double2 *>(src), count / 2, out);
+    TRON_HIP(hipEventRecord(e1, st));
+    TRON_HIP(hipEventSynchronize(e1));
+    float t = 0.f;
+    TRON_HIP(hipEventElapsedTime(&t, e0, e1));
+    std::vector<double> h(grid);
+    TRON_HIP(hipMemcpy(h.data(), out, sizeof(double) * grid, hipMemcpyDeviceToHost));
+    double cs = 0.0;
+    for (double x : h) cs += x;
+    if (ms) *ms = (double)t / reps;
+    if (checksum) *checksum = cs;
+    hipEventDestroy(e0);
+    hipEventDestroy(e1);
+    hipFree(out);
+    return TRON_OK;
+}
+
+}  // namespace tron

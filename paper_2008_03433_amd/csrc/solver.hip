@@ -1,0 +1,230 @@
+// Host driver: function / gradient / Hessian-vector evaluation on top of the kernels, the
+// conjugate-gradient inner solver and the trust-region outer loop (Algorithm 1 of the paper).
+// All vectors stay in device memory; per CG iteration the host reads back a handful of scalars.
+#include <cmath>
+#include <cstring>
+
+#include "common.h"
+
+namespace tron {
+
+// f(w) for the sparse layout: z = X w, loss terms (zhat, D into Dbuf[Dslot]), f = 1/2 w.w + C sum loss.
+// The dense layout computes the same together with the gradient sums in one fused pass.
+int fun_eval(tron_dataset *ds, int loss, double C, const double *w, int Dslot, double *f_out)
+{
+    TRON_TRY(csr_spmv(ds, ds->fwd, SLOT_SPMV_FWD_Z, EPI_PLAIN, w, ds->z, nullptr, 0.0));
+    const int gl = loss_terms(ds, loss, ds->z, ds->zhat, ds->Dbuf[Dslot]);
+    TRON_TRY(gl);
+    TRON_TRY(reduce_final(ds, 1, gl, 0, 0));
+    const int gw = dot_partials(ds, ds->d, w, w, nullptr, nullptr, nullptr, nullptr);
+    TRON_TRY(gw);
+    TRON_TRY(reduce_final(ds, 1, gw, 0, 1));
+    TRON_TRY(read_scalars(ds, 2));
+    *f_out = 0.5 * ds->scal_host[1] + C * ds->scal_host[0];
+    return TRON_OK;
+}
+
+// g = w + C X^T zhat (zhat from the preceding fun_eval) and |g|
+int grad_eval(tron_dataset *ds, double C, const double *w, double *g, double *gnorm_out)
+{
+    TRON_TRY(csr_spmv(ds, ds->bwd, SLOT_SPMV_BWD_G, EPI_AXPY, ds->zhat, g, w, C));
+    const int gg = dot_partials(ds, ds->d, g, g, nullptr, nullptr, nullptr, nullptr);
+    TRON_TRY(gg);
+    TRON_TRY(reduce_final(ds, 1, gg, 0, 0));
+    TRON_TRY(read_scalars(ds, 1));
+    *gnorm_out = std::sqrt(ds->scal_host[0]);
+    return TRON_OK;
+}
+
+// Hv = v + C X^T (D (X v)) with D = Dbuf[Dcur]; scal_dev[0] = v.Hv.  Enqueue only.
+int hv_enqueue(tron_dataset *ds, double C, const double *v, double *Hv)
+{
+    const double *D = ds->Dbuf[ds->Dcur];
+    if (ds->dense) return dense_hv(ds, C, D, v, Hv);
+    TRON_TRY(csr_spmv(ds, ds->fwd, SLOT_SPMV_FWD_A1, EPI_SCALE, v, ds->z, D, 0.0));   // a1 = D (X v)
+    TRON_TRY(csr_spmv(ds, ds->bwd, SLOT_SPMV_BWD_HV, EPI_AXPY, ds->z, Hv, v, C));     // Hv = v + C X^T a1
+    const int g = dot_partials(ds, ds->d, v, Hv, nullptr, nullptr, nullptr, nullptr);
+    TRON_TRY(g);
+    TRON_TRY(reduce_final(ds, 1, g, 0, 0));
+    return TRON_OK;
+}
+
+namespace {
+
+enum { V_W = 0, V_WNEW, V_G, V_GNEW, V_S, V_R, V_P, V_HP, V_COUNT };
+
+int ensure_solver_vectors(tron_dataset *ds)
+{
+    for (int k = 0; k < V_COUNT; ++k)
+        if (!ds->sv[k]) TRON_HIP(hipMalloc(reinterpret_cast<void **>(&ds->sv[k]), sizeof(double) * ds->d));
+    return TRON_OK;
+}
+
+// f and (dense: also the gradient, into gout) at w; D goes to Dbuf[Dslot]
+int eval_f(tron_dataset *ds, const tron_params &P, const double *w, int Dslot, double *gout, double *f, double *gnorm_dense)
+{
+    if (ds->dense) {
+        TRON_TRY(dense_fun_grad(ds, P.loss, P.C, w, ds->Dbuf[Dslot], gout));
+        TRON_TRY(read_scalars(ds, 3));
+        *f = 0.5 * ds->scal_host[1] + P.C * ds->scal_host[0];
+        *gnorm_dense = std::sqrt(ds->scal_host[2]);
+        return TRON_OK;
+    }
+    return fun_eval(ds, P.loss, P.C, w, Dslot, f);
+}
+
+// Steihaug-Toint truncated CG on q(s) = g.s + 1/2 s.H s inside |s| <= delta.
+//   s = 0, r = p = -g;  loop: stop when |r| <= xi |g|;  alpha = r.r / p.Hp;  if |s + alpha p| >= delta go to
+//   the boundary along p and stop;  s += alpha p, r -= alpha Hp, beta = r'.r'/r.r, p = r + beta p.
+int cg_solve(tron_dataset *ds, const tron_params &P, double delta, double gnorm, int *n_hv, int *on_boundary)
+{
+    double *g = ds->sv[V_G], *s = ds->sv[V_S], *r = ds->sv[V_R], *p = ds->sv[V_P], *Hp = ds->sv[V_HP];
+    TRON_TRY(cg_init(ds, g, s, r, p));
+    double rr = gnorm * gnorm, pp = rr, sp = 0.0, ss = 0.0;
+    int it = 0;
+    *on_boundary = 0;
+    while (it < P.max_cg) {
+        if (std::sqrt(rr) <= P.cg_xi * gnorm) break;
+        TRON_TRY(hv_enqueue(ds, P.C, p, Hp));
+        TRON_TRY(read_scalars(ds, 4));  // p.Hp, and p.p, s.p, s.s left by the preceding direction update
+        const double pHp = ds->scal_host[0];
+        if (it > 0) {
+            pp = ds->scal_host[1];
+            sp = ds->scal_host[2];
+            ss = ds->scal_host[3];
+        }
+        ++it;
+        const double alpha = rr / pHp;
+        // |s + alpha p|^2 from the three dot products kept alongside the vectors
+        const double len2 = ss + alpha * (2.0 * sp + alpha * pp);
+        if (std::sqrt(len2) >= delta) {
+            const double gap = delta * delta - ss;
+            const double rad = std::sqrt(sp * sp + pp * gap);
+            const double tau = (sp >= 0.0) ? gap / (sp + rad) : (rad - sp) / pp;
+            TRON_TRY(cg_step(ds, tau, p, Hp, s, r));
+            *on_boundary = 1;
+            break;
+        }
+        const int g1 = cg_step(ds, alpha, p, Hp, s, r);
+        TRON_TRY(g1);
+        TRON_TRY(reduce_final(ds, 1, g1, 0, 0));
+        TRON_TRY(read_scalars(ds, 1));
+        const double rr_new = ds->scal_host[0];
+        const double beta = rr_new / rr;
+        rr = rr_new;
+        if (std::sqrt(rr) <= P.cg_xi * gnorm || it >= P.max_cg) break;  // p is not needed again
+        const int g2 = cg_dir(ds, beta, r, s, p);
+        TRON_TRY(g2);
+        TRON_TRY(reduce_final(ds, 3, g2, kMaxGrid, 1));  // scalars 1..3 = p.p, s.p, s.s, read with the next p.Hp
+    }
+    *n_hv = it;
+    return TRON_OK;
+}
+
+}  // namespace
+}  // namespace tron
+
+using namespace tron;
+
+extern "C" int tron_solve(tron_dataset *ds, const tron_params *params, double *w_dev, tron_result *res)
+{
+    if (!ds || !params || !w_dev || !res) { set_error("tron_solve: null argument"); return TRON_EINVAL; }
+    const tron_params P = *params;
+    if ((P.loss != TRON_LOSS_LR && P.loss != TRON_LOSS_L2SVM) || !(P.C > 0.0) || !std::isfinite(P.C) || !(P.eps > 0.0) ||
+        P.max_outer < 1 || P.max_cg < 1 || !(P.cg_xi > 0.0) || !(P.cg_xi < 1.0) || res->trace_cap < 0 ||
+        (res->trace_cap > 0 && !res->trace)) {
+        set_error("tron_solve: bad parameter (loss, C > 0, eps > 0, max_outer >= 1, max_cg >= 1, 0 < cg_xi < 1, trace)");
+        return TRON_EINVAL;
+    }
+    const double eta0 = 1e-4, eta1 = 0.25, eta2 = 0.75, sig2 = 0.5, sig3 = 4.0;
+    tron_trace_rec *trace = res->trace;
+    const int trace_cap = res->trace_cap;
+    res->f = res->gnorm = res->gnorm0 = 0.0;
+    res->outer_iters = res->cg_iters_total = res->n_fun = res->n_grad = res->n_hv = res->converged = 0;
+    res->trace_len = 0;
+
+    TRON_TRY(ensure_solver_vectors(ds));
+    const size_t dbytes = sizeof(double) * ds->d;
+    double *&w = ds->sv[V_W], *&wnew = ds->sv[V_WNEW], *&g = ds->sv[V_G], *&gnew = ds->sv[V_GNEW];
+    double *s = ds->sv[V_S], *r = ds->sv[V_R];
+    TRON_HIP(hipMemcpyAsync(w, w_dev, dbytes, hipMemcpyDeviceToDevice, ds->stream));
+
+    // |grad f(0)|: the reference of the stopping test.  When w0 = 0 it is the first gradient itself.
+    {
+        const int gz = dot_partials(ds, ds->d, w, w, nullptr, nullptr, nullptr, nullptr);
+        TRON_TRY(gz);
+        TRON_TRY(reduce_final(ds, 1, gz, 0, 0));
+        TRON_TRY(read_scalars(ds, 1));
+        if (ds->scal_host[0] != 0.0) {
+            double f0, gn0 = 0.0;
+            TRON_HIP(hipMemsetAsync(wnew, 0, dbytes, ds->stream));
+            TRON_TRY(eval_f(ds, P, wnew, 0, gnew, &f0, &gn0));
+            if (!ds->dense) TRON_TRY(grad_eval(ds, P.C, wnew, gnew, &gn0));
+            res->gnorm0 = gn0;
+            res->n_fun++;
+            res->n_grad++;
+        }
+    }
+    ds->Dcur = 0;
+    ds->have_D = false;
+    double f, gnorm = 0.0;
+    TRON_TRY(eval_f(ds, P, w, ds->Dcur, g, &f, &gnorm));
+    if (!ds->dense) TRON_TRY(grad_eval(ds, P.C, w, g, &gnorm));
+    ds->have_D = true;
+    res->n_fun++;
+    res->n_grad++;
+    if (res->gnorm0 == 0.0) res->gnorm0 = gnorm;
+    double delta = gnorm;
+    int status = TRON_EMAXITER;
+    if (gnorm <= P.eps * res->gnorm0) { status = TRON_OK; res->converged = 1; }
+
+    for (int k = 1; status == TRON_EMAXITER && k <= P.max_outer; ++k) {
+        int ncg = 0, onb = 0;
+        TRON_TRY(cg_solve(ds, P, delta, gnorm, &ncg, &onb));
+        res->n_hv += ncg;
+        res->cg_iters_total += ncg;
+        // trial point and the model reduction  pred = -q(s) = -1/2 (g.s - s.r)
+        const int gt = trial_point(ds, w, s, g, r, wnew);
+        TRON_TRY(gt);
+        TRON_TRY(reduce_final(ds, 3, gt, kMaxGrid, 0));
+        TRON_TRY(read_scalars(ds, 3));
+        const double gs = ds->scal_host[0], sr = ds->scal_host[1];
+        const double snorm = std::sqrt(ds->scal_host[2]);
+        const double pred = -0.5 * (gs - sr);
+        double fnew, gnorm_new = 0.0;
+        const int trial_slot = 1 - ds->Dcur;
+        TRON_TRY(eval_f(ds, P, wnew, trial_slot, gnew, &fnew, &gnorm_new));  // D of the trial point goes to the other buffer
+        res->n_fun++;
+        const double ared = f - fnew;
+        const bool noise = std::fabs(ared) <= 1e-12 * std::fabs(f) && pred <= 1e-12 * std::fabs(f);
+        const double sigma = noise ? 1.0 : ared / pred;
+        const double gnorm_before = gnorm;
+        if (sigma < eta1) delta = sig2 * std::fmin(snorm, delta);
+        else if (sigma < eta2) { /* unchanged */ }
+        else delta = std::fmin(sig3 * delta, std::fmax(delta, sig3 * snorm));
+        int accepted = 0;
+        if (sigma > eta0) {
+            accepted = 1;
+            if (!ds->dense) TRON_TRY(grad_eval(ds, P.C, wnew, gnew, &gnorm_new));
+            std::swap(w, wnew);
+            std::swap(g, gnew);
+            ds->Dcur = trial_slot;   // the Hessian now uses D at the accepted point
+            f = fnew;
+            gnorm = gnorm_new;
+            res->n_grad++;
+        }
+        res->outer_iters = k;
+        if (trace && res->trace_len < trace_cap) {
+            tron_trace_rec &t = trace[res->trace_len++];
+            t.iter = k; t.cg_iters = ncg; t.accepted = accepted; t.on_boundary = onb;
+            t.f = f; t.gnorm = gnorm; t.delta = delta; t.ared = ared; t.pred = pred; t.snorm = snorm;
+        }
+        if (accepted && gnorm <= P.eps * res->gnorm0) { status = TRON_OK; res->converged = 1; break; }
+        if (pred <= 0.0 || (noise && gnorm >= gnorm_before)) break;
+    }
+    res->f = f;
+    res->gnorm = gnorm;
+    TRON_HIP(hipMemcpyAsync(w_dev, w, dbytes, hipMemcpyDeviceToDevice, ds->stream));
+    TRON_HIP(hipStreamSynchronize(ds->stream));
+    return status;
+}

@@ -1,0 +1,270 @@
+"""GPU parity: every call goes through the C ABI and is compared with the CPU oracle
+element by element (norm-wise 1e-10 per call; objective 1e-8 and identical trajectory per solve)."""
+import numpy as np
+import pytest
+
+import datagen as dg
+from datagen import DenseProblem, SparseProblem
+from oracle import LOSS_LR, LOSS_L2SVM
+
+pytestmark = pytest.mark.gpu
+
+from util import check_calls, compare_solves, dev, torch_mod  # noqa: E402
+
+
+def _dense(rng, n, d, name="rand"):
+    X = rng.standard_normal((n, d))
+    y = np.where(rng.random(n) < 0.5, 1.0, -1.0)
+    return DenseProblem(name, n, d, X, y)
+
+
+def _csr_from_dense(X, y, name="rand"):
+    n, d = X.shape
+    rowptr = np.zeros(n + 1, dtype=np.int64)
+    rowptr[1:] = np.cumsum((X != 0).sum(axis=1))
+    rr, cc = np.nonzero(X)
+    return SparseProblem(name, n, d, rowptr, cc.astype(np.int32), X[rr, cc].copy(), y)
+
+
+# ------------------------------------------------------------------ dense layout
+@pytest.mark.parametrize("loss", [LOSS_LR, LOSS_L2SVM])
+@pytest.mark.parametrize("n,d", [(1000, 24), (4097, 24), (777, 18), (513, 7), (300, 1), (64, 8), (1025, 33),
+                                 (2050, 28), (999, 32), (515, 100), (130, 257), (70, 512), (1, 24), (63, 5)])
+def test_dense_calls(rng, loss, n, d):
+    check_calls(_dense(rng, n, d), loss, 0.7, rng, w_scale=0.5 / np.sqrt(d))
+
+
+@pytest.mark.parametrize("loss", [LOSS_LR, LOSS_L2SVM])
+def test_dense_many_tiles_ragged_tail(rng, loss):
+    # more wave tiles than resident wavefronts (grid-stride loop taken several times) + ragged tail
+    p = dg.config4(n=700_001)
+    check_calls(p, loss, p.C, rng, w_scale=0.05, n_hv=1)
+
+
+# ------------------------------------------------------------------ CSR layout
+@pytest.mark.parametrize("loss", [LOSS_LR, LOSS_L2SVM])
+def test_csr_config1(rng, loss):
+    check_calls(dg.config1(), loss, 1.0, rng, w_scale=1.0)
+
+
+@pytest.mark.parametrize("loss", [LOSS_LR, LOSS_L2SVM])
+def test_csr_zipf_skew(rng, loss):
+    # Zipf columns: the transposed copy has rows spanning many chunks next to empty ones
+    check_calls(dg.config2(), loss, 1.0, rng, w_scale=1.0)
+
+
+def test_csr_url_shape_small(rng):
+    p = dg.config3(scale=0.02)
+    check_calls(p, LOSS_LR, 1.0, rng, w_scale=1.0, n_hv=1)
+
+
+@pytest.mark.parametrize("loss", [LOSS_LR, LOSS_L2SVM])
+def test_csr_degenerate_shapes(rng, loss):
+    # empty rows / columns, one very long row and one very long column, single-entry rows
+    n, d = 3000, 5000
+    X = rng.standard_normal((n, d)) * (rng.random((n, d)) < 0.002)
+    X[5] = rng.standard_normal(d)          # dense row: spans several chunks
+    X[:, 17] = rng.standard_normal(n)      # dense column: long row of the transposed copy
+    X[100:140] = 0.0                       # run of empty rows
+    X[:, 2000:2600] = 0.0                  # run of empty columns
+    X[n - 1] = 0.0                         # trailing empty row
+    X[:, d - 1] = 0.0                      # trailing empty column
+    y = np.where(rng.random(n) < 0.5, 1.0, -1.0)
+    check_calls(_csr_from_dense(X, y), loss, 0.5, rng, w_scale=0.2)
+
+
+def test_csr_tiny_and_empty(rng):
+    # nnz = 0, and a 1 x 1 matrix
+    y = np.array([1.0, -1.0, 1.0])
+    p = SparseProblem("empty", 3, 4, np.zeros(4, dtype=np.int64), np.zeros(0, dtype=np.int32), np.zeros(0), y)
+    check_calls(p, LOSS_LR, 1.0, rng)
+    p = SparseProblem("one", 1, 1, np.array([0, 1], dtype=np.int64), np.array([0], dtype=np.int32), np.array([2.0]),
+                      np.array([-1.0]))
+    check_calls(p, LOSS_L2SVM, 1.0, rng)
+
+
+def test_csr_exact_chunk_multiple(rng):
+    # nnz an exact multiple of the 2048-nonzero chunk, last rows empty
+    n, d, per = 130, 64, 32
+    X = np.zeros((n, d))
+    for i in range(128):
+        X[i, rng.choice(d, per, replace=False)] = rng.standard_normal(per)
+    y = np.where(rng.random(n) < 0.5, 1.0, -1.0)
+    p = _csr_from_dense(X, y)
+    assert p.nnz == 4096
+    check_calls(p, LOSS_LR, 1.0, rng)
+
+
+def test_csr_matches_dense_layout(rng):
+    torch = torch_mod()
+    import paper_2008_03433_amd as tron
+    n, d = 1500, 24
+    X = rng.standard_normal((n, d)) * (rng.random((n, d)) < 0.5)
+    y = np.where(rng.random(n) < 0.5, 1.0, -1.0)
+    a = tron.Dataset.from_problem(DenseProblem("d", n, d, X, y))
+    b = tron.Dataset.from_problem(_csr_from_dense(X, y))
+    w = dev(0.2 * rng.standard_normal(d)); v = dev(rng.standard_normal(d))
+    ga, gb, Ha, Hb = (torch.empty(d, dtype=torch.float64, device="cuda") for _ in range(4))
+    for loss in (LOSS_LR, LOSS_L2SVM):
+        fa, fb = a.fun_grad(loss, 1.0, w, ga), b.fun_grad(loss, 1.0, w, gb)
+        assert abs(fa - fb) <= 1e-13 * abs(fa)
+        np.testing.assert_allclose(ga.cpu().numpy(), gb.cpu().numpy(), rtol=1e-12, atol=1e-12)
+        a.hv(1.0, v, Ha); b.hv(1.0, v, Hb)
+        np.testing.assert_allclose(Ha.cpu().numpy(), Hb.cpu().numpy(), rtol=1e-12, atol=1e-12)
+    a.close(); b.close()
+
+
+# ------------------------------------------------------------------ special values
+def test_svm_ties_and_extreme_margins(rng):
+    torch = torch_mod()
+    import paper_2008_03433_amd as tron
+    from oracle import Oracle
+    # exactly representable margins: y z == 1 must be inactive on both sides
+    X = np.array([[1.0, 0.0], [-1.0, 0.0], [0.5, 0.0], [0.0, 1.0]])
+    y = np.array([1.0, -1.0, 1.0, -1.0])
+    p = DenseProblem("ties", 4, 2, X, y)
+    o = Oracle.from_problem(p)
+    ds = tron.Dataset.from_problem(p)
+    w = np.array([1.0, 3.0])
+    g = torch.empty(2, dtype=torch.float64, device="cuda")
+    f = ds.fun_grad(LOSS_L2SVM, 1.0, dev(w), g)
+    fo, go, Do = o.fun_grad(LOSS_L2SVM, 1.0, w)
+    assert f == fo and np.array_equal(g.cpu().numpy(), go)
+    v = np.array([1.0, 1.0]); Hv = torch.empty_like(g)
+    ds.hv(1.0, dev(v), Hv)
+    assert np.array_equal(Hv.cpu().numpy(), o.hv(1.0, Do, v))
+    ds.close()
+    # logistic loss at |y z| up to 700: finite, matches the oracle
+    X = np.array([[700.0], [-700.0], [40.0], [-40.0], [1e-9], [0.0]])
+    y = np.array([1.0, 1.0, -1.0, -1.0, 1.0, -1.0])
+    check_calls(DenseProblem("big", 6, 1, X, y), LOSS_LR, 1.0, rng, w_scale=0.0)
+    p = DenseProblem("big", 6, 1, X, y)
+    ds = tron.Dataset.from_problem(p)
+    f = ds.fun_grad(LOSS_LR, 1.0, dev(np.array([1.0])), g[:1])
+    fo, go, _ = Oracle.from_problem(p).fun_grad(LOSS_LR, 1.0, np.array([1.0]))
+    assert abs(f - fo) <= 1e-12 * abs(fo) and np.isfinite(g[:1].cpu().numpy()).all()
+    ds.close()
+
+
+# ------------------------------------------------------------------ determinism / state
+def test_repeated_calls_are_bitwise_identical(rng):
+    torch = torch_mod()
+    import paper_2008_03433_amd as tron
+    for p in (dg.config2(), dg.config4(n=50_000)):
+        ds = tron.Dataset.from_problem(p)
+        w = dev(0.1 * rng.standard_normal(p.d)); v = dev(rng.standard_normal(p.d))
+        g1, g2, H1, H2 = (torch.empty(p.d, dtype=torch.float64, device="cuda") for _ in range(4))
+        f1 = ds.fun_grad(p.loss, p.C, w, g1); q1 = ds.hv(p.C, v, H1)
+        f2 = ds.fun_grad(p.loss, p.C, w, g2); q2 = ds.hv(p.C, v, H2)
+        assert f1 == f2 and q1 == q2
+        assert torch.equal(g1, g2) and torch.equal(H1, H2)
+        ds.close()
+
+
+def test_hv_requires_fun_grad(rng):
+    torch = torch_mod()
+    import paper_2008_03433_amd as tron
+    ds = tron.Dataset.from_problem(_dense(rng, 100, 4))
+    v = dev(np.ones(4)); Hv = torch.empty_like(v)
+    with pytest.raises(tron.TronError) as e:
+        ds.hv(1.0, v, Hv)
+    assert e.value.code == -4
+    with pytest.raises(tron.TronError) as e:
+        ds.fun_grad(LOSS_LR, -1.0, v)
+    assert e.value.code == -1
+    ds.close()
+
+
+def test_invalid_inputs_are_rejected(rng):
+    import paper_2008_03433_amd as tron
+    y = np.array([1.0, -1.0])
+    bad = [
+        (np.array([0, 2, 1], dtype=np.int64), np.array([0, 1], dtype=np.int32), np.ones(2), y),      # rowptr decreases
+        (np.array([0, 2, 2], dtype=np.int64), np.array([1, 0], dtype=np.int32), np.ones(2), y),      # unsorted columns
+        (np.array([0, 2, 2], dtype=np.int64), np.array([0, 0], dtype=np.int32), np.ones(2), y),      # duplicate column
+        (np.array([0, 1, 2], dtype=np.int64), np.array([0, 3], dtype=np.int32), np.ones(2), y),      # column out of range
+        (np.array([0, 1, 2], dtype=np.int64), np.array([0, 1], dtype=np.int32), np.array([1.0, np.nan]), y),
+        (np.array([0, 1, 2], dtype=np.int64), np.array([0, 1], dtype=np.int32), np.ones(2), np.array([1.0, 0.0])),
+    ]
+    for rowptr, col, val, yy in bad:
+        with pytest.raises(tron.TronError) as e:
+            tron.tron_dataset_create_csr(2, 3, rowptr, col, val, yy)
+        assert e.value.code == -1
+    with pytest.raises(tron.TronError):
+        tron.tron_dataset_create_dense(2, 2, np.array([[1.0, np.inf], [0.0, 1.0]]), y)
+    with pytest.raises(tron.TronError):
+        tron.tron_dataset_create_dense(2, 600, np.zeros((2, 600)), y)
+
+
+# ------------------------------------------------------------------ full solves
+def test_solve_config1():
+    p = dg.config1()
+    compare_solves(p, p.loss, p.C, p.eps)
+
+
+def test_solve_config2():
+    p = dg.config2()
+    res, ref = compare_solves(p, p.loss, p.C, p.eps)
+    assert res.cg_iters_total > 10
+
+
+def test_solve_config2_svm_loss():
+    # Off-config stress: H = I + X^T X has a well separated top eigenvalue (~2e3, the Zipf head feature),
+    # so CG iterates are sensitive to rounding (plain-fp64 numpy CG departs from the long-double oracle by
+    # ~4e-7 in s after 10 iterations, ~2e-5 in f by the second outer iteration).  The iterates along the
+    # way are compared at 1e-4, the final
+    # objective still at 1e-8.
+    p = dg.config2()
+    compare_solves(p, LOSS_L2SVM, 0.5, 1e-3, trace_rel=1e-4)
+
+
+def test_solve_config4_reduced():
+    p = dg.config4(n=200_000)
+    compare_solves(p, p.loss, p.C, p.eps)
+
+
+def test_solve_dense_lr_tight(rng):
+    p = _dense(rng, 5000, 18)
+    compare_solves(p, LOSS_LR, 2.0, 1e-6)
+
+
+def test_solve_hits_trust_region_boundary(rng):
+    # far-away start with saturated sigmoids: the quadratic model is poor, steps get rejected, the
+    # radius shrinks and CG ends on the boundary (H >= I means the very first step from Delta_0 = |g|
+    # can never be on the boundary)
+    rng = np.random.default_rng(5)
+    n, d = 2000, 40
+    X = 3.0 * rng.standard_normal((n, d)) * (rng.random((n, d)) < 0.3)
+    y = np.where(rng.random(n) < 0.5, 1.0, -1.0)
+    w0 = 3.0 * rng.standard_normal(d)
+    for p in (_csr_from_dense(X, y), DenseProblem("far", n, d, X, y)):
+        res, ref = compare_solves(p, LOSS_LR, 50.0, 1e-4, w0=w0)
+        assert sum(t["on_boundary"] for t in ref.trace) >= 5
+        assert sum(1 - t["accepted"] for t in ref.trace) >= 5
+
+
+def test_solve_warm_start_and_iteration_cap(rng):
+    torch = torch_mod()
+    import paper_2008_03433_amd as tron
+    from oracle import Oracle
+    p = _dense(rng, 3000, 12)
+    o = Oracle.from_problem(p)
+    ds = tron.Dataset.from_problem(p)
+    w = torch.zeros(p.d, dtype=torch.float64, device="cuda")
+    r1 = ds.solve(LOSS_LR, 5.0, 1e-10, w, max_outer=2)
+    ref1 = o.tron(LOSS_LR, 5.0, 1e-10, max_outer=2)
+    assert r1.status == 1 and ref1.status == 1 and r1.outer_iters == 2
+    assert abs(r1.f - ref1.f) <= 1e-8 * abs(ref1.f)
+    # continue from the iterate (w0 != 0: the stopping reference is still |grad f(0)|)
+    r2 = ds.solve(LOSS_LR, 5.0, 1e-6, w)
+    ref2 = o.tron(LOSS_LR, 5.0, 1e-6, w0=ref1.w)
+    assert r2.converged and ref2.converged
+    assert abs(r2.gnorm0 - ref2.gnorm0) <= 1e-10 * ref2.gnorm0
+    assert r2.outer_iters == ref2.outer_iters
+    assert abs(r2.f - ref2.f) <= 1e-8 * abs(ref2.f)
+    # tron_hv may follow a solve: D at the final iterate is cached
+    v = dev(rng.standard_normal(p.d)); Hv = torch.empty_like(v)
+    ds.hv(5.0, v, Hv)
+    _, _, D = o.fun_grad(LOSS_LR, 5.0, w.cpu().numpy())
+    np.testing.assert_allclose(Hv.cpu().numpy(), o.hv(5.0, D, v.cpu().numpy()), rtol=1e-9, atol=1e-9)
+    ds.close()
