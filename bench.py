@@ -131,6 +131,7 @@ def main() -> int:
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only; reported)")
     ap.add_argument("--hv-reps", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tune", action="append", default=[], metavar="KNOB=VALUE", help="library tuning knob (see tron_tuning_set)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1",
@@ -147,6 +148,9 @@ def main() -> int:
         return 3
     torch.cuda.set_device(0)
     tron.load_library()
+    for kv in args.tune:
+        k, v_ = kv.split("=")
+        tron.tron_tuning_set(k, int(v_))
 
     t0 = time.time()
     log(f"generating workload {args.workload} (scale {args.scale:g}) with {dg.num_threads()} host threads")
@@ -219,15 +223,16 @@ def main() -> int:
         except KeyError:
             per_kernel[k] = {"ms": rec["ms"]}
 
-    # attainable streaming-read rate on this device, for context
-    probe_n = min(ds.n * ds.d if ds.dense else 1 << 28, 1 << 29)
-    probe_src = torch.empty(probe_n, dtype=torch.float64, device="cuda").normal_() if not ds.dense else None
-    if ds.dense:
-        probe = None
-    else:
-        ms_probe, _ = tron.tron_probe_read_bandwidth(probe_src, probe_n, reps=10)
-        probe = {"GB/s": probe_n * 8 / (ms_probe * 1e-3) / 1e9, "bytes": probe_n * 8}
-        del probe_src
+    # attainable streaming rates on this device, for context (and the known-size kernels the hardware
+    # byte counters are scaled with): a 2 GiB read-only sum and a 1 GiB -> 1 GiB copy
+    probe_n = 1 << 28
+    probe_src = torch.empty(probe_n, dtype=torch.float64, device="cuda").normal_()
+    ms_probe, _ = tron.tron_probe_read_bandwidth(probe_src, probe_n, reps=10)
+    half = probe_n // 2
+    ms_copy = tron.tron_probe_copy_bandwidth(probe_src[half:], probe_src[:half], half, reps=10)
+    probe = {"read_GB/s": probe_n * 8 / (ms_probe * 1e-3) / 1e9, "read_bytes": probe_n * 8,
+             "copy_GB/s": 2 * half * 8 / (ms_copy * 1e-3) / 1e9, "copy_bytes_read": half * 8, "copy_bytes_written": half * 8}
+    del probe_src
 
     out = {
         "metric": "Hessian-vector products/sec (sustained over full TRON solves) + % HBM peak; end-to-end TRON solve seconds",
@@ -235,7 +240,7 @@ def main() -> int:
         "ms_per_step": solve_s * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f64", "data": "synthetic",
         "config": {"workload": name, "n": ds.n, "d": ds.d, "nnz": ds.nnz, "layout": "dense" if ds.dense else "csr+csr^T",
-                   "loss": "l2svm" if loss == dg.LOSS_L2SVM else "lr", "C": C, "eps": eps, "scale": args.scale},
+                   "loss": "l2svm" if loss == dg.LOSS_L2SVM else "lr", "C": C, "eps": eps, "scale": args.scale, "tune": args.tune},
         "solve": {"seconds": solve_s, "outer_iters": res.outer_iters, "cg_iters": res.cg_iters_total, "n_fun": res.n_fun,
                   "n_grad": res.n_grad, "n_hv": res.n_hv, "f": res.f, "gnorm": res.gnorm, "gnorm0": res.gnorm0,
                   "converged": res.converged},
@@ -244,7 +249,7 @@ def main() -> int:
         "fun_grad_call": {"per_s": 1.0 / fg_s, "ms": fg_s * 1e3},
         "kernels": per_kernel,
         "roofline": roofline,
-        "read_probe": probe,
+        "stream_probe": probe,
     }
     if not args.no_cpu_baseline:
         log("timing the CPU oracle (one thread, bounded sample)")

@@ -189,6 +189,23 @@ TRON_API int tron_profile_read(tron_dataset *ds, int cap, const char **names, do
 TRON_API int tron_probe_read_bandwidth(const double *src_dev, int64_t count, int reps, void *hip_stream,
                                        double *ms_per_launch, double *checksum);
 
+/*
+ * Process-wide tuning knobs, read when a dataset is created.  Results do not depend on them beyond
+ * floating-point summation order.
+ *   "csr_parts": column partitions of the two CSR layouts: 0 = automatic (8 when the gathered
+ *                vector would not stay resident in one L2, else 1), 1 = never partition, 8 = always.
+ * Unknown names or values return TRON_EINVAL.
+ */
+TRON_API int tron_tuning_set(const char *name, int64_t value);
+
+/*
+ * Plain copy probe: dst[i] = src[i] for `count` doubles, `reps` launches, average milliseconds per
+ * launch.  A kernel of known read and write size: the yardstick the hardware byte counters
+ * (FETCH_SIZE / WRITE_SIZE) are scaled with.
+ */
+TRON_API int tron_probe_copy_bandwidth(double *dst_dev, const double *src_dev, int64_t count, int reps,
+                                       void *hip_stream, double *ms_per_launch);
+
 #ifdef __cplusplus
 }
 #endif

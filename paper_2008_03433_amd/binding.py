@@ -54,6 +54,8 @@ _SIGNATURES = {
     "tron_profile_enable": (_int, [_vp, _int]),
     "tron_profile_read": (_int, [_vp, _int, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(_dbl), ctypes.POINTER(_i64), ctypes.POINTER(_int)]),
     "tron_probe_read_bandwidth": (_int, [_vp, _i64, _int, _vp, ctypes.POINTER(_dbl), ctypes.POINTER(_dbl)]),
+    "tron_tuning_set": (_int, [ctypes.c_char_p, _i64]),
+    "tron_probe_copy_bandwidth": (_int, [_vp, _vp, _i64, _int, _vp, ctypes.POINTER(_dbl)]),
 }
 
 _lib = None
@@ -216,6 +218,16 @@ def tron_probe_read_bandwidth(src, count, reps=10, stream=None) -> Tuple[float, 
     ms, cs = _dbl(), _dbl()
     _check(load_library().tron_probe_read_bandwidth(_ptr(src), count, reps, _stream_ptr(stream), ctypes.byref(ms), ctypes.byref(cs)))
     return ms.value, cs.value
+
+
+def tron_tuning_set(name: str, value: int) -> None:
+    _check(load_library().tron_tuning_set(name.encode(), value))
+
+
+def tron_probe_copy_bandwidth(dst, src, count, reps=10, stream=None) -> float:
+    ms = _dbl()
+    _check(load_library().tron_probe_copy_bandwidth(_ptr(dst), _ptr(src), count, reps, _stream_ptr(stream), ctypes.byref(ms)))
+    return ms.value
 
 
 # --------------------------------------------------------------------------- convenience wrapper

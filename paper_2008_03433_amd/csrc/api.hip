@@ -1,4 +1,5 @@
 // C ABI entry points: dataset handles, argument checking, profiling, error text.
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -8,6 +9,8 @@
 #include "common.h"
 
 namespace tron {
+
+Tuning g_tuning;
 
 // ------------------------------------------------------------------ errors
 static thread_local char g_err[512] = "";
@@ -29,7 +32,7 @@ int hip_fail(hipError_t e, const char *what, const char *file, int line)
 
 // ------------------------------------------------------------------ profiler
 const char *const kSlotNames[SLOT_COUNT] = {
-    "spmv_fwd_z", "spmv_fwd_a1", "spmv_bwd_g", "spmv_bwd_hv", "spmv_fixup", "loss_terms",
+    "spmv_fwd_z", "spmv_fwd_a1", "spmv_bwd_g", "spmv_bwd_hv", "spmv_fixup", "spmv_combine", "loss_terms",
     "dense_fun_grad", "dense_hv", "dense_finalize", "dot", "reduce_final", "cg_vec"};
 
 int Profiler::begin(int slot, hipStream_t st)
@@ -162,7 +165,7 @@ void tron_dataset_destroy(tron_dataset *ds)
     ds->fwd.release();
     ds->bwd.release();
     hipFree(ds->y); hipFree(ds->z); hipFree(ds->zhat); hipFree(ds->Dbuf[0]); hipFree(ds->Dbuf[1]);
-    hipFree(ds->partials); hipFree(ds->scal_dev);
+    hipFree(ds->partials); hipFree(ds->row_partials); hipFree(ds->scal_dev);
     if (ds->scal_host) hipHostFree(ds->scal_host);
     for (double *p : ds->sv) hipFree(p);
     ds->prof.destroy();
@@ -231,8 +234,17 @@ int tron_dataset_create_csr(int64_t n, int64_t d, const int64_t *rowptr, const i
     if (!ds) { set_error("out of host memory"); return TRON_ENOMEM; }
     ds->n = n; ds->d = d; ds->dense = false; ds->stream = reinterpret_cast<hipStream_t>(hip_stream);
     int rc = alloc_common(ds);
-    if (rc >= 0) rc = csr_plan_build(ds->fwd, n, d, h_rowptr.data(), h_col.data(), h_val.data(), ds->stream);
-    if (rc >= 0) rc = csr_plan_build(ds->bwd, d, n, t_rowptr.data(), t_col.data(), t_val.data(), ds->stream);
+    if (rc >= 0) rc = csr_plan_build(ds->fwd, n, d, h_rowptr.data(), h_col.data(), h_val.data(), (int)g_tuning.csr_parts, g_tuning.csr_hot != 0, ds->stream);
+    if (rc >= 0) rc = csr_plan_build(ds->bwd, d, n, t_rowptr.data(), t_col.data(), t_val.data(), (int)g_tuning.csr_parts, false, ds->stream);
+    if (rc >= 0) {
+        int64_t need = 0;
+        if (ds->fwd.P > 1) need = std::max<int64_t>(need, (int64_t)ds->fwd.P * n);
+        if (ds->bwd.P > 1) need = std::max<int64_t>(need, (int64_t)ds->bwd.P * d);
+        if (need > 0) {
+            hipError_t e = hipMalloc(reinterpret_cast<void **>(&ds->row_partials), sizeof(double) * need);
+            if (e != hipSuccess) rc = hip_fail(e, "allocate row partials", __FILE__, __LINE__);
+        }
+    }
     if (rc >= 0) {
         hipError_t e = hipMemcpyAsync(ds->y, h_y.data(), sizeof(double) * n, hipMemcpyHostToDevice, ds->stream);
         if (e == hipSuccess) e = hipStreamSynchronize(ds->stream);
@@ -377,6 +389,31 @@ int tron_probe_read_bandwidth(const double *src_dev, int64_t count, int reps, vo
 {
     TRON_TRY(check_device());
     return probe_read(src_dev, count, reps, reinterpret_cast<hipStream_t>(hip_stream), ms_per_launch, checksum);
+}
+
+int tron_tuning_set(const char *name, int64_t value)
+{
+    if (name && strcmp(name, "csr_parts") == 0 && (value == 0 || value == 1 || value == kMaxParts)) {
+        g_tuning.csr_parts = value;
+        return TRON_OK;
+    }
+    if (name && strcmp(name, "csr_hot") == 0 && (value == 0 || value == 1)) {
+        g_tuning.csr_hot = value;
+        return TRON_OK;
+    }
+    if (name && strcmp(name, "csr_hot_blocks_per_part") == 0 && value >= 1 && value <= 4096) {
+        g_tuning.csr_hot_blocks_per_part = value;
+        return TRON_OK;
+    }
+    set_error("tron_tuning_set: unknown knob or value out of range");
+    return TRON_EINVAL;
+}
+
+int tron_probe_copy_bandwidth(double *dst_dev, const double *src_dev, int64_t count, int reps, void *hip_stream,
+                              double *ms_per_launch)
+{
+    TRON_TRY(check_device());
+    return probe_copy(dst_dev, src_dev, count, reps, reinterpret_cast<hipStream_t>(hip_stream), ms_per_launch);
 }
 
 }  // extern "C"

@@ -27,6 +27,14 @@ int hip_fail(hipError_t e, const char *what, const char *file, int line);
         if (rc__ < 0) return rc__; \
     } while (0)
 
+// ---------------------------------------------------------------- process-wide tuning knobs (tron_tuning_set)
+struct Tuning {
+    int64_t csr_parts = 0;   // column partitions of the CSR layouts: 0 = automatic, 1 = never, 8 = always
+    int64_t csr_hot = 1;     // LDS table of frequent columns for the partitioned forward layout (0 = off)
+    int64_t csr_hot_blocks_per_part = 96;  // persistent workgroups per partition (x 8 partitions)
+};
+extern Tuning g_tuning;
+
 // ---------------------------------------------------------------- launch geometry
 constexpr int kBlock = 256;          // threads per workgroup everywhere (4 wavefronts of 64)
 constexpr int kWave = 64;
@@ -42,6 +50,7 @@ enum Slot {
     SLOT_SPMV_BWD_G,       // g = w + C X^T zhat
     SLOT_SPMV_BWD_HV,      // Hv = v + C X^T a1
     SLOT_SPMV_FIXUP,       // rows split across workgroups
+    SLOT_SPMV_COMBINE,     // sum of the column partitions' partial row sums + epilogue
     SLOT_LOSS_TERMS,       // zhat, D, sum loss from z
     SLOT_DENSE_FUN_GRAD,   // fused dense z / loss / D / X^T zhat
     SLOT_DENSE_HV,         // fused dense X^T (D (X v))
@@ -67,22 +76,46 @@ struct Profiler {
 };
 
 // ---------------------------------------------------------------- CSR work partition
-// One orientation of the sparse matrix (rows x cols) with the nnz-balanced partition the SpMV
-// kernel uses: workgroup b streams nonzeros [b*kChunk, (b+1)*kChunk) and owns the rows that
-// *start* in that range, rows [row_lo[b], row_lo[b+1]).  A row that continues into later chunks
-// gets the remainder through `carry` and the fix-up list.
+// One orientation of the sparse matrix (rows x cols) laid out for the SpMV kernels.
+//
+// Work is split by nonzeros: a workgroup streams one chunk of kChunk consecutive nonzeros and owns
+// the rows that *start* inside it (rows [row_lo[c], row_lo[c+1])); a row that continues into later
+// chunks receives the remainder through `carry` and the fix-up list.
+//
+// When the vector that is gathered from (length cols) is too large to stay in one L2, the column
+// space is additionally cut into P contiguous ranges with equal nonzero counts, and the nonzeros are
+// stored range-major ("partitioned"): partition x holds, row by row, the entries whose column lies in
+// range x.  Workgroup b works on partition b % P, so -- with workgroups dealt round-robin to the 8
+// XCDs -- each XCD's L2 only ever gathers from its own 1/8 slice of the vector.  Partitions produce
+// partial row sums (P x rows); a combine kernel adds them in a fixed order and applies the epilogue.
+constexpr int kMaxParts = 8;
+constexpr int kHotSlots = 4096;   // LDS table entries per workgroup (32 KiB)
+
 struct CsrPlan {
     int64_t rows = 0, cols = 0, nnz = 0;
-    int64_t *rowptr = nullptr;   // device, rows+1
-    int32_t *col = nullptr;      // device, nnz
-    double *val = nullptr;       // device, nnz
-    int nblocks = 0;
-    int32_t *row_lo = nullptr;   // device, nblocks+1
-    double *carry = nullptr;     // device, nblocks: partial sum of the row entering chunk b from before
-    int nfix = 0;                // number of split rows
-    int32_t *fix_row = nullptr;  // device, nfix: the split row
-    int32_t *fix_b0 = nullptr;   // device, nfix: first chunk holding a continuation of it
-    int32_t *fix_cnt = nullptr;  // device, nfix: number of consecutive chunks that do
+    int P = 1;                           // number of column partitions (1 = unpartitioned)
+    // P == 1: plain CSR
+    int64_t *rowptr = nullptr;           // device, rows+1
+    // P > 1: per-partition row offsets relative to the partition's first nonzero
+    int32_t *rowptr32 = nullptr;         // device, P*(rows+1)
+    int64_t part_base[kMaxParts] = {0};  // position of partition x in col/val (multiple of kChunk)
+    int64_t part_nnz[kMaxParts] = {0};
+    int part_chunk0[kMaxParts] = {0};    // first chunk id of partition x (= part_base / kChunk)
+    int part_nchunks[kMaxParts] = {0};
+    int part_nhot[kMaxParts] = {0};     // LDS-resident columns of partition x
+    int32_t *hot_ids = nullptr;          // device, P*kHotSlots column ids (null: no LDS table); such columns are
+                                         // stored in `col` as ~slot
+    int max_chunks = 0;                  // max over partitions
+    int32_t *col = nullptr;              // device, padded nnz
+    double *val = nullptr;               // device, padded nnz
+    int nblocks = 0;                     // total number of chunks
+    int32_t *row_lo = nullptr;           // device; partition x: entries [part_chunk0[x] + x, ... + nchunks + 1)
+    double *carry = nullptr;             // device, nblocks: sum of the part of a row entering chunk c from before
+    int nfix = 0;                        // number of (partition, split row) pairs
+    int32_t *fix_row = nullptr;          // device, nfix: the split row
+    int32_t *fix_part = nullptr;         // device, nfix: its partition
+    int32_t *fix_b0 = nullptr;           // device, nfix: first chunk id holding a continuation of it
+    int32_t *fix_cnt = nullptr;          // device, nfix: number of consecutive chunks that do
     void release();
 };
 
@@ -108,6 +141,7 @@ struct tron_dataset {
     bool have_D = false;
 
     // reductions
+    double *row_partials = nullptr;  // sparse, partitioned: P x max(n, d) partial row sums
     double *partials = nullptr;  // device scratch for first-stage partial sums
     int64_t partials_len = 0;
     double *scal_dev = nullptr;  // kScalars device scalars
@@ -145,14 +179,21 @@ int cg_dir(tron_dataset *ds, double beta, const double *r, const double *s, doub
 int trial_point(tron_dataset *ds, const double *w, const double *s, const double *g, const double *r,
                 double *wnew);  // wnew = w+s; slots: g.s, s.r, s.s
 int probe_read(const double *src, int64_t count, int reps, hipStream_t st, double *ms, double *checksum);
+int probe_copy(double *dst, const double *src, int64_t count, int reps, hipStream_t st, double *ms);
 
 // ---- kernels_csr.hip
+// parts: 1 = plain CSR, 0 = choose from the size of the gathered vector
 int csr_plan_build(CsrPlan &P, int64_t rows, int64_t cols, const int64_t *h_rowptr, const int32_t *h_col,
-                   const double *h_val, hipStream_t st);
-enum { EPI_PLAIN = 0, EPI_SCALE = 1, EPI_AXPY = 2 };
-// y[r] = epilogue( sum_k val[k] x[col[k]] ):  PLAIN: sum;  SCALE: scale[r]*sum;  AXPY: add[r] + alpha*sum
-int csr_spmv(tron_dataset *ds, const CsrPlan &P, int slot, int epi, const double *x, double *yout,
-             const double *scale_or_add, double alpha);
+                   const double *h_val, int parts, bool hot, hipStream_t st);
+// Products with one orientation; all enqueue on ds->stream.
+//   spmv_loss:  z = A x, then per-instance loss terms: zhat, D; partial slot 0 of ds->partials = sum loss
+//   spmv_scale: out = scale .* (A x)
+//   spmv_axpy:  out = add + alpha (A x); partial slot 0 = out . (dot_self ? out : add)
+// Each returns the number of first-stage partials in slot 0 (0 if none), or a negative error.
+int spmv_loss(tron_dataset *ds, const CsrPlan &A, int slot, int loss, const double *x, double *zwork, double *zhat, double *D);
+int spmv_scale(tron_dataset *ds, const CsrPlan &A, int slot, const double *x, const double *scale, double *out);
+int spmv_axpy(tron_dataset *ds, const CsrPlan &A, int slot, const double *x, const double *add, double alpha,
+              bool dot_self, double *out);
 
 // ---- kernels_dense.hip
 bool dense_supported(int64_t d);

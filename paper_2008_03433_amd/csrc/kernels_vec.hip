@@ -248,6 +248,37 @@ __global__ __launch_bounds__(kBlock) void k_probe_sum(const double2 *__restrict_
     if (threadIdx.x == 0) out[blockIdx.x] = a;
 }
 
+__global__ __launch_bounds__(kBlock) void k_probe_copy(double2 *__restrict__ dst, const double2 *__restrict__ src, int64_t count2)
+{
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < count2; i += stride) dst[i] = src[i];
+}
+
+int probe_copy(double *dst, const double *src, int64_t count, int reps, hipStream_t st, double *ms)
+{
+    if (!src || !dst || count < 2 || reps < 1 || ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15)) {
+        set_error("tron_probe_copy_bandwidth: need 16-byte aligned device pointers, count >= 2, reps >= 1");
+        return TRON_EINVAL;
+    }
+    hipEvent_t e0, e1;
+    TRON_HIP(hipEventCreate(&e0));
+    TRON_HIP(hipEventCreate(&e1));
+    hipLaunchKernelGGL(k_probe_copy, dim3(kMaxGrid), dim3(kBlock), 0, st, reinterpret_cast<double2 *>(dst),
+                       reinterpret_cast<const double2 *>(src), count / 2);
+    TRON_HIP(hipEventRecord(e0, st));
+    for (int r = 0; r < reps; ++r)
+        hipLaunchKernelGGL(k_probe_copy, dim3(kMaxGrid), dim3(kBlock), 0, st, reinterpret_cast<double2 *>(dst),
+                           reinterpret_cast<const double2 *>(src), count / 2);
+    TRON_HIP(hipEventRecord(e1, st));
+    TRON_HIP(hipEventSynchronize(e1));
+    float t = 0.f;
+    TRON_HIP(hipEventElapsedTime(&t, e0, e1));
+    if (ms) *ms = (double)t / reps;
+    hipEventDestroy(e0);
+    hipEventDestroy(e1);
+    return TRON_OK;
+}
+
 int probe_read(const double *src, int64_t count, int reps, hipStream_t st, double *ms, double *checksum)
 {
     if (!src || count < 2 || reps < 1 || (reinterpret_cast<uintptr_t>(src) & 15)) {

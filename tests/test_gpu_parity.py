@@ -73,6 +73,50 @@ def test_csr_degenerate_shapes(rng, loss):
     check_calls(_csr_from_dense(X, y), loss, 0.5, rng, w_scale=0.2)
 
 
+@pytest.fixture
+def force_partitions():
+    import paper_2008_03433_amd as tron
+    tron.tron_tuning_set("csr_parts", 8)
+    yield
+    tron.tron_tuning_set("csr_parts", 0)
+
+
+@pytest.mark.parametrize("loss", [LOSS_LR, LOSS_L2SVM])
+def test_csr_partitioned_layout(rng, loss, force_partitions):
+    # the 8-way column-partitioned layout (used for large matrices) forced on small and skewed ones
+    check_calls(dg.config2(), loss, 1.0, rng, w_scale=1.0, n_hv=1)
+    n, d = 3000, 5000
+    X = rng.standard_normal((n, d)) * (rng.random((n, d)) < 0.002)
+    X[5] = rng.standard_normal(d)
+    X[:, 17] = rng.standard_normal(n)
+    X[100:140] = 0.0
+    X[:, 2000:2600] = 0.0
+    X[n - 1] = 0.0
+    X[:, d - 1] = 0.0
+    y = np.where(rng.random(n) < 0.5, 1.0, -1.0)
+    check_calls(_csr_from_dense(X, y), loss, 0.5, rng, w_scale=0.2, n_hv=1)
+    # fewer columns than partitions, and an all-zero matrix
+    X = rng.standard_normal((50, 3))
+    check_calls(_csr_from_dense(X, np.where(rng.random(50) < 0.5, 1.0, -1.0)), loss, 1.0, rng, n_hv=1)
+    p = SparseProblem("empty", 3, 4, np.zeros(4, dtype=np.int64), np.zeros(0, dtype=np.int32), np.zeros(0),
+                      np.array([1.0, -1.0, 1.0]))
+    check_calls(p, loss, 1.0, rng, n_hv=1)
+
+
+def test_solve_partitioned_layout(force_partitions):
+    p = dg.config2()
+    compare_solves(p, p.loss, p.C, p.eps)
+    p = dg.config1()
+    compare_solves(p, p.loss, p.C, p.eps)
+
+
+def test_csr_url_shape_partitioned(rng):
+    # large enough that the automatic choice partitions both orientations
+    p = dg.config3(scale=0.1)
+    assert p.nnz > (1 << 22) and p.n * 8 > (3 << 19)
+    check_calls(p, LOSS_LR, 1.0, rng, w_scale=1.0, n_hv=1)
+
+
 def test_csr_tiny_and_empty(rng):
     # nnz = 0, and a 1 x 1 matrix
     y = np.array([1.0, -1.0, 1.0])
