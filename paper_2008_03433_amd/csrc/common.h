@@ -31,7 +31,9 @@ int hip_fail(hipError_t e, const char *what, const char *file, int line);
 struct Tuning {
     int64_t csr_parts = 0;   // column partitions of the CSR layouts: 0 = automatic, 1 = never, 8 = always
     int64_t csr_hot = 1;     // LDS table of frequent columns for the partitioned forward layout (0 = off)
-    int64_t csr_hot_blocks_per_part = 96;  // persistent workgroups per partition (x 8 partitions)
+    int64_t csr_hot_blocks_per_part = 96;  // persistent workgroups per partition when the LDS table is used
+    int64_t csr_blocks_per_part = 0;       // without the table: 0 = one chunk per workgroup, > 0 = persistent workgroups per partition
+    int64_t csr_ablate = 0;  // timing experiments only (wrong results): 1 = no gathers, 2 = no row reduction
 };
 extern Tuning g_tuning;
 
@@ -78,44 +80,53 @@ struct Profiler {
 // ---------------------------------------------------------------- CSR work partition
 // One orientation of the sparse matrix (rows x cols) laid out for the SpMV kernels.
 //
-// Work is split by nonzeros: a workgroup streams one chunk of kChunk consecutive nonzeros and owns
-// the rows that *start* inside it (rows [row_lo[c], row_lo[c+1])); a row that continues into later
-// chunks receives the remainder through `carry` and the fix-up list.
+// Work is split by nonzeros: a workgroup streams chunks of kChunk consecutive nonzeros and owns the
+// rows that *start* inside a chunk; a row that continues into later chunks receives the remainder
+// through `carry` and the fix-up list.
 //
-// When the vector that is gathered from (length cols) is too large to stay in one L2, the column
-// space is additionally cut into P contiguous ranges with equal nonzero counts, and the nonzeros are
-// stored range-major ("partitioned"): partition x holds, row by row, the entries whose column lies in
-// range x.  Workgroup b works on partition b % P, so -- with workgroups dealt round-robin to the 8
-// XCDs -- each XCD's L2 only ever gathers from its own 1/8 slice of the vector.  Partitions produce
-// partial row sums (P x rows); a combine kernel adds them in a fixed order and applies the epilogue.
+// P == 1 (small matrices): plain CSR, one workgroup per chunk, epilogue applied directly.
+//
+// P == 8 (the gathered vector would not stay resident in one L2): the column space is cut into 8
+// contiguous ranges with equal nonzero counts and the nonzeros are stored range-major: partition x
+// holds, row by row, the entries whose column lies in range x.  Workgroup b works on partition b % 8,
+// so -- with workgroups dealt round-robin to the 8 XCDs -- each XCD's L2 only ever gathers from its own
+// slice of the vector.  Inside a partition only the non-empty rows ("segments") are described: their
+// row ids, and per chunk a 16-bit end offset per segment.  Partitions produce partial row sums
+// (partial[x*rows + r], written only where row r has entries in range x -- see row_mask); a combine
+// kernel adds them in a fixed order and applies the epilogue.
 constexpr int kMaxParts = 8;
 constexpr int kHotSlots = 4096;   // LDS table entries per workgroup (32 KiB)
 
 struct CsrPlan {
     int64_t rows = 0, cols = 0, nnz = 0;
     int P = 1;                           // number of column partitions (1 = unpartitioned)
-    // P == 1: plain CSR
-    int64_t *rowptr = nullptr;           // device, rows+1
-    // P > 1: per-partition row offsets relative to the partition's first nonzero
-    int32_t *rowptr32 = nullptr;         // device, P*(rows+1)
-    int64_t part_base[kMaxParts] = {0};  // position of partition x in col/val (multiple of kChunk)
-    int64_t part_nnz[kMaxParts] = {0};
-    int part_chunk0[kMaxParts] = {0};    // first chunk id of partition x (= part_base / kChunk)
-    int part_nchunks[kMaxParts] = {0};
-    int part_nhot[kMaxParts] = {0};     // LDS-resident columns of partition x
-    int32_t *hot_ids = nullptr;          // device, P*kHotSlots column ids (null: no LDS table); such columns are
-                                         // stored in `col` as ~slot
-    int max_chunks = 0;                  // max over partitions
-    int32_t *col = nullptr;              // device, padded nnz
-    double *val = nullptr;               // device, padded nnz
+    int32_t *col = nullptr;              // device, (padded) nnz; with an LDS table, hot columns are stored as ~slot
+    double *val = nullptr;               // device, (padded) nnz
     int nblocks = 0;                     // total number of chunks
-    int32_t *row_lo = nullptr;           // device; partition x: entries [part_chunk0[x] + x, ... + nchunks + 1)
     double *carry = nullptr;             // device, nblocks: sum of the part of a row entering chunk c from before
     int nfix = 0;                        // number of (partition, split row) pairs
     int32_t *fix_row = nullptr;          // device, nfix: the split row
     int32_t *fix_part = nullptr;         // device, nfix: its partition
     int32_t *fix_b0 = nullptr;           // device, nfix: first chunk id holding a continuation of it
     int32_t *fix_cnt = nullptr;          // device, nfix: number of consecutive chunks that do
+    // ---- P == 1
+    int64_t *rowptr = nullptr;           // device, rows+1
+    int32_t *row_lo = nullptr;           // device, nblocks+1: first row starting at or after chunk c
+    // ---- P > 1
+    int64_t part_base[kMaxParts] = {0};  // position of partition x in col/val (multiple of kChunk)
+    int64_t part_nnz[kMaxParts] = {0};
+    int64_t part_seg0[kMaxParts] = {0};  // first segment of partition x in seg_row
+    int part_chunk0[kMaxParts] = {0};    // first chunk id of partition x (= part_base / kChunk)
+    int part_nchunks[kMaxParts] = {0};
+    int part_nhot[kMaxParts] = {0};      // LDS-resident columns of partition x
+    int max_chunks = 0;                  // max over partitions
+    int32_t *hot_ids = nullptr;          // device, P*kHotSlots column ids (null: no LDS table)
+    int32_t *seg_row = nullptr;          // device: row id of every segment, partition-major, ascending inside a partition
+    int4 *chunk_tab = nullptr;           // device, per chunk: {first owned segment (partition-relative), number of owned
+                                         //   segments, offset where the first owned segment starts, index into seg_end}
+    uint16_t *seg_end = nullptr;         // device: end offsets (chunk-relative, clipped to kChunk) of the owned segments of
+                                         //   each chunk; a chunk's block starts at a multiple of 8 entries
+    uint8_t *row_mask = nullptr;         // device, rows: bit x set iff the row has entries in partition x
     void release();
 };
 

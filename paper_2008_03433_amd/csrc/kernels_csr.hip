@@ -31,8 +31,9 @@ constexpr int kHotMinCount = 8;   // columns with fewer entries are not worth an
 
 void CsrPlan::release()
 {
-    hipFree(rowptr); hipFree(rowptr32); hipFree(col); hipFree(val); hipFree(row_lo); hipFree(carry);
-    hipFree(hot_ids); hipFree(fix_row); hipFree(fix_part); hipFree(fix_b0); hipFree(fix_cnt);
+    hipFree(rowptr); hipFree(col); hipFree(val); hipFree(row_lo); hipFree(carry);
+    hipFree(hot_ids); hipFree(seg_row); hipFree(chunk_tab); hipFree(seg_end); hipFree(row_mask);
+    hipFree(fix_row); hipFree(fix_part); hipFree(fix_b0); hipFree(fix_cnt);
     *this = CsrPlan();
 }
 
@@ -123,43 +124,20 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
             for (int64_t j = bound[x]; j < bound[x + 1]; ++j) part_of[j] = (uint8_t)x;
         for (int x = 0; x < P; ++x) {
             A.part_nnz[x] = colcount[bound[x + 1]] - colcount[bound[x]];
-            if (A.part_nnz[x] > 0x7ffffff0) { set_error("partition too large for 32-bit row offsets"); return TRON_EINVAL; }
+            if (A.part_nnz[x] > 0x7ffffff0) { set_error("partition too large for 32-bit offsets"); return TRON_EINVAL; }
         }
-        std::vector<int32_t> colcnt;
-        if (hot) {
-            colcnt.resize((size_t)cols);
-            for (int64_t j = 0; j < cols; ++j) colcnt[j] = (int32_t)std::min<int64_t>(colcount[j + 1] - colcount[j], 0x7fffffff);
-        }
-        std::vector<int64_t>().swap(colcount);
-        // per-partition row offsets
-        std::vector<int32_t> rp32((size_t)P * (rows + 1), 0);
-        for (int64_t r = 0; r < rows; ++r)
-            for (int64_t k = h_rowptr[r]; k < h_rowptr[r + 1]; ++k) rp32[(size_t)part_of[h_col[k]] * (rows + 1) + r + 1]++;
-        int64_t pos = 0;
-        int chunk = 0;
-        A.max_chunks = 0;
-        for (int x = 0; x < P; ++x) {
-            int32_t *rp = rp32.data() + (size_t)x * (rows + 1);
-            for (int64_t r = 0; r < rows; ++r) rp[r + 1] += rp[r];
-            A.part_base[x] = pos;
-            A.part_chunk0[x] = chunk;
-            A.part_nchunks[x] = (int)std::max<int64_t>(1, (A.part_nnz[x] + kChunk - 1) / kChunk);
-            A.max_chunks = std::max(A.max_chunks, A.part_nchunks[x]);
-            chunk += A.part_nchunks[x];
-            pos += (int64_t)A.part_nchunks[x] * kChunk;
-        }
-        A.nblocks = chunk;
         // LDS-resident columns: in each range the kHotSlots most frequent columns with at least kHotMinCount entries
-        std::vector<int32_t> slot_of;
-        std::vector<int32_t> hot_ids;
+        std::vector<int32_t> slot_of, hot_ids;
         if (hot) {
             slot_of.assign((size_t)cols, -1);
             hot_ids.assign((size_t)P * kHotSlots, 0);
             std::vector<std::pair<int64_t, int32_t>> cand;
             for (int x = 0; x < P; ++x) {
                 cand.clear();
-                for (int64_t j = bound[x]; j < bound[x + 1]; ++j)
-                    if (colcnt[j] >= kHotMinCount) cand.emplace_back(-colcnt[j], (int32_t)j);
+                for (int64_t j = bound[x]; j < bound[x + 1]; ++j) {
+                    const int64_t cnt = colcount[j + 1] - colcount[j];
+                    if (cnt >= kHotMinCount) cand.emplace_back(-cnt, (int32_t)j);
+                }
                 const size_t keep = std::min<size_t>(cand.size(), kHotSlots);
                 std::partial_sort(cand.begin(), cand.begin() + keep, cand.end());
                 A.part_nhot[x] = (int)keep;
@@ -169,29 +147,103 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
                 }
             }
         }
+        std::vector<int64_t>().swap(colcount);
+        // per-(partition,row) entry counts -> offsets; non-empty pairs are the segments
+        std::vector<int32_t> rp32((size_t)P * (rows + 1), 0);
+        for (int64_t r = 0; r < rows; ++r)
+            for (int64_t k = h_rowptr[r]; k < h_rowptr[r + 1]; ++k) rp32[(size_t)part_of[h_col[k]] * (rows + 1) + r + 1]++;
+        std::vector<uint8_t> mask((size_t)rows, 0);
+        int64_t pos = 0, nseg_total = 0;
+        int chunk = 0;
+        A.max_chunks = 0;
+        for (int x = 0; x < P; ++x) {
+            int32_t *rp = rp32.data() + (size_t)x * (rows + 1);
+            int64_t nseg = 0;
+            for (int64_t r = 0; r < rows; ++r) {
+                if (rp[r + 1] > 0) { mask[r] |= (uint8_t)(1u << x); ++nseg; }
+                rp[r + 1] += rp[r];
+            }
+            A.part_base[x] = pos;
+            A.part_seg0[x] = nseg_total;
+            A.part_chunk0[x] = chunk;
+            A.part_nchunks[x] = (int)std::max<int64_t>(1, (A.part_nnz[x] + kChunk - 1) / kChunk);
+            A.max_chunks = std::max(A.max_chunks, A.part_nchunks[x]);
+            chunk += A.part_nchunks[x];
+            pos += (int64_t)A.part_nchunks[x] * kChunk;
+            nseg_total += nseg;
+        }
+        A.nblocks = chunk;
+        if (nseg_total + 8 * (int64_t)chunk > 0x7ffffff0) { set_error("too many row segments for 32-bit indexing"); return TRON_EINVAL; }
         // entries partition-major; inside a row the entries of one range are contiguous and stay ordered
         std::vector<int32_t> pcol((size_t)pos, 0);
         std::vector<double> pval((size_t)pos, 0.0);
-        std::vector<int64_t> cursor(P);
-        for (int64_t r = 0; r < rows; ++r) {
-            for (int x = 0; x < P; ++x) cursor[x] = A.part_base[x] + rp32[(size_t)x * (rows + 1) + r];
-            for (int64_t k = h_rowptr[r]; k < h_rowptr[r + 1]; ++k) {
-                const int64_t q = cursor[part_of[h_col[k]]]++;
-                pcol[q] = (hot && slot_of[h_col[k]] >= 0) ? ~slot_of[h_col[k]] : h_col[k];
-                pval[q] = h_val[k];
+        {
+            std::vector<int64_t> cursor(P);
+            for (int64_t r = 0; r < rows; ++r) {
+                for (int x = 0; x < P; ++x) cursor[x] = A.part_base[x] + rp32[(size_t)x * (rows + 1) + r];
+                for (int64_t k = h_rowptr[r]; k < h_rowptr[r + 1]; ++k) {
+                    const int64_t q = cursor[part_of[h_col[k]]]++;
+                    pcol[q] = (hot && slot_of[h_col[k]] >= 0) ? ~slot_of[h_col[k]] : h_col[k];
+                    pval[q] = h_val[k];
+                }
             }
         }
-        for (int x = 0; x < P; ++x)
-            plan_chunks(rp32.data() + (size_t)x * (rows + 1), rows, A.part_nnz[x], A.part_nchunks[x], A.part_chunk0[x], x,
-                        row_lo, fix_row, fix_part, fix_b0, fix_cnt);
+        // segment tables
+        std::vector<int32_t> seg_row((size_t)std::max<int64_t>(nseg_total, 1));
+        std::vector<int4> tab((size_t)chunk);
+        std::vector<uint16_t> seg_end;
+        seg_end.reserve((size_t)(nseg_total + 8 * (int64_t)chunk));
+        for (int x = 0; x < P; ++x) {
+            const int32_t *rp = rp32.data() + (size_t)x * (rows + 1);
+            const int nch = A.part_nchunks[x];
+            // the segments of this partition, in row order, with start/end positions relative to the partition
+            int64_t m = 0;               // segment counter (partition-relative)
+            int c = 0;                   // chunk that owns the segments being emitted
+            int4 t = make_int4(0, 0, 0, (int)seg_end.size());
+            auto close_chunk = [&](int next_first_seg, int64_t next_seg_start) {
+                tab[A.part_chunk0[x] + c] = t;
+                while (seg_end.size() % 8) seg_end.push_back(0);
+                ++c;
+                const int64_t cstart = (int64_t)c * kChunk;
+                const int64_t off = std::min<int64_t>(std::max<int64_t>(next_seg_start - cstart, 0), kChunk);
+                t = make_int4(next_first_seg, 0, (int)off, (int)seg_end.size());
+            };
+            for (int64_t r = 0; r < rows; ++r) {
+                const int64_t rs = rp[r], re = rp[r + 1];
+                if (re == rs) continue;
+                while (rs >= (int64_t)(c + 1) * kChunk) close_chunk((int)m, rs);   // this segment starts in a later chunk
+                seg_row[A.part_seg0[x] + m] = (int32_t)r;
+                const int64_t cstart = (int64_t)c * kChunk;
+                seg_end.push_back((uint16_t)std::min<int64_t>(re - cstart, kChunk));
+                t.y += 1;
+                // continuation chunks of a split row: fix-up list
+                const int c_last = (int)((re - 1) / kChunk);
+                if (c_last > c) {
+                    fix_row.push_back((int32_t)r);
+                    fix_part.push_back(x);
+                    fix_b0.push_back(A.part_chunk0[x] + c + 1);
+                    fix_cnt.push_back(c_last - c);
+                }
+                ++m;
+            }
+            while (c < nch - 1) close_chunk((int)m, (int64_t)A.part_nnz[x]);
+            tab[A.part_chunk0[x] + c] = t;
+            while (seg_end.size() % 8) seg_end.push_back(0);
+        }
+        // first_off of a chunk inside or at the end of a split row: the chunk-relative end of that row
+        // (set above from the start of the next segment; for chunks wholly inside one row that start lies
+        // beyond the chunk and clips to kChunk, which is right)
         if (hot) TRON_TRY(upload(&A.hot_ids, hot_ids.data(), hot_ids.size(), st));
-        TRON_TRY(upload(&A.rowptr32, rp32.data(), rp32.size(), st));
         TRON_TRY(upload(&A.col, pcol.data(), pcol.size(), st));
         TRON_TRY(upload(&A.val, pval.data(), pval.size(), st));
+        TRON_TRY(upload(&A.seg_row, seg_row.data(), seg_row.size(), st));
+        TRON_TRY(upload(&A.chunk_tab, tab.data(), tab.size(), st));
+        TRON_TRY(upload(&A.seg_end, seg_end.data(), seg_end.size(), st));
+        TRON_TRY(upload(&A.row_mask, mask.data(), mask.size(), st));
         TRON_HIP(hipStreamSynchronize(st));
     }
     A.nfix = (int)fix_row.size();
-    TRON_TRY(upload(&A.row_lo, row_lo.data(), row_lo.size(), st));
+    if (A.P == 1) TRON_TRY(upload(&A.row_lo, row_lo.data(), row_lo.size(), st));
     TRON_TRY(upload(&A.fix_row, fix_row.data(), fix_row.size(), st));
     TRON_TRY(upload(&A.fix_part, fix_part.data(), fix_part.size(), st));
     TRON_TRY(upload(&A.fix_b0, fix_b0.data(), fix_b0.size(), st));
@@ -326,54 +378,271 @@ __global__ __launch_bounds__(kBlock) void k_csr_spmv(int64_t nnz, const int64_t 
 struct PartArgs {
     int64_t base[kMaxParts];
     int64_t nnz[kMaxParts];
+    int64_t seg0[kMaxParts];
     int chunk0[kMaxParts];
     int nchunks[kMaxParts];
     int nhot[kMaxParts];
     int P;
 };
 
-// partitioned: partial[x*rows + r] = sum over the entries of row r in column range x
-__global__ __launch_bounds__(kBlock) void k_csr_spmv_part(PartArgs pa, int64_t rows, const int32_t *__restrict__ rowptr32,
-                                                          const int32_t *__restrict__ col, const double *__restrict__ val,
-                                                          const int32_t *__restrict__ row_lo, const double *__restrict__ x,
-                                                          double *__restrict__ partial, double *__restrict__ carry)
+// Partitioned layout, persistent workgroups: workgroup (partition xp, q) walks chunks q, q + Q, ... of its
+// partition (Q = gridDim / P).  Everything the next chunk needs -- the col/val stream, the chunk's table entry,
+// its segment end offsets and the row ids this thread will write -- is fetched into registers while the current
+// chunk is being reduced, so HBM latency is paid once per workgroup, not once per chunk.
+// With HOT the partition's most frequent columns are first copied from x into an LDS table; entries of those
+// columns are stored as ~slot and never touch the vector cache.
+struct StreamRegs {
+    v4i c[2];
+    v2d v[2][2];
+};
+
+__device__ __forceinline__ StreamRegs load_stream(const int32_t *__restrict__ col, const double *__restrict__ val, int64_t start)
 {
-    __shared__ __align__(16) double prod[kChunk];
-    const int xp = blockIdx.x % pa.P;      // partition; with round-robin dispatch also the XCD
-    const int c = blockIdx.x / pa.P;       // chunk inside the partition
-    if (c >= pa.nchunks[xp]) return;
-    const int64_t start = (int64_t)c * kChunk;
-    const int64_t nnz = pa.nnz[xp];
-    const int64_t end = (start + kChunk < nnz) ? start + kChunk : nnz;
-    const int gc = pa.chunk0[xp] + c;      // global chunk id
-    chunk_body<EPI_PLAIN>(prod, nullptr, start, end, c == 0, rowptr32 + (int64_t)xp * (rows + 1), col + pa.base[xp],
-                          val + pa.base[xp], row_lo + gc + xp, x, partial + (int64_t)xp * rows, nullptr, 0.0, carry + gc);
+    StreamRegs s;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int64_t k = start + j * (kChunk / 2) + threadIdx.x * 4;
+        s.c[j] = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(col + k));
+        s.v[j][0] = __builtin_nontemporal_load(reinterpret_cast<const v2d *>(val + k));
+        s.v[j][1] = __builtin_nontemporal_load(reinterpret_cast<const v2d *>(val + k + 2));
+    }
+    return s;
 }
 
-// partitioned with an LDS table of the partition's most frequent columns: persistent workgroups, each
-// loads the table once and then walks chunks q, q + Q, q + 2Q, ... of its partition (Q = gridDim / P)
-__global__ __launch_bounds__(kBlock) void k_csr_spmv_part_hot(PartArgs pa, int64_t rows, const int32_t *__restrict__ rowptr32,
-                                                              const int32_t *__restrict__ col, const double *__restrict__ val,
-                                                              const int32_t *__restrict__ row_lo, const int32_t *__restrict__ hot_ids,
-                                                              const double *__restrict__ x, double *__restrict__ partial,
-                                                              double *__restrict__ carry)
+// lanes per segment: 256 / (number of segments) rounded down to a power of two, at most 64, at least 1
+__device__ __forceinline__ int lanes_per_segment(int nseg)
+{
+    int g = 1;
+    while (g < kWave && nseg * (g * 2) <= kBlock) g *= 2;
+    return g;
+}
+
+constexpr int kSegPasses = kChunk / kBlock;   // a chunk owns at most kChunk segments: 8 passes of 256
+
+struct SegRegs {
+    uint4 ends;             // 8 x uint16 end offsets: segments 8*tid .. 8*tid+7 of the chunk
+    int rid[kSegPasses];    // row ids of the segments this thread writes: (tid / g) + 256 j
+};
+
+__device__ __forceinline__ SegRegs load_segs(const int4 tab, const uint16_t *__restrict__ seg_end,
+                                             const int32_t *__restrict__ seg_row /* of this partition */)
+{
+    SegRegs s;
+    const int nseg = tab.y;
+    s.ends = make_uint4(0, 0, 0, 0);
+    if (8 * (int)threadIdx.x < nseg) s.ends = *reinterpret_cast<const uint4 *>(seg_end + tab.w + 8 * threadIdx.x);
+    const int g = lanes_per_segment(nseg);
+    const int first = threadIdx.x / g;
+#pragma unroll
+    for (int j = 0; j < kSegPasses; ++j) {
+        const int sidx = first + kBlock * j;
+        s.rid[j] = (sidx < nseg && (g == 1 || j == 0)) ? seg_row[tab.x + sidx] : 0;
+    }
+    return s;
+}
+
+template <bool HOT>
+__global__ __launch_bounds__(kBlock) void k_csr_spmv_part(PartArgs pa, int64_t rows, const int32_t *__restrict__ col_all,
+                                                          const double *__restrict__ val_all, const int4 *__restrict__ chunk_tab,
+                                                          const uint16_t *__restrict__ seg_end, const int32_t *__restrict__ seg_row_all,
+                                                          const int32_t *__restrict__ hot_ids, const double *__restrict__ x,
+                                                          double *__restrict__ partial_all, double *__restrict__ carry_all, int ablate)
 {
     __shared__ __align__(16) double prod[kChunk];
-    __shared__ double table[kHotSlots];
+    __shared__ __align__(16) uint16_t ends[kChunk];
+    __shared__ double table[HOT ? kHotSlots : 1];
+    const int tid = threadIdx.x;
     const int xp = blockIdx.x % pa.P;
     const int q = blockIdx.x / pa.P, Q = gridDim.x / pa.P;
-    const int nhot = pa.nhot[xp];
-    for (int k = threadIdx.x; k < nhot; k += kBlock) table[k] = x[hot_ids[xp * kHotSlots + k]];
-    __syncthreads();
+    const int nchunks = pa.nchunks[xp];
+    if (q >= nchunks) return;
+    if (HOT) {
+        const int nhot = pa.nhot[xp];
+        for (int k = tid; k < nhot; k += kBlock) table[k] = x[hot_ids[xp * kHotSlots + k]];
+        __syncthreads();
+    }
     const int64_t nnz = pa.nnz[xp];
-    for (int c = q; c < pa.nchunks[xp]; c += Q) {
+    const int32_t *col = col_all + pa.base[xp];
+    const double *val = val_all + pa.base[xp];
+    const int4 *tabs = chunk_tab + pa.chunk0[xp];
+    const int32_t *seg_row = seg_row_all + pa.seg0[xp];
+    double *partial = partial_all + (int64_t)xp * rows;
+    double *carry = carry_all + pa.chunk0[xp];
+
+    int c = q;
+    int4 tab = tabs[c];
+    int4 tab_n = (c + Q < nchunks) ? tabs[c + Q] : make_int4(0, 0, 0, 0);
+    StreamRegs cur;
+    bool cur_full = ((int64_t)(c + 1) * kChunk <= nnz);
+    if (cur_full) cur = load_stream(col, val, (int64_t)c * kChunk);
+    SegRegs seg = load_segs(tab, seg_end, seg_row);
+
+    for (; c < nchunks; c += Q) {
         const int64_t start = (int64_t)c * kChunk;
         const int64_t end = (start + kChunk < nnz) ? start + kChunk : nnz;
-        const int gc = pa.chunk0[xp] + c;
-        chunk_body<EPI_PLAIN, int32_t, true>(prod, table, start, end, c == 0, rowptr32 + (int64_t)xp * (rows + 1),
-                                             col + pa.base[xp], val + pa.base[xp], row_lo + gc + xp, x,
-                                             partial + (int64_t)xp * rows, nullptr, 0.0, carry + gc);
-        __syncthreads();  // prod is reused by the next chunk
+        const int cn = c + Q;
+        const int nseg = tab.y, first_off = tab.z;
+        if (8 * tid < nseg) *reinterpret_cast<uint4 *>(ends + 8 * tid) = seg.ends;
+
+        StreamRegs nxt;
+        SegRegs seg_n;
+        int4 tab_nn = make_int4(0, 0, 0, 0);
+        bool nxt_full = false;
+        if (cur_full) {
+            double xg[2][4];
+            if (ablate & 1) {
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    xg[j][0] = (double)cur.c[j].x; xg[j][1] = (double)cur.c[j].y;
+                    xg[j][2] = (double)cur.c[j].z; xg[j][3] = (double)cur.c[j].w;
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    xg[j][0] = gather<HOT>(x, table, cur.c[j].x);
+                    xg[j][1] = gather<HOT>(x, table, cur.c[j].y);
+                    xg[j][2] = gather<HOT>(x, table, cur.c[j].z);
+                    xg[j][3] = gather<HOT>(x, table, cur.c[j].w);
+                }
+            }
+            if (cn < nchunks) {   // prefetch the next chunk (issued after the gathers, waited for one iteration later)
+                nxt_full = ((int64_t)(cn + 1) * kChunk <= nnz);
+                if (nxt_full) nxt = load_stream(col, val, (int64_t)cn * kChunk);
+                seg_n = load_segs(tab_n, seg_end, seg_row);
+                if (cn + Q < nchunks) tab_nn = tabs[cn + Q];
+            }
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                double2 p0, p1;
+                p0.x = cur.v[j][0].x * xg[j][0];
+                p0.y = cur.v[j][0].y * xg[j][1];
+                p1.x = cur.v[j][1].x * xg[j][2];
+                p1.y = cur.v[j][1].y * xg[j][3];
+                double2 *dst = reinterpret_cast<double2 *>(prod + j * (kChunk / 2) + tid * 4);
+                dst[0] = p0;
+                dst[1] = p1;
+            }
+        } else {
+            for (int k = tid; k < kChunk; k += kBlock) {
+                const int64_t kk = start + k;
+                prod[k] = (kk < end) ? val[kk] * gather<HOT>(x, table, col[kk]) : 0.0;
+            }
+            if (cn < nchunks) {
+                nxt_full = ((int64_t)(cn + 1) * kChunk <= nnz);
+                if (nxt_full) nxt = load_stream(col, val, (int64_t)cn * kChunk);
+                seg_n = load_segs(tab_n, seg_end, seg_row);
+                if (cn + Q < nchunks) tab_nn = tabs[cn + Q];
+            }
+        }
+        __syncthreads();
+
+        if (ablate & 2) {   // timing experiment only: skip the segment reduction
+            double sacc = prod[tid] + prod[tid + 256] + prod[tid + 512] + prod[tid + 768];
+            sacc = wave_sum(sacc);
+            if (tid == 0) carry[c] = sacc;
+        } else {
+            // carry: the part of the row entering this chunk from before (wavefront 0)
+            if (c > 0 && tid < kWave && first_off > 0) {
+                double sacc = 0.0;
+                for (int k = tid; k < first_off; k += kWave) sacc += prod[k];
+                sacc = wave_sum(sacc);
+                if (tid == 0) carry[c] = sacc;
+            }
+            // segments that start in this chunk: g lanes each
+            const int g = lanes_per_segment(nseg);
+            const int sub = tid & (g - 1);
+            const int first = tid / g;
+#pragma unroll
+            for (int j = 0; j < kSegPasses; ++j) {
+                if (j * kBlock < nseg && (g == 1 || j == 0)) {   // uniform over the workgroup
+                    const int sidx = first + kBlock * j;
+                    double sacc = 0.0;
+                    if (sidx < nseg) {
+                        const int k0 = (sidx == 0) ? first_off : (int)ends[sidx - 1];
+                        const int k1 = (int)ends[sidx];
+                        for (int k = k0 + sub; k < k1; k += g) sacc += prod[k];
+                    }
+                    sacc = group_sum(sacc, g);
+                    if (sidx < nseg && sub == 0) partial[seg.rid[j]] = sacc;
+                }
+            }
+        }
+        __syncthreads();  // prod / ends are reused by the next chunk
+        cur = nxt;
+        cur_full = nxt_full;
+        seg = seg_n;
+        tab = tab_n;
+        tab_n = tab_nn;
+    }
+}
+
+// One chunk per workgroup (no LDS table): few registers, so eight workgroups fit on a CU and the memory latency of
+// one is hidden by the others.  Loads are issued in two waves: {col/val stream, chunk table entry}, then
+// {gathers, segment end offsets, row ids}.
+__global__ __launch_bounds__(kBlock) void k_csr_spmv_part_np(PartArgs pa, int64_t rows, const int32_t *__restrict__ col_all,
+                                                             const double *__restrict__ val_all, const int4 *__restrict__ chunk_tab,
+                                                             const uint16_t *__restrict__ seg_end, const int32_t *__restrict__ seg_row_all,
+                                                             const double *__restrict__ x, double *__restrict__ partial_all,
+                                                             double *__restrict__ carry_all)
+{
+    __shared__ __align__(16) double prod[kChunk];
+    __shared__ __align__(16) uint16_t ends[kChunk];
+    const int tid = threadIdx.x;
+    const int xp = blockIdx.x % pa.P;
+    const int c = blockIdx.x / pa.P;
+    if (c >= pa.nchunks[xp]) return;
+    const int32_t *col = col_all + pa.base[xp];
+    const double *val = val_all + pa.base[xp];
+    const int32_t *seg_row = seg_row_all + pa.seg0[xp];
+    double *partial = partial_all + (int64_t)xp * rows;
+
+    const StreamRegs cur = load_stream(col, val, (int64_t)c * kChunk);   // col/val are padded to whole chunks
+    const int4 tab = chunk_tab[pa.chunk0[xp] + c];
+    const int nseg = tab.y, first_off = tab.z;
+    double xg[2][4];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        xg[j][0] = x[cur.c[j].x];
+        xg[j][1] = x[cur.c[j].y];
+        xg[j][2] = x[cur.c[j].z];
+        xg[j][3] = x[cur.c[j].w];
+    }
+    const SegRegs seg = load_segs(tab, seg_end, seg_row);
+    if (8 * tid < nseg) *reinterpret_cast<uint4 *>(ends + 8 * tid) = seg.ends;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        double2 p0, p1;
+        p0.x = cur.v[j][0].x * xg[j][0];
+        p0.y = cur.v[j][0].y * xg[j][1];
+        p1.x = cur.v[j][1].x * xg[j][2];
+        p1.y = cur.v[j][1].y * xg[j][3];
+        double2 *dst = reinterpret_cast<double2 *>(prod + j * (kChunk / 2) + tid * 4);
+        dst[0] = p0;
+        dst[1] = p1;
+    }
+    __syncthreads();
+    if (c > 0 && tid < kWave && first_off > 0) {
+        double sacc = 0.0;
+        for (int k = tid; k < first_off; k += kWave) sacc += prod[k];
+        sacc = wave_sum(sacc);
+        if (tid == 0) carry_all[pa.chunk0[xp] + c] = sacc;
+    }
+    const int g = lanes_per_segment(nseg);
+    const int sub = tid & (g - 1);
+    const int first = tid / g;
+#pragma unroll
+    for (int j = 0; j < kSegPasses; ++j) {
+        if (j * kBlock < nseg && (g == 1 || j == 0)) {
+            const int sidx = first + kBlock * j;
+            double sacc = 0.0;
+            if (sidx < nseg) {
+                const int k0 = (sidx == 0) ? first_off : (int)ends[sidx - 1];
+                const int k1 = (int)ends[sidx];
+                for (int k = k0 + sub; k < k1; k += g) sacc += prod[k];
+            }
+            sacc = group_sum(sacc, g);
+            if (sidx < nseg && sub == 0) partial[seg.rid[j]] = sacc;
+        }
     }
 }
 
@@ -403,33 +672,27 @@ __global__ __launch_bounds__(kBlock) void k_csr_fixup(int nfix, int64_t rows, co
 }
 
 // ------------------------------------------------------------------ combine kernels (partitioned layout)
-template <int P>
-__device__ __forceinline__ double sum_parts(const double *__restrict__ partial, int64_t rows, int64_t r)
+// sum over the partitions in which row r has entries (bit x of mask), in partition order
+__device__ __forceinline__ double sum_parts(const double *__restrict__ partial, const uint8_t *__restrict__ mask, int64_t rows, int64_t r)
 {
-    double s = partial[r];
+    const unsigned m = mask[r];
+    double s = 0.0;
 #pragma unroll
-    for (int x = 1; x < P; ++x) s += partial[(int64_t)x * rows + r];
-    return s;
-}
-
-__device__ __forceinline__ double sum_parts_rt(const double *__restrict__ partial, int64_t rows, int64_t r, int P)
-{
-    if (P == 8) return sum_parts<8>(partial, rows, r);
-    double s = partial[r];
-    for (int x = 1; x < P; ++x) s += partial[(int64_t)x * rows + r];
+    for (int x = 0; x < kMaxParts; ++x)
+        if (m & (1u << x)) s += partial[(int64_t)x * rows + r];
     return s;
 }
 
 // z = sum of partials; loss terms; partial slot 0 = sum loss
 template <int LOSS>
-__global__ __launch_bounds__(kBlock) void k_combine_loss(int64_t n, int P, const double *__restrict__ partial,
+__global__ __launch_bounds__(kBlock) void k_combine_loss(int64_t n, const double *__restrict__ partial, const uint8_t *__restrict__ mask,
                                                          const double *__restrict__ y, double *__restrict__ zhat,
                                                          double *__restrict__ D, double *__restrict__ red)
 {
     __shared__ double lds[kWavesPerBlock];
     double acc = 0.0;
     for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (int64_t)gridDim.x * kBlock) {
-        const double z = sum_parts_rt(partial, n, i, P);
+        const double z = sum_parts(partial, mask, n, i);
         double a, zh, Di;
         loss_terms_dev<LOSS>(z, y[i], a, zh, Di);
         zhat[i] = zh;
@@ -441,16 +704,16 @@ __global__ __launch_bounds__(kBlock) void k_combine_loss(int64_t n, int P, const
 }
 
 // out = scale .* sum of partials
-__global__ __launch_bounds__(kBlock) void k_combine_scale(int64_t rows, int P, const double *__restrict__ partial,
+__global__ __launch_bounds__(kBlock) void k_combine_scale(int64_t rows, const double *__restrict__ partial, const uint8_t *__restrict__ mask,
                                                           const double *__restrict__ scale, double *__restrict__ out)
 {
     for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < rows; i += (int64_t)gridDim.x * kBlock)
-        out[i] = scale[i] * sum_parts_rt(partial, rows, i, P);
+        out[i] = scale[i] * sum_parts(partial, mask, rows, i);
 }
 
 // out = add + alpha * sum of partials; partial slot 0 = out . (SELF ? out : add)
 template <bool SELF>
-__global__ __launch_bounds__(kBlock) void k_combine_axpy(int64_t rows, int P, const double *__restrict__ partial,
+__global__ __launch_bounds__(kBlock) void k_combine_axpy(int64_t rows, const double *__restrict__ partial, const uint8_t *__restrict__ mask,
                                                          const double *__restrict__ add, double alpha,
                                                          double *__restrict__ out, double *__restrict__ red)
 {
@@ -458,7 +721,7 @@ __global__ __launch_bounds__(kBlock) void k_combine_axpy(int64_t rows, int P, co
     double acc = 0.0;
     for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < rows; i += (int64_t)gridDim.x * kBlock) {
         const double a = add[i];
-        const double o = fma(alpha, sum_parts_rt(partial, rows, i, P), a);
+        const double o = fma(alpha, sum_parts(partial, mask, rows, i), a);
         out[i] = o;
         acc += o * (SELF ? o : a);
     }
@@ -504,20 +767,25 @@ static int launch_partials(tron_dataset *ds, const CsrPlan &A, int slot, const d
     for (int i = 0; i < A.P; ++i) {
         pa.base[i] = A.part_base[i];
         pa.nnz[i] = A.part_nnz[i];
+        pa.seg0[i] = A.part_seg0[i];
         pa.chunk0[i] = A.part_chunk0[i];
         pa.nchunks[i] = A.part_nchunks[i];
         pa.nhot[i] = A.part_nhot[i];
     }
     {
         ProfScope ps(ds, slot);
-        if (A.hot_ids) {
-            int per_part = std::min(A.max_chunks, (int)g_tuning.csr_hot_blocks_per_part);
-            hipLaunchKernelGGL(k_csr_spmv_part_hot, dim3(per_part * A.P), dim3(kBlock), 0, ds->stream, pa, A.rows, A.rowptr32,
-                               A.col, A.val, A.row_lo, A.hot_ids, x, ds->row_partials, A.carry);
-        } else {
-            hipLaunchKernelGGL(k_csr_spmv_part, dim3(A.max_chunks * A.P), dim3(kBlock), 0, ds->stream, pa, A.rows, A.rowptr32,
-                               A.col, A.val, A.row_lo, x, ds->row_partials, A.carry);
-        }
+        const int want = (int)(A.hot_ids ? g_tuning.csr_hot_blocks_per_part : g_tuning.csr_blocks_per_part);
+        const int per_part = std::max(1, std::min(A.max_chunks, want));
+        if (A.hot_ids)
+            hipLaunchKernelGGL(k_csr_spmv_part<true>, dim3(per_part * A.P), dim3(kBlock), 0, ds->stream, pa, A.rows, A.col, A.val,
+                               A.chunk_tab, A.seg_end, A.seg_row, A.hot_ids, x, ds->row_partials, A.carry, (int)g_tuning.csr_ablate);
+        else if (g_tuning.csr_blocks_per_part > 0)
+            hipLaunchKernelGGL(k_csr_spmv_part<false>, dim3(per_part * A.P), dim3(kBlock), 0, ds->stream, pa, A.rows, A.col, A.val,
+                               A.chunk_tab, A.seg_end, A.seg_row, (const int32_t *)nullptr, x, ds->row_partials, A.carry,
+                               (int)g_tuning.csr_ablate);
+        else
+            hipLaunchKernelGGL(k_csr_spmv_part_np, dim3(A.max_chunks * A.P), dim3(kBlock), 0, ds->stream, pa, A.rows, A.col, A.val,
+                               A.chunk_tab, A.seg_end, A.seg_row, x, ds->row_partials, A.carry);
         TRON_HIP(hipGetLastError());
     }
     if (A.nfix > 0) {
@@ -540,9 +808,9 @@ int spmv_loss(tron_dataset *ds, const CsrPlan &A, int slot, int loss, const doub
     ProfScope ps(ds, SLOT_SPMV_COMBINE);
     const int g = vec_grid(A.rows);
     if (loss == TRON_LOSS_LR)
-        hipLaunchKernelGGL(k_combine_loss<TRON_LOSS_LR>, dim3(g), dim3(kBlock), 0, ds->stream, A.rows, A.P, ds->row_partials, ds->y, zhat, D, ds->partials);
+        hipLaunchKernelGGL(k_combine_loss<TRON_LOSS_LR>, dim3(g), dim3(kBlock), 0, ds->stream, A.rows, ds->row_partials, A.row_mask, ds->y, zhat, D, ds->partials);
     else
-        hipLaunchKernelGGL(k_combine_loss<TRON_LOSS_L2SVM>, dim3(g), dim3(kBlock), 0, ds->stream, A.rows, A.P, ds->row_partials, ds->y, zhat, D, ds->partials);
+        hipLaunchKernelGGL(k_combine_loss<TRON_LOSS_L2SVM>, dim3(g), dim3(kBlock), 0, ds->stream, A.rows, ds->row_partials, A.row_mask, ds->y, zhat, D, ds->partials);
     TRON_HIP(hipGetLastError());
     return g;
 }
@@ -552,7 +820,7 @@ int spmv_scale(tron_dataset *ds, const CsrPlan &A, int slot, const double *x, co
     if (A.P == 1) return launch_plain<EPI_SCALE>(ds, A, slot, x, out, scale, 0.0);
     TRON_TRY(launch_partials(ds, A, slot, x));
     ProfScope ps(ds, SLOT_SPMV_COMBINE);
-    hipLaunchKernelGGL(k_combine_scale, dim3(vec_grid(A.rows)), dim3(kBlock), 0, ds->stream, A.rows, A.P, ds->row_partials, scale, out);
+    hipLaunchKernelGGL(k_combine_scale, dim3(vec_grid(A.rows)), dim3(kBlock), 0, ds->stream, A.rows, ds->row_partials, A.row_mask, scale, out);
     TRON_HIP(hipGetLastError());
     return TRON_OK;
 }
@@ -568,9 +836,9 @@ int spmv_axpy(tron_dataset *ds, const CsrPlan &A, int slot, const double *x, con
     ProfScope ps(ds, SLOT_SPMV_COMBINE);
     const int g = vec_grid(A.rows);
     if (dot_self)
-        hipLaunchKernelGGL(k_combine_axpy<true>, dim3(g), dim3(kBlock), 0, ds->stream, A.rows, A.P, ds->row_partials, add, alpha, out, ds->partials);
+        hipLaunchKernelGGL(k_combine_axpy<true>, dim3(g), dim3(kBlock), 0, ds->stream, A.rows, ds->row_partials, A.row_mask, add, alpha, out, ds->partials);
     else
-        hipLaunchKernelGGL(k_combine_axpy<false>, dim3(g), dim3(kBlock), 0, ds->stream, A.rows, A.P, ds->row_partials, add, alpha, out, ds->partials);
+        hipLaunchKernelGGL(k_combine_axpy<false>, dim3(g), dim3(kBlock), 0, ds->stream, A.rows, ds->row_partials, A.row_mask, add, alpha, out, ds->partials);
     TRON_HIP(hipGetLastError());
     return g;
 }
