@@ -32,7 +32,7 @@ int hip_fail(hipError_t e, const char *what, const char *file, int line)
 
 // ------------------------------------------------------------------ profiler
 const char *const kSlotNames[SLOT_COUNT] = {
-    "spmv_fwd_z", "spmv_fwd_a1", "spmv_bwd_g", "spmv_bwd_hv", "spmv_fixup", "spmv_combine", "loss_terms",
+    "spmv_fwd_z", "spmv_fwd_a1", "spmv_bwd_g", "spmv_bwd_hv", "spmv_fixup", "spmv_combine", "spmv_tiles", "loss_terms",
     "dense_fun_grad", "dense_hv", "dense_finalize", "dot", "reduce_final", "cg_vec"};
 
 int Profiler::begin(int slot, hipStream_t st)
@@ -403,6 +403,14 @@ int tron_tuning_set(const char *name, int64_t value)
     }
     if (name && strcmp(name, "csr_hot_blocks_per_part") == 0 && value >= 1 && value <= 4096) {
         g_tuning.csr_hot_blocks_per_part = value;
+        return TRON_OK;
+    }
+    if (name && strcmp(name, "csr_tiles") == 0 && (value == 0 || value == 1)) {
+        g_tuning.csr_tiles = value;
+        return TRON_OK;
+    }
+    if (name && strcmp(name, "csr_tile_blocks_per_slice") == 0 && value >= 1 && value <= 1024) {
+        g_tuning.csr_tile_blocks_per_slice = value;
         return TRON_OK;
     }
     if (name && strcmp(name, "csr_ablate") == 0 && value >= 0 && value <= 3) {

@@ -33,6 +33,8 @@ struct Tuning {
     int64_t csr_hot = 1;     // LDS table of frequent columns for the partitioned forward layout (0 = off)
     int64_t csr_hot_blocks_per_part = 96;  // persistent workgroups per partition when the LDS table is used
     int64_t csr_blocks_per_part = 0;       // without the table: 0 = one chunk per workgroup, > 0 = persistent workgroups per partition
+    int64_t csr_tiles = 1;   // hot-row tiles for the transposed orientation of partitioned matrices (0 = off)
+    int64_t csr_tile_blocks_per_slice = 128;  // persistent workgroups per slice of hot rows
     int64_t csr_ablate = 0;  // timing experiments only (wrong results): 1 = no gathers, 2 = no row reduction
 };
 extern Tuning g_tuning;
@@ -53,6 +55,7 @@ enum Slot {
     SLOT_SPMV_BWD_HV,      // Hv = v + C X^T a1
     SLOT_SPMV_FIXUP,       // rows split across workgroups
     SLOT_SPMV_COMBINE,     // sum of the column partitions' partial row sums + epilogue
+    SLOT_SPMV_TILES,       // hot-row tiles of the transposed product
     SLOT_LOSS_TERMS,       // zhat, D, sum loss from z
     SLOT_DENSE_FUN_GRAD,   // fused dense z / loss / D / X^T zhat
     SLOT_DENSE_HV,         // fused dense X^T (D (X v))
@@ -97,8 +100,36 @@ struct Profiler {
 constexpr int kMaxParts = 8;
 constexpr int kHotSlots = 4096;   // LDS table entries per workgroup (32 KiB)
 
+// Hot-row tiles of the transposed product  out[j] += sum_i val * x[i]  (j = row of the plan, i = column).
+// The rows with the most entries (up to kTileSlices * kTileSlots of them) are taken out of the CSR layout and
+// stored as tiles: a tile holds the entries of one slice of those rows for a short range of consecutive
+// columns, sorted by (row slot, column).  The gather x[i] then stays inside a few cache lines per tile (vector
+// L1 hits instead of one L2 request per entry), and the per-row sums of a tile are added to LDS accumulators
+// that a persistent workgroup keeps for its slice; workgroup accumulators are summed in a fixed order.
+constexpr int kTileSlices = 8;      // slices of hot rows, one per XCD
+constexpr int kTileSlots = 2048;    // hot rows per slice = LDS accumulators per workgroup (16 KiB)
+constexpr int kTileMinCount = 32;   // rows with fewer entries stay in the CSR layout
+
+struct HotTiles {
+    int nhot = 0;                        // hot rows; row with rank r (by entry count) is slot r / 8 of slice r % 8
+    int64_t ntiles_total = 0;
+    int64_t tile0[kTileSlices] = {0};    // first tile of slice s
+    int64_t ntiles[kTileSlices] = {0};
+    int blocks_per_slice = 0;            // persistent workgroups per slice
+    double *val = nullptr;               // device, ntiles_total * kChunk (zero padded)
+    uint16_t *iloc = nullptr;            // device, ntiles_total * kChunk: column minus the tile's first column
+    int4 *hdr = nullptr;                 // device, per tile: {first column, segments, long segments, index into seg_*}
+    uint16_t *seg_slot = nullptr;        // device: slot of each segment (ascending inside a tile)
+    uint16_t *seg_end = nullptr;         // device: end offset of each segment inside its tile
+    int32_t *slot_of_row = nullptr;      // device, rows: slice * kTileSlots + slot, or -1
+    double *wg_acc = nullptr;            // device, kTileSlices * blocks_per_slice * kTileSlots workgroup accumulators
+    double *sums = nullptr;              // device, kTileSlices * kTileSlots: per hot row, sum over its tiles
+    void release();
+};
+
 struct CsrPlan {
     int64_t rows = 0, cols = 0, nnz = 0;
+    HotTiles hot;                        // optional (transposed orientation of large matrices)
     int P = 1;                           // number of column partitions (1 = unpartitioned)
     int32_t *col = nullptr;              // device, (padded) nnz; with an LDS table, hot columns are stored as ~slot
     double *val = nullptr;               // device, (padded) nnz
@@ -196,6 +227,10 @@ int probe_copy(double *dst, const double *src, int64_t count, int reps, hipStrea
 // parts: 1 = plain CSR, 0 = choose from the size of the gathered vector
 int csr_plan_build(CsrPlan &P, int64_t rows, int64_t cols, const int64_t *h_rowptr, const int32_t *h_col,
                    const double *h_val, int parts, bool hot, hipStream_t st);
+// Hot-row tiles for plan A (rows x cols) from the *other* orientation's CSR (cols x rows: t_rowptr over A's columns,
+// t_col = A's row ids).  slot_code[row] = slice * kTileSlots + slot for hot rows, -1 otherwise.
+int hot_tiles_build(CsrPlan &A, const int64_t *t_rowptr, const int32_t *t_col, const double *t_val,
+                    const std::vector<int32_t> &slot_code, int nhot, hipStream_t st);
 // Products with one orientation; all enqueue on ds->stream.
 //   spmv_loss:  z = A x, then per-instance loss terms: zhat, D; partial slot 0 of ds->partials = sum loss
 //   spmv_scale: out = scale .* (A x)
