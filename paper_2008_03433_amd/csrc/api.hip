@@ -115,6 +115,9 @@ static int alloc_common(tron_dataset *ds)
     TRON_HIP(hipMalloc(reinterpret_cast<void **>(&ds->partials), sizeof(double) * need));
     TRON_HIP(hipMalloc(reinterpret_cast<void **>(&ds->scal_dev), sizeof(double) * kScalars));
     TRON_HIP(hipHostMalloc(reinterpret_cast<void **>(&ds->scal_host), sizeof(double) * kScalars, hipHostMallocDefault));
+    TRON_HIP(hipStreamCreateWithFlags(&ds->side, hipStreamNonBlocking));
+    TRON_HIP(hipEventCreateWithFlags(&ds->ev_fork, hipEventDisableTiming));
+    TRON_HIP(hipEventCreateWithFlags(&ds->ev_join, hipEventDisableTiming));
     ds->vec_grid_n = vec_grid_for(ds->n);
     ds->vec_grid_d = vec_grid_for(ds->d);
     return TRON_OK;
@@ -168,6 +171,9 @@ void tron_dataset_destroy(tron_dataset *ds)
     hipFree(ds->partials); hipFree(ds->row_partials); hipFree(ds->scal_dev);
     if (ds->scal_host) hipHostFree(ds->scal_host);
     for (double *p : ds->sv) hipFree(p);
+    if (ds->side) { hipStreamSynchronize(ds->side); hipStreamDestroy(ds->side); }
+    if (ds->ev_fork) hipEventDestroy(ds->ev_fork);
+    if (ds->ev_join) hipEventDestroy(ds->ev_join);
     ds->prof.destroy();
     delete ds;
 }
@@ -213,18 +219,41 @@ int tron_dataset_create_csr(int64_t n, int64_t d, const int64_t *rowptr, const i
             t_rowptr[c + 1] += 1;
         }
     }
+    // Hot-row tiles for the transposed product of large matrices: the features with the most entries (rank r by
+    // count -> slice r % 8, slot r / 8) leave the transposed CSR copy and are stored as tiles instead.
+    std::vector<int32_t> slot_code;
+    int nhot = 0;
+    const bool partitioned = g_tuning.csr_parts == kMaxParts ||
+                             (g_tuning.csr_parts == 0 && n * (int64_t)sizeof(double) > (3 << 19) && nnz >= (1 << 22));
+    if (g_tuning.csr_tiles && partitioned) {
+        std::vector<std::pair<int64_t, int32_t>> cand;
+        for (int64_t j = 0; j < d; ++j)
+            if (t_rowptr[j + 1] >= kTileMinCount) cand.emplace_back(-t_rowptr[j + 1], (int32_t)j);
+        const size_t keep = std::min<size_t>(cand.size(), (size_t)kTileSlices * kTileSlots);
+        std::partial_sort(cand.begin(), cand.begin() + keep, cand.end());
+        if (keep > 0) {
+            slot_code.assign((size_t)d, -1);
+            for (size_t r = 0; r < keep; ++r) {
+                slot_code[cand[r].second] = (int32_t)((r % kTileSlices) * kTileSlots + r / kTileSlices);
+                t_rowptr[cand[r].second + 1] = 0;   // no entries of this feature in the CSR copy
+            }
+            nhot = (int)keep;
+        }
+    }
     // explicit transposed copy (d x n): counting sort by column keeps rows ascending inside each column
     for (int64_t j = 0; j < d; ++j) t_rowptr[j + 1] += t_rowptr[j];
+    const int64_t t_nnz = t_rowptr[d];
     std::vector<int32_t> t_col;
     std::vector<double> t_val;
     std::vector<int64_t> cursor;
     try {
-        t_col.resize((size_t)nnz);
-        t_val.resize((size_t)nnz);
+        t_col.resize((size_t)t_nnz);
+        t_val.resize((size_t)t_nnz);
         cursor.assign(t_rowptr.begin(), t_rowptr.end() - 1);
     } catch (const std::bad_alloc &) { set_error("out of host memory building the transposed copy"); return TRON_ENOMEM; }
     for (int64_t i = 0; i < n; ++i)
         for (int64_t k = h_rowptr[i]; k < h_rowptr[i + 1]; ++k) {
+            if (nhot && slot_code[h_col[k]] >= 0) continue;
             const int64_t pos = cursor[h_col[k]]++;
             t_col[pos] = (int32_t)i;
             t_val[pos] = h_val[k];
@@ -235,7 +264,8 @@ int tron_dataset_create_csr(int64_t n, int64_t d, const int64_t *rowptr, const i
     ds->n = n; ds->d = d; ds->dense = false; ds->stream = reinterpret_cast<hipStream_t>(hip_stream);
     int rc = alloc_common(ds);
     if (rc >= 0) rc = csr_plan_build(ds->fwd, n, d, h_rowptr.data(), h_col.data(), h_val.data(), (int)g_tuning.csr_parts, g_tuning.csr_hot != 0, ds->stream);
-    if (rc >= 0) rc = csr_plan_build(ds->bwd, d, n, t_rowptr.data(), t_col.data(), t_val.data(), (int)g_tuning.csr_parts, false, ds->stream);
+    if (rc >= 0) rc = csr_plan_build(ds->bwd, d, n, t_rowptr.data(), t_col.data(), t_val.data(), partitioned ? kMaxParts : 1, false, ds->stream);
+    if (rc >= 0 && nhot) rc = hot_tiles_build(ds->bwd, h_rowptr.data(), h_col.data(), h_val.data(), slot_code, nhot, ds->stream);
     if (rc >= 0) {
         int64_t need = 0;
         if (ds->fwd.P > 1) need = std::max<int64_t>(need, (int64_t)ds->fwd.P * n);
@@ -407,6 +437,10 @@ int tron_tuning_set(const char *name, int64_t value)
     }
     if (name && strcmp(name, "csr_tiles") == 0 && (value == 0 || value == 1)) {
         g_tuning.csr_tiles = value;
+        return TRON_OK;
+    }
+    if (name && strcmp(name, "csr_two_streams") == 0 && (value == 0 || value == 1)) {
+        g_tuning.csr_two_streams = value;
         return TRON_OK;
     }
     if (name && strcmp(name, "csr_tile_blocks_per_slice") == 0 && value >= 1 && value <= 1024) {

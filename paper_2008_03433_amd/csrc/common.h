@@ -34,6 +34,8 @@ struct Tuning {
     int64_t csr_hot_blocks_per_part = 96;  // persistent workgroups per partition when the LDS table is used
     int64_t csr_blocks_per_part = 0;       // without the table: 0 = one chunk per workgroup, > 0 = persistent workgroups per partition
     int64_t csr_tiles = 1;   // hot-row tiles for the transposed orientation of partitioned matrices (0 = off)
+    int64_t csr_two_streams = 0;  // 1 = run the hot-row tiles beside the CSR remainder on a second stream (measured slower: both
+                                  // kernels compete for the same per-CU miss queue)
     int64_t csr_tile_blocks_per_slice = 128;  // persistent workgroups per slice of hot rows
     int64_t csr_ablate = 0;  // timing experiments only (wrong results): 1 = no gathers, 2 = no row reduction
 };
@@ -168,6 +170,8 @@ struct tron_dataset {
     int64_t n = 0, d = 0;
     bool dense = false;
     hipStream_t stream = nullptr;
+    hipStream_t side = nullptr;      // library-owned second stream: independent kernels of one call run beside `stream`
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     int device = 0;
 
     // dense
@@ -202,8 +206,10 @@ namespace tron {
 // RAII bracket used by the launch helpers
 struct ProfScope {
     tron_dataset *ds; int idx;
-    ProfScope(tron_dataset *d, int slot) : ds(d), idx(d->prof.on ? d->prof.begin(slot, d->stream) : -1) {}
-    ~ProfScope() { if (idx >= 0) ds->prof.end(idx, ds->stream); }
+    hipStream_t st;
+    ProfScope(tron_dataset *d, int slot, hipStream_t s = nullptr)
+        : ds(d), idx(d->prof.on ? d->prof.begin(slot, s ? s : d->stream) : -1), st(s ? s : d->stream) {}
+    ~ProfScope() { if (idx >= 0) ds->prof.end(idx, st); }
 };
 
 // ---- kernels_vec.hip

@@ -29,8 +29,16 @@ constexpr int64_t kGatherBytesForPartitioning = 3 << 19;  // 1.5 MiB: larger gat
 constexpr int64_t kMinNnzForPartitioning = 1 << 22;
 constexpr int kHotMinCount = 8;   // columns with fewer entries are not worth an LDS slot
 
+void HotTiles::release()
+{
+    hipFree(val); hipFree(iloc); hipFree(hdr); hipFree(seg_slot); hipFree(seg_end); hipFree(slot_of_row);
+    hipFree(wg_acc); hipFree(sums);
+    *this = HotTiles();
+}
+
 void CsrPlan::release()
 {
+    hot.release();
     hipFree(rowptr); hipFree(col); hipFree(val); hipFree(row_lo); hipFree(carry);
     hipFree(hot_ids); hipFree(seg_row); hipFree(chunk_tab); hipFree(seg_end); hipFree(row_mask);
     hipFree(fix_row); hipFree(fix_part); hipFree(fix_b0); hipFree(fix_cnt);
@@ -646,6 +654,245 @@ __global__ __launch_bounds__(kBlock) void k_csr_spmv_part_np(PartArgs pa, int64_
     }
 }
 
+// ------------------------------------------------------------------ hot-row tiles (see HotTiles)
+constexpr int kLongSegment = 32;   // segments at least this long are summed by a whole wavefront
+
+int hot_tiles_build(CsrPlan &A, const int64_t *t_rowptr, const int32_t *t_col, const double *t_val,
+                    const std::vector<int32_t> &slot_code, int nhot, hipStream_t st)
+{
+    HotTiles &H = A.hot;
+    H.nhot = nhot;
+    struct Entry { uint16_t slot, iloc; double val; };
+    std::vector<Entry> cur[kTileSlices];
+    int64_t base[kTileSlices] = {0};
+    std::vector<double> tval[kTileSlices];
+    std::vector<uint16_t> tiloc[kTileSlices], sslot[kTileSlices], send[kTileSlices];
+    std::vector<int4> hdrs[kTileSlices];
+    std::vector<int> seglen(kTileSlots);
+    std::vector<Entry> sorted;
+
+    auto close_tile = [&](int s) {
+        std::vector<Entry> &e = cur[s];
+        if (e.empty()) return;
+        // long segments first, then by slot; entries of a slot keep their column order
+        for (const Entry &x : e) seglen[x.slot]++;
+        sorted = e;
+        std::stable_sort(sorted.begin(), sorted.end(), [&](const Entry &a, const Entry &b) {
+            const bool la = seglen[a.slot] >= kLongSegment, lb = seglen[b.slot] >= kLongSegment;
+            if (la != lb) return la;
+            return a.slot < b.slot;
+        });
+        int4 h = make_int4((int)base[s], 0, 0, (int)sslot[s].size());
+        const size_t off = tval[s].size();
+        tval[s].resize(off + kChunk, 0.0);
+        tiloc[s].resize(off + kChunk, 0);
+        for (size_t k = 0; k < sorted.size(); ++k) {
+            tval[s][off + k] = sorted[k].val;
+            tiloc[s][off + k] = sorted[k].iloc;
+            if (k + 1 == sorted.size() || sorted[k + 1].slot != sorted[k].slot) {
+                sslot[s].push_back(sorted[k].slot);
+                send[s].push_back((uint16_t)(k + 1));
+                h.y += 1;
+                if (seglen[sorted[k].slot] >= kLongSegment) h.z += 1;
+            }
+        }
+        while (sslot[s].size() % 8) { sslot[s].push_back(0); send[s].push_back(0); }
+        hdrs[s].push_back(h);
+        for (const Entry &x : e) seglen[x.slot] = 0;
+        e.clear();
+    };
+
+    int cnt[kTileSlices];
+    for (int64_t i = 0; i < A.cols; ++i) {
+        for (int s = 0; s < kTileSlices; ++s) cnt[s] = 0;
+        for (int64_t k = t_rowptr[i]; k < t_rowptr[i + 1]; ++k) {
+            const int32_t code = slot_code[t_col[k]];
+            if (code >= 0) cnt[code / kTileSlots]++;
+        }
+        for (int s = 0; s < kTileSlices; ++s) {
+            if (!cnt[s]) continue;
+            if ((int)cur[s].size() + cnt[s] > kChunk || (!cur[s].empty() && i - base[s] > 65535)) close_tile(s);
+            if (cur[s].empty()) base[s] = i;
+        }
+        for (int64_t k = t_rowptr[i]; k < t_rowptr[i + 1]; ++k) {
+            const int32_t code = slot_code[t_col[k]];
+            if (code >= 0) cur[code / kTileSlots].push_back({(uint16_t)(code % kTileSlots), (uint16_t)(i - base[code / kTileSlots]), t_val[k]});
+        }
+    }
+    for (int s = 0; s < kTileSlices; ++s) close_tile(s);
+
+    // concatenate the slices; segment offsets become global
+    int64_t ntiles = 0, nseg = 0;
+    for (int s = 0; s < kTileSlices; ++s) {
+        H.tile0[s] = ntiles;
+        H.ntiles[s] = (int64_t)hdrs[s].size();
+        for (int4 &h : hdrs[s]) h.w += (int)nseg;
+        ntiles += H.ntiles[s];
+        nseg += (int64_t)sslot[s].size();
+    }
+    H.ntiles_total = ntiles;
+    if (ntiles == 0) return TRON_OK;
+    if (nseg > 0x7ffffff0 || ntiles > 0x7ffffff0 / kChunk * 1024) { set_error("hot tiles too large"); return TRON_EINVAL; }
+    TRON_HIP(hipMalloc(reinterpret_cast<void **>(&H.val), sizeof(double) * ntiles * kChunk));
+    TRON_HIP(hipMalloc(reinterpret_cast<void **>(&H.iloc), sizeof(uint16_t) * ntiles * kChunk));
+    TRON_HIP(hipMalloc(reinterpret_cast<void **>(&H.hdr), sizeof(int4) * ntiles));
+    TRON_HIP(hipMalloc(reinterpret_cast<void **>(&H.seg_slot), sizeof(uint16_t) * std::max<int64_t>(nseg, 8)));
+    TRON_HIP(hipMalloc(reinterpret_cast<void **>(&H.seg_end), sizeof(uint16_t) * std::max<int64_t>(nseg, 8)));
+    int64_t segpos = 0;
+    for (int s = 0; s < kTileSlices; ++s) {
+        const int64_t t0 = H.tile0[s];
+        if (H.ntiles[s] == 0) continue;
+        TRON_HIP(hipMemcpyAsync(H.val + t0 * kChunk, tval[s].data(), sizeof(double) * tval[s].size(), hipMemcpyHostToDevice, st));
+        TRON_HIP(hipMemcpyAsync(H.iloc + t0 * kChunk, tiloc[s].data(), sizeof(uint16_t) * tiloc[s].size(), hipMemcpyHostToDevice, st));
+        TRON_HIP(hipMemcpyAsync(H.hdr + t0, hdrs[s].data(), sizeof(int4) * hdrs[s].size(), hipMemcpyHostToDevice, st));
+        TRON_HIP(hipMemcpyAsync(H.seg_slot + segpos, sslot[s].data(), sizeof(uint16_t) * sslot[s].size(), hipMemcpyHostToDevice, st));
+        TRON_HIP(hipMemcpyAsync(H.seg_end + segpos, send[s].data(), sizeof(uint16_t) * send[s].size(), hipMemcpyHostToDevice, st));
+        segpos += (int64_t)sslot[s].size();
+    }
+    TRON_TRY(upload(&H.slot_of_row, slot_code.data(), slot_code.size(), st));
+    int64_t maxt = 0;
+    for (int s = 0; s < kTileSlices; ++s) maxt = std::max(maxt, H.ntiles[s]);
+    H.blocks_per_slice = (int)std::max<int64_t>(1, std::min<int64_t>(maxt, g_tuning.csr_tile_blocks_per_slice));
+    TRON_HIP(hipMalloc(reinterpret_cast<void **>(&H.wg_acc), sizeof(double) * kTileSlices * H.blocks_per_slice * kTileSlots));
+    TRON_HIP(hipMalloc(reinterpret_cast<void **>(&H.sums), sizeof(double) * kTileSlices * kTileSlots));
+    TRON_HIP(hipStreamSynchronize(st));
+    return TRON_OK;
+}
+
+struct TileArgs {
+    int64_t tile0[kTileSlices];
+    int64_t ntiles[kTileSlices];
+};
+
+struct TileRegs {
+    v2d v[4];
+    uint32_t il[4];     // two 16-bit local column offsets each
+    uint4 ends, slots;  // descriptors 8*tid .. 8*tid+7
+    int4 hdr;
+};
+
+__device__ __forceinline__ TileRegs load_tile(const double *__restrict__ val, const uint16_t *__restrict__ iloc,
+                                              const int4 *__restrict__ hdr, const uint16_t *__restrict__ seg_end,
+                                              const uint16_t *__restrict__ seg_slot, int64_t T)
+{
+    TileRegs r;
+    r.hdr = hdr[T];
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+        const int64_t k = T * kChunk + m * (kChunk / 4) + threadIdx.x * 2;
+        r.v[m] = __builtin_nontemporal_load(reinterpret_cast<const v2d *>(val + k));
+        r.il[m] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(iloc + k));
+    }
+    // descriptor blocks are padded to a multiple of 8 and at least one block exists per tile
+    const int64_t dpos = (int64_t)r.hdr.w + 8 * (int64_t)((8 * (int)threadIdx.x < r.hdr.y) ? threadIdx.x : 0);
+    r.ends = *reinterpret_cast<const uint4 *>(seg_end + dpos);
+    r.slots = *reinterpret_cast<const uint4 *>(seg_slot + dpos);
+    return r;
+}
+
+// Persistent workgroup (slice s, q): tiles q, q + B, ... of the slice; LDS accumulators for the slice's hot rows.
+__global__ __launch_bounds__(kBlock) void k_hot_tiles(TileArgs ta, int B, const double *__restrict__ val,
+                                                      const uint16_t *__restrict__ iloc, const int4 *__restrict__ hdr,
+                                                      const uint16_t *__restrict__ seg_end, const uint16_t *__restrict__ seg_slot,
+                                                      const double *__restrict__ x, double *__restrict__ wg_acc)
+{
+    __shared__ __align__(16) double prod[kChunk];
+    __shared__ __align__(16) uint16_t ends[kChunk];
+    __shared__ __align__(16) uint16_t slots[kChunk];
+    __shared__ double acc[kTileSlots];
+    const int tid = threadIdx.x;
+    const int s = blockIdx.x % kTileSlices;
+    const int q = blockIdx.x / kTileSlices;
+    for (int k = tid; k < kTileSlots; k += kBlock) acc[k] = 0.0;
+    const int64_t nt = ta.ntiles[s];
+    if (q < nt) {
+        const int64_t T0 = ta.tile0[s];
+        TileRegs cur = load_tile(val, iloc, hdr, seg_end, seg_slot, T0 + q);
+        for (int64_t t = q; t < nt; t += B) {
+            const int nseg = cur.hdr.y, nlong = cur.hdr.z;
+            const int64_t cbase = cur.hdr.x;
+            // gathers: a few consecutive cache lines of x per tile
+            double xg[4][2];
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                xg[m][0] = x[cbase + (cur.il[m] & 0xffffu)];
+                xg[m][1] = x[cbase + (cur.il[m] >> 16)];
+            }
+            if (8 * tid < nseg) {
+                *reinterpret_cast<uint4 *>(ends + 8 * tid) = cur.ends;
+                *reinterpret_cast<uint4 *>(slots + 8 * tid) = cur.slots;
+            }
+            // next tile into registers (clamped index: the loads are unconditional, straight-line code)
+            const int64_t tn = (t + B < nt) ? t + B : nt - 1;
+            const TileRegs nxt = load_tile(val, iloc, hdr, seg_end, seg_slot, T0 + tn);
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                double2 p;
+                p.x = cur.v[m].x * xg[m][0];
+                p.y = cur.v[m].y * xg[m][1];
+                *reinterpret_cast<double2 *>(prod + m * (kChunk / 4) + tid * 2) = p;
+            }
+            __syncthreads();
+            // long segments: one wavefront each
+            const int lane = tid & (kWave - 1);
+            for (int sg = tid / kWave; sg < nlong; sg += kWavesPerBlock) {
+                const int k0 = sg ? (int)ends[sg - 1] : 0, k1 = (int)ends[sg];
+                double sacc = 0.0;
+                for (int k = k0 + lane; k < k1; k += kWave) sacc += prod[k];
+                sacc = wave_sum(sacc);
+                if (lane == 0) acc[slots[sg]] += sacc;
+            }
+            // short segments: one thread each (slots inside a tile are distinct, so the updates do not collide)
+            for (int sg = nlong + tid; sg < nseg; sg += kBlock) {
+                const int k0 = sg ? (int)ends[sg - 1] : 0, k1 = (int)ends[sg];
+                double sacc = 0.0;
+                for (int k = k0; k < k1; ++k) sacc += prod[k];
+                acc[slots[sg]] += sacc;
+            }
+            __syncthreads();
+            cur = nxt;
+        }
+    }
+    __syncthreads();
+    double *out = wg_acc + ((int64_t)s * B + q) * kTileSlots;
+    for (int k = tid; k < kTileSlots; k += kBlock) out[k] = acc[k];
+}
+
+// sums[s*K + k] = sum over the B workgroups of slice s, in workgroup order
+__global__ __launch_bounds__(kBlock) void k_hot_reduce(int B, const double *__restrict__ wg_acc, double *__restrict__ sums)
+{
+    const int idx = blockIdx.x * kBlock + threadIdx.x;   // s*K + k
+    if (idx >= kTileSlices * kTileSlots) return;
+    const int s = idx / kTileSlots, k = idx % kTileSlots;
+    const double *p = wg_acc + (int64_t)s * B * kTileSlots + k;
+    double a = 0.0;
+    for (int q = 0; q < B; ++q) a += p[(int64_t)q * kTileSlots];
+    sums[idx] = a;
+}
+
+static int launch_hot_tiles(tron_dataset *ds, const CsrPlan &A, const double *x)
+{
+    const HotTiles &H = A.hot;
+    TileArgs ta;
+    for (int s = 0; s < kTileSlices; ++s) { ta.tile0[s] = H.tile0[s]; ta.ntiles[s] = H.ntiles[s]; }
+    // The tiles stream from HBM, the CSR remainder waits on gather misses: they run side by side on two streams.
+    hipStream_t st = g_tuning.csr_two_streams ? ds->side : ds->stream;
+    if (st != ds->stream) {
+        TRON_HIP(hipEventRecord(ds->ev_fork, ds->stream));
+        TRON_HIP(hipStreamWaitEvent(st, ds->ev_fork, 0));
+    }
+    {
+        ProfScope ps(ds, SLOT_SPMV_TILES, st);
+        hipLaunchKernelGGL(k_hot_tiles, dim3(kTileSlices * H.blocks_per_slice), dim3(kBlock), 0, st, ta, H.blocks_per_slice,
+                           H.val, H.iloc, H.hdr, H.seg_end, H.seg_slot, x, H.wg_acc);
+        hipLaunchKernelGGL(k_hot_reduce, dim3(kTileSlices * kTileSlots / kBlock), dim3(kBlock), 0, st, H.blocks_per_slice,
+                           H.wg_acc, H.sums);
+        TRON_HIP(hipGetLastError());
+    }
+    if (st != ds->stream) TRON_HIP(hipEventRecord(ds->ev_join, st));
+    return TRON_OK;
+}
+
 // ------------------------------------------------------------------ fix-up of split rows
 // One wavefront per split row: y[row] += factor * (carry[b0] + ... + carry[b0+cnt-1]).
 template <int EPI>
@@ -673,10 +920,20 @@ __global__ __launch_bounds__(kBlock) void k_csr_fixup(int nfix, int64_t rows, co
 
 // ------------------------------------------------------------------ combine kernels (partitioned layout)
 // sum over the partitions in which row r has entries (bit x of mask), in partition order
-__device__ __forceinline__ double sum_parts(const double *__restrict__ partial, const uint8_t *__restrict__ mask, int64_t rows, int64_t r)
+struct HotRef {
+    const int32_t *slot_of_row;   // null: no hot rows
+    const double *sums;
+};
+
+__device__ __forceinline__ double sum_parts(const double *__restrict__ partial, const uint8_t *__restrict__ mask, int64_t rows, int64_t r,
+                                            HotRef hot = HotRef{nullptr, nullptr})
 {
     const unsigned m = mask[r];
     double s = 0.0;
+    if (hot.slot_of_row) {
+        const int hs = hot.slot_of_row[r];
+        if (hs >= 0) s = hot.sums[hs];
+    }
 #pragma unroll
     for (int x = 0; x < kMaxParts; ++x)
         if (m & (1u << x)) s += partial[(int64_t)x * rows + r];
@@ -715,13 +972,13 @@ __global__ __launch_bounds__(kBlock) void k_combine_scale(int64_t rows, const do
 template <bool SELF>
 __global__ __launch_bounds__(kBlock) void k_combine_axpy(int64_t rows, const double *__restrict__ partial, const uint8_t *__restrict__ mask,
                                                          const double *__restrict__ add, double alpha,
-                                                         double *__restrict__ out, double *__restrict__ red)
+                                                         double *__restrict__ out, double *__restrict__ red, HotRef hot)
 {
     __shared__ double lds[kWavesPerBlock];
     double acc = 0.0;
     for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < rows; i += (int64_t)gridDim.x * kBlock) {
         const double a = add[i];
-        const double o = fma(alpha, sum_parts(partial, mask, rows, i), a);
+        const double o = fma(alpha, sum_parts(partial, mask, rows, i, hot), a);
         out[i] = o;
         acc += o * (SELF ? o : a);
     }
@@ -832,13 +1089,20 @@ int spmv_axpy(tron_dataset *ds, const CsrPlan &A, int slot, const double *x, con
         TRON_TRY(launch_plain<EPI_AXPY>(ds, A, slot, x, out, add, alpha));
         return dot_partials(ds, A.rows, out, dot_self ? out : add, nullptr, nullptr, nullptr, nullptr);
     }
+    HotRef hot{nullptr, nullptr};
+    if (A.hot.ntiles_total > 0) {
+        TRON_TRY(launch_hot_tiles(ds, A, x));
+        hot.slot_of_row = A.hot.slot_of_row;
+        hot.sums = A.hot.sums;
+    }
     TRON_TRY(launch_partials(ds, A, slot, x));
+    if (hot.sums && g_tuning.csr_two_streams) TRON_HIP(hipStreamWaitEvent(ds->stream, ds->ev_join, 0));
     ProfScope ps(ds, SLOT_SPMV_COMBINE);
     const int g = vec_grid(A.rows);
     if (dot_self)
-        hipLaunchKernelGGL(k_combine_axpy<true>, dim3(g), dim3(kBlock), 0, ds->stream, A.rows, ds->row_partials, A.row_mask, add, alpha, out, ds->partials);
+        hipLaunchKernelGGL(k_combine_axpy<true>, dim3(g), dim3(kBlock), 0, ds->stream, A.rows, ds->row_partials, A.row_mask, add, alpha, out, ds->partials, hot);
     else
-        hipLaunchKernelGGL(k_combine_axpy<false>, dim3(g), dim3(kBlock), 0, ds->stream, A.rows, ds->row_partials, A.row_mask, add, alpha, out, ds->partials);
+        hipLaunchKernelGGL(k_combine_axpy<false>, dim3(g), dim3(kBlock), 0, ds->stream, A.rows, ds->row_partials, A.row_mask, add, alpha, out, ds->partials, hot);
     TRON_HIP(hipGetLastError());
     return g;
 }
