@@ -8,7 +8,11 @@ Hessian-vector products completed per second of solve wall-clock (all stages inc
 stand-alone tron_hv and tron_fun_grad rates, the solve seconds and the HBM roofline of the dominant
 kernel are reported next to it.  One JSON line is printed on stdout; progress goes to stderr.
 
-    python bench.py [--workload c3|c5|c4|c2|c1] [--steps K] [--warmup W] [--gpus 1]
+    python bench.py [--workload c3|c5|c4|c2|c1] [--also c5|none] [--steps K] [--warmup W] [--gpus 1]
+
+The primary workload (default c3, the large sparse config) fills the top-level fields; the workload
+named by --also (default c5, the large dense config) is measured the same way and reported under
+"also".
 """
 from __future__ import annotations
 
@@ -24,13 +28,22 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 
+# library profiler slot -> (kernel name in rocprofv3 output, profiles/ file that holds its byte counters)
+ROCPROF_NAMES = {
+    "dense_hv": ("k_dense_hv<6, 4, 4, true, true>", "dense_hv_fun_grad_c5.md"),
+    "dense_fun_grad": ("k_dense_fun_grad<6, 4, 4, true, 1>", "dense_hv_fun_grad_c5.md"),
+    "spmv_fwd_a1": ("k_csr_spmv_part<true>", "csr_spmv_c3.md"),
+    "spmv_bwd_hv": ("k_csr_spmv_part_np", "csr_spmv_c3.md"),
+    "spmv_tiles": ("k_hot_tiles", "csr_spmv_c3.md"),
+}
+
 
 def log(msg: str) -> None:
     print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
 
 
 def make_workload(name: str, scale: float):
-    """Returns (problem-or-stream, description).  Data are generated on the host, seeded."""
+    """Seeded synthetic workload, generated on the host."""
     import datagen as dg
     if name == "c1":
         return dg.config1()
@@ -53,26 +66,28 @@ def upload(tron, workload):
         t0 = time.time()
         for row0, X, y in workload.chunks():
             tron.tron_dataset_write_rows(ds.handle, row0, X.shape[0], X, y)
-            if (row0 // workload.chunk_rows) % 20 == 0:
+            if (row0 // workload.chunk_rows) % 40 == 0:
                 log(f"  uploaded rows {row0 + X.shape[0]:,} / {workload.n:,} ({time.time() - t0:.0f} s)")
         return ds
     return tron.Dataset.from_problem(workload)
 
 
-def algorithmic_bytes(ds, kernel: str) -> float:
-    """Bytes the method has to move per launch of the named kernel (fp64 values, int32 columns, int64 row
-    pointers): one SpMV pass = 12 nnz + 24 rows + 8 cols; the fused dense pass = 8 n d + 8 n."""
+def algorithmic_bytes(ds, stat, kernel: str) -> float:
+    """Bytes the method has to move per launch of the named kernel: 12 B per nonzero (int32 column + fp64 value),
+    8 B per row pointer / vector element touched; the fused dense pass reads X once."""
     n, d, nnz = ds.n, ds.d, ds.nnz
-    if kernel in ("dense_hv",):
+    if kernel == "dense_hv":
         return 8.0 * n * d + 8.0 * n                       # X once + D
     if kernel == "dense_fun_grad":
         return 8.0 * n * d + 16.0 * n                      # X once + y read + D written
-    if kernel in ("spmv_fwd_a1",):
-        return 12.0 * nnz + 24.0 * n + 8.0 * d             # col+val, rowptr + D + a1 written, v gathered
-    if kernel in ("spmv_bwd_hv", "spmv_bwd_g"):
-        return 12.0 * nnz + 24.0 * d + 8.0 * n             # col+val, rowptr + v/w + out written, a1/zhat gathered
+    if kernel == "spmv_fwd_a1":
+        return 12.0 * nnz + 24.0 * n + 8.0 * d             # col+val; rowptr, D, a1 written; v gathered
     if kernel == "spmv_fwd_z":
         return 12.0 * nnz + 16.0 * n + 8.0 * d
+    if kernel in ("spmv_bwd_hv", "spmv_bwd_g"):            # the CSR part of the transposed pass
+        return 12.0 * stat("bwd_csr_nnz") + 24.0 * d + 8.0 * n
+    if kernel == "spmv_tiles":                             # the tiled part of the transposed pass
+        return 12.0 * stat("bwd_tile_nnz")
     raise KeyError(kernel)
 
 
@@ -82,7 +97,28 @@ def hv_call_bytes(ds) -> float:
     return 24.0 * ds.nnz + 32.0 * ds.n + 32.0 * ds.d
 
 
-def cpu_baseline(workload, loss, C, budget_s: float = 20.0):
+def measured_traffic(slot: str):
+    """HBM-side bytes per launch from the committed rocprofv3 counter summaries (FETCH_SIZE + WRITE_SIZE, scaled)."""
+    if slot not in ROCPROF_NAMES:
+        return None
+    kname, fname = ROCPROF_NAMES[slot]
+    path = os.path.join(ROOT, "profiles", fname)
+    if not os.path.exists(path):
+        return None
+    in_traffic = False
+    for line in open(path):
+        if line.startswith("## "):
+            in_traffic = "traffic" in line
+        if in_traffic and line.startswith(f"| `{kname}` |"):
+            cells = [c.strip() for c in line.strip().strip("|").split("|")]
+            try:
+                return (float(cells[2]) + float(cells[4])) * 1e9
+            except (ValueError, IndexError):
+                return None
+    return None
+
+
+def cpu_baseline(workload, loss, C, budget_s: float = 15.0):
     """The CPU oracle timed on this host, one thread, on a bounded sample of the same workload."""
     import numpy as np
     import datagen as dg
@@ -94,10 +130,6 @@ def cpu_baseline(workload, loss, C, budget_s: float = 20.0):
         o = Oracle(n=rows, d=workload.d, y=y, X=X)
         scale = rows / workload.n
         sample = f"first {rows:,} of {workload.n:,} rows; rate scaled by {scale:.5f}"
-    elif getattr(workload, "X", None) is not None:
-        o = Oracle.from_problem(workload)
-        scale = 1.0
-        sample = "full matrix"
     else:
         o = Oracle.from_problem(workload)
         scale = 1.0
@@ -122,45 +154,24 @@ def cpu_baseline(workload, loss, C, budget_s: float = 20.0):
     }
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
-    ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
-    ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only; reported)")
-    ap.add_argument("--hv-reps", type=int, default=20)
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--tune", action="append", default=[], metavar="KNOB=VALUE", help="library tuning knob (see tron_tuning_set)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1",
-              file=sys.stderr)
-        return 2
-
-    import numpy as np
+def run_workload(args, wname: str) -> dict:
     import torch
     import datagen as dg
     import paper_2008_03433_amd as tron
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible; the library has no CPU fallback", file=sys.stderr)
-        return 3
-    torch.cuda.set_device(0)
-    tron.load_library()
-    for kv in args.tune:
-        k, v_ = kv.split("=")
-        tron.tron_tuning_set(k, int(v_))
-
     t0 = time.time()
-    log(f"generating workload {args.workload} (scale {args.scale:g}) with {dg.num_threads()} host threads")
-    workload = make_workload(args.workload, args.scale)
-    loss, C, eps = (dg.LOSS_L2SVM, 0.1, 0.01) if args.workload in ("c4", "c5") else (dg.LOSS_LR, 1.0, 0.01)
-    log(f"generated in {time.time() - t0:.1f} s; uploading")
+    log(f"generating workload {wname} (scale {args.scale:g}) with {dg.num_threads()} host threads")
+    workload = make_workload(wname, args.scale)
+    loss, C, eps = (dg.LOSS_L2SVM, 0.1, 0.01) if wname in ("c4", "c5") else (dg.LOSS_LR, 1.0, 0.01)
+    log(f"generated in {time.time() - t0:.1f} s; building the device dataset")
     t0 = time.time()
     ds = upload(tron, workload)
-    log(f"dataset resident: n={ds.n:,} d={ds.d:,} nnz={ds.nnz:,} dense={ds.dense} ({time.time() - t0:.1f} s)")
+    setup_s = time.time() - t0
+    log(f"dataset resident: n={ds.n:,} d={ds.d:,} nnz={ds.nnz:,} dense={ds.dense} ({setup_s:.1f} s)")
     name = workload.name if hasattr(workload, "name") else f"c5_dense_svm_{ds.n}"
+
+    def stat(key):
+        return tron.tron_dataset_stat(ds.handle, key)
 
     w = torch.zeros(ds.d, dtype=torch.float64, device="cuda")
 
@@ -182,7 +193,8 @@ def main() -> int:
     solve_s = elapsed / args.steps
     log(f"solve: {solve_s * 1e3:.2f} ms, outer={res.outer_iters} cg={res.cg_iters_total} f={res.f:.10g} converged={res.converged}")
 
-    # ---- stand-alone call rates (HIP events on the handle's stream via the library's profiler)
+    # ---- stand-alone call rates: wall-clock without instrumentation, then per-kernel times with HIP events
+    #      recorded on the handle's stream by the library's profiler
     g = torch.empty_like(w)
     v = torch.randn(ds.d, dtype=torch.float64, device="cuda")
     Hv = torch.empty_like(v)
@@ -191,48 +203,46 @@ def main() -> int:
     for _ in range(3):
         ds.hv(C, v, Hv, want_vHv=False)
     torch.cuda.synchronize()
-    tron.tron_profile_enable(ds.handle, True)
     t0 = time.perf_counter()
     for _ in range(args.hv_reps):
         ds.hv(C, v, Hv, want_vHv=False)
     torch.cuda.synchronize()
     hv_s = (time.perf_counter() - t0) / args.hv_reps
-    prof_hv = tron.tron_profile_read(ds.handle)
     fg_reps = max(3, args.hv_reps // 4)
     t0 = time.perf_counter()
     for _ in range(fg_reps):
         ds.fun_grad(loss, C, w, g)
     torch.cuda.synchronize()
     fg_s = (time.perf_counter() - t0) / fg_reps
+    tron.tron_profile_enable(ds.handle, True)
+    for _ in range(args.hv_reps):
+        ds.hv(C, v, Hv, want_vHv=False)
+    prof_hv = tron.tron_profile_read(ds.handle)
+    for _ in range(fg_reps):
+        ds.fun_grad(loss, C, w, g)
     prof_fg = tron.tron_profile_read(ds.handle)
     tron.tron_profile_enable(ds.handle, False)
 
-    kernels = {k: {"ms": v_["ms"] / v_["calls"], "calls": v_["calls"]} for k, v_ in prof_hv.items()}
-    kernels_fg = {k: {"ms": v_["ms"] / v_["calls"], "calls": v_["calls"]} for k, v_ in prof_fg.items()}
-    dominant = max((k for k in kernels if k in ("dense_hv", "spmv_fwd_a1", "spmv_bwd_hv")), key=lambda k: kernels[k]["ms"])
+    kernels = {k: {"ms": r["ms"] / r["calls"], "calls_per_hv": r["calls"] / args.hv_reps} for k, r in prof_hv.items()}
+    kernels_fg = {k: {"ms": r["ms"] / r["calls"], "calls_per_fun_grad": r["calls"] / fg_reps} for k, r in prof_fg.items()}
+    big = [k for k in kernels if k in ("dense_hv", "spmv_fwd_a1", "spmv_bwd_hv", "spmv_tiles")]
+    dominant = max(big, key=lambda k: kernels[k]["ms"])
     dom_ms = kernels[dominant]["ms"]
-    achieved = algorithmic_bytes(ds, dominant) / (dom_ms * 1e-3) / 1e9
+    dom_bytes = algorithmic_bytes(ds, stat, dominant)
+    achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                "ms_per_launch": dom_ms, "algorithmic_bytes_per_launch": algorithmic_bytes(ds, dominant)}
-    per_kernel = {}
-    for k, rec in {**kernels, **kernels_fg}.items():
-        try:
-            gbs = algorithmic_bytes(ds, k) / (rec["ms"] * 1e-3) / 1e9
-            per_kernel[k] = {"ms": rec["ms"], "GB/s": gbs, "frac": gbs / HBM_PEAK_GBS}
-        except KeyError:
-            per_kernel[k] = {"ms": rec["ms"]}
-
-    # attainable streaming rates on this device, for context (and the known-size kernels the hardware
-    # byte counters are scaled with): a 2 GiB read-only sum and a 1 GiB -> 1 GiB copy
-    probe_n = 1 << 28
-    probe_src = torch.empty(probe_n, dtype=torch.float64, device="cuda").normal_()
-    ms_probe, _ = tron.tron_probe_read_bandwidth(probe_src, probe_n, reps=10)
-    half = probe_n // 2
-    ms_copy = tron.tron_probe_copy_bandwidth(probe_src[half:], probe_src[:half], half, reps=10)
-    probe = {"read_GB/s": probe_n * 8 / (ms_probe * 1e-3) / 1e9, "read_bytes": probe_n * 8,
-             "copy_GB/s": 2 * half * 8 / (ms_copy * 1e-3) / 1e9, "copy_bytes_read": half * 8, "copy_bytes_written": half * 8}
-    del probe_src
+                "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(dominant),
+                "ms_per_launch": dom_ms, "algorithmic_bytes_per_launch": dom_bytes}
+    def with_rates(table):
+        outk = {}
+        for k, rec in table.items():
+            outk[k] = dict(rec)
+            try:
+                gbs = algorithmic_bytes(ds, stat, k) / (rec["ms"] * 1e-3) / 1e9
+                outk[k].update({"GB/s": gbs, "frac": gbs / HBM_PEAK_GBS})
+            except KeyError:
+                pass
+        return outk
 
     out = {
         "metric": "Hessian-vector products/sec (sustained over full TRON solves) + % HBM peak; end-to-end TRON solve seconds",
@@ -240,23 +250,82 @@ def main() -> int:
         "ms_per_step": solve_s * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f64", "data": "synthetic",
         "config": {"workload": name, "n": ds.n, "d": ds.d, "nnz": ds.nnz, "layout": "dense" if ds.dense else "csr+csr^T",
-                   "loss": "l2svm" if loss == dg.LOSS_L2SVM else "lr", "C": C, "eps": eps, "scale": args.scale, "tune": args.tune},
+                   "loss": "l2svm" if loss == dg.LOSS_L2SVM else "lr", "C": C, "eps": eps, "scale": args.scale,
+                   "tune": args.tune, "setup_seconds": setup_s},
         "solve": {"seconds": solve_s, "outer_iters": res.outer_iters, "cg_iters": res.cg_iters_total, "n_fun": res.n_fun,
                   "n_grad": res.n_grad, "n_hv": res.n_hv, "f": res.f, "gnorm": res.gnorm, "gnorm0": res.gnorm0,
                   "converged": res.converged},
         "hv_call": {"per_s": 1.0 / hv_s, "ms": hv_s * 1e3, "GB/s": hv_call_bytes(ds) / hv_s / 1e9,
-                    "frac_hbm_peak": hv_call_bytes(ds) / hv_s / 1e9 / HBM_PEAK_GBS},
+                    "frac_hbm_peak": hv_call_bytes(ds) / hv_s / 1e9 / HBM_PEAK_GBS, "algorithmic_bytes": hv_call_bytes(ds)},
         "fun_grad_call": {"per_s": 1.0 / fg_s, "ms": fg_s * 1e3},
-        "kernels": per_kernel,
+        "kernels_hv": with_rates(kernels),
+        "kernels_fun_grad": with_rates(kernels_fg),
         "roofline": roofline,
-        "stream_probe": probe,
     }
+    if not ds.dense:
+        out["layout"] = {k: stat(k) for k in ("fwd_parts", "bwd_parts", "fwd_csr_nnz", "fwd_lds_columns", "bwd_csr_nnz",
+                                             "bwd_tile_nnz", "bwd_tile_rows", "bwd_tiles")}
     if not args.no_cpu_baseline:
         log("timing the CPU oracle (one thread, bounded sample)")
         out["cpu_baseline"] = cpu_baseline(workload, loss, C)
     else:
         out["cpu_baseline"] = None
     ds.close()
+    del ds, w, g, v, Hv
+    torch.cuda.empty_cache()
+    return out
+
+
+def stream_probe() -> dict:
+    """Attainable streaming rates on this device (also the known-size kernels the byte counters are scaled with)."""
+    import torch
+    import paper_2008_03433_amd as tron
+    probe_n = 1 << 28
+    src = torch.empty(probe_n, dtype=torch.float64, device="cuda").normal_()
+    ms_read, _ = tron.tron_probe_read_bandwidth(src, probe_n, reps=10)
+    half = probe_n // 2
+    ms_copy = tron.tron_probe_copy_bandwidth(src[half:], src[:half], half, reps=10)
+    return {"read_GB/s": probe_n * 8 / (ms_read * 1e-3) / 1e9, "read_bytes": probe_n * 8,
+            "copy_GB/s": 2 * half * 8 / (ms_copy * 1e-3) / 1e9, "copy_bytes_read": half * 8, "copy_bytes_written": half * 8}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--also", default=None, choices=["c1", "c2", "c3", "c4", "c5", "none"],
+                    help="second workload reported under 'also' (default: c5 when the primary is c3)")
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only; reported)")
+    ap.add_argument("--hv-reps", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tune", action="append", default=[], metavar="KNOB=VALUE", help="library tuning knob (see tron_tuning_set)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2008_03433_amd as tron
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the library has no CPU fallback", file=sys.stderr)
+        return 3
+    torch.cuda.set_device(0)
+    tron.load_library()
+    for kv in args.tune:
+        k, v_ = kv.split("=")
+        tron.tron_tuning_set(k, int(v_))
+
+    out = run_workload(args, args.workload)
+    out["stream_probe"] = stream_probe()
+    also = args.also if args.also is not None else ("c5" if args.workload == "c3" and args.scale == 1.0 else "none")
+    if also != "none" and also != args.workload:
+        sub = run_workload(args, also)
+        keep = ("value", "unit", "ms_per_step", "config", "solve", "hv_call", "fun_grad_call", "kernels_hv", "kernels_fun_grad", "roofline", "cpu_baseline")
+        out["also"] = {also: {k: sub[k] for k in keep}}
     print(json.dumps(out), flush=True)
     return 0
 

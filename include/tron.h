@@ -93,6 +93,17 @@ TRON_API void tron_dataset_destroy(tron_dataset *ds);
 /* Shape query: any output pointer may be NULL.  nnz = n*d for dense handles. */
 TRON_API int tron_dataset_shape(const tron_dataset *ds, int64_t *n, int64_t *d, int64_t *nnz, int *is_dense);
 
+/*
+ * Layout statistics of a handle (what the library built from the input), by name:
+ *   "fwd_parts", "bwd_parts"   column partitions of the forward / transposed CSR layouts (0 for dense)
+ *   "fwd_csr_nnz", "bwd_csr_nnz"  nonzeros held in those CSR layouts
+ *   "bwd_tile_nnz", "bwd_tile_rows", "bwd_tiles"  nonzeros, features and tiles of the hot-row tiles
+ *   "fwd_lds_columns"          columns served from LDS tables in the forward pass
+ *   "dense_grid"               workgroups of the dense kernels
+ * Unknown names return TRON_EINVAL.
+ */
+TRON_API int tron_dataset_stat(const tron_dataset *ds, const char *name, int64_t *value);
+
 /* ------------------------------------------------------------------------------------------
  * The three callbacks of Table 1.
  * ------------------------------------------------------------------------------------------ */

@@ -47,6 +47,7 @@ _SIGNATURES = {
     "tron_dataset_write_rows": (_int, [_vp, _i64, _i64, _vp, _vp, _int]),
     "tron_dataset_destroy": (None, [_vp]),
     "tron_dataset_shape": (_int, [_vp, ctypes.POINTER(_i64), ctypes.POINTER(_i64), ctypes.POINTER(_i64), ctypes.POINTER(_int)]),
+    "tron_dataset_stat": (_int, [_vp, ctypes.c_char_p, ctypes.POINTER(_i64)]),
     "tron_fun_grad": (_int, [_vp, _int, _dbl, _vp, ctypes.POINTER(_dbl), _vp]),
     "tron_hv": (_int, [_vp, _dbl, _vp, _vp, ctypes.POINTER(_dbl)]),
     "tron_solve": (_int, [_vp, ctypes.POINTER(_Params), _vp, ctypes.POINTER(_Result)]),
@@ -153,6 +154,12 @@ def tron_dataset_shape(ds) -> Tuple[int, int, int, bool]:
     n, d, nnz, dense = _i64(), _i64(), _i64(), _int()
     _check(load_library().tron_dataset_shape(ds, ctypes.byref(n), ctypes.byref(d), ctypes.byref(nnz), ctypes.byref(dense)))
     return n.value, d.value, nnz.value, bool(dense.value)
+
+
+def tron_dataset_stat(ds, name: str) -> int:
+    v = _i64()
+    _check(load_library().tron_dataset_stat(ds, name.encode(), ctypes.byref(v)))
+    return v.value
 
 
 def tron_fun_grad(ds, loss, C, w, g=None) -> float:

@@ -98,7 +98,8 @@ static int alloc_common(tron_dataset *ds)
 {
     const int64_t n = ds->n;
     TRON_HIP(hipGetDevice(&ds->device));
-    TRON_HIP(hipMalloc(reinterpret_cast<void **>(&ds->y), sizeof(double) * n));
+    if (ds->dense) TRON_HIP(hipMalloc(reinterpret_cast<void **>(&ds->y8), (size_t)n));
+    else TRON_HIP(hipMalloc(reinterpret_cast<void **>(&ds->y), sizeof(double) * n));
     TRON_HIP(hipMalloc(reinterpret_cast<void **>(&ds->Dbuf[0]), sizeof(double) * n));
     TRON_HIP(hipMalloc(reinterpret_cast<void **>(&ds->Dbuf[1]), sizeof(double) * n));
     if (!ds->dense) {
@@ -167,7 +168,7 @@ void tron_dataset_destroy(tron_dataset *ds)
     hipFree(ds->X);
     ds->fwd.release();
     ds->bwd.release();
-    hipFree(ds->y); hipFree(ds->z); hipFree(ds->zhat); hipFree(ds->Dbuf[0]); hipFree(ds->Dbuf[1]);
+    hipFree(ds->y); hipFree(ds->y8); hipFree(ds->z); hipFree(ds->zhat); hipFree(ds->Dbuf[0]); hipFree(ds->Dbuf[1]);
     hipFree(ds->partials); hipFree(ds->row_partials); hipFree(ds->scal_dev);
     if (ds->scal_host) hipHostFree(ds->scal_host);
     for (double *p : ds->sv) hipFree(p);
@@ -322,7 +323,14 @@ int tron_dataset_write_rows(tron_dataset *ds, int64_t row0, int64_t nrows, const
     }
     const hipMemcpyKind kind = (mem == TRON_MEM_HOST) ? hipMemcpyHostToDevice : hipMemcpyDeviceToDevice;
     TRON_HIP(hipMemcpyAsync(ds->X + row0 * ds->d, X_chunk, sizeof(double) * (size_t)nrows * (size_t)ds->d, kind, ds->stream));
-    TRON_HIP(hipMemcpyAsync(ds->y + row0, y_chunk, sizeof(double) * (size_t)nrows, kind, ds->stream));
+    std::vector<int8_t> y8;
+    if (mem == TRON_MEM_HOST) {
+        y8.resize((size_t)nrows);
+        for (int64_t i = 0; i < nrows; ++i) y8[i] = (y_chunk[i] > 0.0) ? 1 : -1;
+        TRON_HIP(hipMemcpyAsync(ds->y8 + row0, y8.data(), (size_t)nrows, hipMemcpyHostToDevice, ds->stream));
+    } else {
+        TRON_TRY(dense_labels_from_device(ds, row0, nrows, y_chunk));
+    }
     TRON_HIP(hipStreamSynchronize(ds->stream));  // the caller may reuse its buffers on return
     ds->have_D = false;
     return TRON_OK;
@@ -351,6 +359,26 @@ int tron_dataset_shape(const tron_dataset *ds, int64_t *n, int64_t *d, int64_t *
     return TRON_OK;
 }
 
+int tron_dataset_stat(const tron_dataset *ds, const char *name, int64_t *value)
+{
+    if (!ds || !name || !value) { set_error("tron_dataset_stat: null argument"); return TRON_EINVAL; }
+    struct { const char *k; int64_t v; } tab[] = {
+        {"fwd_parts", ds->dense ? 0 : ds->fwd.P},
+        {"bwd_parts", ds->dense ? 0 : ds->bwd.P},
+        {"fwd_csr_nnz", ds->dense ? 0 : ds->fwd.nnz},
+        {"bwd_csr_nnz", ds->dense ? 0 : ds->bwd.nnz},
+        {"bwd_tile_nnz", ds->dense ? 0 : ds->bwd.hot.nnz},
+        {"bwd_tile_rows", ds->dense ? 0 : ds->bwd.hot.nhot},
+        {"bwd_tiles", ds->dense ? 0 : ds->bwd.hot.ntiles_total},
+        {"fwd_lds_columns", ds->dense ? 0 : [&] { int64_t t = 0; for (int x = 0; x < kMaxParts; ++x) t += ds->fwd.part_nhot[x]; return t; }()},
+        {"dense_grid", ds->dense_grid},
+    };
+    for (auto &e : tab)
+        if (strcmp(e.k, name) == 0) { *value = e.v; return TRON_OK; }
+    set_error("tron_dataset_stat: unknown name '%s'", name);
+    return TRON_EINVAL;
+}
+
 int tron_fun_grad(tron_dataset *ds, int loss, double C, const double *w_dev, double *f_host, double *g_dev)
 {
     if (!ds || !w_dev || !f_host || (loss != TRON_LOSS_LR && loss != TRON_LOSS_L2SVM) || !(C > 0.0) || !std::isfinite(C)) {
@@ -359,7 +387,7 @@ int tron_fun_grad(tron_dataset *ds, int loss, double C, const double *w_dev, dou
     }
     const int slot = ds->have_D ? 1 - ds->Dcur : ds->Dcur;
     if (ds->dense) {
-        TRON_TRY(dense_fun_grad(ds, loss, C, w_dev, ds->Dbuf[slot], g_dev));
+        TRON_TRY(dense_fun_grad(ds, loss, C, w_dev, slot, g_dev));
         TRON_TRY(read_scalars(ds, 3));
         *f_host = 0.5 * ds->scal_host[1] + C * ds->scal_host[0];
     } else {

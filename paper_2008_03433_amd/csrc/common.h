@@ -113,6 +113,7 @@ constexpr int kTileSlots = 2048;    // hot rows per slice = LDS accumulators per
 constexpr int kTileMinCount = 32;   // rows with fewer entries stay in the CSR layout
 
 struct HotTiles {
+    int64_t nnz = 0;                     // entries held in tiles
     int nhot = 0;                        // hot rows; row with rank r (by entry count) is slot r / 8 of slice r % 8
     int64_t ntiles_total = 0;
     int64_t tile0[kTileSlices] = {0};    // first tile of slice s
@@ -179,10 +180,12 @@ struct tron_dataset {
     // sparse: forward (n x d) and explicit transposed (d x n) copies
     tron::CsrPlan fwd, bwd;
 
-    double *y = nullptr;         // n
+    double *y = nullptr;         // n (sparse layouts)
+    int8_t *y8 = nullptr;        // n (dense layout: labels as +1 / -1 bytes)
     double *z = nullptr;         // n   (sparse: margins X w; also a0 / a1 work space for Hv)
     double *zhat = nullptr;      // n   (sparse only; dense folds it into the fused pass)
     double *Dbuf[2] = {nullptr, nullptr};  // n each: D at the accepted w and at the trial point
+    bool D_is_mask[2] = {false, false};    // dense L2-SVM: the buffer holds one active-set byte per row instead
     int Dcur = 0;
     bool have_D = false;
 
@@ -253,9 +256,10 @@ int dense_grid_for(int64_t n, int64_t d);
 int64_t dense_partials_needed(int64_t n, int64_t d);
 // fused pass: z = X w, loss terms, D -> Dout, partial sums of X^T zhat and of the loss;
 // then g = w + C (column sums) (if g != null), scalars[0] = sum loss, [1] = w.w, [2] = g.g
-int dense_fun_grad(tron_dataset *ds, int loss, double C, const double *w, double *Dout, double *g);
+int dense_fun_grad(tron_dataset *ds, int loss, double C, const double *w, int Dslot, double *g);
+int dense_labels_from_device(tron_dataset *ds, int64_t row0, int64_t m, const double *y_dev);
 // Hv = v + C X^T (D (X v)); scalars[0] = v.Hv
-int dense_hv(tron_dataset *ds, double C, const double *D, const double *v, double *Hv);
+int dense_hv(tron_dataset *ds, double C, int Dslot, const double *v, double *Hv);
 
 // ---- solver.hip
 int fun_eval(tron_dataset *ds, int loss, double C, const double *w, int Dslot, double *f_out);  // syncs

@@ -716,6 +716,7 @@ int hot_tiles_build(CsrPlan &A, const int64_t *t_rowptr, const int32_t *t_col, c
         }
         for (int64_t k = t_rowptr[i]; k < t_rowptr[i + 1]; ++k) {
             const int32_t code = slot_code[t_col[k]];
+            if (code >= 0) H.nnz++;
             if (code >= 0) cur[code / kTileSlots].push_back({(uint16_t)(code % kTileSlots), (uint16_t)(i - base[code / kTileSlots]), t_val[k]});
         }
     }

@@ -114,11 +114,14 @@ struct Tile {
 };
 
 // ------------------------------------------------------------------ Hessian-vector pass
-template <int E, int L, int U, bool VEC>
+// MASK: D is stored as one byte per row (L2-SVM: D_ii = 2 on the active set, else 0) instead of an fp64 value.
+template <int E, int L, int U, bool VEC, bool MASK>
 __global__ __launch_bounds__(kBlock) void k_dense_hv(int64_t n, int64_t d, const double *__restrict__ X,
-                                                     const double *__restrict__ D, const double *__restrict__ v,
+                                                     const void *__restrict__ Dv, const double *__restrict__ v,
                                                      double *__restrict__ partials)
 {
+    const double *D = static_cast<const double *>(Dv);
+    const uint8_t *Dm = static_cast<const uint8_t *>(Dv);
     using T = Tile<E, L, U, VEC>;
     __shared__ double lds[kWavesPerBlock * E * L];
     const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave;
@@ -135,7 +138,8 @@ __global__ __launch_bounds__(kBlock) void k_dense_hv(int64_t n, int64_t d, const
         const int64_t row0 = tile * T::RT;
         double x[U][E], t[U], c[U];
         T::load(X, n, d, row0, lane, x);
-        const double Drow = (lane < T::RT && row0 + lane < n) ? D[row0 + lane] : 0.0;
+        double Drow = 0.0;
+        if (lane < T::RT && row0 + lane < n) Drow = MASK ? (Dm[row0 + lane] ? 2.0 : 0.0) : D[row0 + lane];
         T::row_dots(x, vreg, t);
         const double a1 = Drow * T::to_row_owner(t, lane);   // a1 = D (X v)
         T::from_row_owner(a1, lane, c);
@@ -151,10 +155,12 @@ __global__ __launch_bounds__(kBlock) void k_dense_hv(int64_t n, int64_t d, const
 // ------------------------------------------------------------------ function / gradient pass
 template <int E, int L, int U, bool VEC, int LOSS>
 __global__ __launch_bounds__(kBlock) void k_dense_fun_grad(int64_t n, int64_t d, const double *__restrict__ X,
-                                                           const double *__restrict__ y, const double *__restrict__ w,
-                                                           double *__restrict__ Dout, double *__restrict__ partials,
+                                                           const int8_t *__restrict__ y, const double *__restrict__ w,
+                                                           void *__restrict__ Dv, double *__restrict__ partials,
                                                            double *__restrict__ loss_partials)
 {
+    double *Dout = static_cast<double *>(Dv);       // logistic loss: fp64 D
+    uint8_t *Dmask = static_cast<uint8_t *>(Dv);    // L2-SVM: active-set mask
     using T = Tile<E, L, U, VEC>;
     __shared__ double lds[kWavesPerBlock * E * L];
     __shared__ double lds_red[kWavesPerBlock];
@@ -174,13 +180,14 @@ __global__ __launch_bounds__(kBlock) void k_dense_fun_grad(int64_t n, int64_t d,
         double x[U][E], t[U], c[U];
         T::load(X, n, d, row0, lane, x);
         const bool mine = lane < T::RT && row0 + lane < n;
-        const double yrow = mine ? y[row0 + lane] : 1.0;
+        const double yrow = mine ? (double)y[row0 + lane] : 1.0;
         T::row_dots(x, wreg, t);
         const double z = T::to_row_owner(t, lane);            // z = X w
         double alpha, zhat, Di;
         loss_terms_dev<LOSS>(z, yrow, alpha, zhat, Di);
         if (mine) {
-            Dout[row0 + lane] = Di;
+            if (LOSS == TRON_LOSS_L2SVM) Dmask[row0 + lane] = (Di != 0.0) ? 1 : 0;
+            else Dout[row0 + lane] = Di;
             loss_acc += alpha;
         } else {
             zhat = 0.0;
@@ -260,26 +267,30 @@ bool pick_shape(int64_t d, Shape &s)
 constexpr int pick_U(int E, int L) { return (L < 4 ? L : 4); }
 
 template <int E, int L>
-int launch_hv(tron_dataset *ds, const double *D, const double *v)
+int launch_hv(tron_dataset *ds, const void *D, bool mask, const double *v)
 {
     constexpr int U = pick_U(E, L);
     const bool vec = (E % 2 == 0) && (ds->d % 2 == 0);
     const int grid = ds->dense_grid;
-    if (vec)
-        hipLaunchKernelGGL((k_dense_hv<E, L, U, (E % 2 == 0)>), dim3(grid), dim3(kBlock), 0, ds->stream, ds->n, ds->d, ds->X, D, v, ds->partials);
-    else
-        hipLaunchKernelGGL((k_dense_hv<E, L, U, false>), dim3(grid), dim3(kBlock), 0, ds->stream, ds->n, ds->d, ds->X, D, v, ds->partials);
+#define TRON_HV(V, M) \
+    hipLaunchKernelGGL((k_dense_hv<E, L, U, V, M>), dim3(grid), dim3(kBlock), 0, ds->stream, ds->n, ds->d, ds->X, D, v, ds->partials)
+    if (mask) {
+        if (vec) TRON_HV((E % 2 == 0), true); else TRON_HV(false, true);
+    } else {
+        if (vec) TRON_HV((E % 2 == 0), false); else TRON_HV(false, false);
+    }
+#undef TRON_HV
     return TRON_OK;
 }
 
 template <int E, int L>
-int launch_fg(tron_dataset *ds, int loss, const double *w, double *Dout, double *loss_partials)
+int launch_fg(tron_dataset *ds, int loss, const double *w, void *Dout, double *loss_partials)
 {
     constexpr int U = pick_U(E, L);
     const bool vec = (E % 2 == 0) && (ds->d % 2 == 0);
     const int grid = ds->dense_grid;
 #define TRON_FG(V, LS) \
-    hipLaunchKernelGGL((k_dense_fun_grad<E, L, U, V, LS>), dim3(grid), dim3(kBlock), 0, ds->stream, ds->n, ds->d, ds->X, ds->y, w, Dout, ds->partials, loss_partials)
+    hipLaunchKernelGGL((k_dense_fun_grad<E, L, U, V, LS>), dim3(grid), dim3(kBlock), 0, ds->stream, ds->n, ds->d, ds->X, ds->y8, w, Dout, ds->partials, loss_partials)
     if (loss == TRON_LOSS_LR) {
         if (vec) TRON_FG((E % 2 == 0), TRON_LOSS_LR); else TRON_FG(false, TRON_LOSS_LR);
     } else {
@@ -323,10 +334,25 @@ int launch_fg(tron_dataset *ds, int loss, const double *w, double *Dout, double 
     set_error("internal: no dense kernel for E=%d L=%d", s.E, s.L);              \
     return TRON_EINVAL;
 
-int dispatch_hv(tron_dataset *ds, const double *D, const double *v) { TRON_DISPATCH(launch_hv, ds, D, v) }
-int dispatch_fg(tron_dataset *ds, int loss, const double *w, double *Dout, double *lp) { TRON_DISPATCH(launch_fg, ds, loss, w, Dout, lp) }
+int dispatch_hv(tron_dataset *ds, const void *D, bool mask, const double *v) { TRON_DISPATCH(launch_hv, ds, D, mask, v) }
+int dispatch_fg(tron_dataset *ds, int loss, const double *w, void *Dout, double *lp) { TRON_DISPATCH(launch_fg, ds, loss, w, Dout, lp) }
 
 }  // namespace
+
+__global__ __launch_bounds__(kBlock) void k_labels_to_int8(int64_t m, const double *__restrict__ y, int8_t *__restrict__ y8)
+{
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < m; i += (int64_t)gridDim.x * kBlock)
+        y8[i] = (y[i] > 0.0) ? 1 : -1;
+}
+
+int dense_labels_from_device(tron_dataset *ds, int64_t row0, int64_t m, const double *y_dev)
+{
+    int64_t g = (m + kBlock - 1) / kBlock;
+    if (g > kMaxGrid) g = kMaxGrid;
+    hipLaunchKernelGGL(k_labels_to_int8, dim3((int)g), dim3(kBlock), 0, ds->stream, m, y_dev, ds->y8 + row0);
+    TRON_HIP(hipGetLastError());
+    return TRON_OK;
+}
 
 bool dense_supported(int64_t d)
 {
@@ -354,13 +380,15 @@ int64_t dense_partials_needed(int64_t n, int64_t d)
     return d * g + g + d;
 }
 
-int dense_hv(tron_dataset *ds, double C, const double *D, const double *v, double *Hv)
+int dense_hv(tron_dataset *ds, double C, int Dslot, const double *v, double *Hv)
 {
+    const void *D = ds->Dbuf[Dslot];
+    const bool mask = ds->D_is_mask[Dslot];
     const int grid = ds->dense_grid;
     double *colprod = ds->partials + ds->d * grid + grid;
     {
         ProfScope ps(ds, SLOT_DENSE_HV);
-        TRON_TRY(dispatch_hv(ds, D, v));
+        TRON_TRY(dispatch_hv(ds, D, mask, v));
         TRON_HIP(hipGetLastError());
     }
     ProfScope ps(ds, SLOT_DENSE_FINALIZE);
@@ -372,8 +400,10 @@ int dense_hv(tron_dataset *ds, double C, const double *D, const double *v, doubl
     return TRON_OK;
 }
 
-int dense_fun_grad(tron_dataset *ds, int loss, double C, const double *w, double *Dout, double *g)
+int dense_fun_grad(tron_dataset *ds, int loss, double C, const double *w, int Dslot, double *g)
 {
+    void *Dout = ds->Dbuf[Dslot];
+    ds->D_is_mask[Dslot] = (loss == TRON_LOSS_L2SVM);
     const int grid = ds->dense_grid;
     double *loss_partials = ds->partials + ds->d * grid;
     double *colprod = loss_partials + grid;

@@ -37,8 +37,8 @@ int grad_eval(tron_dataset *ds, double C, const double *w, double *g, double *gn
 // Hv = v + C X^T (D (X v)) with D = Dbuf[Dcur]; scal_dev[0] = v.Hv.  Enqueue only.
 int hv_enqueue(tron_dataset *ds, double C, const double *v, double *Hv)
 {
+    if (ds->dense) return dense_hv(ds, C, ds->Dcur, v, Hv);
     const double *D = ds->Dbuf[ds->Dcur];
-    if (ds->dense) return dense_hv(ds, C, D, v, Hv);
     TRON_TRY(spmv_scale(ds, ds->fwd, SLOT_SPMV_FWD_A1, v, D, ds->z));              // a1 = D (X v)
     const int g = spmv_axpy(ds, ds->bwd, SLOT_SPMV_BWD_HV, ds->z, v, C, false, Hv);  // Hv = v + C X^T a1
     TRON_TRY(g);
@@ -61,7 +61,7 @@ int ensure_solver_vectors(tron_dataset *ds)
 int eval_f(tron_dataset *ds, const tron_params &P, const double *w, int Dslot, double *gout, double *f, double *gnorm_dense)
 {
     if (ds->dense) {
-        TRON_TRY(dense_fun_grad(ds, P.loss, P.C, w, ds->Dbuf[Dslot], gout));
+        TRON_TRY(dense_fun_grad(ds, P.loss, P.C, w, Dslot, gout));
         TRON_TRY(read_scalars(ds, 3));
         *f = 0.5 * ds->scal_host[1] + P.C * ds->scal_host[0];
         *gnorm_dense = std::sqrt(ds->scal_host[2]);

@@ -1,0 +1,131 @@
+"""Parity at the full sizes the benchmark times (same launch configuration).
+
+Config 3 (sparse, 2M x 3M, 123M nonzeros) is small enough for the oracle to evaluate in full.
+Config 5 (dense, 230M x 24, 44 GB) is not: there the full-size device matrix is zero except for
+sampled row ranges (the first rows, a range in the middle that straddles the 2^31-element and
+2^32-byte marks, and a ragged tail), so the oracle can compute every output from the sampled rows
+alone: zero rows add nothing to g and Hv and a known constant to f.  A second test runs the real
+config-5 solve and checks properties that hold at any size.
+"""
+import numpy as np
+import pytest
+
+import datagen as dg
+from oracle import LOSS_LR, LOSS_L2SVM, Oracle
+
+pytestmark = pytest.mark.gpu
+
+from util import assert_scalar_close, assert_vec_close, check_calls, dev, torch_mod  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def c3():
+    return dg.config3()
+
+
+def test_config3_full_calls(c3, rng):
+    assert c3.n == 2_000_000 and c3.d == 3_000_000 and c3.nnz > 100_000_000
+    check_calls(c3, LOSS_LR, c3.C, rng, w_scale=1.0, n_hv=1)
+
+
+def test_config3_full_solve(c3):
+    import paper_2008_03433_amd as tron
+    torch = torch_mod()
+    ds = tron.Dataset.from_problem(c3)
+    w = torch.zeros(c3.d, dtype=torch.float64, device="cuda")
+    res = ds.solve(c3.loss, c3.C, c3.eps, w)
+    ds.close()
+    assert res.converged
+    fs = [t["f"] for t in res.trace]
+    assert all(b < a for a, b in zip([c3.C * c3.n * np.log(2.0)] + fs, fs))      # f(0) = C n ln 2, then monotone
+    # the oracle re-evaluates the GPU's final iterate from scratch: objective and stationarity
+    o = Oracle.from_problem(c3)
+    w_h = w.cpu().numpy()
+    f_o, g_o, _ = o.fun_grad(c3.loss, c3.C, w_h)
+    assert_scalar_close(res.f, f_o, rel=1e-10, what="f at the final iterate")
+    assert_scalar_close(res.gnorm, float(np.linalg.norm(g_o)), rel=1e-8, what="|g| at the final iterate")
+    _, g0, _ = o.fun_grad(c3.loss, c3.C, np.zeros(c3.d))
+    assert_scalar_close(res.gnorm0, float(np.linalg.norm(g0)), rel=1e-10, what="|g(0)|")
+    assert np.linalg.norm(g_o) <= c3.eps * np.linalg.norm(g0)
+
+
+@pytest.mark.parametrize("loss", [LOSS_L2SVM, LOSS_LR])
+def test_config5_full_size_sampled_rows(rng, loss):
+    import paper_2008_03433_amd as tron
+    torch = torch_mod()
+    stream = dg.config5()
+    n, d, C = stream.n, stream.d, 0.1
+    assert n == 230_000_000 and d == 24
+    h = tron.tron_dataset_create_dense_empty(n, d)
+    try:
+        # zero rows with label +1 everywhere ...
+        chunk = 1_000_000
+        zX = torch.zeros(chunk * d, dtype=torch.float64, device="cuda")
+        oy = torch.ones(chunk, dtype=torch.float64, device="cuda")
+        for row0 in range(0, n, chunk):
+            m = min(chunk, n - row0)
+            tron.tron_dataset_write_rows(h, row0, m, zX, oy)
+        del zX, oy
+        # ... except three sampled ranges of real rows
+        mid = (1 << 31) // d - 100_003            # straddles element 2^31 (byte 2^34); 2^32 bytes fall in the first range
+        ranges = [(0, 22_400_017), (mid, 250_001), (n - 123_457, 123_457)]
+        Xs, ys = [], []
+        for row0, m in ranges:
+            X, y = stream.rows(row0, m)
+            tron.tron_dataset_write_rows(h, row0, m, X, y)
+            Xs.append(X); ys.append(y)
+        Xs = np.concatenate(Xs); ys = np.concatenate(ys)
+        n_zero = n - Xs.shape[0]
+        o = Oracle(n=Xs.shape[0], d=d, y=ys, X=Xs)
+        w = 0.05 * rng.standard_normal(d)
+        v = rng.standard_normal(d)
+        f_o, g_o, D_o = o.fun_grad(loss, C, w)
+        f_expected = f_o + C * n_zero * (1.0 if loss == LOSS_L2SVM else np.log(2.0))
+        Hv_o = o.hv(C, D_o, v)
+        g = torch.empty(d, dtype=torch.float64, device="cuda")
+        Hv = torch.empty_like(g)
+        f = tron.tron_fun_grad(h, loss, C, dev(w), g)
+        vHv = tron.tron_hv(h, C, dev(v), Hv)
+        assert_scalar_close(f, f_expected, what="f")
+        assert_vec_close(g.cpu().numpy(), g_o, what="g")
+        assert_vec_close(Hv.cpu().numpy(), Hv_o, what="Hv")
+        assert_scalar_close(vHv, float(v @ Hv_o), what="v.Hv")
+    finally:
+        tron.tron_dataset_destroy(h)
+
+
+def test_config5_full_solve_properties():
+    import paper_2008_03433_amd as tron
+    torch = torch_mod()
+    stream = dg.config5()
+    n, d, C, eps = stream.n, stream.d, 0.1, 0.01
+    h = tron.tron_dataset_create_dense_empty(n, d)
+    try:
+        for row0, X, y in stream.chunks():
+            tron.tron_dataset_write_rows(h, row0, X.shape[0], X, y)
+        w = torch.zeros(d, dtype=torch.float64, device="cuda")
+        g = torch.empty_like(w)
+        f0 = tron.tron_fun_grad(h, LOSS_L2SVM, C, w, g)
+        assert f0 == C * n                                              # every slack is exactly 1 at w = 0
+        res = tron.tron_solve(h, LOSS_L2SVM, C, eps, w)
+        assert res.converged and res.status == 0
+        assert abs(res.gnorm0 - float(g.norm())) <= 1e-12 * res.gnorm0
+        fs = [f0] + [t["f"] for t in res.trace]
+        assert all(b < a for a, b in zip(fs, fs[1:]))
+        # stationarity and objective re-evaluated by a fresh call at the returned iterate
+        f1 = tron.tron_fun_grad(h, LOSS_L2SVM, C, w, g)
+        assert f1 == res.f
+        assert float(g.norm()) <= eps * res.gnorm0
+        # curvature: H >= I, and symmetric
+        u = torch.randn(d, dtype=torch.float64, device="cuda"); v = torch.randn(d, dtype=torch.float64, device="cuda")
+        Hu, Hv = torch.empty_like(u), torch.empty_like(v)
+        uHu = tron.tron_hv(h, C, u, Hu)
+        tron.tron_hv(h, C, v, Hv)
+        assert uHu >= float(u @ u)
+        assert abs(float(u @ Hv) - float(v @ Hu)) <= 1e-10 * abs(float(u @ Hv))
+        # two Gaussians at +-mu with 10% flips: the solution points along mu
+        mu = stream.mu / np.sqrt(1.0 + stream.mu ** 2)
+        cosang = float(w.cpu().numpy() @ mu) / (np.linalg.norm(mu) * float(w.norm()))
+        assert cosang > 0.999
+    finally:
+        tron.tron_dataset_destroy(h)
