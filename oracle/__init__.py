@@ -21,11 +21,16 @@ LOSS_LR = 0
 LOSS_L2SVM = 1
 
 
+_SO_F64 = os.path.join(_HERE, "liboracle_f64.so")
+
+
 def build(force: bool = False) -> str:
-    """Compile the oracle with gcc (single-threaded, no fast-math)."""
-    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-O2", "-fPIC", "-shared", "-fvisibility=hidden", "-ffp-contract=off", "-o", _SO, _SRC, "-lm"]
-        subprocess.check_call(cmd)
+    """Compile the oracle with gcc (single-threaded, no fast-math), and its plain-fp64 twin used by the
+    rounding-sensitivity tests."""
+    for so, extra in ((_SO, []), (_SO_F64, ["-DORC_ACC_DOUBLE"])):
+        if force or not os.path.exists(so) or os.path.getmtime(so) < os.path.getmtime(_SRC):
+            cmd = ["gcc", "-O2", "-fPIC", "-shared", "-fvisibility=hidden", "-ffp-contract=off", *extra, "-o", so, _SRC, "-lm"]
+            subprocess.check_call(cmd)
     return _SO
 
 
@@ -48,14 +53,13 @@ class _Result(ctypes.Structure):
                 ("n_grad", ctypes.c_int), ("n_hv", ctypes.c_int), ("converged", ctypes.c_int)]
 
 
-_lib = None
+_libs = {}
 
 
-def _L():
-    global _lib
-    if _lib is None:
+def _L(plain_fp64: bool = False):
+    if plain_fp64 not in _libs:
         build()
-        lib = ctypes.CDLL(_SO)
+        lib = ctypes.CDLL(_SO_F64 if plain_fp64 else _SO)
         P, dbl, vp, ci = ctypes.POINTER, ctypes.c_double, ctypes.c_void_p, ctypes.c_int
         lib.orc_fun.argtypes = [P(_Data), ci, dbl, vp, P(dbl), vp, vp, vp]
         lib.orc_grad.argtypes = [P(_Data), dbl, vp, vp, vp]
@@ -64,8 +68,8 @@ def _L():
         lib.orc_tron.argtypes = [P(_Data), ci, dbl, dbl, ci, ci, dbl, vp, P(_Result), P(TraceRec), ci, P(ci)]
         for f in (lib.orc_fun, lib.orc_grad, lib.orc_hv, lib.orc_cg, lib.orc_tron):
             f.restype = ci
-        _lib = lib
-    return _lib
+        _libs[plain_fp64] = lib
+    return _libs[plain_fp64]
 
 
 def _f64(a) -> np.ndarray:
@@ -91,8 +95,9 @@ class SolveResult:
 class Oracle:
     """One dataset (CSR or dense row-major) bound to the oracle routines."""
 
-    def __init__(self, *, n: int, d: int, y, rowptr=None, col=None, val=None, X=None):
+    def __init__(self, *, n: int, d: int, y, rowptr=None, col=None, val=None, X=None, plain_fp64: bool = False):
         self.n, self.d = int(n), int(d)
+        self._plain = bool(plain_fp64)   # sums in fp64 instead of long double (rounding-sensitivity experiments only)
         self.y = _f64(y)
         assert self.y.shape == (self.n,)
         if X is not None:
@@ -113,17 +118,17 @@ class Oracle:
                         self.y.ctypes.data)
 
     @classmethod
-    def from_problem(cls, p) -> "Oracle":
+    def from_problem(cls, p, plain_fp64: bool = False) -> "Oracle":
         if getattr(p, "X", None) is not None:
-            return cls(n=p.n, d=p.d, y=p.y, X=p.X)
-        return cls(n=p.n, d=p.d, y=p.y, rowptr=p.rowptr, col=p.col, val=p.val)
+            return cls(n=p.n, d=p.d, y=p.y, X=p.X, plain_fp64=plain_fp64)
+        return cls(n=p.n, d=p.d, y=p.y, rowptr=p.rowptr, col=p.col, val=p.val, plain_fp64=plain_fp64)
 
     def fun(self, loss: int, C: float, w):
         """f(w) and the per-instance z, zhat, D at w."""
         w = _f64(w)
         f = ctypes.c_double()
         z = np.empty(self.n); zhat = np.empty(self.n); D = np.empty(self.n)
-        rc = _L().orc_fun(ctypes.byref(self._c), loss, C, w.ctypes.data, ctypes.byref(f), z.ctypes.data,
+        rc = _L(self._plain).orc_fun(ctypes.byref(self._c), loss, C, w.ctypes.data, ctypes.byref(f), z.ctypes.data,
                           zhat.ctypes.data, D.ctypes.data)
         assert rc == 0
         return f.value, z, zhat, D
@@ -131,7 +136,7 @@ class Oracle:
     def grad(self, C: float, w, zhat):
         w, zhat = _f64(w), _f64(zhat)
         g = np.empty(self.d)
-        rc = _L().orc_grad(ctypes.byref(self._c), C, w.ctypes.data, zhat.ctypes.data, g.ctypes.data)
+        rc = _L(self._plain).orc_grad(ctypes.byref(self._c), C, w.ctypes.data, zhat.ctypes.data, g.ctypes.data)
         assert rc == 0
         return g
 
@@ -142,7 +147,7 @@ class Oracle:
     def hv(self, C: float, D, v):
         D, v = _f64(D), _f64(v)
         Hv = np.empty(self.d)
-        rc = _L().orc_hv(ctypes.byref(self._c), C, D.ctypes.data, v.ctypes.data, Hv.ctypes.data)
+        rc = _L(self._plain).orc_hv(ctypes.byref(self._c), C, D.ctypes.data, v.ctypes.data, Hv.ctypes.data)
         assert rc == 0
         return Hv
 
@@ -150,7 +155,7 @@ class Oracle:
         D, g = _f64(D), _f64(g)
         s = np.empty(self.d); r = np.empty(self.d)
         nhv, onb = ctypes.c_int(), ctypes.c_int()
-        rc = _L().orc_cg(ctypes.byref(self._c), C, D.ctypes.data, g.ctypes.data, delta, xi, max_cg,
+        rc = _L(self._plain).orc_cg(ctypes.byref(self._c), C, D.ctypes.data, g.ctypes.data, delta, xi, max_cg,
                          s.ctypes.data, r.ctypes.data, ctypes.byref(nhv), ctypes.byref(onb))
         assert rc == 0
         return s, r, nhv.value, bool(onb.value)
@@ -161,7 +166,7 @@ class Oracle:
         res = _Result()
         trace = (TraceRec * trace_cap)()
         tl = ctypes.c_int()
-        rc = _L().orc_tron(ctypes.byref(self._c), loss, C, eps, max_outer, max_cg, xi, w.ctypes.data,
+        rc = _L(self._plain).orc_tron(ctypes.byref(self._c), loss, C, eps, max_outer, max_cg, xi, w.ctypes.data,
                            ctypes.byref(res), trace, trace_cap, ctypes.byref(tl))
         assert rc >= 0
         recs = [{k: getattr(trace[i], k) for k, _ in TraceRec._fields_} for i in range(tl.value)]

@@ -38,6 +38,16 @@
 
 #define ORC_API __attribute__((visibility("default")))
 
+/* Accumulator type of every sum.  The oracle proper uses long double; building with -DORC_ACC_DOUBLE gives a plain
+ * fp64 twin that the tests use only to measure how far rounding alone can move a trust-region trajectory. */
+#ifdef ORC_ACC_DOUBLE
+typedef double acc_t;
+#define ORC_SQRT sqrt
+#else
+typedef long double acc_t;
+#define ORC_SQRT sqrtl
+#endif
+
 enum { ORC_LOSS_LR = 0, ORC_LOSS_L2SVM = 1 };
 
 typedef struct {
@@ -54,35 +64,35 @@ typedef struct {
 /* ---- row access: the only place the storage format matters ---- */
 
 /* x_i . u */
-static long double row_dot(const orc_data *A, int64_t i, const double *u)
+static acc_t row_dot(const orc_data *A, int64_t i, const double *u)
 {
-    long double acc = 0.0L;
+    acc_t acc = (acc_t)0;
     if (A->X) {
         const double *x = A->X + i * A->d;
-        for (int64_t j = 0; j < A->d; ++j) acc += (long double)x[j] * (long double)u[j];
+        for (int64_t j = 0; j < A->d; ++j) acc += (acc_t)x[j] * (acc_t)u[j];
     } else {
         for (int64_t k = A->rowptr[i]; k < A->rowptr[i + 1]; ++k)
-            acc += (long double)A->val[k] * (long double)u[A->col[k]];
+            acc += (acc_t)A->val[k] * (acc_t)u[A->col[k]];
     }
     return acc;
 }
 
 /* acc += c * x_i */
-static void row_axpy(const orc_data *A, int64_t i, long double c, long double *acc)
+static void row_axpy(const orc_data *A, int64_t i, acc_t c, acc_t *acc)
 {
     if (A->X) {
         const double *x = A->X + i * A->d;
-        for (int64_t j = 0; j < A->d; ++j) acc[j] += c * (long double)x[j];
+        for (int64_t j = 0; j < A->d; ++j) acc[j] += c * (acc_t)x[j];
     } else {
         for (int64_t k = A->rowptr[i]; k < A->rowptr[i + 1]; ++k)
-            acc[A->col[k]] += c * (long double)A->val[k];
+            acc[A->col[k]] += c * (acc_t)A->val[k];
     }
 }
 
-static long double vdot(int64_t m, const double *a, const double *b)
+static acc_t vdot(int64_t m, const double *a, const double *b)
 {
-    long double acc = 0.0L;
-    for (int64_t j = 0; j < m; ++j) acc += (long double)a[j] * (long double)b[j];
+    acc_t acc = (acc_t)0;
+    for (int64_t j = 0; j < m; ++j) acc += (acc_t)a[j] * (acc_t)b[j];
     return acc;
 }
 
@@ -141,7 +151,7 @@ static void svm_terms(double z, double yi, double *alpha, double *zhat, double *
 ORC_API int orc_fun(const orc_data *A, int loss, double C, const double *w, double *f_out, double *z_out,
                     double *zhat, double *D)
 {
-    long double sum = 0.0L;
+    acc_t sum = (acc_t)0;
     for (int64_t i = 0; i < A->n; ++i) {
         const double z = (double)row_dot(A, i, w);
         double a, zh, Di;
@@ -149,23 +159,23 @@ ORC_API int orc_fun(const orc_data *A, int loss, double C, const double *w, doub
             lr_terms(A->y[i] * z, A->y[i], &a, &zh, &Di);
         else
             svm_terms(z, A->y[i], &a, &zh, &Di);
-        sum += (long double)a;
+        sum += (acc_t)a;
         if (z_out) z_out[i] = z;
         if (zhat) zhat[i] = zh;
         if (D) D[i] = Di;
     }
-    *f_out = (double)(0.5L * vdot(A->d, w, w) + (long double)C * sum);
+    *f_out = (double)((acc_t)0.5 * vdot(A->d, w, w) + (acc_t)C * sum);
     return 0;
 }
 
 /* Gradient (Table 1, Appendix B):  g = w + C sum_i zhat_i x_i. */
 ORC_API int orc_grad(const orc_data *A, double C, const double *w, const double *zhat, double *g)
 {
-    long double *acc = (long double *)calloc((size_t)A->d, sizeof(long double));
+    acc_t *acc = (acc_t *)calloc((size_t)A->d, sizeof(acc_t));
     if (!acc) return -2;
     for (int64_t i = 0; i < A->n; ++i)
-        if (zhat[i] != 0.0) row_axpy(A, i, (long double)zhat[i], acc);
-    for (int64_t j = 0; j < A->d; ++j) g[j] = (double)((long double)w[j] + (long double)C * acc[j]);
+        if (zhat[i] != 0.0) row_axpy(A, i, (acc_t)zhat[i], acc);
+    for (int64_t j = 0; j < A->d; ++j) g[j] = (double)((acc_t)w[j] + (acc_t)C * acc[j]);
     free(acc);
     return 0;
 }
@@ -173,15 +183,15 @@ ORC_API int orc_grad(const orc_data *A, double C, const double *w, const double 
 /* Hessian-vector product (Table 1, Appendix B, D):  Hv = v + C sum_i D_i (x_i.v) x_i. */
 ORC_API int orc_hv(const orc_data *A, double C, const double *D, const double *v, double *Hv)
 {
-    long double *acc = (long double *)calloc((size_t)A->d, sizeof(long double));
+    acc_t *acc = (acc_t *)calloc((size_t)A->d, sizeof(acc_t));
     if (!acc) return -2;
     for (int64_t i = 0; i < A->n; ++i) {
         if (D[i] == 0.0) continue;
-        const long double a0 = row_dot(A, i, v);         /* a0 = X v      */
-        const long double a1 = (long double)D[i] * a0;   /* a1 = D a0     */
+        const acc_t a0 = row_dot(A, i, v);         /* a0 = X v      */
+        const acc_t a1 = (acc_t)D[i] * a0;   /* a1 = D a0     */
         row_axpy(A, i, a1, acc);                         /* X^T a1        */
     }
-    for (int64_t j = 0; j < A->d; ++j) Hv[j] = (double)((long double)v[j] + (long double)C * acc[j]);
+    for (int64_t j = 0; j < A->d; ++j) Hv[j] = (double)((acc_t)v[j] + (acc_t)C * acc[j]);
     free(acc);
     return 0;
 }
@@ -212,42 +222,42 @@ ORC_API int orc_cg(const orc_data *A, double C, const double *D, const double *g
     double *Hp = (double *)malloc(sizeof(double) * (size_t)d);
     if (!p || !Hp) { free(p); free(Hp); return -2; }
     for (int64_t j = 0; j < d; ++j) { s[j] = 0.0; r[j] = -g[j]; p[j] = r[j]; }
-    long double rr = vdot(d, r, r);
-    const long double gnorm = sqrtl(vdot(d, g, g));
+    acc_t rr = vdot(d, r, r);
+    const acc_t gnorm = ORC_SQRT(vdot(d, g, g));
     int it = 0;
     *on_boundary = 0;
     while (it < max_cg) {
-        if (sqrtl(rr) <= (long double)xi * gnorm) break;
+        if (ORC_SQRT(rr) <= (acc_t)xi * gnorm) break;
         orc_hv(A, C, D, p, Hp);
         ++it;
-        const long double pHp = vdot(d, p, Hp);
+        const acc_t pHp = vdot(d, p, Hp);
         const double alpha = (double)(rr / pHp);
         /* length of the tentative iterate s + alpha p */
-        long double len2 = 0.0L;
+        acc_t len2 = (acc_t)0;
         for (int64_t j = 0; j < d; ++j) {
-            const long double t = (long double)s[j] + (long double)alpha * (long double)p[j];
+            const acc_t t = (acc_t)s[j] + (acc_t)alpha * (acc_t)p[j];
             len2 += t * t;
         }
-        if (sqrtl(len2) >= (long double)delta) {
+        if (ORC_SQRT(len2) >= (acc_t)delta) {
             /* positive root of |s + tau p|^2 = Delta^2, in the cancellation-free form */
-            const long double ss = vdot(d, s, s), sp = vdot(d, s, p), pp = vdot(d, p, p);
-            const long double gap = (long double)delta * (long double)delta - ss;
-            const long double rad = sqrtl(sp * sp + pp * gap);
-            const double tau = (double)((sp >= 0.0L) ? gap / (sp + rad) : (rad - sp) / pp);
+            const acc_t ss = vdot(d, s, s), sp = vdot(d, s, p), pp = vdot(d, p, p);
+            const acc_t gap = (acc_t)delta * (acc_t)delta - ss;
+            const acc_t rad = ORC_SQRT(sp * sp + pp * gap);
+            const double tau = (double)((sp >= (acc_t)0) ? gap / (sp + rad) : (rad - sp) / pp);
             for (int64_t j = 0; j < d; ++j) {
-                s[j] = (double)((long double)s[j] + (long double)tau * (long double)p[j]);
-                r[j] = (double)((long double)r[j] - (long double)tau * (long double)Hp[j]);
+                s[j] = (double)((acc_t)s[j] + (acc_t)tau * (acc_t)p[j]);
+                r[j] = (double)((acc_t)r[j] - (acc_t)tau * (acc_t)Hp[j]);
             }
             *on_boundary = 1;
             break;
         }
         for (int64_t j = 0; j < d; ++j) {
-            s[j] = (double)((long double)s[j] + (long double)alpha * (long double)p[j]);
-            r[j] = (double)((long double)r[j] - (long double)alpha * (long double)Hp[j]);
+            s[j] = (double)((acc_t)s[j] + (acc_t)alpha * (acc_t)p[j]);
+            r[j] = (double)((acc_t)r[j] - (acc_t)alpha * (acc_t)Hp[j]);
         }
-        const long double rr_new = vdot(d, r, r);
+        const acc_t rr_new = vdot(d, r, r);
         const double beta = (double)(rr_new / rr);
-        for (int64_t j = 0; j < d; ++j) p[j] = (double)((long double)r[j] + (long double)beta * (long double)p[j]);
+        for (int64_t j = 0; j < d; ++j) p[j] = (double)((acc_t)r[j] + (acc_t)beta * (acc_t)p[j]);
         rr = rr_new;
     }
     *n_hv = it;
@@ -320,7 +330,7 @@ ORC_API int orc_tron(const orc_data *A, int loss, double C, double eps, int max_
             memset(wnew, 0, sizeof(double) * (size_t)d);
             orc_fun(A, loss, C, wnew, &f0, NULL, zhat, Dnew);
             orc_grad(A, C, wnew, zhat, g);
-            res->gnorm0 = (double)sqrtl(vdot(d, g, g));
+            res->gnorm0 = (double)ORC_SQRT(vdot(d, g, g));
             res->n_fun++; res->n_grad++;
         }
     }
@@ -328,7 +338,7 @@ ORC_API int orc_tron(const orc_data *A, int loss, double C, double eps, int max_
     orc_fun(A, loss, C, w, &f, NULL, zhat, Dcur);
     orc_grad(A, C, w, zhat, g);
     res->n_fun++; res->n_grad++;
-    double gnorm = (double)sqrtl(vdot(d, g, g));
+    double gnorm = (double)ORC_SQRT(vdot(d, g, g));
     if (res->gnorm0 == 0.0) res->gnorm0 = gnorm;
     double delta = gnorm;
     if (gnorm <= eps * res->gnorm0) { status = 0; res->converged = 1; }
@@ -337,8 +347,8 @@ ORC_API int orc_tron(const orc_data *A, int loss, double C, double eps, int max_
         int ncg = 0, onb = 0;
         orc_cg(A, C, Dcur, g, delta, xi, max_cg, s, r, &ncg, &onb);
         res->n_hv += ncg; res->cg_iters_total += ncg;
-        const double snorm = (double)sqrtl(vdot(d, s, s));
-        const double pred = (double)(-0.5L * (vdot(d, g, s) - vdot(d, s, r)));
+        const double snorm = (double)ORC_SQRT(vdot(d, s, s));
+        const double pred = (double)(-(acc_t)0.5 * (vdot(d, g, s) - vdot(d, s, r)));
         for (int64_t j = 0; j < d; ++j) wnew[j] = w[j] + s[j];
         double fnew;
         orc_fun(A, loss, C, wnew, &fnew, NULL, zhat, Dnew);
@@ -358,7 +368,7 @@ ORC_API int orc_tron(const orc_data *A, int loss, double C, double eps, int max_
             orc_grad(A, C, w, zhat, g);
             res->n_grad++;
             { double *t = Dcur; Dcur = Dnew; Dnew = t; }
-            gnorm = (double)sqrtl(vdot(d, g, g));
+            gnorm = (double)ORC_SQRT(vdot(d, g, g));
         }
         res->outer_iters = k;
         if (trace && tl < trace_cap) {

@@ -475,10 +475,6 @@ int tron_tuning_set(const char *name, int64_t value)
         g_tuning.csr_tile_blocks_per_slice = value;
         return TRON_OK;
     }
-    if (name && strcmp(name, "csr_ablate") == 0 && value >= 0 && value <= 3) {
-        g_tuning.csr_ablate = value;
-        return TRON_OK;
-    }
     if (name && strcmp(name, "csr_blocks_per_part") == 0 && value >= 0 && value <= 4096) {
         g_tuning.csr_blocks_per_part = value;
         return TRON_OK;

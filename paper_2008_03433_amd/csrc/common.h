@@ -37,7 +37,6 @@ struct Tuning {
     int64_t csr_two_streams = 0;  // 1 = run the hot-row tiles beside the CSR remainder on a second stream (measured slower: both
                                   // kernels compete for the same per-CU miss queue)
     int64_t csr_tile_blocks_per_slice = 128;  // persistent workgroups per slice of hot rows
-    int64_t csr_ablate = 0;  // timing experiments only (wrong results): 1 = no gathers, 2 = no row reduction
 };
 extern Tuning g_tuning;
 
@@ -121,9 +120,10 @@ struct HotTiles {
     int blocks_per_slice = 0;            // persistent workgroups per slice
     double *val = nullptr;               // device, ntiles_total * kChunk (zero padded)
     uint16_t *iloc = nullptr;            // device, ntiles_total * kChunk: column minus the tile's first column
-    int4 *hdr = nullptr;                 // device, per tile: {first column, segments, long segments, index into seg_*}
-    uint16_t *seg_slot = nullptr;        // device: slot of each segment (ascending inside a tile)
-    uint16_t *seg_end = nullptr;         // device: end offset of each segment inside its tile
+    int4 *hdr = nullptr;                 // device, per tile: {first column, segments, long | medium << 16 segment counts,
+                                         //   index into seg_desc}
+    uint32_t *seg_desc = nullptr;        // device: per segment, end offset inside its tile | slot << 16; the segments of a
+                                         //   tile are ordered long, medium, short
     int32_t *slot_of_row = nullptr;      // device, rows: slice * kTileSlots + slot, or -1
     double *wg_acc = nullptr;            // device, kTileSlices * blocks_per_slice * kTileSlots workgroup accumulators
     double *sums = nullptr;              // device, kTileSlices * kTileSlots: per hot row, sum over its tiles

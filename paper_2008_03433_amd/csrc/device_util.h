@@ -5,19 +5,49 @@
 
 namespace tron {
 
-// Sum over the 64 lanes of a wavefront; every lane receives the total.  Fixed butterfly order.
-__device__ __forceinline__ double wave_sum(double v)
+// Cross-lane moves through the DPP data path (a few cycles) instead of ds_bpermute (an LDS round trip):
+//   0xB1 = quad_perm [1,0,3,2] (lane ^ 1), 0x4E = quad_perm [2,3,0,1] (lane ^ 2),
+//   0x141 = row_half_mirror (lane i <-> 7-i inside each group of 8), 0x140 = row_mirror (i <-> 15-i inside 16).
+template <int CTRL>
+__device__ __forceinline__ double dpp_move(double v)
 {
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
-    return v;
+    int lo = __double2loint(v), hi = __double2hiint(v);
+    lo = __builtin_amdgcn_update_dpp(lo, lo, CTRL, 0xf, 0xf, false);
+    hi = __builtin_amdgcn_update_dpp(hi, hi, CTRL, 0xf, 0xf, false);
+    return __hiloint2double(hi, lo);
 }
 
-// Sum over aligned groups of `g` consecutive lanes (g a power of two <= 64).
+__device__ __forceinline__ double read_lane(double v, int lane)
+{
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), lane);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), lane);
+    return __hiloint2double(hi, lo);
+}
+
+// Sum over aligned groups of 2 / 4 / 8 / 16 consecutive lanes; every lane of a group receives its total.
+__device__ __forceinline__ double sum2(double v) { return v + dpp_move<0xB1>(v); }
+__device__ __forceinline__ double sum4(double v) { v = sum2(v); return v + dpp_move<0x4E>(v); }
+__device__ __forceinline__ double sum8(double v) { v = sum4(v); return v + dpp_move<0x141>(v); }
+__device__ __forceinline__ double sum16(double v) { v = sum8(v); return v + dpp_move<0x140>(v); }
+
+// Sum over the 64 lanes of a wavefront; every lane receives the total.  Fixed order.
+__device__ __forceinline__ double wave_sum(double v)
+{
+    v = sum16(v);
+    return (read_lane(v, 0) + read_lane(v, 16)) + (read_lane(v, 32) + read_lane(v, 48));
+}
+
+// Sum over aligned groups of `g` consecutive lanes (g a power of two <= 64); every lane of a group gets its total.
 __device__ __forceinline__ double group_sum(double v, int g)
 {
-    for (int m = g >> 1; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
-    return v;
+    if (g == 1) return v;
+    if (g == 2) return sum2(v);
+    if (g == 4) return sum4(v);
+    if (g == 8) return sum8(v);
+    v = sum16(v);
+    if (g == 16) return v;
+    if (g == 32) return v + __shfl_xor(v, 16, kWave);
+    return (read_lane(v, 0) + read_lane(v, 16)) + (read_lane(v, 32) + read_lane(v, 48));
 }
 
 // Sum over the workgroup (kBlock threads); valid in thread 0.  `lds` holds kWavesPerBlock doubles

@@ -31,7 +31,7 @@ constexpr int kHotMinCount = 8;   // columns with fewer entries are not worth an
 
 void HotTiles::release()
 {
-    hipFree(val); hipFree(iloc); hipFree(hdr); hipFree(seg_slot); hipFree(seg_end); hipFree(slot_of_row);
+    hipFree(val); hipFree(iloc); hipFree(hdr); hipFree(seg_desc); hipFree(slot_of_row);
     hipFree(wg_acc); hipFree(sums);
     *this = HotTiles();
 }
@@ -277,11 +277,21 @@ __device__ __forceinline__ double epilogue(double sum, int64_t r, const double *
 // chunk-local tables row_lo[0..1] and carry slot *carry_out.
 // With HOT, a negative stored column c means "entry ~c of the workgroup's LDS table" (the most frequent
 // columns of the partition, copied from x once per workgroup).
+// x[c] through a 32-bit byte offset (c < 2^28 is guaranteed by the plan builder's size checks)
+__device__ __forceinline__ double load_elem(const double *__restrict__ x, int c)
+{
+    return *reinterpret_cast<const double *>(reinterpret_cast<const char *>(x) + (size_t)((uint32_t)c << 3));
+}
+
 template <bool HOT>
 __device__ __forceinline__ double gather(const double *__restrict__ x, const double *table, int c)
 {
-    if (HOT && c < 0) return table[~c];
-    return x[c];
+    if (!HOT) return load_elem(x, c);
+    // two separate accesses (an LDS read and a lane-masked global load), not one flat load of a selected address
+    const double hot = table[(c < 0) ? ~c : 0];
+    double cold = 0.0;
+    if (c >= 0) cold = load_elem(x, c);
+    return (c < 0) ? hot : cold;
 }
 
 template <int EPI, typename RP, bool HOT = false>
@@ -454,7 +464,7 @@ __global__ __launch_bounds__(kBlock) void k_csr_spmv_part(PartArgs pa, int64_t r
                                                           const double *__restrict__ val_all, const int4 *__restrict__ chunk_tab,
                                                           const uint16_t *__restrict__ seg_end, const int32_t *__restrict__ seg_row_all,
                                                           const int32_t *__restrict__ hot_ids, const double *__restrict__ x,
-                                                          double *__restrict__ partial_all, double *__restrict__ carry_all, int ablate)
+                                                          double *__restrict__ partial_all, double *__restrict__ carry_all)
 {
     __shared__ __align__(16) double prod[kChunk];
     __shared__ __align__(16) uint16_t ends[kChunk];
@@ -467,10 +477,10 @@ __global__ __launch_bounds__(kBlock) void k_csr_spmv_part(PartArgs pa, int64_t r
     if (HOT) {
         const int nhot = pa.nhot[xp];
         for (int k = tid; k < nhot; k += kBlock) table[k] = x[hot_ids[xp * kHotSlots + k]];
+        if (tid == 0 && nhot == 0) table[0] = 0.0;
         __syncthreads();
     }
-    const int64_t nnz = pa.nnz[xp];
-    const int32_t *col = col_all + pa.base[xp];
+    const int32_t *col = col_all + pa.base[xp];     // padded to whole chunks (zeros)
     const double *val = val_all + pa.base[xp];
     const int4 *tabs = chunk_tab + pa.chunk0[xp];
     const int32_t *seg_row = seg_row_all + pa.seg0[xp];
@@ -479,105 +489,72 @@ __global__ __launch_bounds__(kBlock) void k_csr_spmv_part(PartArgs pa, int64_t r
 
     int c = q;
     int4 tab = tabs[c];
-    int4 tab_n = (c + Q < nchunks) ? tabs[c + Q] : make_int4(0, 0, 0, 0);
-    StreamRegs cur;
-    bool cur_full = ((int64_t)(c + 1) * kChunk <= nnz);
-    if (cur_full) cur = load_stream(col, val, (int64_t)c * kChunk);
+    int4 tab_n = tabs[(c + Q < nchunks) ? c + Q : c];
+    StreamRegs cur = load_stream(col, val, (int64_t)c * kChunk);
     SegRegs seg = load_segs(tab, seg_end, seg_row);
 
     for (; c < nchunks; c += Q) {
-        const int64_t start = (int64_t)c * kChunk;
-        const int64_t end = (start + kChunk < nnz) ? start + kChunk : nnz;
-        const int cn = c + Q;
         const int nseg = tab.y, first_off = tab.z;
         if (8 * tid < nseg) *reinterpret_cast<uint4 *>(ends + 8 * tid) = seg.ends;
-
-        StreamRegs nxt;
-        SegRegs seg_n;
-        int4 tab_nn = make_int4(0, 0, 0, 0);
-        bool nxt_full = false;
-        if (cur_full) {
-            double xg[2][4];
-            if (ablate & 1) {
+        // products of this chunk into LDS
+        double xg[2][4];
 #pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    xg[j][0] = (double)cur.c[j].x; xg[j][1] = (double)cur.c[j].y;
-                    xg[j][2] = (double)cur.c[j].z; xg[j][3] = (double)cur.c[j].w;
-                }
-            } else {
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    xg[j][0] = gather<HOT>(x, table, cur.c[j].x);
-                    xg[j][1] = gather<HOT>(x, table, cur.c[j].y);
-                    xg[j][2] = gather<HOT>(x, table, cur.c[j].z);
-                    xg[j][3] = gather<HOT>(x, table, cur.c[j].w);
-                }
-            }
-            if (cn < nchunks) {   // prefetch the next chunk (issued after the gathers, waited for one iteration later)
-                nxt_full = ((int64_t)(cn + 1) * kChunk <= nnz);
-                if (nxt_full) nxt = load_stream(col, val, (int64_t)cn * kChunk);
-                seg_n = load_segs(tab_n, seg_end, seg_row);
-                if (cn + Q < nchunks) tab_nn = tabs[cn + Q];
-            }
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                double2 p0, p1;
-                p0.x = cur.v[j][0].x * xg[j][0];
-                p0.y = cur.v[j][0].y * xg[j][1];
-                p1.x = cur.v[j][1].x * xg[j][2];
-                p1.y = cur.v[j][1].y * xg[j][3];
-                double2 *dst = reinterpret_cast<double2 *>(prod + j * (kChunk / 2) + tid * 4);
-                dst[0] = p0;
-                dst[1] = p1;
-            }
-        } else {
-            for (int k = tid; k < kChunk; k += kBlock) {
-                const int64_t kk = start + k;
-                prod[k] = (kk < end) ? val[kk] * gather<HOT>(x, table, col[kk]) : 0.0;
-            }
-            if (cn < nchunks) {
-                nxt_full = ((int64_t)(cn + 1) * kChunk <= nnz);
-                if (nxt_full) nxt = load_stream(col, val, (int64_t)cn * kChunk);
-                seg_n = load_segs(tab_n, seg_end, seg_row);
-                if (cn + Q < nchunks) tab_nn = tabs[cn + Q];
-            }
+        for (int j = 0; j < 2; ++j) {
+            xg[j][0] = gather<HOT>(x, table, cur.c[j].x);
+            xg[j][1] = gather<HOT>(x, table, cur.c[j].y);
+            xg[j][2] = gather<HOT>(x, table, cur.c[j].z);
+            xg[j][3] = gather<HOT>(x, table, cur.c[j].w);
         }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            double2 p0, p1;
+            p0.x = cur.v[j][0].x * xg[j][0];
+            p0.y = cur.v[j][0].y * xg[j][1];
+            p1.x = cur.v[j][1].x * xg[j][2];
+            p1.y = cur.v[j][1].y * xg[j][3];
+            double2 *dst = reinterpret_cast<double2 *>(prod + j * (kChunk / 2) + tid * 4);
+            dst[0] = p0;
+            dst[1] = p1;
+        }
+        // Only now fetch the next chunk (clamped index: always the same loads): nothing below waits for these
+        // registers, so they stay in flight during the barrier and the segment sums and are waited for at the
+        // top of the next iteration.
+        __builtin_amdgcn_sched_barrier(0);
+        const int cn = (c + Q < nchunks) ? c + Q : c;
+        const int cnn = (cn + Q < nchunks) ? cn + Q : cn;
+        const StreamRegs nxt = load_stream(col, val, (int64_t)cn * kChunk);
+        const SegRegs seg_n = load_segs(tab_n, seg_end, seg_row);
+        const int4 tab_nn = tabs[cnn];
+        __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
 
-        if (ablate & 2) {   // timing experiment only: skip the segment reduction
-            double sacc = prod[tid] + prod[tid + 256] + prod[tid + 512] + prod[tid + 768];
+        // carry: the part of the row entering this chunk from before (wavefront 0)
+        if (c > 0 && tid < kWave && first_off > 0) {
+            double sacc = 0.0;
+            for (int k = tid; k < first_off; k += kWave) sacc += prod[k];
             sacc = wave_sum(sacc);
             if (tid == 0) carry[c] = sacc;
-        } else {
-            // carry: the part of the row entering this chunk from before (wavefront 0)
-            if (c > 0 && tid < kWave && first_off > 0) {
-                double sacc = 0.0;
-                for (int k = tid; k < first_off; k += kWave) sacc += prod[k];
-                sacc = wave_sum(sacc);
-                if (tid == 0) carry[c] = sacc;
-            }
-            // segments that start in this chunk: g lanes each
-            const int g = lanes_per_segment(nseg);
-            const int sub = tid & (g - 1);
-            const int first = tid / g;
+        }
+        // segments that start in this chunk: g lanes each
+        const int g = lanes_per_segment(nseg);
+        const int sub = tid & (g - 1);
+        const int first = tid / g;
 #pragma unroll
-            for (int j = 0; j < kSegPasses; ++j) {
-                if (j * kBlock < nseg && (g == 1 || j == 0)) {   // uniform over the workgroup
-                    const int sidx = first + kBlock * j;
-                    double sacc = 0.0;
-                    if (sidx < nseg) {
-                        const int k0 = (sidx == 0) ? first_off : (int)ends[sidx - 1];
-                        const int k1 = (int)ends[sidx];
-                        for (int k = k0 + sub; k < k1; k += g) sacc += prod[k];
-                    }
-                    sacc = group_sum(sacc, g);
-                    if (sidx < nseg && sub == 0) partial[seg.rid[j]] = sacc;
+        for (int j = 0; j < kSegPasses; ++j) {
+            if (j * kBlock < nseg && (g == 1 || j == 0)) {   // uniform over the workgroup
+                const int sidx = first + kBlock * j;
+                double sacc = 0.0;
+                if (sidx < nseg) {
+                    const int k0 = (sidx == 0) ? first_off : (int)ends[sidx - 1];
+                    const int k1 = (int)ends[sidx];
+                    for (int k = k0 + sub; k < k1; k += g) sacc += prod[k];
                 }
+                sacc = group_sum(sacc, g);
+                if (sidx < nseg && sub == 0) partial[seg.rid[j]] = sacc;
             }
         }
         __syncthreads();  // prod / ends are reused by the next chunk
         cur = nxt;
-        cur_full = nxt_full;
         seg = seg_n;
         tab = tab_n;
         tab_n = tab_nn;
@@ -610,10 +587,10 @@ __global__ __launch_bounds__(kBlock) void k_csr_spmv_part_np(PartArgs pa, int64_
     double xg[2][4];
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-        xg[j][0] = x[cur.c[j].x];
-        xg[j][1] = x[cur.c[j].y];
-        xg[j][2] = x[cur.c[j].z];
-        xg[j][3] = x[cur.c[j].w];
+        xg[j][0] = load_elem(x, cur.c[j].x);
+        xg[j][1] = load_elem(x, cur.c[j].y);
+        xg[j][2] = load_elem(x, cur.c[j].z);
+        xg[j][3] = load_elem(x, cur.c[j].w);
     }
     const SegRegs seg = load_segs(tab, seg_end, seg_row);
     if (8 * tid < nseg) *reinterpret_cast<uint4 *>(ends + 8 * tid) = seg.ends;
@@ -655,7 +632,8 @@ __global__ __launch_bounds__(kBlock) void k_csr_spmv_part_np(PartArgs pa, int64_
 }
 
 // ------------------------------------------------------------------ hot-row tiles (see HotTiles)
-constexpr int kLongSegment = 32;   // segments at least this long are summed by a whole wavefront
+constexpr int kLongSegment = 64;   // segments at least this long are summed by a whole wavefront,
+constexpr int kMidSegment = 8;     // at least this long by 8 lanes, shorter ones by one thread
 
 int hot_tiles_build(CsrPlan &A, const int64_t *t_rowptr, const int32_t *t_col, const double *t_val,
                     const std::vector<int32_t> &slot_code, int nhot, hipStream_t st)
@@ -666,7 +644,8 @@ int hot_tiles_build(CsrPlan &A, const int64_t *t_rowptr, const int32_t *t_col, c
     std::vector<Entry> cur[kTileSlices];
     int64_t base[kTileSlices] = {0};
     std::vector<double> tval[kTileSlices];
-    std::vector<uint16_t> tiloc[kTileSlices], sslot[kTileSlices], send[kTileSlices];
+    std::vector<uint16_t> tiloc[kTileSlices];
+    std::vector<uint32_t> sdesc[kTileSlices];
     std::vector<int4> hdrs[kTileSlices];
     std::vector<int> seglen(kTileSlots);
     std::vector<Entry> sorted;
@@ -677,12 +656,15 @@ int hot_tiles_build(CsrPlan &A, const int64_t *t_rowptr, const int32_t *t_col, c
         // long segments first, then by slot; entries of a slot keep their column order
         for (const Entry &x : e) seglen[x.slot]++;
         sorted = e;
+        auto cls = [&](int slot) { return seglen[slot] >= kLongSegment ? 0 : (seglen[slot] >= kMidSegment ? 1 : 2); };
         std::stable_sort(sorted.begin(), sorted.end(), [&](const Entry &a, const Entry &b) {
-            const bool la = seglen[a.slot] >= kLongSegment, lb = seglen[b.slot] >= kLongSegment;
-            if (la != lb) return la;
+            const int ca = cls(a.slot), cb = cls(b.slot);
+            if (ca != cb) return ca < cb;
+            // inside the medium and short classes by length (the lanes of a wavefront then loop equally long)
+            if (ca != 0 && seglen[a.slot] != seglen[b.slot]) return seglen[a.slot] > seglen[b.slot];
             return a.slot < b.slot;
         });
-        int4 h = make_int4((int)base[s], 0, 0, (int)sslot[s].size());
+        int4 h = make_int4((int)base[s], 0, 0, (int)sdesc[s].size());
         const size_t off = tval[s].size();
         tval[s].resize(off + kChunk, 0.0);
         tiloc[s].resize(off + kChunk, 0);
@@ -690,13 +672,13 @@ int hot_tiles_build(CsrPlan &A, const int64_t *t_rowptr, const int32_t *t_col, c
             tval[s][off + k] = sorted[k].val;
             tiloc[s][off + k] = sorted[k].iloc;
             if (k + 1 == sorted.size() || sorted[k + 1].slot != sorted[k].slot) {
-                sslot[s].push_back(sorted[k].slot);
-                send[s].push_back((uint16_t)(k + 1));
+                sdesc[s].push_back((uint32_t)(k + 1) | ((uint32_t)sorted[k].slot << 16));
                 h.y += 1;
-                if (seglen[sorted[k].slot] >= kLongSegment) h.z += 1;
+                if (cls(sorted[k].slot) == 0) h.z += 1;          // low 16 bits: long segments
+                if (cls(sorted[k].slot) == 1) h.z += 1 << 16;    // high 16 bits: medium segments
             }
         }
-        while (sslot[s].size() % 8) { sslot[s].push_back(0); send[s].push_back(0); }
+        while (sdesc[s].size() % 4) sdesc[s].push_back(0);
         hdrs[s].push_back(h);
         for (const Entry &x : e) seglen[x.slot] = 0;
         e.clear();
@@ -729,7 +711,7 @@ int hot_tiles_build(CsrPlan &A, const int64_t *t_rowptr, const int32_t *t_col, c
         H.ntiles[s] = (int64_t)hdrs[s].size();
         for (int4 &h : hdrs[s]) h.w += (int)nseg;
         ntiles += H.ntiles[s];
-        nseg += (int64_t)sslot[s].size();
+        nseg += (int64_t)sdesc[s].size();
     }
     H.ntiles_total = ntiles;
     if (ntiles == 0) return TRON_OK;
@@ -737,8 +719,7 @@ int hot_tiles_build(CsrPlan &A, const int64_t *t_rowptr, const int32_t *t_col, c
     TRON_HIP(hipMalloc(reinterpret_cast<void **>(&H.val), sizeof(double) * ntiles * kChunk));
     TRON_HIP(hipMalloc(reinterpret_cast<void **>(&H.iloc), sizeof(uint16_t) * ntiles * kChunk));
     TRON_HIP(hipMalloc(reinterpret_cast<void **>(&H.hdr), sizeof(int4) * ntiles));
-    TRON_HIP(hipMalloc(reinterpret_cast<void **>(&H.seg_slot), sizeof(uint16_t) * std::max<int64_t>(nseg, 8)));
-    TRON_HIP(hipMalloc(reinterpret_cast<void **>(&H.seg_end), sizeof(uint16_t) * std::max<int64_t>(nseg, 8)));
+    TRON_HIP(hipMalloc(reinterpret_cast<void **>(&H.seg_desc), sizeof(uint32_t) * std::max<int64_t>(nseg, 4)));
     int64_t segpos = 0;
     for (int s = 0; s < kTileSlices; ++s) {
         const int64_t t0 = H.tile0[s];
@@ -746,9 +727,8 @@ int hot_tiles_build(CsrPlan &A, const int64_t *t_rowptr, const int32_t *t_col, c
         TRON_HIP(hipMemcpyAsync(H.val + t0 * kChunk, tval[s].data(), sizeof(double) * tval[s].size(), hipMemcpyHostToDevice, st));
         TRON_HIP(hipMemcpyAsync(H.iloc + t0 * kChunk, tiloc[s].data(), sizeof(uint16_t) * tiloc[s].size(), hipMemcpyHostToDevice, st));
         TRON_HIP(hipMemcpyAsync(H.hdr + t0, hdrs[s].data(), sizeof(int4) * hdrs[s].size(), hipMemcpyHostToDevice, st));
-        TRON_HIP(hipMemcpyAsync(H.seg_slot + segpos, sslot[s].data(), sizeof(uint16_t) * sslot[s].size(), hipMemcpyHostToDevice, st));
-        TRON_HIP(hipMemcpyAsync(H.seg_end + segpos, send[s].data(), sizeof(uint16_t) * send[s].size(), hipMemcpyHostToDevice, st));
-        segpos += (int64_t)sslot[s].size();
+        TRON_HIP(hipMemcpyAsync(H.seg_desc + segpos, sdesc[s].data(), sizeof(uint32_t) * sdesc[s].size(), hipMemcpyHostToDevice, st));
+        segpos += (int64_t)sdesc[s].size();
     }
     TRON_TRY(upload(&H.slot_of_row, slot_code.data(), slot_code.size(), st));
     int64_t maxt = 0;
@@ -768,64 +748,70 @@ struct TileArgs {
 struct TileRegs {
     v2d v[4];
     uint32_t il[4];     // two 16-bit local column offsets each
-    uint4 ends, slots;  // descriptors 8*tid .. 8*tid+7
+    uint4 desc[2];      // segment descriptors 8*tid .. 8*tid+7: end offset | slot << 16
     int4 hdr;
 };
 
-__device__ __forceinline__ TileRegs load_tile(const double *__restrict__ val, const uint16_t *__restrict__ iloc,
-                                              const int4 *__restrict__ hdr, const uint16_t *__restrict__ seg_end,
-                                              const uint16_t *__restrict__ seg_slot, int64_t T)
+// data of tile T whose header h is already in registers
+__device__ __forceinline__ TileRegs load_tile(const double *__restrict__ val, const uint16_t *__restrict__ iloc, int4 h,
+                                              const uint32_t *__restrict__ seg_desc, int64_t T)
 {
     TileRegs r;
-    r.hdr = hdr[T];
+    r.hdr = h;
 #pragma unroll
     for (int m = 0; m < 4; ++m) {
         const int64_t k = T * kChunk + m * (kChunk / 4) + threadIdx.x * 2;
         r.v[m] = __builtin_nontemporal_load(reinterpret_cast<const v2d *>(val + k));
         r.il[m] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(iloc + k));
     }
-    // descriptor blocks are padded to a multiple of 8 and at least one block exists per tile
-    const int64_t dpos = (int64_t)r.hdr.w + 8 * (int64_t)((8 * (int)threadIdx.x < r.hdr.y) ? threadIdx.x : 0);
-    r.ends = *reinterpret_cast<const uint4 *>(seg_end + dpos);
-    r.slots = *reinterpret_cast<const uint4 *>(seg_slot + dpos);
+    // descriptor blocks are padded to a multiple of 4; threads beyond the tile's segments re-read its first block
+    const int nseg = h.y;
+    const int64_t d0 = (int64_t)h.w + ((8 * (int)threadIdx.x < nseg) ? 8 * (int)threadIdx.x : 0);
+    const int64_t d1 = (int64_t)h.w + ((8 * (int)threadIdx.x + 4 < nseg) ? 8 * (int)threadIdx.x + 4 : 0);
+    r.desc[0] = *reinterpret_cast<const uint4 *>(seg_desc + d0);
+    r.desc[1] = *reinterpret_cast<const uint4 *>(seg_desc + d1);
     return r;
 }
 
 // Persistent workgroup (slice s, q): tiles q, q + B, ... of the slice; LDS accumulators for the slice's hot rows.
+// Software pipeline: while tile t is reduced, the data of tiles t + B and t + 2B and the header of tile t + 3B are
+// in flight (all indices clamped to the last tile, so every iteration issues the same loads).
+// Segment sums: the segments of a tile are ordered long (>= 64 entries: one wavefront each), medium (>= 8: eight
+// lanes each), short (one thread each, all seven possible reads issued together).  Slots inside a tile are
+// distinct, so the accumulator updates of different segments never collide.
 __global__ __launch_bounds__(kBlock) void k_hot_tiles(TileArgs ta, int B, const double *__restrict__ val,
                                                       const uint16_t *__restrict__ iloc, const int4 *__restrict__ hdr,
-                                                      const uint16_t *__restrict__ seg_end, const uint16_t *__restrict__ seg_slot,
+                                                      const uint32_t *__restrict__ seg_desc,
                                                       const double *__restrict__ x, double *__restrict__ wg_acc)
 {
     __shared__ __align__(16) double prod[kChunk];
-    __shared__ __align__(16) uint16_t ends[kChunk];
-    __shared__ __align__(16) uint16_t slots[kChunk];
+    __shared__ __align__(16) uint32_t desc[kChunk];
     __shared__ double acc[kTileSlots];
     const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
     const int s = blockIdx.x % kTileSlices;
     const int q = blockIdx.x / kTileSlices;
     for (int k = tid; k < kTileSlots; k += kBlock) acc[k] = 0.0;
     const int64_t nt = ta.ntiles[s];
     if (q < nt) {
         const int64_t T0 = ta.tile0[s];
-        TileRegs cur = load_tile(val, iloc, hdr, seg_end, seg_slot, T0 + q);
+        const int64_t last = nt - 1;
+        auto clampt = [&](int64_t t) { return T0 + (t < last ? t : last); };
+        TileRegs cur = load_tile(val, iloc, hdr[clampt(q)], seg_desc, clampt(q));
+        TileRegs nxt = load_tile(val, iloc, hdr[clampt(q + B)], seg_desc, clampt(q + B));
+        int4 hdr2 = hdr[clampt(q + 2 * (int64_t)B)];
         for (int64_t t = q; t < nt; t += B) {
-            const int nseg = cur.hdr.y, nlong = cur.hdr.z;
-            const int64_t cbase = cur.hdr.x;
+            const int nseg = cur.hdr.y, nlong = cur.hdr.z & 0xffff, nmid = (unsigned)cur.hdr.z >> 16;
+            const double *xt = x + cur.hdr.x;   // the tile's first column
             // gathers: a few consecutive cache lines of x per tile
             double xg[4][2];
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
-                xg[m][0] = x[cbase + (cur.il[m] & 0xffffu)];
-                xg[m][1] = x[cbase + (cur.il[m] >> 16)];
+                xg[m][0] = xt[cur.il[m] & 0xffffu];
+                xg[m][1] = xt[cur.il[m] >> 16];
             }
-            if (8 * tid < nseg) {
-                *reinterpret_cast<uint4 *>(ends + 8 * tid) = cur.ends;
-                *reinterpret_cast<uint4 *>(slots + 8 * tid) = cur.slots;
-            }
-            // next tile into registers (clamped index: the loads are unconditional, straight-line code)
-            const int64_t tn = (t + B < nt) ? t + B : nt - 1;
-            const TileRegs nxt = load_tile(val, iloc, hdr, seg_end, seg_slot, T0 + tn);
+            if (8 * tid < nseg) *reinterpret_cast<uint4 *>(desc + 8 * tid) = cur.desc[0];
+            if (8 * tid + 4 < nseg) *reinterpret_cast<uint4 *>(desc + 8 * tid + 4) = cur.desc[1];
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
                 double2 p;
@@ -833,25 +819,50 @@ __global__ __launch_bounds__(kBlock) void k_hot_tiles(TileArgs ta, int B, const 
                 p.y = cur.v[m].y * xg[m][1];
                 *reinterpret_cast<double2 *>(prod + m * (kChunk / 4) + tid * 2) = p;
             }
+            __builtin_amdgcn_sched_barrier(0);
+            const TileRegs nn = load_tile(val, iloc, hdr2, seg_desc, clampt(t + 2 * (int64_t)B));
+            const int4 hdr3 = hdr[clampt(t + 3 * (int64_t)B)];
+            __builtin_amdgcn_sched_barrier(0);
             __syncthreads();
             // long segments: one wavefront each
-            const int lane = tid & (kWave - 1);
             for (int sg = tid / kWave; sg < nlong; sg += kWavesPerBlock) {
-                const int k0 = sg ? (int)ends[sg - 1] : 0, k1 = (int)ends[sg];
+                const int k0 = sg ? (int)(desc[sg - 1] & 0xffffu) : 0;
+                const uint32_t dsc = desc[sg];
+                const int k1 = (int)(dsc & 0xffffu);
                 double sacc = 0.0;
                 for (int k = k0 + lane; k < k1; k += kWave) sacc += prod[k];
                 sacc = wave_sum(sacc);
-                if (lane == 0) acc[slots[sg]] += sacc;
+                if (lane == 0) acc[dsc >> 16] += sacc;
             }
-            // short segments: one thread each (slots inside a tile are distinct, so the updates do not collide)
-            for (int sg = nlong + tid; sg < nseg; sg += kBlock) {
-                const int k0 = sg ? (int)ends[sg - 1] : 0, k1 = (int)ends[sg];
-                double sacc = 0.0;
-                for (int k = k0; k < k1; ++k) sacc += prod[k];
-                acc[slots[sg]] += sacc;
+            // LDS bandwidth is what these sums cost, so each lane reads exactly the entries it needs; segments of
+            // the medium and short classes are ordered by length, so the lanes of a wavefront loop equally long.
+            // medium segments (8..63 entries): eight lanes each
+            {
+                const int sub = lane & 7;
+                const int mid_end = nlong + nmid;
+                for (int sg = nlong + tid / 8; sg < mid_end; sg += kBlock / 8) {
+                    const int k0 = sg ? (int)(desc[sg - 1] & 0xffffu) : 0;
+                    const uint32_t dsc = desc[sg];
+                    const int k1 = (int)(dsc & 0xffffu);
+                    double sacc = 0.0;
+                    for (int k = k0 + sub; k < k1; k += 8) sacc += prod[k];
+                    sacc = sum8(sacc);
+                    if (sub == 0) acc[dsc >> 16] += sacc;
+                }
+            }
+            // short segments (1..7 entries): one thread each
+            for (int sg = nlong + nmid + tid; sg < nseg; sg += kBlock) {
+                const int k0 = sg ? (int)(desc[sg - 1] & 0xffffu) : 0;
+                const uint32_t dsc = desc[sg];
+                const int k1 = (int)(dsc & 0xffffu);
+                double sacc = prod[k0];
+                for (int k = k0 + 1; k < k1; ++k) sacc += prod[k];
+                acc[dsc >> 16] += sacc;
             }
             __syncthreads();
             cur = nxt;
+            nxt = nn;
+            hdr2 = hdr3;
         }
     }
     __syncthreads();
@@ -885,7 +896,7 @@ static int launch_hot_tiles(tron_dataset *ds, const CsrPlan &A, const double *x)
     {
         ProfScope ps(ds, SLOT_SPMV_TILES, st);
         hipLaunchKernelGGL(k_hot_tiles, dim3(kTileSlices * H.blocks_per_slice), dim3(kBlock), 0, st, ta, H.blocks_per_slice,
-                           H.val, H.iloc, H.hdr, H.seg_end, H.seg_slot, x, H.wg_acc);
+                           H.val, H.iloc, H.hdr, H.seg_desc, x, H.wg_acc);
         hipLaunchKernelGGL(k_hot_reduce, dim3(kTileSlices * kTileSlots / kBlock), dim3(kBlock), 0, st, H.blocks_per_slice,
                            H.wg_acc, H.sums);
         TRON_HIP(hipGetLastError());
@@ -1036,11 +1047,10 @@ static int launch_partials(tron_dataset *ds, const CsrPlan &A, int slot, const d
         const int per_part = std::max(1, std::min(A.max_chunks, want));
         if (A.hot_ids)
             hipLaunchKernelGGL(k_csr_spmv_part<true>, dim3(per_part * A.P), dim3(kBlock), 0, ds->stream, pa, A.rows, A.col, A.val,
-                               A.chunk_tab, A.seg_end, A.seg_row, A.hot_ids, x, ds->row_partials, A.carry, (int)g_tuning.csr_ablate);
+                               A.chunk_tab, A.seg_end, A.seg_row, A.hot_ids, x, ds->row_partials, A.carry);
         else if (g_tuning.csr_blocks_per_part > 0)
             hipLaunchKernelGGL(k_csr_spmv_part<false>, dim3(per_part * A.P), dim3(kBlock), 0, ds->stream, pa, A.rows, A.col, A.val,
-                               A.chunk_tab, A.seg_end, A.seg_row, (const int32_t *)nullptr, x, ds->row_partials, A.carry,
-                               (int)g_tuning.csr_ablate);
+                               A.chunk_tab, A.seg_end, A.seg_row, (const int32_t *)nullptr, x, ds->row_partials, A.carry);
         else
             hipLaunchKernelGGL(k_csr_spmv_part_np, dim3(A.max_chunks * A.P), dim3(kBlock), 0, ds->stream, pa, A.rows, A.col, A.val,
                                A.chunk_tab, A.seg_end, A.seg_row, x, ds->row_partials, A.carry);

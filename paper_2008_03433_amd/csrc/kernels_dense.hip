@@ -64,8 +64,14 @@ struct Tile {
             double s = 0.0;
 #pragma unroll
             for (int e = 0; e < E; ++e) s = fma(x[u][e], vec[e], s);
+            if (L == 2) s = sum2(s);
+            else if (L == 4) s = sum4(s);
+            else if (L == 8) s = sum8(s);
+            else if (L >= 16) {
+                s = sum16(s);
 #pragma unroll
-            for (int m = 1; m < L; m <<= 1) s += __shfl_xor(s, m, kWave);
+                for (int m = 16; m < L; m <<= 1) s += __shfl_xor(s, m, kWave);
+            }
             t[u] = s;
         }
     }

@@ -110,6 +110,37 @@ def test_solve_partitioned_layout(force_partitions):
     compare_solves(p, p.loss, p.C, p.eps)
 
 
+def test_solve_url_shape_scaled(force_partitions):
+    # url-shaped workload: per-call parity is 1e-10, but CG amplifies rounding on this matrix (the oracle's own
+    # plain-fp64 twin departs from it by ~1e-5 in f at eps = 0.01, see tests/test_oracle_pins.py), so solve-level
+    # parity is: same history while the histories agree, both end within the strong-convexity bound, and the
+    # objectives agree to 1e-8 once eps is tight.
+    import paper_2008_03433_amd as tron
+    from oracle import Oracle
+    torch = torch_mod()
+    p = dg.config3(scale=0.1)
+    o = Oracle.from_problem(p)
+    ds = tron.Dataset.from_problem(p)
+    try:
+        for eps in (1e-2, 1e-6):
+            ref = o.tron(p.loss, p.C, eps)
+            w = torch.zeros(p.d, dtype=torch.float64, device="cuda")
+            res = ds.solve(p.loss, p.C, eps, w)
+            assert res.converged and ref.converged
+            assert abs(res.gnorm0 - ref.gnorm0) <= 1e-10 * ref.gnorm0
+            for a, b in list(zip(res.trace, ref.trace))[:3]:
+                assert (a["cg_iters"], a["accepted"]) == (b["cg_iters"], b["accepted"])
+                assert abs(a["f"] - b["f"]) <= 1e-8 * abs(b["f"])
+            assert abs(res.f - ref.f) <= 0.5 * (eps * ref.gnorm0) ** 2
+            f_chk, g_chk, _ = o.fun_grad(p.loss, p.C, w.cpu().numpy())
+            assert abs(f_chk - res.f) <= 1e-10 * abs(f_chk)
+            assert np.linalg.norm(g_chk) <= eps * ref.gnorm0 * (1 + 1e-9)
+            if eps == 1e-6:
+                assert abs(res.f - ref.f) <= 1e-8 * abs(ref.f)
+    finally:
+        ds.close()
+
+
 def test_csr_url_shape_partitioned(rng):
     # large enough that the automatic choice partitions both orientations
     p = dg.config3(scale=0.1)
@@ -253,13 +284,32 @@ def test_solve_config2():
 
 
 def test_solve_config2_svm_loss():
-    # Off-config stress: H = I + X^T X has a well separated top eigenvalue (~2e3, the Zipf head feature),
-    # so CG iterates are sensitive to rounding (plain-fp64 numpy CG departs from the long-double oracle by
-    # ~4e-7 in s after 10 iterations, ~2e-5 in f by the second outer iteration).  The iterates along the
-    # way are compared at 1e-4, the final
-    # objective still at 1e-8.
+    # Off-config stress: H = I + X^T X has a well separated top eigenvalue (~2e3, the Zipf head feature), so CG
+    # iterates are sensitive to rounding (plain-fp64 numpy CG departs from the long-double oracle by ~4e-7 in s
+    # after 10 iterations, ~2e-5 in f by the second outer iteration, and a CG stopping test can flip).  So at
+    # eps = 1e-3 only what the mathematics fixes is compared -- the first outer iteration, convergence, and the
+    # objectives to 1e-6 -- and at eps = 1e-8, where both sit on the minimiser, the objectives to 1e-8.
+    import paper_2008_03433_amd as tron
+    from oracle import Oracle
+    torch = torch_mod()
     p = dg.config2()
-    compare_solves(p, LOSS_L2SVM, 0.5, 1e-3, trace_rel=1e-4)
+    o = Oracle.from_problem(p)
+    ds = tron.Dataset.from_problem(p)
+    try:
+        for eps, tol in ((1e-3, 1e-6), (1e-8, 1e-8)):
+            ref = o.tron(LOSS_L2SVM, 0.5, eps)
+            w = torch.zeros(p.d, dtype=torch.float64, device="cuda")
+            res = ds.solve(LOSS_L2SVM, 0.5, eps, w)
+            assert res.converged and ref.converged
+            a, b = res.trace[0], ref.trace[0]
+            assert (a["cg_iters"], a["accepted"]) == (b["cg_iters"], b["accepted"])
+            assert abs(a["f"] - b["f"]) <= 1e-5 * abs(b["f"])
+            assert abs(res.f - ref.f) <= tol * abs(ref.f)
+            f_chk, g_chk, _ = o.fun_grad(LOSS_L2SVM, 0.5, w.cpu().numpy())
+            assert abs(f_chk - res.f) <= 1e-10 * abs(f_chk)
+            assert np.linalg.norm(g_chk) <= eps * ref.gnorm0 * (1 + 1e-9)
+    finally:
+        ds.close()
 
 
 def test_solve_config4_reduced():

@@ -405,3 +405,31 @@ def test_tron_respects_iteration_cap(rng):
     X, y = _dense_problem(rng, n, d)
     res = Oracle(n=n, d=d, y=y, X=X).tron(LOSS_LR, 10.0, 1e-12, max_outer=2)
     assert res.status == 1 and not res.converged and res.outer_iters == 2
+
+
+# ----------------------------------------------------------------------------
+# how much of a trajectory does the arithmetic fix?  (oracle vs its plain-fp64 twin)
+# ----------------------------------------------------------------------------
+def test_rounding_alone_moves_the_eps_0p01_iterate_on_zipf_data():
+    """The same source compiled with fp64 instead of long-double accumulators is a second, equally valid
+    implementation.  On the url-shaped workload (well separated top Hessian eigenvalue from the Zipf head
+    feature) the two agree call by call and for the first outer iterations, then CG amplifies the 1e-16
+    differences: the eps = 0.01 iterates differ by ~1e-5 in f.  Both are eps-solutions; with a tight eps both
+    reach the same minimiser.  This is why solve-level parity on that workload is stated at eps = 1e-6."""
+    import datagen as dg
+    p = dg.config3(0.05)
+    a = Oracle.from_problem(p)
+    b = Oracle.from_problem(p, plain_fp64=True)
+    w = 0.5 * np.random.default_rng(3).standard_normal(p.d)
+    fa, ga, Da = a.fun_grad(LOSS_LR, 1.0, w)
+    fb, gb, Db = b.fun_grad(LOSS_LR, 1.0, w)
+    assert abs(fa - fb) <= 1e-12 * abs(fa)
+    assert np.linalg.norm(ga - gb) <= 1e-12 * np.linalg.norm(ga)
+    ra, rb = a.tron(LOSS_LR, 1.0, 1e-2), b.tron(LOSS_LR, 1.0, 1e-2)
+    assert ra.converged and rb.converged and ra.outer_iters == rb.outer_iters
+    early = [abs(x["f"] - y["f"]) / abs(x["f"]) for x, y in zip(ra.trace[:3], rb.trace[:3])]
+    assert max(early) <= 1e-9
+    # both satisfy the stopping rule; their objectives are within the strong-convexity bound of each other
+    assert abs(ra.f - rb.f) <= 0.5 * (1e-2 * ra.gnorm0) ** 2
+    ta, tb = a.tron(LOSS_LR, 1.0, 1e-6), b.tron(LOSS_LR, 1.0, 1e-6)
+    assert abs(ta.f - tb.f) <= 1e-8 * abs(ta.f)
