@@ -224,7 +224,7 @@ int tron_dataset_create_csr(int64_t n, int64_t d, const int64_t *rowptr, const i
     // count -> slice r % 8, slot r / 8) leave the transposed CSR copy and are stored as tiles instead.
     std::vector<int32_t> slot_code;
     int nhot = 0;
-    const bool partitioned = g_tuning.csr_parts == kMaxParts ||
+    const bool partitioned = g_tuning.csr_parts == kColParts ||
                              (g_tuning.csr_parts == 0 && n * (int64_t)sizeof(double) > (3 << 19) && nnz >= (1 << 22));
     if (g_tuning.csr_tiles && partitioned) {
         std::vector<std::pair<int64_t, int32_t>> cand;
@@ -265,12 +265,12 @@ int tron_dataset_create_csr(int64_t n, int64_t d, const int64_t *rowptr, const i
     ds->n = n; ds->d = d; ds->dense = false; ds->stream = reinterpret_cast<hipStream_t>(hip_stream);
     int rc = alloc_common(ds);
     if (rc >= 0) rc = csr_plan_build(ds->fwd, n, d, h_rowptr.data(), h_col.data(), h_val.data(), (int)g_tuning.csr_parts, g_tuning.csr_hot != 0, ds->stream);
-    if (rc >= 0) rc = csr_plan_build(ds->bwd, d, n, t_rowptr.data(), t_col.data(), t_val.data(), partitioned ? kMaxParts : 1, false, ds->stream);
+    if (rc >= 0) rc = csr_plan_build(ds->bwd, d, n, t_rowptr.data(), t_col.data(), t_val.data(), partitioned ? kColParts : 1, false, ds->stream);
     if (rc >= 0 && nhot) rc = hot_tiles_build(ds->bwd, h_rowptr.data(), h_col.data(), h_val.data(), slot_code, nhot, ds->stream);
     if (rc >= 0) {
         int64_t need = 0;
-        if (ds->fwd.P > 1) need = std::max<int64_t>(need, (int64_t)ds->fwd.P * n);
-        if (ds->bwd.P > 1) need = std::max<int64_t>(need, (int64_t)ds->bwd.P * d);
+        if (ds->fwd.P > 1) need = std::max<int64_t>(need, (int64_t)kMaxParts * n);
+        if (ds->bwd.P > 1) need = std::max<int64_t>(need, (int64_t)kMaxParts * d);
         if (need > 0) {
             hipError_t e = hipMalloc(reinterpret_cast<void **>(&ds->row_partials), sizeof(double) * need);
             if (e != hipSuccess) rc = hip_fail(e, "allocate row partials", __FILE__, __LINE__);
@@ -451,7 +451,7 @@ int tron_probe_read_bandwidth(const double *src_dev, int64_t count, int reps, vo
 
 int tron_tuning_set(const char *name, int64_t value)
 {
-    if (name && strcmp(name, "csr_parts") == 0 && (value == 0 || value == 1 || value == kMaxParts)) {
+    if (name && strcmp(name, "csr_parts") == 0 && (value == 0 || value == 1 || value == kColParts)) {
         g_tuning.csr_parts = value;
         return TRON_OK;
     }
@@ -461,6 +461,10 @@ int tron_tuning_set(const char *name, int64_t value)
     }
     if (name && strcmp(name, "csr_hot_blocks_per_part") == 0 && value >= 1 && value <= 4096) {
         g_tuning.csr_hot_blocks_per_part = value;
+        return TRON_OK;
+    }
+    if (name && strcmp(name, "csr_head") == 0 && (value == 0 || value == 1)) {
+        g_tuning.csr_head = value;
         return TRON_OK;
     }
     if (name && strcmp(name, "csr_tiles") == 0 && (value == 0 || value == 1)) {

@@ -31,6 +31,7 @@ int hip_fail(hipError_t e, const char *what, const char *file, int line);
 struct Tuning {
     int64_t csr_parts = 0;   // column partitions of the CSR layouts: 0 = automatic, 1 = never, 8 = always
     int64_t csr_hot = 1;     // LDS table of frequent columns for the partitioned forward layout (0 = off)
+    int64_t csr_head = 1;    // head partition for the matrix' most frequent columns (needs csr_hot; 0 = off)
     int64_t csr_hot_blocks_per_part = 96;  // persistent workgroups per partition when the LDS table is used
     int64_t csr_blocks_per_part = 0;       // without the table: 0 = one chunk per workgroup, > 0 = persistent workgroups per partition
     int64_t csr_tiles = 1;   // hot-row tiles for the transposed orientation of partitioned matrices (0 = off)
@@ -98,7 +99,8 @@ struct Profiler {
 // row ids, and per chunk a 16-bit end offset per segment.  Partitions produce partial row sums
 // (partial[x*rows + r], written only where row r has entries in range x -- see row_mask); a combine
 // kernel adds them in a fixed order and applies the epilogue.
-constexpr int kMaxParts = 8;
+constexpr int kColParts = 8;            // column ranges, one per XCD
+constexpr int kMaxParts = kColParts + 1;   // + the head partition (see CsrPlan::head)
 constexpr int kHotSlots = 4096;   // LDS table entries per workgroup (32 KiB)
 
 // Hot-row tiles of the transposed product  out[j] += sum_i val * x[i]  (j = row of the plan, i = column).
@@ -120,10 +122,9 @@ struct HotTiles {
     int blocks_per_slice = 0;            // persistent workgroups per slice
     double *val = nullptr;               // device, ntiles_total * kChunk (zero padded)
     uint16_t *iloc = nullptr;            // device, ntiles_total * kChunk: column minus the tile's first column
-    int4 *hdr = nullptr;                 // device, per tile: {first column, segments, long | medium << 16 segment counts,
-                                         //   index into seg_desc}
-    uint32_t *seg_desc = nullptr;        // device: per segment, end offset inside its tile | slot << 16; the segments of a
-                                         //   tile are ordered long, medium, short
+    uint8_t *flags = nullptr;            // device, ntiles_total * 256: bit e of byte t = entry 8t + e of the tile is the last of its segment
+    int4 *hdr = nullptr;                 // device, per tile: {first column, segments, unused, index into seg_slot}
+    uint16_t *seg_slot = nullptr;        // device: slot of every segment, tile by tile (a tile's block starts at a multiple of 8)
     int32_t *slot_of_row = nullptr;      // device, rows: slice * kTileSlots + slot, or -1
     double *wg_acc = nullptr;            // device, kTileSlices * blocks_per_slice * kTileSlots workgroup accumulators
     double *sums = nullptr;              // device, kTileSlices * kTileSlots: per hot row, sum over its tiles
@@ -133,8 +134,11 @@ struct HotTiles {
 struct CsrPlan {
     int64_t rows = 0, cols = 0, nnz = 0;
     HotTiles hot;                        // optional (transposed orientation of large matrices)
-    int P = 1;                           // number of column partitions (1 = unpartitioned)
-    int32_t *col = nullptr;              // device, (padded) nnz; with an LDS table, hot columns are stored as ~slot
+    int P = 1;                           // number of column ranges (1 = unpartitioned)
+    int head = -1;                       // P, when partition P holds the entries of the matrix' most frequent columns
+                                         //   (whole rows, every entry served from one LDS table, 16-bit slots in col16); else -1
+    int32_t *col = nullptr;              // device, (padded) nnz of the ranges; with an LDS table, hot columns are stored as ~slot
+    uint16_t *col16 = nullptr;           // device, (padded) nnz of the head partition: LDS slot of each entry
     double *val = nullptr;               // device, (padded) nnz
     int nblocks = 0;                     // total number of chunks
     double *carry = nullptr;             // device, nblocks: sum of the part of a row entering chunk c from before
@@ -157,10 +161,10 @@ struct CsrPlan {
     int32_t *hot_ids = nullptr;          // device, P*kHotSlots column ids (null: no LDS table)
     int32_t *seg_row = nullptr;          // device: row id of every segment, partition-major, ascending inside a partition
     int4 *chunk_tab = nullptr;           // device, per chunk: {first owned segment (partition-relative), number of owned
-                                         //   segments, offset where the first owned segment starts, index into seg_end}
-    uint16_t *seg_end = nullptr;         // device: end offsets (chunk-relative, clipped to kChunk) of the owned segments of
-                                         //   each chunk; a chunk's block starts at a multiple of 8 entries
-    uint8_t *row_mask = nullptr;         // device, rows: bit x set iff the row has entries in partition x
+                                         //   segments, offset where the first owned segment starts, unused}
+    uint8_t *flags = nullptr;            // device, nblocks * 256: bit e of byte t of a chunk = its entry 8t + e is the last
+                                         //   entry of a row inside the chunk
+    uint16_t *row_mask = nullptr;        // device, rows: bit x set iff the row has entries in partition x
     void release();
 };
 

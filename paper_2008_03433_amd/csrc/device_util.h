@@ -50,6 +50,67 @@ __device__ __forceinline__ double group_sum(double v, int g)
     return (read_lane(v, 0) + read_lane(v, 16)) + (read_lane(v, 32) + read_lane(v, 48));
 }
 
+// ---- inclusive scans over the 64 lanes of a wavefront, through DPP (no LDS).
+// Steps: row_shr 1, 2, 4, 8 inside each row of 16 lanes, then row_bcast:15 into rows 1 and 3 (lane 15 of the row
+// before), then row_bcast:31 into rows 2 and 3.  A lane that has no source in a step keeps the identity it passes in.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_int(int v)
+{
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, ROW_MASK, 0xf, false);
+}
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_f64(double v)
+{
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, ROW_MASK, 0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, ROW_MASK, 0xf, false);
+    return __hiloint2double(hi, lo);
+}
+
+// c := c[0] + ... + c[lane]
+__device__ __forceinline__ int wave_scan_add(int c)
+{
+    c += dpp_int<0x111, 0xf>(c);
+    c += dpp_int<0x112, 0xf>(c);
+    c += dpp_int<0x114, 0xf>(c);
+    c += dpp_int<0x118, 0xf>(c);
+    c += dpp_int<0x142, 0xa>(c);
+    c += dpp_int<0x143, 0xc>(c);
+    return c;
+}
+
+// Segmented sum: every lane holds (t, h) = (sum of the open run at its end, whether a run ended inside it).
+// Afterwards t = t[lane] + the t of the lanes before it back to, and including, the nearest one with h set, and
+// h = whether any lane up to this one had h set.  The operator (ta,ha)+(tb,hb) = (hb ? tb : ta+tb, ha|hb) is
+// associative, so the tree order above applies.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ void seg_scan_step(double &t, int &h)
+{
+    const double st = dpp_f64<CTRL, ROW_MASK>(t);
+    const int sh = dpp_int<CTRL, ROW_MASK>(h);
+    t = h ? t : t + st;
+    h |= sh;
+}
+
+__device__ __forceinline__ void wave_seg_scan(double &t, int &h)
+{
+    seg_scan_step<0x111, 0xf>(t, h);
+    seg_scan_step<0x112, 0xf>(t, h);
+    seg_scan_step<0x114, 0xf>(t, h);
+    seg_scan_step<0x118, 0xf>(t, h);
+    seg_scan_step<0x142, 0xa>(t, h);
+    seg_scan_step<0x143, 0xc>(t, h);
+}
+
+// value of the lane before (lane 0 receives 0): wave_shr:1
+__device__ __forceinline__ double lane_before(double v)
+{
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), 0x138, 0xf, 0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), 0x138, 0xf, 0xf, false);
+    return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ int lane_before(int v) { return __builtin_amdgcn_update_dpp(0, v, 0x138, 0xf, 0xf, false); }
+
 // Sum over the workgroup (kBlock threads); valid in thread 0.  `lds` holds kWavesPerBlock doubles
 // and may be reused right after the call returns (the trailing barrier orders it).
 __device__ __forceinline__ double block_sum(double v, double *lds)

@@ -23,7 +23,9 @@
 namespace tron {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v2i __attribute__((ext_vector_type(2)));
 typedef double v2d __attribute__((ext_vector_type(2)));
+typedef unsigned int v2u __attribute__((ext_vector_type(2)));
 
 constexpr int64_t kGatherBytesForPartitioning = 3 << 19;  // 1.5 MiB: larger gather vectors get partitioned
 constexpr int64_t kMinNnzForPartitioning = 1 << 22;
@@ -31,7 +33,7 @@ constexpr int kHotMinCount = 8;   // columns with fewer entries are not worth an
 
 void HotTiles::release()
 {
-    hipFree(val); hipFree(iloc); hipFree(hdr); hipFree(seg_desc); hipFree(slot_of_row);
+    hipFree(val); hipFree(iloc); hipFree(flags); hipFree(hdr); hipFree(seg_slot); hipFree(slot_of_row);
     hipFree(wg_acc); hipFree(sums);
     *this = HotTiles();
 }
@@ -39,8 +41,8 @@ void HotTiles::release()
 void CsrPlan::release()
 {
     hot.release();
-    hipFree(rowptr); hipFree(col); hipFree(val); hipFree(row_lo); hipFree(carry);
-    hipFree(hot_ids); hipFree(seg_row); hipFree(chunk_tab); hipFree(seg_end); hipFree(row_mask);
+    hipFree(rowptr); hipFree(col); hipFree(col16); hipFree(val); hipFree(row_lo); hipFree(carry);
+    hipFree(hot_ids); hipFree(seg_row); hipFree(chunk_tab); hipFree(flags); hipFree(row_mask);
     hipFree(fix_row); hipFree(fix_part); hipFree(fix_b0); hipFree(fix_cnt);
     *this = CsrPlan();
 }
@@ -98,8 +100,8 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
     A.cols = cols;
     A.nnz = h_rowptr[rows];
     if (parts <= 0)
-        parts = (cols * (int64_t)sizeof(double) > kGatherBytesForPartitioning && A.nnz >= kMinNnzForPartitioning) ? kMaxParts : 1;
-    if (parts > kMaxParts) parts = kMaxParts;
+        parts = (cols * (int64_t)sizeof(double) > kGatherBytesForPartitioning && A.nnz >= kMinNnzForPartitioning) ? kColParts : 1;
+    if (parts > kColParts) parts = kColParts;
     A.P = parts;
     std::vector<int32_t> row_lo, fix_row, fix_part, fix_b0, fix_cnt;
 
@@ -115,35 +117,61 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
         TRON_TRY(upload(&A.val, h_val, (size_t)A.nnz, st));
     } else {
         const int P = A.P;
-        // column ranges with equal nonzero counts: bound[x] = first column of range x
         std::vector<int64_t> colcount((size_t)cols + 1, 0);
         for (int64_t k = 0; k < A.nnz; ++k) colcount[h_col[k] + 1]++;
+        // Head partition: the kHotSlots most frequent columns of the whole matrix, when they hold a good part of
+        // the nonzeros.  Their entries need no locality in L2 (one LDS table serves them all), so they are not
+        // split by column range: one segment per row instead of one per row and range.
+        std::vector<uint8_t> part_of((size_t)cols, 0);
+        std::vector<int32_t> slot_of, hot_ids;
+        std::vector<std::pair<int64_t, int32_t>> cand;
+        int64_t head_nnz = 0;
+        if (hot) {
+            slot_of.assign((size_t)cols, -1);
+            hot_ids.assign((size_t)(P + 1) * kHotSlots, 0);
+        }
+        if (hot && g_tuning.csr_head) {
+            for (int64_t j = 0; j < cols; ++j)
+                if (colcount[j + 1] >= kHotMinCount) cand.emplace_back(-colcount[j + 1], (int32_t)j);
+            const size_t keep = std::min<size_t>(cand.size(), kHotSlots);
+            std::partial_sort(cand.begin(), cand.begin() + keep, cand.end());
+            for (size_t k = 0; k < keep; ++k) head_nnz -= cand[k].first;
+            if (head_nnz * 4 >= A.nnz) {
+                A.head = P;
+                A.part_nhot[P] = (int)keep;
+                A.part_nnz[P] = head_nnz;
+                for (size_t k = 0; k < keep; ++k) {
+                    part_of[cand[k].second] = (uint8_t)P;
+                    slot_of[cand[k].second] = (int32_t)k;
+                    hot_ids[(size_t)P * kHotSlots + k] = cand[k].second;
+                    colcount[cand[k].second + 1] = 0;   // not counted in the ranges below
+                }
+            }
+        }
+        const int NP = (A.head >= 0) ? P + 1 : P;   // partitions in all
+        const int64_t range_nnz = A.nnz - ((A.head >= 0) ? head_nnz : 0);
+        // column ranges with equal nonzero counts (head columns excluded): bound[x] = first column of range x
         for (int64_t j = 0; j < cols; ++j) colcount[j + 1] += colcount[j];
         std::vector<int64_t> bound(P + 1, cols);
         bound[0] = 0;
         for (int x = 1; x < P; ++x) {
-            const int64_t target = A.nnz / P * x;
+            const int64_t target = range_nnz / P * x;
             bound[x] = std::lower_bound(colcount.begin(), colcount.end(), target) - colcount.begin();
             if (bound[x] > cols) bound[x] = cols;
             if (bound[x] < bound[x - 1]) bound[x] = bound[x - 1];
         }
-        std::vector<uint8_t> part_of((size_t)cols);
         for (int x = 0; x < P; ++x)
-            for (int64_t j = bound[x]; j < bound[x + 1]; ++j) part_of[j] = (uint8_t)x;
-        for (int x = 0; x < P; ++x) {
-            A.part_nnz[x] = colcount[bound[x + 1]] - colcount[bound[x]];
+            for (int64_t j = bound[x]; j < bound[x + 1]; ++j)
+                if (part_of[j] != P || A.head < 0) part_of[j] = (uint8_t)x;
+        for (int x = 0; x < P; ++x) A.part_nnz[x] = colcount[bound[x + 1]] - colcount[bound[x]];
+        for (int x = 0; x < NP; ++x)
             if (A.part_nnz[x] > 0x7ffffff0) { set_error("partition too large for 32-bit offsets"); return TRON_EINVAL; }
-        }
-        // LDS-resident columns: in each range the kHotSlots most frequent columns with at least kHotMinCount entries
-        std::vector<int32_t> slot_of, hot_ids;
+        // LDS-resident columns of a range: its kHotSlots most frequent columns with at least kHotMinCount entries
         if (hot) {
-            slot_of.assign((size_t)cols, -1);
-            hot_ids.assign((size_t)P * kHotSlots, 0);
-            std::vector<std::pair<int64_t, int32_t>> cand;
             for (int x = 0; x < P; ++x) {
                 cand.clear();
                 for (int64_t j = bound[x]; j < bound[x + 1]; ++j) {
-                    const int64_t cnt = colcount[j + 1] - colcount[j];
+                    const int64_t cnt = colcount[j + 1] - colcount[j];   // 0 for head columns
                     if (cnt >= kHotMinCount) cand.emplace_back(-cnt, (int32_t)j);
                 }
                 const size_t keep = std::min<size_t>(cand.size(), kHotSlots);
@@ -157,41 +185,41 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
         }
         std::vector<int64_t>().swap(colcount);
         // per-(partition,row) entry counts -> offsets; non-empty pairs are the segments
-        std::vector<int32_t> rp32((size_t)P * (rows + 1), 0);
+        std::vector<int32_t> rp32((size_t)NP * (rows + 1), 0);
         for (int64_t r = 0; r < rows; ++r)
             for (int64_t k = h_rowptr[r]; k < h_rowptr[r + 1]; ++k) rp32[(size_t)part_of[h_col[k]] * (rows + 1) + r + 1]++;
-        std::vector<uint8_t> mask((size_t)rows, 0);
+        std::vector<uint16_t> mask((size_t)rows, 0);
         int64_t pos = 0, nseg_total = 0;
         int chunk = 0;
         A.max_chunks = 0;
-        for (int x = 0; x < P; ++x) {
+        for (int x = 0; x < NP; ++x) {
             int32_t *rp = rp32.data() + (size_t)x * (rows + 1);
             int64_t nseg = 0;
             for (int64_t r = 0; r < rows; ++r) {
-                if (rp[r + 1] > 0) { mask[r] |= (uint8_t)(1u << x); ++nseg; }
+                if (rp[r + 1] > 0) { mask[r] |= (uint16_t)(1u << x); ++nseg; }
                 rp[r + 1] += rp[r];
             }
             A.part_base[x] = pos;
             A.part_seg0[x] = nseg_total;
             A.part_chunk0[x] = chunk;
             A.part_nchunks[x] = (int)std::max<int64_t>(1, (A.part_nnz[x] + kChunk - 1) / kChunk);
-            A.max_chunks = std::max(A.max_chunks, A.part_nchunks[x]);
+            if (x < P) A.max_chunks = std::max(A.max_chunks, A.part_nchunks[x]);
             chunk += A.part_nchunks[x];
             pos += (int64_t)A.part_nchunks[x] * kChunk;
             nseg_total += nseg;
         }
         A.nblocks = chunk;
-        if (nseg_total + 8 * (int64_t)chunk > 0x7ffffff0) { set_error("too many row segments for 32-bit indexing"); return TRON_EINVAL; }
+        if (nseg_total > 0x7ffffff0) { set_error("too many row segments for 32-bit indexing"); return TRON_EINVAL; }
         // entries partition-major; inside a row the entries of one range are contiguous and stay ordered
         std::vector<int32_t> pcol((size_t)pos, 0);
         std::vector<double> pval((size_t)pos, 0.0);
         {
-            std::vector<int64_t> cursor(P);
+            std::vector<int64_t> cursor(NP);
             for (int64_t r = 0; r < rows; ++r) {
-                for (int x = 0; x < P; ++x) cursor[x] = A.part_base[x] + rp32[(size_t)x * (rows + 1) + r];
+                for (int x = 0; x < NP; ++x) cursor[x] = A.part_base[x] + rp32[(size_t)x * (rows + 1) + r];
                 for (int64_t k = h_rowptr[r]; k < h_rowptr[r + 1]; ++k) {
                     const int64_t q = cursor[part_of[h_col[k]]]++;
-                    pcol[q] = (hot && slot_of[h_col[k]] >= 0) ? ~slot_of[h_col[k]] : h_col[k];
+                    pcol[q] = (hot && slot_of[h_col[k]] >= 0) ? ~slot_of[h_col[k]] : h_col[k];   // the head's become 16-bit slots below
                     pval[q] = h_val[k];
                 }
             }
@@ -199,33 +227,33 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
         // segment tables
         std::vector<int32_t> seg_row((size_t)std::max<int64_t>(nseg_total, 1));
         std::vector<int4> tab((size_t)chunk);
-        std::vector<uint16_t> seg_end;
-        seg_end.reserve((size_t)(nseg_total + 8 * (int64_t)chunk));
-        for (int x = 0; x < P; ++x) {
+        std::vector<uint8_t> flags((size_t)chunk * kBlock, 0);   // per chunk: one bit per entry, set on the last entry of a segment
+        for (int x = 0; x < NP; ++x) {
             const int32_t *rp = rp32.data() + (size_t)x * (rows + 1);
             const int nch = A.part_nchunks[x];
             // the segments of this partition, in row order, with start/end positions relative to the partition
             int64_t m = 0;               // segment counter (partition-relative)
             int c = 0;                   // chunk that owns the segments being emitted
-            int4 t = make_int4(0, 0, 0, (int)seg_end.size());
+            int4 t = make_int4(0, 0, 0, 0);
             auto close_chunk = [&](int next_first_seg, int64_t next_seg_start) {
                 tab[A.part_chunk0[x] + c] = t;
-                while (seg_end.size() % 8) seg_end.push_back(0);
                 ++c;
                 const int64_t cstart = (int64_t)c * kChunk;
                 const int64_t off = std::min<int64_t>(std::max<int64_t>(next_seg_start - cstart, 0), kChunk);
-                t = make_int4(next_first_seg, 0, (int)off, (int)seg_end.size());
+                t = make_int4(next_first_seg, 0, (int)off, 0);
             };
             for (int64_t r = 0; r < rows; ++r) {
                 const int64_t rs = rp[r], re = rp[r + 1];
                 if (re == rs) continue;
                 while (rs >= (int64_t)(c + 1) * kChunk) close_chunk((int)m, rs);   // this segment starts in a later chunk
                 seg_row[A.part_seg0[x] + m] = (int32_t)r;
-                const int64_t cstart = (int64_t)c * kChunk;
-                seg_end.push_back((uint16_t)std::min<int64_t>(re - cstart, kChunk));
                 t.y += 1;
-                // continuation chunks of a split row: fix-up list
+                // the row's piece in each chunk it touches ends with a flag; continuation chunks go to the fix-up list
                 const int c_last = (int)((re - 1) / kChunk);
+                for (int ck = c; ck <= c_last; ++ck) {
+                    const int64_t pe = std::min<int64_t>(re, (int64_t)(ck + 1) * kChunk) - 1 - (int64_t)ck * kChunk;
+                    flags[((size_t)A.part_chunk0[x] + ck) * kBlock + pe / 8] |= (uint8_t)(1u << (pe % 8));
+                }
                 if (c_last > c) {
                     fix_row.push_back((int32_t)r);
                     fix_part.push_back(x);
@@ -236,17 +264,25 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
             }
             while (c < nch - 1) close_chunk((int)m, (int64_t)A.part_nnz[x]);
             tab[A.part_chunk0[x] + c] = t;
-            while (seg_end.size() % 8) seg_end.push_back(0);
         }
         // first_off of a chunk inside or at the end of a split row: the chunk-relative end of that row
         // (set above from the start of the next segment; for chunks wholly inside one row that start lies
         // beyond the chunk and clips to kChunk, which is right)
         if (hot) TRON_TRY(upload(&A.hot_ids, hot_ids.data(), hot_ids.size(), st));
+        if (A.head >= 0) {
+            // the head partition is the last one: its columns go to col16, the ranges' stay in col
+            const size_t h0 = (size_t)A.part_base[A.head];
+            std::vector<uint16_t> c16(pcol.size() - h0, 0);
+            for (size_t k = h0; k < pcol.size(); ++k) c16[k - h0] = (uint16_t)(pcol[k] < 0 ? ~pcol[k] : 0);   // padding: slot 0, value 0
+            TRON_TRY(upload(&A.col16, c16.data(), c16.size(), st));
+            TRON_HIP(hipStreamSynchronize(st));
+            pcol.resize(h0);
+        }
         TRON_TRY(upload(&A.col, pcol.data(), pcol.size(), st));
         TRON_TRY(upload(&A.val, pval.data(), pval.size(), st));
         TRON_TRY(upload(&A.seg_row, seg_row.data(), seg_row.size(), st));
         TRON_TRY(upload(&A.chunk_tab, tab.data(), tab.size(), st));
-        TRON_TRY(upload(&A.seg_end, seg_end.data(), seg_end.size(), st));
+        TRON_TRY(upload(&A.flags, flags.data(), flags.size(), st));
         TRON_TRY(upload(&A.row_mask, mask.data(), mask.size(), st));
         TRON_HIP(hipStreamSynchronize(st));
     }
@@ -304,33 +340,27 @@ __device__ __forceinline__ void chunk_body(double *prod, const double *table, in
     const int tid = threadIdx.x;
     // ---- phase 1: products into LDS (two passes of 1024 nonzeros, 4 per thread per pass)
     if (end - start == kChunk) {
-        v4i c[2];
-        v2d v[2][2];
+        // thread t takes entries m*512 + 2t, m*512 + 2t + 1: every load instruction covers whole cache lines
+        v2i c[4];
+        v2d v[4];
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int64_t k = start + j * (kChunk / 2) + tid * 4;
-            c[j] = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(col + k));
-            v[j][0] = __builtin_nontemporal_load(reinterpret_cast<const v2d *>(val + k));
-            v[j][1] = __builtin_nontemporal_load(reinterpret_cast<const v2d *>(val + k + 2));
+        for (int m = 0; m < 4; ++m) {
+            const int64_t k = start + m * (kChunk / 4) + tid * 2;
+            c[m] = __builtin_nontemporal_load(reinterpret_cast<const v2i *>(col + k));
+            v[m] = __builtin_nontemporal_load(reinterpret_cast<const v2d *>(val + k));
         }
-        double xg[2][4];
+        double xg[4][2];
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            xg[j][0] = gather<HOT>(x, table, c[j].x);
-            xg[j][1] = gather<HOT>(x, table, c[j].y);
-            xg[j][2] = gather<HOT>(x, table, c[j].z);
-            xg[j][3] = gather<HOT>(x, table, c[j].w);
+        for (int m = 0; m < 4; ++m) {
+            xg[m][0] = gather<HOT>(x, table, c[m].x);
+            xg[m][1] = gather<HOT>(x, table, c[m].y);
         }
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            double2 p0, p1;
-            p0.x = v[j][0].x * xg[j][0];
-            p0.y = v[j][0].y * xg[j][1];
-            p1.x = v[j][1].x * xg[j][2];
-            p1.y = v[j][1].y * xg[j][3];
-            double2 *dst = reinterpret_cast<double2 *>(prod + j * (kChunk / 2) + tid * 4);
-            dst[0] = p0;
-            dst[1] = p1;
+        for (int m = 0; m < 4; ++m) {
+            double2 p;
+            p.x = v[m].x * xg[m][0];
+            p.y = v[m].y * xg[m][1];
+            *reinterpret_cast<double2 *>(prod + m * (kChunk / 4) + tid * 2) = p;
         }
     } else {
         for (int k = tid; k < kChunk; k += kBlock) {
@@ -409,151 +439,238 @@ struct PartArgs {
 // chunk is being reduced, so HBM latency is paid once per workgroup, not once per chunk.
 // With HOT the partition's most frequent columns are first copied from x into an LDS table; entries of those
 // columns are stored as ~slot and never touch the vector cache.
+// Stream registers of one chunk: thread t holds entries m*512 + 2t, m*512 + 2t + 1 (m = 0..3), so that every load
+// instruction of a wavefront covers whole consecutive cache lines (a wavefront that reads 16 of every 32 bytes is
+// served in 64-byte requests, twice as many, and the number of requests a CU keeps in flight is what bounds it).
+constexpr int kQuarter = kChunk / 4;
+
+template <bool HEAD>
 struct StreamRegs {
-    v4i c[2];
-    v2d v[2][2];
+    v2i c[4];
+    v2d v[4];
+};
+template <>
+struct StreamRegs<true> {
+    uint32_t c[4];   // two 16-bit LDS slots each
+    v2d v[4];
 };
 
-__device__ __forceinline__ StreamRegs load_stream(const int32_t *__restrict__ col, const double *__restrict__ val, int64_t start)
+template <bool HEAD>
+__device__ __forceinline__ StreamRegs<HEAD> load_stream(const void *__restrict__ col, const double *__restrict__ val, int64_t start)
 {
-    StreamRegs s;
+    StreamRegs<HEAD> s;
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int64_t k = start + j * (kChunk / 2) + threadIdx.x * 4;
-        s.c[j] = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(col + k));
-        s.v[j][0] = __builtin_nontemporal_load(reinterpret_cast<const v2d *>(val + k));
-        s.v[j][1] = __builtin_nontemporal_load(reinterpret_cast<const v2d *>(val + k + 2));
+    for (int m = 0; m < 4; ++m) {
+        const int64_t k = start + m * kQuarter + threadIdx.x * 2;
+        if constexpr (HEAD)
+            s.c[m] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(static_cast<const uint16_t *>(col) + k));
+        else
+            s.c[m] = __builtin_nontemporal_load(reinterpret_cast<const v2i *>(static_cast<const int32_t *>(col) + k));
+        s.v[m] = __builtin_nontemporal_load(reinterpret_cast<const v2d *>(val + k));
     }
     return s;
 }
 
-// lanes per segment: 256 / (number of segments) rounded down to a power of two, at most 64, at least 1
-__device__ __forceinline__ int lanes_per_segment(int nseg)
+// the two gathered vector entries of quarter m
+template <bool HOT, bool HEAD>
+__device__ __forceinline__ void gather2(const StreamRegs<HEAD> &r, int m, const double *__restrict__ x, const double *table, double *out)
 {
-    int g = 1;
-    while (g < kWave && nseg * (g * 2) <= kBlock) g *= 2;
-    return g;
+    if constexpr (HEAD) {
+        out[0] = table[r.c[m] & 0xffffu];
+        out[1] = table[r.c[m] >> 16];
+    } else {
+        out[0] = gather<HOT>(x, table, r.c[m].x);
+        out[1] = gather<HOT>(x, table, r.c[m].y);
+    }
 }
 
-constexpr int kSegPasses = kChunk / kBlock;   // a chunk owns at most kChunk segments: 8 passes of 256
+// ------------------------------------------------------------------ segment sums of a chunk
+// The entries of a chunk are in segment order (a segment = the entries of one row inside the chunk) and a flag bit
+// marks the last entry of every segment.  Products are written to LDS in load order and read back so that thread
+// t owns entries 8t .. 8t+7; the thread sums its own runs in registers, the open run at its end is carried to the
+// following threads by a segmented scan over the wavefront (DPP) and across the four wavefronts through LDS.
+// No loop depends on how long the segments are.
+//
+// LDS layout of the products: blocks of 8 entries padded to 10 doubles, so that the 128-bit reads of a wavefront
+// (80-byte lane stride) fall into distinct banks; the padding of the first four blocks holds the wavefront totals.
+constexpr int kProdDoubles = kChunk / 8 * 10;   // 2560 doubles = 20 KiB
+constexpr int kOutOffset = 40;                  // segment sums are parked at prod[kOutOffset ...] (behind the totals)
+constexpr int kSegPasses = kChunk / kBlock;     // a chunk holds at most kChunk segments: 8 passes of 256
+
+__device__ __forceinline__ int prod_pos(int e) { return e + 2 * (e >> 3); }
+
+// products of the chunk in `r` into LDS
+template <bool HOT, bool HEAD>
+__device__ __forceinline__ void products_to_lds(const StreamRegs<HEAD> &r, const double *__restrict__ x, const double *table, double *prod)
+{
+    double xg[4][2];
+#pragma unroll
+    for (int m = 0; m < 4; ++m) gather2<HOT, HEAD>(r, m, x, table, xg[m]);
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+        double2 p;
+        p.x = r.v[m].x * xg[m][0];
+        p.y = r.v[m].y * xg[m][1];
+        *reinterpret_cast<double2 *>(prod + prod_pos(m * kQuarter + threadIdx.x * 2)) = p;   // an even entry: the pair stays together
+    }
+}
+
+// Call after the barrier that follows the product writes.  f = the thread's 8 flag bits.
+// On return p[e] = sum of the thread's entries from the start of the run containing e up to e, cin = what the
+// entries before the thread add to its first run, idx0 = number of flags in the threads before it.
+// Contains one barrier; after it the product area may be overwritten (the totals at prod[8..39] may not).
+__device__ __forceinline__ void chunk_runs(double *prod, const unsigned f, double (&p)[8], double &cin, int &idx0)
+{
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    const double2 *src = reinterpret_cast<const double2 *>(prod + 10 * tid);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const double2 d = src[q];
+        p[2 * q] = d.x;
+        p[2 * q + 1] = d.y;
+    }
+    double run = 0.0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        run += p[e];
+        p[e] = run;
+        if ((f >> e) & 1u) run = 0.0;
+    }
+    const int cnt = __popc(f);
+    double t = run;
+    int h = (f != 0u);
+    wave_seg_scan(t, h);
+    const int ci = wave_scan_add(cnt);
+    const double ext = lane_before(t);
+    const int exh = lane_before(h);
+    if (lane == kWave - 1) {
+        prod[10 * wv + 8] = t;
+        *reinterpret_cast<int2 *>(prod + 10 * wv + 9) = make_int2(h, ci);
+    }
+    __syncthreads();
+    double ct = 0.0;
+    int cb = 0;
+#pragma unroll
+    for (int w = 0; w < kWavesPerBlock - 1; ++w) {
+        if (w < wv) {
+            const double wt = prod[10 * w + 8];
+            const int2 hc = *reinterpret_cast<const int2 *>(prod + 10 * w + 9);
+            ct = hc.x ? wt : ct + wt;
+            cb += hc.y;
+        }
+    }
+    cin = exh ? ext : ct + ext;
+    idx0 = cb + ci - cnt;
+}
 
 struct SegRegs {
-    uint4 ends;             // 8 x uint16 end offsets: segments 8*tid .. 8*tid+7 of the chunk
-    int rid[kSegPasses];    // row ids of the segments this thread writes: (tid / g) + 256 j
+    unsigned flags;         // bit e: entry 8*tid + e is the last of its segment
+    int rid[kSegPasses];    // row ids of the owned segments tid + 256 j
 };
 
-__device__ __forceinline__ SegRegs load_segs(const int4 tab, const uint16_t *__restrict__ seg_end,
+__device__ __forceinline__ SegRegs load_segs(const int4 tab, const uint8_t *__restrict__ flags /* of this chunk */,
                                              const int32_t *__restrict__ seg_row /* of this partition */)
 {
     SegRegs s;
+    s.flags = flags[threadIdx.x];
     const int nseg = tab.y;
-    s.ends = make_uint4(0, 0, 0, 0);
-    if (8 * (int)threadIdx.x < nseg) s.ends = *reinterpret_cast<const uint4 *>(seg_end + tab.w + 8 * threadIdx.x);
-    const int g = lanes_per_segment(nseg);
-    const int first = threadIdx.x / g;
 #pragma unroll
     for (int j = 0; j < kSegPasses; ++j) {
-        const int sidx = first + kBlock * j;
-        s.rid[j] = (sidx < nseg && (g == 1 || j == 0)) ? seg_row[tab.x + sidx] : 0;
+        const int sidx = (int)threadIdx.x + kBlock * j;
+        s.rid[j] = (sidx < nseg) ? seg_row[tab.x + sidx] : 0;
     }
     return s;
 }
 
-template <bool HOT>
-__global__ __launch_bounds__(kBlock) void k_csr_spmv_part(PartArgs pa, int64_t rows, const int32_t *__restrict__ col_all,
-                                                          const double *__restrict__ val_all, const int4 *__restrict__ chunk_tab,
-                                                          const uint16_t *__restrict__ seg_end, const int32_t *__restrict__ seg_row_all,
-                                                          const int32_t *__restrict__ hot_ids, const double *__restrict__ x,
-                                                          double *__restrict__ partial_all, double *__restrict__ carry_all)
+// Segment sums of the chunk whose products are in LDS: owned segments to partial[row], the piece of a row that
+// started in an earlier chunk to *carry_slot.  Three barriers; the caller adds one before it reuses `prod`.
+__device__ __forceinline__ void chunk_segments(double *prod, const SegRegs &seg, const int nseg, const bool continued,
+                                               double *__restrict__ partial, double *__restrict__ carry_slot)
 {
-    __shared__ __align__(16) double prod[kChunk];
-    __shared__ __align__(16) uint16_t ends[kChunk];
-    __shared__ double table[HOT ? kHotSlots : 1];
+    double p[8], cin;
+    int idx0;
+    chunk_runs(prod, seg.flags, p, cin, idx0);
+    double *outv = prod + kOutOffset;
+    int i = idx0 - (continued ? 1 : 0);
+    bool first = true;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        if ((seg.flags >> e) & 1u) {
+            const double v = first ? p[e] + cin : p[e];
+            if (i < 0) *carry_slot = v;
+            else outv[i] = v;
+            first = false;
+            ++i;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < kSegPasses; ++j) {
+        const int sidx = (int)threadIdx.x + kBlock * j;
+        if (j * kBlock < nseg && sidx < nseg) partial[seg.rid[j]] = outv[sidx];
+    }
+}
+
+struct PartPtrs {   // device arrays of one partitioned plan (or of its head partition, pre-offset where noted)
+    const void *col;           // int32 columns of the ranges, or the head's 16-bit slots
+    const double *val;
+    const int4 *chunk_tab;
+    const uint8_t *flags;
+    const int32_t *seg_row;
+    const int32_t *hot_ids;    // null without LDS tables
+    double *partial;
+    double *carry;
+};
+
+// Partitioned layout, persistent workgroups: workgroup (partition xp, q) walks chunks q, q + Q, ... of its
+// partition.  Everything the next chunk needs -- the col/val stream, the chunk's table entry, its flags and the row
+// ids this thread will write -- is fetched into registers while the current chunk is being reduced, so HBM latency
+// is paid once per workgroup, not once per chunk.
+template <bool HOT, bool HEAD>
+__device__ __forceinline__ void part_body(double *prod, double *table, const PartArgs &pa, const int xp, const int q, const int Q,
+                                          const int64_t rows, const PartPtrs &pp, const double *__restrict__ x)
+{
     const int tid = threadIdx.x;
-    const int xp = blockIdx.x % pa.P;
-    const int q = blockIdx.x / pa.P, Q = gridDim.x / pa.P;
     const int nchunks = pa.nchunks[xp];
     if (q >= nchunks) return;
     if (HOT) {
         const int nhot = pa.nhot[xp];
+        const int32_t *__restrict__ hot_ids = pp.hot_ids;
         for (int k = tid; k < nhot; k += kBlock) table[k] = x[hot_ids[xp * kHotSlots + k]];
         if (tid == 0 && nhot == 0) table[0] = 0.0;
         __syncthreads();
     }
-    const int32_t *col = col_all + pa.base[xp];     // padded to whole chunks (zeros)
-    const double *val = val_all + pa.base[xp];
-    const int4 *tabs = chunk_tab + pa.chunk0[xp];
-    const int32_t *seg_row = seg_row_all + pa.seg0[xp];
-    double *partial = partial_all + (int64_t)xp * rows;
-    double *carry = carry_all + pa.chunk0[xp];
+    // col/val are padded to whole chunks (zeros)
+    const void *col = HEAD ? static_cast<const void *>(static_cast<const uint16_t *>(pp.col) + pa.base[xp])
+                           : static_cast<const void *>(static_cast<const int32_t *>(pp.col) + pa.base[xp]);
+    const double *val = pp.val + pa.base[xp];
+    const int4 *__restrict__ tabs = pp.chunk_tab + pa.chunk0[xp];
+    const uint8_t *__restrict__ flags = pp.flags + (int64_t)pa.chunk0[xp] * kBlock;
+    const int32_t *__restrict__ seg_row = pp.seg_row + pa.seg0[xp];
+    double *partial = pp.partial + (int64_t)xp * rows;
+    double *carry = pp.carry + pa.chunk0[xp];
 
     int c = q;
     int4 tab = tabs[c];
     int4 tab_n = tabs[(c + Q < nchunks) ? c + Q : c];
-    StreamRegs cur = load_stream(col, val, (int64_t)c * kChunk);
-    SegRegs seg = load_segs(tab, seg_end, seg_row);
+    StreamRegs<HEAD> cur = load_stream<HEAD>(col, val, (int64_t)c * kChunk);
+    SegRegs seg = load_segs(tab, flags + (int64_t)c * kBlock, seg_row);
 
     for (; c < nchunks; c += Q) {
-        const int nseg = tab.y, first_off = tab.z;
-        if (8 * tid < nseg) *reinterpret_cast<uint4 *>(ends + 8 * tid) = seg.ends;
-        // products of this chunk into LDS
-        double xg[2][4];
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            xg[j][0] = gather<HOT>(x, table, cur.c[j].x);
-            xg[j][1] = gather<HOT>(x, table, cur.c[j].y);
-            xg[j][2] = gather<HOT>(x, table, cur.c[j].z);
-            xg[j][3] = gather<HOT>(x, table, cur.c[j].w);
-        }
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            double2 p0, p1;
-            p0.x = cur.v[j][0].x * xg[j][0];
-            p0.y = cur.v[j][0].y * xg[j][1];
-            p1.x = cur.v[j][1].x * xg[j][2];
-            p1.y = cur.v[j][1].y * xg[j][3];
-            double2 *dst = reinterpret_cast<double2 *>(prod + j * (kChunk / 2) + tid * 4);
-            dst[0] = p0;
-            dst[1] = p1;
-        }
+        products_to_lds<HOT, HEAD>(cur, x, table, prod);
         // Only now fetch the next chunk (clamped index: always the same loads): nothing below waits for these
-        // registers, so they stay in flight during the barrier and the segment sums and are waited for at the
-        // top of the next iteration.
+        // registers, so they stay in flight during the segment sums and are waited for at the top of the next
+        // iteration.
         __builtin_amdgcn_sched_barrier(0);
         const int cn = (c + Q < nchunks) ? c + Q : c;
         const int cnn = (cn + Q < nchunks) ? cn + Q : cn;
-        const StreamRegs nxt = load_stream(col, val, (int64_t)cn * kChunk);
-        const SegRegs seg_n = load_segs(tab_n, seg_end, seg_row);
+        const StreamRegs<HEAD> nxt = load_stream<HEAD>(col, val, (int64_t)cn * kChunk);
+        const SegRegs seg_n = load_segs(tab_n, flags + (int64_t)cn * kBlock, seg_row);
         const int4 tab_nn = tabs[cnn];
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
-
-        // carry: the part of the row entering this chunk from before (wavefront 0)
-        if (c > 0 && tid < kWave && first_off > 0) {
-            double sacc = 0.0;
-            for (int k = tid; k < first_off; k += kWave) sacc += prod[k];
-            sacc = wave_sum(sacc);
-            if (tid == 0) carry[c] = sacc;
-        }
-        // segments that start in this chunk: g lanes each
-        const int g = lanes_per_segment(nseg);
-        const int sub = tid & (g - 1);
-        const int first = tid / g;
-#pragma unroll
-        for (int j = 0; j < kSegPasses; ++j) {
-            if (j * kBlock < nseg && (g == 1 || j == 0)) {   // uniform over the workgroup
-                const int sidx = first + kBlock * j;
-                double sacc = 0.0;
-                if (sidx < nseg) {
-                    const int k0 = (sidx == 0) ? first_off : (int)ends[sidx - 1];
-                    const int k1 = (int)ends[sidx];
-                    for (int k = k0 + sub; k < k1; k += g) sacc += prod[k];
-                }
-                sacc = group_sum(sacc, g);
-                if (sidx < nseg && sub == 0) partial[seg.rid[j]] = sacc;
-            }
-        }
-        __syncthreads();  // prod / ends are reused by the next chunk
+        chunk_segments(prod, seg, tab.y, tab.z > 0, partial, carry + c);
+        __syncthreads();  // prod is reused by the next chunk
         cur = nxt;
         seg = seg_n;
         tab = tab_n;
@@ -561,79 +678,44 @@ __global__ __launch_bounds__(kBlock) void k_csr_spmv_part(PartArgs pa, int64_t r
     }
 }
 
-// One chunk per workgroup (no LDS table): few registers, so eight workgroups fit on a CU and the memory latency of
-// one is hidden by the others.  Loads are issued in two waves: {col/val stream, chunk table entry}, then
-// {gathers, segment end offsets, row ids}.
-__global__ __launch_bounds__(kBlock) void k_csr_spmv_part_np(PartArgs pa, int64_t rows, const int32_t *__restrict__ col_all,
-                                                             const double *__restrict__ val_all, const int4 *__restrict__ chunk_tab,
-                                                             const uint16_t *__restrict__ seg_end, const int32_t *__restrict__ seg_row_all,
-                                                             const double *__restrict__ x, double *__restrict__ partial_all,
-                                                             double *__restrict__ carry_all)
+template <bool HOT, bool HEAD>
+__global__ __launch_bounds__(kBlock) void k_csr_spmv_part(PartArgs pa, int64_t rows, PartPtrs pp, const double *__restrict__ x)
 {
-    __shared__ __align__(16) double prod[kChunk];
-    __shared__ __align__(16) uint16_t ends[kChunk];
-    const int tid = threadIdx.x;
+    __shared__ __align__(16) double prod[kProdDoubles];
+    __shared__ double table[HOT ? kHotSlots : 1];
+    part_body<HOT, HEAD>(prod, table, pa, blockIdx.x % pa.P, blockIdx.x / pa.P, gridDim.x / pa.P, rows, pp, x);
+}
+
+// One chunk per workgroup (no LDS table): few registers, so many workgroups fit on a CU and the memory latency of
+// one is hidden by the others.  Loads are issued in two waves: {col/val stream, chunk table entry}, then
+// {gathers, flags, row ids}.
+__global__ __launch_bounds__(kBlock) void k_csr_spmv_part_np(PartArgs pa, int64_t rows, PartPtrs pp, const double *__restrict__ x)
+{
+    __shared__ __align__(16) double prod[kProdDoubles];
     const int xp = blockIdx.x % pa.P;
     const int c = blockIdx.x / pa.P;
     if (c >= pa.nchunks[xp]) return;
-    const int32_t *col = col_all + pa.base[xp];
-    const double *val = val_all + pa.base[xp];
-    const int32_t *seg_row = seg_row_all + pa.seg0[xp];
-    double *partial = partial_all + (int64_t)xp * rows;
-
-    const StreamRegs cur = load_stream(col, val, (int64_t)c * kChunk);   // col/val are padded to whole chunks
-    const int4 tab = chunk_tab[pa.chunk0[xp] + c];
-    const int nseg = tab.y, first_off = tab.z;
-    double xg[2][4];
+    const int32_t *col = static_cast<const int32_t *>(pp.col) + pa.base[xp];
+    const double *val = pp.val + pa.base[xp];
+    const StreamRegs<false> cur = load_stream<false>(col, val, (int64_t)c * kChunk);   // col/val are padded to whole chunks
+    const int4 tab = pp.chunk_tab[pa.chunk0[xp] + c];
+    double xg[4][2];
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        xg[j][0] = load_elem(x, cur.c[j].x);
-        xg[j][1] = load_elem(x, cur.c[j].y);
-        xg[j][2] = load_elem(x, cur.c[j].z);
-        xg[j][3] = load_elem(x, cur.c[j].w);
-    }
-    const SegRegs seg = load_segs(tab, seg_end, seg_row);
-    if (8 * tid < nseg) *reinterpret_cast<uint4 *>(ends + 8 * tid) = seg.ends;
+    for (int m = 0; m < 4; ++m) gather2<false, false>(cur, m, x, nullptr, xg[m]);
+    const SegRegs seg = load_segs(tab, pp.flags + ((int64_t)pa.chunk0[xp] + c) * kBlock, pp.seg_row + pa.seg0[xp]);
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        double2 p0, p1;
-        p0.x = cur.v[j][0].x * xg[j][0];
-        p0.y = cur.v[j][0].y * xg[j][1];
-        p1.x = cur.v[j][1].x * xg[j][2];
-        p1.y = cur.v[j][1].y * xg[j][3];
-        double2 *dst = reinterpret_cast<double2 *>(prod + j * (kChunk / 2) + tid * 4);
-        dst[0] = p0;
-        dst[1] = p1;
+    for (int m = 0; m < 4; ++m) {
+        double2 p;
+        p.x = cur.v[m].x * xg[m][0];
+        p.y = cur.v[m].y * xg[m][1];
+        *reinterpret_cast<double2 *>(prod + prod_pos(m * kQuarter + threadIdx.x * 2)) = p;
     }
     __syncthreads();
-    if (c > 0 && tid < kWave && first_off > 0) {
-        double sacc = 0.0;
-        for (int k = tid; k < first_off; k += kWave) sacc += prod[k];
-        sacc = wave_sum(sacc);
-        if (tid == 0) carry_all[pa.chunk0[xp] + c] = sacc;
-    }
-    const int g = lanes_per_segment(nseg);
-    const int sub = tid & (g - 1);
-    const int first = tid / g;
-#pragma unroll
-    for (int j = 0; j < kSegPasses; ++j) {
-        if (j * kBlock < nseg && (g == 1 || j == 0)) {
-            const int sidx = first + kBlock * j;
-            double sacc = 0.0;
-            if (sidx < nseg) {
-                const int k0 = (sidx == 0) ? first_off : (int)ends[sidx - 1];
-                const int k1 = (int)ends[sidx];
-                for (int k = k0 + sub; k < k1; k += g) sacc += prod[k];
-            }
-            sacc = group_sum(sacc, g);
-            if (sidx < nseg && sub == 0) partial[seg.rid[j]] = sacc;
-        }
-    }
+    chunk_segments(prod, seg, tab.y, tab.z > 0, pp.partial + (int64_t)xp * rows, pp.carry + pa.chunk0[xp] + c);
 }
 
 // ------------------------------------------------------------------ hot-row tiles (see HotTiles)
-constexpr int kLongSegment = 64;   // segments at least this long are summed by a whole wavefront,
-constexpr int kMidSegment = 8;     // at least this long by 8 lanes, shorter ones by one thread
+constexpr int kMaxTileBlocks = 128;   // workgroups per slice: at most 1024 / kTileSlices
 
 int hot_tiles_build(CsrPlan &A, const int64_t *t_rowptr, const int32_t *t_col, const double *t_val,
                     const std::vector<int32_t> &slot_code, int nhot, hipStream_t st)
@@ -645,42 +727,31 @@ int hot_tiles_build(CsrPlan &A, const int64_t *t_rowptr, const int32_t *t_col, c
     int64_t base[kTileSlices] = {0};
     std::vector<double> tval[kTileSlices];
     std::vector<uint16_t> tiloc[kTileSlices];
-    std::vector<uint32_t> sdesc[kTileSlices];
+    std::vector<uint8_t> tflags[kTileSlices];
+    std::vector<uint16_t> sslot[kTileSlices];
     std::vector<int4> hdrs[kTileSlices];
-    std::vector<int> seglen(kTileSlots);
-    std::vector<Entry> sorted;
 
     auto close_tile = [&](int s) {
         std::vector<Entry> &e = cur[s];
         if (e.empty()) return;
-        // long segments first, then by slot; entries of a slot keep their column order
-        for (const Entry &x : e) seglen[x.slot]++;
-        sorted = e;
-        auto cls = [&](int slot) { return seglen[slot] >= kLongSegment ? 0 : (seglen[slot] >= kMidSegment ? 1 : 2); };
-        std::stable_sort(sorted.begin(), sorted.end(), [&](const Entry &a, const Entry &b) {
-            const int ca = cls(a.slot), cb = cls(b.slot);
-            if (ca != cb) return ca < cb;
-            // inside the medium and short classes by length (the lanes of a wavefront then loop equally long)
-            if (ca != 0 && seglen[a.slot] != seglen[b.slot]) return seglen[a.slot] > seglen[b.slot];
-            return a.slot < b.slot;
-        });
-        int4 h = make_int4((int)base[s], 0, 0, (int)sdesc[s].size());
+        // by slot; the entries of a slot keep their column order
+        std::stable_sort(e.begin(), e.end(), [](const Entry &a, const Entry &b) { return a.slot < b.slot; });
+        int4 h = make_int4((int)base[s], 0, 0, (int)sslot[s].size());
         const size_t off = tval[s].size();
         tval[s].resize(off + kChunk, 0.0);
         tiloc[s].resize(off + kChunk, 0);
-        for (size_t k = 0; k < sorted.size(); ++k) {
-            tval[s][off + k] = sorted[k].val;
-            tiloc[s][off + k] = sorted[k].iloc;
-            if (k + 1 == sorted.size() || sorted[k + 1].slot != sorted[k].slot) {
-                sdesc[s].push_back((uint32_t)(k + 1) | ((uint32_t)sorted[k].slot << 16));
+        tflags[s].resize((off + kChunk) / 8, 0);
+        for (size_t k = 0; k < e.size(); ++k) {
+            tval[s][off + k] = e[k].val;
+            tiloc[s][off + k] = e[k].iloc;
+            if (k + 1 == e.size() || e[k + 1].slot != e[k].slot) {
+                tflags[s][(off + k) / 8] |= (uint8_t)(1u << (k % 8));
+                sslot[s].push_back(e[k].slot);
                 h.y += 1;
-                if (cls(sorted[k].slot) == 0) h.z += 1;          // low 16 bits: long segments
-                if (cls(sorted[k].slot) == 1) h.z += 1 << 16;    // high 16 bits: medium segments
             }
         }
-        while (sdesc[s].size() % 4) sdesc[s].push_back(0);
+        while (sslot[s].size() % 8) sslot[s].push_back(0);
         hdrs[s].push_back(h);
-        for (const Entry &x : e) seglen[x.slot] = 0;
         e.clear();
     };
 
@@ -711,29 +782,31 @@ int hot_tiles_build(CsrPlan &A, const int64_t *t_rowptr, const int32_t *t_col, c
         H.ntiles[s] = (int64_t)hdrs[s].size();
         for (int4 &h : hdrs[s]) h.w += (int)nseg;
         ntiles += H.ntiles[s];
-        nseg += (int64_t)sdesc[s].size();
+        nseg += (int64_t)sslot[s].size();
     }
     H.ntiles_total = ntiles;
     if (ntiles == 0) return TRON_OK;
     if (nseg > 0x7ffffff0 || ntiles > 0x7ffffff0 / kChunk * 1024) { set_error("hot tiles too large"); return TRON_EINVAL; }
     TRON_HIP(hipMalloc(reinterpret_cast<void **>(&H.val), sizeof(double) * ntiles * kChunk));
     TRON_HIP(hipMalloc(reinterpret_cast<void **>(&H.iloc), sizeof(uint16_t) * ntiles * kChunk));
+    TRON_HIP(hipMalloc(reinterpret_cast<void **>(&H.flags), ntiles * kBlock));
     TRON_HIP(hipMalloc(reinterpret_cast<void **>(&H.hdr), sizeof(int4) * ntiles));
-    TRON_HIP(hipMalloc(reinterpret_cast<void **>(&H.seg_desc), sizeof(uint32_t) * std::max<int64_t>(nseg, 4)));
+    TRON_HIP(hipMalloc(reinterpret_cast<void **>(&H.seg_slot), sizeof(uint16_t) * std::max<int64_t>(nseg, 8)));
     int64_t segpos = 0;
     for (int s = 0; s < kTileSlices; ++s) {
         const int64_t t0 = H.tile0[s];
         if (H.ntiles[s] == 0) continue;
         TRON_HIP(hipMemcpyAsync(H.val + t0 * kChunk, tval[s].data(), sizeof(double) * tval[s].size(), hipMemcpyHostToDevice, st));
         TRON_HIP(hipMemcpyAsync(H.iloc + t0 * kChunk, tiloc[s].data(), sizeof(uint16_t) * tiloc[s].size(), hipMemcpyHostToDevice, st));
+        TRON_HIP(hipMemcpyAsync(H.flags + t0 * kBlock, tflags[s].data(), tflags[s].size(), hipMemcpyHostToDevice, st));
         TRON_HIP(hipMemcpyAsync(H.hdr + t0, hdrs[s].data(), sizeof(int4) * hdrs[s].size(), hipMemcpyHostToDevice, st));
-        TRON_HIP(hipMemcpyAsync(H.seg_desc + segpos, sdesc[s].data(), sizeof(uint32_t) * sdesc[s].size(), hipMemcpyHostToDevice, st));
-        segpos += (int64_t)sdesc[s].size();
+        TRON_HIP(hipMemcpyAsync(H.seg_slot + segpos, sslot[s].data(), sizeof(uint16_t) * sslot[s].size(), hipMemcpyHostToDevice, st));
+        segpos += (int64_t)sslot[s].size();
     }
     TRON_TRY(upload(&H.slot_of_row, slot_code.data(), slot_code.size(), st));
     int64_t maxt = 0;
     for (int s = 0; s < kTileSlices; ++s) maxt = std::max(maxt, H.ntiles[s]);
-    H.blocks_per_slice = (int)std::max<int64_t>(1, std::min<int64_t>(maxt, g_tuning.csr_tile_blocks_per_slice));
+    H.blocks_per_slice = (int)std::max<int64_t>(1, std::min<int64_t>(maxt, std::min<int64_t>(g_tuning.csr_tile_blocks_per_slice, kMaxTileBlocks)));
     TRON_HIP(hipMalloc(reinterpret_cast<void **>(&H.wg_acc), sizeof(double) * kTileSlices * H.blocks_per_slice * kTileSlots));
     TRON_HIP(hipMalloc(reinterpret_cast<void **>(&H.sums), sizeof(double) * kTileSlices * kTileSlots));
     TRON_HIP(hipStreamSynchronize(st));
@@ -748,60 +821,58 @@ struct TileArgs {
 struct TileRegs {
     v2d v[4];
     uint32_t il[4];     // two 16-bit local column offsets each
-    uint4 desc[2];      // segment descriptors 8*tid .. 8*tid+7: end offset | slot << 16
+    uint4 slots;        // slots of the segments 8*tid .. 8*tid+7 (16 bits each)
+    unsigned flags;     // bit e: entry 8*tid + e is the last of its segment
     int4 hdr;
 };
 
+struct TilePtrs {
+    const double *val;
+    const uint16_t *iloc;
+    const uint8_t *flags;
+    const int4 *hdr;
+    const uint16_t *seg_slot;
+    double *wg_acc;
+};
+
 // data of tile T whose header h is already in registers
-__device__ __forceinline__ TileRegs load_tile(const double *__restrict__ val, const uint16_t *__restrict__ iloc, int4 h,
-                                              const uint32_t *__restrict__ seg_desc, int64_t T)
+__device__ __forceinline__ TileRegs load_tile(const TilePtrs &tp, int4 h, int64_t T)
 {
     TileRegs r;
     r.hdr = h;
 #pragma unroll
     for (int m = 0; m < 4; ++m) {
-        const int64_t k = T * kChunk + m * (kChunk / 4) + threadIdx.x * 2;
-        r.v[m] = __builtin_nontemporal_load(reinterpret_cast<const v2d *>(val + k));
-        r.il[m] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(iloc + k));
+        const int64_t k = T * kChunk + m * kQuarter + threadIdx.x * 2;
+        r.v[m] = __builtin_nontemporal_load(reinterpret_cast<const v2d *>(tp.val + k));
+        r.il[m] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(tp.iloc + k));
     }
-    // descriptor blocks are padded to a multiple of 4; threads beyond the tile's segments re-read its first block
+    r.flags = tp.flags[T * kBlock + threadIdx.x];
+    // slot blocks are padded to a multiple of 8; threads beyond the tile's segments re-read its first block
     const int nseg = h.y;
     const int64_t d0 = (int64_t)h.w + ((8 * (int)threadIdx.x < nseg) ? 8 * (int)threadIdx.x : 0);
-    const int64_t d1 = (int64_t)h.w + ((8 * (int)threadIdx.x + 4 < nseg) ? 8 * (int)threadIdx.x + 4 : 0);
-    r.desc[0] = *reinterpret_cast<const uint4 *>(seg_desc + d0);
-    r.desc[1] = *reinterpret_cast<const uint4 *>(seg_desc + d1);
+    r.slots = *reinterpret_cast<const uint4 *>(tp.seg_slot + d0);
     return r;
 }
 
 // Persistent workgroup (slice s, q): tiles q, q + B, ... of the slice; LDS accumulators for the slice's hot rows.
 // Software pipeline: while tile t is reduced, the data of tiles t + B and t + 2B and the header of tile t + 3B are
 // in flight (all indices clamped to the last tile, so every iteration issues the same loads).
-// Segment sums: the segments of a tile are ordered long (>= 64 entries: one wavefront each), medium (>= 8: eight
-// lanes each), short (one thread each, all seven possible reads issued together).  Slots inside a tile are
-// distinct, so the accumulator updates of different segments never collide.
-__global__ __launch_bounds__(kBlock) void k_hot_tiles(TileArgs ta, int B, const double *__restrict__ val,
-                                                      const uint16_t *__restrict__ iloc, const int4 *__restrict__ hdr,
-                                                      const uint32_t *__restrict__ seg_desc,
-                                                      const double *__restrict__ x, double *__restrict__ wg_acc)
+// Slots inside a tile are distinct, so the accumulator updates of different segments never collide.
+__device__ __forceinline__ void tiles_body(double *prod, uint16_t *slots, double *acc, const TileArgs &ta, const int s, const int q,
+                                           const int B, const TilePtrs &tp, const double *__restrict__ x)
 {
-    __shared__ __align__(16) double prod[kChunk];
-    __shared__ __align__(16) uint32_t desc[kChunk];
-    __shared__ double acc[kTileSlots];
     const int tid = threadIdx.x;
-    const int lane = tid & (kWave - 1);
-    const int s = blockIdx.x % kTileSlices;
-    const int q = blockIdx.x / kTileSlices;
     for (int k = tid; k < kTileSlots; k += kBlock) acc[k] = 0.0;
     const int64_t nt = ta.ntiles[s];
     if (q < nt) {
         const int64_t T0 = ta.tile0[s];
         const int64_t last = nt - 1;
         auto clampt = [&](int64_t t) { return T0 + (t < last ? t : last); };
-        TileRegs cur = load_tile(val, iloc, hdr[clampt(q)], seg_desc, clampt(q));
-        TileRegs nxt = load_tile(val, iloc, hdr[clampt(q + B)], seg_desc, clampt(q + B));
-        int4 hdr2 = hdr[clampt(q + 2 * (int64_t)B)];
+        TileRegs cur = load_tile(tp, tp.hdr[clampt(q)], clampt(q));
+        TileRegs nxt = load_tile(tp, tp.hdr[clampt(q + B)], clampt(q + B));
+        int4 hdr2 = tp.hdr[clampt(q + 2 * (int64_t)B)];
         for (int64_t t = q; t < nt; t += B) {
-            const int nseg = cur.hdr.y, nlong = cur.hdr.z & 0xffff, nmid = (unsigned)cur.hdr.z >> 16;
+            const int nseg = cur.hdr.y;
             const double *xt = x + cur.hdr.x;   // the tile's first column
             // gathers: a few consecutive cache lines of x per tile
             double xg[4][2];
@@ -810,83 +881,89 @@ __global__ __launch_bounds__(kBlock) void k_hot_tiles(TileArgs ta, int B, const 
                 xg[m][0] = xt[cur.il[m] & 0xffffu];
                 xg[m][1] = xt[cur.il[m] >> 16];
             }
-            if (8 * tid < nseg) *reinterpret_cast<uint4 *>(desc + 8 * tid) = cur.desc[0];
-            if (8 * tid + 4 < nseg) *reinterpret_cast<uint4 *>(desc + 8 * tid + 4) = cur.desc[1];
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
                 double2 p;
                 p.x = cur.v[m].x * xg[m][0];
                 p.y = cur.v[m].y * xg[m][1];
-                *reinterpret_cast<double2 *>(prod + m * (kChunk / 4) + tid * 2) = p;
+                *reinterpret_cast<double2 *>(prod + prod_pos(m * kQuarter + tid * 2)) = p;
             }
             __builtin_amdgcn_sched_barrier(0);
-            const TileRegs nn = load_tile(val, iloc, hdr2, seg_desc, clampt(t + 2 * (int64_t)B));
-            const int4 hdr3 = hdr[clampt(t + 3 * (int64_t)B)];
+            const TileRegs nn = load_tile(tp, hdr2, clampt(t + 2 * (int64_t)B));
+            const int4 hdr3 = tp.hdr[clampt(t + 3 * (int64_t)B)];
             __builtin_amdgcn_sched_barrier(0);
             __syncthreads();
-            // long segments: one wavefront each
-            for (int sg = tid / kWave; sg < nlong; sg += kWavesPerBlock) {
-                const int k0 = sg ? (int)(desc[sg - 1] & 0xffffu) : 0;
-                const uint32_t dsc = desc[sg];
-                const int k1 = (int)(dsc & 0xffffu);
-                double sacc = 0.0;
-                for (int k = k0 + lane; k < k1; k += kWave) sacc += prod[k];
-                sacc = wave_sum(sacc);
-                if (lane == 0) acc[dsc >> 16] += sacc;
-            }
-            // LDS bandwidth is what these sums cost, so each lane reads exactly the entries it needs; segments of
-            // the medium and short classes are ordered by length, so the lanes of a wavefront loop equally long.
-            // medium segments (8..63 entries): eight lanes each
-            {
-                const int sub = lane & 7;
-                const int mid_end = nlong + nmid;
-                for (int sg = nlong + tid / 8; sg < mid_end; sg += kBlock / 8) {
-                    const int k0 = sg ? (int)(desc[sg - 1] & 0xffffu) : 0;
-                    const uint32_t dsc = desc[sg];
-                    const int k1 = (int)(dsc & 0xffffu);
-                    double sacc = 0.0;
-                    for (int k = k0 + sub; k < k1; k += 8) sacc += prod[k];
-                    sacc = sum8(sacc);
-                    if (sub == 0) acc[dsc >> 16] += sacc;
+            // every thread is past the accumulator updates of the tile before: its slots may be replaced
+            if (8 * tid < nseg) *reinterpret_cast<uint4 *>(slots + 8 * tid) = cur.slots;
+            double p[8], cin;
+            int idx0;
+            chunk_runs(prod, cur.flags, p, cin, idx0);   // barrier inside: the slots are visible after it
+            int i = idx0;
+            bool first = true;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                if ((cur.flags >> e) & 1u) {
+                    acc[slots[i]] += first ? p[e] + cin : p[e];
+                    first = false;
+                    ++i;
                 }
             }
-            // short segments (1..7 entries): one thread each
-            for (int sg = nlong + nmid + tid; sg < nseg; sg += kBlock) {
-                const int k0 = sg ? (int)(desc[sg - 1] & 0xffffu) : 0;
-                const uint32_t dsc = desc[sg];
-                const int k1 = (int)(dsc & 0xffffu);
-                double sacc = prod[k0];
-                for (int k = k0 + 1; k < k1; ++k) sacc += prod[k];
-                acc[dsc >> 16] += sacc;
-            }
-            __syncthreads();
+            // no barrier here: the next tile's products do not touch acc or slots, and its wavefront totals are
+            // written after its first barrier
             cur = nxt;
             nxt = nn;
             hdr2 = hdr3;
         }
     }
     __syncthreads();
-    double *out = wg_acc + ((int64_t)s * B + q) * kTileSlots;
+    double *out = tp.wg_acc + ((int64_t)s * B + q) * kTileSlots;
     for (int k = tid; k < kTileSlots; k += kBlock) out[k] = acc[k];
 }
 
-// sums[s*K + k] = sum over the B workgroups of slice s, in workgroup order
-__global__ __launch_bounds__(kBlock) void k_hot_reduce(int B, const double *__restrict__ wg_acc, double *__restrict__ sums)
+__global__ __launch_bounds__(kBlock) void k_hot_tiles(TileArgs ta, int B, TilePtrs tp, const double *__restrict__ x)
 {
-    const int idx = blockIdx.x * kBlock + threadIdx.x;   // s*K + k
-    if (idx >= kTileSlices * kTileSlots) return;
-    const int s = idx / kTileSlots, k = idx % kTileSlots;
-    const double *p = wg_acc + (int64_t)s * B * kTileSlots + k;
-    double a = 0.0;
-    for (int q = 0; q < B; ++q) a += p[(int64_t)q * kTileSlots];
-    sums[idx] = a;
+    __shared__ __align__(16) double prod[kProdDoubles];
+    __shared__ __align__(16) uint16_t slots[kChunk];
+    __shared__ double acc[kTileSlots];
+    tiles_body(prod, slots, acc, ta, blockIdx.x % kTileSlices, blockIdx.x / kTileSlices, B, tp, x);
 }
 
+// sums[s*K + k] = sum over the B workgroups of slice s: four quarter sums (workgroup order inside each), added in
+// order.  A workgroup covers 64 consecutive slots, one wavefront per quarter, so every read is one 512-byte row.
+__global__ __launch_bounds__(kBlock) void k_hot_reduce(int B, const double *__restrict__ wg_acc, double *__restrict__ sums)
+{
+    __shared__ double part[kWavesPerBlock][kWave];
+    const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave;
+    const int idx = blockIdx.x * kWave + lane;   // s*K + k
+    const int s = idx / kTileSlots, k = idx % kTileSlots;
+    const int per = (B + kWavesPerBlock - 1) / kWavesPerBlock;
+    const int q0 = wv * per, q1 = (q0 + per < B) ? q0 + per : B;
+    const double *p = wg_acc + (int64_t)s * B * kTileSlots + k;
+    double a = 0.0;
+    for (int q = q0; q < q1; ++q) a += p[(int64_t)q * kTileSlots];
+    part[wv][lane] = a;
+    __syncthreads();
+    if (wv == 0) {
+        double t = part[0][lane];
+#pragma unroll
+        for (int m = 1; m < kWavesPerBlock; ++m) t += part[m][lane];
+        sums[idx] = t;
+    }
+}
+
+static TileArgs tile_args(const HotTiles &H)
+{
+    TileArgs ta;
+    for (int s = 0; s < kTileSlices; ++s) { ta.tile0[s] = H.tile0[s]; ta.ntiles[s] = H.ntiles[s]; }
+    return ta;
+}
+
+static TilePtrs tile_ptrs(const HotTiles &H) { return TilePtrs{H.val, H.iloc, H.flags, H.hdr, H.seg_slot, H.wg_acc}; }
+
+// tiles + the reduction of the workgroup accumulators (B = workgroups per slice)
 static int launch_hot_tiles(tron_dataset *ds, const CsrPlan &A, const double *x)
 {
     const HotTiles &H = A.hot;
-    TileArgs ta;
-    for (int s = 0; s < kTileSlices; ++s) { ta.tile0[s] = H.tile0[s]; ta.ntiles[s] = H.ntiles[s]; }
     // The tiles stream from HBM, the CSR remainder waits on gather misses: they run side by side on two streams.
     hipStream_t st = g_tuning.csr_two_streams ? ds->side : ds->stream;
     if (st != ds->stream) {
@@ -895,9 +972,9 @@ static int launch_hot_tiles(tron_dataset *ds, const CsrPlan &A, const double *x)
     }
     {
         ProfScope ps(ds, SLOT_SPMV_TILES, st);
-        hipLaunchKernelGGL(k_hot_tiles, dim3(kTileSlices * H.blocks_per_slice), dim3(kBlock), 0, st, ta, H.blocks_per_slice,
-                           H.val, H.iloc, H.hdr, H.seg_desc, x, H.wg_acc);
-        hipLaunchKernelGGL(k_hot_reduce, dim3(kTileSlices * kTileSlots / kBlock), dim3(kBlock), 0, st, H.blocks_per_slice,
+        hipLaunchKernelGGL(k_hot_tiles, dim3(kTileSlices * H.blocks_per_slice), dim3(kBlock), 0, st, tile_args(H), H.blocks_per_slice,
+                           tile_ptrs(H), x);
+        hipLaunchKernelGGL(k_hot_reduce, dim3(kTileSlices * kTileSlots / kWave), dim3(kBlock), 0, st, H.blocks_per_slice,
                            H.wg_acc, H.sums);
         TRON_HIP(hipGetLastError());
     }
@@ -937,7 +1014,7 @@ struct HotRef {
     const double *sums;
 };
 
-__device__ __forceinline__ double sum_parts(const double *__restrict__ partial, const uint8_t *__restrict__ mask, int64_t rows, int64_t r,
+__device__ __forceinline__ double sum_parts(const double *__restrict__ partial, const uint16_t *__restrict__ mask, int64_t rows, int64_t r,
                                             HotRef hot = HotRef{nullptr, nullptr})
 {
     const unsigned m = mask[r];
@@ -954,7 +1031,7 @@ __device__ __forceinline__ double sum_parts(const double *__restrict__ partial, 
 
 // z = sum of partials; loss terms; partial slot 0 = sum loss
 template <int LOSS>
-__global__ __launch_bounds__(kBlock) void k_combine_loss(int64_t n, const double *__restrict__ partial, const uint8_t *__restrict__ mask,
+__global__ __launch_bounds__(kBlock) void k_combine_loss(int64_t n, const double *__restrict__ partial, const uint16_t *__restrict__ mask,
                                                          const double *__restrict__ y, double *__restrict__ zhat,
                                                          double *__restrict__ D, double *__restrict__ red)
 {
@@ -973,7 +1050,7 @@ __global__ __launch_bounds__(kBlock) void k_combine_loss(int64_t n, const double
 }
 
 // out = scale .* sum of partials
-__global__ __launch_bounds__(kBlock) void k_combine_scale(int64_t rows, const double *__restrict__ partial, const uint8_t *__restrict__ mask,
+__global__ __launch_bounds__(kBlock) void k_combine_scale(int64_t rows, const double *__restrict__ partial, const uint16_t *__restrict__ mask,
                                                           const double *__restrict__ scale, double *__restrict__ out)
 {
     for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < rows; i += (int64_t)gridDim.x * kBlock)
@@ -982,7 +1059,7 @@ __global__ __launch_bounds__(kBlock) void k_combine_scale(int64_t rows, const do
 
 // out = add + alpha * sum of partials; partial slot 0 = out . (SELF ? out : add)
 template <bool SELF>
-__global__ __launch_bounds__(kBlock) void k_combine_axpy(int64_t rows, const double *__restrict__ partial, const uint8_t *__restrict__ mask,
+__global__ __launch_bounds__(kBlock) void k_combine_axpy(int64_t rows, const double *__restrict__ partial, const uint16_t *__restrict__ mask,
                                                          const double *__restrict__ add, double alpha,
                                                          double *__restrict__ out, double *__restrict__ red, HotRef hot)
 {
@@ -1027,8 +1104,7 @@ static int launch_plain(tron_dataset *ds, const CsrPlan &A, int slot, const doub
     return TRON_OK;
 }
 
-// partial row sums of all partitions into ds->row_partials (with split rows fixed up)
-static int launch_partials(tron_dataset *ds, const CsrPlan &A, int slot, const double *x)
+static PartArgs part_args(const CsrPlan &A)
 {
     PartArgs pa;
     std::memset(&pa, 0, sizeof(pa));
@@ -1041,19 +1117,59 @@ static int launch_partials(tron_dataset *ds, const CsrPlan &A, int slot, const d
         pa.nchunks[i] = A.part_nchunks[i];
         pa.nhot[i] = A.part_nhot[i];
     }
+    return pa;
+}
+
+// The head partition as a one-partition launch: val, hot_ids and the partials are passed pre-offset, col16 only
+// holds this partition; chunk and segment tables are indexed through the offsets in the arguments.
+static PartArgs head_args(const CsrPlan &A)
+{
+    const int h = A.head;
+    PartArgs ha;
+    std::memset(&ha, 0, sizeof(ha));
+    ha.P = 1;
+    ha.nnz[0] = A.part_nnz[h];
+    ha.seg0[0] = A.part_seg0[h];
+    ha.chunk0[0] = A.part_chunk0[h];
+    ha.nchunks[0] = A.part_nchunks[h];
+    ha.nhot[0] = A.part_nhot[h];
+    return ha;
+}
+
+static PartPtrs part_ptrs(const tron_dataset *ds, const CsrPlan &A)
+{
+    return PartPtrs{A.col, A.val, A.chunk_tab, A.flags, A.seg_row, A.hot_ids, ds->row_partials, A.carry};
+}
+
+static PartPtrs head_ptrs(const tron_dataset *ds, const CsrPlan &A)
+{
+    const int h = A.head;
+    return PartPtrs{A.col16, A.val + A.part_base[h], A.chunk_tab, A.flags, A.seg_row, A.hot_ids + (size_t)h * kHotSlots,
+                    ds->row_partials + (int64_t)h * A.rows, A.carry};
+}
+
+// partial row sums of all partitions into ds->row_partials (with split rows fixed up)
+static int launch_partials(tron_dataset *ds, const CsrPlan &A, int slot, const double *x)
+{
+    const PartArgs pa = part_args(A);
     {
         ProfScope ps(ds, slot);
+        if (A.head >= 0) {
+            const int grid = std::max(1, std::min(A.part_nchunks[A.head], (int)g_tuning.csr_hot_blocks_per_part * kColParts));
+            hipLaunchKernelGGL((k_csr_spmv_part<true, true>), dim3(grid), dim3(kBlock), 0, ds->stream, head_args(A), A.rows,
+                               head_ptrs(ds, A), x);
+        }
         const int want = (int)(A.hot_ids ? g_tuning.csr_hot_blocks_per_part : g_tuning.csr_blocks_per_part);
         const int per_part = std::max(1, std::min(A.max_chunks, want));
         if (A.hot_ids)
-            hipLaunchKernelGGL(k_csr_spmv_part<true>, dim3(per_part * A.P), dim3(kBlock), 0, ds->stream, pa, A.rows, A.col, A.val,
-                               A.chunk_tab, A.seg_end, A.seg_row, A.hot_ids, x, ds->row_partials, A.carry);
+            hipLaunchKernelGGL((k_csr_spmv_part<true, false>), dim3(per_part * A.P), dim3(kBlock), 0, ds->stream, pa, A.rows,
+                               part_ptrs(ds, A), x);
         else if (g_tuning.csr_blocks_per_part > 0)
-            hipLaunchKernelGGL(k_csr_spmv_part<false>, dim3(per_part * A.P), dim3(kBlock), 0, ds->stream, pa, A.rows, A.col, A.val,
-                               A.chunk_tab, A.seg_end, A.seg_row, (const int32_t *)nullptr, x, ds->row_partials, A.carry);
+            hipLaunchKernelGGL((k_csr_spmv_part<false, false>), dim3(per_part * A.P), dim3(kBlock), 0, ds->stream, pa, A.rows,
+                               part_ptrs(ds, A), x);
         else
-            hipLaunchKernelGGL(k_csr_spmv_part_np, dim3(A.max_chunks * A.P), dim3(kBlock), 0, ds->stream, pa, A.rows, A.col, A.val,
-                               A.chunk_tab, A.seg_end, A.seg_row, x, ds->row_partials, A.carry);
+            hipLaunchKernelGGL(k_csr_spmv_part_np, dim3(A.max_chunks * A.P), dim3(kBlock), 0, ds->stream, pa, A.rows,
+                               part_ptrs(ds, A), x);
         TRON_HIP(hipGetLastError());
     }
     if (A.nfix > 0) {
