@@ -158,7 +158,8 @@ struct CsrPlan {
     int part_nchunks[kMaxParts] = {0};
     int part_nhot[kMaxParts] = {0};      // LDS-resident columns of partition x
     int max_chunks = 0;                  // max over partitions
-    int32_t *hot_ids = nullptr;          // device, P*kHotSlots column ids (null: no LDS table)
+    int32_t *hot_ids = nullptr;          // device, (P+1)*kHotSlots column ids of the LDS tables (null: no LDS table)
+    double *hot_x = nullptr;             // device, (P+1)*kHotSlots: the gather vector at those columns, refreshed every call
     int32_t *seg_row = nullptr;          // device: row id of every segment, partition-major, ascending inside a partition
     int4 *chunk_tab = nullptr;           // device, per chunk: {first owned segment (partition-relative), number of owned
                                          //   segments, offset where the first owned segment starts, unused}

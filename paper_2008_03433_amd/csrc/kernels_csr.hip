@@ -42,7 +42,7 @@ void CsrPlan::release()
 {
     hot.release();
     hipFree(rowptr); hipFree(col); hipFree(col16); hipFree(val); hipFree(row_lo); hipFree(carry);
-    hipFree(hot_ids); hipFree(seg_row); hipFree(chunk_tab); hipFree(flags); hipFree(row_mask);
+    hipFree(hot_ids); hipFree(hot_x); hipFree(seg_row); hipFree(chunk_tab); hipFree(flags); hipFree(row_mask);
     hipFree(fix_row); hipFree(fix_part); hipFree(fix_b0); hipFree(fix_cnt);
     *this = CsrPlan();
 }
@@ -268,7 +268,10 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
         // first_off of a chunk inside or at the end of a split row: the chunk-relative end of that row
         // (set above from the start of the next segment; for chunks wholly inside one row that start lies
         // beyond the chunk and clips to kChunk, which is right)
-        if (hot) TRON_TRY(upload(&A.hot_ids, hot_ids.data(), hot_ids.size(), st));
+        if (hot) {
+            TRON_TRY(upload(&A.hot_ids, hot_ids.data(), hot_ids.size(), st));   // unused slots: column 0
+            TRON_HIP(hipMalloc(reinterpret_cast<void **>(&A.hot_x), sizeof(double) * hot_ids.size()));
+        }
         if (A.head >= 0) {
             // the head partition is the last one: its columns go to col16, the ranges' stay in col
             const size_t h0 = (size_t)A.part_base[A.head];
@@ -611,13 +614,22 @@ __device__ __forceinline__ void chunk_segments(double *prod, const SegRegs &seg,
     }
 }
 
+// hot_x[k] = x[hot_ids[k]]: the LDS tables of all partitions, so that a workgroup fills its table with 128 line
+// requests instead of 4096 gathers
+__global__ __launch_bounds__(kBlock) void k_gather_hot(int n, const int32_t *__restrict__ hot_ids, const double *__restrict__ x,
+                                                       double *__restrict__ hot_x)
+{
+    const int k = blockIdx.x * kBlock + threadIdx.x;
+    if (k < n) hot_x[k] = x[hot_ids[k]];
+}
+
 struct PartPtrs {   // device arrays of one partitioned plan (or of its head partition, pre-offset where noted)
     const void *col;           // int32 columns of the ranges, or the head's 16-bit slots
     const double *val;
     const int4 *chunk_tab;
     const uint8_t *flags;
     const int32_t *seg_row;
-    const int32_t *hot_ids;    // null without LDS tables
+    const double *hot_x;       // x at the LDS-resident columns, kHotSlots per partition (null without LDS tables)
     double *partial;
     double *carry;
 };
@@ -634,10 +646,9 @@ __device__ __forceinline__ void part_body(double *prod, double *table, const Par
     const int nchunks = pa.nchunks[xp];
     if (q >= nchunks) return;
     if (HOT) {
-        const int nhot = pa.nhot[xp];
-        const int32_t *__restrict__ hot_ids = pp.hot_ids;
-        for (int k = tid; k < nhot; k += kBlock) table[k] = x[hot_ids[xp * kHotSlots + k]];
-        if (tid == 0 && nhot == 0) table[0] = 0.0;
+        // the vector entries of this partition's LDS-resident columns, gathered once per call by k_gather_hot
+        const double2 *__restrict__ src = reinterpret_cast<const double2 *>(pp.hot_x + (size_t)xp * kHotSlots);
+        for (int k = tid; k < kHotSlots / 2; k += kBlock) reinterpret_cast<double2 *>(table)[k] = src[k];
         __syncthreads();
     }
     // col/val are padded to whole chunks (zeros)
@@ -1138,13 +1149,13 @@ static PartArgs head_args(const CsrPlan &A)
 
 static PartPtrs part_ptrs(const tron_dataset *ds, const CsrPlan &A)
 {
-    return PartPtrs{A.col, A.val, A.chunk_tab, A.flags, A.seg_row, A.hot_ids, ds->row_partials, A.carry};
+    return PartPtrs{A.col, A.val, A.chunk_tab, A.flags, A.seg_row, A.hot_x, ds->row_partials, A.carry};
 }
 
 static PartPtrs head_ptrs(const tron_dataset *ds, const CsrPlan &A)
 {
     const int h = A.head;
-    return PartPtrs{A.col16, A.val + A.part_base[h], A.chunk_tab, A.flags, A.seg_row, A.hot_ids + (size_t)h * kHotSlots,
+    return PartPtrs{A.col16, A.val + A.part_base[h], A.chunk_tab, A.flags, A.seg_row, A.hot_x ? A.hot_x + (size_t)h * kHotSlots : nullptr,
                     ds->row_partials + (int64_t)h * A.rows, A.carry};
 }
 
@@ -1154,6 +1165,10 @@ static int launch_partials(tron_dataset *ds, const CsrPlan &A, int slot, const d
     const PartArgs pa = part_args(A);
     {
         ProfScope ps(ds, slot);
+        if (A.hot_ids) {
+            const int nh = (A.P + 1) * kHotSlots;
+            hipLaunchKernelGGL(k_gather_hot, dim3((nh + kBlock - 1) / kBlock), dim3(kBlock), 0, ds->stream, nh, A.hot_ids, x, A.hot_x);
+        }
         if (A.head >= 0) {
             const int grid = std::max(1, std::min(A.part_nchunks[A.head], (int)g_tuning.csr_hot_blocks_per_part * kColParts));
             hipLaunchKernelGGL((k_csr_spmv_part<true, true>), dim3(grid), dim3(kBlock), 0, ds->stream, head_args(A), A.rows,
