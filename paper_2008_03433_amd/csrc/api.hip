@@ -463,6 +463,14 @@ int tron_tuning_set(const char *name, int64_t value)
         g_tuning.csr_hot_blocks_per_part = value;
         return TRON_OK;
     }
+    if (name && strcmp(name, "csr_range_slots") == 0 && value >= 2 && value <= kHotSlots) {
+        g_tuning.csr_range_slots = value;
+        return TRON_OK;
+    }
+    if (name && strcmp(name, "csr_range_blocks_per_part") == 0 && value >= 1 && value <= 1024) {
+        g_tuning.csr_range_blocks_per_part = value;
+        return TRON_OK;
+    }
     if (name && strcmp(name, "csr_head") == 0 && (value == 0 || value == 1)) {
         g_tuning.csr_head = value;
         return TRON_OK;
@@ -479,7 +487,7 @@ int tron_tuning_set(const char *name, int64_t value)
         g_tuning.csr_tile_blocks_per_slice = value;
         return TRON_OK;
     }
-    if (name && strcmp(name, "csr_blocks_per_part") == 0 && value >= 0 && value <= 4096) {
+    if (name && strcmp(name, "csr_blocks_per_part") == 0 && value >= 1 && value <= 4096) {
         g_tuning.csr_blocks_per_part = value;
         return TRON_OK;
     }

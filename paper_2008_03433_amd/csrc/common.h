@@ -31,13 +31,15 @@ int hip_fail(hipError_t e, const char *what, const char *file, int line);
 struct Tuning {
     int64_t csr_parts = 0;   // column partitions of the CSR layouts: 0 = automatic, 1 = never, 8 = always
     int64_t csr_hot = 1;     // LDS table of frequent columns for the partitioned forward layout (0 = off)
+    int64_t csr_range_blocks_per_part = 96;   // persistent workgroups per column range when LDS tables are used
+    int64_t csr_range_slots = 4096;   // LDS table entries per column range (the head partition always has kHotSlots)
     int64_t csr_head = 1;    // head partition for the matrix' most frequent columns (needs csr_hot; 0 = off)
     int64_t csr_hot_blocks_per_part = 96;  // persistent workgroups per partition when the LDS table is used
-    int64_t csr_blocks_per_part = 0;       // without the table: 0 = one chunk per workgroup, > 0 = persistent workgroups per partition
+    int64_t csr_blocks_per_part = 128;     // persistent workgroups per column range without LDS tables
     int64_t csr_tiles = 1;   // hot-row tiles for the transposed orientation of partitioned matrices (0 = off)
     int64_t csr_two_streams = 0;  // 1 = run the hot-row tiles beside the CSR remainder on a second stream (measured slower: both
                                   // kernels compete for the same per-CU miss queue)
-    int64_t csr_tile_blocks_per_slice = 128;  // persistent workgroups per slice of hot rows
+    int64_t csr_tile_blocks_per_slice = 96;  // persistent workgroups per slice of hot rows
 };
 extern Tuning g_tuning;
 
@@ -143,6 +145,7 @@ struct CsrPlan {
     int nblocks = 0;                     // total number of chunks
     double *carry = nullptr;             // device, nblocks: sum of the part of a row entering chunk c from before
     int nfix = 0;                        // number of (partition, split row) pairs
+    int fix_max_cnt = 0;                 // largest fix_cnt
     int32_t *fix_row = nullptr;          // device, nfix: the split row
     int32_t *fix_part = nullptr;         // device, nfix: its partition
     int32_t *fix_b0 = nullptr;           // device, nfix: first chunk id holding a continuation of it
@@ -158,6 +161,7 @@ struct CsrPlan {
     int part_nchunks[kMaxParts] = {0};
     int part_nhot[kMaxParts] = {0};      // LDS-resident columns of partition x
     int max_chunks = 0;                  // max over partitions
+    int range_slots = 0;                 // LDS table entries used by the column ranges (<= kHotSlots)
     int32_t *hot_ids = nullptr;          // device, (P+1)*kHotSlots column ids of the LDS tables (null: no LDS table)
     double *hot_x = nullptr;             // device, (P+1)*kHotSlots: the gather vector at those columns, refreshed every call
     int32_t *seg_row = nullptr;          // device: row id of every segment, partition-major, ascending inside a partition

@@ -127,6 +127,7 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
         std::vector<std::pair<int64_t, int32_t>> cand;
         int64_t head_nnz = 0;
         if (hot) {
+            A.range_slots = (int)std::min<int64_t>(kHotSlots, std::max<int64_t>(2, g_tuning.csr_range_slots / 2 * 2));
             slot_of.assign((size_t)cols, -1);
             hot_ids.assign((size_t)(P + 1) * kHotSlots, 0);
         }
@@ -174,7 +175,7 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
                     const int64_t cnt = colcount[j + 1] - colcount[j];   // 0 for head columns
                     if (cnt >= kHotMinCount) cand.emplace_back(-cnt, (int32_t)j);
                 }
-                const size_t keep = std::min<size_t>(cand.size(), kHotSlots);
+                const size_t keep = std::min<size_t>(cand.size(), (size_t)A.range_slots);
                 std::partial_sort(cand.begin(), cand.begin() + keep, cand.end());
                 A.part_nhot[x] = (int)keep;
                 for (size_t k = 0; k < keep; ++k) {
@@ -290,6 +291,8 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
         TRON_HIP(hipStreamSynchronize(st));
     }
     A.nfix = (int)fix_row.size();
+    A.fix_max_cnt = 0;
+    for (int32_t c : fix_cnt) A.fix_max_cnt = std::max(A.fix_max_cnt, (int)c);
     if (A.P == 1) TRON_TRY(upload(&A.row_lo, row_lo.data(), row_lo.size(), st));
     TRON_TRY(upload(&A.fix_row, fix_row.data(), fix_row.size(), st));
     TRON_TRY(upload(&A.fix_part, fix_part.data(), fix_part.size(), st));
@@ -434,6 +437,7 @@ struct PartArgs {
     int nchunks[kMaxParts];
     int nhot[kMaxParts];
     int P;
+    int slots;   // LDS table entries per workgroup (a multiple of 2; the tables are stored kHotSlots apart)
 };
 
 // Partitioned layout, persistent workgroups: workgroup (partition xp, q) walks chunks q, q + Q, ... of its
@@ -648,7 +652,7 @@ __device__ __forceinline__ void part_body(double *prod, double *table, const Par
     if (HOT) {
         // the vector entries of this partition's LDS-resident columns, gathered once per call by k_gather_hot
         const double2 *__restrict__ src = reinterpret_cast<const double2 *>(pp.hot_x + (size_t)xp * kHotSlots);
-        for (int k = tid; k < kHotSlots / 2; k += kBlock) reinterpret_cast<double2 *>(table)[k] = src[k];
+        for (int k = tid; k < pa.slots / 2; k += kBlock) reinterpret_cast<double2 *>(table)[k] = src[k];
         __syncthreads();
     }
     // col/val are padded to whole chunks (zeros)
@@ -693,36 +697,8 @@ template <bool HOT, bool HEAD>
 __global__ __launch_bounds__(kBlock) void k_csr_spmv_part(PartArgs pa, int64_t rows, PartPtrs pp, const double *__restrict__ x)
 {
     __shared__ __align__(16) double prod[kProdDoubles];
-    __shared__ double table[HOT ? kHotSlots : 1];
+    extern __shared__ __align__(16) double table[];   // pa.slots doubles (none without HOT)
     part_body<HOT, HEAD>(prod, table, pa, blockIdx.x % pa.P, blockIdx.x / pa.P, gridDim.x / pa.P, rows, pp, x);
-}
-
-// One chunk per workgroup (no LDS table): few registers, so many workgroups fit on a CU and the memory latency of
-// one is hidden by the others.  Loads are issued in two waves: {col/val stream, chunk table entry}, then
-// {gathers, flags, row ids}.
-__global__ __launch_bounds__(kBlock) void k_csr_spmv_part_np(PartArgs pa, int64_t rows, PartPtrs pp, const double *__restrict__ x)
-{
-    __shared__ __align__(16) double prod[kProdDoubles];
-    const int xp = blockIdx.x % pa.P;
-    const int c = blockIdx.x / pa.P;
-    if (c >= pa.nchunks[xp]) return;
-    const int32_t *col = static_cast<const int32_t *>(pp.col) + pa.base[xp];
-    const double *val = pp.val + pa.base[xp];
-    const StreamRegs<false> cur = load_stream<false>(col, val, (int64_t)c * kChunk);   // col/val are padded to whole chunks
-    const int4 tab = pp.chunk_tab[pa.chunk0[xp] + c];
-    double xg[4][2];
-#pragma unroll
-    for (int m = 0; m < 4; ++m) gather2<false, false>(cur, m, x, nullptr, xg[m]);
-    const SegRegs seg = load_segs(tab, pp.flags + ((int64_t)pa.chunk0[xp] + c) * kBlock, pp.seg_row + pa.seg0[xp]);
-#pragma unroll
-    for (int m = 0; m < 4; ++m) {
-        double2 p;
-        p.x = cur.v[m].x * xg[m][0];
-        p.y = cur.v[m].y * xg[m][1];
-        *reinterpret_cast<double2 *>(prod + prod_pos(m * kQuarter + threadIdx.x * 2)) = p;
-    }
-    __syncthreads();
-    chunk_segments(prod, seg, tab.y, tab.z > 0, pp.partial + (int64_t)xp * rows, pp.carry + pa.chunk0[xp] + c);
 }
 
 // ------------------------------------------------------------------ hot-row tiles (see HotTiles)
@@ -994,21 +970,22 @@ static int launch_hot_tiles(tron_dataset *ds, const CsrPlan &A, const double *x)
 }
 
 // ------------------------------------------------------------------ fix-up of split rows
-// One wavefront per split row: y[row] += factor * (carry[b0] + ... + carry[b0+cnt-1]).
-template <int EPI>
+// G lanes per split row: y[row] += factor * (carry[b0] + ... + carry[b0+cnt-1]).  G = 8 when no row spans more than
+// 64 chunks (one workgroup then fixes 32 rows), else a whole wavefront per row.
+template <int EPI, int G>
 __global__ __launch_bounds__(kBlock) void k_csr_fixup(int nfix, int64_t rows, const int32_t *__restrict__ fix_row,
                                                       const int32_t *__restrict__ fix_part, const int32_t *__restrict__ fix_b0,
                                                       const int32_t *__restrict__ fix_cnt, const double *__restrict__ carry,
                                                       double *__restrict__ yout, const double *__restrict__ aux, double alpha)
 {
-    const int m = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
-    if (m >= nfix) return;
-    const int lane = threadIdx.x & (kWave - 1);
-    const int b0 = fix_b0[m], cnt = fix_cnt[m];
+    const int m = blockIdx.x * (kBlock / G) + threadIdx.x / G;
+    const int sub = threadIdx.x & (G - 1);
+    const bool live = m < nfix;   // the lane sums below need every lane of the wavefront
+    const int b0 = live ? fix_b0[m] : 0, cnt = live ? fix_cnt[m] : 0;
     double s = 0.0;
-    for (int k = lane; k < cnt; k += kWave) s += carry[b0 + k];
-    s = wave_sum(s);
-    if (lane == 0) {
+    for (int k = sub; k < cnt; k += G) s += carry[b0 + k];
+    s = group_sum(s, G);
+    if (live && sub == 0) {
         const int64_t r = fix_row[m];
         double factor = 1.0;
         if (EPI == EPI_SCALE) factor = aux[r];
@@ -1016,6 +993,24 @@ __global__ __launch_bounds__(kBlock) void k_csr_fixup(int nfix, int64_t rows, co
         double *dst = yout + (int64_t)fix_part[m] * rows + r;   // fix_part is 0 when unpartitioned
         *dst = fma(factor, s, *dst);
     }
+}
+
+template <int EPI>
+static int launch_fixup(tron_dataset *ds, const CsrPlan &A, double *yout, const double *aux, double alpha)
+{
+    if (A.nfix <= 0) return TRON_OK;
+    ProfScope ps(ds, SLOT_SPMV_FIXUP);
+    if (A.fix_max_cnt <= 64) {
+        const int per = kBlock / 8;
+        hipLaunchKernelGGL((k_csr_fixup<EPI, 8>), dim3((A.nfix + per - 1) / per), dim3(kBlock), 0, ds->stream, A.nfix, A.rows, A.fix_row,
+                           A.fix_part, A.fix_b0, A.fix_cnt, A.carry, yout, aux, alpha);
+    } else {
+        const int per = kBlock / kWave;
+        hipLaunchKernelGGL((k_csr_fixup<EPI, kWave>), dim3((A.nfix + per - 1) / per), dim3(kBlock), 0, ds->stream, A.nfix, A.rows,
+                           A.fix_row, A.fix_part, A.fix_b0, A.fix_cnt, A.carry, yout, aux, alpha);
+    }
+    TRON_HIP(hipGetLastError());
+    return TRON_OK;
 }
 
 // ------------------------------------------------------------------ combine kernels (partitioned layout)
@@ -1105,13 +1100,7 @@ static int launch_plain(tron_dataset *ds, const CsrPlan &A, int slot, const doub
                            A.row_lo, x, yout, aux, alpha, A.carry);
         TRON_HIP(hipGetLastError());
     }
-    if (A.nfix > 0) {
-        ProfScope ps(ds, SLOT_SPMV_FIXUP);
-        const int grid = (A.nfix + kWavesPerBlock - 1) / kWavesPerBlock;
-        hipLaunchKernelGGL(k_csr_fixup<EPI>, dim3(grid), dim3(kBlock), 0, ds->stream, A.nfix, A.rows, A.fix_row, A.fix_part,
-                           A.fix_b0, A.fix_cnt, A.carry, yout, aux, alpha);
-        TRON_HIP(hipGetLastError());
-    }
+    TRON_TRY(launch_fixup<EPI>(ds, A, yout, aux, alpha));
     return TRON_OK;
 }
 
@@ -1128,6 +1117,7 @@ static PartArgs part_args(const CsrPlan &A)
         pa.nchunks[i] = A.part_nchunks[i];
         pa.nhot[i] = A.part_nhot[i];
     }
+    pa.slots = A.range_slots;
     return pa;
 }
 
@@ -1144,6 +1134,7 @@ static PartArgs head_args(const CsrPlan &A)
     ha.chunk0[0] = A.part_chunk0[h];
     ha.nchunks[0] = A.part_nchunks[h];
     ha.nhot[0] = A.part_nhot[h];
+    ha.slots = kHotSlots;
     return ha;
 }
 
@@ -1171,29 +1162,20 @@ static int launch_partials(tron_dataset *ds, const CsrPlan &A, int slot, const d
         }
         if (A.head >= 0) {
             const int grid = std::max(1, std::min(A.part_nchunks[A.head], (int)g_tuning.csr_hot_blocks_per_part * kColParts));
-            hipLaunchKernelGGL((k_csr_spmv_part<true, true>), dim3(grid), dim3(kBlock), 0, ds->stream, head_args(A), A.rows,
+            hipLaunchKernelGGL((k_csr_spmv_part<true, true>), dim3(grid), dim3(kBlock), kHotSlots * sizeof(double), ds->stream, head_args(A), A.rows,
                                head_ptrs(ds, A), x);
         }
-        const int want = (int)(A.hot_ids ? g_tuning.csr_hot_blocks_per_part : g_tuning.csr_blocks_per_part);
+        const int want = (int)(A.hot_ids ? g_tuning.csr_range_blocks_per_part : g_tuning.csr_blocks_per_part);
         const int per_part = std::max(1, std::min(A.max_chunks, want));
         if (A.hot_ids)
-            hipLaunchKernelGGL((k_csr_spmv_part<true, false>), dim3(per_part * A.P), dim3(kBlock), 0, ds->stream, pa, A.rows,
-                               part_ptrs(ds, A), x);
-        else if (g_tuning.csr_blocks_per_part > 0)
+            hipLaunchKernelGGL((k_csr_spmv_part<true, false>), dim3(per_part * A.P), dim3(kBlock), A.range_slots * sizeof(double), ds->stream,
+                               pa, A.rows, part_ptrs(ds, A), x);
+        else
             hipLaunchKernelGGL((k_csr_spmv_part<false, false>), dim3(per_part * A.P), dim3(kBlock), 0, ds->stream, pa, A.rows,
                                part_ptrs(ds, A), x);
-        else
-            hipLaunchKernelGGL(k_csr_spmv_part_np, dim3(A.max_chunks * A.P), dim3(kBlock), 0, ds->stream, pa, A.rows,
-                               part_ptrs(ds, A), x);
         TRON_HIP(hipGetLastError());
     }
-    if (A.nfix > 0) {
-        ProfScope ps(ds, SLOT_SPMV_FIXUP);
-        const int grid = (A.nfix + kWavesPerBlock - 1) / kWavesPerBlock;
-        hipLaunchKernelGGL(k_csr_fixup<EPI_PLAIN>, dim3(grid), dim3(kBlock), 0, ds->stream, A.nfix, A.rows, A.fix_row,
-                           A.fix_part, A.fix_b0, A.fix_cnt, A.carry, ds->row_partials, (const double *)nullptr, 0.0);
-        TRON_HIP(hipGetLastError());
-    }
+    TRON_TRY(launch_fixup<EPI_PLAIN>(ds, A, ds->row_partials, nullptr, 0.0));
     return TRON_OK;
 }
 

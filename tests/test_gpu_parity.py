@@ -103,6 +103,26 @@ def test_csr_partitioned_layout(rng, loss, force_partitions):
     check_calls(p, loss, 1.0, rng, n_hv=1)
 
 
+@pytest.mark.parametrize("knobs", [{"csr_head": 0}, {"csr_hot": 0}, {"csr_tiles": 0}, {"csr_range_slots": 64},
+                                   {"csr_blocks_per_part": 3, "csr_range_blocks_per_part": 2, "csr_hot_blocks_per_part": 1,
+                                    "csr_tile_blocks_per_slice": 2}])
+def test_csr_layout_variants(rng, force_partitions, knobs):
+    # every building block of the partitioned layout switched off or shrunk in turn: the ranges without the head
+    # partition, no LDS tables, no hot-row tiles, tiny tables, very few persistent workgroups (many chunks each)
+    import paper_2008_03433_amd as tron
+    defaults = {"csr_head": 1, "csr_hot": 1, "csr_tiles": 1, "csr_range_slots": 4096, "csr_blocks_per_part": 128,
+                "csr_range_blocks_per_part": 96, "csr_hot_blocks_per_part": 96, "csr_tile_blocks_per_slice": 96}
+    try:
+        for k, v in knobs.items():
+            tron.tron_tuning_set(k, v)
+        check_calls(dg.config2(), LOSS_LR, 1.0, rng, w_scale=1.0, n_hv=1)
+        p = dg.config3(scale=0.02)
+        check_calls(p, LOSS_L2SVM, 1.0, rng, w_scale=0.5, n_hv=1)
+    finally:
+        for k in knobs:
+            tron.tron_tuning_set(k, defaults[k])
+
+
 def test_solve_partitioned_layout(force_partitions):
     p = dg.config2()
     compare_solves(p, p.loss, p.C, p.eps)
