@@ -32,8 +32,9 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 ROCPROF_NAMES = {
     "dense_hv": ("k_dense_hv<6, 4, 4, true, true>", "dense_hv_fun_grad_c5.md"),
     "dense_fun_grad": ("k_dense_fun_grad<6, 4, 4, true, 1>", "dense_hv_fun_grad_c5.md"),
-    "spmv_fwd_a1": ("k_csr_spmv_part<true>", "csr_spmv_c3.md"),
-    "spmv_bwd_hv": ("k_csr_spmv_part_np", "csr_spmv_c3.md"),
+    "spmv_head": ("k_csr_spmv_part<true, true>", "csr_spmv_c3.md"),
+    "spmv_fwd": ("k_csr_spmv_part<true, false>", "csr_spmv_c3.md"),
+    "spmv_bwd": ("k_csr_spmv_part<false, false>", "csr_spmv_c3.md"),
     "spmv_tiles": ("k_hot_tiles", "csr_spmv_c3.md"),
 }
 
@@ -80,14 +81,16 @@ def algorithmic_bytes(ds, stat, kernel: str) -> float:
         return 8.0 * n * d + 8.0 * n                       # X once + D
     if kernel == "dense_fun_grad":
         return 8.0 * n * d + 16.0 * n                      # X once + y read + D written
-    if kernel == "spmv_fwd_a1":
-        return 12.0 * nnz + 24.0 * n + 8.0 * d             # col+val; rowptr, D, a1 written; v gathered
-    if kernel == "spmv_fwd_z":
-        return 12.0 * nnz + 16.0 * n + 8.0 * d
-    if kernel in ("spmv_bwd_hv", "spmv_bwd_g"):            # the CSR part of the transposed pass
-        return 12.0 * stat("bwd_csr_nnz") + 24.0 * d + 8.0 * n
-    if kernel == "spmv_tiles":                             # the tiled part of the transposed pass
-        return 12.0 * stat("bwd_tile_nnz")
+    # Sparse kernels: 12 B per nonzero they process, 8 B per element of the vector they gather from and of the
+    # row sums they write (their shares add up to the 24 nnz + O(n + d) of one Hv call).
+    if kernel == "spmv_head":                              # head partition of X: LDS-table gathers only
+        return 12.0 * stat("fwd_head_nnz") + 8.0 * n
+    if kernel == "spmv_fwd":                               # the rest of X (all of it when there is no head partition)
+        return 12.0 * (stat("fwd_csr_nnz") - stat("fwd_head_nnz")) + 8.0 * d + 8.0 * n
+    if kernel == "spmv_tiles":                             # hot rows of the transposed copy
+        return 12.0 * stat("bwd_tile_nnz") + 8.0 * n
+    if kernel == "spmv_bwd":                               # the rest of the transposed copy
+        return 12.0 * stat("bwd_csr_nnz") + 8.0 * n + 8.0 * d
     raise KeyError(kernel)
 
 
@@ -225,7 +228,7 @@ def run_workload(args, wname: str) -> dict:
 
     kernels = {k: {"ms": r["ms"] / r["calls"], "calls_per_hv": r["calls"] / args.hv_reps} for k, r in prof_hv.items()}
     kernels_fg = {k: {"ms": r["ms"] / r["calls"], "calls_per_fun_grad": r["calls"] / fg_reps} for k, r in prof_fg.items()}
-    big = [k for k in kernels if k in ("dense_hv", "spmv_fwd_a1", "spmv_bwd_hv", "spmv_tiles")]
+    big = [k for k in kernels if k in ("dense_hv", "spmv_head", "spmv_fwd", "spmv_bwd", "spmv_tiles")]
     dominant = max(big, key=lambda k: kernels[k]["ms"])
     dom_ms = kernels[dominant]["ms"]
     dom_bytes = algorithmic_bytes(ds, stat, dominant)
@@ -263,7 +266,7 @@ def run_workload(args, wname: str) -> dict:
         "roofline": roofline,
     }
     if not ds.dense:
-        out["layout"] = {k: stat(k) for k in ("fwd_parts", "bwd_parts", "fwd_csr_nnz", "fwd_lds_columns", "bwd_csr_nnz",
+        out["layout"] = {k: stat(k) for k in ("fwd_parts", "bwd_parts", "fwd_csr_nnz", "fwd_head_nnz", "fwd_lds_columns", "bwd_csr_nnz",
                                              "bwd_tile_nnz", "bwd_tile_rows", "bwd_tiles")}
     if not args.no_cpu_baseline:
         log("timing the CPU oracle (one thread, bounded sample)")

@@ -97,6 +97,7 @@ TRON_API int tron_dataset_shape(const tron_dataset *ds, int64_t *n, int64_t *d, 
  * Layout statistics of a handle (what the library built from the input), by name:
  *   "fwd_parts", "bwd_parts"   column partitions of the forward / transposed CSR layouts (0 for dense)
  *   "fwd_csr_nnz", "bwd_csr_nnz"  nonzeros held in those CSR layouts
+ *   "fwd_head_nnz"             of fwd_csr_nnz, the nonzeros of the head partition (the most frequent columns)
  *   "bwd_tile_nnz", "bwd_tile_rows", "bwd_tiles"  nonzeros, features and tiles of the hot-row tiles
  *   "fwd_lds_columns"          columns served from LDS tables in the forward pass
  *   "dense_grid"               workgroups of the dense kernels
@@ -205,6 +206,14 @@ TRON_API int tron_probe_read_bandwidth(const double *src_dev, int64_t count, int
  * floating-point summation order.
  *   "csr_parts": column partitions of the two CSR layouts: 0 = automatic (8 when the gathered
  *                vector would not stay resident in one L2, else 1), 1 = never partition, 8 = always.
+ * Partitioned layouts only:
+ *   "csr_hot" (0/1): LDS tables of frequent columns in the forward layout;
+ *   "csr_head" (0/1): a head partition for the most frequent columns of the whole matrix (needs csr_hot);
+ *   "csr_range_slots" (2..4096): LDS table entries per column range;
+ *   "csr_tiles" (0/1): hot-row tiles for the transposed product;
+ *   "csr_two_streams" (0/1): tiles on a second stream;
+ *   "csr_hot_blocks_per_part", "csr_range_blocks_per_part", "csr_blocks_per_part",
+ *   "csr_tile_blocks_per_slice": persistent workgroups of the head, table, table-less and tile kernels.
  * Unknown names or values return TRON_EINVAL.
  */
 TRON_API int tron_tuning_set(const char *name, int64_t value);

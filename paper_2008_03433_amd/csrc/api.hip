@@ -32,7 +32,7 @@ int hip_fail(hipError_t e, const char *what, const char *file, int line)
 
 // ------------------------------------------------------------------ profiler
 const char *const kSlotNames[SLOT_COUNT] = {
-    "spmv_fwd_z", "spmv_fwd_a1", "spmv_bwd_g", "spmv_bwd_hv", "spmv_fixup", "spmv_combine", "spmv_tiles", "loss_terms",
+    "spmv_fwd", "spmv_bwd", "spmv_head", "spmv_tiles", "spmv_tile_reduce", "spmv_gather", "spmv_fixup", "spmv_combine", "loss_terms",
     "dense_fun_grad", "dense_hv", "dense_finalize", "dot", "reduce_final", "cg_vec"};
 
 int Profiler::begin(int slot, hipStream_t st)
@@ -366,6 +366,7 @@ int tron_dataset_stat(const tron_dataset *ds, const char *name, int64_t *value)
         {"fwd_parts", ds->dense ? 0 : ds->fwd.P},
         {"bwd_parts", ds->dense ? 0 : ds->bwd.P},
         {"fwd_csr_nnz", ds->dense ? 0 : ds->fwd.nnz},
+        {"fwd_head_nnz", (ds->dense || ds->fwd.head < 0) ? 0 : ds->fwd.part_nnz[ds->fwd.head]},
         {"bwd_csr_nnz", ds->dense ? 0 : ds->bwd.nnz},
         {"bwd_tile_nnz", ds->dense ? 0 : ds->bwd.hot.nnz},
         {"bwd_tile_rows", ds->dense ? 0 : ds->bwd.hot.nhot},

@@ -53,13 +53,14 @@ constexpr int kScalars = 16;         // scalar slots shared by the reductions
 
 // ---------------------------------------------------------------- profiling slots
 enum Slot {
-    SLOT_SPMV_FWD_Z = 0,   // z = X w
-    SLOT_SPMV_FWD_A1,      // a1 = D .* (X v)
-    SLOT_SPMV_BWD_G,       // g = w + C X^T zhat
-    SLOT_SPMV_BWD_HV,      // Hv = v + C X^T a1
-    SLOT_SPMV_FIXUP,       // rows split across workgroups
-    SLOT_SPMV_COMBINE,     // sum of the column partitions' partial row sums + epilogue
+    SLOT_SPMV_FWD = 0,     // X times a vector: the chunk kernel (unpartitioned) or the kernel over the column ranges
+    SLOT_SPMV_BWD,         // the same for the transposed copy
+    SLOT_SPMV_HEAD,        // head partition of X (most frequent columns)
     SLOT_SPMV_TILES,       // hot-row tiles of the transposed product
+    SLOT_SPMV_TILE_REDUCE, // sum of the tiles' workgroup accumulators
+    SLOT_SPMV_GATHER,      // vector entries of the LDS-resident columns
+    SLOT_SPMV_FIXUP,       // rows split across workgroups
+    SLOT_SPMV_COMBINE,     // sum of the partitions' partial row sums + epilogue
     SLOT_LOSS_TERMS,       // zhat, D, sum loss from z
     SLOT_DENSE_FUN_GRAD,   // fused dense z / loss / D / X^T zhat
     SLOT_DENSE_HV,         // fused dense X^T (D (X v))

@@ -961,6 +961,10 @@ static int launch_hot_tiles(tron_dataset *ds, const CsrPlan &A, const double *x)
         ProfScope ps(ds, SLOT_SPMV_TILES, st);
         hipLaunchKernelGGL(k_hot_tiles, dim3(kTileSlices * H.blocks_per_slice), dim3(kBlock), 0, st, tile_args(H), H.blocks_per_slice,
                            tile_ptrs(H), x);
+        TRON_HIP(hipGetLastError());
+    }
+    {
+        ProfScope ps(ds, SLOT_SPMV_TILE_REDUCE, st);
         hipLaunchKernelGGL(k_hot_reduce, dim3(kTileSlices * kTileSlots / kWave), dim3(kBlock), 0, st, H.blocks_per_slice,
                            H.wg_acc, H.sums);
         TRON_HIP(hipGetLastError());
@@ -1154,17 +1158,21 @@ static PartPtrs head_ptrs(const tron_dataset *ds, const CsrPlan &A)
 static int launch_partials(tron_dataset *ds, const CsrPlan &A, int slot, const double *x)
 {
     const PartArgs pa = part_args(A);
+    if (A.hot_ids) {
+        ProfScope ps(ds, SLOT_SPMV_GATHER);
+        const int nh = (A.P + 1) * kHotSlots;
+        hipLaunchKernelGGL(k_gather_hot, dim3((nh + kBlock - 1) / kBlock), dim3(kBlock), 0, ds->stream, nh, A.hot_ids, x, A.hot_x);
+        TRON_HIP(hipGetLastError());
+    }
+    if (A.head >= 0) {
+        ProfScope ps(ds, SLOT_SPMV_HEAD);
+        const int grid = std::max(1, std::min(A.part_nchunks[A.head], (int)g_tuning.csr_hot_blocks_per_part * kColParts));
+        hipLaunchKernelGGL((k_csr_spmv_part<true, true>), dim3(grid), dim3(kBlock), kHotSlots * sizeof(double), ds->stream,
+                           head_args(A), A.rows, head_ptrs(ds, A), x);
+        TRON_HIP(hipGetLastError());
+    }
     {
         ProfScope ps(ds, slot);
-        if (A.hot_ids) {
-            const int nh = (A.P + 1) * kHotSlots;
-            hipLaunchKernelGGL(k_gather_hot, dim3((nh + kBlock - 1) / kBlock), dim3(kBlock), 0, ds->stream, nh, A.hot_ids, x, A.hot_x);
-        }
-        if (A.head >= 0) {
-            const int grid = std::max(1, std::min(A.part_nchunks[A.head], (int)g_tuning.csr_hot_blocks_per_part * kColParts));
-            hipLaunchKernelGGL((k_csr_spmv_part<true, true>), dim3(grid), dim3(kBlock), kHotSlots * sizeof(double), ds->stream, head_args(A), A.rows,
-                               head_ptrs(ds, A), x);
-        }
         const int want = (int)(A.hot_ids ? g_tuning.csr_range_blocks_per_part : g_tuning.csr_blocks_per_part);
         const int per_part = std::max(1, std::min(A.max_chunks, want));
         if (A.hot_ids)
