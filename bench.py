@@ -188,8 +188,11 @@ def run_workload(args, wname: str) -> dict:
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     n_hv = 0
+    solve_times = []
     for _ in range(args.steps):
-        res = one_solve()
+        t1 = time.perf_counter()
+        res = one_solve()          # returns after the solver's last scalar read-back: the stream is idle
+        solve_times.append(time.perf_counter() - t1)
         n_hv += res.n_hv
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
@@ -211,6 +214,14 @@ def run_workload(args, wname: str) -> dict:
         ds.hv(C, v, Hv, want_vHv=False)
     torch.cuda.synchronize()
     hv_s = (time.perf_counter() - t0) / args.hv_reps
+    # per-call times with events on the handle's stream (it is torch's current stream)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.hv_reps)]
+    for a, b in evs:
+        a.record()
+        ds.hv(C, v, Hv, want_vHv=False)
+        b.record()
+    torch.cuda.synchronize()
+    hv_each = sorted(a.elapsed_time(b) for a, b in evs)
     fg_reps = max(3, args.hv_reps // 4)
     t0 = time.perf_counter()
     for _ in range(fg_reps):
@@ -257,9 +268,10 @@ def run_workload(args, wname: str) -> dict:
                    "tune": args.tune, "setup_seconds": setup_s},
         "solve": {"seconds": solve_s, "outer_iters": res.outer_iters, "cg_iters": res.cg_iters_total, "n_fun": res.n_fun,
                   "n_grad": res.n_grad, "n_hv": res.n_hv, "f": res.f, "gnorm": res.gnorm, "gnorm0": res.gnorm0,
-                  "converged": res.converged},
+                  "converged": res.converged, "min_seconds": min(solve_times)},
         "hv_call": {"per_s": 1.0 / hv_s, "ms": hv_s * 1e3, "GB/s": hv_call_bytes(ds) / hv_s / 1e9,
-                    "frac_hbm_peak": hv_call_bytes(ds) / hv_s / 1e9 / HBM_PEAK_GBS, "algorithmic_bytes": hv_call_bytes(ds)},
+                    "frac_hbm_peak": hv_call_bytes(ds) / hv_s / 1e9 / HBM_PEAK_GBS, "algorithmic_bytes": hv_call_bytes(ds),
+                    "event_ms_median": hv_each[len(hv_each) // 2], "event_ms_min": hv_each[0]},
         "fun_grad_call": {"per_s": 1.0 / fg_s, "ms": fg_s * 1e3},
         "kernels_hv": with_rates(kernels),
         "kernels_fun_grad": with_rates(kernels_fg),
@@ -276,6 +288,28 @@ def run_workload(args, wname: str) -> dict:
     ds.close()
     del ds, w, g, v, Hv
     torch.cuda.empty_cache()
+    return out
+
+
+def small_config(args, wname: str) -> dict:
+    """The small configurations (cache-resident / launch-bound): solve and call times, and the oracle's full solve."""
+    sub = run_workload(argparse.Namespace(**{**vars(args), "no_cpu_baseline": True, "steps": 5, "warmup": 1}), wname)
+    out = {"config": sub["config"]["workload"], "solve_ms": sub["ms_per_step"], "solve_min_ms": sub["solve"]["min_seconds"] * 1e3,
+           "outer_iters": sub["solve"]["outer_iters"], "cg_iters": sub["solve"]["cg_iters"], "f": sub["solve"]["f"],
+           "hv_ms": sub["hv_call"]["ms"], "hv_effective_GB/s": sub["hv_call"]["GB/s"], "fun_grad_ms": sub["fun_grad_call"]["ms"],
+           "kernels_hv": sub["kernels_hv"], "cpu_baseline": None}
+    if not args.no_cpu_baseline:
+        import datagen as dg
+        from oracle import Oracle
+        workload = make_workload(wname, 1.0)
+        loss, C, eps = (dg.LOSS_L2SVM, 0.1, 0.01) if wname == "c4" else (dg.LOSS_LR, 1.0, 0.01)
+        o = Oracle.from_problem(workload)
+        t0 = time.perf_counter()
+        ref = o.tron(loss, C, eps)
+        t_solve = time.perf_counter() - t0
+        out["cpu_baseline"] = {"kind": "oracle", "cores": 1, "solve_seconds": t_solve, "f": ref.f,
+                               "outer_iters": ref.outer_iters, "cg_iters": ref.cg_iters_total,
+                               "value": ref.n_hv / t_solve, "unit": "Hv/s", "sample": "one full solve"}
     return out
 
 
@@ -329,6 +363,8 @@ def main() -> int:
         sub = run_workload(args, also)
         keep = ("value", "unit", "ms_per_step", "config", "solve", "hv_call", "fun_grad_call", "kernels_hv", "kernels_fun_grad", "roofline", "cpu_baseline")
         out["also"] = {also: {k: sub[k] for k in keep}}
+    if args.workload == "c3" and args.scale == 1.0 and args.also is None:
+        out["others"] = {w: small_config(args, w) for w in ("c1", "c2", "c4")}
     print(json.dumps(out), flush=True)
     return 0
 

@@ -627,6 +627,16 @@ __global__ __launch_bounds__(kBlock) void k_gather_hot(int n, const int32_t *__r
     if (k < n) hot_x[k] = x[hot_ids[k]];
 }
 
+// A table entry that every thread of the workgroup needs, fetched with a vector load.  A scalar load would be counted
+// by the same counter as the LDS operations, so the wait for LDS before the next barrier would also wait for it --
+// a full memory latency in every iteration of the persistent loops, which prefetch these entries two chunks ahead.
+__device__ __forceinline__ int4 load_uniform(const int4 *__restrict__ p)
+{
+    int zero;
+    asm volatile("v_mov_b32 %0, 0" : "=v"(zero));   // a lane-dependent zero as far as the compiler can tell
+    return p[zero];
+}
+
 struct PartPtrs {   // device arrays of one partitioned plan (or of its head partition, pre-offset where noted)
     const void *col;           // int32 columns of the ranges, or the head's 16-bit slots
     const double *val;
@@ -666,8 +676,8 @@ __device__ __forceinline__ void part_body(double *prod, double *table, const Par
     double *carry = pp.carry + pa.chunk0[xp];
 
     int c = q;
-    int4 tab = tabs[c];
-    int4 tab_n = tabs[(c + Q < nchunks) ? c + Q : c];
+    int4 tab = load_uniform(tabs + c);
+    int4 tab_n = load_uniform(tabs + ((c + Q < nchunks) ? c + Q : c));
     StreamRegs<HEAD> cur = load_stream<HEAD>(col, val, (int64_t)c * kChunk);
     SegRegs seg = load_segs(tab, flags + (int64_t)c * kBlock, seg_row);
 
@@ -681,7 +691,7 @@ __device__ __forceinline__ void part_body(double *prod, double *table, const Par
         const int cnn = (cn + Q < nchunks) ? cn + Q : cn;
         const StreamRegs<HEAD> nxt = load_stream<HEAD>(col, val, (int64_t)cn * kChunk);
         const SegRegs seg_n = load_segs(tab_n, flags + (int64_t)cn * kBlock, seg_row);
-        const int4 tab_nn = tabs[cnn];
+        const int4 tab_nn = load_uniform(tabs + cnn);
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
         chunk_segments(prod, seg, tab.y, tab.z > 0, partial, carry + c);
@@ -855,9 +865,9 @@ __device__ __forceinline__ void tiles_body(double *prod, uint16_t *slots, double
         const int64_t T0 = ta.tile0[s];
         const int64_t last = nt - 1;
         auto clampt = [&](int64_t t) { return T0 + (t < last ? t : last); };
-        TileRegs cur = load_tile(tp, tp.hdr[clampt(q)], clampt(q));
-        TileRegs nxt = load_tile(tp, tp.hdr[clampt(q + B)], clampt(q + B));
-        int4 hdr2 = tp.hdr[clampt(q + 2 * (int64_t)B)];
+        TileRegs cur = load_tile(tp, load_uniform(tp.hdr + clampt(q)), clampt(q));
+        TileRegs nxt = load_tile(tp, load_uniform(tp.hdr + clampt(q + B)), clampt(q + B));
+        int4 hdr2 = load_uniform(tp.hdr + clampt(q + 2 * (int64_t)B));
         for (int64_t t = q; t < nt; t += B) {
             const int nseg = cur.hdr.y;
             const double *xt = x + cur.hdr.x;   // the tile's first column
@@ -877,7 +887,7 @@ __device__ __forceinline__ void tiles_body(double *prod, uint16_t *slots, double
             }
             __builtin_amdgcn_sched_barrier(0);
             const TileRegs nn = load_tile(tp, hdr2, clampt(t + 2 * (int64_t)B));
-            const int4 hdr3 = tp.hdr[clampt(t + 3 * (int64_t)B)];
+            const int4 hdr3 = load_uniform(tp.hdr + clampt(t + 3 * (int64_t)B));
             __builtin_amdgcn_sched_barrier(0);
             __syncthreads();
             // every thread is past the accumulator updates of the tile before: its slots may be replaced
