@@ -66,7 +66,10 @@ def _L(plain_fp64: bool = False):
         lib.orc_hv.argtypes = [P(_Data), dbl, vp, vp, vp]
         lib.orc_cg.argtypes = [P(_Data), dbl, vp, vp, dbl, dbl, ci, vp, vp, P(ci), P(ci)]
         lib.orc_tron.argtypes = [P(_Data), ci, dbl, dbl, ci, ci, dbl, vp, P(_Result), P(TraceRec), ci, P(ci)]
-        for f in (lib.orc_fun, lib.orc_grad, lib.orc_hv, lib.orc_cg, lib.orc_tron):
+        lib.orc_hess_diag.argtypes = [P(_Data), dbl, vp, vp]
+        lib.orc_pcg.argtypes = [P(_Data), dbl, vp, vp, vp, dbl, dbl, ci, vp, vp, P(ci), P(ci)]
+        lib.orc_tron_pcg.argtypes = [P(_Data), ci, dbl, dbl, ci, ci, dbl, dbl, vp, P(_Result), P(TraceRec), ci, P(ci)]
+        for f in (lib.orc_fun, lib.orc_grad, lib.orc_hv, lib.orc_cg, lib.orc_tron, lib.orc_hess_diag, lib.orc_pcg, lib.orc_tron_pcg):
             f.restype = ci
         _libs[plain_fp64] = lib
     return _libs[plain_fp64]
@@ -160,13 +163,37 @@ class Oracle:
         assert rc == 0
         return s, r, nhv.value, bool(onb.value)
 
+    def hess_diag(self, C: float, D):
+        """diag(H) = 1 + C sum_i D_i x_ij^2."""
+        D = _f64(D)
+        hd = np.empty(self.d)
+        rc = _L(self._plain).orc_hess_diag(ctypes.byref(self._c), C, D.ctypes.data, hd.ctypes.data)
+        assert rc == 0
+        return hd
+
+    def pcg(self, C: float, D, g, M, delta: float, xi: float = 0.1, max_cg: int = 1000):
+        """Steihaug-Toint iteration preconditioned by the diagonal M, trust region in the M-norm."""
+        D, g, M = _f64(D), _f64(g), _f64(M)
+        s = np.empty(self.d); r = np.empty(self.d)
+        nhv, onb = ctypes.c_int(), ctypes.c_int()
+        rc = _L(self._plain).orc_pcg(ctypes.byref(self._c), C, D.ctypes.data, g.ctypes.data, M.ctypes.data, delta, xi,
+                                     max_cg, s.ctypes.data, r.ctypes.data, ctypes.byref(nhv), ctypes.byref(onb))
+        assert rc == 0
+        return s, r, nhv.value, bool(onb.value)
+
     def tron(self, loss: int, C: float, eps: float, w0=None, max_outer: int = 1000, max_cg: int = 1000,
-             xi: float = 0.1, trace_cap: int = 1024) -> SolveResult:
+             xi: float = 0.1, trace_cap: int = 1024, precond_blend=None) -> SolveResult:
+        """precond_blend = None: plain CG; a number a in (0, 1]: CG preconditioned by (1-a) I + a diag(H)."""
         w = np.zeros(self.d) if w0 is None else _f64(w0).copy()
         res = _Result()
         trace = (TraceRec * trace_cap)()
         tl = ctypes.c_int()
-        rc = _L(self._plain).orc_tron(ctypes.byref(self._c), loss, C, eps, max_outer, max_cg, xi, w.ctypes.data,
+        if precond_blend is not None:
+            rc = _L(self._plain).orc_tron_pcg(ctypes.byref(self._c), loss, C, eps, max_outer, max_cg, xi,
+                                              float(precond_blend), w.ctypes.data, ctypes.byref(res), trace, trace_cap,
+                                              ctypes.byref(tl))
+        else:
+            rc = _L(self._plain).orc_tron(ctypes.byref(self._c), loss, C, eps, max_outer, max_cg, xi, w.ctypes.data,
                            ctypes.byref(res), trace, trace_cap, ctypes.byref(tl))
         assert rc >= 0
         recs = [{k: getattr(trace[i], k) for k, _ in TraceRec._fields_} for i in range(tl.value)]

@@ -408,6 +408,142 @@ def test_tron_respects_iteration_cap(rng):
 
 
 # ----------------------------------------------------------------------------
+# diagonal preconditioner (the paper only names it; pins = what the mathematics fixes)
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("loss", [LOSS_LR, LOSS_L2SVM])
+@pytest.mark.parametrize("layout", ["dense", "csr"])
+def test_hess_diag_is_the_diagonal_of_the_explicit_hessian(rng, loss, layout):
+    n, d, C = 70, 9, 0.7
+    X, y = _dense_problem(rng, n, d, density=0.6)
+    if layout == "dense":
+        o = Oracle(n=n, d=d, y=y, X=X)
+    else:
+        rowptr, col, val = _to_csr(X)
+        o = Oracle(n=n, d=d, y=y, rowptr=rowptr, col=col, val=val)
+    _, _, D = o.fun_grad(loss, C, 0.4 * rng.standard_normal(d))
+    H = np.eye(d) + C * X.T @ (X * D[:, None])
+    np.testing.assert_allclose(o.hess_diag(C, D), np.diag(H), rtol=1e-13)
+    # and of the operator itself: e_j . H e_j
+    for j in (0, d // 2, d - 1):
+        e = np.zeros(d); e[j] = 1.0
+        assert o.hess_diag(C, D)[j] == pytest.approx(o.hv(C, D, e)[j], rel=1e-13)
+
+
+def test_pcg_with_identity_preconditioner_is_cg(rng):
+    o, C, D, g, H = _explicit_system(rng)
+    ones = np.ones(len(g))
+    for delta, xi, cap in ((1e30, 1e-14, 8), (0.3 * np.linalg.norm(np.linalg.solve(H, -g)), 1e-12, 50), (1e30, 0.1, 100)):
+        a = o.cg(C, D, g, delta=delta, xi=xi, max_cg=cap)
+        b = o.pcg(C, D, g, ones, delta=delta, xi=xi, max_cg=cap)
+        np.testing.assert_array_equal(a[0], b[0])
+        np.testing.assert_array_equal(a[1], b[1])
+        assert a[2:] == b[2:]
+
+
+def test_pcg_unconstrained_solves_newton_system(rng):
+    o, C, D, g, H = _explicit_system(rng)
+    d = len(g)
+    M = 0.99 + 0.01 * np.diag(H)
+    s, r, nhv, onb = o.pcg(C, D, g, M, delta=1e30, xi=1e-14, max_cg=d)
+    assert not onb and nhv <= d
+    np.testing.assert_allclose(s, np.linalg.solve(H, -g), rtol=1e-9, atol=1e-12)
+    np.testing.assert_allclose(r, -g - H @ s, rtol=0, atol=1e-12)
+    # exact diagonal scaling of a diagonal system: one product solves it (a diagonal X makes H diagonal)
+    n = 12
+    y = np.where(rng.random(n) < 0.5, 1.0, -1.0)
+    oi = Oracle(n=n, d=n, y=y, X=np.diag(rng.uniform(0.5, 3.0, n)))
+    _, gi, Di = oi.fun_grad(LOSS_LR, 2.0, rng.standard_normal(n))
+    hd = oi.hess_diag(2.0, Di)
+    s1, _, n1, _ = oi.pcg(2.0, Di, gi, hd, delta=1e30, xi=1e-13, max_cg=n)
+    assert n1 == 1
+    np.testing.assert_allclose(s1, -gi / hd, rtol=1e-13)
+
+
+def test_pcg_residuals_are_conjugate_in_the_inverse_preconditioner(rng):
+    o, C, D, g, H = _explicit_system(rng)
+    M = rng.uniform(0.5, 4.0, len(g))
+    res = [-g] + [o.pcg(C, D, g, M, delta=1e30, xi=0.0, max_cg=k)[1] for k in range(1, 5)]
+    for a in range(len(res)):
+        for b in range(a):
+            cosang = (res[a] / M) @ res[b] / np.sqrt(((res[a] / M) @ res[a]) * ((res[b] / M) @ res[b]))
+            assert abs(cosang) < 1e-10
+
+
+def test_pcg_equals_cg_on_the_scaled_variables(rng):
+    # PCG with M on (H, g) is CG on (M^-1/2 H M^-1/2, M^-1/2 g) in the variables M^1/2 s; the scaled system is
+    # solved here with a few lines of textbook CG in numpy
+    o, C, D, g, H = _explicit_system(rng)
+    M = rng.uniform(0.5, 4.0, len(g))
+    Hs = H / np.sqrt(M)[:, None] / np.sqrt(M)[None, :]
+    gs = g / np.sqrt(M)
+    for k in (1, 2, 3, 5):
+        u = np.zeros_like(gs); r = -gs.copy(); p = r.copy()
+        for _ in range(k):
+            Hp = Hs @ p
+            al = (r @ r) / (p @ Hp)
+            u = u + al * p
+            rn = r - al * Hp
+            p = rn + (rn @ rn) / (r @ r) * p
+            r = rn
+        s, rr, nhv, onb = o.pcg(C, D, g, M, delta=1e30, xi=0.0, max_cg=k)
+        assert nhv == k and not onb
+        np.testing.assert_allclose(s, u / np.sqrt(M), rtol=1e-10, atol=1e-13)
+        np.testing.assert_allclose(rr, r * np.sqrt(M), rtol=1e-9, atol=1e-12)
+
+
+def test_pcg_boundary_step_is_measured_in_the_m_norm(rng):
+    o, C, D, g, H = _explicit_system(rng)
+    M = rng.uniform(0.5, 4.0, len(g))
+    mnorm = lambda u: np.sqrt(u @ (M * u))
+    newton = np.linalg.solve(H, -g)
+    delta = 0.3 * mnorm(newton)
+    s, r, nhv, onb = o.pcg(C, D, g, M, delta=delta, xi=1e-12, max_cg=50)
+    assert onb
+    assert mnorm(s) == pytest.approx(delta, rel=1e-14)
+    np.testing.assert_allclose(r, -g - H @ s, rtol=0, atol=1e-12)
+    # a tiny radius: one product, the step is -delta M^-1 g / |M^-1 g|_M
+    tiny = 1e-3 * delta / np.linalg.norm(H, 2)
+    s1, _, n1, onb1 = o.pcg(C, D, g, M, delta=tiny, xi=1e-12, max_cg=50)
+    assert onb1 and n1 == 1
+    np.testing.assert_allclose(s1, -tiny * (g / M) / mnorm(g / M), rtol=1e-12, atol=1e-16)
+    # the model value is no worse than at the scaled Cauchy point
+    q = lambda u: g @ u + 0.5 * u @ H @ u
+    dirn = -g / M
+    tc = min(-(g @ dirn) / (dirn @ H @ dirn), delta / mnorm(dirn))
+    assert q(s) <= q(tc * dirn) + 1e-14
+
+
+@pytest.mark.parametrize("loss", [LOSS_LR, LOSS_L2SVM])
+def test_preconditioned_tron_reaches_the_same_minimiser(rng, loss):
+    n, d, C = 200, 20, 1.0
+    X, y = _dense_problem(rng, n, d)
+    X[:, :3] *= 30.0          # badly scaled features: what the diagonal is for
+    w_star, gn = _newton_minimise(X, y, loss, C)
+    assert gn <= 1e-9
+    o = Oracle(n=n, d=d, y=y, X=X)
+    res = o.tron(loss, C, eps=1e-10, precond_blend=0.01)
+    assert res.converged
+    assert np.linalg.norm(res.w - w_star) <= 1e-7 * np.linalg.norm(w_star)
+    assert res.f == pytest.approx(_f_numpy(X, y, w_star, loss, C), rel=1e-12)
+    fs = [t["f"] for t in res.trace if t["accepted"]]
+    assert all(b <= a for a, b in zip(fs, fs[1:]))
+    assert res.n_hv == sum(t["cg_iters"] for t in res.trace)
+    # blend = 1 (pure diagonal) also converges there
+    res1 = o.tron(loss, C, eps=1e-10, precond_blend=1.0)
+    assert res1.converged and np.linalg.norm(res1.w - w_star) <= 1e-7 * np.linalg.norm(w_star)
+
+
+def test_preconditioned_tron_on_identity_features(rng):
+    # X = I: H is diagonal, so with blend = 1 every inner solve is exact after one product
+    n, C = 25, 0.8
+    y = np.where(rng.random(n) < 0.5, 1.0, -1.0)
+    o = Oracle(n=n, d=n, y=y, X=np.eye(n))
+    res = o.tron(LOSS_L2SVM, C, eps=1e-12, precond_blend=1.0)
+    np.testing.assert_allclose(res.w, 2 * C * y / (1 + 2 * C), rtol=1e-10)
+    assert all(t["cg_iters"] <= 1 for t in res.trace)
+
+
+# ----------------------------------------------------------------------------
 # how much of a trajectory does the arithmetic fix?  (oracle vs its plain-fp64 twin)
 # ----------------------------------------------------------------------------
 def test_rounding_alone_moves_the_eps_0p01_iterate_on_zipf_data():
