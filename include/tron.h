@@ -129,6 +129,13 @@ TRON_API int tron_fun_grad(tron_dataset *ds, int loss, double C, const double *w
  */
 TRON_API int tron_hv(tron_dataset *ds, double C, const double *v_dev, double *Hv_dev, double *vHv_host);
 
+/*
+ * Diagonal of the Hessian at the w of the last tron_fun_grad (Appendix B: H = I + C X^T D X):
+ *   hd_j = 1 + C sum_i D_i x_ij^2.
+ * hd_dev: device pointer, d doubles.  Synchronises the stream.  TRON_ESTATE if no D is cached.
+ */
+TRON_API int tron_hess_diag(tron_dataset *ds, double C, double *hd_dev);
+
 /* ------------------------------------------------------------------------------------------
  * Full solve: Algorithm 1 with the conjugate-gradient inner solver, all vectors on the device;
  * only scalars reach the host.
@@ -140,6 +147,7 @@ typedef struct {
     int max_outer;  /* > 0 */
     int max_cg;     /* > 0: cap on Hessian-vector products per outer iteration */
     double cg_xi;   /* in (0,1): CG stops when |r| <= cg_xi |g| */
+    double precond_blend; /* 0: plain CG.  a in (0,1]: CG preconditioned by the diagonal M = (1-a) I + a diag(H) */
 } tron_params;
 
 typedef struct {
@@ -152,7 +160,7 @@ typedef struct {
     double delta;     /* radius after the update */
     double ared;      /* f(w) - f(w+s) */
     double pred;      /* -q(s) */
-    double snorm;     /* |s| */
+    double snorm;     /* |s| (with a preconditioner: the M-norm sqrt(s.Ms)) */
 } tron_trace_rec;
 
 typedef struct {
@@ -170,6 +178,10 @@ typedef struct {
  *   Delta_0 = |g(w0)|;  accept iff sigma = ared/pred > 1e-4;  sigma < 1/4: Delta = min(|s|,Delta)/2;
  *   sigma < 3/4: unchanged;  else Delta = min(4 Delta, max(Delta, 4|s|));  when |ared| and pred are
  *   both below 1e-12 |f| sigma is taken as 1;  CG is Steihaug's truncated iteration.
+ * With precond_blend = a > 0 the inner solver is preconditioned by M = (1-a) I + a diag(H(w)), rebuilt at every
+ * accepted iterate: the trust region and |s| are then measured in the M-norm, Delta_0 = sqrt(g.M^-1 g), CG stops when
+ * sqrt(r.M^-1 r) <= cg_xi sqrt(g.M^-1 g).  (The paper names a preconditioner -- Sections 2, 4.3, Appendix D -- without
+ * giving it; this is the diagonal one of the work it cites, a = 0.01 being that work's choice.)
  * Returns TRON_OK when converged, TRON_EMAXITER when max_outer was reached or progress stalled.
  * On return the handle caches D at the final iterate (so tron_hv may follow).
  */

@@ -25,7 +25,8 @@ class TronError(RuntimeError):
 
 
 class _Params(ctypes.Structure):
-    _fields_ = [("loss", _int), ("C", _dbl), ("eps", _dbl), ("max_outer", _int), ("max_cg", _int), ("cg_xi", _dbl)]
+    _fields_ = [("loss", _int), ("C", _dbl), ("eps", _dbl), ("max_outer", _int), ("max_cg", _int), ("cg_xi", _dbl),
+                ("precond_blend", _dbl)]
 
 
 class TraceRec(ctypes.Structure):
@@ -51,6 +52,7 @@ _SIGNATURES = {
     "tron_fun_grad": (_int, [_vp, _int, _dbl, _vp, ctypes.POINTER(_dbl), _vp]),
     "tron_hv": (_int, [_vp, _dbl, _vp, _vp, ctypes.POINTER(_dbl)]),
     "tron_solve": (_int, [_vp, ctypes.POINTER(_Params), _vp, ctypes.POINTER(_Result)]),
+    "tron_hess_diag": (_int, [_vp, _dbl, _vp]),
     "tron_last_error": (ctypes.c_char_p, []),
     "tron_profile_enable": (_int, [_vp, _int]),
     "tron_profile_read": (_int, [_vp, _int, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(_dbl), ctypes.POINTER(_i64), ctypes.POINTER(_int)]),
@@ -179,6 +181,11 @@ def tron_hv(ds, C, v, Hv, want_vHv=True) -> Optional[float]:
     return None
 
 
+def tron_hess_diag(ds, C, hd) -> None:
+    """hd (CUDA tensor, d doubles) = diagonal of the Hessian at the w of the last tron_fun_grad."""
+    _check(load_library().tron_hess_diag(ds, C, _ptr(hd)))
+
+
 @dataclass
 class SolveResult:
     f: float
@@ -194,9 +201,9 @@ class SolveResult:
     trace: List[dict]
 
 
-def tron_solve(ds, loss, C, eps, w, max_outer=1000, max_cg=1000, cg_xi=0.1, trace_cap=1024) -> SolveResult:
+def tron_solve(ds, loss, C, eps, w, max_outer=1000, max_cg=1000, cg_xi=0.1, trace_cap=1024, precond_blend=0.0) -> SolveResult:
     """Runs the solve in place on the CUDA tensor w (in: w0, out: final iterate)."""
-    params = _Params(loss, C, eps, max_outer, max_cg, cg_xi)
+    params = _Params(loss, C, eps, max_outer, max_cg, cg_xi, precond_blend)
     trace = (TraceRec * max(trace_cap, 1))()
     res = _Result()
     res.trace_cap = trace_cap
@@ -265,6 +272,9 @@ class Dataset:
 
     def hv(self, C, v, Hv, want_vHv=True):
         return tron_hv(self.handle, C, v, Hv, want_vHv)
+
+    def hess_diag(self, C, hd):
+        return tron_hess_diag(self.handle, C, hd)
 
     def solve(self, loss, C, eps, w, **kw):
         return tron_solve(self.handle, loss, C, eps, w, **kw)

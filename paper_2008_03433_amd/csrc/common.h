@@ -209,7 +209,7 @@ struct tron_dataset {
     int vec_grid_n = 0, vec_grid_d = 0;  // workgroups of elementwise kernels over n / d
 
     // solver vectors (d each), allocated on first tron_solve
-    double *sv[8] = {nullptr};
+    double *sv[9] = {nullptr};
 
     tron::Profiler prof;
 };
@@ -233,12 +233,12 @@ int dot_partials(tron_dataset *ds, int64_t m, const double *a0, const double *b0
                  const double *a2, const double *b2);
 int loss_terms(tron_dataset *ds, int loss, const double *z, double *zhat, double *D);  // partial slot 0 = sum loss
 int read_scalars(tron_dataset *ds, int count);  // D2H of scal_dev[0..count) + stream sync
-// CG vector kernels (see solver.hip)
-int cg_init(tron_dataset *ds, const double *g, double *s, double *r, double *p);
-int cg_step(tron_dataset *ds, double alpha, const double *p, const double *Hp, double *s, double *r);  // slot0 = r.r
-int cg_dir(tron_dataset *ds, double beta, const double *r, const double *s, double *p);  // slots: p.p, s.p, s.s
-int trial_point(tron_dataset *ds, const double *w, const double *s, const double *g, const double *r,
-                double *wnew);  // wnew = w+s; slots: g.s, s.r, s.s
+// CG vector kernels (see solver.hip); M = diagonal preconditioner or null
+int cg_init(tron_dataset *ds, const double *g, const double *M, double *s, double *r, double *p);  // M: slot0 = g.(g/M); returns #partials
+int cg_step(tron_dataset *ds, double alpha, const double *p, const double *Hp, const double *M, double *s, double *r);  // slot0 = r.r | r.(r/M)
+int cg_dir(tron_dataset *ds, double beta, const double *r, const double *s, const double *M, double *p);  // slots: p.p, s.p, s.s (M-weighted)
+int trial_point(tron_dataset *ds, const double *w, const double *s, const double *g, const double *r, const double *M,
+                double *wnew);  // wnew = w+s; slots: g.s, s.r, s.s | s.Ms
 int probe_read(const double *src, int64_t count, int reps, hipStream_t st, double *ms, double *checksum);
 int probe_copy(double *dst, const double *src, int64_t count, int reps, hipStream_t st, double *ms);
 
@@ -253,12 +253,13 @@ int hot_tiles_build(CsrPlan &A, const int64_t *t_rowptr, const int32_t *t_col, c
 // Products with one orientation; all enqueue on ds->stream.
 //   spmv_loss:  z = A x, then per-instance loss terms: zhat, D; partial slot 0 of ds->partials = sum loss
 //   spmv_scale: out = scale .* (A x)
-//   spmv_axpy:  out = add + alpha (A x); partial slot 0 = out . (dot_self ? out : add)
+//   spmv_axpy:  out = add + alpha (A x); partial slot 0 = out . (dot_self ? out : add).  add == null: add 1.
+//               square: the entries of A are squared (transposed orientation only)
 // Each returns the number of first-stage partials in slot 0 (0 if none), or a negative error.
 int spmv_loss(tron_dataset *ds, const CsrPlan &A, int slot, int loss, const double *x, double *zwork, double *zhat, double *D);
 int spmv_scale(tron_dataset *ds, const CsrPlan &A, int slot, const double *x, const double *scale, double *out);
 int spmv_axpy(tron_dataset *ds, const CsrPlan &A, int slot, const double *x, const double *add, double alpha,
-              bool dot_self, double *out);
+              bool dot_self, double *out, bool square = false);
 
 // ---- kernels_dense.hip
 bool dense_supported(int64_t d);
@@ -271,8 +272,13 @@ int dense_labels_from_device(tron_dataset *ds, int64_t row0, int64_t m, const do
 // Hv = v + C X^T (D (X v)); scalars[0] = v.Hv
 int dense_hv(tron_dataset *ds, double C, int Dslot, const double *v, double *Hv);
 
+// out = 1 + C diag(X^T D X)
+int dense_hess_diag(tron_dataset *ds, double C, int Dslot, double *out);
+
 // ---- solver.hip
 int fun_eval(tron_dataset *ds, int loss, double C, const double *w, int Dslot, double *f_out);  // syncs
+// out = 1 + C sum_i D_i x_ij^2 with D = Dbuf[Dslot] (the diagonal of the Hessian; C scaled by the caller for a blend). Enqueue only.
+int hess_diag_enqueue(tron_dataset *ds, double C, int Dslot, double *out);
 int grad_eval(tron_dataset *ds, double C, const double *w, double *g, double *gnorm_out);        // syncs
 int hv_enqueue(tron_dataset *ds, double C, const double *v, double *Hv);                         // scalars[0]=v.Hv, no sync
 

@@ -312,7 +312,7 @@ __device__ __forceinline__ double epilogue(double sum, int64_t r, const double *
 {
     if (EPI == EPI_PLAIN) return sum;
     if (EPI == EPI_SCALE) return aux[r] * sum;
-    return fma(alpha, sum, aux[r]);
+    return fma(alpha, sum, aux ? aux[r] : 1.0);   // no addend vector: add 1 (the Hessian diagonal)
 }
 
 // One chunk: nonzeros [start, end) of a (sub)matrix whose row offsets are rp (relative to col/val),
@@ -336,7 +336,7 @@ __device__ __forceinline__ double gather(const double *__restrict__ x, const dou
     return (c < 0) ? hot : cold;
 }
 
-template <int EPI, typename RP, bool HOT = false>
+template <int EPI, typename RP, bool HOT = false, bool SQ = false>
 __device__ __forceinline__ void chunk_body(double *prod, const double *table, int64_t start, int64_t end, bool first_chunk,
                                            const RP *__restrict__ rp, const int32_t *__restrict__ col,
                                            const double *__restrict__ val, const int32_t *__restrict__ row_lo,
@@ -364,14 +364,14 @@ __device__ __forceinline__ void chunk_body(double *prod, const double *table, in
 #pragma unroll
         for (int m = 0; m < 4; ++m) {
             double2 p;
-            p.x = v[m].x * xg[m][0];
-            p.y = v[m].y * xg[m][1];
+            p.x = (SQ ? v[m].x * v[m].x : v[m].x) * xg[m][0];
+            p.y = (SQ ? v[m].y * v[m].y : v[m].y) * xg[m][1];
             *reinterpret_cast<double2 *>(prod + m * (kChunk / 4) + tid * 2) = p;
         }
     } else {
         for (int k = tid; k < kChunk; k += kBlock) {
             const int64_t kk = start + k;
-            prod[k] = (kk < end) ? val[kk] * gather<HOT>(x, table, col[kk]) : 0.0;
+            prod[k] = (kk < end) ? (SQ ? val[kk] * val[kk] : val[kk]) * gather<HOT>(x, table, col[kk]) : 0.0;
         }
     }
     __syncthreads();
@@ -415,7 +415,7 @@ __device__ __forceinline__ void chunk_body(double *prod, const double *table, in
 }
 
 // unpartitioned: y = epilogue(A x) directly
-template <int EPI>
+template <int EPI, bool SQ>
 __global__ __launch_bounds__(kBlock) void k_csr_spmv(int64_t nnz, const int64_t *__restrict__ rowptr,
                                                      const int32_t *__restrict__ col, const double *__restrict__ val,
                                                      const int32_t *__restrict__ row_lo, const double *__restrict__ x,
@@ -426,7 +426,7 @@ __global__ __launch_bounds__(kBlock) void k_csr_spmv(int64_t nnz, const int64_t 
     const int b = blockIdx.x;
     const int64_t start = (int64_t)b * kChunk;
     const int64_t end = (start + kChunk < nnz) ? start + kChunk : nnz;
-    chunk_body<EPI>(prod, nullptr, start, end, b == 0, rowptr, col, val, row_lo + b, x, yout, aux, alpha, carry + b);
+    chunk_body<EPI, int64_t, false, SQ>(prod, nullptr, start, end, b == 0, rowptr, col, val, row_lo + b, x, yout, aux, alpha, carry + b);
 }
 
 struct PartArgs {
@@ -507,7 +507,7 @@ constexpr int kSegPasses = kChunk / kBlock;     // a chunk holds at most kChunk 
 __device__ __forceinline__ int prod_pos(int e) { return e + 2 * (e >> 3); }
 
 // products of the chunk in `r` into LDS
-template <bool HOT, bool HEAD>
+template <bool HOT, bool HEAD, bool SQ>
 __device__ __forceinline__ void products_to_lds(const StreamRegs<HEAD> &r, const double *__restrict__ x, const double *table, double *prod)
 {
     double xg[4][2];
@@ -516,8 +516,8 @@ __device__ __forceinline__ void products_to_lds(const StreamRegs<HEAD> &r, const
 #pragma unroll
     for (int m = 0; m < 4; ++m) {
         double2 p;
-        p.x = r.v[m].x * xg[m][0];
-        p.y = r.v[m].y * xg[m][1];
+        p.x = (SQ ? r.v[m].x * r.v[m].x : r.v[m].x) * xg[m][0];
+        p.y = (SQ ? r.v[m].y * r.v[m].y : r.v[m].y) * xg[m][1];
         *reinterpret_cast<double2 *>(prod + prod_pos(m * kQuarter + threadIdx.x * 2)) = p;   // an even entry: the pair stays together
     }
 }
@@ -652,7 +652,8 @@ struct PartPtrs {   // device arrays of one partitioned plan (or of its head par
 // partition.  Everything the next chunk needs -- the col/val stream, the chunk's table entry, its flags and the row
 // ids this thread will write -- is fetched into registers while the current chunk is being reduced, so HBM latency
 // is paid once per workgroup, not once per chunk.
-template <bool HOT, bool HEAD>
+// SQ: the values are squared (sum_i x_ij^2 a_i, for the diagonal of the Hessian)
+template <bool HOT, bool HEAD, bool SQ>
 __device__ __forceinline__ void part_body(double *prod, double *table, const PartArgs &pa, const int xp, const int q, const int Q,
                                           const int64_t rows, const PartPtrs &pp, const double *__restrict__ x)
 {
@@ -682,7 +683,7 @@ __device__ __forceinline__ void part_body(double *prod, double *table, const Par
     SegRegs seg = load_segs(tab, flags + (int64_t)c * kBlock, seg_row);
 
     for (; c < nchunks; c += Q) {
-        products_to_lds<HOT, HEAD>(cur, x, table, prod);
+        products_to_lds<HOT, HEAD, SQ>(cur, x, table, prod);
         // Only now fetch the next chunk (clamped index: always the same loads): nothing below waits for these
         // registers, so they stay in flight during the segment sums and are waited for at the top of the next
         // iteration.
@@ -703,12 +704,12 @@ __device__ __forceinline__ void part_body(double *prod, double *table, const Par
     }
 }
 
-template <bool HOT, bool HEAD>
+template <bool HOT, bool HEAD, bool SQ>
 __global__ __launch_bounds__(kBlock) void k_csr_spmv_part(PartArgs pa, int64_t rows, PartPtrs pp, const double *__restrict__ x)
 {
     __shared__ __align__(16) double prod[kProdDoubles];
     extern __shared__ __align__(16) double table[];   // pa.slots doubles (none without HOT)
-    part_body<HOT, HEAD>(prod, table, pa, blockIdx.x % pa.P, blockIdx.x / pa.P, gridDim.x / pa.P, rows, pp, x);
+    part_body<HOT, HEAD, SQ>(prod, table, pa, blockIdx.x % pa.P, blockIdx.x / pa.P, gridDim.x / pa.P, rows, pp, x);
 }
 
 // ------------------------------------------------------------------ hot-row tiles (see HotTiles)
@@ -855,6 +856,7 @@ __device__ __forceinline__ TileRegs load_tile(const TilePtrs &tp, int4 h, int64_
 // Software pipeline: while tile t is reduced, the data of tiles t + B and t + 2B and the header of tile t + 3B are
 // in flight (all indices clamped to the last tile, so every iteration issues the same loads).
 // Slots inside a tile are distinct, so the accumulator updates of different segments never collide.
+template <bool SQ>
 __device__ __forceinline__ void tiles_body(double *prod, uint16_t *slots, double *acc, const TileArgs &ta, const int s, const int q,
                                            const int B, const TilePtrs &tp, const double *__restrict__ x)
 {
@@ -881,8 +883,8 @@ __device__ __forceinline__ void tiles_body(double *prod, uint16_t *slots, double
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
                 double2 p;
-                p.x = cur.v[m].x * xg[m][0];
-                p.y = cur.v[m].y * xg[m][1];
+                p.x = (SQ ? cur.v[m].x * cur.v[m].x : cur.v[m].x) * xg[m][0];
+                p.y = (SQ ? cur.v[m].y * cur.v[m].y : cur.v[m].y) * xg[m][1];
                 *reinterpret_cast<double2 *>(prod + prod_pos(m * kQuarter + tid * 2)) = p;
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -917,12 +919,13 @@ __device__ __forceinline__ void tiles_body(double *prod, uint16_t *slots, double
     for (int k = tid; k < kTileSlots; k += kBlock) out[k] = acc[k];
 }
 
+template <bool SQ>
 __global__ __launch_bounds__(kBlock) void k_hot_tiles(TileArgs ta, int B, TilePtrs tp, const double *__restrict__ x)
 {
     __shared__ __align__(16) double prod[kProdDoubles];
     __shared__ __align__(16) uint16_t slots[kChunk];
     __shared__ double acc[kTileSlots];
-    tiles_body(prod, slots, acc, ta, blockIdx.x % kTileSlices, blockIdx.x / kTileSlices, B, tp, x);
+    tiles_body<SQ>(prod, slots, acc, ta, blockIdx.x % kTileSlices, blockIdx.x / kTileSlices, B, tp, x);
 }
 
 // sums[s*K + k] = sum over the B workgroups of slice s: four quarter sums (workgroup order inside each), added in
@@ -958,7 +961,7 @@ static TileArgs tile_args(const HotTiles &H)
 static TilePtrs tile_ptrs(const HotTiles &H) { return TilePtrs{H.val, H.iloc, H.flags, H.hdr, H.seg_slot, H.wg_acc}; }
 
 // tiles + the reduction of the workgroup accumulators (B = workgroups per slice)
-static int launch_hot_tiles(tron_dataset *ds, const CsrPlan &A, const double *x)
+static int launch_hot_tiles(tron_dataset *ds, const CsrPlan &A, const double *x, bool square)
 {
     const HotTiles &H = A.hot;
     // The tiles stream from HBM, the CSR remainder waits on gather misses: they run side by side on two streams.
@@ -969,8 +972,12 @@ static int launch_hot_tiles(tron_dataset *ds, const CsrPlan &A, const double *x)
     }
     {
         ProfScope ps(ds, SLOT_SPMV_TILES, st);
-        hipLaunchKernelGGL(k_hot_tiles, dim3(kTileSlices * H.blocks_per_slice), dim3(kBlock), 0, st, tile_args(H), H.blocks_per_slice,
-                           tile_ptrs(H), x);
+        if (square)
+            hipLaunchKernelGGL(k_hot_tiles<true>, dim3(kTileSlices * H.blocks_per_slice), dim3(kBlock), 0, st, tile_args(H),
+                               H.blocks_per_slice, tile_ptrs(H), x);
+        else
+            hipLaunchKernelGGL(k_hot_tiles<false>, dim3(kTileSlices * H.blocks_per_slice), dim3(kBlock), 0, st, tile_args(H),
+                               H.blocks_per_slice, tile_ptrs(H), x);
         TRON_HIP(hipGetLastError());
     }
     {
@@ -1086,7 +1093,7 @@ __global__ __launch_bounds__(kBlock) void k_combine_axpy(int64_t rows, const dou
     __shared__ double lds[kWavesPerBlock];
     double acc = 0.0;
     for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < rows; i += (int64_t)gridDim.x * kBlock) {
-        const double a = add[i];
+        const double a = add ? add[i] : 1.0;
         const double o = fma(alpha, sum_parts(partial, mask, rows, i, hot), a);
         out[i] = o;
         acc += o * (SELF ? o : a);
@@ -1106,12 +1113,16 @@ static inline int vec_grid(int64_t m)
 
 template <int EPI>
 static int launch_plain(tron_dataset *ds, const CsrPlan &A, int slot, const double *x, double *yout, const double *aux,
-                        double alpha)
+                        double alpha, bool square = false)
 {
     {
         ProfScope ps(ds, slot);
-        hipLaunchKernelGGL(k_csr_spmv<EPI>, dim3(A.nblocks), dim3(kBlock), 0, ds->stream, A.nnz, A.rowptr, A.col, A.val,
-                           A.row_lo, x, yout, aux, alpha, A.carry);
+        if (square)
+            hipLaunchKernelGGL((k_csr_spmv<EPI, true>), dim3(A.nblocks), dim3(kBlock), 0, ds->stream, A.nnz, A.rowptr, A.col, A.val,
+                               A.row_lo, x, yout, aux, alpha, A.carry);
+        else
+            hipLaunchKernelGGL((k_csr_spmv<EPI, false>), dim3(A.nblocks), dim3(kBlock), 0, ds->stream, A.nnz, A.rowptr, A.col, A.val,
+                               A.row_lo, x, yout, aux, alpha, A.carry);
         TRON_HIP(hipGetLastError());
     }
     TRON_TRY(launch_fixup<EPI>(ds, A, yout, aux, alpha));
@@ -1165,7 +1176,7 @@ static PartPtrs head_ptrs(const tron_dataset *ds, const CsrPlan &A)
 }
 
 // partial row sums of all partitions into ds->row_partials (with split rows fixed up)
-static int launch_partials(tron_dataset *ds, const CsrPlan &A, int slot, const double *x)
+static int launch_partials(tron_dataset *ds, const CsrPlan &A, int slot, const double *x, bool square = false)
 {
     const PartArgs pa = part_args(A);
     if (A.hot_ids) {
@@ -1177,7 +1188,7 @@ static int launch_partials(tron_dataset *ds, const CsrPlan &A, int slot, const d
     if (A.head >= 0) {
         ProfScope ps(ds, SLOT_SPMV_HEAD);
         const int grid = std::max(1, std::min(A.part_nchunks[A.head], (int)g_tuning.csr_hot_blocks_per_part * kColParts));
-        hipLaunchKernelGGL((k_csr_spmv_part<true, true>), dim3(grid), dim3(kBlock), kHotSlots * sizeof(double), ds->stream,
+        hipLaunchKernelGGL((k_csr_spmv_part<true, true, false>), dim3(grid), dim3(kBlock), kHotSlots * sizeof(double), ds->stream,
                            head_args(A), A.rows, head_ptrs(ds, A), x);
         TRON_HIP(hipGetLastError());
     }
@@ -1186,10 +1197,13 @@ static int launch_partials(tron_dataset *ds, const CsrPlan &A, int slot, const d
         const int want = (int)(A.hot_ids ? g_tuning.csr_range_blocks_per_part : g_tuning.csr_blocks_per_part);
         const int per_part = std::max(1, std::min(A.max_chunks, want));
         if (A.hot_ids)
-            hipLaunchKernelGGL((k_csr_spmv_part<true, false>), dim3(per_part * A.P), dim3(kBlock), A.range_slots * sizeof(double), ds->stream,
+            hipLaunchKernelGGL((k_csr_spmv_part<true, false, false>), dim3(per_part * A.P), dim3(kBlock), A.range_slots * sizeof(double), ds->stream,
                                pa, A.rows, part_ptrs(ds, A), x);
+        else if (square)
+            hipLaunchKernelGGL((k_csr_spmv_part<false, false, true>), dim3(per_part * A.P), dim3(kBlock), 0, ds->stream, pa, A.rows,
+                               part_ptrs(ds, A), x);
         else
-            hipLaunchKernelGGL((k_csr_spmv_part<false, false>), dim3(per_part * A.P), dim3(kBlock), 0, ds->stream, pa, A.rows,
+            hipLaunchKernelGGL((k_csr_spmv_part<false, false, false>), dim3(per_part * A.P), dim3(kBlock), 0, ds->stream, pa, A.rows,
                                part_ptrs(ds, A), x);
         TRON_HIP(hipGetLastError());
     }
@@ -1225,19 +1239,21 @@ int spmv_scale(tron_dataset *ds, const CsrPlan &A, int slot, const double *x, co
 }
 
 int spmv_axpy(tron_dataset *ds, const CsrPlan &A, int slot, const double *x, const double *add, double alpha, bool dot_self,
-              double *out)
+              double *out, bool square)
 {
+    if (square && A.hot_ids) { set_error("internal: squared product on a layout with LDS tables"); return TRON_EINVAL; }
     if (A.P == 1) {
-        TRON_TRY(launch_plain<EPI_AXPY>(ds, A, slot, x, out, add, alpha));
+        TRON_TRY(launch_plain<EPI_AXPY>(ds, A, slot, x, out, add, alpha, square));
+        if (!add) return 0;
         return dot_partials(ds, A.rows, out, dot_self ? out : add, nullptr, nullptr, nullptr, nullptr);
     }
     HotRef hot{nullptr, nullptr};
     if (A.hot.ntiles_total > 0) {
-        TRON_TRY(launch_hot_tiles(ds, A, x));
+        TRON_TRY(launch_hot_tiles(ds, A, x, square));
         hot.slot_of_row = A.hot.slot_of_row;
         hot.sums = A.hot.sums;
     }
-    TRON_TRY(launch_partials(ds, A, slot, x));
+    TRON_TRY(launch_partials(ds, A, slot, x, square));
     if (hot.sums && g_tuning.csr_two_streams) TRON_HIP(hipStreamWaitEvent(ds->stream, ds->ev_join, 0));
     ProfScope ps(ds, SLOT_SPMV_COMBINE);
     const int g = vec_grid(A.rows);

@@ -121,7 +121,8 @@ struct Tile {
 
 // ------------------------------------------------------------------ Hessian-vector pass
 // MASK: D is stored as one byte per row (L2-SVM: D_ii = 2 on the active set, else 0) instead of an fp64 value.
-template <int E, int L, int U, bool VEC, bool MASK>
+// DIAG: column sums of D_i x_ij^2 instead (the diagonal of X^T D X; v is not read).
+template <int E, int L, int U, bool VEC, bool MASK, bool DIAG>
 __global__ __launch_bounds__(kBlock) void k_dense_hv(int64_t n, int64_t d, const double *__restrict__ X,
                                                      const void *__restrict__ Dv, const double *__restrict__ v,
                                                      double *__restrict__ partials)
@@ -135,7 +136,7 @@ __global__ __launch_bounds__(kBlock) void k_dense_hv(int64_t n, int64_t d, const
     double vreg[E], acc[E];
 #pragma unroll
     for (int e = 0; e < E; ++e) {
-        vreg[e] = (q * E + e < d) ? v[q * E + e] : 0.0;
+        vreg[e] = (!DIAG && q * E + e < d) ? v[q * E + e] : 0.0;
         acc[e] = 0.0;
     }
     const int64_t ntiles = (n + T::RT - 1) / T::RT;
@@ -146,13 +147,22 @@ __global__ __launch_bounds__(kBlock) void k_dense_hv(int64_t n, int64_t d, const
         T::load(X, n, d, row0, lane, x);
         double Drow = 0.0;
         if (lane < T::RT && row0 + lane < n) Drow = MASK ? (Dm[row0 + lane] ? 2.0 : 0.0) : D[row0 + lane];
-        T::row_dots(x, vreg, t);
-        const double a1 = Drow * T::to_row_owner(t, lane);   // a1 = D (X v)
-        T::from_row_owner(a1, lane, c);
+        if (DIAG) {
+            T::from_row_owner(Drow, lane, c);
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
+            for (int u = 0; u < U; ++u) {
 #pragma unroll
-            for (int e = 0; e < E; ++e) acc[e] = fma(c[u], x[u][e], acc[e]);
+                for (int e = 0; e < E; ++e) acc[e] = fma(c[u] * x[u][e], x[u][e], acc[e]);
+            }
+        } else {
+            T::row_dots(x, vreg, t);
+            const double a1 = Drow * T::to_row_owner(t, lane);   // a1 = D (X v)
+            T::from_row_owner(a1, lane, c);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+#pragma unroll
+                for (int e = 0; e < E; ++e) acc[e] = fma(c[u], x[u][e], acc[e]);
+            }
         }
     }
     T::flush(acc, d, lane, wv, lds, partials);
@@ -225,7 +235,7 @@ __global__ __launch_bounds__(kBlock) void k_dense_columns(int64_t d, int grid, c
     for (int b = lane; b < grid; b += kWave) s += p[b];
     s = wave_sum(s);
     if (lane == 0) {
-        const double o = fma(C, s, add[c]);
+        const double o = fma(C, s, add ? add[c] : 1.0);
         if (out) out[c] = o;
         colprod[c] = o * (dotw ? dotw[c] : o);
     }
@@ -278,12 +288,20 @@ int launch_hv(tron_dataset *ds, const void *D, bool mask, const double *v)
     constexpr int U = pick_U(E, L);
     const bool vec = (E % 2 == 0) && (ds->d % 2 == 0);
     const int grid = ds->dense_grid;
-#define TRON_HV(V, M) \
-    hipLaunchKernelGGL((k_dense_hv<E, L, U, V, M>), dim3(grid), dim3(kBlock), 0, ds->stream, ds->n, ds->d, ds->X, D, v, ds->partials)
-    if (mask) {
-        if (vec) TRON_HV((E % 2 == 0), true); else TRON_HV(false, true);
-    } else {
-        if (vec) TRON_HV((E % 2 == 0), false); else TRON_HV(false, false);
+#define TRON_HV(V, M, G) \
+    hipLaunchKernelGGL((k_dense_hv<E, L, U, V, M, G>), dim3(grid), dim3(kBlock), 0, ds->stream, ds->n, ds->d, ds->X, D, v, ds->partials)
+    if (v) {
+        if (mask) {
+            if (vec) TRON_HV((E % 2 == 0), true, false); else TRON_HV(false, true, false);
+        } else {
+            if (vec) TRON_HV((E % 2 == 0), false, false); else TRON_HV(false, false, false);
+        }
+    } else {   // no vector: the diagonal sums
+        if (mask) {
+            if (vec) TRON_HV((E % 2 == 0), true, true); else TRON_HV(false, true, true);
+        } else {
+            if (vec) TRON_HV((E % 2 == 0), false, true); else TRON_HV(false, false, true);
+        }
     }
 #undef TRON_HV
     return TRON_OK;
@@ -402,6 +420,24 @@ int dense_hv(tron_dataset *ds, double C, int Dslot, const double *v, double *Hv)
     hipLaunchKernelGGL(k_dense_columns, dim3(cg), dim3(kBlock), 0, ds->stream, ds->d, grid, ds->partials, v, C, Hv, v, colprod);
     hipLaunchKernelGGL(k_dense_scalars, dim3(1), dim3(kBlock), 0, ds->stream, ds->d, 0, (const double *)nullptr,
                        (const double *)nullptr, colprod, ds->scal_dev);
+    TRON_HIP(hipGetLastError());
+    return TRON_OK;
+}
+
+// out = 1 + C diag(X^T D X): the same pass as dense_hv with squared entries
+int dense_hess_diag(tron_dataset *ds, double C, int Dslot, double *out)
+{
+    const int grid = ds->dense_grid;
+    double *colprod = ds->partials + ds->d * grid + grid;
+    {
+        ProfScope ps(ds, SLOT_DENSE_HV);
+        TRON_TRY(dispatch_hv(ds, ds->Dbuf[Dslot], ds->D_is_mask[Dslot], nullptr));
+        TRON_HIP(hipGetLastError());
+    }
+    ProfScope ps(ds, SLOT_DENSE_FINALIZE);
+    const int cg = (int)((ds->d + kWavesPerBlock - 1) / kWavesPerBlock);
+    hipLaunchKernelGGL(k_dense_columns, dim3(cg), dim3(kBlock), 0, ds->stream, ds->d, grid, ds->partials, (const double *)nullptr, C,
+                       out, (const double *)nullptr, colprod);
     TRON_HIP(hipGetLastError());
     return TRON_OK;
 }

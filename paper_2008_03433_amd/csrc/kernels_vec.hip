@@ -118,30 +118,47 @@ int loss_terms(tron_dataset *ds, int loss, const double *z, double *zhat, double
 }
 
 // ------------------------------------------------------------------ conjugate-gradient vector updates
-// s = 0, r = p = -g
-__global__ __launch_bounds__(kBlock) void k_cg_init(int64_t d, const double *__restrict__ g, double *__restrict__ s,
-                                                    double *__restrict__ r, double *__restrict__ p)
+// PRE = preconditioned by the diagonal M (the trust region is then measured in the M-norm): z = r / M takes the
+// place of r in the direction, r.z of r.r, and the three dot products that locate the boundary are M-weighted.
+// Without PRE the arithmetic is exactly that of plain CG (M is not read).
+
+// s = 0, r = -g, p = r (PRE: p = r / M; partial slot 0 = r.p)
+template <bool PRE>
+__global__ __launch_bounds__(kBlock) void k_cg_init(int64_t d, const double *__restrict__ g, const double *__restrict__ M,
+                                                    double *__restrict__ s, double *__restrict__ r, double *__restrict__ p,
+                                                    double *__restrict__ partials)
 {
+    __shared__ double lds[kWavesPerBlock];
+    double acc = 0.0;
     for (int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x; j < d; j += (int64_t)gridDim.x * kBlock) {
         const double t = -g[j];
+        const double z = PRE ? t / M[j] : t;
         s[j] = 0.0;
         r[j] = t;
-        p[j] = t;
+        p[j] = z;
+        acc += t * z;
+    }
+    if (PRE) {
+        acc = block_sum(acc, lds);
+        if (threadIdx.x == 0) partials[blockIdx.x] = acc;
     }
 }
 
-int cg_init(tron_dataset *ds, const double *g, double *s, double *r, double *p)
+int cg_init(tron_dataset *ds, const double *g, const double *M, double *s, double *r, double *p)
 {
     ProfScope ps(ds, SLOT_CG_VEC);
-    hipLaunchKernelGGL(k_cg_init, dim3(vec_grid(ds->d)), dim3(kBlock), 0, ds->stream, ds->d, g, s, r, p);
+    const int gr = vec_grid(ds->d);
+    if (M) hipLaunchKernelGGL(k_cg_init<true>, dim3(gr), dim3(kBlock), 0, ds->stream, ds->d, g, M, s, r, p, ds->partials);
+    else hipLaunchKernelGGL(k_cg_init<false>, dim3(gr), dim3(kBlock), 0, ds->stream, ds->d, g, M, s, r, p, ds->partials);
     TRON_HIP(hipGetLastError());
-    return TRON_OK;
+    return gr;
 }
 
-// s += alpha p;  r -= alpha Hp;  partial slot 0 = r.r
+// s += alpha p;  r -= alpha Hp;  partial slot 0 = r.r (PRE: r.(r / M))
+template <bool PRE>
 __global__ __launch_bounds__(kBlock) void k_cg_step(int64_t d, double alpha, const double *__restrict__ p,
-                                                    const double *__restrict__ Hp, double *__restrict__ s,
-                                                    double *__restrict__ r, double *__restrict__ partials)
+                                                    const double *__restrict__ Hp, const double *__restrict__ M,
+                                                    double *__restrict__ s, double *__restrict__ r, double *__restrict__ partials)
 {
     __shared__ double lds[kWavesPerBlock];
     double acc = 0.0;
@@ -149,35 +166,44 @@ __global__ __launch_bounds__(kBlock) void k_cg_step(int64_t d, double alpha, con
         s[j] = fma(alpha, p[j], s[j]);
         const double rj = fma(-alpha, Hp[j], r[j]);
         r[j] = rj;
-        acc += rj * rj;
+        acc += rj * (PRE ? rj / M[j] : rj);
     }
     acc = block_sum(acc, lds);
     if (threadIdx.x == 0) partials[blockIdx.x] = acc;
 }
 
-int cg_step(tron_dataset *ds, double alpha, const double *p, const double *Hp, double *s, double *r)
+int cg_step(tron_dataset *ds, double alpha, const double *p, const double *Hp, const double *M, double *s, double *r)
 {
     ProfScope ps(ds, SLOT_CG_VEC);
     const int g = vec_grid(ds->d);
-    hipLaunchKernelGGL(k_cg_step, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, alpha, p, Hp, s, r, ds->partials);
+    if (M) hipLaunchKernelGGL(k_cg_step<true>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, alpha, p, Hp, M, s, r, ds->partials);
+    else hipLaunchKernelGGL(k_cg_step<false>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, alpha, p, Hp, M, s, r, ds->partials);
     TRON_HIP(hipGetLastError());
     return g;
 }
 
-// p = r + beta p;  partial slots: 0 = p.p, 1 = s.p, 2 = s.s
+// p = r + beta p (PRE: r / M + beta p);  partial slots: 0 = p.p, 1 = s.p, 2 = s.s (PRE: M-weighted)
+template <bool PRE>
 __global__ __launch_bounds__(kBlock) void k_cg_dir(int64_t d, double beta, const double *__restrict__ r,
-                                                   const double *__restrict__ s, double *__restrict__ p,
-                                                   double *__restrict__ partials, int stride)
+                                                   const double *__restrict__ s, const double *__restrict__ M,
+                                                   double *__restrict__ p, double *__restrict__ partials, int stride)
 {
     __shared__ double lds[kWavesPerBlock];
     double pp = 0.0, sp = 0.0, ss = 0.0;
     for (int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x; j < d; j += (int64_t)gridDim.x * kBlock) {
-        const double pj = fma(beta, p[j], r[j]);
+        const double m = PRE ? M[j] : 1.0;
+        const double pj = fma(beta, p[j], PRE ? r[j] / m : r[j]);
         const double sj = s[j];
         p[j] = pj;
-        pp += pj * pj;
-        sp += sj * pj;
-        ss += sj * sj;
+        if (PRE) {
+            pp += m * pj * pj;
+            sp += m * sj * pj;
+            ss += m * sj * sj;
+        } else {
+            pp += pj * pj;
+            sp += sj * pj;
+            ss += sj * sj;
+        }
     }
     pp = block_sum(pp, lds);
     if (threadIdx.x == 0) partials[blockIdx.x] = pp;
@@ -187,19 +213,22 @@ __global__ __launch_bounds__(kBlock) void k_cg_dir(int64_t d, double beta, const
     if (threadIdx.x == 0) partials[2 * stride + blockIdx.x] = ss;
 }
 
-int cg_dir(tron_dataset *ds, double beta, const double *r, const double *s, double *p)
+int cg_dir(tron_dataset *ds, double beta, const double *r, const double *s, const double *M, double *p)
 {
     ProfScope ps(ds, SLOT_CG_VEC);
     const int g = vec_grid(ds->d);
-    hipLaunchKernelGGL(k_cg_dir, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, beta, r, s, p, ds->partials, kMaxGrid);
+    if (M) hipLaunchKernelGGL(k_cg_dir<true>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, beta, r, s, M, p, ds->partials, kMaxGrid);
+    else hipLaunchKernelGGL(k_cg_dir<false>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, beta, r, s, M, p, ds->partials, kMaxGrid);
     TRON_HIP(hipGetLastError());
     return g;
 }
 
-// wnew = w + s;  partial slots: 0 = g.s, 1 = s.r, 2 = s.s
+// wnew = w + s;  partial slots: 0 = g.s, 1 = s.r, 2 = s.s (PRE: s.Ms)
+template <bool PRE>
 __global__ __launch_bounds__(kBlock) void k_trial_point(int64_t d, const double *__restrict__ w, const double *__restrict__ s,
                                                         const double *__restrict__ g, const double *__restrict__ r,
-                                                        double *__restrict__ wnew, double *__restrict__ partials, int stride)
+                                                        const double *__restrict__ M, double *__restrict__ wnew,
+                                                        double *__restrict__ partials, int stride)
 {
     __shared__ double lds[kWavesPerBlock];
     double gs = 0.0, sr = 0.0, ss = 0.0;
@@ -208,7 +237,7 @@ __global__ __launch_bounds__(kBlock) void k_trial_point(int64_t d, const double 
         wnew[j] = w[j] + sj;
         gs += g[j] * sj;
         sr += sj * r[j];
-        ss += sj * sj;
+        ss += PRE ? M[j] * sj * sj : sj * sj;
     }
     gs = block_sum(gs, lds);
     if (threadIdx.x == 0) partials[blockIdx.x] = gs;
@@ -218,11 +247,13 @@ __global__ __launch_bounds__(kBlock) void k_trial_point(int64_t d, const double 
     if (threadIdx.x == 0) partials[2 * stride + blockIdx.x] = ss;
 }
 
-int trial_point(tron_dataset *ds, const double *w, const double *s, const double *g, const double *r, double *wnew)
+int trial_point(tron_dataset *ds, const double *w, const double *s, const double *g, const double *r, const double *M,
+                double *wnew)
 {
     ProfScope ps(ds, SLOT_CG_VEC);
     const int gr = vec_grid(ds->d);
-    hipLaunchKernelGGL(k_trial_point, dim3(gr), dim3(kBlock), 0, ds->stream, ds->d, w, s, g, r, wnew, ds->partials, kMaxGrid);
+    if (M) hipLaunchKernelGGL(k_trial_point<true>, dim3(gr), dim3(kBlock), 0, ds->stream, ds->d, w, s, g, r, M, wnew, ds->partials, kMaxGrid);
+    else hipLaunchKernelGGL(k_trial_point<false>, dim3(gr), dim3(kBlock), 0, ds->stream, ds->d, w, s, g, r, M, wnew, ds->partials, kMaxGrid);
     TRON_HIP(hipGetLastError());
     return gr;
 }

@@ -46,14 +46,22 @@ int hv_enqueue(tron_dataset *ds, double C, const double *v, double *Hv)
     return TRON_OK;
 }
 
+// out = 1 + C sum_i D_i x_ij^2  (diagonal of the Hessian of Appendix B when C is the solver's C)
+int hess_diag_enqueue(tron_dataset *ds, double C, int Dslot, double *out)
+{
+    if (ds->dense) return dense_hess_diag(ds, C, Dslot, out);
+    const int g = spmv_axpy(ds, ds->bwd, SLOT_SPMV_BWD, ds->Dbuf[Dslot], nullptr, C, false, out, true);
+    return g < 0 ? g : TRON_OK;
+}
+
 namespace {
 
-enum { V_W = 0, V_WNEW, V_G, V_GNEW, V_S, V_R, V_P, V_HP, V_COUNT };
+enum { V_W = 0, V_WNEW, V_G, V_GNEW, V_S, V_R, V_P, V_HP, V_M, V_COUNT };
 
-int ensure_solver_vectors(tron_dataset *ds)
+int ensure_solver_vectors(tron_dataset *ds, bool precond)
 {
     for (int k = 0; k < V_COUNT; ++k)
-        if (!ds->sv[k]) TRON_HIP(hipMalloc(reinterpret_cast<void **>(&ds->sv[k]), sizeof(double) * ds->d));
+        if (!ds->sv[k] && (k != V_M || precond)) TRON_HIP(hipMalloc(reinterpret_cast<void **>(&ds->sv[k]), sizeof(double) * ds->d));
     return TRON_OK;
 }
 
@@ -73,15 +81,17 @@ int eval_f(tron_dataset *ds, const tron_params &P, const double *w, int Dslot, d
 // Steihaug-Toint truncated CG on q(s) = g.s + 1/2 s.H s inside |s| <= delta.
 //   s = 0, r = p = -g;  loop: stop when |r| <= xi |g|;  alpha = r.r / p.Hp;  if |s + alpha p| >= delta go to
 //   the boundary along p and stop;  s += alpha p, r -= alpha Hp, beta = r'.r'/r.r, p = r + beta p.
-int cg_solve(tron_dataset *ds, const tron_params &P, double delta, double gnorm, int *n_hv, int *on_boundary)
+// With a diagonal preconditioner M (not null): z = r / M replaces r in p and in the dot products r.r, and the lengths
+// are M-norms (the iteration is plain CG in the variables M^(1/2) s); gscaled = sqrt(g.M^-1 g) takes the place of |g|.
+int cg_solve(tron_dataset *ds, const tron_params &P, const double *M, double delta, double gscaled, int *n_hv, int *on_boundary)
 {
     double *g = ds->sv[V_G], *s = ds->sv[V_S], *r = ds->sv[V_R], *p = ds->sv[V_P], *Hp = ds->sv[V_HP];
-    TRON_TRY(cg_init(ds, g, s, r, p));
-    double rr = gnorm * gnorm, pp = rr, sp = 0.0, ss = 0.0;
+    TRON_TRY(cg_init(ds, g, M, s, r, p));
+    double rr = gscaled * gscaled, pp = rr, sp = 0.0, ss = 0.0;   // p = z = -g / M at the start: p.Mp = r.z
     int it = 0;
     *on_boundary = 0;
     while (it < P.max_cg) {
-        if (std::sqrt(rr) <= P.cg_xi * gnorm) break;
+        if (std::sqrt(rr) <= P.cg_xi * gscaled) break;
         TRON_TRY(hv_enqueue(ds, P.C, p, Hp));
         TRON_TRY(read_scalars(ds, 4));  // p.Hp, and p.p, s.p, s.s left by the preceding direction update
         const double pHp = ds->scal_host[0];
@@ -98,23 +108,36 @@ int cg_solve(tron_dataset *ds, const tron_params &P, double delta, double gnorm,
             const double gap = delta * delta - ss;
             const double rad = std::sqrt(sp * sp + pp * gap);
             const double tau = (sp >= 0.0) ? gap / (sp + rad) : (rad - sp) / pp;
-            TRON_TRY(cg_step(ds, tau, p, Hp, s, r));
+            TRON_TRY(cg_step(ds, tau, p, Hp, M, s, r));
             *on_boundary = 1;
             break;
         }
-        const int g1 = cg_step(ds, alpha, p, Hp, s, r);
+        const int g1 = cg_step(ds, alpha, p, Hp, M, s, r);
         TRON_TRY(g1);
         TRON_TRY(reduce_final(ds, 1, g1, 0, 0));
         TRON_TRY(read_scalars(ds, 1));
         const double rr_new = ds->scal_host[0];
         const double beta = rr_new / rr;
         rr = rr_new;
-        if (std::sqrt(rr) <= P.cg_xi * gnorm || it >= P.max_cg) break;  // p is not needed again
-        const int g2 = cg_dir(ds, beta, r, s, p);
+        if (std::sqrt(rr) <= P.cg_xi * gscaled || it >= P.max_cg) break;  // p is not needed again
+        const int g2 = cg_dir(ds, beta, r, s, M, p);
         TRON_TRY(g2);
         TRON_TRY(reduce_final(ds, 3, g2, kMaxGrid, 1));  // scalars 1..3 = p.p, s.p, s.s, read with the next p.Hp
     }
     *n_hv = it;
+    return TRON_OK;
+}
+
+// M = (1 - blend) I + blend diag(H) at the point whose D is in Dbuf[Dslot], and sqrt(g.M^-1 g)
+int build_preconditioner(tron_dataset *ds, const tron_params &P, int Dslot, const double *g, double *M, double *gscaled)
+{
+    TRON_TRY(hess_diag_enqueue(ds, P.precond_blend * P.C, Dslot, M));   // 1 + blend C sum D x^2
+    // g.(g / M) with the CG start-up kernel (s, r, p are scratch here: the inner solver initialises them again)
+    const int gr = cg_init(ds, g, M, ds->sv[V_S], ds->sv[V_R], ds->sv[V_P]);
+    TRON_TRY(gr);
+    TRON_TRY(reduce_final(ds, 1, gr, 0, 0));
+    TRON_TRY(read_scalars(ds, 1));
+    *gscaled = std::sqrt(ds->scal_host[0]);
     return TRON_OK;
 }
 
@@ -128,9 +151,10 @@ extern "C" int tron_solve(tron_dataset *ds, const tron_params *params, double *w
     if (!ds || !params || !w_dev || !res) { set_error("tron_solve: null argument"); return TRON_EINVAL; }
     const tron_params P = *params;
     if ((P.loss != TRON_LOSS_LR && P.loss != TRON_LOSS_L2SVM) || !(P.C > 0.0) || !std::isfinite(P.C) || !(P.eps > 0.0) ||
-        P.max_outer < 1 || P.max_cg < 1 || !(P.cg_xi > 0.0) || !(P.cg_xi < 1.0) || res->trace_cap < 0 ||
-        (res->trace_cap > 0 && !res->trace)) {
-        set_error("tron_solve: bad parameter (loss, C > 0, eps > 0, max_outer >= 1, max_cg >= 1, 0 < cg_xi < 1, trace)");
+        P.max_outer < 1 || P.max_cg < 1 || !(P.cg_xi > 0.0) || !(P.cg_xi < 1.0) || !(P.precond_blend >= 0.0) ||
+        !(P.precond_blend <= 1.0) || res->trace_cap < 0 || (res->trace_cap > 0 && !res->trace)) {
+        set_error("tron_solve: bad parameter (loss, C > 0, eps > 0, max_outer >= 1, max_cg >= 1, 0 < cg_xi < 1, "
+                  "0 <= precond_blend <= 1, trace)");
         return TRON_EINVAL;
     }
     const double eta0 = 1e-4, eta1 = 0.25, eta2 = 0.75, sig2 = 0.5, sig3 = 4.0;
@@ -140,7 +164,9 @@ extern "C" int tron_solve(tron_dataset *ds, const tron_params *params, double *w
     res->outer_iters = res->cg_iters_total = res->n_fun = res->n_grad = res->n_hv = res->converged = 0;
     res->trace_len = 0;
 
-    TRON_TRY(ensure_solver_vectors(ds));
+    const bool precond = P.precond_blend > 0.0;
+    TRON_TRY(ensure_solver_vectors(ds, precond));
+    double *M = precond ? ds->sv[V_M] : nullptr;
     const size_t dbytes = sizeof(double) * ds->d;
     double *&w = ds->sv[V_W], *&wnew = ds->sv[V_WNEW], *&g = ds->sv[V_G], *&gnew = ds->sv[V_GNEW];
     double *s = ds->sv[V_S], *r = ds->sv[V_R];
@@ -171,17 +197,20 @@ extern "C" int tron_solve(tron_dataset *ds, const tron_params *params, double *w
     res->n_fun++;
     res->n_grad++;
     if (res->gnorm0 == 0.0) res->gnorm0 = gnorm;
-    double delta = gnorm;
+    // gscaled: the length of the gradient the inner solver measures its residual against (|g|, or sqrt(g.M^-1 g))
+    double gscaled = gnorm;
+    if (precond) TRON_TRY(build_preconditioner(ds, P, ds->Dcur, g, M, &gscaled));
+    double delta = gscaled;
     int status = TRON_EMAXITER;
     if (gnorm <= P.eps * res->gnorm0) { status = TRON_OK; res->converged = 1; }
 
     for (int k = 1; status == TRON_EMAXITER && k <= P.max_outer; ++k) {
         int ncg = 0, onb = 0;
-        TRON_TRY(cg_solve(ds, P, delta, gnorm, &ncg, &onb));
+        TRON_TRY(cg_solve(ds, P, M, delta, gscaled, &ncg, &onb));
         res->n_hv += ncg;
         res->cg_iters_total += ncg;
         // trial point and the model reduction  pred = -q(s) = -1/2 (g.s - s.r)
-        const int gt = trial_point(ds, w, s, g, r, wnew);
+        const int gt = trial_point(ds, w, s, g, r, M, wnew);
         TRON_TRY(gt);
         TRON_TRY(reduce_final(ds, 3, gt, kMaxGrid, 0));
         TRON_TRY(read_scalars(ds, 3));
@@ -208,7 +237,9 @@ extern "C" int tron_solve(tron_dataset *ds, const tron_params *params, double *w
             ds->Dcur = trial_slot;   // the Hessian now uses D at the accepted point
             f = fnew;
             gnorm = gnorm_new;
+            gscaled = gnorm;
             res->n_grad++;
+            if (precond && gnorm > P.eps * res->gnorm0) TRON_TRY(build_preconditioner(ds, P, ds->Dcur, g, M, &gscaled));
         }
         res->outer_iters = k;
         if (trace && res->trace_len < trace_cap) {
@@ -224,4 +255,14 @@ extern "C" int tron_solve(tron_dataset *ds, const tron_params *params, double *w
     TRON_HIP(hipMemcpyAsync(w_dev, w, dbytes, hipMemcpyDeviceToDevice, ds->stream));
     TRON_HIP(hipStreamSynchronize(ds->stream));
     return status;
+}
+
+extern "C" int tron_hess_diag(tron_dataset *ds, double C, double *hd_dev)
+{
+    if (!ds || !hd_dev) { set_error("tron_hess_diag: null argument"); return TRON_EINVAL; }
+    if (!(C > 0.0) || !std::isfinite(C)) { set_error("tron_hess_diag: C must be positive and finite"); return TRON_EINVAL; }
+    if (!ds->have_D) { set_error("tron_hess_diag: no D cached; call tron_fun_grad first"); return TRON_ESTATE; }
+    TRON_TRY(hess_diag_enqueue(ds, C, ds->Dcur, hd_dev));
+    TRON_HIP(hipStreamSynchronize(ds->stream));
+    return TRON_OK;
 }
