@@ -30,7 +30,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 
 # library profiler slot -> (kernel name in rocprofv3 output, profiles/ file that holds its byte counters)
 ROCPROF_NAMES = {
-    "dense_hv": ("k_dense_hv<6, 4, 4, true, true>", "dense_hv_fun_grad_c5.md"),
+    "dense_hv": ("k_dense_hv<6, 4, 4, true, true, false>", "dense_hv_fun_grad_c5.md"),
     "dense_fun_grad": ("k_dense_fun_grad<6, 4, 4, true, 1>", "dense_hv_fun_grad_c5.md"),
     "spmv_head": ("k_csr_spmv_part<true, true>", "csr_spmv_c3.md"),
     "spmv_fwd": ("k_csr_spmv_part<true, false>", "csr_spmv_c3.md"),
@@ -56,7 +56,25 @@ def make_workload(name: str, scale: float):
         return dg.config4(n=max(1000, int(round(1_000_000 * scale))))
     if name == "c5":
         return dg.config5(n=max(1000, int(round(230_000_000 * scale))))
+    # other loss / storage mixes of the paper's dataset table: dense logistic regression at the shapes of its two
+    # dense UCI sets (5M x 18 and 11M x 28), and the L2-SVM on the url-shaped sparse matrix
+    if name == "susy_shape":
+        return dg.config5(n=max(1000, int(round(5_000_000 * scale))), d=18)
+    if name == "higgs_shape":
+        return dg.config5(n=max(1000, int(round(11_000_000 * scale))), d=28)
+    if name == "c3_svm":
+        return dg.config3(scale)
     raise SystemExit(f"unknown workload {name!r}")
+
+
+def workload_params(name: str):
+    """(loss, C, eps) of a workload."""
+    import datagen as dg
+    if name in ("c4", "c5"):
+        return dg.LOSS_L2SVM, 0.1, 0.01
+    if name == "c3_svm":
+        return dg.LOSS_L2SVM, 1.0, 0.01
+    return dg.LOSS_LR, 1.0, 0.01
 
 
 def upload(tron, workload):
@@ -165,13 +183,15 @@ def run_workload(args, wname: str) -> dict:
     t0 = time.time()
     log(f"generating workload {wname} (scale {args.scale:g}) with {dg.num_threads()} host threads")
     workload = make_workload(wname, args.scale)
-    loss, C, eps = (dg.LOSS_L2SVM, 0.1, 0.01) if wname in ("c4", "c5") else (dg.LOSS_LR, 1.0, 0.01)
+    loss, C, eps = workload_params(wname)
     log(f"generated in {time.time() - t0:.1f} s; building the device dataset")
     t0 = time.time()
     ds = upload(tron, workload)
     setup_s = time.time() - t0
     log(f"dataset resident: n={ds.n:,} d={ds.d:,} nnz={ds.nnz:,} dense={ds.dense} ({setup_s:.1f} s)")
-    name = workload.name if hasattr(workload, "name") else f"c5_dense_svm_{ds.n}"
+    name = workload.name if hasattr(workload, "name") else (f"c5_dense_svm_{ds.n}" if wname == "c5" else f"{wname}_dense_{ds.n}x{ds.d}")
+    if wname == "c3_svm":
+        name += "_l2svm"
 
     def stat(key):
         return tron.tron_dataset_stat(ds.handle, key)
@@ -310,13 +330,14 @@ def small_config(args, wname: str) -> dict:
     sub = run_workload(argparse.Namespace(**{**vars(args), "no_cpu_baseline": True, "steps": 5, "warmup": 1}), wname)
     out = {"config": sub["config"]["workload"], "solve_ms": sub["ms_per_step"], "solve_min_ms": sub["solve"]["min_seconds"] * 1e3,
            "outer_iters": sub["solve"]["outer_iters"], "cg_iters": sub["solve"]["cg_iters"], "f": sub["solve"]["f"],
-           "hv_ms": sub["hv_call"]["ms"], "hv_effective_GB/s": sub["hv_call"]["GB/s"], "fun_grad_ms": sub["fun_grad_call"]["ms"],
+           "hv_ms": sub["hv_call"]["ms"], "hv_effective_GB/s": sub["hv_call"]["GB/s"], "hv_frac_hbm_peak": sub["hv_call"]["frac_hbm_peak"],
+           "fun_grad_ms": sub["fun_grad_call"]["ms"], "solve_preconditioned": sub["solve_preconditioned"],
            "kernels_hv": sub["kernels_hv"], "cpu_baseline": None}
     if not args.no_cpu_baseline:
         import datagen as dg
         from oracle import Oracle
         workload = make_workload(wname, 1.0)
-        loss, C, eps = (dg.LOSS_L2SVM, 0.1, 0.01) if wname == "c4" else (dg.LOSS_LR, 1.0, 0.01)
+        loss, C, eps = workload_params(wname)
         o = Oracle.from_problem(workload)
         t0 = time.perf_counter()
         ref = o.tron(loss, C, eps)
@@ -345,8 +366,9 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
-    ap.add_argument("--also", default=None, choices=["c1", "c2", "c3", "c4", "c5", "none"],
+    names = ["c1", "c2", "c3", "c4", "c5", "susy_shape", "higgs_shape", "c3_svm"]
+    ap.add_argument("--workload", default="c3", choices=names)
+    ap.add_argument("--also", default=None, choices=names + ["none"],
                     help="second workload reported under 'also' (default: c5 when the primary is c3)")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only; reported)")
     ap.add_argument("--hv-reps", type=int, default=20)
@@ -379,6 +401,9 @@ def main() -> int:
         out["also"] = {also: {k: sub[k] for k in keep}}
     if args.workload == "c3" and args.scale == 1.0 and args.also is None:
         out["others"] = {w: small_config(args, w) for w in ("c1", "c2", "c4")}
+        # the other loss / storage mixes (GPU only: their oracle solves take minutes)
+        quiet = argparse.Namespace(**{**vars(args), "no_cpu_baseline": True})
+        out["mixes"] = {w: small_config(quiet, w) for w in ("susy_shape", "higgs_shape", "c3_svm")}
     print(json.dumps(out), flush=True)
     return 0
 

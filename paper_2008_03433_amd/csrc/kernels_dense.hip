@@ -270,12 +270,18 @@ __global__ __launch_bounds__(kBlock) void k_dense_scalars(int64_t d, int nloss, 
 // ------------------------------------------------------------------ dispatch
 struct Shape { int E, L; };
 
-// smallest L in {1,2,4,...,64} with ceil(d/L) <= 8
+// smallest L in {1,2,4,...,64} with E = ceil(d/L) <= 8; for even d an odd E is rounded up, so that every lane can
+// use 16-byte loads (the columns past d are masked: d = 18 runs as 4 lanes x 6 columns, d = 28 as 4 x 8)
 bool pick_shape(int64_t d, Shape &s)
 {
     for (int L = 1; L <= kWave; L *= 2) {
-        const int64_t E = (d + L - 1) / L;
-        if (E <= 8) { s.E = (int)E; s.L = L; return true; }
+        int64_t E = (d + L - 1) / L;
+        if (E <= 8) {
+            if (L > 1 && d % 2 == 0 && E % 2 == 1) E += 1;
+            s.E = (int)E;
+            s.L = L;
+            return true;
+        }
     }
     return false;
 }
