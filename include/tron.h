@@ -66,7 +66,7 @@ enum { TRON_MEM_HOST = 0, TRON_MEM_DEVICE = 1 };
  * CSR input: rowptr int64[n+1] (rowptr[0] = 0, non-decreasing, rowptr[n] = nnz), col int32[nnz]
  * (inside each row strictly increasing and in [0,d)), val fp64[nnz] (finite), y fp64[n]
  * (exactly +1.0 or -1.0).  mem says whether the four arrays are host or device pointers (all
- * alike).  Validation failures return TRON_EINVAL and create nothing.  n, d >= 1; nnz may be 0;
+ * alike).  Validation failures return TRON_EINVAL and create nothing.  1 <= n, d < 2^29; nnz may be 0;
  * empty rows and columns are allowed.
  */
 TRON_API int tron_dataset_create_csr(int64_t n, int64_t d, const int64_t *rowptr, const int32_t *col,

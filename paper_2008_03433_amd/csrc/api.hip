@@ -183,9 +183,10 @@ int tron_dataset_create_csr(int64_t n, int64_t d, const int64_t *rowptr, const i
                             const double *y, int mem, void *hip_stream, tron_dataset **out)
 {
     if (out) *out = nullptr;
-    if (!out || !rowptr || !y || n < 1 || d < 1 || n > 0x7ffffff0 || d > 0x7ffffff0 ||
+    // the sparse kernels address the gathered vectors through 32-bit byte offsets: n, d < 2^29
+    if (!out || !rowptr || !y || n < 1 || d < 1 || n >= (1 << 29) || d >= (1 << 29) ||
         (mem != TRON_MEM_HOST && mem != TRON_MEM_DEVICE)) {
-        set_error("tron_dataset_create_csr: bad argument (need 1 <= n,d < 2^31, non-null rowptr/y/out, mem in {0,1})");
+        set_error("tron_dataset_create_csr: bad argument (need 1 <= n,d < 2^29, non-null rowptr/y/out, mem in {0,1})");
         return TRON_EINVAL;
     }
     TRON_TRY(check_device());

@@ -319,7 +319,7 @@ __device__ __forceinline__ double epilogue(double sum, int64_t r, const double *
 // chunk-local tables row_lo[0..1] and carry slot *carry_out.
 // With HOT, a negative stored column c means "entry ~c of the workgroup's LDS table" (the most frequent
 // columns of the partition, copied from x once per workgroup).
-// x[c] through a 32-bit byte offset (c < 2^28 is guaranteed by the plan builder's size checks)
+// x[c] through a 32-bit byte offset (tron_dataset_create_csr accepts n, d < 2^29 only)
 __device__ __forceinline__ double load_elem(const double *__restrict__ x, int c)
 {
     return *reinterpret_cast<const double *>(reinterpret_cast<const char *>(x) + (size_t)((uint32_t)c << 3));

@@ -120,7 +120,8 @@ struct Tile {
 };
 
 // ------------------------------------------------------------------ Hessian-vector pass
-// MASK: D is stored as one byte per row (L2-SVM: D_ii = 2 on the active set, else 0) instead of an fp64 value.
+// MASK: D is the active set of the L2-SVM (D_ii = 2 on it, else 0) instead of an fp64 value per row: one bit per row,
+// a 64-bit word per wave tile, when a tile has 64 rows (d <= 32); one byte per row otherwise.
 // DIAG: column sums of D_i x_ij^2 instead (the diagonal of X^T D X; v is not read).
 template <int E, int L, int U, bool VEC, bool MASK, bool DIAG>
 __global__ __launch_bounds__(kBlock) void k_dense_hv(int64_t n, int64_t d, const double *__restrict__ X,
@@ -146,7 +147,13 @@ __global__ __launch_bounds__(kBlock) void k_dense_hv(int64_t n, int64_t d, const
         double x[U][E], t[U], c[U];
         T::load(X, n, d, row0, lane, x);
         double Drow = 0.0;
-        if (lane < T::RT && row0 + lane < n) Drow = MASK ? (Dm[row0 + lane] ? 2.0 : 0.0) : D[row0 + lane];
+        if (MASK && T::RT == kWave) {
+            // one 64-bit word per tile: bit i = row row0 + i is active (rows past n are never set)
+            const uint64_t bits = reinterpret_cast<const uint64_t *>(Dv)[tile];
+            Drow = ((bits >> lane) & 1u) ? 2.0 : 0.0;
+        } else if (lane < T::RT && row0 + lane < n) {
+            Drow = MASK ? (Dm[row0 + lane] ? 2.0 : 0.0) : D[row0 + lane];
+        }
         if (DIAG) {
             T::from_row_owner(Drow, lane, c);
 #pragma unroll
@@ -189,9 +196,25 @@ __global__ __launch_bounds__(kBlock) void k_dense_fun_grad(int64_t n, int64_t d,
         acc[e] = 0.0;
     }
     double loss_acc = 0.0;
+    // D of a tile is stored only after the loads of the next tile have been issued: the memory counter retires in
+    // order, so a store issued before them would have to complete before their data could be used.
+    // Active set of the L2-SVM when a tile has 64 rows: one 64-bit word per tile.  A wavefront then walks a
+    // contiguous range of tiles, lane i keeps the word of its i-th, 64+i-th, ... tile, and every 64 tiles the words
+    // go out as one 512-byte store: small stores between the reads cost far more than their bytes.
+    constexpr bool kBits = (LOSS == TRON_LOSS_L2SVM) && (T::RT == kWave);
+    uint64_t *Dbits = static_cast<uint64_t *>(Dv);
+    uint64_t held_bits = 0;
+    int64_t held_tile = -1;
     const int64_t ntiles = (n + T::RT - 1) / T::RT;
     const int64_t nwaves = (int64_t)gridDim.x * kWavesPerBlock;
-    for (int64_t tile = (int64_t)blockIdx.x * kWavesPerBlock + wv; tile < ntiles; tile += nwaves) {
+    const int64_t wave_id = (int64_t)blockIdx.x * kWavesPerBlock + wv;
+    const int64_t per_wave = (ntiles + nwaves - 1) / nwaves;
+    // kBits: tiles [first, last) one after the other; otherwise tiles wave_id, wave_id + nwaves, ...
+    const int64_t first = kBits ? wave_id * per_wave : wave_id;
+    const int64_t last = kBits ? ((first + per_wave < ntiles) ? first + per_wave : ntiles) : ntiles;
+    const int64_t step = kBits ? 1 : nwaves;
+    int it = 0;
+    for (int64_t tile = first; tile < last; tile += step, ++it) {
         const int64_t row0 = tile * T::RT;
         double x[U][E], t[U], c[U];
         T::load(X, n, d, row0, lane, x);
@@ -202,11 +225,21 @@ __global__ __launch_bounds__(kBlock) void k_dense_fun_grad(int64_t n, int64_t d,
         double alpha, zhat, Di;
         loss_terms_dev<LOSS>(z, yrow, alpha, zhat, Di);
         if (mine) {
-            if (LOSS == TRON_LOSS_L2SVM) Dmask[row0 + lane] = (Di != 0.0) ? 1 : 0;
-            else Dout[row0 + lane] = Di;
             loss_acc += alpha;
         } else {
+            Di = 0.0;
             zhat = 0.0;
+        }
+        if (kBits) {
+            const uint64_t bits = __ballot(Di != 0.0);
+            if (lane == (it & (kWave - 1))) { held_bits = bits; held_tile = tile; }
+            if ((it & (kWave - 1)) == kWave - 1) {
+                Dbits[held_tile] = held_bits;   // every lane holds one: 64 consecutive words
+                held_tile = -1;
+            }
+        } else if (mine) {
+            if (LOSS == TRON_LOSS_L2SVM) Dmask[row0 + lane] = (Di != 0.0) ? 1 : 0;
+            else Dout[row0 + lane] = Di;
         }
         T::from_row_owner(zhat, lane, c);
 #pragma unroll
@@ -215,6 +248,7 @@ __global__ __launch_bounds__(kBlock) void k_dense_fun_grad(int64_t n, int64_t d,
             for (int e = 0; e < E; ++e) acc[e] = fma(c[u], x[u][e], acc[e]);
         }
     }
+    if (kBits && held_tile >= 0) Dbits[held_tile] = held_bits;
     T::flush(acc, d, lane, wv, lds, partials);
     loss_acc = block_sum(loss_acc, lds_red);
     if (threadIdx.x == 0) loss_partials[blockIdx.x] = loss_acc;
