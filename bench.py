@@ -348,6 +348,38 @@ def small_config(args, wname: str) -> dict:
     return out
 
 
+def active_set_sweep() -> dict:
+    """Dense L2-SVM Hessian-vector time against the active fraction |I|/n: the pass does not read the rows outside
+    the active set (the paper compacts X_I into a copy instead, Section 5).  20M x 24 rows of the config-5 generator;
+    w is moved along the class direction to shrink the active set; the fraction is counted on the first 200k rows."""
+    import numpy as np
+    import torch
+    import datagen as dg
+    import paper_2008_03433_amd as tron
+    n, d = 20_000_000, 24
+    p = dg.config5(n=n, d=d)
+    ds = upload(tron, p)
+    mu = p.mu / np.linalg.norm(p.mu)
+    Xs, ys = p.rows(0, 200_000)
+    v = torch.randn(d, dtype=torch.float64, device="cuda")
+    Hv = torch.empty_like(v)
+    points = []
+    for scale in (0.0, 1.0, 3.0, 12.0):
+        w = torch.tensor(scale * mu, dtype=torch.float64, device="cuda")
+        ds.fun_grad(dg.LOSS_L2SVM, 0.1, w, None)
+        frac = float(np.mean(ys * (Xs @ (scale * mu)) < 1.0))
+        for _ in range(3):
+            ds.hv(0.1, v, Hv, want_vHv=False)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(20):
+            ds.hv(0.1, v, Hv, want_vHv=False)
+        torch.cuda.synchronize()
+        points.append({"w_norm": scale, "active_fraction": frac, "hv_ms": (time.perf_counter() - t0) / 20 * 1e3})
+    ds.close()
+    return {"n": n, "d": d, "points": points}
+
+
 def stream_probe() -> dict:
     """Attainable streaming rates on this device (also the known-size kernels the byte counters are scaled with)."""
     import torch
@@ -404,6 +436,7 @@ def main() -> int:
         # the other loss / storage mixes (GPU only: their oracle solves take minutes)
         quiet = argparse.Namespace(**{**vars(args), "no_cpu_baseline": True})
         out["mixes"] = {w: small_config(quiet, w) for w in ("susy_shape", "higgs_shape", "c3_svm")}
+        out["active_set"] = active_set_sweep()
     print(json.dumps(out), flush=True)
     return 0
 

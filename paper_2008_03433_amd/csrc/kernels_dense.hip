@@ -30,16 +30,17 @@ struct Tile {
     static constexpr int RW = kWave / L;     // rows per step
     static constexpr int RT = U * RW;        // rows per wave tile
 
-    // load the U x E block of this lane; out-of-range rows / columns read as zero
+    // load the U x E block of this lane; out-of-range rows / columns read as zero.  rows: bit i clear = row row0 + i
+    // is not needed (its coefficient is zero) and is not read at all
     __device__ static __forceinline__ void load(const double *__restrict__ X, int64_t n, int64_t d, int64_t row0,
-                                                int lane, double (&x)[U][E])
+                                                int lane, double (&x)[U][E], uint64_t rows = ~0ull)
     {
         const int q = lane % L, rl = lane / L;
         const int c0 = q * E;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t row = row0 + u * RW + rl;
-            const bool rok = row < n;
+            const bool rok = row < n && ((rows >> (u * RW + rl)) & 1u);
             const double *p = X + row * d + c0;
             if (VEC) {
 #pragma unroll
@@ -142,14 +143,24 @@ __global__ __launch_bounds__(kBlock) void k_dense_hv(int64_t n, int64_t d, const
     }
     const int64_t ntiles = (n + T::RT - 1) / T::RT;
     const int64_t nwaves = (int64_t)gridDim.x * kWavesPerBlock;
-    for (int64_t tile = (int64_t)blockIdx.x * kWavesPerBlock + wv; tile < ntiles; tile += nwaves) {
+    // With the active set as one 64-bit word per tile (bit i = row row0 + i is active; rows past n are never set)
+    // the rows outside it are not read: the pass moves 8 |I| d bytes, the saving the paper gets from a compacted
+    // copy X_I (Section 5) without the copy.  The word of the next tile is fetched one iteration ahead.
+    constexpr bool kBits = MASK && T::RT == kWave;
+    const uint64_t *Dbits = static_cast<const uint64_t *>(Dv);
+    const int64_t tile0 = (int64_t)blockIdx.x * kWavesPerBlock + wv;
+    uint64_t bits_next = (kBits && tile0 < ntiles) ? Dbits[tile0] : 0;
+    for (int64_t tile = tile0; tile < ntiles; tile += nwaves) {
         const int64_t row0 = tile * T::RT;
         double x[U][E], t[U], c[U];
-        T::load(X, n, d, row0, lane, x);
+        const uint64_t bits = bits_next;
+        if (kBits) {
+            bits_next = (tile + nwaves < ntiles) ? Dbits[tile + nwaves] : 0;
+            if (bits == 0) continue;   // no active row in the tile
+        }
+        T::load(X, n, d, row0, lane, x, kBits ? bits : ~0ull);
         double Drow = 0.0;
-        if (MASK && T::RT == kWave) {
-            // one 64-bit word per tile: bit i = row row0 + i is active (rows past n are never set)
-            const uint64_t bits = reinterpret_cast<const uint64_t *>(Dv)[tile];
+        if (kBits) {
             Drow = ((bits >> lane) & 1u) ? 2.0 : 0.0;
         } else if (lane < T::RT && row0 + lane < n) {
             Drow = MASK ? (Dm[row0 + lane] ? 2.0 : 0.0) : D[row0 + lane];

@@ -41,6 +41,43 @@ def test_dense_many_tiles_ragged_tail(rng, loss):
     check_calls(p, loss, p.C, rng, w_scale=0.05, n_hv=1)
 
 
+def test_dense_svm_mostly_inactive_rows(rng):
+    # separable data and a long w along the separating direction: most rows (and many whole 64-row tiles) leave the
+    # active set, so the Hessian-vector pass skips them; a second w leaves (almost) no active row (Hv ~ v)
+    import paper_2008_03433_amd as tron
+    from oracle import Oracle
+    torch = torch_mod()
+    n, d = 40_000, 24
+    y = np.where(rng.random(n) < 0.5, 1.0, -1.0)
+    u = rng.standard_normal(d); u /= np.linalg.norm(u)
+    X = rng.standard_normal((n, d)) + 4.0 * y[:, None] * u[None, :]
+    X[5000:9000] = np.abs(X[5000:9000]) * 0 + 6.0 * y[5000:9000, None] * u[None, :]   # a run of rows far inside their class
+    p = DenseProblem("separable", n, d, X, y)
+    o = Oracle.from_problem(p)
+    ds = tron.Dataset.from_problem(p)
+    try:
+        for scale in (0.4, 50.0):
+            w = scale * u
+            f_o, g_o, D_o = o.fun_grad(LOSS_L2SVM, 0.5, w)
+            frac = float(np.mean(D_o != 0.0))
+            assert (0.0 < frac < 0.5) if scale < 1 else frac < 1e-3
+            assert not D_o[5000:9000].any()          # whole tiles without an active row
+            g_d = torch.empty(d, dtype=torch.float64, device="cuda")
+            f_g = ds.fun_grad(LOSS_L2SVM, 0.5, dev(w), g_d)
+            assert abs(f_g - f_o) <= 1e-10 * abs(f_o)
+            v = rng.standard_normal(d)
+            Hv_d = torch.empty(d, dtype=torch.float64, device="cuda")
+            vHv = ds.hv(0.5, dev(v), Hv_d)
+            Hv_o = o.hv(0.5, D_o, v)
+            assert np.linalg.norm(Hv_d.cpu().numpy() - Hv_o) <= 1e-10 * np.linalg.norm(Hv_o)
+            assert abs(vHv - v @ Hv_o) <= 1e-10 * abs(v @ Hv_o)
+            hd = torch.empty(d, dtype=torch.float64, device="cuda")
+            ds.hess_diag(0.5, hd)
+            assert np.linalg.norm(hd.cpu().numpy() - o.hess_diag(0.5, D_o)) <= 1e-10 * np.linalg.norm(o.hess_diag(0.5, D_o))
+    finally:
+        ds.close()
+
+
 # ------------------------------------------------------------------ CSR layout
 @pytest.mark.parametrize("loss", [LOSS_LR, LOSS_L2SVM])
 def test_csr_config1(rng, loss):
