@@ -223,7 +223,6 @@ TRON_API int tron_probe_read_bandwidth(const double *src_dev, int64_t count, int
  *   "csr_head" (0/1): a head partition for the most frequent columns of the whole matrix (needs csr_hot);
  *   "csr_range_slots" (2..4096): LDS table entries per column range;
  *   "csr_tiles" (0/1): hot-row tiles for the transposed product;
- *   "csr_two_streams" (0/1): tiles on a second stream;
  *   "csr_hot_blocks_per_part", "csr_range_blocks_per_part", "csr_blocks_per_part",
  *   "csr_tile_blocks_per_slice": persistent workgroups of the head, table, table-less and tile kernels.
  * Unknown names or values return TRON_EINVAL.

@@ -116,9 +116,6 @@ static int alloc_common(tron_dataset *ds)
     TRON_HIP(hipMalloc(reinterpret_cast<void **>(&ds->partials), sizeof(double) * need));
     TRON_HIP(hipMalloc(reinterpret_cast<void **>(&ds->scal_dev), sizeof(double) * kScalars));
     TRON_HIP(hipHostMalloc(reinterpret_cast<void **>(&ds->scal_host), sizeof(double) * kScalars, hipHostMallocDefault));
-    TRON_HIP(hipStreamCreateWithFlags(&ds->side, hipStreamNonBlocking));
-    TRON_HIP(hipEventCreateWithFlags(&ds->ev_fork, hipEventDisableTiming));
-    TRON_HIP(hipEventCreateWithFlags(&ds->ev_join, hipEventDisableTiming));
     ds->vec_grid_n = vec_grid_for(ds->n);
     ds->vec_grid_d = vec_grid_for(ds->d);
     return TRON_OK;
@@ -172,9 +169,6 @@ void tron_dataset_destroy(tron_dataset *ds)
     hipFree(ds->partials); hipFree(ds->row_partials); hipFree(ds->scal_dev);
     if (ds->scal_host) hipHostFree(ds->scal_host);
     for (double *p : ds->sv) hipFree(p);
-    if (ds->side) { hipStreamSynchronize(ds->side); hipStreamDestroy(ds->side); }
-    if (ds->ev_fork) hipEventDestroy(ds->ev_fork);
-    if (ds->ev_join) hipEventDestroy(ds->ev_join);
     ds->prof.destroy();
     delete ds;
 }
@@ -479,10 +473,6 @@ int tron_tuning_set(const char *name, int64_t value)
     }
     if (name && strcmp(name, "csr_tiles") == 0 && (value == 0 || value == 1)) {
         g_tuning.csr_tiles = value;
-        return TRON_OK;
-    }
-    if (name && strcmp(name, "csr_two_streams") == 0 && (value == 0 || value == 1)) {
-        g_tuning.csr_two_streams = value;
         return TRON_OK;
     }
     if (name && strcmp(name, "csr_tile_blocks_per_slice") == 0 && value >= 1 && value <= 1024) {

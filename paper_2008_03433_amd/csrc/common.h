@@ -37,8 +37,6 @@ struct Tuning {
     int64_t csr_hot_blocks_per_part = 96;  // persistent workgroups per partition when the LDS table is used
     int64_t csr_blocks_per_part = 128;     // persistent workgroups per column range without LDS tables
     int64_t csr_tiles = 1;   // hot-row tiles for the transposed orientation of partitioned matrices (0 = off)
-    int64_t csr_two_streams = 0;  // 1 = run the hot-row tiles beside the CSR remainder on a second stream (measured slower: both
-                                  // kernels compete for the same per-CU miss queue)
     int64_t csr_tile_blocks_per_slice = 96;  // persistent workgroups per slice of hot rows
 };
 extern Tuning g_tuning;
@@ -181,8 +179,6 @@ struct tron_dataset {
     int64_t n = 0, d = 0;
     bool dense = false;
     hipStream_t stream = nullptr;
-    hipStream_t side = nullptr;      // library-owned second stream: independent kernels of one call run beside `stream`
-    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     int device = 0;
 
     // dense

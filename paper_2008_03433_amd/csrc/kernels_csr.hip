@@ -964,12 +964,7 @@ static TilePtrs tile_ptrs(const HotTiles &H) { return TilePtrs{H.val, H.iloc, H.
 static int launch_hot_tiles(tron_dataset *ds, const CsrPlan &A, const double *x, bool square)
 {
     const HotTiles &H = A.hot;
-    // The tiles stream from HBM, the CSR remainder waits on gather misses: they run side by side on two streams.
-    hipStream_t st = g_tuning.csr_two_streams ? ds->side : ds->stream;
-    if (st != ds->stream) {
-        TRON_HIP(hipEventRecord(ds->ev_fork, ds->stream));
-        TRON_HIP(hipStreamWaitEvent(st, ds->ev_fork, 0));
-    }
+    hipStream_t st = ds->stream;
     {
         ProfScope ps(ds, SLOT_SPMV_TILES, st);
         if (square)
@@ -986,7 +981,6 @@ static int launch_hot_tiles(tron_dataset *ds, const CsrPlan &A, const double *x,
                            H.wg_acc, H.sums);
         TRON_HIP(hipGetLastError());
     }
-    if (st != ds->stream) TRON_HIP(hipEventRecord(ds->ev_join, st));
     return TRON_OK;
 }
 
@@ -1254,7 +1248,6 @@ int spmv_axpy(tron_dataset *ds, const CsrPlan &A, int slot, const double *x, con
         hot.sums = A.hot.sums;
     }
     TRON_TRY(launch_partials(ds, A, slot, x, square));
-    if (hot.sums && g_tuning.csr_two_streams) TRON_HIP(hipStreamWaitEvent(ds->stream, ds->ev_join, 0));
     ProfScope ps(ds, SLOT_SPMV_COMBINE);
     const int g = vec_grid(A.rows);
     if (dot_self)
