@@ -384,7 +384,8 @@ int tron_fun_grad(tron_dataset *ds, int loss, double C, const double *w_dev, dou
     const int slot = ds->have_D ? 1 - ds->Dcur : ds->Dcur;
     if (ds->dense) {
         TRON_TRY(dense_fun_grad(ds, loss, C, w_dev, slot, g_dev));
-        TRON_TRY(read_scalars(ds, 3));
+        TRON_TRY(read_scalars(ds, 4));
+        ds->active_frac[slot] = ds->scal_host[3] / (double)ds->n;
         *f_host = 0.5 * ds->scal_host[1] + C * ds->scal_host[0];
     } else {
         TRON_TRY(fun_eval(ds, loss, C, w_dev, slot, f_host));

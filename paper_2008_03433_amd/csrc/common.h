@@ -191,6 +191,7 @@ struct tron_dataset {
     double *z = nullptr;         // n   (sparse: margins X w; also a0 / a1 work space for Hv)
     double *zhat = nullptr;      // n   (sparse only; dense folds it into the fused pass)
     double *Dbuf[2] = {nullptr, nullptr};  // n each: D at the accepted w and at the trial point
+    double active_frac[2] = {1.0, 1.0};    // dense: fraction of rows with D != 0 in each buffer (from the last fun/grad pass)
     bool D_is_mask[2] = {false, false};    // dense L2-SVM: the buffer holds one active-set byte per row instead
     int Dcur = 0;
     bool have_D = false;
@@ -262,7 +263,8 @@ bool dense_supported(int64_t d);
 int dense_grid_for(int64_t n, int64_t d);
 int64_t dense_partials_needed(int64_t n, int64_t d);
 // fused pass: z = X w, loss terms, D -> Dout, partial sums of X^T zhat and of the loss;
-// then g = w + C (column sums) (if g != null), scalars[0] = sum loss, [1] = w.w, [2] = g.g
+// then g = w + C (column sums) (if g != null), scalars[0] = sum loss, [1] = w.w, [2] = g.g, [3] = rows with D != 0
+// (the caller reads the four scalars and records scalars[3] / n in active_frac[Dslot])
 int dense_fun_grad(tron_dataset *ds, int loss, double C, const double *w, int Dslot, double *g);
 int dense_labels_from_device(tron_dataset *ds, int64_t row0, int64_t m, const double *y_dev);
 // Hv = v + C X^T (D (X v)); scalars[0] = v.Hv

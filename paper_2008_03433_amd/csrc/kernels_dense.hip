@@ -124,7 +124,9 @@ struct Tile {
 // MASK: D is the active set of the L2-SVM (D_ii = 2 on it, else 0) instead of an fp64 value per row: one bit per row,
 // a 64-bit word per wave tile, when a tile has 64 rows (d <= 32); one byte per row otherwise.
 // DIAG: column sums of D_i x_ij^2 instead (the diagonal of X^T D X; v is not read).
-template <int E, int L, int U, bool VEC, bool MASK, bool DIAG>
+// SKIP (with the bit words only): rows outside the active set are not read.  Chosen by the host when a noticeable
+// part of the rows is inactive; with (almost) every row active the plain loop is about 1% faster.
+template <int E, int L, int U, bool VEC, bool MASK, bool DIAG, bool SKIP>
 __global__ __launch_bounds__(kBlock) void k_dense_hv(int64_t n, int64_t d, const double *__restrict__ X,
                                                      const void *__restrict__ Dv, const double *__restrict__ v,
                                                      double *__restrict__ partials)
@@ -149,16 +151,18 @@ __global__ __launch_bounds__(kBlock) void k_dense_hv(int64_t n, int64_t d, const
     constexpr bool kBits = MASK && T::RT == kWave;
     const uint64_t *Dbits = static_cast<const uint64_t *>(Dv);
     const int64_t tile0 = (int64_t)blockIdx.x * kWavesPerBlock + wv;
-    uint64_t bits_next = (kBits && tile0 < ntiles) ? Dbits[tile0] : 0;
+    uint64_t bits_next = (kBits && SKIP && tile0 < ntiles) ? Dbits[tile0] : 0;
     for (int64_t tile = tile0; tile < ntiles; tile += nwaves) {
         const int64_t row0 = tile * T::RT;
         double x[U][E], t[U], c[U];
-        const uint64_t bits = bits_next;
-        if (kBits) {
+        uint64_t bits = 0;
+        if (kBits && SKIP) {
+            bits = bits_next;
             bits_next = (tile + nwaves < ntiles) ? Dbits[tile + nwaves] : 0;
             if (bits == 0) continue;   // no active row in the tile
         }
-        T::load(X, n, d, row0, lane, x, kBits ? bits : ~0ull);
+        T::load(X, n, d, row0, lane, x, (kBits && SKIP) ? bits : ~0ull);
+        if (kBits && !SKIP) bits = Dbits[tile];
         double Drow = 0.0;
         if (kBits) {
             Drow = ((bits >> lane) & 1u) ? 2.0 : 0.0;
@@ -191,7 +195,7 @@ template <int E, int L, int U, bool VEC, int LOSS>
 __global__ __launch_bounds__(kBlock) void k_dense_fun_grad(int64_t n, int64_t d, const double *__restrict__ X,
                                                            const int8_t *__restrict__ y, const double *__restrict__ w,
                                                            void *__restrict__ Dv, double *__restrict__ partials,
-                                                           double *__restrict__ loss_partials)
+                                                           double *__restrict__ loss_partials, double *__restrict__ active_partials)
 {
     double *Dout = static_cast<double *>(Dv);       // logistic loss: fp64 D
     uint8_t *Dmask = static_cast<uint8_t *>(Dv);    // L2-SVM: active-set mask
@@ -206,7 +210,7 @@ __global__ __launch_bounds__(kBlock) void k_dense_fun_grad(int64_t n, int64_t d,
         wreg[e] = (q * E + e < d) ? w[q * E + e] : 0.0;
         acc[e] = 0.0;
     }
-    double loss_acc = 0.0;
+    double loss_acc = 0.0, active_acc = 0.0;   // sum of the losses; number of rows with D != 0
     // D of a tile is stored only after the loads of the next tile have been issued: the memory counter retires in
     // order, so a store issued before them would have to complete before their data could be used.
     // Active set of the L2-SVM when a tile has 64 rows: one 64-bit word per tile.  A wavefront then walks a
@@ -237,6 +241,7 @@ __global__ __launch_bounds__(kBlock) void k_dense_fun_grad(int64_t n, int64_t d,
         loss_terms_dev<LOSS>(z, yrow, alpha, zhat, Di);
         if (mine) {
             loss_acc += alpha;
+            active_acc += (Di != 0.0) ? 1.0 : 0.0;
         } else {
             Di = 0.0;
             zhat = 0.0;
@@ -263,6 +268,8 @@ __global__ __launch_bounds__(kBlock) void k_dense_fun_grad(int64_t n, int64_t d,
     T::flush(acc, d, lane, wv, lds, partials);
     loss_acc = block_sum(loss_acc, lds_red);
     if (threadIdx.x == 0) loss_partials[blockIdx.x] = loss_acc;
+    active_acc = block_sum(active_acc, lds_red);
+    if (threadIdx.x == 0) active_partials[blockIdx.x] = active_acc;
 }
 
 // ------------------------------------------------------------------ second stage
@@ -286,14 +293,19 @@ __global__ __launch_bounds__(kBlock) void k_dense_columns(int64_t d, int grid, c
     }
 }
 
-// scal[0] = sum loss partials (or v.Hv when nloss == 0: then scal[0] = sum colprod), scal[1] = w.w, scal[2] = sum colprod
+// scal[0] = sum loss partials (or v.Hv when nloss == 0: then scal[0] = sum colprod), scal[1] = w.w, scal[2] = sum colprod,
+// scal[3] = sum of the active-row counts
 __global__ __launch_bounds__(kBlock) void k_dense_scalars(int64_t d, int nloss, const double *__restrict__ loss_partials,
+                                                          const double *__restrict__ active_partials,
                                                           const double *__restrict__ w, const double *__restrict__ colprod,
                                                           double *__restrict__ scal)
 {
     __shared__ double lds[kWavesPerBlock];
-    double a = 0.0, b = 0.0, c = 0.0;
-    for (int i = threadIdx.x; i < nloss; i += kBlock) a += loss_partials[i];
+    double a = 0.0, b = 0.0, c = 0.0, e = 0.0;
+    for (int i = threadIdx.x; i < nloss; i += kBlock) {
+        a += loss_partials[i];
+        e += active_partials[i];
+    }
     for (int64_t j = threadIdx.x; j < d; j += kBlock) {
         if (w) b += w[j] * w[j];
         c += colprod[j];
@@ -301,11 +313,13 @@ __global__ __launch_bounds__(kBlock) void k_dense_scalars(int64_t d, int nloss, 
     a = block_sum(a, lds);
     b = block_sum(b, lds);
     c = block_sum(c, lds);
+    e = block_sum(e, lds);
     if (threadIdx.x == 0) {
         if (nloss > 0) {
             scal[0] = a;
             scal[1] = b;
             scal[2] = c;
+            scal[3] = e;
         } else {
             scal[0] = c;
         }
@@ -313,6 +327,8 @@ __global__ __launch_bounds__(kBlock) void k_dense_scalars(int64_t d, int nloss, 
 }
 
 // ------------------------------------------------------------------ dispatch
+constexpr double kSkipBelow = 0.95;   // active fraction under which the Hessian-vector pass skips the inactive rows
+
 struct Shape { int E, L; };
 
 // smallest L in {1,2,4,...,64} with E = ceil(d/L) <= 8; for even d an odd E is rounded up, so that every lane can
@@ -334,38 +350,36 @@ bool pick_shape(int64_t d, Shape &s)
 constexpr int pick_U(int E, int L) { return (L < 4 ? L : 4); }
 
 template <int E, int L>
-int launch_hv(tron_dataset *ds, const void *D, bool mask, const double *v)
+int launch_hv(tron_dataset *ds, const void *D, bool mask, bool skip, const double *v)
 {
     constexpr int U = pick_U(E, L);
     const bool vec = (E % 2 == 0) && (ds->d % 2 == 0);
     const int grid = ds->dense_grid;
-#define TRON_HV(V, M, G) \
-    hipLaunchKernelGGL((k_dense_hv<E, L, U, V, M, G>), dim3(grid), dim3(kBlock), 0, ds->stream, ds->n, ds->d, ds->X, D, v, ds->partials)
+#define TRON_HV(V, M, G, S) \
+    hipLaunchKernelGGL((k_dense_hv<E, L, U, V, M, G, S>), dim3(grid), dim3(kBlock), 0, ds->stream, ds->n, ds->d, ds->X, D, v, ds->partials)
+#define TRON_HV_V(M, G, S) do { if (vec) TRON_HV((E % 2 == 0), M, G, S); else TRON_HV(false, M, G, S); } while (0)
     if (v) {
-        if (mask) {
-            if (vec) TRON_HV((E % 2 == 0), true, false); else TRON_HV(false, true, false);
-        } else {
-            if (vec) TRON_HV((E % 2 == 0), false, false); else TRON_HV(false, false, false);
-        }
+        if (!mask) TRON_HV_V(false, false, false);
+        else if (skip) TRON_HV_V(true, false, true);
+        else TRON_HV_V(true, false, false);
     } else {   // no vector: the diagonal sums
-        if (mask) {
-            if (vec) TRON_HV((E % 2 == 0), true, true); else TRON_HV(false, true, true);
-        } else {
-            if (vec) TRON_HV((E % 2 == 0), false, true); else TRON_HV(false, false, true);
-        }
+        if (!mask) TRON_HV_V(false, true, false);
+        else if (skip) TRON_HV_V(true, true, true);
+        else TRON_HV_V(true, true, false);
     }
+#undef TRON_HV_V
 #undef TRON_HV
     return TRON_OK;
 }
 
 template <int E, int L>
-int launch_fg(tron_dataset *ds, int loss, const double *w, void *Dout, double *loss_partials)
+int launch_fg(tron_dataset *ds, int loss, const double *w, void *Dout, double *loss_partials, double *active_partials)
 {
     constexpr int U = pick_U(E, L);
     const bool vec = (E % 2 == 0) && (ds->d % 2 == 0);
     const int grid = ds->dense_grid;
 #define TRON_FG(V, LS) \
-    hipLaunchKernelGGL((k_dense_fun_grad<E, L, U, V, LS>), dim3(grid), dim3(kBlock), 0, ds->stream, ds->n, ds->d, ds->X, ds->y8, w, Dout, ds->partials, loss_partials)
+    hipLaunchKernelGGL((k_dense_fun_grad<E, L, U, V, LS>), dim3(grid), dim3(kBlock), 0, ds->stream, ds->n, ds->d, ds->X, ds->y8, w, Dout, ds->partials, loss_partials, active_partials)
     if (loss == TRON_LOSS_LR) {
         if (vec) TRON_FG((E % 2 == 0), TRON_LOSS_LR); else TRON_FG(false, TRON_LOSS_LR);
     } else {
@@ -409,8 +423,8 @@ int launch_fg(tron_dataset *ds, int loss, const double *w, void *Dout, double *l
     set_error("internal: no dense kernel for E=%d L=%d", s.E, s.L);              \
     return TRON_EINVAL;
 
-int dispatch_hv(tron_dataset *ds, const void *D, bool mask, const double *v) { TRON_DISPATCH(launch_hv, ds, D, mask, v) }
-int dispatch_fg(tron_dataset *ds, int loss, const double *w, void *Dout, double *lp) { TRON_DISPATCH(launch_fg, ds, loss, w, Dout, lp) }
+int dispatch_hv(tron_dataset *ds, const void *D, bool mask, bool skip, const double *v) { TRON_DISPATCH(launch_hv, ds, D, mask, skip, v) }
+int dispatch_fg(tron_dataset *ds, int loss, const double *w, void *Dout, double *lp, double *ap) { TRON_DISPATCH(launch_fg, ds, loss, w, Dout, lp, ap) }
 
 }  // namespace
 
@@ -448,11 +462,11 @@ int dense_grid_for(int64_t n, int64_t d)
     return (int)g;
 }
 
-// column partials (d * grid) followed by loss partials (grid) and column products (d)
+// column partials (d * grid) followed by loss partials (grid), column products (d) and active-row counts (grid)
 int64_t dense_partials_needed(int64_t n, int64_t d)
 {
     const int64_t g = dense_grid_for(n, d);
-    return d * g + g + d;
+    return d * g + g + d + g;
 }
 
 int dense_hv(tron_dataset *ds, double C, int Dslot, const double *v, double *Hv)
@@ -463,14 +477,14 @@ int dense_hv(tron_dataset *ds, double C, int Dslot, const double *v, double *Hv)
     double *colprod = ds->partials + ds->d * grid + grid;
     {
         ProfScope ps(ds, SLOT_DENSE_HV);
-        TRON_TRY(dispatch_hv(ds, D, mask, v));
+        TRON_TRY(dispatch_hv(ds, D, mask, mask && ds->active_frac[Dslot] < kSkipBelow, v));
         TRON_HIP(hipGetLastError());
     }
     ProfScope ps(ds, SLOT_DENSE_FINALIZE);
     const int cg = (int)((ds->d + kWavesPerBlock - 1) / kWavesPerBlock);
     hipLaunchKernelGGL(k_dense_columns, dim3(cg), dim3(kBlock), 0, ds->stream, ds->d, grid, ds->partials, v, C, Hv, v, colprod);
     hipLaunchKernelGGL(k_dense_scalars, dim3(1), dim3(kBlock), 0, ds->stream, ds->d, 0, (const double *)nullptr,
-                       (const double *)nullptr, colprod, ds->scal_dev);
+                       (const double *)nullptr, (const double *)nullptr, colprod, ds->scal_dev);
     TRON_HIP(hipGetLastError());
     return TRON_OK;
 }
@@ -482,7 +496,7 @@ int dense_hess_diag(tron_dataset *ds, double C, int Dslot, double *out)
     double *colprod = ds->partials + ds->d * grid + grid;
     {
         ProfScope ps(ds, SLOT_DENSE_HV);
-        TRON_TRY(dispatch_hv(ds, ds->Dbuf[Dslot], ds->D_is_mask[Dslot], nullptr));
+        TRON_TRY(dispatch_hv(ds, ds->Dbuf[Dslot], ds->D_is_mask[Dslot], ds->D_is_mask[Dslot] && ds->active_frac[Dslot] < kSkipBelow, nullptr));
         TRON_HIP(hipGetLastError());
     }
     ProfScope ps(ds, SLOT_DENSE_FINALIZE);
@@ -500,16 +514,18 @@ int dense_fun_grad(tron_dataset *ds, int loss, double C, const double *w, int Ds
     const int grid = ds->dense_grid;
     double *loss_partials = ds->partials + ds->d * grid;
     double *colprod = loss_partials + grid;
+    double *active_partials = colprod + ds->d;
     {
         ProfScope ps(ds, SLOT_DENSE_FUN_GRAD);
-        TRON_TRY(dispatch_fg(ds, loss, w, Dout, loss_partials));
+        TRON_TRY(dispatch_fg(ds, loss, w, Dout, loss_partials, active_partials));
         TRON_HIP(hipGetLastError());
     }
     ProfScope ps(ds, SLOT_DENSE_FINALIZE);
     const int cg = (int)((ds->d + kWavesPerBlock - 1) / kWavesPerBlock);
     hipLaunchKernelGGL(k_dense_columns, dim3(cg), dim3(kBlock), 0, ds->stream, ds->d, grid, ds->partials, w, C, g,
                        (const double *)nullptr, colprod);
-    hipLaunchKernelGGL(k_dense_scalars, dim3(1), dim3(kBlock), 0, ds->stream, ds->d, grid, loss_partials, w, colprod, ds->scal_dev);
+    hipLaunchKernelGGL(k_dense_scalars, dim3(1), dim3(kBlock), 0, ds->stream, ds->d, grid, loss_partials, active_partials, w, colprod,
+                       ds->scal_dev);
     TRON_HIP(hipGetLastError());
     return TRON_OK;
 }

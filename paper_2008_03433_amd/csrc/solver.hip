@@ -70,7 +70,8 @@ int eval_f(tron_dataset *ds, const tron_params &P, const double *w, int Dslot, d
 {
     if (ds->dense) {
         TRON_TRY(dense_fun_grad(ds, P.loss, P.C, w, Dslot, gout));
-        TRON_TRY(read_scalars(ds, 3));
+        TRON_TRY(read_scalars(ds, 4));
+        ds->active_frac[Dslot] = ds->scal_host[3] / (double)ds->n;
         *f = 0.5 * ds->scal_host[1] + P.C * ds->scal_host[0];
         *gnorm_dense = std::sqrt(ds->scal_host[2]);
         return TRON_OK;
