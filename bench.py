@@ -30,12 +30,12 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 
 # library profiler slot -> (kernel name in rocprofv3 output, profiles/ file that holds its byte counters)
 ROCPROF_NAMES = {
-    "dense_hv": ("k_dense_hv<6, 4, 4, true, true, false>", "dense_hv_fun_grad_c5.md"),
+    "dense_hv": ("k_dense_hv<6, 4, 4, true, true, false, false>", "dense_hv_fun_grad_c5.md"),
     "dense_fun_grad": ("k_dense_fun_grad<6, 4, 4, true, 1>", "dense_hv_fun_grad_c5.md"),
-    "spmv_head": ("k_csr_spmv_part<true, true>", "csr_spmv_c3.md"),
-    "spmv_fwd": ("k_csr_spmv_part<true, false>", "csr_spmv_c3.md"),
-    "spmv_bwd": ("k_csr_spmv_part<false, false>", "csr_spmv_c3.md"),
-    "spmv_tiles": ("k_hot_tiles", "csr_spmv_c3.md"),
+    "spmv_head": ("k_csr_spmv_part<true, true, false>", "csr_spmv_c3.md"),
+    "spmv_fwd": ("k_csr_spmv_part<true, false, false>", "csr_spmv_c3.md"),
+    "spmv_bwd": ("k_csr_spmv_part<false, false, false>", "csr_spmv_c3.md"),
+    "spmv_tiles": ("k_hot_tiles<false>", "csr_spmv_c3.md"),
 }
 
 
@@ -133,9 +133,10 @@ def measured_traffic(slot: str):
         if in_traffic and line.startswith(f"| `{kname}` |"):
             cells = [c.strip() for c in line.strip().strip("|").split("|")]
             try:
-                return (float(cells[2]) + float(cells[4])) * 1e9
+                total = (float(cells[2]) + float(cells[4])) * 1e9
             except (ValueError, IndexError):
                 return None
+            return total if total > 0.0 else None    # a row of zeros: the kernel was not in that profile
     return None
 
 
