@@ -264,8 +264,8 @@ int tron_dataset_create_csr(int64_t n, int64_t d, const int64_t *rowptr, const i
     if (rc >= 0 && nhot) rc = hot_tiles_build(ds->bwd, h_rowptr.data(), h_col.data(), h_val.data(), slot_code, nhot, ds->stream);
     if (rc >= 0) {
         int64_t need = 0;
-        if (ds->fwd.P > 1) need = std::max<int64_t>(need, (int64_t)kMaxParts * n);
-        if (ds->bwd.P > 1) need = std::max<int64_t>(need, (int64_t)kMaxParts * d);
+        if (ds->fwd.P > 1) need = std::max<int64_t>(need, ds->fwd.nseg_total);   // one partial sum per segment
+        if (ds->bwd.P > 1) need = std::max<int64_t>(need, ds->bwd.nseg_total);
         if (need > 0) {
             hipError_t e = hipMalloc(reinterpret_cast<void **>(&ds->row_partials), sizeof(double) * need);
             if (e != hipSuccess) rc = hip_fail(e, "allocate row partials", __FILE__, __LINE__);

@@ -132,6 +132,11 @@ struct HotTiles {
     void release();
 };
 
+// per group of 64 consecutive rows: the first segment of each partition whose row lies in the group or after it
+struct alignas(64) GroupBase {
+    int32_t first[16];   // kMaxParts used
+};
+
 struct CsrPlan {
     int64_t rows = 0, cols = 0, nnz = 0;
     HotTiles hot;                        // optional (transposed orientation of large matrices)
@@ -155,7 +160,7 @@ struct CsrPlan {
     // ---- P > 1
     int64_t part_base[kMaxParts] = {0};  // position of partition x in col/val (multiple of kChunk)
     int64_t part_nnz[kMaxParts] = {0};
-    int64_t part_seg0[kMaxParts] = {0};  // first segment of partition x in seg_row
+    int64_t part_seg0[kMaxParts] = {0};  // first segment of partition x (segments are numbered partition by partition)
     int part_chunk0[kMaxParts] = {0};    // first chunk id of partition x (= part_base / kChunk)
     int part_nchunks[kMaxParts] = {0};
     int part_nhot[kMaxParts] = {0};      // LDS-resident columns of partition x
@@ -163,7 +168,9 @@ struct CsrPlan {
     int range_slots = 0;                 // LDS table entries used by the column ranges (<= kHotSlots)
     int32_t *hot_ids = nullptr;          // device, (P+1)*kHotSlots column ids of the LDS tables (null: no LDS table)
     double *hot_x = nullptr;             // device, (P+1)*kHotSlots: the gather vector at those columns, refreshed every call
-    int32_t *seg_row = nullptr;          // device: row id of every segment, partition-major, ascending inside a partition
+    int64_t nseg_total = 0;              // segments (= partial sums) of the plan
+    int64_t ngroups = 0;                 // ceil(rows / 64)
+    GroupBase *group_base = nullptr;     // device, ngroups records
     int4 *chunk_tab = nullptr;           // device, per chunk: {first owned segment (partition-relative), number of owned
                                          //   segments, offset where the first owned segment starts, unused}
     uint8_t *flags = nullptr;            // device, nblocks * 256: bit e of byte t of a chunk = its entry 8t + e is the last

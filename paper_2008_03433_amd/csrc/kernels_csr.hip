@@ -42,7 +42,7 @@ void CsrPlan::release()
 {
     hot.release();
     hipFree(rowptr); hipFree(col); hipFree(col16); hipFree(val); hipFree(row_lo); hipFree(carry);
-    hipFree(hot_ids); hipFree(hot_x); hipFree(seg_row); hipFree(chunk_tab); hipFree(flags); hipFree(row_mask);
+    hipFree(hot_ids); hipFree(hot_x); hipFree(group_base); hipFree(chunk_tab); hipFree(flags); hipFree(row_mask);
     hipFree(fix_row); hipFree(fix_part); hipFree(fix_b0); hipFree(fix_cnt);
     *this = CsrPlan();
 }
@@ -256,8 +256,8 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
                     flags[((size_t)A.part_chunk0[x] + ck) * kBlock + pe / 8] |= (uint8_t)(1u << (pe % 8));
                 }
                 if (c_last > c) {
-                    fix_row.push_back((int32_t)r);
-                    fix_part.push_back(x);
+                    fix_row.push_back((int32_t)(A.part_seg0[x] + m));   // partitioned plans: the segment's slot in the partial sums
+                    fix_part.push_back(0);
                     fix_b0.push_back(A.part_chunk0[x] + c + 1);
                     fix_cnt.push_back(c_last - c);
                 }
@@ -284,7 +284,20 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
         }
         TRON_TRY(upload(&A.col, pcol.data(), pcol.size(), st));
         TRON_TRY(upload(&A.val, pval.data(), pval.size(), st));
-        TRON_TRY(upload(&A.seg_row, seg_row.data(), seg_row.size(), st));
+        // group_base[G].first[x] = first segment of partition x whose row is >= 64 G (see sum_parts)
+        A.ngroups = (rows + kWave - 1) / kWave;
+        A.nseg_total = nseg_total;
+        std::vector<GroupBase> gbase((size_t)A.ngroups);
+        std::memset(gbase.data(), 0, sizeof(GroupBase) * gbase.size());
+        for (int x = 0; x < NP; ++x) {
+            const int64_t s0 = A.part_seg0[x], s1 = (x + 1 < NP) ? A.part_seg0[x + 1] : nseg_total;
+            int64_t m = s0;
+            for (int64_t G = 0; G < A.ngroups; ++G) {
+                while (m < s1 && seg_row[m] < G * kWave) ++m;
+                gbase[(size_t)G].first[x] = (int32_t)m;
+            }
+        }
+        TRON_TRY(upload(&A.group_base, gbase.data(), gbase.size(), st));
         TRON_TRY(upload(&A.chunk_tab, tab.data(), tab.size(), st));
         TRON_TRY(upload(&A.flags, flags.data(), flags.size(), st));
         TRON_TRY(upload(&A.row_mask, mask.data(), mask.size(), st));
@@ -570,39 +583,28 @@ __device__ __forceinline__ void chunk_runs(double *prod, const unsigned f, doubl
     idx0 = cb + ci - cnt;
 }
 
-struct SegRegs {
-    unsigned flags;         // bit e: entry 8*tid + e is the last of its segment
-    int rid[kSegPasses];    // row ids of the owned segments tid + 256 j
-};
-
-__device__ __forceinline__ SegRegs load_segs(const int4 tab, const uint8_t *__restrict__ flags /* of this chunk */,
-                                             const int32_t *__restrict__ seg_row /* of this partition */)
+// flag byte of the calling thread: bit e = entry 8*tid + e is the last of its segment
+__device__ __forceinline__ unsigned load_flags(const uint8_t *__restrict__ flags /* of this chunk */)
 {
-    SegRegs s;
-    s.flags = flags[threadIdx.x];
-    const int nseg = tab.y;
-#pragma unroll
-    for (int j = 0; j < kSegPasses; ++j) {
-        const int sidx = (int)threadIdx.x + kBlock * j;
-        s.rid[j] = (sidx < nseg) ? seg_row[tab.x + sidx] : 0;
-    }
-    return s;
+    return flags[threadIdx.x];
 }
 
-// Segment sums of the chunk whose products are in LDS: owned segments to partial[row], the piece of a row that
-// started in an earlier chunk to *carry_slot.  Three barriers; the caller adds one before it reuses `prod`.
-__device__ __forceinline__ void chunk_segments(double *prod, const SegRegs &seg, const int nseg, const bool continued,
-                                               double *__restrict__ partial, double *__restrict__ carry_slot)
+// Segment sums of the chunk whose products are in LDS: the sums of the owned segments go to out[0 .. nseg) in segment
+// order (one coalesced store per 64 segments; the partial sums of a plan are stored segment by segment, not by row:
+// see sum_parts), the piece of a row that started in an earlier chunk to *carry_slot.  Three barriers; the caller
+// adds one before it reuses `prod`.
+__device__ __forceinline__ void chunk_segments(double *prod, const unsigned flags, const int nseg, const bool continued,
+                                               double *__restrict__ out, double *__restrict__ carry_slot)
 {
     double p[8], cin;
     int idx0;
-    chunk_runs(prod, seg.flags, p, cin, idx0);
+    chunk_runs(prod, flags, p, cin, idx0);
     double *outv = prod + kOutOffset;
     int i = idx0 - (continued ? 1 : 0);
     bool first = true;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-        if ((seg.flags >> e) & 1u) {
+        if ((flags >> e) & 1u) {
             const double v = first ? p[e] + cin : p[e];
             if (i < 0) *carry_slot = v;
             else outv[i] = v;
@@ -614,7 +616,7 @@ __device__ __forceinline__ void chunk_segments(double *prod, const SegRegs &seg,
 #pragma unroll
     for (int j = 0; j < kSegPasses; ++j) {
         const int sidx = (int)threadIdx.x + kBlock * j;
-        if (j * kBlock < nseg && sidx < nseg) partial[seg.rid[j]] = outv[sidx];
+        if (j * kBlock < nseg && sidx < nseg) out[sidx] = outv[sidx];
     }
 }
 
@@ -642,9 +644,8 @@ struct PartPtrs {   // device arrays of one partitioned plan (or of its head par
     const double *val;
     const int4 *chunk_tab;
     const uint8_t *flags;
-    const int32_t *seg_row;
     const double *hot_x;       // x at the LDS-resident columns, kHotSlots per partition (null without LDS tables)
-    double *partial;
+    double *partial;           // partial sums, one per segment of the plan
     double *carry;
 };
 
@@ -672,15 +673,14 @@ __device__ __forceinline__ void part_body(double *prod, double *table, const Par
     const double *val = pp.val + pa.base[xp];
     const int4 *__restrict__ tabs = pp.chunk_tab + pa.chunk0[xp];
     const uint8_t *__restrict__ flags = pp.flags + (int64_t)pa.chunk0[xp] * kBlock;
-    const int32_t *__restrict__ seg_row = pp.seg_row + pa.seg0[xp];
-    double *partial = pp.partial + (int64_t)xp * rows;
+    double *partial = pp.partial + pa.seg0[xp];
     double *carry = pp.carry + pa.chunk0[xp];
 
     int c = q;
     int4 tab = load_uniform(tabs + c);
     int4 tab_n = load_uniform(tabs + ((c + Q < nchunks) ? c + Q : c));
     StreamRegs<HEAD> cur = load_stream<HEAD>(col, val, (int64_t)c * kChunk);
-    SegRegs seg = load_segs(tab, flags + (int64_t)c * kBlock, seg_row);
+    unsigned fl = load_flags(flags + (int64_t)c * kBlock);
 
     for (; c < nchunks; c += Q) {
         products_to_lds<HOT, HEAD, SQ>(cur, x, table, prod);
@@ -691,14 +691,14 @@ __device__ __forceinline__ void part_body(double *prod, double *table, const Par
         const int cn = (c + Q < nchunks) ? c + Q : c;
         const int cnn = (cn + Q < nchunks) ? cn + Q : cn;
         const StreamRegs<HEAD> nxt = load_stream<HEAD>(col, val, (int64_t)cn * kChunk);
-        const SegRegs seg_n = load_segs(tab_n, flags + (int64_t)cn * kBlock, seg_row);
+        const unsigned fl_n = load_flags(flags + (int64_t)cn * kBlock);
         const int4 tab_nn = load_uniform(tabs + cnn);
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
-        chunk_segments(prod, seg, tab.y, tab.z > 0, partial, carry + c);
+        chunk_segments(prod, fl, tab.y, tab.z > 0, partial + tab.x, carry + c);
         __syncthreads();  // prod is reused by the next chunk
         cur = nxt;
-        seg = seg_n;
+        fl = fl_n;
         tab = tab_n;
         tab_n = tab_nn;
     }
@@ -1029,68 +1029,97 @@ static int launch_fixup(tron_dataset *ds, const CsrPlan &A, double *yout, const 
 }
 
 // ------------------------------------------------------------------ combine kernels (partitioned layout)
-// sum over the partitions in which row r has entries (bit x of mask), in partition order
+// The partial sums of a plan are stored one per segment (a segment = a row's entries in one partition), partition by
+// partition, rows ascending inside a partition -- the kernels above write them as dense 512-byte stores.  A row's
+// slots are found by rank: mask[r] says in which partitions row r has a segment; inside the 64 rows of a wavefront
+// the slot of (r, x) is group_base[x][r / 64] + (number of lower rows of the group with bit x set).
+struct PartialRef {
+    const double *partial;
+    const uint16_t *mask;
+    const GroupBase *group_base;   // one record per group of 64 rows
+};
+
 struct HotRef {
     const int32_t *slot_of_row;   // null: no hot rows
     const double *sums;
 };
 
-__device__ __forceinline__ double sum_parts(const double *__restrict__ partial, const uint16_t *__restrict__ mask, int64_t rows, int64_t r,
-                                            HotRef hot = HotRef{nullptr, nullptr})
+// Sum over the partitions of row r = 64 G + lane, in partition order.  Every lane of the wavefront calls it with
+// the same G; `valid` is false for rows past the end.  All loads are issued before the first is used.
+__device__ __forceinline__ double sum_parts(const PartialRef &P, int64_t G, int64_t r, bool valid, HotRef hot = HotRef{nullptr, nullptr})
 {
-    const unsigned m = mask[r];
+    const unsigned m = valid ? P.mask[r] : 0u;
+    const GroupBase gb = P.group_base[G];   // uniform: scalar loads
     double s = 0.0;
-    if (hot.slot_of_row) {
+    if (valid && hot.slot_of_row) {
         const int hs = hot.slot_of_row[r];
         if (hs >= 0) s = hot.sums[hs];
     }
+    double v[kMaxParts];
 #pragma unroll
-    for (int x = 0; x < kMaxParts; ++x)
-        if (m & (1u << x)) s += partial[(int64_t)x * rows + r];
+    for (int x = 0; x < kMaxParts; ++x) {
+        const bool bit = (m >> x) & 1u;
+        const uint64_t b = __ballot(bit);
+        const int rank = __builtin_amdgcn_mbcnt_hi((unsigned)(b >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)b, 0u));
+        v[x] = bit ? P.partial[(int64_t)gb.first[x] + rank] : 0.0;
+    }
+#pragma unroll
+    for (int x = 0; x < kMaxParts; ++x) s += v[x];
     return s;
 }
 
+// rows are dealt to wavefronts in groups of 64: group g0, g0 + (wavefronts in the grid), ...
+#define TRON_FOR_ROW_GROUPS(rows, G, r, valid)                                                                     \
+    for (int64_t G = (int64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave, r = G * kWave + (threadIdx.x & (kWave - 1)); \
+         G * kWave < (rows); G += (int64_t)gridDim.x * kWavesPerBlock, r += (int64_t)gridDim.x * kBlock)            \
+        if (const bool valid = r < (rows); true)
+
 // z = sum of partials; loss terms; partial slot 0 = sum loss
 template <int LOSS>
-__global__ __launch_bounds__(kBlock) void k_combine_loss(int64_t n, const double *__restrict__ partial, const uint16_t *__restrict__ mask,
-                                                         const double *__restrict__ y, double *__restrict__ zhat,
-                                                         double *__restrict__ D, double *__restrict__ red)
+__global__ __launch_bounds__(kBlock) void k_combine_loss(int64_t n, PartialRef P, const double *__restrict__ y,
+                                                         double *__restrict__ zhat, double *__restrict__ D, double *__restrict__ red)
 {
     __shared__ double lds[kWavesPerBlock];
     double acc = 0.0;
-    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (int64_t)gridDim.x * kBlock) {
-        const double z = sum_parts(partial, mask, n, i);
-        double a, zh, Di;
-        loss_terms_dev<LOSS>(z, y[i], a, zh, Di);
-        zhat[i] = zh;
-        D[i] = Di;
-        acc += a;
+    TRON_FOR_ROW_GROUPS(n, G, i, valid) {
+        const double z = sum_parts(P, G, i, valid);
+        if (valid) {
+            double a, zh, Di;
+            loss_terms_dev<LOSS>(z, y[i], a, zh, Di);
+            zhat[i] = zh;
+            D[i] = Di;
+            acc += a;
+        }
     }
     acc = block_sum(acc, lds);
     if (threadIdx.x == 0) red[blockIdx.x] = acc;
 }
 
 // out = scale .* sum of partials
-__global__ __launch_bounds__(kBlock) void k_combine_scale(int64_t rows, const double *__restrict__ partial, const uint16_t *__restrict__ mask,
-                                                          const double *__restrict__ scale, double *__restrict__ out)
+__global__ __launch_bounds__(kBlock) void k_combine_scale(int64_t rows, PartialRef P, const double *__restrict__ scale,
+                                                          double *__restrict__ out)
 {
-    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < rows; i += (int64_t)gridDim.x * kBlock)
-        out[i] = scale[i] * sum_parts(partial, mask, rows, i);
+    TRON_FOR_ROW_GROUPS(rows, G, i, valid) {
+        const double s = sum_parts(P, G, i, valid);
+        if (valid) out[i] = scale[i] * s;
+    }
 }
 
-// out = add + alpha * sum of partials; partial slot 0 = out . (SELF ? out : add)
+// out = add + alpha * sum of partials (add == null: add 1); partial slot 0 = out . (SELF ? out : add)
 template <bool SELF>
-__global__ __launch_bounds__(kBlock) void k_combine_axpy(int64_t rows, const double *__restrict__ partial, const uint16_t *__restrict__ mask,
-                                                         const double *__restrict__ add, double alpha,
+__global__ __launch_bounds__(kBlock) void k_combine_axpy(int64_t rows, PartialRef P, const double *__restrict__ add, double alpha,
                                                          double *__restrict__ out, double *__restrict__ red, HotRef hot)
 {
     __shared__ double lds[kWavesPerBlock];
     double acc = 0.0;
-    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < rows; i += (int64_t)gridDim.x * kBlock) {
-        const double a = add ? add[i] : 1.0;
-        const double o = fma(alpha, sum_parts(partial, mask, rows, i, hot), a);
-        out[i] = o;
-        acc += o * (SELF ? o : a);
+    TRON_FOR_ROW_GROUPS(rows, G, i, valid) {
+        const double s = sum_parts(P, G, i, valid, hot);
+        if (valid) {
+            const double a = add ? add[i] : 1.0;
+            const double o = fma(alpha, s, a);
+            out[i] = o;
+            acc += o * (SELF ? o : a);
+        }
     }
     acc = block_sum(acc, lds);
     if (threadIdx.x == 0) red[blockIdx.x] = acc;
@@ -1157,16 +1186,21 @@ static PartArgs head_args(const CsrPlan &A)
     return ha;
 }
 
+static PartialRef partial_ref(const tron_dataset *ds, const CsrPlan &A)
+{
+    return PartialRef{ds->row_partials, A.row_mask, A.group_base};
+}
+
 static PartPtrs part_ptrs(const tron_dataset *ds, const CsrPlan &A)
 {
-    return PartPtrs{A.col, A.val, A.chunk_tab, A.flags, A.seg_row, A.hot_x, ds->row_partials, A.carry};
+    return PartPtrs{A.col, A.val, A.chunk_tab, A.flags, A.hot_x, ds->row_partials, A.carry};
 }
 
 static PartPtrs head_ptrs(const tron_dataset *ds, const CsrPlan &A)
 {
     const int h = A.head;
-    return PartPtrs{A.col16, A.val + A.part_base[h], A.chunk_tab, A.flags, A.seg_row, A.hot_x ? A.hot_x + (size_t)h * kHotSlots : nullptr,
-                    ds->row_partials + (int64_t)h * A.rows, A.carry};
+    return PartPtrs{A.col16, A.val + A.part_base[h], A.chunk_tab, A.flags, A.hot_x ? A.hot_x + (size_t)h * kHotSlots : nullptr,
+                    ds->row_partials, A.carry};
 }
 
 // partial row sums of all partitions into ds->row_partials (with split rows fixed up)
@@ -1215,9 +1249,9 @@ int spmv_loss(tron_dataset *ds, const CsrPlan &A, int slot, int loss, const doub
     ProfScope ps(ds, SLOT_SPMV_COMBINE);
     const int g = vec_grid(A.rows);
     if (loss == TRON_LOSS_LR)
-        hipLaunchKernelGGL(k_combine_loss<TRON_LOSS_LR>, dim3(g), dim3(kBlock), 0, ds->stream, A.rows, ds->row_partials, A.row_mask, ds->y, zhat, D, ds->partials);
+        hipLaunchKernelGGL(k_combine_loss<TRON_LOSS_LR>, dim3(g), dim3(kBlock), 0, ds->stream, A.rows, partial_ref(ds, A), ds->y, zhat, D, ds->partials);
     else
-        hipLaunchKernelGGL(k_combine_loss<TRON_LOSS_L2SVM>, dim3(g), dim3(kBlock), 0, ds->stream, A.rows, ds->row_partials, A.row_mask, ds->y, zhat, D, ds->partials);
+        hipLaunchKernelGGL(k_combine_loss<TRON_LOSS_L2SVM>, dim3(g), dim3(kBlock), 0, ds->stream, A.rows, partial_ref(ds, A), ds->y, zhat, D, ds->partials);
     TRON_HIP(hipGetLastError());
     return g;
 }
@@ -1227,7 +1261,7 @@ int spmv_scale(tron_dataset *ds, const CsrPlan &A, int slot, const double *x, co
     if (A.P == 1) return launch_plain<EPI_SCALE>(ds, A, slot, x, out, scale, 0.0);
     TRON_TRY(launch_partials(ds, A, slot, x));
     ProfScope ps(ds, SLOT_SPMV_COMBINE);
-    hipLaunchKernelGGL(k_combine_scale, dim3(vec_grid(A.rows)), dim3(kBlock), 0, ds->stream, A.rows, ds->row_partials, A.row_mask, scale, out);
+    hipLaunchKernelGGL(k_combine_scale, dim3(vec_grid(A.rows)), dim3(kBlock), 0, ds->stream, A.rows, partial_ref(ds, A), scale, out);
     TRON_HIP(hipGetLastError());
     return TRON_OK;
 }
@@ -1251,9 +1285,9 @@ int spmv_axpy(tron_dataset *ds, const CsrPlan &A, int slot, const double *x, con
     ProfScope ps(ds, SLOT_SPMV_COMBINE);
     const int g = vec_grid(A.rows);
     if (dot_self)
-        hipLaunchKernelGGL(k_combine_axpy<true>, dim3(g), dim3(kBlock), 0, ds->stream, A.rows, ds->row_partials, A.row_mask, add, alpha, out, ds->partials, hot);
+        hipLaunchKernelGGL(k_combine_axpy<true>, dim3(g), dim3(kBlock), 0, ds->stream, A.rows, partial_ref(ds, A), add, alpha, out, ds->partials, hot);
     else
-        hipLaunchKernelGGL(k_combine_axpy<false>, dim3(g), dim3(kBlock), 0, ds->stream, A.rows, ds->row_partials, A.row_mask, add, alpha, out, ds->partials, hot);
+        hipLaunchKernelGGL(k_combine_axpy<false>, dim3(g), dim3(kBlock), 0, ds->stream, A.rows, partial_ref(ds, A), add, alpha, out, ds->partials, hot);
     TRON_HIP(hipGetLastError());
     return g;
 }
