@@ -96,10 +96,10 @@ struct Profiler {
 // contiguous ranges with equal nonzero counts and the nonzeros are stored range-major: partition x
 // holds, row by row, the entries whose column lies in range x.  Workgroup b works on partition b % 8,
 // so -- with workgroups dealt round-robin to the 8 XCDs -- each XCD's L2 only ever gathers from its own
-// slice of the vector.  Inside a partition only the non-empty rows ("segments") are described: their
-// row ids, and per chunk a 16-bit end offset per segment.  Partitions produce partial row sums
-// (partial[x*rows + r], written only where row r has entries in range x -- see row_mask); a combine
-// kernel adds them in a fixed order and applies the epilogue.
+// slice of the vector.  Inside a partition only the non-empty rows ("segments") are described: per
+// chunk a table entry and one flag bit per entry (last entry of its segment).  Every segment owns one
+// partial sum, stored in segment order; row_mask and group_base let the combine kernels find the
+// partial sums of a row and add them in a fixed order before applying the epilogue.
 constexpr int kColParts = 8;            // column ranges, one per XCD
 constexpr int kMaxParts = kColParts + 1;   // + the head partition (see CsrPlan::head)
 constexpr int kHotSlots = 4096;   // LDS table entries per workgroup (32 KiB)
@@ -150,8 +150,8 @@ struct CsrPlan {
     double *carry = nullptr;             // device, nblocks: sum of the part of a row entering chunk c from before
     int nfix = 0;                        // number of (partition, split row) pairs
     int fix_max_cnt = 0;                 // largest fix_cnt
-    int32_t *fix_row = nullptr;          // device, nfix: the split row
-    int32_t *fix_part = nullptr;         // device, nfix: its partition
+    int32_t *fix_row = nullptr;          // device, nfix: the split row (P > 1: its segment's slot in the partial sums)
+    int32_t *fix_part = nullptr;         // device, nfix: 0 (kept for the address arithmetic shared by both layouts)
     int32_t *fix_b0 = nullptr;           // device, nfix: first chunk id holding a continuation of it
     int32_t *fix_cnt = nullptr;          // device, nfix: number of consecutive chunks that do
     // ---- P == 1
@@ -164,7 +164,7 @@ struct CsrPlan {
     int part_chunk0[kMaxParts] = {0};    // first chunk id of partition x (= part_base / kChunk)
     int part_nchunks[kMaxParts] = {0};
     int part_nhot[kMaxParts] = {0};      // LDS-resident columns of partition x
-    int max_chunks = 0;                  // max over partitions
+    int max_chunks = 0;                  // max over the column ranges
     int range_slots = 0;                 // LDS table entries used by the column ranges (<= kHotSlots)
     int32_t *hot_ids = nullptr;          // device, (P+1)*kHotSlots column ids of the LDS tables (null: no LDS table)
     double *hot_x = nullptr;             // device, (P+1)*kHotSlots: the gather vector at those columns, refreshed every call

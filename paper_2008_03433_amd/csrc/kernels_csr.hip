@@ -1,20 +1,26 @@
-// CSR sparse matrix-vector products for both orientations (X and the explicit X^T copy):
+// Sparse matrix-vector products for both orientations (X and the explicit X^T copy):
 //   z = X w,  a1 = D .* (X v)               (Table 1 / Appendix D of the paper: a0 = X v, a1 = D a0)
 //   g = w + C X^T zhat,  Hv = v + C X^T a1   (a2 = C X^T a1)
 //
 // Work is split by nonzeros, not by rows, because row lengths are heavily skewed (Zipf-distributed
 // features give the transposed copy rows of length ~n next to millions of length 0/1): a workgroup
-// streams one chunk of kChunk nonzeros with coalesced 16-byte non-temporal loads, multiplies them by
-// the gathered vector entries and parks the products in LDS; the rows that start inside the chunk are
-// then summed from LDS by lane groups sized to the number of such rows.  A row that runs past the end
-// of its chunk receives the rest from the `carry` of the following chunks in a small fix-up kernel, in
-// a fixed order -- no atomics anywhere, so results are bit-reproducible.
+// streams one chunk of kChunk nonzeros with 16-byte non-temporal loads that cover whole cache lines,
+// multiplies them by the gathered vector entries and parks the products in LDS; the sums of the row
+// pieces ("segments") of the chunk come out of a segmented scan (see chunk_runs).  A row that runs past
+// the end of its chunk receives the rest from the `carry` of the following chunks in a small fix-up
+// kernel, in a fixed order -- no atomics anywhere, so results are bit-reproducible.
 //
-// The gathers decide the speed: every L2 miss pulls a 128-byte line for 8 useful bytes.  For vectors
-// that do not fit one XCD's L2 the matrix is therefore stored in P = 8 column partitions (see CsrPlan)
-// and workgroup b handles partition b % 8, so that each XCD gathers from its own slice only; the
-// partial row sums of the partitions are added by a combine kernel that also applies the epilogue
-// (loss terms, D scaling, v + C * sum) and the first stage of the scalar reductions.
+// The gathers decide the speed.  A gather that misses the vector L1 costs an L2 request of its own, and
+// a CU keeps only ~100 of them in flight; one that misses L2 as well pulls a 64-byte sector for 8 useful
+// bytes.  Large matrices are therefore regrouped by where the gathered element can be kept:
+//   - forward orientation: a head partition (the most frequent columns of the whole matrix, served from
+//     one LDS table, 16-bit slots, whole rows) and 8 column ranges, workgroup b on range b % 8 so that
+//     each XCD's L2 gathers from its own slice of the vector; each range has an LDS table of its own;
+//   - transposed orientation: hot-row tiles (see HotTiles: LDS accumulators, gathers that stay in L1)
+//     and 8 column ranges for the rest.
+// Partitions write one partial sum per segment; combine kernels add a row's partial sums in a fixed
+// order and apply the epilogue (loss terms, D scaling, v + C * sum) and the first stage of the scalar
+// reductions.
 #include <algorithm>
 #include <cstring>
 
