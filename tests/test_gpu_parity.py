@@ -200,9 +200,21 @@ def test_solve_url_shape_scaled(force_partitions):
 
 def test_csr_url_shape_partitioned(rng):
     # large enough that the automatic choice partitions both orientations
+    import paper_2008_03433_amd as tron
     p = dg.config3(scale=0.1)
     assert p.nnz > (1 << 22) and p.n * 8 > (3 << 19)
     check_calls(p, LOSS_LR, 1.0, rng, w_scale=1.0, n_hv=1)
+    # ... and that every building block of the regrouped layout took part
+    ds = tron.Dataset.from_problem(p)
+    try:
+        st = {k: tron.tron_dataset_stat(ds.handle, k) for k in ("fwd_parts", "bwd_parts", "fwd_csr_nnz", "fwd_head_nnz",
+                                                                 "fwd_lds_columns", "bwd_csr_nnz", "bwd_tile_nnz", "bwd_tile_rows")}
+        assert st["fwd_parts"] == 8 and st["bwd_parts"] == 8
+        assert st["fwd_csr_nnz"] == p.nnz and 0.25 * p.nnz <= st["fwd_head_nnz"] < p.nnz
+        assert st["fwd_lds_columns"] > 4096                      # head table + range tables
+        assert st["bwd_csr_nnz"] + st["bwd_tile_nnz"] == p.nnz and st["bwd_tile_rows"] > 0 and st["bwd_csr_nnz"] > 0
+    finally:
+        ds.close()
 
 
 def test_csr_tiny_and_empty(rng):
