@@ -126,6 +126,19 @@ class Oracle:
             return cls(n=p.n, d=p.d, y=p.y, X=p.X, plain_fp64=plain_fp64)
         return cls(n=p.n, d=p.d, y=p.y, rowptr=p.rowptr, col=p.col, val=p.val, plain_fp64=plain_fp64)
 
+    def restrict(self, rows) -> "Oracle":
+        """The problem over the listed instances only (one training fold of the cross-validation of Section 2.1):
+        same features, rows X[rows] and labels y[rows], in the order given."""
+        rows = np.asarray(rows, dtype=np.int64)
+        if self.X is not None:
+            return Oracle(n=len(rows), d=self.d, y=self.y[rows], X=self.X[rows], plain_fp64=self._plain)
+        lens = self.rowptr[rows + 1] - self.rowptr[rows]
+        rowptr = np.zeros(len(rows) + 1, dtype=np.int64)
+        np.cumsum(lens, out=rowptr[1:])
+        take = np.concatenate([np.arange(self.rowptr[i], self.rowptr[i + 1]) for i in rows]) if len(rows) else np.zeros(0, np.int64)
+        return Oracle(n=len(rows), d=self.d, y=self.y[rows], rowptr=rowptr, col=self.col[take], val=self.val[take],
+                      plain_fp64=self._plain)
+
     def fun(self, loss: int, C: float, w):
         """f(w) and the per-instance z, zhat, D at w."""
         w = _f64(w)

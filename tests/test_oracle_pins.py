@@ -569,3 +569,78 @@ def test_rounding_alone_moves_the_eps_0p01_iterate_on_zipf_data():
     assert abs(ra.f - rb.f) <= 0.5 * (1e-2 * ra.gnorm0) ** 2
     ta, tb = a.tron(LOSS_LR, 1.0, 1e-6), b.tron(LOSS_LR, 1.0, 1e-6)
     assert abs(ta.f - tb.f) <= 1e-8 * abs(ta.f)
+
+
+# ----------------------------------------------------------------------------
+# Problems over a subset of the instances (the training folds of cross-validation, Section 2.1): the oracle of a
+# fold is the oracle over the rows of the fold.  Pinned through the full-data oracle with masked per-instance terms.
+# ----------------------------------------------------------------------------
+def _folds(rng, n, k=3):
+    return rng.integers(0, k, size=n)
+
+
+@pytest.mark.parametrize("loss", [LOSS_LR, LOSS_L2SVM])
+@pytest.mark.parametrize("layout", ["dense", "csr"])
+def test_fold_objective_and_gradient_are_masked_sums(rng, loss, layout):
+    X, y = _dense_problem(rng, 90, 7, density=0.6 if layout == "csr" else 1.0)
+    if layout == "csr":
+        rowptr, col, val = _to_csr(X)
+        full = Oracle(n=90, d=7, y=y, rowptr=rowptr, col=col, val=val)
+    else:
+        full = Oracle(n=90, d=7, y=y, X=X)
+    fold = _folds(rng, 90)
+    w = 0.4 * rng.standard_normal(7)
+    C = 0.7
+    f_full, z, zhat, D = full.fun(loss, C, w)
+    t = y * z
+    per_row = np.logaddexp(0.0, -t) if loss == LOSS_LR else np.maximum(0.0, 1.0 - t) ** 2
+    total = 0.0
+    for k in range(3):
+        rows = np.nonzero(fold != k)[0]          # train on the other two folds
+        sub = full.restrict(rows)
+        f_k, z_k, zhat_k, D_k = sub.fun(loss, C, w)
+        assert np.array_equal(z_k, z[rows]) and np.array_equal(zhat_k, zhat[rows]) and np.array_equal(D_k, D[rows])
+        assert abs(f_k - (0.5 * w @ w + C * per_row[rows].sum())) <= 1e-13 * abs(f_k)
+        g_k = sub.grad(C, w, zhat_k)
+        masked = np.where(fold != k, zhat, 0.0)
+        np.testing.assert_allclose(g_k, full.grad(C, w, masked), rtol=0, atol=1e-13 * np.abs(g_k).max())
+        np.testing.assert_allclose(g_k, w + C * X[rows].T @ zhat[rows], rtol=0, atol=1e-12 * np.abs(g_k).max())
+        total += (f_k - 0.5 * w @ w) / C
+    # every instance is left out exactly once: the three training sums count each loss twice
+    assert abs(total - 2.0 * (f_full - 0.5 * w @ w) / C) <= 1e-12 * abs(total)
+
+
+@pytest.mark.parametrize("loss", [LOSS_LR, LOSS_L2SVM])
+def test_fold_hessian_product_is_the_full_product_with_masked_D(rng, loss):
+    X, y = _dense_problem(rng, 120, 9)
+    full = Oracle(n=120, d=9, y=y, X=X)
+    fold = _folds(rng, 120)
+    w = 0.3 * rng.standard_normal(9)
+    v = rng.standard_normal(9)
+    C = 1.3
+    _, _, _, D = full.fun(loss, C, w)
+    for k in range(3):
+        rows = np.nonzero(fold != k)[0]
+        sub = full.restrict(rows)
+        _, _, _, D_k = sub.fun(loss, C, w)
+        Hv_k = sub.hv(C, D_k, v)
+        Hv_masked = full.hv(C, np.where(fold != k, D, 0.0), v)
+        np.testing.assert_allclose(Hv_k, Hv_masked, rtol=0, atol=1e-13 * np.abs(Hv_k).max())
+        H = np.eye(9) + C * X[rows].T @ (D[rows, None] * X[rows])
+        np.testing.assert_allclose(Hv_k, H @ v, rtol=0, atol=1e-12 * np.abs(Hv_k).max())
+
+
+@pytest.mark.parametrize("loss", [LOSS_LR, LOSS_L2SVM])
+def test_fold_solutions_are_stationary_for_the_masked_full_problem(rng, loss):
+    X, y = _dense_problem(rng, 150, 6)
+    full = Oracle(n=150, d=6, y=y, X=X)
+    fold = _folds(rng, 150)
+    for k, C in zip(range(3), (0.05, 0.5, 2.0)):
+        rows = np.nonzero(fold != k)[0]
+        res = full.restrict(rows).tron(loss, C, 1e-9)
+        assert res.converged
+        _, _, zhat, _ = full.fun(loss, C, res.w)
+        g = full.grad(C, res.w, np.where(fold != k, zhat, 0.0))
+        assert np.linalg.norm(g) <= 1e-9 * res.gnorm0 * (1 + 1e-6)
+        w_ref, _ = _newton_minimise(X[rows], y[rows], loss, C)
+        np.testing.assert_allclose(res.w, w_ref, rtol=0, atol=1e-7 * max(1.0, np.abs(w_ref).max()))
