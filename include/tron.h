@@ -188,6 +188,61 @@ typedef struct {
 TRON_API int tron_solve(tron_dataset *ds, const tron_params *params, double *w_dev, tron_result *res_host);
 
 /* ------------------------------------------------------------------------------------------
+ * Several problems over one resident matrix.
+ * Section 2.1: Percolator trains its SVMs under three-fold cross-validation with a nested
+ * cross-validation inside every fold, i.e. many problems of Section 3 that differ only in the
+ * subset of instances they train on and in C.  A batch runs up to TRON_BATCH_MAX such problems in
+ * lock-step: one pass over X serves every problem's pending product -- X^T(D(Xv)) for those inside
+ * CG, the function/gradient pass for those at a trial point -- so X is read once per round, not once
+ * per problem.  Problem k is exactly the problem of Section 3 over the instances {i : bit k of
+ * member[i] is set}: the rows outside it contribute nothing to f, g or Hv.
+ * Dense handles with d <= TRON_BATCH_MAX_D only.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct tron_batch tron_batch; /* opaque: membership bits, per-problem D, solver state, work space */
+
+#define TRON_BATCH_MAX 8
+#define TRON_BATCH_MAX_D 32
+
+/*
+ * K in [1, TRON_BATCH_MAX].  member: n words, host or device per mem; bit k (k < K) of member[i] says
+ * whether instance i belongs to problem k; higher bits must be zero.  The words are copied.  The batch
+ * uses the dataset's matrix, labels, stream and profiler: ds must stay alive, and must not be used by
+ * another thread, while the batch exists.  A problem with no instance is allowed (f = 1/2 w.w).
+ */
+TRON_API int tron_batch_create(tron_dataset *ds, int K, const uint32_t *member, int mem, tron_batch **out);
+
+/* Frees the batch (not the dataset).  NULL is ignored. */
+TRON_API void tron_batch_destroy(tron_batch *b);
+
+/*
+ * tron_fun_grad for every problem in one pass.  C_host: K values > 0 (host).  W_dev: K*d doubles,
+ * problem k's w at W_dev + k*d (device).  f_host: K doubles (host).  G_dev: K*d doubles (device) or
+ * NULL.  D of every problem at its w is cached in the batch for tron_batch_hv.  Synchronises.
+ */
+TRON_API int tron_batch_fun_grad(tron_batch *b, int loss, const double *C_host, const double *W_dev, double *f_host,
+                                 double *G_dev);
+
+/*
+ * tron_hv for every problem in one pass, with the D cached by the last tron_batch_fun_grad or
+ * tron_batch_solve.  V_dev, HV_dev: K*d doubles each (device), must not alias.  vHv_host: K doubles
+ * (host) or NULL.  Synchronises.  TRON_ESTATE if no D is cached.
+ */
+TRON_API int tron_batch_hv(tron_batch *b, const double *C_host, const double *V_dev, double *HV_dev, double *vHv_host);
+
+/*
+ * tron_solve for every problem, in lock-step rounds of one pass over X each.  params: loss, eps,
+ * max_outer, max_cg, cg_xi apply to every problem; params->C is ignored (C_host[k] is problem k's C);
+ * params->precond_blend must be 0.  W_dev: K*d doubles, in: starting points, out: final iterates.
+ * res_host: K results, each with its own trace / trace_cap set before the call.  Every problem follows
+ * the rules stated for tron_solve; the whole trust-region and CG logic runs on the device (the vectors
+ * have d <= 32 entries), the host only learns which problems are still running.
+ * Returns TRON_OK when every problem converged, TRON_EMAXITER when some problem stopped at its
+ * iteration limit or stalled (status_host[k], if not NULL, receives each problem's own status).
+ */
+TRON_API int tron_batch_solve(tron_batch *b, const tron_params *params, const double *C_host, double *W_dev,
+                              tron_result *res_host, int *status_host);
+
+/* ------------------------------------------------------------------------------------------
  * Diagnostics.
  * ------------------------------------------------------------------------------------------ */
 

@@ -53,6 +53,11 @@ _SIGNATURES = {
     "tron_hv": (_int, [_vp, _dbl, _vp, _vp, ctypes.POINTER(_dbl)]),
     "tron_solve": (_int, [_vp, ctypes.POINTER(_Params), _vp, ctypes.POINTER(_Result)]),
     "tron_hess_diag": (_int, [_vp, _dbl, _vp]),
+    "tron_batch_create": (_int, [_vp, _int, _vp, _int, ctypes.POINTER(_vp)]),
+    "tron_batch_destroy": (None, [_vp]),
+    "tron_batch_fun_grad": (_int, [_vp, _int, ctypes.POINTER(_dbl), _vp, ctypes.POINTER(_dbl), _vp]),
+    "tron_batch_hv": (_int, [_vp, ctypes.POINTER(_dbl), _vp, _vp, ctypes.POINTER(_dbl)]),
+    "tron_batch_solve": (_int, [_vp, ctypes.POINTER(_Params), ctypes.POINTER(_dbl), _vp, ctypes.POINTER(_Result), ctypes.POINTER(_int)]),
     "tron_last_error": (ctypes.c_char_p, []),
     "tron_profile_enable": (_int, [_vp, _int]),
     "tron_profile_read": (_int, [_vp, _int, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(_dbl), ctypes.POINTER(_i64), ctypes.POINTER(_int)]),
@@ -214,6 +219,61 @@ def tron_solve(ds, loss, C, eps, w, max_outer=1000, max_cg=1000, cg_xi=0.1, trac
                        res.n_hv, bool(res.converged), rc, recs)
 
 
+BATCH_MAX = 8
+BATCH_MAX_D = 32
+
+
+def tron_batch_create(ds, K, member) -> int:
+    """member: n uint32 words (numpy or torch CUDA tensor of dtype int32/uint32); bit k = instance belongs to problem k."""
+    mem = MEM_DEVICE if _is_device(member) else MEM_HOST
+    out = _vp()
+    _check(load_library().tron_batch_create(ds, K, _ptr(member), mem, ctypes.byref(out)))
+    return out.value
+
+
+def tron_batch_destroy(b) -> None:
+    load_library().tron_batch_destroy(b)
+
+
+def _dbl_array(values):
+    return (_dbl * len(values))(*[float(v) for v in values])
+
+
+def tron_batch_fun_grad(b, loss, C, W, G=None) -> List[float]:
+    """C: K values; W, G: CUDA tensors of K*d doubles.  Returns the K function values."""
+    K = len(C)
+    f = (_dbl * K)()
+    _check(load_library().tron_batch_fun_grad(b, loss, _dbl_array(C), _ptr(W), f, _ptr(G)))
+    return list(f)
+
+
+def tron_batch_hv(b, C, V, HV, want_vHv=True) -> Optional[List[float]]:
+    K = len(C)
+    s = (_dbl * K)() if want_vHv else None
+    _check(load_library().tron_batch_hv(b, _dbl_array(C), _ptr(V), _ptr(HV), s))
+    return list(s) if want_vHv else None
+
+
+def tron_batch_solve(b, loss, C, eps, W, max_outer=1000, max_cg=1000, cg_xi=0.1, trace_cap=1024) -> List[SolveResult]:
+    """Solves the K problems in place on the CUDA tensor W (K*d doubles); one SolveResult per problem."""
+    K = len(C)
+    params = _Params(loss, 0.0, eps, max_outer, max_cg, cg_xi, 0.0)
+    traces = [(TraceRec * max(trace_cap, 1))() for _ in range(K)]
+    res = (_Result * K)()
+    for k in range(K):
+        res[k].trace_cap = trace_cap
+        res[k].trace = ctypes.cast(traces[k], ctypes.POINTER(TraceRec)) if trace_cap > 0 else None
+    status = (_int * K)()
+    _check(load_library().tron_batch_solve(b, ctypes.byref(params), _dbl_array(C), _ptr(W), res, status))
+    out = []
+    for k in range(K):
+        r = res[k]
+        recs = [{f: getattr(traces[k][i], f) for f, _ in TraceRec._fields_} for i in range(r.trace_len)]
+        out.append(SolveResult(r.f, r.gnorm, r.gnorm0, r.outer_iters, r.cg_iters_total, r.n_fun, r.n_grad, r.n_hv,
+                               bool(r.converged), status[k], recs))
+    return out
+
+
 def tron_profile_enable(ds, on: bool) -> None:
     _check(load_library().tron_profile_enable(ds, 1 if on else 0))
 
@@ -282,6 +342,35 @@ class Dataset:
     def close(self):
         if self.handle:
             tron_dataset_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Batch:
+    """Up to BATCH_MAX problems over the rows of one dense Dataset (which must outlive the batch)."""
+
+    def __init__(self, dataset: Dataset, K: int, member):
+        self.dataset = dataset
+        self.K = K
+        self.handle = tron_batch_create(dataset.handle, K, member)
+
+    def fun_grad(self, loss, C, W, G=None):
+        return tron_batch_fun_grad(self.handle, loss, C, W, G)
+
+    def hv(self, C, V, HV, want_vHv=True):
+        return tron_batch_hv(self.handle, C, V, HV, want_vHv)
+
+    def solve(self, loss, C, eps, W, **kw):
+        return tron_batch_solve(self.handle, loss, C, eps, W, **kw)
+
+    def close(self):
+        if self.handle:
+            tron_batch_destroy(self.handle)
             self.handle = None
 
     def __del__(self):

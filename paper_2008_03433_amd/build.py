@@ -10,8 +10,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtron_hip.so")
-SOURCES = ["api.hip", "solver.hip", "kernels_vec.hip", "kernels_csr.hip", "kernels_dense.hip"]
-HEADERS = ["common.h", "device_util.h", os.path.join("..", "..", "include", "tron.h")]
+SOURCES = ["api.hip", "solver.hip", "kernels_vec.hip", "kernels_csr.hip", "kernels_dense.hip", "batch.hip"]
+HEADERS = ["common.h", "device_util.h", "dense_tile.h", os.path.join("..", "..", "include", "tron.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

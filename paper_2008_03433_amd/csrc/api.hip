@@ -33,7 +33,7 @@ int hip_fail(hipError_t e, const char *what, const char *file, int line)
 // ------------------------------------------------------------------ profiler
 const char *const kSlotNames[SLOT_COUNT] = {
     "spmv_fwd", "spmv_bwd", "spmv_head", "spmv_tiles", "spmv_tile_reduce", "spmv_gather", "spmv_fixup", "spmv_combine", "loss_terms",
-    "dense_fun_grad", "dense_hv", "dense_finalize", "dot", "reduce_final", "cg_vec"};
+    "dense_fun_grad", "dense_hv", "dense_finalize", "dot", "reduce_final", "cg_vec", "batch_pass", "batch_advance"};
 
 int Profiler::begin(int slot, hipStream_t st)
 {
@@ -482,6 +482,10 @@ int tron_tuning_set(const char *name, int64_t value)
     }
     if (name && strcmp(name, "csr_blocks_per_part") == 0 && value >= 1 && value <= 4096) {
         g_tuning.csr_blocks_per_part = value;
+        return TRON_OK;
+    }
+    if (name && strcmp(name, "batch_grid") == 0 && value >= 0 && value <= 4096) {
+        g_tuning.batch_grid = value;
         return TRON_OK;
     }
     set_error("tron_tuning_set: unknown knob or value out of range");

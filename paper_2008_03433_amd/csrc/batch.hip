@@ -1,0 +1,755 @@
+// Several problems of Section 3 of the paper over one resident dense matrix: the cross-validation setting of
+// Section 2.1 (three folds, nested cross-validation inside each), where the problems differ only in the instances
+// they train on and in C.  The problems advance in lock-step rounds.  A round is
+//   1. one pass over X (k_batch_pass) that serves every problem's pending request -- X^T (D (X v)) for a problem inside
+//      its CG iteration, or z = X w / loss / D / X^T zhat for one at a trial point (Table 1) -- so that an element of X
+//      read from HBM is used by all of them;
+//   2. one small kernel (k_batch_advance) that adds up the pass's per-workgroup partial sums and then runs, for every
+//      problem, the step of Algorithm 1 / of the truncated CG iteration that was waiting for the product, and posts
+//      the problem's next request.
+// The trust-region logic runs on the device: the vectors have d <= 32 entries, one lane each.  The host only reads,
+// every few rounds, which problems are still running.
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "dense_tile.h"
+
+namespace tron {
+namespace {
+
+constexpr int kBatchMax = TRON_BATCH_MAX;
+constexpr int kVecPad = TRON_BATCH_MAX_D;   // doubles per stored vector
+static_assert(kVecPad <= kWave, "one lane per vector entry");
+
+enum { MODE_IDLE = 0, MODE_HV = 1, MODE_FG = 2 };
+enum { PH_DONE = 0, PH_ONESHOT, PH_REF, PH_START, PH_CG, PH_TRIAL };
+enum { BEGIN_SOLVE = 0, BEGIN_FG, BEGIN_HV };
+
+// request of the next pass: written by the begin / advance kernels, read by the pass
+struct BatchCtl {
+    int32_t mode[kBatchMax];    // MODE_*
+    int32_t dslot[kBatchMax];   // which of the problem's two D buffers the pass reads (MODE_HV) or writes (MODE_FG)
+    double vec[kBatchMax][kVecPad];   // v (MODE_HV) or w (MODE_FG), zero past d
+};
+
+struct ProbScalars {
+    int32_t phase, status, converged, outer, cg_total, n_fun, n_grad, n_hv, cg_it, onb, dcur, trace_len;
+    double C, f, gnorm, gnorm0, delta, rr, pred, snorm, out_scal;
+};
+
+// solver state of one problem (device memory)
+struct ProbState {
+    ProbScalars sc;
+    double w[kVecPad], wnew[kVecPad], g[kVecPad], s[kVecPad], r[kVecPad], p[kVecPad], out[kVecPad];
+};
+
+struct SolveParams {
+    int loss, max_outer, max_cg, trace_cap;
+    double eps, xi;
+};
+
+struct BatchC { double v[kBatchMax]; };
+
+// ------------------------------------------------------------------ the pass over X
+// Work layout as in the single-problem kernels: a wave tile is 64 consecutive rows, a wavefront walks a contiguous
+// range of tiles.  Per tile and problem one 64-bit word says which rows concern the problem: its members
+// (function/gradient pass, logistic Hessian) or its active set I (L2-SVM Hessian: D_ii = 2 on I).  Rows that concern no
+// problem are not read.  The words of the next tile are fetched (scalar loads) while the current one is processed.
+// New active-set words are kept one per lane and stored 64 tiles at a time.
+//   member: [k][tile]     Dbits: [k][slot][tile]     Dval (logistic D): [k][slot][row]
+//   partials: [k][column 0..d-1, then the loss sum][workgroup]
+// Dbits_in and Dbits_out are the same array: a problem's plane is either read (MODE_HV) or written (MODE_FG) by a pass.
+template <int E, int L, int U, bool VEC, int KT>
+__global__ __launch_bounds__(kBlock) void k_batch_pass(int64_t n, int64_t d, const double *__restrict__ X,
+                                                       const int8_t *__restrict__ y, int loss,
+                                                       const BatchCtl *__restrict__ ctl, const uint64_t *__restrict__ member,
+                                                       const uint64_t *__restrict__ Dbits_in, uint64_t *Dbits_out,
+                                                       double *Dval, int64_t ntiles, double *__restrict__ partials)
+{
+    using T = Tile<E, L, U, VEC>;
+    static_assert(T::RT == kWave, "one 64-bit word per tile");
+    __shared__ double lvec[KT][E * L];
+    __shared__ double lds[kWavesPerBlock * E * L];
+    __shared__ double lds_red[kWavesPerBlock];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int q = lane % L;
+    int mode[KT], dslot[KT];
+    bool any = false, any_fg = false;
+#pragma unroll
+    for (int k = 0; k < KT; ++k) {
+        mode[k] = ctl->mode[k];
+        dslot[k] = ctl->dslot[k];
+        any |= mode[k] != MODE_IDLE;
+        any_fg |= mode[k] == MODE_FG;
+    }
+    if (!any) return;
+    for (int i = threadIdx.x; i < KT * E * L; i += kBlock) {
+        const int k = i / (E * L), c = i % (E * L);
+        lvec[k][c] = (c < d) ? ctl->vec[k][c] : 0.0;
+    }
+    __syncthreads();
+    const bool svm = loss == TRON_LOSS_L2SVM;
+    // plane of the words that say which rows concern problem k
+    const uint64_t *words[KT];
+#pragma unroll
+    for (int k = 0; k < KT; ++k) {
+        if (mode[k] == MODE_HV && svm) words[k] = Dbits_in + ((int64_t)k * 2 + dslot[k]) * ntiles;
+        else words[k] = member + (int64_t)k * ntiles;
+    }
+    double acc[KT][E], loss_acc[KT];
+    uint64_t held[KT];
+#pragma unroll
+    for (int k = 0; k < KT; ++k) {
+        loss_acc[k] = 0.0;
+        held[k] = 0;
+#pragma unroll
+        for (int e = 0; e < E; ++e) acc[k][e] = 0.0;
+    }
+    const int64_t nwaves = (int64_t)gridDim.x * kWavesPerBlock;
+    const int64_t wave_id = (int64_t)blockIdx.x * kWavesPerBlock + wv;
+    const int64_t per_wave = (ntiles + nwaves - 1) / nwaves;
+    const int64_t first = wave_id * per_wave;
+    const int64_t last = (first + per_wave < ntiles) ? first + per_wave : ntiles;
+    uint64_t wnext[KT];
+#pragma unroll
+    for (int k = 0; k < KT; ++k) wnext[k] = (mode[k] != MODE_IDLE && first < last) ? words[k][first] : 0;
+    int it = 0;
+    for (int64_t tile = first; tile < last; ++tile, ++it) {
+        const int slotl = it & (kWave - 1);
+        const int64_t row0 = tile * kWave;
+        uint64_t wk[KT], rows = 0;
+#pragma unroll
+        for (int k = 0; k < KT; ++k) {
+            wk[k] = wnext[k];
+            rows |= wk[k];
+            wnext[k] = (mode[k] != MODE_IDLE && tile + 1 < last) ? words[k][tile + 1] : 0;
+        }
+        if (rows != 0) {
+            double x[U][E];
+            T::load(X, n, d, row0, lane, x, rows);
+            const double yrow = (any_fg && row0 + lane < n) ? (double)y[row0 + lane] : 1.0;
+#pragma unroll
+            for (int k = 0; k < KT; ++k) {
+                if (mode[k] == MODE_IDLE || wk[k] == 0) continue;   // uniform
+                double vk[E], t[U], c[U];
+#pragma unroll
+                for (int e = 0; e < E; ++e) vk[e] = lvec[k][q * E + e];
+                T::row_dots(x, vk, t);
+                const double z = T::to_row_owner(t, lane);
+                const bool mine = (wk[k] >> lane) & 1u;
+                double coef;
+                if (mode[k] == MODE_HV) {
+                    double Dr = 0.0;
+                    if (mine) Dr = svm ? 2.0 : Dval[((int64_t)k * 2 + dslot[k]) * n + row0 + lane];
+                    coef = Dr * z;   // a1 = D (X v)
+                } else {
+                    double alpha, zhat, Di;
+                    if (svm) loss_terms_dev<TRON_LOSS_L2SVM>(z, yrow, alpha, zhat, Di);
+                    else loss_terms_dev<TRON_LOSS_LR>(z, yrow, alpha, zhat, Di);
+                    if (!mine) { alpha = 0.0; zhat = 0.0; Di = 0.0; }
+                    loss_acc[k] += alpha;
+                    if (svm) {
+                        const uint64_t nb = __ballot(Di != 0.0);
+                        if (lane == slotl) held[k] = nb;
+                    } else if (mine) {
+                        Dval[((int64_t)k * 2 + dslot[k]) * n + row0 + lane] = Di;
+                    }
+                    coef = zhat;
+                }
+                T::from_row_owner(coef, lane, c);
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+#pragma unroll
+                    for (int e = 0; e < E; ++e) acc[k][e] = fma(c[u], x[u][e], acc[k][e]);
+                }
+            }
+        }
+        if (svm && any_fg && (slotl == kWave - 1 || tile + 1 == last)) {
+            // lane i holds the words of tile (tile - slotl + i): consecutive 8-byte words per problem
+#pragma unroll
+            for (int k = 0; k < KT; ++k) {
+                if (mode[k] == MODE_FG && lane <= slotl)
+                    Dbits_out[((int64_t)k * 2 + dslot[k]) * ntiles + (tile - slotl) + lane] = held[k];
+                held[k] = 0;
+            }
+        }
+    }
+    const int64_t cols = d + 1;
+#pragma unroll
+    for (int k = 0; k < KT; ++k) {
+        if (mode[k] == MODE_IDLE) continue;   // uniform over the workgroup
+        double *pk = partials + (int64_t)k * cols * gridDim.x;
+        T::flush(acc[k], d, lane, wv, lds, pk);
+        const double ls = block_sum(loss_acc[k], lds_red);   // its barriers also order the reuse of lds
+        if (threadIdx.x == 0) pk[d * (int64_t)gridDim.x + blockIdx.x] = ls;
+    }
+}
+
+// ------------------------------------------------------------------ membership words
+// planes[k][tile] bit i = bit k of member[tile*64 + i]; rows past n give zero bits.  bad[0] is set when a word has a bit
+// at or above K.
+__global__ __launch_bounds__(kBlock) void k_member_planes(int64_t n, int K, const uint32_t *__restrict__ member,
+                                                          int64_t ntiles, uint64_t *__restrict__ planes, int *bad)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t nwaves = (int64_t)gridDim.x * kWavesPerBlock;
+    for (int64_t tile = (int64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave; tile < ntiles; tile += nwaves) {
+        const int64_t row = tile * kWave + lane;
+        const uint32_t m = (row < n) ? member[row] : 0u;
+        if (K < 32 && (m >> K) != 0u) bad[0] = 1;
+        for (int k = 0; k < K; ++k) {
+            const uint64_t b = __ballot((m >> k) & 1u);
+            if (lane == 0) planes[(int64_t)k * ntiles + tile] = b;
+        }
+    }
+}
+
+// ------------------------------------------------------------------ per-problem steps on the device
+// Every lane of the wavefront executes every statement (the sums run over all 64 lanes); lanes at or past d hold zeros
+// and their memory accesses are masked by `in`.
+__device__ __forceinline__ double dot64(double a, double b) { return wave_sum(a * b); }
+
+struct Request {
+    int mode, slot;
+    double vec;   // this lane's entry of the vector
+};
+
+// Start of the truncated CG iteration at the current iterate: s = 0, r = p = -g; the first product is H p.
+__device__ __forceinline__ Request cg_begin(ProbState &S, ProbScalars &sc, int j, bool in, double g)
+{
+    if (in) {
+        S.s[j] = 0.0;
+        S.r[j] = -g;
+        S.p[j] = -g;
+    }
+    sc.rr = sc.gnorm * sc.gnorm;
+    sc.cg_it = 0;
+    sc.onb = 0;
+    sc.phase = PH_CG;
+    return Request{MODE_HV, sc.dcur, -g};
+}
+
+// End of the inner iteration: trial point w + s and the model's reduction pred = -q(s) = -1/2 (g.s - s.r);
+// the next pass evaluates f and the gradient there, D going to the problem's other buffer.
+__device__ __forceinline__ Request cg_end(ProbState &S, ProbScalars &sc, int j, bool in, double s, double r)
+{
+    const double w = in ? S.w[j] : 0.0, g = in ? S.g[j] : 0.0;
+    const double wnew = w + s;
+    const double gs = dot64(g, s), sr = dot64(s, r);
+    sc.snorm = sqrt(dot64(s, s));
+    sc.pred = -0.5 * (gs - sr);
+    if (in) S.wnew[j] = wnew;
+    sc.phase = PH_TRIAL;
+    return Request{MODE_FG, 1 - sc.dcur, wnew};
+}
+
+__device__ __forceinline__ void finish(ProbScalars &sc, int status)
+{
+    sc.status = status;
+    sc.converged = (status == TRON_OK) ? 1 : 0;
+    sc.phase = PH_DONE;
+}
+
+// One workgroup per problem.  All four wavefronts add up the pass's partial sums (fixed order); the first one then runs
+// the step that was waiting for them.  The rules are those of the single-problem driver (Algorithm 1 with
+// Steihaug's truncated CG), lane j holding entry j of every vector.
+__global__ __launch_bounds__(kBlock) void k_batch_advance(int64_t d, int grid, const double *__restrict__ partials,
+                                                          BatchCtl *ctl, ProbState *st, SolveParams P,
+                                                          tron_trace_rec *trace)
+{
+    const int k = blockIdx.x;
+    const int mode = ctl->mode[k];
+    if (mode == MODE_IDLE) return;
+    __shared__ double cs[kVecPad + 1];
+    const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave;
+    for (int c = wv; c <= d; c += kWavesPerBlock) {
+        const double *p = partials + ((int64_t)k * (d + 1) + c) * grid;
+        double s = 0.0;
+        for (int b = lane; b < grid; b += kWave) s += p[b];
+        s = wave_sum(s);
+        if (lane == 0) cs[c] = s;
+    }
+    __syncthreads();
+    if (wv != 0) return;
+
+    ProbState &S = st[k];
+    ProbScalars sc = S.sc;   // every lane works on a copy; lane 0 writes it back
+    const bool in = lane < d;
+    const int j = in ? lane : 0;
+    const double C = sc.C;
+    const double u = in ? ctl->vec[k][j] : 0.0;     // entry j of the vector the pass used
+    const double o = in ? fma(C, cs[j], u) : 0.0;   // entry j of  v + C X^T(D(Xv))  or of  w + C X^T zhat
+    Request next{MODE_IDLE, sc.dcur, 0.0};
+    const double eta0 = 1e-4, eta1 = 0.25, eta2 = 0.75, sig2 = 0.5, sig3 = 4.0;
+
+    if (mode == MODE_HV) {
+        const double pHp = dot64(u, o);
+        if (sc.phase == PH_ONESHOT) {
+            if (in) S.out[j] = o;
+            sc.out_scal = pHp;
+            sc.phase = PH_DONE;
+        } else {   // PH_CG: u is the direction p
+            double s = in ? S.s[j] : 0.0, r = in ? S.r[j] : 0.0;
+            sc.cg_it += 1;
+            sc.n_hv += 1;
+            sc.cg_total += 1;
+            const double alpha = sc.rr / pHp;
+            const double pp = dot64(u, u), sp = dot64(s, u), ss = dot64(s, s);
+            bool end = false;
+            if (sqrt(ss + alpha * (2.0 * sp + alpha * pp)) >= sc.delta) {
+                // to the boundary along p
+                const double gap = sc.delta * sc.delta - ss;
+                const double rad = sqrt(sp * sp + pp * gap);
+                const double tau = (sp >= 0.0) ? gap / (sp + rad) : (rad - sp) / pp;
+                s = fma(tau, u, s);
+                r = fma(-tau, o, r);
+                sc.onb = 1;
+                end = true;
+            } else {
+                s = fma(alpha, u, s);
+                r = fma(-alpha, o, r);
+                const double rr_new = dot64(r, r);
+                const double beta = rr_new / sc.rr;
+                sc.rr = rr_new;
+                if (sqrt(rr_new) <= P.xi * sc.gnorm || sc.cg_it >= P.max_cg) {
+                    end = true;
+                } else {
+                    const double p = fma(beta, u, r);
+                    if (in) S.p[j] = p;
+                    next = Request{MODE_HV, sc.dcur, p};
+                }
+            }
+            if (in) {
+                S.s[j] = s;
+                S.r[j] = r;
+            }
+            if (end) next = cg_end(S, sc, j, in, s, r);
+        }
+    } else {   // MODE_FG: u is the point, o the gradient there
+        const double f = 0.5 * dot64(u, u) + C * cs[d];
+        const double gn = sqrt(dot64(o, o));
+        if (sc.phase == PH_ONESHOT) {
+            if (in) S.out[j] = o;
+            sc.out_scal = f;
+            sc.phase = PH_DONE;
+        } else if (sc.phase == PH_REF) {
+            // the gradient at w = 0 is the reference of the stopping test; now the starting point itself
+            sc.gnorm0 = gn;
+            sc.n_fun += 1;
+            sc.n_grad += 1;
+            sc.phase = PH_START;
+            next = Request{MODE_FG, sc.dcur, in ? S.w[j] : 0.0};
+        } else if (sc.phase == PH_START) {
+            sc.f = f;
+            sc.gnorm = gn;
+            if (in) S.g[j] = o;
+            sc.n_fun += 1;
+            sc.n_grad += 1;
+            if (sc.gnorm0 == 0.0) sc.gnorm0 = gn;
+            sc.delta = gn;
+            if (gn <= P.eps * sc.gnorm0) finish(sc, TRON_OK);
+            else next = cg_begin(S, sc, j, in, o);
+        } else {   // PH_TRIAL
+            sc.n_fun += 1;
+            const double ared = sc.f - f;
+            const bool noise = fabs(ared) <= 1e-12 * fabs(sc.f) && sc.pred <= 1e-12 * fabs(sc.f);
+            const double sigma = noise ? 1.0 : ared / sc.pred;
+            const double gnorm_before = sc.gnorm;
+            if (sigma < eta1) sc.delta = sig2 * fmin(sc.snorm, sc.delta);
+            else if (sigma < eta2) { /* unchanged */ }
+            else sc.delta = fmin(sig3 * sc.delta, fmax(sc.delta, sig3 * sc.snorm));
+            const bool accepted = sigma > eta0;
+            double g = in ? S.g[j] : 0.0;
+            if (accepted) {
+                if (in) {
+                    S.w[j] = u;
+                    S.g[j] = o;
+                }
+                g = o;
+                sc.dcur = 1 - sc.dcur;   // the Hessian now uses D at the accepted point
+                sc.f = f;
+                sc.gnorm = gn;
+                sc.n_grad += 1;
+            }
+            sc.outer += 1;
+            if (trace && sc.trace_len < P.trace_cap) {
+                if (lane == 0) {
+                    tron_trace_rec &t = trace[(int64_t)k * P.trace_cap + sc.trace_len];
+                    t.iter = sc.outer; t.cg_iters = sc.cg_it; t.accepted = accepted ? 1 : 0; t.on_boundary = sc.onb;
+                    t.f = sc.f; t.gnorm = sc.gnorm; t.delta = sc.delta; t.ared = ared; t.pred = sc.pred; t.snorm = sc.snorm;
+                }
+                sc.trace_len += 1;
+            }
+            if (accepted && sc.gnorm <= P.eps * sc.gnorm0) finish(sc, TRON_OK);
+            else if (sc.pred <= 0.0 || (noise && sc.gnorm >= gnorm_before)) finish(sc, TRON_EMAXITER);
+            else if (sc.outer >= P.max_outer) finish(sc, TRON_EMAXITER);
+            else next = cg_begin(S, sc, j, in, g);
+        }
+    }
+    if (lane < kVecPad) ctl->vec[k][lane] = in ? next.vec : 0.0;
+    if (lane == 0) {
+        ctl->mode[k] = next.mode;
+        ctl->dslot[k] = next.slot;
+        S.sc = sc;
+    }
+}
+
+// First request of every problem.  what = BEGIN_SOLVE: state reset, w0 = IN[k]; when w0 is not zero the gradient at zero
+// is evaluated first (it is the reference of the stopping test).  BEGIN_FG / BEGIN_HV: a single product with IN[k],
+// using the problem's current D buffer.
+__global__ __launch_bounds__(kWave) void k_batch_begin(int what, int64_t d, const double *__restrict__ IN, BatchC Cs,
+                                                       BatchCtl *ctl, ProbState *st)
+{
+    const int k = blockIdx.x, lane = threadIdx.x;
+    ProbState &S = st[k];
+    const bool in = lane < d;
+    const double x = in ? IN[(int64_t)k * d + lane] : 0.0;
+    ProbScalars sc = S.sc;
+    sc.C = Cs.v[k];
+    Request next{MODE_IDLE, 0, 0.0};
+    if (what == BEGIN_SOLVE) {
+        sc.status = TRON_EMAXITER;
+        sc.converged = sc.outer = sc.cg_total = sc.n_fun = sc.n_grad = sc.n_hv = sc.cg_it = sc.onb = sc.trace_len = 0;
+        sc.dcur = 0;
+        sc.f = sc.gnorm = sc.gnorm0 = sc.delta = sc.rr = sc.pred = sc.snorm = sc.out_scal = 0.0;
+        if (in) S.w[lane] = x;
+        const bool nonzero = __ballot(x != 0.0) != 0;
+        sc.phase = nonzero ? PH_REF : PH_START;
+        next = Request{MODE_FG, 0, nonzero ? 0.0 : x};
+    } else {
+        sc.phase = PH_ONESHOT;
+        next = Request{what == BEGIN_FG ? MODE_FG : MODE_HV, sc.dcur, x};
+    }
+    if (lane < kVecPad) ctl->vec[k][lane] = in ? next.vec : 0.0;
+    if (lane == 0) {
+        ctl->mode[k] = next.mode;
+        ctl->dslot[k] = next.slot;
+        S.sc = sc;
+    }
+}
+
+// OUT[k*d + j] = entry j of problem k's iterate (which = 0) or of its last single product (which = 1)
+__global__ __launch_bounds__(kWave) void k_batch_store(int which, int64_t d, const ProbState *__restrict__ st,
+                                                       double *__restrict__ OUT)
+{
+    const int k = blockIdx.x, lane = threadIdx.x;
+    if (lane < d) OUT[(int64_t)k * d + lane] = which ? st[k].out[lane] : st[k].w[lane];
+}
+
+// ------------------------------------------------------------------ kernel choice
+using PassFn = void (*)(int64_t, int64_t, const double *, const int8_t *, int, const BatchCtl *, const uint64_t *,
+                        const uint64_t *, uint64_t *, double *, int64_t, double *);
+
+template <int E, int L, int KT>
+PassFn pass_for(bool vec)
+{
+    constexpr int U = pick_U(E, L);
+    if constexpr (E % 2 == 0) {
+        if (vec) return k_batch_pass<E, L, U, true, KT>;
+    }
+    return k_batch_pass<E, L, U, false, KT>;
+}
+
+template <int KT>
+PassFn pass_for_shape(const Shape &s, bool vec)
+{
+    switch (s.L * 16 + s.E) {
+    case 16 + 1: return pass_for<1, 1, KT>(vec);
+    case 16 + 2: return pass_for<2, 1, KT>(vec);
+    case 16 + 3: return pass_for<3, 1, KT>(vec);
+    case 16 + 4: return pass_for<4, 1, KT>(vec);
+    case 16 + 5: return pass_for<5, 1, KT>(vec);
+    case 16 + 6: return pass_for<6, 1, KT>(vec);
+    case 16 + 7: return pass_for<7, 1, KT>(vec);
+    case 16 + 8: return pass_for<8, 1, KT>(vec);
+    case 32 + 5: return pass_for<5, 2, KT>(vec);
+    case 32 + 6: return pass_for<6, 2, KT>(vec);
+    case 32 + 7: return pass_for<7, 2, KT>(vec);
+    case 32 + 8: return pass_for<8, 2, KT>(vec);
+    case 64 + 5: return pass_for<5, 4, KT>(vec);
+    case 64 + 6: return pass_for<6, 4, KT>(vec);
+    case 64 + 7: return pass_for<7, 4, KT>(vec);
+    case 64 + 8: return pass_for<8, 4, KT>(vec);
+    default: return nullptr;
+    }
+}
+
+}  // namespace
+}  // namespace tron
+
+// ------------------------------------------------------------------ the handle
+struct tron_batch {
+    tron_dataset *ds = nullptr;
+    int K = 0, KT = 0;
+    int64_t ntiles = 0;
+    uint64_t *member = nullptr;   // K planes of ntiles words
+    uint64_t *Dbits = nullptr;    // K x 2 planes (L2-SVM active sets)
+    double *Dval = nullptr;       // K x 2 x n (logistic D), allocated at the first logistic call
+    tron::BatchCtl *ctl = nullptr;
+    tron::ProbState *st = nullptr;
+    tron::ProbState *st_host = nullptr;   // pinned
+    int32_t *mode_host = nullptr;         // pinned, kBatchMax
+    tron_trace_rec *trace = nullptr;      // device, K * trace_cap
+    int trace_cap = 0;
+    double *partials = nullptr;           // K x (d+1) x grid
+    int grid = 0;
+    tron::PassFn pass = nullptr;
+    int D_loss = -1;                      // loss whose D the buffers hold (-1: none)
+};
+
+namespace tron {
+namespace {
+
+int launch_pass(tron_batch *b, int loss)
+{
+    tron_dataset *ds = b->ds;
+    ProfScope ps(ds, SLOT_BATCH_PASS);
+    int64_t n = ds->n, d = ds->d, ntiles = b->ntiles;
+    const double *X = ds->X;
+    const int8_t *y = ds->y8;
+    const BatchCtl *ctl = b->ctl;
+    const uint64_t *member = b->member, *Din = b->Dbits;
+    uint64_t *Dout = b->Dbits;
+    double *Dval = b->Dval, *partials = b->partials;
+    void *args[] = {&n, &d, &X, &y, &loss, &ctl, &member, &Din, &Dout, &Dval, &ntiles, &partials};
+    TRON_HIP(hipLaunchKernel(reinterpret_cast<const void *>(b->pass), dim3(b->grid), dim3(kBlock), args, 0, ds->stream));
+    return TRON_OK;
+}
+
+int launch_advance(tron_batch *b, const SolveParams &P)
+{
+    tron_dataset *ds = b->ds;
+    ProfScope ps(ds, SLOT_BATCH_ADVANCE);
+    hipLaunchKernelGGL(k_batch_advance, dim3(b->K), dim3(kBlock), 0, ds->stream, ds->d, b->grid, b->partials, b->ctl, b->st, P,
+                       P.trace_cap > 0 ? b->trace : nullptr);
+    TRON_HIP(hipGetLastError());
+    return TRON_OK;
+}
+
+int launch_begin(tron_batch *b, int what, const double *IN, const double *C_host)
+{
+    BatchC Cs;
+    for (int k = 0; k < kBatchMax; ++k) Cs.v[k] = (k < b->K) ? C_host[k] : 1.0;
+    ProfScope ps(b->ds, SLOT_BATCH_ADVANCE);
+    hipLaunchKernelGGL(k_batch_begin, dim3(b->K), dim3(kWave), 0, b->ds->stream, what, b->ds->d, IN, Cs, b->ctl, b->st);
+    TRON_HIP(hipGetLastError());
+    return TRON_OK;
+}
+
+int ensure_D(tron_batch *b, int loss)
+{
+    if (loss == TRON_LOSS_LR && !b->Dval)
+        TRON_HIP(hipMalloc(reinterpret_cast<void **>(&b->Dval), sizeof(double) * 2 * (size_t)b->K * (size_t)b->ds->n));
+    return TRON_OK;
+}
+
+bool bad_C(const tron_batch *b, const double *C_host)
+{
+    for (int k = 0; k < b->K; ++k)
+        if (!(C_host[k] > 0.0) || !std::isfinite(C_host[k])) return true;
+    return false;
+}
+
+// one single product for every problem: begin, pass, advance, results to OUT (K*d) and scal_host (K)
+int one_shot(tron_batch *b, int what, int loss, const double *C_host, const double *IN, double *OUT, double *scal_host)
+{
+    tron_dataset *ds = b->ds;
+    SolveParams P{};
+    P.loss = loss;
+    TRON_TRY(launch_begin(b, what, IN, C_host));
+    TRON_TRY(launch_pass(b, loss));
+    TRON_TRY(launch_advance(b, P));
+    if (OUT) {
+        hipLaunchKernelGGL(k_batch_store, dim3(b->K), dim3(kWave), 0, ds->stream, 1, ds->d, b->st, OUT);
+        TRON_HIP(hipGetLastError());
+    }
+    TRON_HIP(hipMemcpyAsync(b->st_host, b->st, sizeof(ProbState) * b->K, hipMemcpyDeviceToHost, ds->stream));
+    TRON_HIP(hipStreamSynchronize(ds->stream));
+    if (scal_host)
+        for (int k = 0; k < b->K; ++k) scal_host[k] = b->st_host[k].sc.out_scal;
+    return TRON_OK;
+}
+
+}  // namespace
+}  // namespace tron
+
+using namespace tron;
+
+extern "C" void tron_batch_destroy(tron_batch *b)
+{
+    if (!b) return;
+    if (b->ds) hipStreamSynchronize(b->ds->stream);
+    hipFree(b->member); hipFree(b->Dbits); hipFree(b->Dval); hipFree(b->ctl); hipFree(b->st); hipFree(b->trace); hipFree(b->partials);
+    if (b->st_host) hipHostFree(b->st_host);
+    if (b->mode_host) hipHostFree(b->mode_host);
+    delete b;
+}
+
+extern "C" int tron_batch_create(tron_dataset *ds, int K, const uint32_t *member, int mem, tron_batch **out)
+{
+    if (out) *out = nullptr;
+    if (!ds || !out || !member || K < 1 || K > kBatchMax || (mem != TRON_MEM_HOST && mem != TRON_MEM_DEVICE)) {
+        set_error("tron_batch_create: bad argument (need a handle, 1 <= K <= %d, member, mem in {0,1}, out)", kBatchMax);
+        return TRON_EINVAL;
+    }
+    if (!ds->dense || ds->d > kVecPad) {
+        set_error("tron_batch_create: needs a dense dataset with d <= %d", kVecPad);
+        return TRON_EINVAL;
+    }
+    const int64_t n = ds->n, d = ds->d;
+    if (mem == TRON_MEM_HOST && K < 32)
+        for (int64_t i = 0; i < n; ++i)
+            if ((member[i] >> K) != 0u) { set_error("tron_batch_create: member[%lld] has a bit at or above K", (long long)i); return TRON_EINVAL; }
+    Shape s;
+    if (!pick_shape(d, s) || s.L > 4) { set_error("tron_batch_create: internal: no tile shape for d = %lld", (long long)d); return TRON_EINVAL; }
+    tron_batch *b = new (std::nothrow) tron_batch();
+    if (!b) { set_error("out of host memory"); return TRON_ENOMEM; }
+    b->ds = ds;
+    b->K = K;
+    b->KT = (K <= 4) ? 4 : 8;
+    b->ntiles = (n + kWave - 1) / kWave;
+    const bool vec = (s.E % 2 == 0) && (d % 2 == 0);
+    b->pass = (b->KT == 4) ? pass_for_shape<4>(s, vec) : pass_for_shape<8>(s, vec);
+    auto fail = [&](int rc) { tron_batch_destroy(b); return rc; };
+#define TRON_B(expr) do { hipError_t e__ = (expr); if (e__ != hipSuccess) return fail(hip_fail(e__, #expr, __FILE__, __LINE__)); } while (0)
+    if (!b->pass) { set_error("tron_batch_create: internal: no kernel for E=%d L=%d", s.E, s.L); return fail(TRON_EINVAL); }
+    // resident workgroups of the pass: all of them hold their accumulators for the whole pass
+    int per_cu = 0, cus = 0;
+    TRON_B(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(b->pass), kBlock, 0));
+    TRON_B(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, ds->device));
+    int64_t grid = (int64_t)cus * (per_cu < 1 ? 1 : per_cu);
+    if (g_tuning.batch_grid > 0) grid = g_tuning.batch_grid;
+    const int64_t by_tiles = (b->ntiles + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (grid > by_tiles) grid = by_tiles;
+    if (grid < 1) grid = 1;
+    b->grid = (int)grid;
+    TRON_B(hipMalloc(reinterpret_cast<void **>(&b->member), sizeof(uint64_t) * (size_t)K * (size_t)b->ntiles));
+    TRON_B(hipMalloc(reinterpret_cast<void **>(&b->Dbits), sizeof(uint64_t) * 2 * (size_t)K * (size_t)b->ntiles));
+    TRON_B(hipMalloc(reinterpret_cast<void **>(&b->ctl), sizeof(BatchCtl)));
+    TRON_B(hipMalloc(reinterpret_cast<void **>(&b->st), sizeof(ProbState) * kBatchMax));
+    TRON_B(hipMalloc(reinterpret_cast<void **>(&b->partials), sizeof(double) * (size_t)K * (size_t)(d + 1) * (size_t)b->grid));
+    TRON_B(hipHostMalloc(reinterpret_cast<void **>(&b->st_host), sizeof(ProbState) * kBatchMax, hipHostMallocDefault));
+    TRON_B(hipHostMalloc(reinterpret_cast<void **>(&b->mode_host), sizeof(int32_t) * (kBatchMax + 1), hipHostMallocDefault));
+    TRON_B(hipMemsetAsync(b->ctl, 0, sizeof(BatchCtl), ds->stream));
+    TRON_B(hipMemsetAsync(b->st, 0, sizeof(ProbState) * kBatchMax, ds->stream));
+    TRON_B(hipMemsetAsync(b->Dbits, 0, sizeof(uint64_t) * 2 * (size_t)K * (size_t)b->ntiles, ds->stream));
+    // membership words; a device-side check of the unused bits for device input
+    uint32_t *staged = nullptr;
+    int *bad = nullptr;
+    TRON_B(hipMalloc(reinterpret_cast<void **>(&bad), sizeof(int)));
+    hipError_t e = hipMemsetAsync(bad, 0, sizeof(int), ds->stream);
+    const uint32_t *src = member;
+    if (e == hipSuccess && mem == TRON_MEM_HOST) {
+        e = hipMalloc(reinterpret_cast<void **>(&staged), sizeof(uint32_t) * (size_t)n);
+        if (e == hipSuccess) e = hipMemcpyAsync(staged, member, sizeof(uint32_t) * (size_t)n, hipMemcpyHostToDevice, ds->stream);
+        src = staged;
+    }
+    int bad_host = 0;
+    if (e == hipSuccess) {
+        int64_t g = (b->ntiles + kWavesPerBlock - 1) / kWavesPerBlock;
+        if (g > kMaxGrid) g = kMaxGrid;
+        hipLaunchKernelGGL(k_member_planes, dim3((int)g), dim3(kBlock), 0, ds->stream, n, K, src, b->ntiles, b->member, bad);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipMemcpyAsync(&bad_host, bad, sizeof(int), hipMemcpyDeviceToHost, ds->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ds->stream);
+    hipFree(staged);
+    hipFree(bad);
+    if (e != hipSuccess) return fail(hip_fail(e, "membership words", __FILE__, __LINE__));
+    if (bad_host) { set_error("tron_batch_create: a member word has a bit at or above K"); return fail(TRON_EINVAL); }
+#undef TRON_B
+    *out = b;
+    return TRON_OK;
+}
+
+extern "C" int tron_batch_fun_grad(tron_batch *b, int loss, const double *C_host, const double *W_dev, double *f_host,
+                                   double *G_dev)
+{
+    if (!b || !C_host || !W_dev || !f_host || (loss != TRON_LOSS_LR && loss != TRON_LOSS_L2SVM) || bad_C(b, C_host)) {
+        set_error("tron_batch_fun_grad: bad argument (null batch/C/W/f, unknown loss, or some C <= 0)");
+        return TRON_EINVAL;
+    }
+    TRON_TRY(ensure_D(b, loss));
+    TRON_TRY(one_shot(b, BEGIN_FG, loss, C_host, W_dev, G_dev, f_host));
+    b->D_loss = loss;
+    return TRON_OK;
+}
+
+extern "C" int tron_batch_hv(tron_batch *b, const double *C_host, const double *V_dev, double *HV_dev, double *vHv_host)
+{
+    if (!b || !C_host || !V_dev || !HV_dev || V_dev == HV_dev || bad_C(b, C_host)) {
+        set_error("tron_batch_hv: bad argument (null batch/C/V/HV, V aliases HV, or some C <= 0)");
+        return TRON_EINVAL;
+    }
+    if (b->D_loss < 0) { set_error("tron_batch_hv: no cached D; call tron_batch_fun_grad first"); return TRON_ESTATE; }
+    return one_shot(b, BEGIN_HV, b->D_loss, C_host, V_dev, HV_dev, vHv_host);
+}
+
+extern "C" int tron_batch_solve(tron_batch *b, const tron_params *params, const double *C_host, double *W_dev,
+                                tron_result *res, int *status_host)
+{
+    if (!b || !params || !C_host || !W_dev || !res) { set_error("tron_batch_solve: null argument"); return TRON_EINVAL; }
+    const tron_params &Q = *params;
+    if ((Q.loss != TRON_LOSS_LR && Q.loss != TRON_LOSS_L2SVM) || bad_C(b, C_host) || !(Q.eps > 0.0) || Q.max_outer < 1 ||
+        Q.max_cg < 1 || !(Q.cg_xi > 0.0) || !(Q.cg_xi < 1.0) || Q.precond_blend != 0.0) {
+        set_error("tron_batch_solve: bad parameter (loss, every C > 0, eps > 0, max_outer >= 1, max_cg >= 1, 0 < cg_xi < 1, "
+                  "precond_blend = 0)");
+        return TRON_EINVAL;
+    }
+    int cap = 0;
+    for (int k = 0; k < b->K; ++k) {
+        if (res[k].trace_cap < 0 || (res[k].trace_cap > 0 && !res[k].trace)) { set_error("tron_batch_solve: bad trace of problem %d", k); return TRON_EINVAL; }
+        if (res[k].trace_cap > cap) cap = res[k].trace_cap;
+    }
+    tron_dataset *ds = b->ds;
+    TRON_TRY(ensure_D(b, Q.loss));
+    if (cap > b->trace_cap) {
+        hipFree(b->trace);
+        b->trace = nullptr;
+        b->trace_cap = 0;
+        TRON_HIP(hipMalloc(reinterpret_cast<void **>(&b->trace), sizeof(tron_trace_rec) * (size_t)b->K * (size_t)cap));
+        b->trace_cap = cap;
+    }
+    SolveParams P{Q.loss, Q.max_outer, Q.max_cg, cap, Q.eps, Q.cg_xi};
+    b->D_loss = -1;
+    TRON_TRY(launch_begin(b, BEGIN_SOLVE, W_dev, C_host));
+    // A problem needs at most 2 + max_outer (max_cg + 1) rounds.  The host looks at the modes every `poll` rounds; a
+    // pass that finds every problem idle returns at once.
+    const int64_t round_cap = 2 + (int64_t)Q.max_outer * ((int64_t)Q.max_cg + 1);
+    const double pass_bytes = (double)ds->n * (double)ds->d * 8.0;
+    const int poll = pass_bytes < 4e8 ? 4 : 1;
+    bool live = true;
+    for (int64_t round = 0; live && round < round_cap + poll; round += poll) {
+        for (int i = 0; i < poll; ++i) {
+            TRON_TRY(launch_pass(b, Q.loss));
+            TRON_TRY(launch_advance(b, P));
+        }
+        TRON_HIP(hipMemcpyAsync(b->mode_host, b->ctl->mode, sizeof(int32_t) * kBatchMax, hipMemcpyDeviceToHost, ds->stream));
+        TRON_HIP(hipStreamSynchronize(ds->stream));
+        live = false;
+        for (int k = 0; k < b->K; ++k) live |= b->mode_host[k] != MODE_IDLE;
+    }
+    if (live) { set_error("tron_batch_solve: internal: problems still running after the round limit"); return TRON_ESTATE; }
+    hipLaunchKernelGGL(k_batch_store, dim3(b->K), dim3(kWave), 0, ds->stream, 0, ds->d, b->st, W_dev);
+    TRON_HIP(hipGetLastError());
+    TRON_HIP(hipMemcpyAsync(b->st_host, b->st, sizeof(ProbState) * b->K, hipMemcpyDeviceToHost, ds->stream));
+    TRON_HIP(hipStreamSynchronize(ds->stream));
+    int overall = TRON_OK;
+    for (int k = 0; k < b->K; ++k) {
+        const ProbScalars &sc = b->st_host[k].sc;
+        tron_result &r = res[k];
+        r.f = sc.f; r.gnorm = sc.gnorm; r.gnorm0 = sc.gnorm0;
+        r.outer_iters = sc.outer; r.cg_iters_total = sc.cg_total; r.n_fun = sc.n_fun; r.n_grad = sc.n_grad; r.n_hv = sc.n_hv;
+        r.converged = sc.converged;
+        r.trace_len = sc.trace_len < r.trace_cap ? sc.trace_len : r.trace_cap;
+        if (r.trace_len > 0)
+            TRON_HIP(hipMemcpy(r.trace, b->trace + (size_t)k * cap, sizeof(tron_trace_rec) * r.trace_len, hipMemcpyDeviceToHost));
+        if (status_host) status_host[k] = sc.status;
+        if (sc.status != TRON_OK) overall = TRON_EMAXITER;
+    }
+    b->D_loss = Q.loss;
+    return overall;
+}

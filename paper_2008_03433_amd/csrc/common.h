@@ -38,6 +38,7 @@ struct Tuning {
     int64_t csr_blocks_per_part = 128;     // persistent workgroups per column range without LDS tables
     int64_t csr_tiles = 1;   // hot-row tiles for the transposed orientation of partitioned matrices (0 = off)
     int64_t csr_tile_blocks_per_slice = 96;  // persistent workgroups per slice of hot rows
+    int64_t batch_grid = 0;  // workgroups of the multi-problem pass: 0 = as many as are resident at once
 };
 extern Tuning g_tuning;
 
@@ -66,6 +67,8 @@ enum Slot {
     SLOT_DOT,              // dot products / norms (first stage)
     SLOT_REDUCE_FINAL,     // second reduction stage -> scalars
     SLOT_CG_VEC,           // CG vector updates
+    SLOT_BATCH_PASS,       // multi-problem pass over X
+    SLOT_BATCH_ADVANCE,    // multi-problem partial sums + trust-region / CG step
     SLOT_COUNT
 };
 extern const char *const kSlotNames[SLOT_COUNT];

@@ -73,4 +73,9 @@ def test_argument_errors_are_reported_before_touching_the_device():
     assert lib.tron_solve(None, None, None, None) == binding.EINVAL
     assert lib.tron_tuning_set(b"no_such_knob", 1) == binding.EINVAL
     assert "tron_tuning_set" in tron.tron_last_error()
+    assert lib.tron_batch_create(None, 3, None, 0, ctypes.byref(out)) == binding.EINVAL
+    assert lib.tron_batch_fun_grad(None, 0, None, None, None, None) == binding.EINVAL
+    assert lib.tron_batch_hv(None, None, None, None, None) == binding.EINVAL
+    assert lib.tron_batch_solve(None, None, None, None, None, None) == binding.EINVAL
+    lib.tron_batch_destroy(None)
     lib.tron_dataset_destroy(None)  # NULL is ignored
