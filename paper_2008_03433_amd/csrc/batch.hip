@@ -52,18 +52,20 @@ struct SolveParams {
 
 struct BatchC { double v[kBatchMax]; };
 
+typedef const uint64_t __attribute__((address_space(4))) *ConstWords;
+
 // ------------------------------------------------------------------ the pass over X
 // Work layout as in the single-problem kernels: a wave tile is 64 consecutive rows, a wavefront walks a contiguous
 // range of tiles.  Per tile and problem one 64-bit word says which rows concern the problem: its members
 // (function/gradient pass, logistic Hessian) or its active set I (L2-SVM Hessian: D_ii = 2 on I).  Rows that concern no
 // problem are not read.  The words of the next tile are fetched (scalar loads) while the current one is processed.
-// New active-set words are kept one per lane and stored 64 tiles at a time.
+// New active-set words are collected in LDS and stored 64 tiles at a time.
 //   member: [k][tile]     Dbits: [k][slot][tile]     Dval (logistic D): [k][slot][row]
 //   partials: [k][column 0..d-1, then the loss sum][workgroup]
 // Dbits_in and Dbits_out are the same array: a problem's plane is either read (MODE_HV) or written (MODE_FG) by a pass.
-template <int E, int L, int U, bool VEC, int KT>
-__global__ __launch_bounds__(kBlock) void k_batch_pass(int64_t n, int64_t d, const double *__restrict__ X,
-                                                       const int8_t *__restrict__ y, int loss,
+template <int E, int L, int U, bool VEC, int KT, int LOSS>
+__global__ __launch_bounds__(kBlock, 2) void k_batch_pass(int64_t n, int64_t d, const double *__restrict__ X,
+                                                       const int8_t *__restrict__ y,
                                                        const BatchCtl *__restrict__ ctl, const uint64_t *__restrict__ member,
                                                        const uint64_t *__restrict__ Dbits_in, uint64_t *Dbits_out,
                                                        double *Dval, int64_t ntiles, double *__restrict__ partials)
@@ -73,6 +75,10 @@ __global__ __launch_bounds__(kBlock) void k_batch_pass(int64_t n, int64_t d, con
     __shared__ double lvec[KT][E * L];
     __shared__ double lds[kWavesPerBlock * E * L];
     __shared__ double lds_red[kWavesPerBlock];
+    // function/gradient pass only, kept out of the registers: per wavefront and problem the loss sum of every lane's rows
+    // and the new active-set words of up to 64 tiles
+    __shared__ double lloss[kWavesPerBlock][KT][kWave];
+    __shared__ uint64_t lheld[kWavesPerBlock][KT][kWave];
     const int lane = threadIdx.x & (kWave - 1);
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int q = lane % L;
@@ -86,25 +92,33 @@ __global__ __launch_bounds__(kBlock) void k_batch_pass(int64_t n, int64_t d, con
         any_fg |= mode[k] == MODE_FG;
     }
     if (!any) return;
+    constexpr bool svm = LOSS == TRON_LOSS_L2SVM;
+    // L2-SVM Hessian: D_ii = 2 on the active set.  The factor is put into v (exact: a power of two), the product
+    // then only selects rows.
     for (int i = threadIdx.x; i < KT * E * L; i += kBlock) {
         const int k = i / (E * L), c = i % (E * L);
-        lvec[k][c] = (c < d) ? ctl->vec[k][c] : 0.0;
+        const double scale = (svm && ctl->mode[k] == MODE_HV) ? 2.0 : 1.0;
+        lvec[k][c] = (c < d) ? scale * ctl->vec[k][c] : 0.0;
     }
     __syncthreads();
-    const bool svm = loss == TRON_LOSS_L2SVM;
-    // plane of the words that say which rows concern problem k
-    const uint64_t *words[KT];
+    // this lane's row in step u is tile row u * RW + rl: its bit in a 64-bit word, as a 32-bit mask of the word's half
+    const int rl = lane / L;
+    uint32_t rowbit[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) rowbit[u] = 1u << ((u * T::RW + rl) & 31);
+    // plane of the words that say which rows concern problem k.  The words are the same for all lanes: read through
+    // the constant address space they arrive in scalar registers.  (No plane read here is written by this pass.)
+    ConstWords words[KT];
 #pragma unroll
     for (int k = 0; k < KT; ++k) {
-        if (mode[k] == MODE_HV && svm) words[k] = Dbits_in + ((int64_t)k * 2 + dslot[k]) * ntiles;
-        else words[k] = member + (int64_t)k * ntiles;
+        if (mode[k] == MODE_HV && svm) words[k] = (ConstWords)(Dbits_in + ((int64_t)k * 2 + dslot[k]) * ntiles);
+        else words[k] = (ConstWords)(member + (int64_t)k * ntiles);
     }
-    double acc[KT][E], loss_acc[KT];
-    uint64_t held[KT];
+    double acc[KT][E];
 #pragma unroll
     for (int k = 0; k < KT; ++k) {
-        loss_acc[k] = 0.0;
-        held[k] = 0;
+        lloss[wv][k][lane] = 0.0;
+        lheld[wv][k][lane] = 0;
 #pragma unroll
         for (int e = 0; e < E; ++e) acc[k][e] = 0.0;
     }
@@ -131,35 +145,52 @@ __global__ __launch_bounds__(kBlock) void k_batch_pass(int64_t n, int64_t d, con
             double x[U][E];
             T::load(X, n, d, row0, lane, x, rows);
             const double yrow = (any_fg && row0 + lane < n) ? (double)y[row0 + lane] : 1.0;
+            // the vectors are read from LDS again for every tile: hoisted out of the loop they would take KT * E
+            // registers per lane (the empty statement hides the loop invariance from the compiler)
+            int qoff = q * E;
+            asm volatile("" : "+v"(qoff));
 #pragma unroll
             for (int k = 0; k < KT; ++k) {
                 if (mode[k] == MODE_IDLE || wk[k] == 0) continue;   // uniform
                 double vk[E], t[U], c[U];
 #pragma unroll
-                for (int e = 0; e < E; ++e) vk[e] = lvec[k][q * E + e];
+                for (int e = 0; e < E; ++e) vk[e] = lvec[k][qoff + e];
                 T::row_dots(x, vk, t);
-                const double z = T::to_row_owner(t, lane);
-                const bool mine = (wk[k] >> lane) & 1u;
-                double coef;
                 if (mode[k] == MODE_HV) {
-                    double Dr = 0.0;
-                    if (mine) Dr = svm ? 2.0 : Dval[((int64_t)k * 2 + dslot[k]) * n + row0 + lane];
-                    coef = Dr * z;   // a1 = D (X v)
+                    // a1 = D (X v), formed by every lane of a row for itself (all of them hold the row's x.v)
+                    if (svm) {
+                        const uint32_t lo = (uint32_t)wk[k], hi = (uint32_t)(wk[k] >> 32);
+#pragma unroll
+                        for (int u = 0; u < U; ++u) {
+                            uint32_t half;
+                            if (T::RW == kWave) half = (lane < 32) ? lo : hi;
+                            else half = (u * T::RW < 32) ? lo : hi;
+                            c[u] = (half & rowbit[u]) ? t[u] : 0.0;
+                        }
+                    } else {
+                        const double *Dk = Dval + ((int64_t)k * 2 + dslot[k]) * n;   // zero outside the problem's rows
+#pragma unroll
+                        for (int u = 0; u < U; ++u) {
+                            const int64_t row = row0 + u * T::RW + rl;
+                            c[u] = (row < n) ? Dk[row] * t[u] : 0.0;
+                        }
+                    }
                 } else {
+                    // the per-row terms of Table 1 run once per row, lane i owning tile row i
+                    const double z = T::to_row_owner(t, lane);
+                    const bool mine = (wk[k] >> lane) & 1u;
                     double alpha, zhat, Di;
-                    if (svm) loss_terms_dev<TRON_LOSS_L2SVM>(z, yrow, alpha, zhat, Di);
-                    else loss_terms_dev<TRON_LOSS_LR>(z, yrow, alpha, zhat, Di);
+                    loss_terms_dev<LOSS>(z, yrow, alpha, zhat, Di);
                     if (!mine) { alpha = 0.0; zhat = 0.0; Di = 0.0; }
-                    loss_acc[k] += alpha;
+                    lloss[wv][k][lane] += alpha;
                     if (svm) {
                         const uint64_t nb = __ballot(Di != 0.0);
-                        if (lane == slotl) held[k] = nb;
+                        if (lane == 0) lheld[wv][k][slotl] = nb;
                     } else if (mine) {
                         Dval[((int64_t)k * 2 + dslot[k]) * n + row0 + lane] = Di;
                     }
-                    coef = zhat;
+                    T::from_row_owner(zhat, lane, c);
                 }
-                T::from_row_owner(coef, lane, c);
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
 #pragma unroll
@@ -168,12 +199,12 @@ __global__ __launch_bounds__(kBlock) void k_batch_pass(int64_t n, int64_t d, con
             }
         }
         if (svm && any_fg && (slotl == kWave - 1 || tile + 1 == last)) {
-            // lane i holds the words of tile (tile - slotl + i): consecutive 8-byte words per problem
+            // lane i takes the word of tile (tile - slotl + i): consecutive 8-byte words per problem
 #pragma unroll
             for (int k = 0; k < KT; ++k) {
                 if (mode[k] == MODE_FG && lane <= slotl)
-                    Dbits_out[((int64_t)k * 2 + dslot[k]) * ntiles + (tile - slotl) + lane] = held[k];
-                held[k] = 0;
+                    Dbits_out[((int64_t)k * 2 + dslot[k]) * ntiles + (tile - slotl) + lane] = lheld[wv][k][lane];
+                lheld[wv][k][lane] = 0;
             }
         }
     }
@@ -183,7 +214,7 @@ __global__ __launch_bounds__(kBlock) void k_batch_pass(int64_t n, int64_t d, con
         if (mode[k] == MODE_IDLE) continue;   // uniform over the workgroup
         double *pk = partials + (int64_t)k * cols * gridDim.x;
         T::flush(acc[k], d, lane, wv, lds, pk);
-        const double ls = block_sum(loss_acc[k], lds_red);   // its barriers also order the reuse of lds
+        const double ls = block_sum(lloss[wv][k][lane], lds_red);   // its barriers also order the reuse of lds
         if (threadIdx.x == 0) pk[d * (int64_t)gridDim.x + blockIdx.x] = ls;
     }
 }
@@ -253,10 +284,12 @@ __device__ __forceinline__ void finish(ProbScalars &sc, int status)
     sc.phase = PH_DONE;
 }
 
-// One workgroup per problem.  All four wavefronts add up the pass's partial sums (fixed order); the first one then runs
+constexpr int kAdvanceBlock = 1024;
+
+// One workgroup per problem.  All sixteen wavefronts add up the pass's partial sums (fixed order); the first one then runs
 // the step that was waiting for them.  The rules are those of the single-problem driver (Algorithm 1 with
 // Steihaug's truncated CG), lane j holding entry j of every vector.
-__global__ __launch_bounds__(kBlock) void k_batch_advance(int64_t d, int grid, const double *__restrict__ partials,
+__global__ __launch_bounds__(kAdvanceBlock) void k_batch_advance(int64_t d, int grid, const double *__restrict__ partials,
                                                           BatchCtl *ctl, ProbState *st, SolveParams P,
                                                           tron_trace_rec *trace)
 {
@@ -265,7 +298,7 @@ __global__ __launch_bounds__(kBlock) void k_batch_advance(int64_t d, int grid, c
     if (mode == MODE_IDLE) return;
     __shared__ double cs[kVecPad + 1];
     const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave;
-    for (int c = wv; c <= d; c += kWavesPerBlock) {
+    for (int c = wv; c <= d; c += kAdvanceBlock / kWave) {
         const double *p = partials + ((int64_t)k * (d + 1) + c) * grid;
         double s = 0.0;
         for (int b = lane; b < grid; b += kWave) s += p[b];
@@ -440,21 +473,23 @@ __global__ __launch_bounds__(kWave) void k_batch_store(int which, int64_t d, con
 }
 
 // ------------------------------------------------------------------ kernel choice
-using PassFn = void (*)(int64_t, int64_t, const double *, const int8_t *, int, const BatchCtl *, const uint64_t *,
+using PassFn = void (*)(int64_t, int64_t, const double *, const int8_t *, const BatchCtl *, const uint64_t *,
                         const uint64_t *, uint64_t *, double *, int64_t, double *);
 
+struct PassPair { PassFn fn[2]; };   // by loss
+
 template <int E, int L, int KT>
-PassFn pass_for(bool vec)
+PassPair pass_for(bool vec)
 {
     constexpr int U = pick_U(E, L);
     if constexpr (E % 2 == 0) {
-        if (vec) return k_batch_pass<E, L, U, true, KT>;
+        if (vec) return {{k_batch_pass<E, L, U, true, KT, TRON_LOSS_LR>, k_batch_pass<E, L, U, true, KT, TRON_LOSS_L2SVM>}};
     }
-    return k_batch_pass<E, L, U, false, KT>;
+    return {{k_batch_pass<E, L, U, false, KT, TRON_LOSS_LR>, k_batch_pass<E, L, U, false, KT, TRON_LOSS_L2SVM>}};
 }
 
 template <int KT>
-PassFn pass_for_shape(const Shape &s, bool vec)
+PassPair pass_for_shape(const Shape &s, bool vec)
 {
     switch (s.L * 16 + s.E) {
     case 16 + 1: return pass_for<1, 1, KT>(vec);
@@ -473,7 +508,7 @@ PassFn pass_for_shape(const Shape &s, bool vec)
     case 64 + 6: return pass_for<6, 4, KT>(vec);
     case 64 + 7: return pass_for<7, 4, KT>(vec);
     case 64 + 8: return pass_for<8, 4, KT>(vec);
-    default: return nullptr;
+    default: return {{nullptr, nullptr}};
     }
 }
 
@@ -496,7 +531,7 @@ struct tron_batch {
     int trace_cap = 0;
     double *partials = nullptr;           // K x (d+1) x grid
     int grid = 0;
-    tron::PassFn pass = nullptr;
+    tron::PassPair pass{{nullptr, nullptr}};
     int D_loss = -1;                      // loss whose D the buffers hold (-1: none)
 };
 
@@ -514,8 +549,8 @@ int launch_pass(tron_batch *b, int loss)
     const uint64_t *member = b->member, *Din = b->Dbits;
     uint64_t *Dout = b->Dbits;
     double *Dval = b->Dval, *partials = b->partials;
-    void *args[] = {&n, &d, &X, &y, &loss, &ctl, &member, &Din, &Dout, &Dval, &ntiles, &partials};
-    TRON_HIP(hipLaunchKernel(reinterpret_cast<const void *>(b->pass), dim3(b->grid), dim3(kBlock), args, 0, ds->stream));
+    void *args[] = {&n, &d, &X, &y, &ctl, &member, &Din, &Dout, &Dval, &ntiles, &partials};
+    TRON_HIP(hipLaunchKernel(reinterpret_cast<const void *>(b->pass.fn[loss == TRON_LOSS_L2SVM ? 1 : 0]), dim3(b->grid), dim3(kBlock), args, 0, ds->stream));
     return TRON_OK;
 }
 
@@ -523,7 +558,7 @@ int launch_advance(tron_batch *b, const SolveParams &P)
 {
     tron_dataset *ds = b->ds;
     ProfScope ps(ds, SLOT_BATCH_ADVANCE);
-    hipLaunchKernelGGL(k_batch_advance, dim3(b->K), dim3(kBlock), 0, ds->stream, ds->d, b->grid, b->partials, b->ctl, b->st, P,
+    hipLaunchKernelGGL(k_batch_advance, dim3(b->K), dim3(kAdvanceBlock), 0, ds->stream, ds->d, b->grid, b->partials, b->ctl, b->st, P,
                        P.trace_cap > 0 ? b->trace : nullptr);
     TRON_HIP(hipGetLastError());
     return TRON_OK;
@@ -541,8 +576,12 @@ int launch_begin(tron_batch *b, int what, const double *IN, const double *C_host
 
 int ensure_D(tron_batch *b, int loss)
 {
-    if (loss == TRON_LOSS_LR && !b->Dval)
-        TRON_HIP(hipMalloc(reinterpret_cast<void **>(&b->Dval), sizeof(double) * 2 * (size_t)b->K * (size_t)b->ds->n));
+    if (loss == TRON_LOSS_LR && !b->Dval) {
+        // zero once: a pass only ever writes D of a problem's own rows, the others stay zero
+        const size_t bytes = sizeof(double) * 2 * (size_t)b->K * (size_t)b->ds->n;
+        TRON_HIP(hipMalloc(reinterpret_cast<void **>(&b->Dval), bytes));
+        TRON_HIP(hipMemsetAsync(b->Dval, 0, bytes, b->ds->stream));
+    }
     return TRON_OK;
 }
 
@@ -615,10 +654,12 @@ extern "C" int tron_batch_create(tron_dataset *ds, int K, const uint32_t *member
     b->pass = (b->KT == 4) ? pass_for_shape<4>(s, vec) : pass_for_shape<8>(s, vec);
     auto fail = [&](int rc) { tron_batch_destroy(b); return rc; };
 #define TRON_B(expr) do { hipError_t e__ = (expr); if (e__ != hipSuccess) return fail(hip_fail(e__, #expr, __FILE__, __LINE__)); } while (0)
-    if (!b->pass) { set_error("tron_batch_create: internal: no kernel for E=%d L=%d", s.E, s.L); return fail(TRON_EINVAL); }
+    if (!b->pass.fn[0]) { set_error("tron_batch_create: internal: no kernel for E=%d L=%d", s.E, s.L); return fail(TRON_EINVAL); }
     // resident workgroups of the pass: all of them hold their accumulators for the whole pass
-    int per_cu = 0, cus = 0;
-    TRON_B(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(b->pass), kBlock, 0));
+    int per_cu = 0, per_cu_lr = 0, cus = 0;
+    TRON_B(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(b->pass.fn[1]), kBlock, 0));
+    TRON_B(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_lr, reinterpret_cast<const void *>(b->pass.fn[0]), kBlock, 0));
+    if (per_cu_lr > per_cu) per_cu = per_cu_lr;
     TRON_B(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, ds->device));
     int64_t grid = (int64_t)cus * (per_cu < 1 ? 1 : per_cu);
     if (g_tuning.batch_grid > 0) grid = g_tuning.batch_grid;
