@@ -381,6 +381,110 @@ def active_set_sweep() -> dict:
     return {"n": n, "d": d, "points": points}
 
 
+def cross_validation(X, y, label: str, folds: int = 3, Cs=(0.1, 1.0), eps: float = 0.01, reps: int = 3) -> dict:
+    """Cross-validation folds over one resident matrix (Section 2.1 of the paper): problem (fold f, C) trains the L2-SVM
+    on the rows outside fold f.  Batched: every problem advances on the same pass over X (tron_batch_solve).  One at a
+    time: the same problems solved one after the other by tron_solve, each on its own compacted copy of its rows (what
+    the paper does for X_I, Section 5).  X, y: CUDA tensors."""
+    import torch
+    import datagen as dg
+    import paper_2008_03433_amd as tron
+    n, d = X.shape
+    K = folds * len(Cs)
+    u = torch.from_numpy(dg.uniforms(200803433, 77, n)).cuda()
+    fold = torch.clamp((u * folds).to(torch.int32), max=folds - 1)
+    C_list = [float(c) for c in Cs for _ in range(folds)]
+    member = torch.zeros(n, dtype=torch.int32, device="cuda")
+    for k in range(K):
+        member |= (fold != (k % folds)).to(torch.int32) << k
+    ds = tron.Dataset(tron.tron_dataset_create_dense(n, d, X, y))
+    b = tron.Batch(ds, K, member)
+    best, res = float("inf"), None
+    for _ in range(reps):
+        W = torch.zeros((K, d), dtype=torch.float64, device="cuda")
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        res = b.solve(dg.LOSS_L2SVM, C_list, eps, W)
+        best = min(best, time.perf_counter() - t0)
+    rounds = max(r.n_fun + r.n_hv for r in res)
+    # one round at the final iterates, by kernel
+    V = torch.randn((K, d), dtype=torch.float64, device="cuda")
+    HV = torch.empty_like(V)
+    tron.tron_profile_enable(ds.handle, True)
+    for _ in range(10):
+        b.hv(C_list, V, HV, want_vHv=False)
+    prof_hv = tron.tron_profile_read(ds.handle)
+    for _ in range(5):
+        b.fun_grad(dg.LOSS_L2SVM, C_list, W, None)
+    prof_fg = tron.tron_profile_read(ds.handle)
+    tron.tron_profile_enable(ds.handle, False)
+    hv_pass_ms = prof_hv["batch_pass"]["ms"] / prof_hv["batch_pass"]["calls"]
+    fg_pass_ms = prof_fg["batch_pass"]["ms"] / prof_fg["batch_pass"]["calls"]
+    advance_ms = prof_hv["batch_advance"]["ms"] / prof_hv["batch_advance"]["calls"]
+    batch_f = [r.f for r in res]
+    b.close()
+    ds.close()
+    # one problem at a time on compacted copies
+    seq_solve, seq_hv, seq_f, seq_hv_count = 0.0, 0.0, [], 0
+    for f in range(folds):
+        keep = fold != f
+        sub = tron.Dataset(tron.tron_dataset_create_dense(int(keep.sum()), d, X[keep].contiguous(), y[keep].contiguous()))
+        for c in Cs:
+            t_best, r1 = float("inf"), None
+            for _ in range(reps):
+                w = torch.zeros(d, dtype=torch.float64, device="cuda")
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                r1 = sub.solve(dg.LOSS_L2SVM, float(c), eps, w)
+                t_best = min(t_best, time.perf_counter() - t0)
+            seq_solve += t_best
+            seq_f.append((list(Cs).index(c) * folds + f, r1.f))
+            seq_hv_count += r1.n_hv
+            v, hv = V[0].contiguous(), torch.empty(d, dtype=torch.float64, device="cuda")
+            for _ in range(3):
+                sub.hv(float(c), v, hv, want_vHv=False)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(10):
+                sub.hv(float(c), v, hv, want_vHv=False)
+            torch.cuda.synchronize()
+            seq_hv += (time.perf_counter() - t0) / 10
+        sub.close()
+        del sub
+        torch.cuda.empty_cache()
+    agree = max(abs(batch_f[k] - fk) / abs(fk) for k, fk in seq_f)
+    return {"workload": label, "n": n, "d": d, "folds": folds, "C": list(Cs), "problems": K, "loss": "l2svm", "eps": eps,
+            "batched": {"solve_ms": best * 1e3, "rounds": rounds, "hv_pass_ms": hv_pass_ms, "fun_grad_pass_ms": fg_pass_ms,
+                        "advance_ms": advance_ms, "hv_per_second_all_problems": K / ((hv_pass_ms + advance_ms) * 1e-3),
+                        "X_read_GB/s": 8.0 * n * d / (hv_pass_ms * 1e-3) / 1e9,
+                        "outer_iters": [r.outer_iters for r in res], "cg_iters": [r.cg_iters_total for r in res],
+                        "converged": all(r.converged for r in res)},
+            "one_at_a_time": {"solve_ms_total": seq_solve * 1e3, "hv_ms_total": seq_hv * 1e3, "cg_iters_total": seq_hv_count,
+                              "note": "tron_solve / tron_hv on a compacted copy of each problem's rows, one after the other"},
+            "speedup_solve": seq_solve / best, "speedup_hv_round": seq_hv * 1e3 / (hv_pass_ms + advance_ms),
+            "max_rel_diff_f": agree}
+
+
+def cross_validation_configs(which: str = "all") -> dict:
+    import torch
+    import datagen as dg
+    out = {}
+    if which in ("all", "c4"):
+        p4 = dg.config4()
+        out["c4_shape"] = cross_validation(torch.from_numpy(p4.X).cuda(), torch.from_numpy(p4.y).cuda(), p4.name)
+    if which == "c4":
+        return out
+    n, d = 20_000_000, 24
+    p = dg.config5(n=n, d=d)
+    X = torch.empty((n, d), dtype=torch.float64, device="cuda")
+    y = torch.empty(n, dtype=torch.float64, device="cuda")
+    for row0, Xc, yc in p.chunks():
+        X[row0:row0 + Xc.shape[0]] = torch.from_numpy(Xc).cuda()
+        y[row0:row0 + Xc.shape[0]] = torch.from_numpy(yc).cuda()
+    out["20M_x_24"] = cross_validation(X, y, f"config-5 generator, {n} x {d}", reps=2)
+    return out
+
+
 def stream_probe() -> dict:
     """Attainable streaming rates on this device (also the known-size kernels the byte counters are scaled with)."""
     import torch
@@ -406,6 +510,8 @@ def main() -> int:
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only; reported)")
     ap.add_argument("--hv-reps", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only-cv", nargs="?", const="all", default=None, choices=["all", "c4", "20M"],
+                    help="run the cross-validation (multi-problem) measurements only (optionally one of the two sizes)")
     ap.add_argument("--tune", action="append", default=[], metavar="KNOB=VALUE", help="library tuning knob (see tron_tuning_set)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -425,6 +531,9 @@ def main() -> int:
         k, v_ = kv.split("=")
         tron.tron_tuning_set(k, int(v_))
 
+    if args.only_cv:
+        print(json.dumps({"cross_validation": cross_validation_configs(args.only_cv), "stream_probe": stream_probe()}), flush=True)
+        return 0
     out = run_workload(args, args.workload)
     out["stream_probe"] = stream_probe()
     also = args.also if args.also is not None else ("c5" if args.workload == "c3" and args.scale == 1.0 else "none")
@@ -438,6 +547,7 @@ def main() -> int:
         quiet = argparse.Namespace(**{**vars(args), "no_cpu_baseline": True})
         out["mixes"] = {w: small_config(quiet, w) for w in ("susy_shape", "higgs_shape", "c3_svm")}
         out["active_set"] = active_set_sweep()
+        out["cross_validation"] = cross_validation_configs()
     print(json.dumps(out), flush=True)
     return 0
 
