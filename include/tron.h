@@ -101,6 +101,7 @@ TRON_API int tron_dataset_shape(const tron_dataset *ds, int64_t *n, int64_t *d, 
  *   "bwd_tile_nnz", "bwd_tile_rows", "bwd_tiles"  nonzeros, features and tiles of the hot-row tiles
  *   "fwd_lds_columns"          columns served from LDS tables in the forward pass
  *   "dense_grid"               workgroups of the dense kernels
+ *   "unit_values"              1 when the sparse layouts keep no values (every instance's entries share one value)
  * Unknown names return TRON_EINVAL.
  */
 TRON_API int tron_dataset_stat(const tron_dataset *ds, const char *name, int64_t *value);
@@ -278,8 +279,10 @@ TRON_API int tron_probe_read_bandwidth(const double *src_dev, int64_t count, int
  *   "csr_head" (0/1): a head partition for the most frequent columns of the whole matrix (needs csr_hot);
  *   "csr_range_slots" (2..4096): LDS table entries per column range;
  *   "csr_tiles" (0/1): hot-row tiles for the transposed product;
+ *   "csr_unit" (0/1): layouts without a value stream when every instance's entries share one value;
  *   "csr_hot_blocks_per_part", "csr_range_blocks_per_part", "csr_blocks_per_part",
  *   "csr_tile_blocks_per_slice": persistent workgroups of the head, table, table-less and tile kernels.
+ * "batch_grid" (0..4096): workgroups of the multi-problem pass (0 = as many as are resident at once).
  * Unknown names or values return TRON_EINVAL.
  */
 TRON_API int tron_tuning_set(const char *name, int64_t value);

@@ -166,7 +166,7 @@ void tron_dataset_destroy(tron_dataset *ds)
     ds->fwd.release();
     ds->bwd.release();
     hipFree(ds->y); hipFree(ds->y8); hipFree(ds->z); hipFree(ds->zhat); hipFree(ds->Dbuf[0]); hipFree(ds->Dbuf[1]);
-    hipFree(ds->partials); hipFree(ds->row_partials); hipFree(ds->scal_dev);
+    hipFree(ds->partials); hipFree(ds->row_partials); hipFree(ds->scal_dev); hipFree(ds->unit_scale);
     if (ds->scal_host) hipHostFree(ds->scal_host);
     for (double *p : ds->sv) hipFree(p);
     ds->prof.destroy();
@@ -215,12 +215,31 @@ int tron_dataset_create_csr(int64_t n, int64_t d, const int64_t *rowptr, const i
             t_rowptr[c + 1] += 1;
         }
     }
+    // Unit plans: when both layouts are partitioned and every instance's entries share one value r_i (binary features,
+    // optionally scaled per instance, e.g. normalised to unit length), X = diag(r) B with B binary: the layouts keep no
+    // values, the row sums of X are multiplied by r afterwards and X^T gathers from r .* (its vector).
+    const bool fwd_partitioned = g_tuning.csr_parts == kColParts ||
+                                 (g_tuning.csr_parts == 0 && d * (int64_t)sizeof(double) > (3 << 19) && nnz >= (1 << 22));
+    const bool bwd_partitioned = g_tuning.csr_parts == kColParts ||
+                                 (g_tuning.csr_parts == 0 && n * (int64_t)sizeof(double) > (3 << 19) && nnz >= (1 << 22));
+    bool unit = g_tuning.csr_unit != 0 && fwd_partitioned && bwd_partitioned;
+    std::vector<double> row_value;
+    if (unit) {
+        try {
+            row_value.assign((size_t)n, 1.0);
+        } catch (const std::bad_alloc &) { set_error("out of host memory"); return TRON_ENOMEM; }
+        for (int64_t i = 0; i < n && unit; ++i) {
+            const int64_t k0 = h_rowptr[i], k1 = h_rowptr[i + 1];
+            if (k1 > k0) row_value[i] = h_val[k0];
+            for (int64_t k = k0 + 1; k < k1; ++k)
+                if (h_val[k] != h_val[k0]) { unit = false; break; }
+        }
+    }
     // Hot-row tiles for the transposed product of large matrices: the features with the most entries (rank r by
     // count -> slice r % 8, slot r / 8) leave the transposed CSR copy and are stored as tiles instead.
     std::vector<int32_t> slot_code;
     int nhot = 0;
-    const bool partitioned = g_tuning.csr_parts == kColParts ||
-                             (g_tuning.csr_parts == 0 && n * (int64_t)sizeof(double) > (3 << 19) && nnz >= (1 << 22));
+    const bool partitioned = bwd_partitioned;
     if (g_tuning.csr_tiles && partitioned) {
         std::vector<std::pair<int64_t, int32_t>> cand;
         for (int64_t j = 0; j < d; ++j)
@@ -244,7 +263,7 @@ int tron_dataset_create_csr(int64_t n, int64_t d, const int64_t *rowptr, const i
     std::vector<int64_t> cursor;
     try {
         t_col.resize((size_t)t_nnz);
-        t_val.resize((size_t)t_nnz);
+        if (!unit) t_val.resize((size_t)t_nnz);
         cursor.assign(t_rowptr.begin(), t_rowptr.end() - 1);
     } catch (const std::bad_alloc &) { set_error("out of host memory building the transposed copy"); return TRON_ENOMEM; }
     for (int64_t i = 0; i < n; ++i)
@@ -252,16 +271,26 @@ int tron_dataset_create_csr(int64_t n, int64_t d, const int64_t *rowptr, const i
             if (nhot && slot_code[h_col[k]] >= 0) continue;
             const int64_t pos = cursor[h_col[k]]++;
             t_col[pos] = (int32_t)i;
-            t_val[pos] = h_val[k];
+            if (!unit) t_val[pos] = h_val[k];
         }
 
     tron_dataset *ds = new (std::nothrow) tron_dataset();
     if (!ds) { set_error("out of host memory"); return TRON_ENOMEM; }
     ds->n = n; ds->d = d; ds->dense = false; ds->stream = reinterpret_cast<hipStream_t>(hip_stream);
     int rc = alloc_common(ds);
-    if (rc >= 0) rc = csr_plan_build(ds->fwd, n, d, h_rowptr.data(), h_col.data(), h_val.data(), (int)g_tuning.csr_parts, g_tuning.csr_hot != 0, ds->stream);
-    if (rc >= 0) rc = csr_plan_build(ds->bwd, d, n, t_rowptr.data(), t_col.data(), t_val.data(), partitioned ? kColParts : 1, false, ds->stream);
+    if (rc >= 0) rc = csr_plan_build(ds->fwd, n, d, h_rowptr.data(), h_col.data(), unit ? nullptr : h_val.data(),
+                                     fwd_partitioned ? kColParts : 1, g_tuning.csr_hot != 0, unit, ds->stream);
+    if (rc >= 0) rc = csr_plan_build(ds->bwd, d, n, t_rowptr.data(), t_col.data(), unit ? nullptr : t_val.data(), partitioned ? kColParts : 1,
+                                     false, unit, ds->stream);
     if (rc >= 0 && nhot) rc = hot_tiles_build(ds->bwd, h_rowptr.data(), h_col.data(), h_val.data(), slot_code, nhot, ds->stream);
+    if (rc >= 0 && unit) {
+        hipError_t e = hipMalloc(reinterpret_cast<void **>(&ds->unit_scale), sizeof(double) * (size_t)n);
+        if (e == hipSuccess) e = hipMemcpyAsync(ds->unit_scale, row_value.data(), sizeof(double) * (size_t)n, hipMemcpyHostToDevice, ds->stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(ds->stream);
+        if (e != hipSuccess) rc = hip_fail(e, "copy the instances' values", __FILE__, __LINE__);
+        ds->fwd.row_scale = ds->unit_scale;
+        ds->bwd.col_scale = ds->unit_scale;
+    }
     if (rc >= 0) {
         int64_t need = 0;
         if (ds->fwd.P > 1) need = std::max<int64_t>(need, ds->fwd.nseg_total);   // one partial sum per segment
@@ -368,6 +397,7 @@ int tron_dataset_stat(const tron_dataset *ds, const char *name, int64_t *value)
         {"bwd_tiles", ds->dense ? 0 : ds->bwd.hot.ntiles_total},
         {"fwd_lds_columns", ds->dense ? 0 : [&] { int64_t t = 0; for (int x = 0; x < kMaxParts; ++x) t += ds->fwd.part_nhot[x]; return t; }()},
         {"dense_grid", ds->dense_grid},
+        {"unit_values", (!ds->dense && ds->fwd.unit) ? 1 : 0},
     };
     for (auto &e : tab)
         if (strcmp(e.k, name) == 0) { *value = e.v; return TRON_OK; }
@@ -482,6 +512,10 @@ int tron_tuning_set(const char *name, int64_t value)
     }
     if (name && strcmp(name, "csr_blocks_per_part") == 0 && value >= 1 && value <= 4096) {
         g_tuning.csr_blocks_per_part = value;
+        return TRON_OK;
+    }
+    if (name && strcmp(name, "csr_unit") == 0 && (value == 0 || value == 1)) {
+        g_tuning.csr_unit = value;
         return TRON_OK;
     }
     if (name && strcmp(name, "batch_grid") == 0 && value >= 0 && value <= 4096) {

@@ -38,6 +38,7 @@ struct Tuning {
     int64_t csr_blocks_per_part = 128;     // persistent workgroups per column range without LDS tables
     int64_t csr_tiles = 1;   // hot-row tiles for the transposed orientation of partitioned matrices (0 = off)
     int64_t csr_tile_blocks_per_slice = 96;  // persistent workgroups per slice of hot rows
+    int64_t csr_unit = 1;    // partitioned layouts: drop the value stream when every row of X holds one repeated value (0 = off)
     int64_t batch_grid = 0;  // workgroups of the multi-problem pass: 0 = as many as are resident at once
 };
 extern Tuning g_tuning;
@@ -124,7 +125,7 @@ struct HotTiles {
     int64_t tile0[kTileSlices] = {0};    // first tile of slice s
     int64_t ntiles[kTileSlices] = {0};
     int blocks_per_slice = 0;            // persistent workgroups per slice
-    double *val = nullptr;               // device, ntiles_total * kChunk (zero padded)
+    double *val = nullptr;               // device, ntiles_total * kChunk (zero padded); null for a unit plan
     uint16_t *iloc = nullptr;            // device, ntiles_total * kChunk: column minus the tile's first column
     uint8_t *flags = nullptr;            // device, ntiles_total * 256: bit e of byte t = entry 8t + e of the tile is the last of its segment
     int4 *hdr = nullptr;                 // device, per tile: {first column, segments, unused, index into seg_slot}
@@ -148,7 +149,14 @@ struct CsrPlan {
                                          //   (whole rows, every entry served from one LDS table, 16-bit slots in col16); else -1
     int32_t *col = nullptr;              // device, (padded) nnz of the ranges; with an LDS table, hot columns are stored as ~slot
     uint16_t *col16 = nullptr;           // device, (padded) nnz of the head partition: LDS slot of each entry
-    double *val = nullptr;               // device, (padded) nnz
+    double *val = nullptr;               // device, (padded) nnz; null for a unit plan
+    // Unit plan (partitioned layouts of a matrix X = diag(r) B with B binary, i.e. every instance's entries share one
+    // value r_i): the entries carry no values.  The plan of X multiplies row sum i by row_scale[i]; the plan of X^T
+    // gathers from the vector x .* col_scale (formed by the caller or by spmv_axpy itself into xs).
+    bool unit = false;
+    const double *row_scale = nullptr;   // device, rows (not owned) or null
+    const double *col_scale = nullptr;   // device, cols (not owned) or null
+    double *xs = nullptr;                // device, cols: work space for x .* col_scale
     int nblocks = 0;                     // total number of chunks
     double *carry = nullptr;             // device, nblocks: sum of the part of a row entering chunk c from before
     int nfix = 0;                        // number of (partition, split row) pairs
@@ -215,6 +223,8 @@ struct tron_dataset {
     int dense_grid = 0;          // workgroups of the dense kernels
     int vec_grid_n = 0, vec_grid_d = 0;  // workgroups of elementwise kernels over n / d
 
+    double *unit_scale = nullptr;  // sparse, unit plans: r (n), the value shared by the entries of instance i
+
     // solver vectors (d each), allocated on first tron_solve
     double *sv[9] = {nullptr};
 
@@ -251,8 +261,9 @@ int probe_copy(double *dst, const double *src, int64_t count, int reps, hipStrea
 
 // ---- kernels_csr.hip
 // parts: 1 = plain CSR, 0 = choose from the size of the gathered vector
+// unit: build a unit plan (see CsrPlan::unit; partitioned layouts only; h_val is not read)
 int csr_plan_build(CsrPlan &P, int64_t rows, int64_t cols, const int64_t *h_rowptr, const int32_t *h_col,
-                   const double *h_val, int parts, bool hot, hipStream_t st);
+                   const double *h_val, int parts, bool hot, bool unit, hipStream_t st);
 // Hot-row tiles for plan A (rows x cols) from the *other* orientation's CSR (cols x rows: t_rowptr over A's columns,
 // t_col = A's row ids).  slot_code[row] = slice * kTileSlots + slot for hot rows, -1 otherwise.
 int hot_tiles_build(CsrPlan &A, const int64_t *t_rowptr, const int32_t *t_col, const double *t_val,
@@ -262,11 +273,15 @@ int hot_tiles_build(CsrPlan &A, const int64_t *t_rowptr, const int32_t *t_col, c
 //   spmv_scale: out = scale .* (A x)
 //   spmv_axpy:  out = add + alpha (A x); partial slot 0 = out . (dot_self ? out : add).  add == null: add 1.
 //               square: the entries of A are squared (transposed orientation only)
+//   post (spmv_loss: applied to zhat; spmv_scale: to out), when not null: the stored vector is multiplied by it
+//   elementwise -- the column scale of the unit plan that will gather from it (then passed with x_prescaled = true)
 // Each returns the number of first-stage partials in slot 0 (0 if none), or a negative error.
-int spmv_loss(tron_dataset *ds, const CsrPlan &A, int slot, int loss, const double *x, double *zwork, double *zhat, double *D);
-int spmv_scale(tron_dataset *ds, const CsrPlan &A, int slot, const double *x, const double *scale, double *out);
+int spmv_loss(tron_dataset *ds, const CsrPlan &A, int slot, int loss, const double *x, double *zwork, double *zhat, double *D,
+              const double *post = nullptr);
+int spmv_scale(tron_dataset *ds, const CsrPlan &A, int slot, const double *x, const double *scale, double *out,
+               const double *post = nullptr);
 int spmv_axpy(tron_dataset *ds, const CsrPlan &A, int slot, const double *x, const double *add, double alpha,
-              bool dot_self, double *out, bool square = false);
+              bool dot_self, double *out, bool square = false, bool x_prescaled = false);
 
 // ---- kernels_dense.hip
 bool dense_supported(int64_t d);

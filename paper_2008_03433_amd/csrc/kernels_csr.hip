@@ -48,7 +48,7 @@ void CsrPlan::release()
 {
     hot.release();
     hipFree(rowptr); hipFree(col); hipFree(col16); hipFree(val); hipFree(row_lo); hipFree(carry);
-    hipFree(hot_ids); hipFree(hot_x); hipFree(group_base); hipFree(chunk_tab); hipFree(flags); hipFree(row_mask);
+    hipFree(xs); hipFree(hot_ids); hipFree(hot_x); hipFree(group_base); hipFree(chunk_tab); hipFree(flags); hipFree(row_mask);
     hipFree(fix_row); hipFree(fix_part); hipFree(fix_b0); hipFree(fix_cnt);
     *this = CsrPlan();
 }
@@ -100,17 +100,19 @@ static void plan_chunks(const RP *rp, int64_t rows, int64_t nnz_x, int nchunks, 
 }
 
 int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowptr, const int32_t *h_col,
-                   const double *h_val, int parts, bool hot, hipStream_t st)
+                   const double *h_val, int parts, bool hot, bool unit, hipStream_t st)
 {
     A.rows = rows;
     A.cols = cols;
     A.nnz = h_rowptr[rows];
+    A.unit = unit;
     if (parts <= 0)
         parts = (cols * (int64_t)sizeof(double) > kGatherBytesForPartitioning && A.nnz >= kMinNnzForPartitioning) ? kColParts : 1;
     if (parts > kColParts) parts = kColParts;
     A.P = parts;
     std::vector<int32_t> row_lo, fix_row, fix_part, fix_b0, fix_cnt;
 
+    if (A.unit && A.P == 1) { set_error("internal: unit plan without partitions"); return TRON_EINVAL; }
     if (A.P == 1) {
         const int64_t nb64 = std::max<int64_t>(1, (A.nnz + kChunk - 1) / kChunk);
         if (nb64 > 0x7ffffff0) { set_error("matrix too large: %lld chunks", (long long)nb64); return TRON_EINVAL; }
@@ -219,7 +221,7 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
         if (nseg_total > 0x7ffffff0) { set_error("too many row segments for 32-bit indexing"); return TRON_EINVAL; }
         // entries partition-major; inside a row the entries of one range are contiguous and stay ordered
         std::vector<int32_t> pcol((size_t)pos, 0);
-        std::vector<double> pval((size_t)pos, 0.0);
+        std::vector<double> pval(A.unit ? 0 : (size_t)pos, 0.0);
         {
             std::vector<int64_t> cursor(NP);
             for (int64_t r = 0; r < rows; ++r) {
@@ -227,7 +229,7 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
                 for (int64_t k = h_rowptr[r]; k < h_rowptr[r + 1]; ++k) {
                     const int64_t q = cursor[part_of[h_col[k]]]++;
                     pcol[q] = (hot && slot_of[h_col[k]] >= 0) ? ~slot_of[h_col[k]] : h_col[k];   // the head's become 16-bit slots below
-                    pval[q] = h_val[k];
+                    if (!A.unit) pval[q] = h_val[k];
                 }
             }
         }
@@ -283,13 +285,16 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
             // the head partition is the last one: its columns go to col16, the ranges' stay in col
             const size_t h0 = (size_t)A.part_base[A.head];
             std::vector<uint16_t> c16(pcol.size() - h0, 0);
-            for (size_t k = h0; k < pcol.size(); ++k) c16[k - h0] = (uint16_t)(pcol[k] < 0 ? ~pcol[k] : 0);   // padding: slot 0, value 0
+            // padding: slot 0 (value 0; in a unit plan the padding lies behind the last flagged entry of the partition, and
+            // what follows the last flag of a chunk never reaches a sum)
+            for (size_t k = h0; k < pcol.size(); ++k) c16[k - h0] = (uint16_t)(pcol[k] < 0 ? ~pcol[k] : 0);
             TRON_TRY(upload(&A.col16, c16.data(), c16.size(), st));
             TRON_HIP(hipStreamSynchronize(st));
             pcol.resize(h0);
         }
         TRON_TRY(upload(&A.col, pcol.data(), pcol.size(), st));
-        TRON_TRY(upload(&A.val, pval.data(), pval.size(), st));
+        if (!A.unit) TRON_TRY(upload(&A.val, pval.data(), pval.size(), st));
+        else TRON_HIP(hipMalloc(reinterpret_cast<void **>(&A.xs), sizeof(double) * (size_t)(cols + 1)));
         // group_base[G].first[x] = first segment of partition x whose row is >= 64 G (see sum_parts)
         A.ngroups = (rows + kWave - 1) / kWave;
         A.nseg_total = nseg_total;
@@ -481,7 +486,8 @@ struct StreamRegs<true> {
     v2d v[4];
 };
 
-template <bool HEAD>
+// UNIT: the entries carry no values (see CsrPlan::unit); v stays unset and unused
+template <bool HEAD, bool UNIT>
 __device__ __forceinline__ StreamRegs<HEAD> load_stream(const void *__restrict__ col, const double *__restrict__ val, int64_t start)
 {
     StreamRegs<HEAD> s;
@@ -492,7 +498,7 @@ __device__ __forceinline__ StreamRegs<HEAD> load_stream(const void *__restrict__
             s.c[m] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(static_cast<const uint16_t *>(col) + k));
         else
             s.c[m] = __builtin_nontemporal_load(reinterpret_cast<const v2i *>(static_cast<const int32_t *>(col) + k));
-        s.v[m] = __builtin_nontemporal_load(reinterpret_cast<const v2d *>(val + k));
+        if constexpr (!UNIT) s.v[m] = __builtin_nontemporal_load(reinterpret_cast<const v2d *>(val + k));
     }
     return s;
 }
@@ -526,7 +532,7 @@ constexpr int kSegPasses = kChunk / kBlock;     // a chunk holds at most kChunk 
 __device__ __forceinline__ int prod_pos(int e) { return e + 2 * (e >> 3); }
 
 // products of the chunk in `r` into LDS
-template <bool HOT, bool HEAD, bool SQ>
+template <bool HOT, bool HEAD, bool SQ, bool UNIT>
 __device__ __forceinline__ void products_to_lds(const StreamRegs<HEAD> &r, const double *__restrict__ x, const double *table, double *prod)
 {
     double xg[4][2];
@@ -535,8 +541,13 @@ __device__ __forceinline__ void products_to_lds(const StreamRegs<HEAD> &r, const
 #pragma unroll
     for (int m = 0; m < 4; ++m) {
         double2 p;
-        p.x = (SQ ? r.v[m].x * r.v[m].x : r.v[m].x) * xg[m][0];
-        p.y = (SQ ? r.v[m].y * r.v[m].y : r.v[m].y) * xg[m][1];
+        if constexpr (UNIT) {
+            p.x = xg[m][0];
+            p.y = xg[m][1];
+        } else {
+            p.x = (SQ ? r.v[m].x * r.v[m].x : r.v[m].x) * xg[m][0];
+            p.y = (SQ ? r.v[m].y * r.v[m].y : r.v[m].y) * xg[m][1];
+        }
         *reinterpret_cast<double2 *>(prod + prod_pos(m * kQuarter + threadIdx.x * 2)) = p;   // an even entry: the pair stays together
     }
 }
@@ -660,7 +671,7 @@ struct PartPtrs {   // device arrays of one partitioned plan (or of its head par
 // ids this thread will write -- is fetched into registers while the current chunk is being reduced, so HBM latency
 // is paid once per workgroup, not once per chunk.
 // SQ: the values are squared (sum_i x_ij^2 a_i, for the diagonal of the Hessian)
-template <bool HOT, bool HEAD, bool SQ>
+template <bool HOT, bool HEAD, bool SQ, bool UNIT>
 __device__ __forceinline__ void part_body(double *prod, double *table, const PartArgs &pa, const int xp, const int q, const int Q,
                                           const int64_t rows, const PartPtrs &pp, const double *__restrict__ x)
 {
@@ -676,7 +687,7 @@ __device__ __forceinline__ void part_body(double *prod, double *table, const Par
     // col/val are padded to whole chunks (zeros)
     const void *col = HEAD ? static_cast<const void *>(static_cast<const uint16_t *>(pp.col) + pa.base[xp])
                            : static_cast<const void *>(static_cast<const int32_t *>(pp.col) + pa.base[xp]);
-    const double *val = pp.val + pa.base[xp];
+    const double *val = UNIT ? nullptr : pp.val + pa.base[xp];
     const int4 *__restrict__ tabs = pp.chunk_tab + pa.chunk0[xp];
     const uint8_t *__restrict__ flags = pp.flags + (int64_t)pa.chunk0[xp] * kBlock;
     double *partial = pp.partial + pa.seg0[xp];
@@ -685,18 +696,18 @@ __device__ __forceinline__ void part_body(double *prod, double *table, const Par
     int c = q;
     int4 tab = load_uniform(tabs + c);
     int4 tab_n = load_uniform(tabs + ((c + Q < nchunks) ? c + Q : c));
-    StreamRegs<HEAD> cur = load_stream<HEAD>(col, val, (int64_t)c * kChunk);
+    StreamRegs<HEAD> cur = load_stream<HEAD, UNIT>(col, val, (int64_t)c * kChunk);
     unsigned fl = load_flags(flags + (int64_t)c * kBlock);
 
     for (; c < nchunks; c += Q) {
-        products_to_lds<HOT, HEAD, SQ>(cur, x, table, prod);
+        products_to_lds<HOT, HEAD, SQ, UNIT>(cur, x, table, prod);
         // Only now fetch the next chunk (clamped index: always the same loads): nothing below waits for these
         // registers, so they stay in flight during the segment sums and are waited for at the top of the next
         // iteration.
         __builtin_amdgcn_sched_barrier(0);
         const int cn = (c + Q < nchunks) ? c + Q : c;
         const int cnn = (cn + Q < nchunks) ? cn + Q : cn;
-        const StreamRegs<HEAD> nxt = load_stream<HEAD>(col, val, (int64_t)cn * kChunk);
+        const StreamRegs<HEAD> nxt = load_stream<HEAD, UNIT>(col, val, (int64_t)cn * kChunk);
         const unsigned fl_n = load_flags(flags + (int64_t)cn * kBlock);
         const int4 tab_nn = load_uniform(tabs + cnn);
         __builtin_amdgcn_sched_barrier(0);
@@ -710,12 +721,12 @@ __device__ __forceinline__ void part_body(double *prod, double *table, const Par
     }
 }
 
-template <bool HOT, bool HEAD, bool SQ>
+template <bool HOT, bool HEAD, bool SQ, bool UNIT>
 __global__ __launch_bounds__(kBlock) void k_csr_spmv_part(PartArgs pa, int64_t rows, PartPtrs pp, const double *__restrict__ x)
 {
     __shared__ __align__(16) double prod[kProdDoubles];
     extern __shared__ __align__(16) double table[];   // pa.slots doubles (none without HOT)
-    part_body<HOT, HEAD, SQ>(prod, table, pa, blockIdx.x % pa.P, blockIdx.x / pa.P, gridDim.x / pa.P, rows, pp, x);
+    part_body<HOT, HEAD, SQ, UNIT>(prod, table, pa, blockIdx.x % pa.P, blockIdx.x / pa.P, gridDim.x / pa.P, rows, pp, x);
 }
 
 // ------------------------------------------------------------------ hot-row tiles (see HotTiles)
@@ -729,6 +740,7 @@ int hot_tiles_build(CsrPlan &A, const int64_t *t_rowptr, const int32_t *t_col, c
     struct Entry { uint16_t slot, iloc; double val; };
     std::vector<Entry> cur[kTileSlices];
     int64_t base[kTileSlices] = {0};
+    const bool unit = A.unit;
     std::vector<double> tval[kTileSlices];
     std::vector<uint16_t> tiloc[kTileSlices];
     std::vector<uint8_t> tflags[kTileSlices];
@@ -741,12 +753,12 @@ int hot_tiles_build(CsrPlan &A, const int64_t *t_rowptr, const int32_t *t_col, c
         // by slot; the entries of a slot keep their column order
         std::stable_sort(e.begin(), e.end(), [](const Entry &a, const Entry &b) { return a.slot < b.slot; });
         int4 h = make_int4((int)base[s], 0, 0, (int)sslot[s].size());
-        const size_t off = tval[s].size();
-        tval[s].resize(off + kChunk, 0.0);
+        const size_t off = tiloc[s].size();
+        if (!unit) tval[s].resize(off + kChunk, 0.0);
         tiloc[s].resize(off + kChunk, 0);
         tflags[s].resize((off + kChunk) / 8, 0);
         for (size_t k = 0; k < e.size(); ++k) {
-            tval[s][off + k] = e[k].val;
+            if (!unit) tval[s][off + k] = e[k].val;
             tiloc[s][off + k] = e[k].iloc;
             if (k + 1 == e.size() || e[k + 1].slot != e[k].slot) {
                 tflags[s][(off + k) / 8] |= (uint8_t)(1u << (k % 8));
@@ -774,7 +786,7 @@ int hot_tiles_build(CsrPlan &A, const int64_t *t_rowptr, const int32_t *t_col, c
         for (int64_t k = t_rowptr[i]; k < t_rowptr[i + 1]; ++k) {
             const int32_t code = slot_code[t_col[k]];
             if (code >= 0) H.nnz++;
-            if (code >= 0) cur[code / kTileSlots].push_back({(uint16_t)(code % kTileSlots), (uint16_t)(i - base[code / kTileSlots]), t_val[k]});
+            if (code >= 0) cur[code / kTileSlots].push_back({(uint16_t)(code % kTileSlots), (uint16_t)(i - base[code / kTileSlots]), unit ? 1.0 : t_val[k]});
         }
     }
     for (int s = 0; s < kTileSlices; ++s) close_tile(s);
@@ -791,7 +803,7 @@ int hot_tiles_build(CsrPlan &A, const int64_t *t_rowptr, const int32_t *t_col, c
     H.ntiles_total = ntiles;
     if (ntiles == 0) return TRON_OK;
     if (nseg > 0x7ffffff0 || ntiles > 0x7ffffff0 / kChunk * 1024) { set_error("hot tiles too large"); return TRON_EINVAL; }
-    TRON_HIP(hipMalloc(reinterpret_cast<void **>(&H.val), sizeof(double) * ntiles * kChunk));
+    if (!unit) TRON_HIP(hipMalloc(reinterpret_cast<void **>(&H.val), sizeof(double) * ntiles * kChunk));
     TRON_HIP(hipMalloc(reinterpret_cast<void **>(&H.iloc), sizeof(uint16_t) * ntiles * kChunk));
     TRON_HIP(hipMalloc(reinterpret_cast<void **>(&H.flags), ntiles * kBlock));
     TRON_HIP(hipMalloc(reinterpret_cast<void **>(&H.hdr), sizeof(int4) * ntiles));
@@ -800,7 +812,7 @@ int hot_tiles_build(CsrPlan &A, const int64_t *t_rowptr, const int32_t *t_col, c
     for (int s = 0; s < kTileSlices; ++s) {
         const int64_t t0 = H.tile0[s];
         if (H.ntiles[s] == 0) continue;
-        TRON_HIP(hipMemcpyAsync(H.val + t0 * kChunk, tval[s].data(), sizeof(double) * tval[s].size(), hipMemcpyHostToDevice, st));
+        if (!unit) TRON_HIP(hipMemcpyAsync(H.val + t0 * kChunk, tval[s].data(), sizeof(double) * tval[s].size(), hipMemcpyHostToDevice, st));
         TRON_HIP(hipMemcpyAsync(H.iloc + t0 * kChunk, tiloc[s].data(), sizeof(uint16_t) * tiloc[s].size(), hipMemcpyHostToDevice, st));
         TRON_HIP(hipMemcpyAsync(H.flags + t0 * kBlock, tflags[s].data(), tflags[s].size(), hipMemcpyHostToDevice, st));
         TRON_HIP(hipMemcpyAsync(H.hdr + t0, hdrs[s].data(), sizeof(int4) * hdrs[s].size(), hipMemcpyHostToDevice, st));
@@ -840,6 +852,7 @@ struct TilePtrs {
 };
 
 // data of tile T whose header h is already in registers
+template <bool UNIT>
 __device__ __forceinline__ TileRegs load_tile(const TilePtrs &tp, int4 h, int64_t T)
 {
     TileRegs r;
@@ -847,7 +860,7 @@ __device__ __forceinline__ TileRegs load_tile(const TilePtrs &tp, int4 h, int64_
 #pragma unroll
     for (int m = 0; m < 4; ++m) {
         const int64_t k = T * kChunk + m * kQuarter + threadIdx.x * 2;
-        r.v[m] = __builtin_nontemporal_load(reinterpret_cast<const v2d *>(tp.val + k));
+        if constexpr (!UNIT) r.v[m] = __builtin_nontemporal_load(reinterpret_cast<const v2d *>(tp.val + k));
         r.il[m] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(tp.iloc + k));
     }
     r.flags = tp.flags[T * kBlock + threadIdx.x];
@@ -862,7 +875,7 @@ __device__ __forceinline__ TileRegs load_tile(const TilePtrs &tp, int4 h, int64_
 // Software pipeline: while tile t is reduced, the data of tiles t + B and t + 2B and the header of tile t + 3B are
 // in flight (all indices clamped to the last tile, so every iteration issues the same loads).
 // Slots inside a tile are distinct, so the accumulator updates of different segments never collide.
-template <bool SQ>
+template <bool SQ, bool UNIT>
 __device__ __forceinline__ void tiles_body(double *prod, uint16_t *slots, double *acc, const TileArgs &ta, const int s, const int q,
                                            const int B, const TilePtrs &tp, const double *__restrict__ x)
 {
@@ -873,8 +886,8 @@ __device__ __forceinline__ void tiles_body(double *prod, uint16_t *slots, double
         const int64_t T0 = ta.tile0[s];
         const int64_t last = nt - 1;
         auto clampt = [&](int64_t t) { return T0 + (t < last ? t : last); };
-        TileRegs cur = load_tile(tp, load_uniform(tp.hdr + clampt(q)), clampt(q));
-        TileRegs nxt = load_tile(tp, load_uniform(tp.hdr + clampt(q + B)), clampt(q + B));
+        TileRegs cur = load_tile<UNIT>(tp, load_uniform(tp.hdr + clampt(q)), clampt(q));
+        TileRegs nxt = load_tile<UNIT>(tp, load_uniform(tp.hdr + clampt(q + B)), clampt(q + B));
         int4 hdr2 = load_uniform(tp.hdr + clampt(q + 2 * (int64_t)B));
         for (int64_t t = q; t < nt; t += B) {
             const int nseg = cur.hdr.y;
@@ -889,12 +902,17 @@ __device__ __forceinline__ void tiles_body(double *prod, uint16_t *slots, double
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
                 double2 p;
-                p.x = (SQ ? cur.v[m].x * cur.v[m].x : cur.v[m].x) * xg[m][0];
-                p.y = (SQ ? cur.v[m].y * cur.v[m].y : cur.v[m].y) * xg[m][1];
+                if constexpr (UNIT) {
+                    p.x = xg[m][0];
+                    p.y = xg[m][1];
+                } else {
+                    p.x = (SQ ? cur.v[m].x * cur.v[m].x : cur.v[m].x) * xg[m][0];
+                    p.y = (SQ ? cur.v[m].y * cur.v[m].y : cur.v[m].y) * xg[m][1];
+                }
                 *reinterpret_cast<double2 *>(prod + prod_pos(m * kQuarter + tid * 2)) = p;
             }
             __builtin_amdgcn_sched_barrier(0);
-            const TileRegs nn = load_tile(tp, hdr2, clampt(t + 2 * (int64_t)B));
+            const TileRegs nn = load_tile<UNIT>(tp, hdr2, clampt(t + 2 * (int64_t)B));
             const int4 hdr3 = load_uniform(tp.hdr + clampt(t + 3 * (int64_t)B));
             __builtin_amdgcn_sched_barrier(0);
             __syncthreads();
@@ -925,13 +943,13 @@ __device__ __forceinline__ void tiles_body(double *prod, uint16_t *slots, double
     for (int k = tid; k < kTileSlots; k += kBlock) out[k] = acc[k];
 }
 
-template <bool SQ>
+template <bool SQ, bool UNIT>
 __global__ __launch_bounds__(kBlock) void k_hot_tiles(TileArgs ta, int B, TilePtrs tp, const double *__restrict__ x)
 {
     __shared__ __align__(16) double prod[kProdDoubles];
     __shared__ __align__(16) uint16_t slots[kChunk];
     __shared__ double acc[kTileSlots];
-    tiles_body<SQ>(prod, slots, acc, ta, blockIdx.x % kTileSlices, blockIdx.x / kTileSlices, B, tp, x);
+    tiles_body<SQ, UNIT>(prod, slots, acc, ta, blockIdx.x % kTileSlices, blockIdx.x / kTileSlices, B, tp, x);
 }
 
 // sums[s*K + k] = sum over the B workgroups of slice s: four quarter sums (workgroup order inside each), added in
@@ -973,11 +991,14 @@ static int launch_hot_tiles(tron_dataset *ds, const CsrPlan &A, const double *x,
     hipStream_t st = ds->stream;
     {
         ProfScope ps(ds, SLOT_SPMV_TILES, st);
-        if (square)
-            hipLaunchKernelGGL(k_hot_tiles<true>, dim3(kTileSlices * H.blocks_per_slice), dim3(kBlock), 0, st, tile_args(H),
+        if (A.unit)   // squares, if any, are in the scaled vector
+            hipLaunchKernelGGL((k_hot_tiles<false, true>), dim3(kTileSlices * H.blocks_per_slice), dim3(kBlock), 0, st, tile_args(H),
+                               H.blocks_per_slice, tile_ptrs(H), x);
+        else if (square)
+            hipLaunchKernelGGL((k_hot_tiles<true, false>), dim3(kTileSlices * H.blocks_per_slice), dim3(kBlock), 0, st, tile_args(H),
                                H.blocks_per_slice, tile_ptrs(H), x);
         else
-            hipLaunchKernelGGL(k_hot_tiles<false>, dim3(kTileSlices * H.blocks_per_slice), dim3(kBlock), 0, st, tile_args(H),
+            hipLaunchKernelGGL((k_hot_tiles<false, false>), dim3(kTileSlices * H.blocks_per_slice), dim3(kBlock), 0, st, tile_args(H),
                                H.blocks_per_slice, tile_ptrs(H), x);
         TRON_HIP(hipGetLastError());
     }
@@ -1043,6 +1064,7 @@ struct PartialRef {
     const double *partial;
     const uint16_t *mask;
     const GroupBase *group_base;   // one record per group of 64 rows
+    const double *row_scale;       // unit plan of X: the value of row i's entries (null otherwise)
 };
 
 struct HotRef {
@@ -1071,6 +1093,7 @@ __device__ __forceinline__ double sum_parts(const PartialRef &P, int64_t G, int6
     }
 #pragma unroll
     for (int x = 0; x < kMaxParts; ++x) s += v[x];
+    if (P.row_scale && valid) s *= P.row_scale[r];
     return s;
 }
 
@@ -1083,7 +1106,8 @@ __device__ __forceinline__ double sum_parts(const PartialRef &P, int64_t G, int6
 // z = sum of partials; loss terms; partial slot 0 = sum loss
 template <int LOSS>
 __global__ __launch_bounds__(kBlock) void k_combine_loss(int64_t n, PartialRef P, const double *__restrict__ y,
-                                                         double *__restrict__ zhat, double *__restrict__ D, double *__restrict__ red)
+                                                         double *__restrict__ zhat, double *__restrict__ D, double *__restrict__ red,
+                                                         const double *__restrict__ post)
 {
     __shared__ double lds[kWavesPerBlock];
     double acc = 0.0;
@@ -1092,7 +1116,7 @@ __global__ __launch_bounds__(kBlock) void k_combine_loss(int64_t n, PartialRef P
         if (valid) {
             double a, zh, Di;
             loss_terms_dev<LOSS>(z, y[i], a, zh, Di);
-            zhat[i] = zh;
+            zhat[i] = post ? post[i] * zh : zh;
             D[i] = Di;
             acc += a;
         }
@@ -1103,11 +1127,14 @@ __global__ __launch_bounds__(kBlock) void k_combine_loss(int64_t n, PartialRef P
 
 // out = scale .* sum of partials
 __global__ __launch_bounds__(kBlock) void k_combine_scale(int64_t rows, PartialRef P, const double *__restrict__ scale,
-                                                          double *__restrict__ out)
+                                                          double *__restrict__ out, const double *__restrict__ post)
 {
     TRON_FOR_ROW_GROUPS(rows, G, i, valid) {
         const double s = sum_parts(P, G, i, valid);
-        if (valid) out[i] = scale[i] * s;
+        if (valid) {
+            const double o = scale[i] * s;
+            out[i] = post ? post[i] * o : o;
+        }
     }
 }
 
@@ -1194,7 +1221,7 @@ static PartArgs head_args(const CsrPlan &A)
 
 static PartialRef partial_ref(const tron_dataset *ds, const CsrPlan &A)
 {
-    return PartialRef{ds->row_partials, A.row_mask, A.group_base};
+    return PartialRef{ds->row_partials, A.row_mask, A.group_base, A.row_scale};
 }
 
 static PartPtrs part_ptrs(const tron_dataset *ds, const CsrPlan &A)
@@ -1205,7 +1232,7 @@ static PartPtrs part_ptrs(const tron_dataset *ds, const CsrPlan &A)
 static PartPtrs head_ptrs(const tron_dataset *ds, const CsrPlan &A)
 {
     const int h = A.head;
-    return PartPtrs{A.col16, A.val + A.part_base[h], A.chunk_tab, A.flags, A.hot_x ? A.hot_x + (size_t)h * kHotSlots : nullptr,
+    return PartPtrs{A.col16, A.val ? A.val + A.part_base[h] : nullptr, A.chunk_tab, A.flags, A.hot_x ? A.hot_x + (size_t)h * kHotSlots : nullptr,
                     ds->row_partials, A.carry};
 }
 
@@ -1222,22 +1249,32 @@ static int launch_partials(tron_dataset *ds, const CsrPlan &A, int slot, const d
     if (A.head >= 0) {
         ProfScope ps(ds, SLOT_SPMV_HEAD);
         const int grid = std::max(1, std::min(A.part_nchunks[A.head], (int)g_tuning.csr_hot_blocks_per_part * kColParts));
-        hipLaunchKernelGGL((k_csr_spmv_part<true, true, false>), dim3(grid), dim3(kBlock), kHotSlots * sizeof(double), ds->stream,
-                           head_args(A), A.rows, head_ptrs(ds, A), x);
+        if (A.unit)
+            hipLaunchKernelGGL((k_csr_spmv_part<true, true, false, true>), dim3(grid), dim3(kBlock), kHotSlots * sizeof(double), ds->stream,
+                               head_args(A), A.rows, head_ptrs(ds, A), x);
+        else
+            hipLaunchKernelGGL((k_csr_spmv_part<true, true, false, false>), dim3(grid), dim3(kBlock), kHotSlots * sizeof(double), ds->stream,
+                               head_args(A), A.rows, head_ptrs(ds, A), x);
         TRON_HIP(hipGetLastError());
     }
     {
         ProfScope ps(ds, slot);
         const int want = (int)(A.hot_ids ? g_tuning.csr_range_blocks_per_part : g_tuning.csr_blocks_per_part);
         const int per_part = std::max(1, std::min(A.max_chunks, want));
-        if (A.hot_ids)
-            hipLaunchKernelGGL((k_csr_spmv_part<true, false, false>), dim3(per_part * A.P), dim3(kBlock), A.range_slots * sizeof(double), ds->stream,
+        if (A.hot_ids && A.unit)
+            hipLaunchKernelGGL((k_csr_spmv_part<true, false, false, true>), dim3(per_part * A.P), dim3(kBlock), A.range_slots * sizeof(double), ds->stream,
                                pa, A.rows, part_ptrs(ds, A), x);
+        else if (A.hot_ids)
+            hipLaunchKernelGGL((k_csr_spmv_part<true, false, false, false>), dim3(per_part * A.P), dim3(kBlock), A.range_slots * sizeof(double), ds->stream,
+                               pa, A.rows, part_ptrs(ds, A), x);
+        else if (A.unit)   // squares, if any, are in the scaled vector
+            hipLaunchKernelGGL((k_csr_spmv_part<false, false, false, true>), dim3(per_part * A.P), dim3(kBlock), 0, ds->stream, pa, A.rows,
+                               part_ptrs(ds, A), x);
         else if (square)
-            hipLaunchKernelGGL((k_csr_spmv_part<false, false, true>), dim3(per_part * A.P), dim3(kBlock), 0, ds->stream, pa, A.rows,
+            hipLaunchKernelGGL((k_csr_spmv_part<false, false, true, false>), dim3(per_part * A.P), dim3(kBlock), 0, ds->stream, pa, A.rows,
                                part_ptrs(ds, A), x);
         else
-            hipLaunchKernelGGL((k_csr_spmv_part<false, false, false>), dim3(per_part * A.P), dim3(kBlock), 0, ds->stream, pa, A.rows,
+            hipLaunchKernelGGL((k_csr_spmv_part<false, false, false, false>), dim3(per_part * A.P), dim3(kBlock), 0, ds->stream, pa, A.rows,
                                part_ptrs(ds, A), x);
         TRON_HIP(hipGetLastError());
     }
@@ -1245,9 +1282,11 @@ static int launch_partials(tron_dataset *ds, const CsrPlan &A, int slot, const d
     return TRON_OK;
 }
 
-int spmv_loss(tron_dataset *ds, const CsrPlan &A, int slot, int loss, const double *x, double *zwork, double *zhat, double *D)
+int spmv_loss(tron_dataset *ds, const CsrPlan &A, int slot, int loss, const double *x, double *zwork, double *zhat, double *D,
+              const double *post)
 {
     if (A.P == 1) {
+        if (post) { set_error("internal: post-scaling on an unpartitioned plan"); return TRON_EINVAL; }
         TRON_TRY(launch_plain<EPI_PLAIN>(ds, A, slot, x, zwork, nullptr, 0.0));
         return loss_terms(ds, loss, zwork, zhat, D);
     }
@@ -1255,27 +1294,50 @@ int spmv_loss(tron_dataset *ds, const CsrPlan &A, int slot, int loss, const doub
     ProfScope ps(ds, SLOT_SPMV_COMBINE);
     const int g = vec_grid(A.rows);
     if (loss == TRON_LOSS_LR)
-        hipLaunchKernelGGL(k_combine_loss<TRON_LOSS_LR>, dim3(g), dim3(kBlock), 0, ds->stream, A.rows, partial_ref(ds, A), ds->y, zhat, D, ds->partials);
+        hipLaunchKernelGGL(k_combine_loss<TRON_LOSS_LR>, dim3(g), dim3(kBlock), 0, ds->stream, A.rows, partial_ref(ds, A), ds->y, zhat, D, ds->partials, post);
     else
-        hipLaunchKernelGGL(k_combine_loss<TRON_LOSS_L2SVM>, dim3(g), dim3(kBlock), 0, ds->stream, A.rows, partial_ref(ds, A), ds->y, zhat, D, ds->partials);
+        hipLaunchKernelGGL(k_combine_loss<TRON_LOSS_L2SVM>, dim3(g), dim3(kBlock), 0, ds->stream, A.rows, partial_ref(ds, A), ds->y, zhat, D, ds->partials, post);
     TRON_HIP(hipGetLastError());
     return g;
 }
 
-int spmv_scale(tron_dataset *ds, const CsrPlan &A, int slot, const double *x, const double *scale, double *out)
+int spmv_scale(tron_dataset *ds, const CsrPlan &A, int slot, const double *x, const double *scale, double *out, const double *post)
 {
-    if (A.P == 1) return launch_plain<EPI_SCALE>(ds, A, slot, x, out, scale, 0.0);
+    if (A.P == 1) {
+        if (post) { set_error("internal: post-scaling on an unpartitioned plan"); return TRON_EINVAL; }
+        return launch_plain<EPI_SCALE>(ds, A, slot, x, out, scale, 0.0);
+    }
     TRON_TRY(launch_partials(ds, A, slot, x));
     ProfScope ps(ds, SLOT_SPMV_COMBINE);
-    hipLaunchKernelGGL(k_combine_scale, dim3(vec_grid(A.rows)), dim3(kBlock), 0, ds->stream, A.rows, partial_ref(ds, A), scale, out);
+    hipLaunchKernelGGL(k_combine_scale, dim3(vec_grid(A.rows)), dim3(kBlock), 0, ds->stream, A.rows, partial_ref(ds, A), scale, out, post);
     TRON_HIP(hipGetLastError());
     return TRON_OK;
 }
 
+// xs = x .* scale  (or x .* scale^2)
+__global__ __launch_bounds__(kBlock) void k_prescale(int64_t m, const double *__restrict__ x, const double *__restrict__ scale,
+                                                     int square, double *__restrict__ xs)
+{
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < m; i += (int64_t)gridDim.x * kBlock) {
+        const double r = scale[i];
+        xs[i] = x[i] * (square ? r * r : r);
+    }
+}
+
 int spmv_axpy(tron_dataset *ds, const CsrPlan &A, int slot, const double *x, const double *add, double alpha, bool dot_self,
-              double *out, bool square)
+              double *out, bool square, bool x_prescaled)
 {
     if (square && A.hot_ids) { set_error("internal: squared product on a layout with LDS tables"); return TRON_EINVAL; }
+    if (A.unit && A.col_scale && !x_prescaled) {
+        // the plan gathers from x .* col_scale (the entries themselves carry no values)
+        ProfScope ps(ds, SLOT_SPMV_GATHER);
+        hipLaunchKernelGGL(k_prescale, dim3(vec_grid(A.cols)), dim3(kBlock), 0, ds->stream, A.cols, x, A.col_scale, square ? 1 : 0, A.xs);
+        TRON_HIP(hipGetLastError());
+        x = A.xs;
+    } else if (x_prescaled && !(A.unit && A.col_scale)) {
+        set_error("internal: pre-scaled vector for a plan without column scale");
+        return TRON_EINVAL;
+    }
     if (A.P == 1) {
         TRON_TRY(launch_plain<EPI_AXPY>(ds, A, slot, x, out, add, alpha, square));
         if (!add) return 0;

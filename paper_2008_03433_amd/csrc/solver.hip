@@ -12,7 +12,8 @@ namespace tron {
 // The dense layout computes the same together with the gradient sums in one fused pass.
 int fun_eval(tron_dataset *ds, int loss, double C, const double *w, int Dslot, double *f_out)
 {
-    const int gl = spmv_loss(ds, ds->fwd, SLOT_SPMV_FWD, loss, w, ds->z, ds->zhat, ds->Dbuf[Dslot]);
+    // with unit plans zhat is stored already multiplied by the instances' values, as the transposed plan gathers it
+    const int gl = spmv_loss(ds, ds->fwd, SLOT_SPMV_FWD, loss, w, ds->z, ds->zhat, ds->Dbuf[Dslot], ds->bwd.col_scale);
     TRON_TRY(gl);
     TRON_TRY(reduce_final(ds, 1, gl, 0, 0));
     const int gw = dot_partials(ds, ds->d, w, w, nullptr, nullptr, nullptr, nullptr);
@@ -26,7 +27,7 @@ int fun_eval(tron_dataset *ds, int loss, double C, const double *w, int Dslot, d
 // g = w + C X^T zhat (zhat from the preceding fun_eval) and |g|
 int grad_eval(tron_dataset *ds, double C, const double *w, double *g, double *gnorm_out)
 {
-    const int gg = spmv_axpy(ds, ds->bwd, SLOT_SPMV_BWD, ds->zhat, w, C, true, g);
+    const int gg = spmv_axpy(ds, ds->bwd, SLOT_SPMV_BWD, ds->zhat, w, C, true, g, false, ds->bwd.col_scale != nullptr);
     TRON_TRY(gg);
     TRON_TRY(reduce_final(ds, 1, gg, 0, 0));
     TRON_TRY(read_scalars(ds, 1));
@@ -39,8 +40,8 @@ int hv_enqueue(tron_dataset *ds, double C, const double *v, double *Hv)
 {
     if (ds->dense) return dense_hv(ds, C, ds->Dcur, v, Hv);
     const double *D = ds->Dbuf[ds->Dcur];
-    TRON_TRY(spmv_scale(ds, ds->fwd, SLOT_SPMV_FWD, v, D, ds->z));              // a1 = D (X v)
-    const int g = spmv_axpy(ds, ds->bwd, SLOT_SPMV_BWD, ds->z, v, C, false, Hv);  // Hv = v + C X^T a1
+    TRON_TRY(spmv_scale(ds, ds->fwd, SLOT_SPMV_FWD, v, D, ds->z, ds->bwd.col_scale));   // a1 = D (X v)
+    const int g = spmv_axpy(ds, ds->bwd, SLOT_SPMV_BWD, ds->z, v, C, false, Hv, false, ds->bwd.col_scale != nullptr);  // Hv = v + C X^T a1
     TRON_TRY(g);
     TRON_TRY(reduce_final(ds, 1, g, 0, 0));
     return TRON_OK;

@@ -93,6 +93,7 @@ def test_csr_zipf_skew(rng, loss):
 def test_csr_url_shape_small(rng):
     p = dg.config3(scale=0.02)
     check_calls(p, LOSS_LR, 1.0, rng, w_scale=1.0, n_hv=1)
+    check_calls(p, LOSS_L2SVM, 1.0, rng, w_scale=0.5, n_hv=1)
 
 
 @pytest.mark.parametrize("loss", [LOSS_LR, LOSS_L2SVM])
@@ -140,14 +141,16 @@ def test_csr_partitioned_layout(rng, loss, force_partitions):
     check_calls(p, loss, 1.0, rng, n_hv=1)
 
 
-@pytest.mark.parametrize("knobs", [{"csr_head": 0}, {"csr_hot": 0}, {"csr_tiles": 0}, {"csr_range_slots": 64},
+@pytest.mark.parametrize("knobs", [{"csr_head": 0}, {"csr_hot": 0}, {"csr_tiles": 0}, {"csr_range_slots": 64}, {"csr_unit": 0},
+                                   {"csr_unit": 0, "csr_head": 0, "csr_tiles": 0},
                                    {"csr_blocks_per_part": 3, "csr_range_blocks_per_part": 2, "csr_hot_blocks_per_part": 1,
                                     "csr_tile_blocks_per_slice": 2}])
 def test_csr_layout_variants(rng, force_partitions, knobs):
     # every building block of the partitioned layout switched off or shrunk in turn: the ranges without the head
     # partition, no LDS tables, no hot-row tiles, tiny tables, very few persistent workgroups (many chunks each)
     import paper_2008_03433_amd as tron
-    defaults = {"csr_head": 1, "csr_hot": 1, "csr_tiles": 1, "csr_range_slots": 4096, "csr_blocks_per_part": 128,
+    # (config 3 has one value per instance: its layouts keep no value stream unless csr_unit = 0; config 2 has free values)
+    defaults = {"csr_head": 1, "csr_hot": 1, "csr_tiles": 1, "csr_range_slots": 4096, "csr_unit": 1, "csr_blocks_per_part": 128,
                 "csr_range_blocks_per_part": 96, "csr_hot_blocks_per_part": 96, "csr_tile_blocks_per_slice": 96}
     try:
         for k, v in knobs.items():
@@ -158,6 +161,49 @@ def test_csr_layout_variants(rng, force_partitions, knobs):
     finally:
         for k in knobs:
             tron.tron_tuning_set(k, defaults[k])
+
+
+@pytest.mark.parametrize("loss", [LOSS_LR, LOSS_L2SVM])
+def test_csr_one_value_per_instance(rng, loss, force_partitions):
+    """Matrices X = diag(r) B with B binary: the partitioned layouts keep no values ("unit_values" = 1); a single
+    differing entry switches back to the layouts with values.  Same results either way (to rounding)."""
+    import paper_2008_03433_amd as tron
+    n, d = 4000, 6000
+    B = (rng.random((n, d)) < 0.004).astype(np.float64)
+    B[7] = 1.0                      # a full row
+    B[:, 11] = 1.0                  # a full column
+    B[200:260] = 0.0                # empty rows
+    B[:, 3000:3500] = 0.0           # empty columns
+    r = np.exp(rng.standard_normal(n))
+    r[::5] = 1.0
+    r[3] = -0.75                    # the shared value may be negative
+    y = np.where(rng.random(n) < 0.5, 1.0, -1.0)
+    p = _csr_from_dense(B * r[:, None], y)
+    ds = tron.Dataset.from_problem(p)
+    assert tron.tron_dataset_stat(ds.handle, "unit_values") == 1
+    ds.close()
+    check_calls(p, loss, 0.5, rng, w_scale=0.3, n_hv=2)
+    # a solve on binary features normalised to unit length (r_i = 1 / sqrt(number of entries)); the rounding differs
+    # from the oracle's (r_i times a sum instead of a sum of products), intermediate iterates agree to 1e-6
+    Bn = (rng.random((n, d)) < 0.004).astype(np.float64)
+    Bn[:, 11] = 1.0
+    pn = _csr_from_dense(Bn / np.sqrt(Bn.sum(axis=1))[:, None], y)
+    compare_solves(pn, loss, 1.0, 1e-4, trace_rel=1e-6)
+    X2 = B * r[:, None]
+    X2[7, 5] *= 1.5
+    p2 = _csr_from_dense(X2, y)
+    ds = tron.Dataset.from_problem(p2)
+    assert tron.tron_dataset_stat(ds.handle, "unit_values") == 0
+    ds.close()
+    check_calls(p2, loss, 0.5, rng, w_scale=0.3, n_hv=1)
+    tron.tron_tuning_set("csr_unit", 0)
+    try:
+        ds = tron.Dataset.from_problem(p)
+        assert tron.tron_dataset_stat(ds.handle, "unit_values") == 0
+        ds.close()
+        check_calls(p, loss, 0.5, rng, w_scale=0.3, n_hv=1)
+    finally:
+        tron.tron_tuning_set("csr_unit", 1)
 
 
 def test_solve_partitioned_layout(force_partitions):
@@ -208,8 +254,9 @@ def test_csr_url_shape_partitioned(rng):
     ds = tron.Dataset.from_problem(p)
     try:
         st = {k: tron.tron_dataset_stat(ds.handle, k) for k in ("fwd_parts", "bwd_parts", "fwd_csr_nnz", "fwd_head_nnz",
-                                                                 "fwd_lds_columns", "bwd_csr_nnz", "bwd_tile_nnz", "bwd_tile_rows")}
+                                                                 "fwd_lds_columns", "bwd_csr_nnz", "bwd_tile_nnz", "bwd_tile_rows", "unit_values")}
         assert st["fwd_parts"] == 8 and st["bwd_parts"] == 8
+        assert st["unit_values"] == 1                            # one value per instance: no value stream
         assert st["fwd_csr_nnz"] == p.nnz and 0.25 * p.nnz <= st["fwd_head_nnz"] < p.nnz
         assert st["fwd_lds_columns"] > 4096                      # head table + range tables
         assert st["bwd_csr_nnz"] + st["bwd_tile_nnz"] == p.nnz and st["bwd_tile_rows"] > 0 and st["bwd_csr_nnz"] > 0
