@@ -506,7 +506,7 @@ int tron_tuning_set(const char *name, int64_t value)
         g_tuning.csr_tiles = value;
         return TRON_OK;
     }
-    if (name && strcmp(name, "csr_tile_blocks_per_slice") == 0 && value >= 1 && value <= 1024) {
+    if (name && strcmp(name, "csr_tile_blocks_per_slice") == 0 && value >= 0 && value <= 1024) {
         g_tuning.csr_tile_blocks_per_slice = value;
         return TRON_OK;
     }

@@ -553,19 +553,12 @@ __device__ __forceinline__ void products_to_lds(const StreamRegs<HEAD> &r, const
 }
 
 // Call after the barrier that follows the product writes.  f = the thread's 8 flag bits.
-// On return p[e] = sum of the thread's entries from the start of the run containing e up to e, cin = what the
-// entries before the thread add to its first run, idx0 = number of flags in the threads before it.
-// Contains one barrier; after it the product area may be overwritten (the totals at prod[8..39] may not).
-__device__ __forceinline__ void chunk_runs(double *prod, const unsigned f, double (&p)[8], double &cin, int &idx0)
+// p[e] in: the product of entry 8 * tid + e.  On return p[e] = sum of the thread's entries from the start of the run
+// containing e up to e, cin = what the entries before the thread add to its first run, idx0 = number of flags in the
+// threads before it.  Uses prod[8..39] for the wavefront totals; contains one barrier.
+__device__ __forceinline__ void runs_from_regs(double *prod, const unsigned f, double (&p)[8], double &cin, int &idx0)
 {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
-    const double2 *src = reinterpret_cast<const double2 *>(prod + 10 * tid);
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const double2 d = src[q];
-        p[2 * q] = d.x;
-        p[2 * q + 1] = d.y;
-    }
     double run = 0.0;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
@@ -600,6 +593,20 @@ __device__ __forceinline__ void chunk_runs(double *prod, const unsigned f, doubl
     idx0 = cb + ci - cnt;
 }
 
+// The same with the products taken from LDS (call after the barrier that follows the product writes).  After the barrier
+// inside, the product area may be overwritten (the totals at prod[8..39] may not).
+__device__ __forceinline__ void chunk_runs(double *prod, const unsigned f, double (&p)[8], double &cin, int &idx0)
+{
+    const double2 *src = reinterpret_cast<const double2 *>(prod + 10 * threadIdx.x);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const double2 d = src[q];
+        p[2 * q] = d.x;
+        p[2 * q + 1] = d.y;
+    }
+    runs_from_regs(prod, f, p, cin, idx0);
+}
+
 // flag byte of the calling thread: bit e = entry 8*tid + e is the last of its segment
 __device__ __forceinline__ unsigned load_flags(const uint8_t *__restrict__ flags /* of this chunk */)
 {
@@ -610,12 +617,20 @@ __device__ __forceinline__ unsigned load_flags(const uint8_t *__restrict__ flags
 // order (one coalesced store per 64 segments; the partial sums of a plan are stored segment by segment, not by row:
 // see sum_parts), the piece of a row that started in an earlier chunk to *carry_slot.  Three barriers; the caller
 // adds one before it reuses `prod`.
+// FROM_REGS: p holds the products of the thread's own 8 entries (nothing is read from the product area)
+template <bool FROM_REGS = false>
 __device__ __forceinline__ void chunk_segments(double *prod, const unsigned flags, const int nseg, const bool continued,
-                                               double *__restrict__ out, double *__restrict__ carry_slot)
+                                               double *__restrict__ out, double *__restrict__ carry_slot, double *regs = nullptr)
 {
     double p[8], cin;
     int idx0;
-    chunk_runs(prod, flags, p, cin, idx0);
+    if constexpr (FROM_REGS) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) p[e] = regs[e];
+        runs_from_regs(prod, flags, p, cin, idx0);
+    } else {
+        chunk_runs(prod, flags, p, cin, idx0);
+    }
     double *outv = prod + kOutOffset;
     int i = idx0 - (continued ? 1 : 0);
     bool first = true;
@@ -721,6 +736,63 @@ __device__ __forceinline__ void part_body(double *prod, double *table, const Par
     }
 }
 
+// The head partition of a unit plan: an entry is a 16-bit slot of the LDS table and nothing else, so thread t loads the
+// slots of entries 8t .. 8t+7 with one 16-byte load and gathers their table values straight into the registers the
+// segment sums start from -- no trip of the products through LDS.
+__device__ __forceinline__ void head_unit_body(double *prod, double *table, const PartArgs &pa, const int q, const int Q,
+                                               const PartPtrs &pp)
+{
+    const int tid = threadIdx.x;
+    const int nchunks = pa.nchunks[0];
+    if (q >= nchunks) return;
+    {
+        const double2 *__restrict__ src = reinterpret_cast<const double2 *>(pp.hot_x);
+        for (int k = tid; k < pa.slots / 2; k += kBlock) reinterpret_cast<double2 *>(table)[k] = src[k];
+        __syncthreads();
+    }
+    const uint16_t *col = static_cast<const uint16_t *>(pp.col) + pa.base[0];
+    const int4 *__restrict__ tabs = pp.chunk_tab + pa.chunk0[0];
+    const uint8_t *__restrict__ flags = pp.flags + (int64_t)pa.chunk0[0] * kBlock;
+    double *partial = pp.partial + pa.seg0[0];
+    double *carry = pp.carry + pa.chunk0[0];
+    auto load8 = [&](int c) { return __builtin_nontemporal_load(reinterpret_cast<const v4i *>(col + (int64_t)c * kChunk + 8 * tid)); };
+
+    int c = q;
+    int4 tab = load_uniform(tabs + c);
+    int4 tab_n = load_uniform(tabs + ((c + Q < nchunks) ? c + Q : c));
+    v4i cur = load8(c);
+    unsigned fl = load_flags(flags + (int64_t)c * kBlock);
+    for (; c < nchunks; c += Q) {
+        double p[8];
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            const unsigned two = (unsigned)cur[m];
+            p[2 * m] = table[two & 0xffffu];
+            p[2 * m + 1] = table[two >> 16];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        const int cn = (c + Q < nchunks) ? c + Q : c;
+        const int cnn = (cn + Q < nchunks) ? cn + Q : cn;
+        const v4i nxt = load8(cn);
+        const unsigned fl_n = load_flags(flags + (int64_t)cn * kBlock);
+        const int4 tab_nn = load_uniform(tabs + cnn);
+        __builtin_amdgcn_sched_barrier(0);
+        chunk_segments<true>(prod, fl, tab.y, tab.z > 0, partial + tab.x, carry + c, p);
+        __syncthreads();  // the totals and the parked sums are reused by the next chunk
+        cur = nxt;
+        fl = fl_n;
+        tab = tab_n;
+        tab_n = tab_nn;
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void k_csr_head_unit(PartArgs pa, PartPtrs pp)
+{
+    __shared__ __align__(16) double prod[kOutOffset + kChunk];
+    extern __shared__ __align__(16) double table[];   // pa.slots doubles
+    head_unit_body(prod, table, pa, blockIdx.x, gridDim.x, pp);
+}
+
 template <bool HOT, bool HEAD, bool SQ, bool UNIT>
 __global__ __launch_bounds__(kBlock) void k_csr_spmv_part(PartArgs pa, int64_t rows, PartPtrs pp, const double *__restrict__ x)
 {
@@ -730,7 +802,7 @@ __global__ __launch_bounds__(kBlock) void k_csr_spmv_part(PartArgs pa, int64_t r
 }
 
 // ------------------------------------------------------------------ hot-row tiles (see HotTiles)
-constexpr int kMaxTileBlocks = 128;   // workgroups per slice: at most 1024 / kTileSlices
+constexpr int kMaxTileBlocks = 256;   // workgroups per slice
 
 int hot_tiles_build(CsrPlan &A, const int64_t *t_rowptr, const int32_t *t_col, const double *t_val,
                     const std::vector<int32_t> &slot_code, int nhot, hipStream_t st)
@@ -822,7 +894,9 @@ int hot_tiles_build(CsrPlan &A, const int64_t *t_rowptr, const int32_t *t_col, c
     TRON_TRY(upload(&H.slot_of_row, slot_code.data(), slot_code.size(), st));
     int64_t maxt = 0;
     for (int s = 0; s < kTileSlices; ++s) maxt = std::max(maxt, H.ntiles[s]);
-    H.blocks_per_slice = (int)std::max<int64_t>(1, std::min<int64_t>(maxt, std::min<int64_t>(g_tuning.csr_tile_blocks_per_slice, kMaxTileBlocks)));
+    // 0 = automatic: 3 workgroups per CU with values (the kernel is then bound by HBM), 4 without (bound by issue and latency)
+    const int64_t want_blocks = g_tuning.csr_tile_blocks_per_slice > 0 ? g_tuning.csr_tile_blocks_per_slice : (A.unit ? 128 : 96);
+    H.blocks_per_slice = (int)std::max<int64_t>(1, std::min<int64_t>(maxt, std::min<int64_t>(want_blocks, kMaxTileBlocks)));
     TRON_HIP(hipMalloc(reinterpret_cast<void **>(&H.wg_acc), sizeof(double) * kTileSlices * H.blocks_per_slice * kTileSlots));
     TRON_HIP(hipMalloc(reinterpret_cast<void **>(&H.sums), sizeof(double) * kTileSlices * kTileSlots));
     TRON_HIP(hipStreamSynchronize(st));
@@ -943,6 +1017,95 @@ __device__ __forceinline__ void tiles_body(double *prod, uint16_t *slots, double
     for (int k = tid; k < kTileSlots; k += kBlock) out[k] = acc[k];
 }
 
+// The tiles of a unit plan: an entry is a 16-bit column offset and nothing else; thread t loads the offsets of entries
+// 8t .. 8t+7 with one 16-byte load and gathers x straight into the registers the segment sums start from.
+struct TileRegsU {
+    v4i il;             // eight 16-bit local column offsets
+    uint4 slots;
+    unsigned flags;
+    int4 hdr;
+};
+
+__device__ __forceinline__ TileRegsU load_tile_unit(const TilePtrs &tp, int4 h, int64_t T)
+{
+    TileRegsU r;
+    r.hdr = h;
+    r.il = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(tp.iloc + T * kChunk + 8 * threadIdx.x));
+    r.flags = tp.flags[T * kBlock + threadIdx.x];
+    const int nseg = h.y;
+    const int64_t d0 = (int64_t)h.w + ((8 * (int)threadIdx.x < nseg) ? 8 * (int)threadIdx.x : 0);
+    r.slots = *reinterpret_cast<const uint4 *>(tp.seg_slot + d0);
+    return r;
+}
+
+__device__ __forceinline__ void tiles_unit_body(double *prod, uint16_t *slots, double *acc, const TileArgs &ta, const int s, const int q,
+                                                const int B, const TilePtrs &tp, const double *__restrict__ x)
+{
+    const int tid = threadIdx.x;
+    for (int k = tid; k < kTileSlots; k += kBlock) acc[k] = 0.0;
+    const int64_t nt = ta.ntiles[s];
+    if (q < nt) {
+        const int64_t T0 = ta.tile0[s];
+        const int64_t last = nt - 1;
+        auto clampt = [&](int64_t t) { return T0 + (t < last ? t : last); };
+        auto gather8 = [&](const TileRegsU &r, double (&g)[8]) {
+            const double *xt = x + r.hdr.x;   // the tile's first column
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                const unsigned two = (unsigned)r.il[m];
+                g[2 * m] = xt[two & 0xffffu];
+                g[2 * m + 1] = xt[two >> 16];
+            }
+        };
+        TileRegsU cur = load_tile_unit(tp, load_uniform(tp.hdr + clampt(q)), clampt(q));
+        TileRegsU nxt = load_tile_unit(tp, load_uniform(tp.hdr + clampt(q + B)), clampt(q + B));
+        int4 hdr2 = load_uniform(tp.hdr + clampt(q + 2 * (int64_t)B));
+        double p[8], pn[8], cin;
+        gather8(cur, p);
+        for (int64_t t = q; t < nt; t += B) {
+            const int nseg = cur.hdr.y;
+            // the gathers of the next tile and the data of the one after it are issued before this tile is reduced:
+            // neither a gather nor a stream load is waited for in the iteration that issues it
+            __builtin_amdgcn_sched_barrier(0);
+            gather8(nxt, pn);
+            const TileRegsU nn = load_tile_unit(tp, hdr2, clampt(t + 2 * (int64_t)B));
+            const int4 hdr3 = load_uniform(tp.hdr + clampt(t + 3 * (int64_t)B));
+            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();
+            // every thread is past the accumulator updates and the totals of the tile before
+            if (8 * tid < nseg) *reinterpret_cast<uint4 *>(slots + 8 * tid) = cur.slots;
+            int idx0;
+            runs_from_regs(prod, cur.flags, p, cin, idx0);   // barrier inside: the slots are visible after it
+            int i = idx0;
+            bool first = true;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                if ((cur.flags >> e) & 1u) {
+                    acc[slots[i]] += first ? p[e] + cin : p[e];
+                    first = false;
+                    ++i;
+                }
+            }
+            cur = nxt;
+            nxt = nn;
+            hdr2 = hdr3;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) p[e] = pn[e];
+        }
+    }
+    __syncthreads();
+    double *out = tp.wg_acc + ((int64_t)s * B + q) * kTileSlots;
+    for (int k = tid; k < kTileSlots; k += kBlock) out[k] = acc[k];
+}
+
+__global__ __launch_bounds__(kBlock) void k_hot_tiles_unit(TileArgs ta, int B, TilePtrs tp, const double *__restrict__ x)
+{
+    __shared__ __align__(16) double prod[kOutOffset];   // the wavefront totals only
+    __shared__ __align__(16) uint16_t slots[kChunk];
+    __shared__ double acc[kTileSlots];
+    tiles_unit_body(prod, slots, acc, ta, blockIdx.x % kTileSlices, blockIdx.x / kTileSlices, B, tp, x);
+}
+
 template <bool SQ, bool UNIT>
 __global__ __launch_bounds__(kBlock) void k_hot_tiles(TileArgs ta, int B, TilePtrs tp, const double *__restrict__ x)
 {
@@ -992,7 +1155,7 @@ static int launch_hot_tiles(tron_dataset *ds, const CsrPlan &A, const double *x,
     {
         ProfScope ps(ds, SLOT_SPMV_TILES, st);
         if (A.unit)   // squares, if any, are in the scaled vector
-            hipLaunchKernelGGL((k_hot_tiles<false, true>), dim3(kTileSlices * H.blocks_per_slice), dim3(kBlock), 0, st, tile_args(H),
+            hipLaunchKernelGGL(k_hot_tiles_unit, dim3(kTileSlices * H.blocks_per_slice), dim3(kBlock), 0, st, tile_args(H),
                                H.blocks_per_slice, tile_ptrs(H), x);
         else if (square)
             hipLaunchKernelGGL((k_hot_tiles<true, false>), dim3(kTileSlices * H.blocks_per_slice), dim3(kBlock), 0, st, tile_args(H),
@@ -1250,8 +1413,8 @@ static int launch_partials(tron_dataset *ds, const CsrPlan &A, int slot, const d
         ProfScope ps(ds, SLOT_SPMV_HEAD);
         const int grid = std::max(1, std::min(A.part_nchunks[A.head], (int)g_tuning.csr_hot_blocks_per_part * kColParts));
         if (A.unit)
-            hipLaunchKernelGGL((k_csr_spmv_part<true, true, false, true>), dim3(grid), dim3(kBlock), kHotSlots * sizeof(double), ds->stream,
-                               head_args(A), A.rows, head_ptrs(ds, A), x);
+            hipLaunchKernelGGL(k_csr_head_unit, dim3(grid), dim3(kBlock), kHotSlots * sizeof(double), ds->stream, head_args(A),
+                               head_ptrs(ds, A));
         else
             hipLaunchKernelGGL((k_csr_spmv_part<true, true, false, false>), dim3(grid), dim3(kBlock), kHotSlots * sizeof(double), ds->stream,
                                head_args(A), A.rows, head_ptrs(ds, A), x);

@@ -151,7 +151,7 @@ def test_csr_layout_variants(rng, force_partitions, knobs):
     import paper_2008_03433_amd as tron
     # (config 3 has one value per instance: its layouts keep no value stream unless csr_unit = 0; config 2 has free values)
     defaults = {"csr_head": 1, "csr_hot": 1, "csr_tiles": 1, "csr_range_slots": 4096, "csr_unit": 1, "csr_blocks_per_part": 128,
-                "csr_range_blocks_per_part": 96, "csr_hot_blocks_per_part": 96, "csr_tile_blocks_per_slice": 96}
+                "csr_range_blocks_per_part": 96, "csr_hot_blocks_per_part": 96, "csr_tile_blocks_per_slice": 0}
     try:
         for k, v in knobs.items():
             tron.tron_tuning_set(k, v)
