@@ -32,10 +32,11 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 ROCPROF_NAMES = {
     "dense_hv": ("k_dense_hv<6, 4, 4, true, true, false, false>", "dense_hv_fun_grad_c5.md"),
     "dense_fun_grad": ("k_dense_fun_grad<6, 4, 4, true, 1>", "dense_hv_fun_grad_c5.md"),
-    "spmv_head": ("k_csr_spmv_part<true, true, false>", "csr_spmv_c3.md"),
-    "spmv_fwd": ("k_csr_spmv_part<true, false, false>", "csr_spmv_c3.md"),
-    "spmv_bwd": ("k_csr_spmv_part<false, false, false>", "csr_spmv_c3.md"),
-    "spmv_tiles": ("k_hot_tiles<false>", "csr_spmv_c3.md"),
+    # config 3 has one value per instance: its layouts keep no value stream and run the "unit" kernels
+    "spmv_head": ("k_csr_head_unit", "csr_spmv_c3.md"),
+    "spmv_fwd": ("k_csr_spmv_part<true, false, false, true>", "csr_spmv_c3.md"),
+    "spmv_bwd": ("k_csr_spmv_part<false, false, false, true>", "csr_spmv_c3.md"),
+    "spmv_tiles": ("k_hot_tiles_unit", "csr_spmv_c3.md"),
 }
 
 
@@ -279,6 +280,10 @@ def run_workload(args, wname: str) -> dict:
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(dominant),
                 "ms_per_launch": dom_ms, "algorithmic_bytes_per_launch": dom_bytes}
+    if not ds.dense and stat("unit_values"):
+        roofline["note"] = ("algorithmic bytes count 12 B per nonzero (int32 column + fp64 value); every instance of this matrix has "
+                            "one value for all its entries, so the layouts keep no value stream and the kernel moves fewer bytes than "
+                            "that (traffic): it is bound by issue and latency, not by HBM, and frac can exceed 1")
     def with_rates(table):
         outk = {}
         for k, rec in table.items():
@@ -314,7 +319,7 @@ def run_workload(args, wname: str) -> dict:
     }
     if not ds.dense:
         out["layout"] = {k: stat(k) for k in ("fwd_parts", "bwd_parts", "fwd_csr_nnz", "fwd_head_nnz", "fwd_lds_columns", "bwd_csr_nnz",
-                                             "bwd_tile_nnz", "bwd_tile_rows", "bwd_tiles")}
+                                             "bwd_tile_nnz", "bwd_tile_rows", "bwd_tiles", "unit_values")}
     if not args.no_cpu_baseline:
         log("timing the CPU oracle (one thread, bounded sample)")
         out["cpu_baseline"] = cpu_baseline(workload, loss, C)
