@@ -145,6 +145,16 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass(int64_t n, int64_t d, 
             double x[U][E];
             T::load(X, n, d, row0, lane, x, rows);
             const double yrow = (any_fg && row0 + lane < n) ? (double)y[row0 + lane] : 1.0;
+            // logistic Hessian: D of the tile's rows for every problem, lane i taking row i, fetched together with x
+            double Drow[KT];
+            if constexpr (!svm) {
+#pragma unroll
+                for (int k = 0; k < KT; ++k) {
+                    Drow[k] = 0.0;
+                    if (mode[k] == MODE_HV && wk[k] != 0 && row0 + lane < n)
+                        Drow[k] = Dval[((int64_t)k * 2 + dslot[k]) * n + row0 + lane];   // zero outside the problem's rows
+                }
+            }
             // the vectors are read from LDS again for every tile: hoisted out of the loop they would take KT * E
             // registers per lane (the empty statement hides the loop invariance from the compiler)
             int qoff = q * E;
@@ -168,12 +178,9 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass(int64_t n, int64_t d, 
                             c[u] = (half & rowbit[u]) ? t[u] : 0.0;
                         }
                     } else {
-                        const double *Dk = Dval + ((int64_t)k * 2 + dslot[k]) * n;   // zero outside the problem's rows
+                        T::from_row_owner(Drow[k], lane, c);
 #pragma unroll
-                        for (int u = 0; u < U; ++u) {
-                            const int64_t row = row0 + u * T::RW + rl;
-                            c[u] = (row < n) ? Dk[row] * t[u] : 0.0;
-                        }
+                        for (int u = 0; u < U; ++u) c[u] *= t[u];
                     }
                 } else {
                     // the per-row terms of Table 1 run once per row, lane i owning tile row i
