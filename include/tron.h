@@ -185,6 +185,8 @@ typedef struct {
  * giving it; this is the diagonal one of the work it cites, a = 0.01 being that work's choice.)
  * Returns TRON_OK when converged, TRON_EMAXITER when max_outer was reached or progress stalled.
  * On return the handle caches D at the final iterate (so tron_hv may follow).
+ * Small dense L2-SVM problems (d <= 32, no preconditioner) are driven from the device, like tron_batch_solve with one
+ * problem over all rows: same rules, same results up to summation order (knob "dense_device_driver").
  */
 TRON_API int tron_solve(tron_dataset *ds, const tron_params *params, double *w_dev, tron_result *res_host);
 
@@ -282,6 +284,8 @@ TRON_API int tron_probe_read_bandwidth(const double *src_dev, int64_t count, int
  *   "csr_unit" (0/1): layouts without a value stream when every instance's entries share one value;
  *   "csr_hot_blocks_per_part", "csr_range_blocks_per_part", "csr_blocks_per_part",
  *   "csr_tile_blocks_per_slice": persistent workgroups of the head, table, table-less and tile kernels.
+ * "dense_device_driver" (-1/0/1): tron_solve on a dense matrix with d <= 32 and no preconditioner runs its trust-region and
+ *   CG steps on the device (as tron_batch_solve does): 0 never, 1 always, -1 (default) for the L2-SVM on matrices up to 1 GB.
  * "batch_grid" (0..4096): workgroups of the multi-problem pass (0 = as many as are resident at once).
  * Unknown names or values return TRON_EINVAL.
  */

@@ -162,6 +162,7 @@ void tron_dataset_destroy(tron_dataset *ds)
 {
     if (!ds) return;
     hipStreamSynchronize(ds->stream);
+    dense_device_release(ds);
     hipFree(ds->X);
     ds->fwd.release();
     ds->bwd.release();
@@ -516,6 +517,10 @@ int tron_tuning_set(const char *name, int64_t value)
     }
     if (name && strcmp(name, "csr_unit") == 0 && (value == 0 || value == 1)) {
         g_tuning.csr_unit = value;
+        return TRON_OK;
+    }
+    if (name && strcmp(name, "dense_device_driver") == 0 && value >= -1 && value <= 1) {
+        g_tuning.dense_device_driver = value;
         return TRON_OK;
     }
     if (name && strcmp(name, "batch_grid") == 0 && value >= 0 && value <= 4096) {

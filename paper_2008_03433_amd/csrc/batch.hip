@@ -227,8 +227,8 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass(int64_t n, int64_t d, 
 }
 
 // ------------------------------------------------------------------ membership words
-// planes[k][tile] bit i = bit k of member[tile*64 + i]; rows past n give zero bits.  bad[0] is set when a word has a bit
-// at or above K.
+// planes[k][tile] bit i = bit k of member[tile*64 + i] (member == null: every row belongs to every problem); rows past n
+// give zero bits.  bad[0] is set when a word has a bit at or above K.
 __global__ __launch_bounds__(kBlock) void k_member_planes(int64_t n, int K, const uint32_t *__restrict__ member,
                                                           int64_t ntiles, uint64_t *__restrict__ planes, int *bad)
 {
@@ -236,7 +236,7 @@ __global__ __launch_bounds__(kBlock) void k_member_planes(int64_t n, int K, cons
     const int64_t nwaves = (int64_t)gridDim.x * kWavesPerBlock;
     for (int64_t tile = (int64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave; tile < ntiles; tile += nwaves) {
         const int64_t row = tile * kWave + lane;
-        const uint32_t m = (row < n) ? member[row] : 0u;
+        const uint32_t m = (row < n) ? (member ? member[row] : ((K < 32) ? (1u << K) - 1u : ~0u)) : 0u;
         if (K < 32 && (m >> K) != 0u) bad[0] = 1;
         for (int k = 0; k < K; ++k) {
             const uint64_t b = __ballot((m >> k) & 1u);
@@ -634,19 +634,16 @@ extern "C" void tron_batch_destroy(tron_batch *b)
     delete b;
 }
 
-extern "C" int tron_batch_create(tron_dataset *ds, int K, const uint32_t *member, int mem, tron_batch **out)
+// member == null: every row belongs to every problem
+static int batch_create_impl(tron_dataset *ds, int K, const uint32_t *member, int mem, tron_batch **out)
 {
-    if (out) *out = nullptr;
-    if (!ds || !out || !member || K < 1 || K > kBatchMax || (mem != TRON_MEM_HOST && mem != TRON_MEM_DEVICE)) {
-        set_error("tron_batch_create: bad argument (need a handle, 1 <= K <= %d, member, mem in {0,1}, out)", kBatchMax);
-        return TRON_EINVAL;
-    }
+    *out = nullptr;
     if (!ds->dense || ds->d > kVecPad) {
         set_error("tron_batch_create: needs a dense dataset with d <= %d", kVecPad);
         return TRON_EINVAL;
     }
     const int64_t n = ds->n, d = ds->d;
-    if (mem == TRON_MEM_HOST && K < 32)
+    if (member && mem == TRON_MEM_HOST && K < 32)
         for (int64_t i = 0; i < n; ++i)
             if ((member[i] >> K) != 0u) { set_error("tron_batch_create: member[%lld] has a bit at or above K", (long long)i); return TRON_EINVAL; }
     Shape s;
@@ -690,7 +687,7 @@ extern "C" int tron_batch_create(tron_dataset *ds, int K, const uint32_t *member
     TRON_B(hipMalloc(reinterpret_cast<void **>(&bad), sizeof(int)));
     hipError_t e = hipMemsetAsync(bad, 0, sizeof(int), ds->stream);
     const uint32_t *src = member;
-    if (e == hipSuccess && mem == TRON_MEM_HOST) {
+    if (e == hipSuccess && member && mem == TRON_MEM_HOST) {
         e = hipMalloc(reinterpret_cast<void **>(&staged), sizeof(uint32_t) * (size_t)n);
         if (e == hipSuccess) e = hipMemcpyAsync(staged, member, sizeof(uint32_t) * (size_t)n, hipMemcpyHostToDevice, ds->stream);
         src = staged;
@@ -711,6 +708,16 @@ extern "C" int tron_batch_create(tron_dataset *ds, int K, const uint32_t *member
 #undef TRON_B
     *out = b;
     return TRON_OK;
+}
+
+extern "C" int tron_batch_create(tron_dataset *ds, int K, const uint32_t *member, int mem, tron_batch **out)
+{
+    if (out) *out = nullptr;
+    if (!ds || !out || !member || K < 1 || K > kBatchMax || (mem != TRON_MEM_HOST && mem != TRON_MEM_DEVICE)) {
+        set_error("tron_batch_create: bad argument (need a handle, 1 <= K <= %d, member, mem in {0,1}, out)", kBatchMax);
+        return TRON_EINVAL;
+    }
+    return batch_create_impl(ds, K, member, mem, out);
 }
 
 extern "C" int tron_batch_fun_grad(tron_batch *b, int loss, const double *C_host, const double *W_dev, double *f_host,
@@ -801,3 +808,41 @@ extern "C" int tron_batch_solve(tron_batch *b, const tron_params *params, const 
     b->D_loss = Q.loss;
     return overall;
 }
+
+// ------------------------------------------------------------------ one problem, driven from the device
+// tron_solve for a dense matrix with d <= 32 as a batch of one problem over all rows: the trust-region and CG steps run
+// on the device between the passes, so no scalar is waited for by the host inside an iteration.  For matrices of a few
+// GB and less that wait is most of a host-driven solve.
+namespace tron {
+
+int dense_device_solve(tron_dataset *ds, const tron_params &P, double *w_dev, tron_result *res)
+{
+    if (!ds->self_batch) TRON_TRY(batch_create_impl(ds, 1, nullptr, TRON_MEM_DEVICE, &ds->self_batch));
+    tron_batch *b = ds->self_batch;
+    const double C = P.C;
+    int status = TRON_OK;
+    TRON_TRY(tron_batch_solve(b, &P, &C, w_dev, res, &status));
+    // D at the final iterate goes where the single-problem calls expect it (same layouts: one bit per row in 64-bit
+    // words for the L2-SVM, fp64 per row for the logistic loss)
+    const int slot = b->st_host[0].sc.dcur;
+    if (P.loss == TRON_LOSS_L2SVM)
+        TRON_HIP(hipMemcpyAsync(ds->Dbuf[0], b->Dbits + (size_t)slot * (size_t)b->ntiles, sizeof(uint64_t) * (size_t)b->ntiles,
+                                hipMemcpyDeviceToDevice, ds->stream));
+    else
+        TRON_HIP(hipMemcpyAsync(ds->Dbuf[0], b->Dval + (size_t)slot * (size_t)ds->n, sizeof(double) * (size_t)ds->n,
+                                hipMemcpyDeviceToDevice, ds->stream));
+    TRON_HIP(hipStreamSynchronize(ds->stream));
+    ds->Dcur = 0;
+    ds->have_D = true;
+    ds->D_is_mask[0] = (P.loss == TRON_LOSS_L2SVM);
+    ds->active_frac[0] = 1.0;   // not counted here: the Hessian pass then reads every row, which is always right
+    return status;
+}
+
+void dense_device_release(tron_dataset *ds)
+{
+    tron_batch_destroy(ds->self_batch);
+    ds->self_batch = nullptr;
+}
+
+}  // namespace tron

@@ -39,6 +39,8 @@ struct Tuning {
     int64_t csr_tiles = 1;   // hot-row tiles for the transposed orientation of partitioned matrices (0 = off)
     int64_t csr_tile_blocks_per_slice = 0;   // persistent workgroups per slice of hot rows (0 = automatic: 96, or 128 for unit plans)
     int64_t csr_unit = 1;    // partitioned layouts: drop the value stream when every row of X holds one repeated value (0 = off)
+    int64_t dense_device_driver = -1;   // tron_solve on dense d <= 32 without preconditioner driven from the device:
+                                        //   0 never, 1 always, -1 automatic (the L2-SVM on matrices up to 1 GB)
     int64_t batch_grid = 0;  // workgroups of the multi-problem pass: 0 = as many as are resident at once
 };
 extern Tuning g_tuning;
@@ -193,6 +195,7 @@ struct CsrPlan {
 }  // namespace tron
 
 // ---------------------------------------------------------------- the handle
+struct tron_batch;
 struct tron_dataset {
     int64_t n = 0, d = 0;
     bool dense = false;
@@ -224,6 +227,8 @@ struct tron_dataset {
     int vec_grid_n = 0, vec_grid_d = 0;  // workgroups of elementwise kernels over n / d
 
     double *unit_scale = nullptr;  // sparse, unit plans: r (n), the value shared by the entries of instance i
+
+    tron_batch *self_batch = nullptr;   // dense: one problem over all rows, for solves driven from the device
 
     // solver vectors (d each), allocated on first tron_solve
     double *sv[9] = {nullptr};
@@ -297,6 +302,10 @@ int dense_hv(tron_dataset *ds, double C, int Dslot, const double *v, double *Hv)
 
 // out = 1 + C diag(X^T D X)
 int dense_hess_diag(tron_dataset *ds, double C, int Dslot, double *out);
+
+// ---- batch.hip
+int dense_device_solve(tron_dataset *ds, const tron_params &P, double *w_dev, tron_result *res);
+void dense_device_release(tron_dataset *ds);
 
 // ---- solver.hip
 int fun_eval(tron_dataset *ds, int loss, double C, const double *w, int Dslot, double *f_out);  // syncs

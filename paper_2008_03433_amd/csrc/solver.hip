@@ -159,6 +159,14 @@ extern "C" int tron_solve(tron_dataset *ds, const tron_params *params, double *w
                   "0 <= precond_blend <= 1, trace)");
         return TRON_EINVAL;
     }
+    // Dense matrices with d <= 32: the solve can be driven from the device (batch.hip), which saves the host's waits for
+    // scalars inside every iteration.  Measured: 0.31 ms against 0.40 ms on the 1M x 24 L2-SVM configuration; no gain
+    // for the logistic loss (its multi-problem pass is slower than the single-problem kernels) or for large matrices
+    // (there the waits are small next to the passes).  So by default: the L2-SVM up to 1 GB.
+    if (ds->dense && ds->d <= TRON_BATCH_MAX_D && P.precond_blend == 0.0 && g_tuning.dense_device_driver != 0) {
+        const double bytes = (double)ds->n * (double)ds->d * 8.0;
+        if (g_tuning.dense_device_driver > 0 || (P.loss == TRON_LOSS_L2SVM && bytes <= 1e9)) return dense_device_solve(ds, P, w_dev, res);
+    }
     const double eta0 = 1e-4, eta1 = 0.25, eta2 = 0.75, sig2 = 0.5, sig3 = 4.0;
     tron_trace_rec *trace = res->trace;
     const int trace_cap = res->trace_cap;

@@ -4,7 +4,8 @@ Config 3 (sparse, 2M x 3M, 123M nonzeros) is small enough for the oracle to eval
 Config 5 (dense, 230M x 24, 44 GB) is not: there the full-size device matrix is zero except for
 sampled row ranges (the first rows, a range in the middle that straddles the 2^31-element and
 2^32-byte marks, and a ragged tail), so the oracle can compute every output from the sampled rows
-alone: zero rows add nothing to g and Hv and a known constant to f.  A second test runs the real
+alone: zero rows add nothing to g and Hv and a known constant to f.  The same matrix then goes through the
+multi-problem pass with three memberships (sampled ranges, strided rows, every row).  A second test runs the real
 config-5 solve and checks properties that hold at any size.
 """
 import numpy as np
@@ -90,6 +91,44 @@ def test_config5_full_size_sampled_rows(rng, loss):
         assert_vec_close(g.cpu().numpy(), g_o, what="g")
         assert_vec_close(Hv.cpu().numpy(), Hv_o, what="Hv")
         assert_scalar_close(vHv, float(v @ Hv_o), what="v.Hv")
+
+        # The multi-problem pass over the same 230M rows.  Problem 0: the middle and the tail range; problem 1: every
+        # third row of the first range and 1000 of the zero rows; problem 2: every row (= the single-problem results above).
+        m0, m1, m2 = (r[1] for r in ranges)
+        member = torch.zeros(n, dtype=torch.int32, device="cuda")
+        member[ranges[1][0]:ranges[1][0] + m1] |= 1
+        member[ranges[2][0]:] |= 1
+        member[0:m0:3] |= 2
+        member[30_000_000:30_001_000] |= 2
+        member |= 4
+        rows_k = [np.arange(m0, m0 + m1 + m2), np.arange(0, m0, 3), np.arange(0, m0 + m1 + m2)]
+        zero_rows_k = [0, 1000, n_zero]
+        loss0 = 1.0 if loss == LOSS_L2SVM else np.log(2.0)
+        Cs = [0.1, 0.3, C]
+        W = np.stack([w, -0.5 * w, w])
+        V = np.stack([v, v[::-1].copy(), v])
+        b = tron.tron_batch_create(h, 3, member)
+        try:
+            del member
+            W_d, V_d = dev(W), dev(V)
+            G_d, HV_d = torch.empty_like(W_d), torch.empty_like(V_d)
+            fb = tron.tron_batch_fun_grad(b, loss, Cs, W_d, G_d)
+            vHvb = tron.tron_batch_hv(b, Cs, V_d, HV_d)
+            G, HV = G_d.cpu().numpy(), HV_d.cpu().numpy()
+            for k in range(3):
+                ok = o.restrict(rows_k[k])
+                f_k, g_k, D_k = ok.fun_grad(loss, Cs[k], W[k])
+                assert_scalar_close(fb[k], f_k + Cs[k] * zero_rows_k[k] * loss0, what=f"batch f[{k}]")
+                assert_vec_close(G[k], g_k, what=f"batch g[{k}]")
+                Hv_k = ok.hv(Cs[k], D_k, V[k])
+                assert_vec_close(HV[k], Hv_k, what=f"batch Hv[{k}]")
+                assert_scalar_close(vHvb[k], float(V[k] @ Hv_k), what=f"batch v.Hv[{k}]")
+            # problem 2 sees what the single-problem calls saw
+            assert_scalar_close(fb[2], f, rel=1e-13, what="batch f against tron_fun_grad")
+            assert_vec_close(G[2], g.cpu().numpy(), rel=1e-12, what="batch g against tron_fun_grad")
+            assert_vec_close(HV[2], Hv.cpu().numpy(), rel=1e-12, what="batch Hv against tron_hv")
+        finally:
+            tron.tron_batch_destroy(b)
     finally:
         tron.tron_dataset_destroy(h)
 

@@ -428,14 +428,26 @@ def test_solve_config2_svm_loss():
         ds.close()
 
 
-def test_solve_config4_reduced():
+@pytest.fixture(params=[0, 1], ids=["host_driver", "device_driver"])
+def dense_driver(request):
+    """tron_solve on dense matrices with d <= 32: trust-region / CG steps on the host (scalars read back every iteration)
+    or on the device (the multi-problem machinery with one problem over all rows)."""
+    import paper_2008_03433_amd as tron
+    tron.tron_tuning_set("dense_device_driver", request.param)
+    yield request.param
+    tron.tron_tuning_set("dense_device_driver", -1)
+
+
+def test_solve_config4_reduced(dense_driver):
     p = dg.config4(n=200_000)
     compare_solves(p, p.loss, p.C, p.eps)
+    compare_solves(p, LOSS_LR, 1e-3, 1e-4)
 
 
-def test_solve_dense_lr_tight(rng):
+def test_solve_dense_lr_tight(rng, dense_driver):
     p = _dense(rng, 5000, 18)
     compare_solves(p, LOSS_LR, 2.0, 1e-6)
+    compare_solves(p, LOSS_L2SVM, 0.5, 1e-6)
 
 
 def test_solve_hits_trust_region_boundary(rng):
@@ -453,7 +465,7 @@ def test_solve_hits_trust_region_boundary(rng):
         assert sum(1 - t["accepted"] for t in ref.trace) >= 5
 
 
-def test_solve_warm_start_and_iteration_cap(rng):
+def test_solve_warm_start_and_iteration_cap(rng, dense_driver):
     torch = torch_mod()
     import paper_2008_03433_amd as tron
     from oracle import Oracle
@@ -477,4 +489,14 @@ def test_solve_warm_start_and_iteration_cap(rng):
     ds.hv(5.0, v, Hv)
     _, _, D = o.fun_grad(LOSS_LR, 5.0, w.cpu().numpy())
     np.testing.assert_allclose(Hv.cpu().numpy(), o.hv(5.0, D, v.cpu().numpy()), rtol=1e-9, atol=1e-9)
+    # the same after an L2-SVM solve (the active set of the final iterate), and the Hessian diagonal
+    w2 = torch.zeros(p.d, dtype=torch.float64, device="cuda")
+    r3 = ds.solve(LOSS_L2SVM, 0.5, 1e-4, w2)
+    assert r3.converged
+    ds.hv(0.5, v, Hv)
+    _, _, D2 = o.fun_grad(LOSS_L2SVM, 0.5, w2.cpu().numpy())
+    np.testing.assert_allclose(Hv.cpu().numpy(), o.hv(0.5, D2, v.cpu().numpy()), rtol=1e-9, atol=1e-9)
+    hd = torch.empty_like(v)
+    ds.hess_diag(0.5, hd)
+    np.testing.assert_allclose(hd.cpu().numpy(), o.hess_diag(0.5, D2), rtol=1e-10)
     ds.close()
