@@ -76,7 +76,8 @@ def _check_calls(rng, X, y, member, K, loss, Cs, n_hv=2):
 
 @pytest.mark.parametrize("loss", [LOSS_LR, LOSS_L2SVM])
 @pytest.mark.parametrize("n,d,K", [(1000, 24, 3), (4133, 24, 8), (70000, 18, 6), (5000, 7, 2), (3000, 32, 5), (300, 1, 1),
-                                   (20011, 13, 4), (64, 24, 8), (63, 5, 7)])
+                                   (20011, 13, 4), (64, 24, 8), (63, 5, 7), (2000, 32, 8), (1500, 28, 7), (900, 9, 8),
+                                   (700, 3, 6), (1200, 16, 5), (6000, 23, 3)])
 def test_batch_calls_match_the_oracle(rng, loss, n, d, K):
     X, y = _dense(rng, n, d)
     member = _cv_members(rng, n, K)
@@ -176,6 +177,35 @@ def test_batch_on_the_dense_benchmark_shape(rng):
     p = datagen.config4(n=20000)
     member = _cv_members(rng, p.n, 6)
     _compare_batch_solve(rng, p.X, p.y, member, 6, LOSS_L2SVM, [0.1, 0.1, 0.1, 1.0, 1.0, 1.0], 0.01)
+
+
+def test_batch_solve_with_an_empty_problem(rng):
+    """A problem without instances is f = 1/2 w.w: it is converged at w = 0 and does not hold the others up."""
+    torch = torch_mod()
+    n, d, K = 3000, 10, 3
+    X, y = _dense(rng, n, d)
+    member = np.where(rng.random(n) < 0.5, 1, 4).astype(np.uint32)      # problem 1 has no rows
+    full = Oracle(n=n, d=d, y=y, X=X)
+    ds = tron.Dataset.from_dense(X, y)
+    b = tron.Batch(ds, K, member)
+    try:
+        W_d = torch.zeros((K, d), dtype=torch.float64, device="cuda")
+        res = b.solve(LOSS_LR, [1.0, 1.0, 0.3], 1e-6, W_d)
+        W = W_d.cpu().numpy()
+        assert res[1].converged and res[1].outer_iters == 0 and res[1].f == 0.0 and not W[1].any()
+        for k in (0, 2):
+            ref = full.restrict(_rows(member, k)).tron(LOSS_LR, [1.0, 1.0, 0.3][k], 1e-6)
+            assert res[k].converged and res[k].outer_iters == ref.outer_iters
+            assert abs(res[k].f - ref.f) <= 1e-8 * abs(ref.f)
+            assert_vec_close(W[k], ref.w, rel=1e-8, what=f"w[{k}]")
+        # started away from zero, the empty problem walks back to w = 0 (its gradient at zero is zero: the stopping
+        # test then has no reference and it runs until its progress stalls or the model predicts no decrease)
+        W_d = dev(np.tile(0.1 * rng.standard_normal(d), (K, 1)))
+        res = b.solve(LOSS_LR, [1.0, 1.0, 0.3], 1e-6, W_d)
+        assert np.abs(W_d.cpu().numpy()[1]).max() <= 1e-12
+    finally:
+        b.close()
+        ds.close()
 
 
 def test_batch_hv_after_solve_uses_the_final_D(rng):
