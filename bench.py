@@ -169,8 +169,16 @@ def cpu_baseline(workload, loss, C, budget_s: float = 15.0):
         o.hv(C, D, v)
         times.append(time.perf_counter() - t0)
     med = float(np.median(times))
+    cpu_model = "unknown"
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                cpu_model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
     return {
-        "value": scale / med, "unit": "Hv/s", "cores": 1, "kind": "oracle",
+        "value": scale / med, "unit": "Hv/s", "cores": 1, "kind": "oracle", "host_cpu": cpu_model, "host_nproc": os.cpu_count(),
         "sample": f"{len(times)} oracle Hv calls, {sample}; median {med:.3f} s per sampled call; "
                   f"one fun+grad took {t_fg:.3f} s",
         "fun_grad_per_s": scale / t_fg,
