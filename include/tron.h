@@ -264,9 +264,10 @@ TRON_API int tron_profile_read(tron_dataset *ds, int cap, const char **names, do
                                int *count);
 
 /*
- * Streaming-read probe: sums `count` doubles at src_dev with the library's reduction kernel,
- * `reps` launches back to back, and returns the average milliseconds per launch measured with
- * HIP events.  Used to report the attainable HBM read rate next to the nominal peak.
+ * Streaming-read probe: sums `count` doubles at src_dev, every wavefront reading 12 KiB blocks of
+ * consecutive bytes with twelve 16-byte loads per lane in flight (the access pattern of the dense
+ * kernels), `reps` launches back to back, and returns the average milliseconds per launch measured
+ * with HIP events.  Used to report the attainable HBM read rate next to the nominal peak.
  */
 TRON_API int tron_probe_read_bandwidth(const double *src_dev, int64_t count, int reps, void *hip_stream,
                                        double *ms_per_launch, double *checksum);

@@ -259,18 +259,30 @@ int trial_point(tron_dataset *ds, const double *w, const double *s, const double
 }
 
 // ------------------------------------------------------------------ streaming-read probe
+// Every wavefront reads blocks of 12 KiB of consecutive bytes -- twelve 16-byte loads per lane in flight, each instruction
+// covering 1 KiB -- the access pattern of the dense kernels (block w, w + W, ... for wavefront w of W).
 __global__ __launch_bounds__(kBlock) void k_probe_sum(const double2 *__restrict__ src, int64_t count2, double *__restrict__ out)
 {
     __shared__ double lds[kWavesPerBlock];
+    constexpr int kInFlight = 12;
+    constexpr int64_t kPerBlock = (int64_t)kInFlight * kWave;   // double2 elements per 12 KiB block
     double a = 0.0, b = 0.0;
-    const int64_t stride = (int64_t)gridDim.x * kBlock;
-    int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    for (; i + 3 * stride < count2; i += 4 * stride) {
-        const double2 x0 = src[i], x1 = src[i + stride], x2 = src[i + 2 * stride], x3 = src[i + 3 * stride];
-        a += (x0.x + x1.x) + (x2.x + x3.x);
-        b += (x0.y + x1.y) + (x2.y + x3.y);
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t nwaves = (int64_t)gridDim.x * kWavesPerBlock;
+    const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+    const int64_t nblocks = count2 / kPerBlock;
+    for (int64_t blk = wave; blk < nblocks; blk += nwaves) {
+        const double2 *p = src + blk * kPerBlock + lane;
+        double2 x[kInFlight];
+#pragma unroll
+        for (int m = 0; m < kInFlight; ++m) x[m] = p[m * kWave];
+#pragma unroll
+        for (int m = 0; m < kInFlight; ++m) {
+            a += x[m].x;
+            b += x[m].y;
+        }
     }
-    for (; i < count2; i += stride) {
+    for (int64_t i = nblocks * kPerBlock + (int64_t)blockIdx.x * kBlock + threadIdx.x; i < count2; i += (int64_t)gridDim.x * kBlock) {
         const double2 x0 = src[i];
         a += x0.x;
         b += x0.y;
