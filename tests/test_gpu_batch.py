@@ -85,6 +85,22 @@ def test_batch_calls_match_the_oracle(rng, loss, n, d, K):
     _check_calls(rng, X, y, member, K, loss, Cs)
 
 
+@pytest.mark.parametrize("grid", [1, 7, 300])
+def test_batch_pass_with_few_or_many_workgroups(rng, grid):
+    """One workgroup walking every tile (active-set words stored over several 64-tile rounds), an odd count, and more
+    workgroups than tiles / 4."""
+    tron.tron_tuning_set("batch_grid", grid)
+    try:
+        n, d, K = 40_037, 24, 5
+        X, y = _dense(rng, n, d)
+        member = _cv_members(rng, n, K)
+        _check_calls(rng, X, y, member, K, LOSS_L2SVM, [0.3, 0.1, 1.0, 0.5, 0.2], n_hv=1)
+        _check_calls(rng, X, y, member, K, LOSS_LR, [0.3, 0.1, 1.0, 0.5, 0.2], n_hv=1)
+        _compare_batch_solve(rng, X, y, member, K, LOSS_L2SVM, [0.03, 0.01, 0.1, 0.05, 0.02], 1e-4)
+    finally:
+        tron.tron_tuning_set("batch_grid", 0)
+
+
 @pytest.mark.parametrize("loss", [LOSS_LR, LOSS_L2SVM])
 def test_batch_membership_patterns(rng, loss):
     """Empty problems, a problem over everything, long runs of rows that nobody needs, rows used by one problem only."""
