@@ -560,6 +560,14 @@ def main() -> int:
         quiet = argparse.Namespace(**{**vars(args), "no_cpu_baseline": True})
         out["mixes"] = {w: small_config(quiet, w) for w in ("susy_shape", "higgs_shape", "c3_svm")}
         out["active_set"] = active_set_sweep()
+        # config 3 again with the general 12-byte layout (its own layouts keep no value stream, see roofline.note)
+        tron.tron_tuning_set("csr_unit", 0)
+        try:
+            sub = run_workload(argparse.Namespace(**{**vars(args), "no_cpu_baseline": True, "steps": 2, "warmup": 1}), "c3")
+            out["c3_with_value_stream"] = {"hv_call": sub["hv_call"], "solve_ms": sub["ms_per_step"], "kernels_hv": sub["kernels_hv"],
+                                           "layout": sub["layout"]}
+        finally:
+            tron.tron_tuning_set("csr_unit", 1)
         out["cross_validation"] = cross_validation_configs()
     print(json.dumps(out), flush=True)
     return 0
