@@ -33,7 +33,7 @@ ROCPROF_NAMES = {
     "dense_hv": ("k_dense_hv<6, 4, 4, true, true, false, false>", "dense_hv_fun_grad_c5.md"),
     "dense_fun_grad": ("k_dense_fun_grad<6, 4, 4, true, 1>", "dense_hv_fun_grad_c5.md"),
     # config 3 has one value per instance: its layouts keep no value stream and run the "unit" kernels
-    "spmv_head": ("k_csr_head_unit", "csr_spmv_c3.md"),
+    "spmv_head": ("k_head_sell", "csr_spmv_c3.md"),
     "spmv_fwd": ("k_csr_spmv_part<true, false, false, true>", "csr_spmv_c3.md"),
     "spmv_bwd": ("k_csr_spmv_part<false, false, false, true>", "csr_spmv_c3.md"),
     "spmv_tiles": ("k_hot_tiles_unit", "csr_spmv_c3.md"),

@@ -515,6 +515,14 @@ int tron_tuning_set(const char *name, int64_t value)
         g_tuning.csr_blocks_per_part = value;
         return TRON_OK;
     }
+    if (name && strcmp(name, "csr_sell") == 0 && (value == 0 || value == 1)) {
+        g_tuning.csr_sell = value;
+        return TRON_OK;
+    }
+    if (name && strcmp(name, "csr_sell_blocks") == 0 && value >= 1 && value <= 4096) {
+        g_tuning.csr_sell_blocks = value;
+        return TRON_OK;
+    }
     if (name && strcmp(name, "csr_unit") == 0 && (value == 0 || value == 1)) {
         g_tuning.csr_unit = value;
         return TRON_OK;

@@ -38,6 +38,8 @@ struct Tuning {
     int64_t csr_blocks_per_part = 128;     // persistent workgroups per column range without LDS tables
     int64_t csr_tiles = 1;   // hot-row tiles for the transposed orientation of partitioned matrices (0 = off)
     int64_t csr_tile_blocks_per_slice = 0;   // persistent workgroups per slice of hot rows (0 = automatic: 96, or 128 for unit plans)
+    int64_t csr_sell_blocks = 1024;   // workgroups of the sorted-slice head kernel
+    int64_t csr_sell = 1;    // unit plans: the head partition as sorted slices of 64 rows, one row per lane (0 = as chunks)
     int64_t csr_unit = 1;    // partitioned layouts: drop the value stream when every row of X holds one repeated value (0 = off)
     int64_t dense_device_driver = -1;   // tron_solve on dense d <= 32 without preconditioner driven from the device:
                                         //   0 never, 1 always, -1 automatic (the L2-SVM on matrices up to 1 GB)
@@ -143,8 +145,33 @@ struct alignas(64) GroupBase {
     int32_t first[16];   // kMaxParts used
 };
 
+// Head partition of a unit plan as sorted slices (sliced ELLPACK): the rows are sorted by their number of head entries
+// inside windows of kSellWindow consecutive rows and cut into slices of 64; a slice stores, for each of its rows, the
+// 16-bit LDS slots of the row's entries padded to the slice's longest row (a multiple of 8), in groups of 8 entries
+// per row: a group is 64 x 16 bytes, lane after lane.  A header group precedes the groups of a slice: lane l's 16 bytes
+// hold where the sum of lane l's row goes (int32, -1: no row) and the number of groups that follow (int32).  One lane
+// then sums one row -- no segment bookkeeping at all.  The sums are stored in sorted order, sums[pos[row]] -- the 64 sums
+// of a slice are one 512-byte store; scattered 8-byte stores, one per row, cost a third of the kernel -- and the combine
+// kernels read them through pos (a row's position stays inside its window).  Rows without head entries are never
+// written and stay 0.
+// The slices are dealt to a fixed number of wavefronts (longest first, each to the wavefront with the least work so
+// far) and stored wavefront by wavefront, so that a wavefront reads one contiguous stream of groups.
+constexpr int kSellWindow = 8192;
+constexpr int kSellAhead = 8;     // groups a wavefront keeps in flight; every wavefront's stream is a multiple of it long
+struct SellHead {
+    bool on = false;
+    int nwaves = 0;               // wavefronts the slices were dealt to (= 4 x workgroups of the kernel)
+    int nslices = 0;
+    int64_t *wave_off = nullptr;     // device, nwaves + 1: first group of each wavefront's stream in data
+    uint16_t *data = nullptr;     // device: groups (headers and slots; kHotSlots = the padding slot, whose table entry is 0)
+    double *sums = nullptr;       // device, rows: in sorted order
+    int32_t *pos = nullptr;       // device, rows: where the sum of a row is
+    void release();
+};
+
 struct CsrPlan {
     int64_t rows = 0, cols = 0, nnz = 0;
+    SellHead sell;                       // optional (head partition of a unit plan)
     HotTiles hot;                        // optional (transposed orientation of large matrices)
     int P = 1;                           // number of column ranges (1 = unpartitioned)
     int head = -1;                       // P, when partition P holds the entries of the matrix' most frequent columns

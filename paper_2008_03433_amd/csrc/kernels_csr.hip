@@ -44,9 +44,16 @@ void HotTiles::release()
     *this = HotTiles();
 }
 
+void SellHead::release()
+{
+    hipFree(wave_off); hipFree(data); hipFree(sums); hipFree(pos);
+    *this = SellHead();
+}
+
 void CsrPlan::release()
 {
     hot.release();
+    sell.release();
     hipFree(rowptr); hipFree(col); hipFree(col16); hipFree(val); hipFree(row_lo); hipFree(carry);
     hipFree(xs); hipFree(hot_ids); hipFree(hot_x); hipFree(group_base); hipFree(chunk_tab); hipFree(flags); hipFree(row_mask);
     hipFree(fix_row); hipFree(fix_part); hipFree(fix_b0); hipFree(fix_cnt);
@@ -157,7 +164,9 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
                 }
             }
         }
-        const int NP = (A.head >= 0) ? P + 1 : P;   // partitions in all
+        // unit plans keep the head partition as sorted slices (SellHead) instead of chunks
+        const bool sell = A.unit && A.head >= 0 && g_tuning.csr_sell != 0;
+        const int NP = (A.head >= 0 && !sell) ? P + 1 : P;   // chunked partitions in all
         const int64_t range_nnz = A.nnz - ((A.head >= 0) ? head_nnz : 0);
         // column ranges with equal nonzero counts (head columns excluded): bound[x] = first column of range x
         for (int64_t j = 0; j < cols; ++j) colcount[j + 1] += colcount[j];
@@ -196,7 +205,8 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
         // per-(partition,row) entry counts -> offsets; non-empty pairs are the segments
         std::vector<int32_t> rp32((size_t)NP * (rows + 1), 0);
         for (int64_t r = 0; r < rows; ++r)
-            for (int64_t k = h_rowptr[r]; k < h_rowptr[r + 1]; ++k) rp32[(size_t)part_of[h_col[k]] * (rows + 1) + r + 1]++;
+            for (int64_t k = h_rowptr[r]; k < h_rowptr[r + 1]; ++k)
+                if (part_of[h_col[k]] < NP) rp32[(size_t)part_of[h_col[k]] * (rows + 1) + r + 1]++;
         std::vector<uint16_t> mask((size_t)rows, 0);
         int64_t pos = 0, nseg_total = 0;
         int chunk = 0;
@@ -227,6 +237,7 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
             for (int64_t r = 0; r < rows; ++r) {
                 for (int x = 0; x < NP; ++x) cursor[x] = A.part_base[x] + rp32[(size_t)x * (rows + 1) + r];
                 for (int64_t k = h_rowptr[r]; k < h_rowptr[r + 1]; ++k) {
+                    if (part_of[h_col[k]] >= NP) continue;   // head entries of a plan with sorted slices
                     const int64_t q = cursor[part_of[h_col[k]]]++;
                     pcol[q] = (hot && slot_of[h_col[k]] >= 0) ? ~slot_of[h_col[k]] : h_col[k];   // the head's become 16-bit slots below
                     if (!A.unit) pval[q] = h_val[k];
@@ -281,7 +292,99 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
             TRON_TRY(upload(&A.hot_ids, hot_ids.data(), hot_ids.size(), st));   // unused slots: column 0
             TRON_HIP(hipMalloc(reinterpret_cast<void **>(&A.hot_x), sizeof(double) * hot_ids.size()));
         }
-        if (A.head >= 0) {
+        if (sell) {
+            // ---- sorted slices of the head partition
+            std::vector<int32_t> cnt((size_t)rows, 0);
+            for (int64_t r = 0; r < rows; ++r)
+                for (int64_t k = h_rowptr[r]; k < h_rowptr[r + 1]; ++k)
+                    if (part_of[h_col[k]] == P) cnt[r]++;
+            struct Slice { int32_t len8; int64_t first; };   // first: position of its 64 rows in `order`
+            std::vector<int32_t> order((size_t)rows);
+            std::vector<Slice> slices;
+            for (int64_t w0 = 0; w0 < rows; w0 += kSellWindow) {
+                const int64_t w1 = std::min<int64_t>(rows, w0 + kSellWindow);
+                for (int64_t r = w0; r < w1; ++r) order[r] = (int32_t)r;
+                std::stable_sort(order.begin() + w0, order.begin() + w1, [&](int32_t a, int32_t b) { return cnt[a] > cnt[b]; });
+                for (int64_t s0 = w0; s0 < w1; s0 += kWave) {
+                    const int32_t longest = cnt[order[s0]];
+                    if (longest == 0) break;   // the rest of the window has no head entries
+                    slices.push_back({(longest + 7) / 8, s0});
+                }
+            }
+            std::stable_sort(slices.begin(), slices.end(), [](const Slice &a, const Slice &b) { return a.len8 > b.len8; });
+            SellHead &S = A.sell;
+            S.on = true;
+            S.nslices = (int)slices.size();
+            S.nwaves = (int)std::max<int64_t>(1, std::min<int64_t>(g_tuning.csr_sell_blocks, 4096)) * kWavesPerBlock;
+            // longest first, each slice to the wavefront with the least work so far (ties: the lower wavefront)
+            std::vector<std::vector<int32_t>> mine((size_t)S.nwaves);
+            {
+                std::vector<std::pair<int64_t, int32_t>> heap;   // (-load, -wave): the top is the least loaded, lowest wave
+                for (int w = 0; w < S.nwaves; ++w) heap.emplace_back(0, -w);
+                std::make_heap(heap.begin(), heap.end());
+                for (size_t i = 0; i < slices.size(); ++i) {
+                    std::pop_heap(heap.begin(), heap.end());
+                    auto &top = heap.back();
+                    mine[(size_t)(-top.second)].push_back((int32_t)i);
+                    top.first -= slices[i].len8;
+                    std::push_heap(heap.begin(), heap.end());
+                }
+            }
+            std::vector<int64_t> wave_off((size_t)S.nwaves + 1);
+            std::vector<int64_t> goff(slices.size());    // header group of each slice (in stored order)
+            std::vector<int32_t> stored(slices.size());  // stored position -> index into slices
+            int64_t groups = 0;
+            int32_t sl = 0;
+            std::vector<int64_t> null_groups;   // padding of every stream to a whole number of kSellAhead groups
+            for (int w = 0; w < S.nwaves; ++w) {
+                wave_off[w] = groups;
+                for (int32_t i : mine[(size_t)w]) {
+                    stored[sl] = i;
+                    goff[sl] = groups;
+                    groups += 1 + slices[i].len8;
+                    ++sl;
+                }
+                while ((groups - wave_off[w]) % kSellAhead) null_groups.push_back(groups++);
+            }
+            wave_off[S.nwaves] = groups;
+            std::vector<uint16_t> data((size_t)std::max<int64_t>(groups, 1) * kWave * 8, (uint16_t)kHotSlots);
+            for (int64_t gpad : null_groups)
+                for (int l = 0; l < kWave; ++l) {
+                    const int32_t hdr[4] = {-1, 0, 0, 0};   // a header of a slice without groups
+                    std::memcpy(&data[((size_t)gpad * kWave + l) * 8], hdr, sizeof(hdr));
+                }
+            for (size_t p = 0; p < slices.size(); ++p) {
+                const Slice &sc = slices[stored[p]];
+                const int64_t w1 = std::min<int64_t>(rows, (sc.first / kSellWindow + 1) * (int64_t)kSellWindow);
+                for (int l = 0; l < kWave; ++l) {
+                    int32_t hdr[4] = {-1, sc.len8, 0, 0};
+                    const int64_t pos = sc.first + l;
+                    const int32_t r = (pos < w1) ? order[pos] : -1;
+                    if (r >= 0 && cnt[r] > 0) {
+                        hdr[0] = (int32_t)pos;   // sums are kept in sorted order
+                        int j = 0;
+                        for (int64_t k = h_rowptr[r]; k < h_rowptr[r + 1]; ++k) {
+                            if (part_of[h_col[k]] != P) continue;
+                            // entry j of the row: group 1 + j / 8 of the slice, lane l, place j % 8
+                            data[((size_t)(goff[p] + 1 + j / 8) * kWave + l) * 8 + j % 8] = (uint16_t)slot_of[h_col[k]];
+                            ++j;
+                        }
+                    }
+                    std::memcpy(&data[((size_t)goff[p] * kWave + l) * 8], hdr, sizeof(hdr));
+                }
+            }
+            {
+                std::vector<int32_t> pos_of((size_t)rows);
+                for (int64_t q = 0; q < rows; ++q) pos_of[order[q]] = (int32_t)q;
+                TRON_TRY(upload(&S.pos, pos_of.data(), pos_of.size(), st));
+                TRON_HIP(hipStreamSynchronize(st));
+            }
+            TRON_TRY(upload(&S.wave_off, wave_off.data(), wave_off.size(), st));
+            TRON_TRY(upload(&S.data, data.data(), data.size(), st));
+            TRON_HIP(hipMalloc(reinterpret_cast<void **>(&S.sums), sizeof(double) * (size_t)rows));
+            TRON_HIP(hipMemsetAsync(S.sums, 0, sizeof(double) * (size_t)rows, st));
+            TRON_HIP(hipStreamSynchronize(st));
+        } else if (A.head >= 0) {
             // the head partition is the last one: its columns go to col16, the ranges' stay in col
             const size_t h0 = (size_t)A.part_base[A.head];
             std::vector<uint16_t> c16(pcol.size() - h0, 0);
@@ -793,6 +896,71 @@ __global__ __launch_bounds__(kBlock) void k_csr_head_unit(PartArgs pa, PartPtrs 
     head_unit_body(prod, table, pa, blockIdx.x, gridDim.x, pp);
 }
 
+// Head partition of a unit plan stored as sorted slices (see SellHead).  A wavefront reads its own contiguous stream of
+// groups (64 lanes x 16 bytes = eight 16-bit slots per lane); lane l sums row l of the current slice and writes the
+// sum when the slice ends.  The loads of the next kSellAhead groups are always in flight, also across the ends of
+// slices (they are short: the pipeline must not drain there); a slice's row ids and length come in its header group.  No barrier after the table is filled, no segment bookkeeping.  The sum of a row is
+// (entries 0, 2, 4, ...) + (entries 1, 3, 5, ...), each in storage order.
+__device__ __forceinline__ int64_t uniform64(int64_t v)
+{
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uint64_t)v >> 32));
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
+__global__ __launch_bounds__(kBlock) void k_head_sell(int nwaves, const int64_t *__restrict__ wave_off, const uint16_t *__restrict__ data,
+                                                     const double *__restrict__ hot_x, double *__restrict__ sums)
+{
+    __shared__ __align__(16) double table[kHotSlots + 2];
+    {
+        const double2 *__restrict__ src = reinterpret_cast<const double2 *>(hot_x);
+        for (int k = threadIdx.x; k < kHotSlots / 2; k += kBlock) reinterpret_cast<double2 *>(table)[k] = src[k];
+        if (threadIdx.x == 0) table[kHotSlots] = 0.0;   // the padding slot
+        __syncthreads();
+    }
+    const int lane = threadIdx.x & (kWave - 1);
+    const int w = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+    if (w >= nwaves) return;
+    // everything that steers the loop is kept in scalar registers: a branch on a vector condition would make the compiler
+    // wait for every load in flight where the paths join
+    const int64_t g0 = uniform64(wave_off[w]);
+    const int64_t total = uniform64(wave_off[w + 1]) - g0;   // a multiple of kSellAhead
+    if (total <= 0) return;
+    const v4i *__restrict__ p = reinterpret_cast<const v4i *>(data) + g0 * kWave + lane;
+    v4i buf[kSellAhead];
+#pragma unroll
+    for (int a = 0; a < kSellAhead; ++a) buf[a] = __builtin_nontemporal_load(p + (int64_t)a * kWave);
+    int left = 0;    // groups left in the current slice (0: the next group is a header)
+    int row = -1;
+    double e0 = 0.0, e1 = 0.0;
+    // buffer a holds group g + a: the body is unrolled over the buffers, so no buffer is ever copied (a copy would have to
+    // wait for the load that fills its source); everything a slice needs arrives through this one stream, in order
+    for (int64_t g = 0; g < total; g += kSellAhead) {
+#pragma unroll
+        for (int a = 0; a < kSellAhead; ++a) {
+            const v4i cur = buf[a];
+            const int64_t nx = g + a + kSellAhead;
+            buf[a] = __builtin_nontemporal_load(p + ((nx < total) ? nx : total - 1) * kWave);
+            if (left == 0) {   // a header (a slice without groups is padding)
+                row = cur[0];
+                left = __builtin_amdgcn_readfirstlane(cur[1]);
+            } else {
+#pragma unroll
+                for (int m = 0; m < 4; ++m) {
+                    const unsigned two = (unsigned)cur[m];
+                    e0 += table[two & 0xffffu];
+                    e1 += table[two >> 16];
+                }
+                if (--left == 0) {   // the slice ends
+                    if (row >= 0) sums[row] = e0 + e1;
+                    e0 = 0.0;
+                    e1 = 0.0;
+                }
+            }
+        }
+    }
+}
+
 template <bool HOT, bool HEAD, bool SQ, bool UNIT>
 __global__ __launch_bounds__(kBlock) void k_csr_spmv_part(PartArgs pa, int64_t rows, PartPtrs pp, const double *__restrict__ x)
 {
@@ -1228,6 +1396,8 @@ struct PartialRef {
     const uint16_t *mask;
     const GroupBase *group_base;   // one record per group of 64 rows
     const double *row_scale;       // unit plan of X: the value of row i's entries (null otherwise)
+    const double *head_sums;       // head partition kept as sorted slices: its sums, row r's at head_pos[r] (null otherwise)
+    const int32_t *head_pos;
 };
 
 struct HotRef {
@@ -1242,6 +1412,7 @@ __device__ __forceinline__ double sum_parts(const PartialRef &P, int64_t G, int6
     const unsigned m = valid ? P.mask[r] : 0u;
     const GroupBase gb = P.group_base[G];   // uniform: scalar loads
     double s = 0.0;
+    if (valid && P.head_sums) s = P.head_sums[P.head_pos[r]];
     if (valid && hot.slot_of_row) {
         const int hs = hot.slot_of_row[r];
         if (hs >= 0) s = hot.sums[hs];
@@ -1384,7 +1555,7 @@ static PartArgs head_args(const CsrPlan &A)
 
 static PartialRef partial_ref(const tron_dataset *ds, const CsrPlan &A)
 {
-    return PartialRef{ds->row_partials, A.row_mask, A.group_base, A.row_scale};
+    return PartialRef{ds->row_partials, A.row_mask, A.group_base, A.row_scale, A.sell.on ? A.sell.sums : nullptr, A.sell.on ? A.sell.pos : nullptr};
 }
 
 static PartPtrs part_ptrs(const tron_dataset *ds, const CsrPlan &A)
@@ -1412,7 +1583,11 @@ static int launch_partials(tron_dataset *ds, const CsrPlan &A, int slot, const d
     if (A.head >= 0) {
         ProfScope ps(ds, SLOT_SPMV_HEAD);
         const int grid = std::max(1, std::min(A.part_nchunks[A.head], (int)g_tuning.csr_hot_blocks_per_part * kColParts));
-        if (A.unit)
+        if (A.sell.on) {
+            const SellHead &S = A.sell;
+            hipLaunchKernelGGL(k_head_sell, dim3(S.nwaves / kWavesPerBlock), dim3(kBlock), 0, ds->stream, S.nwaves, S.wave_off, S.data,
+                               A.hot_x + (size_t)A.head * kHotSlots, S.sums);
+        } else if (A.unit)
             hipLaunchKernelGGL(k_csr_head_unit, dim3(grid), dim3(kBlock), kHotSlots * sizeof(double), ds->stream, head_args(A),
                                head_ptrs(ds, A));
         else

@@ -141,7 +141,8 @@ def test_csr_partitioned_layout(rng, loss, force_partitions):
     check_calls(p, loss, 1.0, rng, n_hv=1)
 
 
-@pytest.mark.parametrize("knobs", [{"csr_head": 0}, {"csr_hot": 0}, {"csr_tiles": 0}, {"csr_range_slots": 64}, {"csr_unit": 0},
+@pytest.mark.parametrize("knobs", [{"csr_head": 0}, {"csr_hot": 0}, {"csr_tiles": 0}, {"csr_range_slots": 64}, {"csr_unit": 0}, {"csr_sell": 0},
+                                   {"csr_sell_blocks": 1},
                                    {"csr_unit": 0, "csr_head": 0, "csr_tiles": 0},
                                    {"csr_blocks_per_part": 3, "csr_range_blocks_per_part": 2, "csr_hot_blocks_per_part": 1,
                                     "csr_tile_blocks_per_slice": 2}])
@@ -150,7 +151,7 @@ def test_csr_layout_variants(rng, force_partitions, knobs):
     # partition, no LDS tables, no hot-row tiles, tiny tables, very few persistent workgroups (many chunks each)
     import paper_2008_03433_amd as tron
     # (config 3 has one value per instance: its layouts keep no value stream unless csr_unit = 0; config 2 has free values)
-    defaults = {"csr_head": 1, "csr_hot": 1, "csr_tiles": 1, "csr_range_slots": 4096, "csr_unit": 1, "csr_blocks_per_part": 128,
+    defaults = {"csr_head": 1, "csr_hot": 1, "csr_tiles": 1, "csr_range_slots": 4096, "csr_unit": 1, "csr_sell": 1, "csr_sell_blocks": 1024, "csr_blocks_per_part": 128,
                 "csr_range_blocks_per_part": 96, "csr_hot_blocks_per_part": 96, "csr_tile_blocks_per_slice": 0}
     try:
         for k, v in knobs.items():
