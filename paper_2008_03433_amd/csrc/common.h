@@ -37,7 +37,7 @@ struct Tuning {
     int64_t csr_hot_blocks_per_part = 96;  // persistent workgroups per partition when the LDS table is used
     int64_t csr_blocks_per_part = 128;     // persistent workgroups per column range without LDS tables
     int64_t csr_tiles = 1;   // hot-row tiles for the transposed orientation of partitioned matrices (0 = off)
-    int64_t csr_tile_blocks_per_slice = 0;   // persistent workgroups per slice of hot rows (0 = automatic: 96, or 128 for unit plans)
+    int64_t csr_tile_blocks_per_slice = 0;   // persistent workgroups per slice of hot rows (0 = automatic: 96, or 160 for unit plans)
     int64_t csr_sell_blocks = 1024;   // workgroups of the sorted-slice head kernel
     int64_t csr_sell = 1;    // unit plans: the head partition as sorted slices of 64 rows, one row per lane (0 = as chunks)
     int64_t csr_unit = 1;    // partitioned layouts: drop the value stream when every row of X holds one repeated value (0 = off)

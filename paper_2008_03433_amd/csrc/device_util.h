@@ -86,9 +86,12 @@ __device__ __forceinline__ int wave_scan_add(int c)
 template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ void seg_scan_step(double &t, int &h)
 {
-    const double st = dpp_f64<CTRL, ROW_MASK>(t);
+    // h is 0 or 1: the mask keeps the incoming sum only while no run has ended up to this lane (t + 0.0 is t)
+    const int open = h - 1;
+    const int lo = dpp_int<CTRL, ROW_MASK>(__double2loint(t)) & open;
+    const int hi = dpp_int<CTRL, ROW_MASK>(__double2hiint(t)) & open;
     const int sh = dpp_int<CTRL, ROW_MASK>(h);
-    t = h ? t : t + st;
+    t += __hiloint2double(hi, lo);
     h |= sh;
 }
 

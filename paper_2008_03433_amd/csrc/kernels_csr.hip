@@ -663,11 +663,13 @@ __device__ __forceinline__ void runs_from_regs(double *prod, const unsigned f, d
 {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     double run = 0.0;
+    const unsigned nf = ~f;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         run += p[e];
         p[e] = run;
-        if ((f >> e) & 1u) run = 0.0;
+        const int keep = (int)(nf << (31 - e)) >> 31;   // all ones unless entry e ends a segment
+        run = __hiloint2double(__double2hiint(run) & keep, __double2loint(run) & keep);
     }
     const int cnt = __popc(f);
     double t = run;
@@ -971,6 +973,7 @@ __global__ __launch_bounds__(kBlock) void k_csr_spmv_part(PartArgs pa, int64_t r
 
 // ------------------------------------------------------------------ hot-row tiles (see HotTiles)
 constexpr int kMaxTileBlocks = 256;   // workgroups per slice
+constexpr int kTileWindow = 512;      // columns a tile of a unit plan may span (two per thread)
 
 int hot_tiles_build(CsrPlan &A, const int64_t *t_rowptr, const int32_t *t_col, const double *t_val,
                     const std::vector<int32_t> &slot_code, int nhot, hipStream_t st)
@@ -1007,10 +1010,13 @@ int hot_tiles_build(CsrPlan &A, const int64_t *t_rowptr, const int32_t *t_col, c
             }
         }
         while (sslot[s].size() % 8) sslot[s].push_back(0);
+        for (const Entry &x : e) h.z = std::max<int>(h.z, x.iloc + 1);   // columns the tile spans
         hdrs[s].push_back(h);
         e.clear();
     };
 
+    // a unit plan gathers from a copy of the tile's columns in LDS: a tile spans at most kTileWindow of them
+    const int64_t span = unit ? kTileWindow : 65536;
     int cnt[kTileSlices];
     for (int64_t i = 0; i < A.cols; ++i) {
         for (int s = 0; s < kTileSlices; ++s) cnt[s] = 0;
@@ -1020,7 +1026,7 @@ int hot_tiles_build(CsrPlan &A, const int64_t *t_rowptr, const int32_t *t_col, c
         }
         for (int s = 0; s < kTileSlices; ++s) {
             if (!cnt[s]) continue;
-            if ((int)cur[s].size() + cnt[s] > kChunk || (!cur[s].empty() && i - base[s] > 65535)) close_tile(s);
+            if ((int)cur[s].size() + cnt[s] > kChunk || (!cur[s].empty() && i - base[s] >= span)) close_tile(s);
             if (cur[s].empty()) base[s] = i;
         }
         for (int64_t k = t_rowptr[i]; k < t_rowptr[i + 1]; ++k) {
@@ -1062,8 +1068,9 @@ int hot_tiles_build(CsrPlan &A, const int64_t *t_rowptr, const int32_t *t_col, c
     TRON_TRY(upload(&H.slot_of_row, slot_code.data(), slot_code.size(), st));
     int64_t maxt = 0;
     for (int s = 0; s < kTileSlices; ++s) maxt = std::max(maxt, H.ntiles[s]);
-    // 0 = automatic: 3 workgroups per CU with values (the kernel is then bound by HBM), 4 without (bound by issue and latency)
-    const int64_t want_blocks = g_tuning.csr_tile_blocks_per_slice > 0 ? g_tuning.csr_tile_blocks_per_slice : (A.unit ? 128 : 96);
+    // 0 = automatic: 3 workgroups per CU with values (the kernel is then bound by HBM), 5 without (as many as fit in LDS:
+    // the kernel is bound by instruction issue and LDS latency)
+    const int64_t want_blocks = g_tuning.csr_tile_blocks_per_slice > 0 ? g_tuning.csr_tile_blocks_per_slice : (A.unit ? 160 : 96);
     H.blocks_per_slice = (int)std::max<int64_t>(1, std::min<int64_t>(maxt, std::min<int64_t>(want_blocks, kMaxTileBlocks)));
     TRON_HIP(hipMalloc(reinterpret_cast<void **>(&H.wg_acc), sizeof(double) * kTileSlices * H.blocks_per_slice * kTileSlots));
     TRON_HIP(hipMalloc(reinterpret_cast<void **>(&H.sums), sizeof(double) * kTileSlices * kTileSlots));
@@ -1186,28 +1193,94 @@ __device__ __forceinline__ void tiles_body(double *prod, uint16_t *slots, double
 }
 
 // The tiles of a unit plan: an entry is a 16-bit column offset and nothing else; thread t loads the offsets of entries
-// 8t .. 8t+7 with one 16-byte load and gathers x straight into the registers the segment sums start from.
+// 8t .. 8t+7 with one 16-byte load.  A tile spans at most kTileWindow columns: the workgroup copies them from x into
+// LDS with two coalesced loads per thread and gathers from the copy -- the gathers of a tile go to a few hundred
+// consecutive doubles, and the vector memory pipeline, which handles about one lane of such a gather per clock, was
+// what bound this kernel when they went to x itself.
 struct TileRegsU {
     v4i il;             // eight 16-bit local column offsets
     uint4 slots;
     unsigned flags;
+    double w[2];        // the two columns of the tile that the thread copies into LDS
     int4 hdr;
 };
 
-__device__ __forceinline__ TileRegsU load_tile_unit(const TilePtrs &tp, int4 h, int64_t T)
+// the data of tile T, whose header is h; columns clamped to the tile's last one
+__device__ __forceinline__ void load_tile_unit(TileRegsU &r, const TilePtrs &tp, const double *__restrict__ x, int4 h, int64_t T)
 {
-    TileRegsU r;
+    const int tid = threadIdx.x;
     r.hdr = h;
-    r.il = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(tp.iloc + T * kChunk + 8 * threadIdx.x));
-    r.flags = tp.flags[T * kBlock + threadIdx.x];
+    r.il = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(tp.iloc + T * kChunk + 8 * tid));
+    r.flags = tp.flags[T * kBlock + tid];
     const int nseg = h.y;
-    const int64_t d0 = (int64_t)h.w + ((8 * (int)threadIdx.x < nseg) ? 8 * (int)threadIdx.x : 0);
+    const int64_t d0 = (int64_t)h.w + ((8 * tid < nseg) ? 8 * tid : 0);
     r.slots = *reinterpret_cast<const uint4 *>(tp.seg_slot + d0);
-    return r;
+    const int lastc = h.z - 1;
+    const double *xt = x + h.x;
+    r.w[0] = xt[tid < lastc ? tid : lastc];
+    r.w[1] = xt[tid + kBlock < lastc ? tid + kBlock : lastc];
 }
 
-__device__ __forceinline__ void tiles_unit_body(double *prod, uint16_t *slots, double *acc, const TileArgs &ta, const int s, const int q,
-                                                const int B, const TilePtrs &tp, const double *__restrict__ x)
+__device__ __forceinline__ void store_window(double *window, const TileRegsU &r)
+{
+    window[threadIdx.x] = r.w[0];
+    window[threadIdx.x + kBlock] = r.w[1];
+}
+
+// One tile: cur is reduced (its columns are in window[BUF]) while the data of the next tile of the workgroup, whose
+// header is ahead, are loaded into nxt; they are not waited for before the end of the step, where the columns go to
+// the other window buffer.  ahead becomes the header of the tile after that.
+template <int BUF>
+__device__ __forceinline__ void tile_step_unit(double *prod, uint16_t *slots, double *acc, double (*window)[kTileWindow], TileRegsU &cur,
+                                               TileRegsU &nxt, int4 &ahead, const TilePtrs &tp, const double *__restrict__ x,
+                                               const int64_t Tn, const int64_t Tnn)
+{
+    const int tid = threadIdx.x;
+    const int nseg = cur.hdr.y;
+    __builtin_amdgcn_sched_barrier(0);
+    load_tile_unit(nxt, tp, x, ahead, Tn);
+    ahead = load_uniform(tp.hdr + Tnn);
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();
+    // every thread is past the accumulator updates and the totals of the tile before, and this tile's columns are
+    // in window[BUF]
+    double p[8], cin;
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+        const unsigned two = (unsigned)cur.il[m];
+        p[2 * m] = window[BUF][two & 0xffffu];
+        p[2 * m + 1] = window[BUF][two >> 16];
+    }
+    if (8 * tid < nseg) *reinterpret_cast<uint4 *>(slots + 8 * tid) = cur.slots;
+    int idx0;
+    runs_from_regs(prod, cur.flags, p, cin, idx0);   // barrier inside: the slots are visible after it
+    // What the threads before add to the thread's first segment goes in on its own.  The thread's segments have
+    // distinct slots, so their updates are independent: all slot reads, then all accumulator reads, then all writes.
+    if (cur.flags) acc[slots[idx0]] += cin;
+    int sl[8];
+    double a[8];
+    int i = idx0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        sl[e] = slots[i];   // an entry that ends no segment reads a slot it does not use (then i < 2048: there are fewer segments than entries)
+        i += (cur.flags >> e) & 1u;
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        if ((cur.flags >> e) & 1u) a[e] = acc[sl[e]];
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        if ((cur.flags >> e) & 1u) acc[sl[e]] = a[e] + p[e];
+    // the other buffer was last read before the barrier inside runs_from_regs of the step before
+    store_window(window[BUF ^ 1], nxt);
+}
+
+// Persistent workgroup (slice s, q): tiles q, q + B, ... of the slice, two steps per iteration so that the two sets of
+// tile registers and the two window buffers swap roles without copies (indices clamped to the last tile, so every
+// step issues the same loads).
+__device__ __forceinline__ void tiles_unit_body(double *prod, uint16_t *slots, double *acc, double (*window)[kTileWindow],
+                                                const TileArgs &ta, const int s, const int q, const int B, const TilePtrs &tp,
+                                                const double *__restrict__ x)
 {
     const int tid = threadIdx.x;
     for (int k = tid; k < kTileSlots; k += kBlock) acc[k] = 0.0;
@@ -1216,49 +1289,14 @@ __device__ __forceinline__ void tiles_unit_body(double *prod, uint16_t *slots, d
         const int64_t T0 = ta.tile0[s];
         const int64_t last = nt - 1;
         auto clampt = [&](int64_t t) { return T0 + (t < last ? t : last); };
-        auto gather8 = [&](const TileRegsU &r, double (&g)[8]) {
-            const double *xt = x + r.hdr.x;   // the tile's first column
-#pragma unroll
-            for (int m = 0; m < 4; ++m) {
-                const unsigned two = (unsigned)r.il[m];
-                g[2 * m] = xt[two & 0xffffu];
-                g[2 * m + 1] = xt[two >> 16];
-            }
-        };
-        TileRegsU cur = load_tile_unit(tp, load_uniform(tp.hdr + clampt(q)), clampt(q));
-        TileRegsU nxt = load_tile_unit(tp, load_uniform(tp.hdr + clampt(q + B)), clampt(q + B));
-        int4 hdr2 = load_uniform(tp.hdr + clampt(q + 2 * (int64_t)B));
-        double p[8], pn[8], cin;
-        gather8(cur, p);
-        for (int64_t t = q; t < nt; t += B) {
-            const int nseg = cur.hdr.y;
-            // the gathers of the next tile and the data of the one after it are issued before this tile is reduced:
-            // neither a gather nor a stream load is waited for in the iteration that issues it
-            __builtin_amdgcn_sched_barrier(0);
-            gather8(nxt, pn);
-            const TileRegsU nn = load_tile_unit(tp, hdr2, clampt(t + 2 * (int64_t)B));
-            const int4 hdr3 = load_uniform(tp.hdr + clampt(t + 3 * (int64_t)B));
-            __builtin_amdgcn_sched_barrier(0);
-            __syncthreads();
-            // every thread is past the accumulator updates and the totals of the tile before
-            if (8 * tid < nseg) *reinterpret_cast<uint4 *>(slots + 8 * tid) = cur.slots;
-            int idx0;
-            runs_from_regs(prod, cur.flags, p, cin, idx0);   // barrier inside: the slots are visible after it
-            int i = idx0;
-            bool first = true;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                if ((cur.flags >> e) & 1u) {
-                    acc[slots[i]] += first ? p[e] + cin : p[e];
-                    first = false;
-                    ++i;
-                }
-            }
-            cur = nxt;
-            nxt = nn;
-            hdr2 = hdr3;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) p[e] = pn[e];
+        TileRegsU r0, r1;
+        load_tile_unit(r0, tp, x, load_uniform(tp.hdr + clampt(q)), clampt(q));
+        int4 ahead = load_uniform(tp.hdr + clampt(q + B));
+        store_window(window[0], r0);
+        for (int64_t t = q; t < nt; t += 2 * (int64_t)B) {
+            tile_step_unit<0>(prod, slots, acc, window, r0, r1, ahead, tp, x, clampt(t + B), clampt(t + 2 * (int64_t)B));
+            if (t + B >= nt) break;
+            tile_step_unit<1>(prod, slots, acc, window, r1, r0, ahead, tp, x, clampt(t + 2 * (int64_t)B), clampt(t + 3 * (int64_t)B));
         }
     }
     __syncthreads();
@@ -1271,7 +1309,9 @@ __global__ __launch_bounds__(kBlock) void k_hot_tiles_unit(TileArgs ta, int B, T
     __shared__ __align__(16) double prod[kOutOffset];   // the wavefront totals only
     __shared__ __align__(16) uint16_t slots[kChunk];
     __shared__ double acc[kTileSlots];
-    tiles_unit_body(prod, slots, acc, ta, blockIdx.x % kTileSlices, blockIdx.x / kTileSlices, B, tp, x);
+    __shared__ double window[2][kTileWindow];
+    static_assert(kTileWindow == 2 * kBlock, "two columns per thread");
+    tiles_unit_body(prod, slots, acc, window, ta, blockIdx.x % kTileSlices, blockIdx.x / kTileSlices, B, tp, x);
 }
 
 template <bool SQ, bool UNIT>
