@@ -80,6 +80,10 @@ def load_library():
         if not os.path.exists(_LIB_PATH):
             raise ImportError(f"{_LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
                               "(or paper_2008_03433_amd/build.py) first; there is no CPU fallback")
+        # torch first: it carries its own copy of the HIP runtime, and the tensors this binding passes are allocated by
+        # that copy.  Loaded afterwards, the library resolves its HIP calls against the runtime already in the process
+        # instead of bringing in a second one that knows nothing of those allocations.
+        import torch  # noqa: F401
         lib = ctypes.CDLL(_LIB_PATH)
         for name, (res, args) in _SIGNATURES.items():
             fn = getattr(lib, name)

@@ -190,6 +190,18 @@ def test_csr_one_value_per_instance(rng, loss, force_partitions):
     Bn[:, 11] = 1.0
     pn = _csr_from_dense(Bn / np.sqrt(Bn.sum(axis=1))[:, None], y)
     compare_solves(pn, loss, 1.0, 1e-4, trace_rel=1e-6)
+    # many instances, few features: a tile of the transposed product fills up slowly, so the limit on the columns it may
+    # span (they are copied into LDS) closes it first
+    nt, dt = 20000, 300
+    Bt = (rng.random((nt, dt)) < 0.01).astype(np.float64)
+    Bt[:, 5] = 1.0
+    pt = _csr_from_dense(Bt * np.exp(rng.standard_normal(nt))[:, None], np.where(rng.random(nt) < 0.5, 1.0, -1.0))
+    ds = tron.Dataset.from_problem(pt)
+    assert tron.tron_dataset_stat(ds.handle, "unit_values") == 1
+    tiles, tile_nnz = tron.tron_dataset_stat(ds.handle, "bwd_tiles"), tron.tron_dataset_stat(ds.handle, "bwd_tile_nnz")
+    ds.close()
+    assert tiles > 0 and tile_nnz / tiles < 0.8 * 2048, (tiles, tile_nnz)   # not filled: closed by the span limit
+    check_calls(pt, loss, 0.5, rng, w_scale=0.3, n_hv=2)
     X2 = B * r[:, None]
     X2[7, 5] *= 1.5
     p2 = _csr_from_dense(X2, y)
