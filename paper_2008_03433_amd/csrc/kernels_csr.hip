@@ -16,8 +16,8 @@
 //   - forward orientation: a head partition (the most frequent columns of the whole matrix, served from
 //     one LDS table, 16-bit slots, whole rows) and 8 column ranges, workgroup b on range b % 8 so that
 //     each XCD's L2 gathers from its own slice of the vector; each range has an LDS table of its own;
-//   - transposed orientation: hot-row tiles (see HotTiles: LDS accumulators, gathers that stay in L1)
-//     and 8 column ranges for the rest.
+//   - transposed orientation: hot-row tiles (see HotTiles: LDS accumulators, gathers that stay in L1, or,
+//     without a value stream, go to a copy of the tile's columns in LDS) and 8 column ranges for the rest.
 // Partitions write one partial sum per segment; combine kernels add a row's partial sums in a fixed
 // order and apply the epilogue (loss terms, D scaling, v + C * sum) and the first stage of the scalar
 // reductions.
