@@ -114,8 +114,10 @@ static int alloc_common(tron_dataset *ds)
     }
     ds->partials_len = need;
     TRON_HIP(hipMalloc(reinterpret_cast<void **>(&ds->partials), sizeof(double) * need));
-    TRON_HIP(hipMalloc(reinterpret_cast<void **>(&ds->scal_dev), sizeof(double) * kScalars));
-    TRON_HIP(hipHostMalloc(reinterpret_cast<void **>(&ds->scal_host), sizeof(double) * kScalars, hipHostMallocDefault));
+    // The scalars the host steers by live in pinned host memory that the kernels write directly: they are there when
+    // the stream has drained, without a copy operation between the last kernel and the host's wait.
+    TRON_HIP(hipHostMalloc(reinterpret_cast<void **>(&ds->scal_host), sizeof(double) * kScalars, hipHostMallocMapped));
+    TRON_HIP(hipHostGetDevicePointer(reinterpret_cast<void **>(&ds->scal_dev), ds->scal_host, 0));
     ds->vec_grid_n = vec_grid_for(ds->n);
     ds->vec_grid_d = vec_grid_for(ds->d);
     return TRON_OK;
@@ -167,7 +169,7 @@ void tron_dataset_destroy(tron_dataset *ds)
     ds->fwd.release();
     ds->bwd.release();
     hipFree(ds->y); hipFree(ds->y8); hipFree(ds->z); hipFree(ds->zhat); hipFree(ds->Dbuf[0]); hipFree(ds->Dbuf[1]);
-    hipFree(ds->partials); hipFree(ds->row_partials); hipFree(ds->scal_dev); hipFree(ds->unit_scale);
+    hipFree(ds->partials); hipFree(ds->row_partials); hipFree(ds->unit_scale);
     if (ds->scal_host) hipHostFree(ds->scal_host);
     for (double *p : ds->sv) hipFree(p);
     ds->prof.destroy();

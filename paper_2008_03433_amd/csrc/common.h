@@ -250,8 +250,8 @@ struct tron_dataset {
     double *row_partials = nullptr;  // sparse, partitioned: P x max(n, d) partial row sums
     double *partials = nullptr;  // device scratch for first-stage partial sums
     int64_t partials_len = 0;
-    double *scal_dev = nullptr;  // kScalars device scalars
-    double *scal_host = nullptr; // kScalars pinned host scalars
+    double *scal_host = nullptr; // kScalars pinned host scalars, mapped into the device's address space
+    double *scal_dev = nullptr;  // the device address of scal_host (kernels write the scalars there)
     int dense_grid = 0;          // workgroups of the dense kernels
     int vec_grid_n = 0, vec_grid_d = 0;  // workgroups of elementwise kernels over n / d
 
@@ -283,7 +283,7 @@ int reduce_final(tron_dataset *ds, int nslots, int count, int stride, int first_
 int dot_partials(tron_dataset *ds, int64_t m, const double *a0, const double *b0, const double *a1, const double *b1,
                  const double *a2, const double *b2);
 int loss_terms(tron_dataset *ds, int loss, const double *z, double *zhat, double *D);  // partial slot 0 = sum loss
-int read_scalars(tron_dataset *ds, int count);  // D2H of scal_dev[0..count) + stream sync
+int read_scalars(tron_dataset *ds, int count);  // stream sync; then scal_host[0..count) holds what the kernels wrote
 // CG vector kernels (see solver.hip); M = diagonal preconditioner or null
 int cg_init(tron_dataset *ds, const double *g, const double *M, double *s, double *r, double *p);  // M: slot0 = g.(g/M); returns #partials
 int cg_step(tron_dataset *ds, double alpha, const double *p, const double *Hp, const double *M, double *s, double *r);  // slot0 = r.r | r.(r/M)
