@@ -1205,6 +1205,14 @@ struct TileRegsU {
     int4 hdr;
 };
 
+// *a += v with the LDS add instruction: one operation instead of a read, an add and a write, and nothing to wait for.
+// Used where no two lanes address the same word between two barriers and a lane's own additions to one word are issued
+// in program order (LDS operations of a wavefront complete in order), so the sum is built in a fixed order.
+__device__ __forceinline__ void lds_add(double *a, double v)
+{
+    (void)__hip_atomic_fetch_add(a, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
 // the data of tile T, whose header is h; columns clamped to the tile's last one
 __device__ __forceinline__ void load_tile_unit(TileRegsU &r, const TilePtrs &tp, const double *__restrict__ x, int4 h, int64_t T)
 {
@@ -1254,23 +1262,18 @@ __device__ __forceinline__ void tile_step_unit(double *prod, uint16_t *slots, do
     if (8 * tid < nseg) *reinterpret_cast<uint4 *>(slots + 8 * tid) = cur.slots;
     int idx0;
     runs_from_regs(prod, cur.flags, p, cin, idx0);   // barrier inside: the slots are visible after it
-    // What the threads before add to the thread's first segment goes in on its own.  The thread's segments have
-    // distinct slots, so their updates are independent: all slot reads, then all accumulator reads, then all writes.
-    if (cur.flags) acc[slots[idx0]] += cin;
+    // What the threads before add to the thread's first segment goes in on its own, before the segment's own sum.
     int sl[8];
-    double a[8];
     int i = idx0;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         sl[e] = slots[i];   // an entry that ends no segment reads a slot it does not use (then i < 2048: there are fewer segments than entries)
         i += (cur.flags >> e) & 1u;
     }
+    if (cur.flags) lds_add(acc + sl[0], cin);   // sl[0] is the slot of the thread's first segment
 #pragma unroll
     for (int e = 0; e < 8; ++e)
-        if ((cur.flags >> e) & 1u) a[e] = acc[sl[e]];
-#pragma unroll
-    for (int e = 0; e < 8; ++e)
-        if ((cur.flags >> e) & 1u) acc[sl[e]] = a[e] + p[e];
+        if ((cur.flags >> e) & 1u) lds_add(acc + sl[e], p[e]);
     // the other buffer was last read before the barrier inside runs_from_regs of the step before
     store_window(window[BUF ^ 1], nxt);
 }
