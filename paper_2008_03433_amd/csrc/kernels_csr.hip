@@ -1102,7 +1102,6 @@ struct TilePtrs {
 };
 
 // data of tile T whose header h is already in registers
-template <bool UNIT>
 __device__ __forceinline__ TileRegs load_tile(const TilePtrs &tp, int4 h, int64_t T)
 {
     TileRegs r;
@@ -1110,7 +1109,7 @@ __device__ __forceinline__ TileRegs load_tile(const TilePtrs &tp, int4 h, int64_
 #pragma unroll
     for (int m = 0; m < 4; ++m) {
         const int64_t k = T * kChunk + m * kQuarter + threadIdx.x * 2;
-        if constexpr (!UNIT) r.v[m] = __builtin_nontemporal_load(reinterpret_cast<const v2d *>(tp.val + k));
+        r.v[m] = __builtin_nontemporal_load(reinterpret_cast<const v2d *>(tp.val + k));
         r.il[m] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(tp.iloc + k));
     }
     r.flags = tp.flags[T * kBlock + threadIdx.x];
@@ -1125,7 +1124,7 @@ __device__ __forceinline__ TileRegs load_tile(const TilePtrs &tp, int4 h, int64_
 // Software pipeline: while tile t is reduced, the data of tiles t + B and t + 2B and the header of tile t + 3B are
 // in flight (all indices clamped to the last tile, so every iteration issues the same loads).
 // Slots inside a tile are distinct, so the accumulator updates of different segments never collide.
-template <bool SQ, bool UNIT>
+template <bool SQ>
 __device__ __forceinline__ void tiles_body(double *prod, uint16_t *slots, double *acc, const TileArgs &ta, const int s, const int q,
                                            const int B, const TilePtrs &tp, const double *__restrict__ x)
 {
@@ -1136,8 +1135,8 @@ __device__ __forceinline__ void tiles_body(double *prod, uint16_t *slots, double
         const int64_t T0 = ta.tile0[s];
         const int64_t last = nt - 1;
         auto clampt = [&](int64_t t) { return T0 + (t < last ? t : last); };
-        TileRegs cur = load_tile<UNIT>(tp, load_uniform(tp.hdr + clampt(q)), clampt(q));
-        TileRegs nxt = load_tile<UNIT>(tp, load_uniform(tp.hdr + clampt(q + B)), clampt(q + B));
+        TileRegs cur = load_tile(tp, load_uniform(tp.hdr + clampt(q)), clampt(q));
+        TileRegs nxt = load_tile(tp, load_uniform(tp.hdr + clampt(q + B)), clampt(q + B));
         int4 hdr2 = load_uniform(tp.hdr + clampt(q + 2 * (int64_t)B));
         for (int64_t t = q; t < nt; t += B) {
             const int nseg = cur.hdr.y;
@@ -1152,17 +1151,12 @@ __device__ __forceinline__ void tiles_body(double *prod, uint16_t *slots, double
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
                 double2 p;
-                if constexpr (UNIT) {
-                    p.x = xg[m][0];
-                    p.y = xg[m][1];
-                } else {
-                    p.x = (SQ ? cur.v[m].x * cur.v[m].x : cur.v[m].x) * xg[m][0];
-                    p.y = (SQ ? cur.v[m].y * cur.v[m].y : cur.v[m].y) * xg[m][1];
-                }
+                p.x = (SQ ? cur.v[m].x * cur.v[m].x : cur.v[m].x) * xg[m][0];
+                p.y = (SQ ? cur.v[m].y * cur.v[m].y : cur.v[m].y) * xg[m][1];
                 *reinterpret_cast<double2 *>(prod + prod_pos(m * kQuarter + tid * 2)) = p;
             }
             __builtin_amdgcn_sched_barrier(0);
-            const TileRegs nn = load_tile<UNIT>(tp, hdr2, clampt(t + 2 * (int64_t)B));
+            const TileRegs nn = load_tile(tp, hdr2, clampt(t + 2 * (int64_t)B));
             const int4 hdr3 = load_uniform(tp.hdr + clampt(t + 3 * (int64_t)B));
             __builtin_amdgcn_sched_barrier(0);
             __syncthreads();
@@ -1318,13 +1312,13 @@ __global__ __launch_bounds__(kBlock) void k_hot_tiles_unit(TileArgs ta, int B, T
     tiles_unit_body(prod, slots, acc, window, ta, blockIdx.x % kTileSlices, blockIdx.x / kTileSlices, B, tp, x);
 }
 
-template <bool SQ, bool UNIT>
+template <bool SQ>
 __global__ __launch_bounds__(kBlock) void k_hot_tiles(TileArgs ta, int B, TilePtrs tp, const double *__restrict__ x)
 {
     __shared__ __align__(16) double prod[kProdDoubles];
     __shared__ __align__(16) uint16_t slots[kChunk];
     __shared__ double acc[kTileSlots];
-    tiles_body<SQ, UNIT>(prod, slots, acc, ta, blockIdx.x % kTileSlices, blockIdx.x / kTileSlices, B, tp, x);
+    tiles_body<SQ>(prod, slots, acc, ta, blockIdx.x % kTileSlices, blockIdx.x / kTileSlices, B, tp, x);
 }
 
 // sums[s*K + k] = sum over the B workgroups of slice s: four quarter sums (workgroup order inside each), added in
@@ -1370,10 +1364,10 @@ static int launch_hot_tiles(tron_dataset *ds, const CsrPlan &A, const double *x,
             hipLaunchKernelGGL(k_hot_tiles_unit, dim3(kTileSlices * H.blocks_per_slice), dim3(kBlock), 0, st, tile_args(H),
                                H.blocks_per_slice, tile_ptrs(H), x);
         else if (square)
-            hipLaunchKernelGGL((k_hot_tiles<true, false>), dim3(kTileSlices * H.blocks_per_slice), dim3(kBlock), 0, st, tile_args(H),
+            hipLaunchKernelGGL((k_hot_tiles<true>), dim3(kTileSlices * H.blocks_per_slice), dim3(kBlock), 0, st, tile_args(H),
                                H.blocks_per_slice, tile_ptrs(H), x);
         else
-            hipLaunchKernelGGL((k_hot_tiles<false, false>), dim3(kTileSlices * H.blocks_per_slice), dim3(kBlock), 0, st, tile_args(H),
+            hipLaunchKernelGGL((k_hot_tiles<false>), dim3(kTileSlices * H.blocks_per_slice), dim3(kBlock), 0, st, tile_args(H),
                                H.blocks_per_slice, tile_ptrs(H), x);
         TRON_HIP(hipGetLastError());
     }
