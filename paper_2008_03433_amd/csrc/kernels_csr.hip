@@ -17,8 +17,8 @@
 //   - forward orientation: a head partition (the most frequent columns of the whole matrix, served from
 //     one LDS table, 16-bit slots, whole rows) and 8 column ranges, workgroup b on range b % 8 so that
 //     each XCD's L2 gathers from its own slice of the vector; each range has an LDS table of its own;
-//   - transposed orientation: hot-row tiles (see HotTiles: LDS accumulators, gathers that stay in L1, or,
-//     without a value stream, go to a copy of the tile's columns in LDS) and 8 column ranges for the rest.
+//   - transposed orientation: hot-row tiles (see HotTiles: LDS accumulators, gathers from a copy of the tile's
+//     columns in LDS) and 8 column ranges for the rest.
 // Partitions write one partial sum per segment; combine kernels add a row's partial sums in a fixed
 // order and apply the epilogue (loss terms, D scaling, v + C * sum) and the first stage of the scalar
 // reductions.
@@ -974,7 +974,7 @@ __global__ __launch_bounds__(kBlock) void k_csr_spmv_part(PartArgs pa, int64_t r
 
 // ------------------------------------------------------------------ hot-row tiles (see HotTiles)
 constexpr int kMaxTileBlocks = 256;   // workgroups per slice
-constexpr int kTileWindow = 512;      // columns a tile of a unit plan may span (two per thread)
+constexpr int kTileWindow = 512;      // columns a tile may span (two per thread)
 
 int hot_tiles_build(CsrPlan &A, const int64_t *t_rowptr, const int32_t *t_col, const double *t_val,
                     const std::vector<int32_t> &slot_code, int nhot, hipStream_t st)
@@ -1016,8 +1016,8 @@ int hot_tiles_build(CsrPlan &A, const int64_t *t_rowptr, const int32_t *t_col, c
         e.clear();
     };
 
-    // a unit plan gathers from a copy of the tile's columns in LDS: a tile spans at most kTileWindow of them
-    const int64_t span = unit ? kTileWindow : 65536;
+    // the kernels gather from a copy of the tile's columns in LDS: a tile spans at most kTileWindow of them
+    const int64_t span = kTileWindow;
     int cnt[kTileSlices];
     for (int64_t i = 0; i < A.cols; ++i) {
         for (int s = 0; s < kTileSlices; ++s) cnt[s] = 0;
@@ -1089,6 +1089,7 @@ struct TileRegs {
     uint32_t il[4];     // two 16-bit local column offsets each
     uint4 slots;        // slots of the segments 8*tid .. 8*tid+7 (16 bits each)
     unsigned flags;     // bit e: entry 8*tid + e is the last of its segment
+    double w[2];        // the two columns of the tile that the thread copies into LDS
     int4 hdr;
 };
 
@@ -1101,11 +1102,17 @@ struct TilePtrs {
     double *wg_acc;
 };
 
-// data of tile T whose header h is already in registers
-__device__ __forceinline__ TileRegs load_tile(const TilePtrs &tp, int4 h, int64_t T)
+// data of tile T whose header h is already in registers; columns clamped to the tile's last one
+__device__ __forceinline__ TileRegs load_tile(const TilePtrs &tp, const double *__restrict__ x, int4 h, int64_t T)
 {
     TileRegs r;
     r.hdr = h;
+    {
+        const int tid = threadIdx.x, lastc = h.z - 1;
+        const double *xt = x + h.x;
+        r.w[0] = xt[tid < lastc ? tid : lastc];
+        r.w[1] = xt[tid + kBlock < lastc ? tid + kBlock : lastc];
+    }
 #pragma unroll
     for (int m = 0; m < 4; ++m) {
         const int64_t k = T * kChunk + m * kQuarter + threadIdx.x * 2;
@@ -1125,8 +1132,8 @@ __device__ __forceinline__ TileRegs load_tile(const TilePtrs &tp, int4 h, int64_
 // in flight (all indices clamped to the last tile, so every iteration issues the same loads).
 // Slots inside a tile are distinct, so the accumulator updates of different segments never collide.
 template <bool SQ>
-__device__ __forceinline__ void tiles_body(double *prod, uint16_t *slots, double *acc, const TileArgs &ta, const int s, const int q,
-                                           const int B, const TilePtrs &tp, const double *__restrict__ x)
+__device__ __forceinline__ void tiles_body(double *prod, uint16_t *slots, double *acc, double (*window)[kTileWindow], const TileArgs &ta,
+                                           const int s, const int q, const int B, const TilePtrs &tp, const double *__restrict__ x)
 {
     const int tid = threadIdx.x;
     for (int k = tid; k < kTileSlots; k += kBlock) acc[k] = 0.0;
@@ -1135,13 +1142,17 @@ __device__ __forceinline__ void tiles_body(double *prod, uint16_t *slots, double
         const int64_t T0 = ta.tile0[s];
         const int64_t last = nt - 1;
         auto clampt = [&](int64_t t) { return T0 + (t < last ? t : last); };
-        TileRegs cur = load_tile(tp, load_uniform(tp.hdr + clampt(q)), clampt(q));
-        TileRegs nxt = load_tile(tp, load_uniform(tp.hdr + clampt(q + B)), clampt(q + B));
+        TileRegs cur = load_tile(tp, x, load_uniform(tp.hdr + clampt(q)), clampt(q));
+        TileRegs nxt = load_tile(tp, x, load_uniform(tp.hdr + clampt(q + B)), clampt(q + B));
         int4 hdr2 = load_uniform(tp.hdr + clampt(q + 2 * (int64_t)B));
+        window[0][tid] = cur.w[0];
+        window[0][tid + kBlock] = cur.w[1];
+        __syncthreads();
+        int buf = 0;
         for (int64_t t = q; t < nt; t += B) {
             const int nseg = cur.hdr.y;
-            const double *xt = x + cur.hdr.x;   // the tile's first column
-            // gathers: a few consecutive cache lines of x per tile
+            // gathers from the copy of the tile's columns (at most kTileWindow of them) in LDS: see k_hot_tiles_unit
+            const double *xt = window[buf];
             double xg[4][2];
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
@@ -1156,15 +1167,19 @@ __device__ __forceinline__ void tiles_body(double *prod, uint16_t *slots, double
                 *reinterpret_cast<double2 *>(prod + prod_pos(m * kQuarter + tid * 2)) = p;
             }
             __builtin_amdgcn_sched_barrier(0);
-            const TileRegs nn = load_tile(tp, hdr2, clampt(t + 2 * (int64_t)B));
+            const TileRegs nn = load_tile(tp, x, hdr2, clampt(t + 2 * (int64_t)B));
             const int4 hdr3 = load_uniform(tp.hdr + clampt(t + 3 * (int64_t)B));
             __builtin_amdgcn_sched_barrier(0);
             __syncthreads();
-            // every thread is past the accumulator updates of the tile before: its slots may be replaced
+            // every thread is past the accumulator updates of the tile before: its slots may be replaced; and past the
+            // gathers of the tile before that one, which were the last to read the other window buffer
             if (8 * tid < nseg) *reinterpret_cast<uint4 *>(slots + 8 * tid) = cur.slots;
+            window[buf ^ 1][tid] = nxt.w[0];
+            window[buf ^ 1][tid + kBlock] = nxt.w[1];
+            buf ^= 1;
             double p[8], cin;
             int idx0;
-            chunk_runs(prod, cur.flags, p, cin, idx0);   // barrier inside: the slots are visible after it
+            chunk_runs(prod, cur.flags, p, cin, idx0);   // barrier inside: the slots and the next tile's columns are visible after it
             int i = idx0;
             bool first = true;
 #pragma unroll
@@ -1318,7 +1333,8 @@ __global__ __launch_bounds__(kBlock) void k_hot_tiles(TileArgs ta, int B, TilePt
     __shared__ __align__(16) double prod[kProdDoubles];
     __shared__ __align__(16) uint16_t slots[kChunk];
     __shared__ double acc[kTileSlots];
-    tiles_body<SQ>(prod, slots, acc, ta, blockIdx.x % kTileSlices, blockIdx.x / kTileSlices, B, tp, x);
+    __shared__ double window[2][kTileWindow];
+    tiles_body<SQ>(prod, slots, acc, window, ta, blockIdx.x % kTileSlices, blockIdx.x / kTileSlices, B, tp, x);
 }
 
 // sums[s*K + k] = sum over the B workgroups of slice s: four quarter sums (workgroup order inside each), added in
