@@ -115,11 +115,11 @@ constexpr int kHotSlots = 4096;   // LDS table entries per workgroup (32 KiB)
 // Hot-row tiles of the transposed product  out[j] += sum_i val * x[i]  (j = row of the plan, i = column).
 // The rows with the most entries (up to kTileSlices * kTileSlots of them) are taken out of the CSR layout and
 // stored as tiles: a tile holds the entries of one slice of those rows for a short range of consecutive
-// columns, sorted by (row slot, column).  The gather x[i] then stays inside a few cache lines per tile (vector
-// L1 hits instead of one L2 request per entry), and the per-row sums of a tile are added to LDS accumulators
-// that a persistent workgroup keeps for its slice; workgroup accumulators are summed in a fixed order.
-// A tile spans at most 512 columns and the workgroup gathers from a copy of them in LDS; the header of a tile is
-// {first column, segments, columns spanned, offset of its segment slots}.
+// columns (at most 512), sorted by (row slot, column).  The workgroup copies those columns of x into LDS and
+// gathers from the copy (no L2 request per entry, and none of the vector memory pipeline's one-lane-per-clock
+// gathers), and the per-row sums of a tile are added to LDS accumulators that a persistent workgroup keeps for its
+// slice; workgroup accumulators are summed in a fixed order.  The header of a tile is {first column, segments,
+// columns spanned, offset of its segment slots}.
 constexpr int kTileSlices = 8;      // slices of hot rows, one per XCD
 constexpr int kTileSlots = 2048;    // hot rows per slice = LDS accumulators per workgroup (16 KiB)
 constexpr int kTileMinCount = 32;   // rows with fewer entries stay in the CSR layout
