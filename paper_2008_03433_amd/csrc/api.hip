@@ -247,8 +247,17 @@ int tron_dataset_create_csr(int64_t n, int64_t d, const int64_t *rowptr, const i
         std::vector<std::pair<int64_t, int32_t>> cand;
         for (int64_t j = 0; j < d; ++j)
             if (t_rowptr[j + 1] >= kTileMinCount) cand.emplace_back(-t_rowptr[j + 1], (int32_t)j);
-        const size_t keep = std::min<size_t>(cand.size(), (size_t)kTileSlices * kTileSlots);
+        size_t keep = std::min<size_t>(cand.size(), (size_t)kTileSlices * kTileSlots);
         std::partial_sort(cand.begin(), cand.begin() + keep, cand.end());
+        // A tile spans at most kTileWindow instances, so a slice has about n / kTileWindow of them however few entries
+        // they hold, and a tile costs the kernel about as much as 400 entries cost the range kernels: where there are
+        // many tiles they must be at least a quarter full on average, or the features stay in the CSR copy.
+        {
+            int64_t entries = 0;
+            for (size_t r = 0; r < keep; ++r) entries -= cand[r].first;
+            const int64_t windows = (n + kTileWindow - 1) / kTileWindow * kTileSlices;
+            if (windows > 4096 && entries < windows * (kChunk / 4)) keep = 0;
+        }
         if (keep > 0) {
             slot_code.assign((size_t)d, -1);
             for (size_t r = 0; r < keep; ++r) {

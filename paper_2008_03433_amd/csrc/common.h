@@ -123,6 +123,7 @@ constexpr int kHotSlots = 4096;   // LDS table entries per workgroup (32 KiB)
 constexpr int kTileSlices = 8;      // slices of hot rows, one per XCD
 constexpr int kTileSlots = 2048;    // hot rows per slice = LDS accumulators per workgroup (16 KiB)
 constexpr int kTileMinCount = 32;   // rows with fewer entries stay in the CSR layout
+constexpr int kTileWindow = 512;    // columns a tile may span (the kernels copy them into LDS, two per thread)
 
 struct HotTiles {
     int64_t nnz = 0;                     // entries held in tiles

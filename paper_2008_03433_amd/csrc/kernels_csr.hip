@@ -974,7 +974,6 @@ __global__ __launch_bounds__(kBlock) void k_csr_spmv_part(PartArgs pa, int64_t r
 
 // ------------------------------------------------------------------ hot-row tiles (see HotTiles)
 constexpr int kMaxTileBlocks = 256;   // workgroups per slice
-constexpr int kTileWindow = 512;      // columns a tile may span (two per thread)
 
 int hot_tiles_build(CsrPlan &A, const int64_t *t_rowptr, const int32_t *t_col, const double *t_val,
                     const std::vector<int32_t> &slot_code, int nhot, hipStream_t st)

@@ -193,7 +193,7 @@ def test_csr_one_value_per_instance(rng, loss, force_partitions):
     # many instances, few features: a tile of the transposed product fills up slowly, so the limit on the columns it may
     # span (they are copied into LDS) closes it first
     nt, dt = 20000, 300
-    Bt = (rng.random((nt, dt)) < 0.01).astype(np.float64)
+    Bt = (rng.random((nt, dt)) < 0.05).astype(np.float64)
     Bt[:, 5] = 1.0
     pt = _csr_from_dense(Bt * np.exp(rng.standard_normal(nt))[:, None], np.where(rng.random(nt) < 0.5, 1.0, -1.0))
     ds = tron.Dataset.from_problem(pt)
@@ -217,6 +217,25 @@ def test_csr_one_value_per_instance(rng, loss, force_partitions):
         check_calls(p, loss, 0.5, rng, w_scale=0.3, n_hv=1)
     finally:
         tron.tron_tuning_set("csr_unit", 1)
+
+
+def test_hot_row_tiles_are_left_out_when_they_would_stay_nearly_empty(rng, force_partitions):
+    """Many instances, every feature equally rare: a tile may span 512 instances only, so the tiles of such a matrix
+    would hold a few entries each and cost more than they save; the features stay in the transposed CSR copy."""
+    import paper_2008_03433_amd as tron
+    n, d, nnz = 300_000, 2000, 90_000
+    keys = np.unique(rng.integers(0, n * d, size=nnz))
+    rows, cols = keys // d, (keys % d).astype(np.int32)      # sorted by (row, column)
+    rowptr = np.zeros(n + 1, dtype=np.int64)
+    np.add.at(rowptr, rows + 1, 1)
+    rowptr = np.cumsum(rowptr)
+    p = SparseProblem("flat", n, d, rowptr, cols, rng.standard_normal(len(keys)),
+                      np.where(rng.random(n) < 0.5, 1.0, -1.0))
+    ds = tron.Dataset.from_problem(p)
+    assert tron.tron_dataset_stat(ds.handle, "bwd_parts") == 8
+    assert tron.tron_dataset_stat(ds.handle, "bwd_tiles") == 0
+    ds.close()
+    check_calls(p, LOSS_LR, 0.5, rng, w_scale=0.3, n_hv=1)
 
 
 def test_solve_partitioned_layout(force_partitions):
