@@ -1336,15 +1336,17 @@ __global__ __launch_bounds__(kBlock) void k_hot_tiles(TileArgs ta, int B, TilePt
     tiles_body<SQ>(prod, slots, acc, window, ta, blockIdx.x % kTileSlices, blockIdx.x / kTileSlices, B, tp, x);
 }
 
-// sums[s*K + k] = sum over the B workgroups of slice s: four quarter sums (workgroup order inside each), added in
-// order.  A workgroup covers 64 consecutive slots, one wavefront per quarter, so every read is one 512-byte row.
-__global__ __launch_bounds__(kBlock) void k_hot_reduce(int B, const double *__restrict__ wg_acc, double *__restrict__ sums)
+// sums[s*K + k] = sum over the B workgroups of slice s: sixteen partial sums (workgroup order inside each), added in
+// order.  A workgroup covers 64 consecutive slots, one wavefront per part, so every read is one 512-byte row and a CU
+// has sixteen rows in flight (with four the kernel waited for HBM most of the time).
+constexpr int kReduceWaves = 16;
+__global__ __launch_bounds__(kReduceWaves * kWave) void k_hot_reduce(int B, const double *__restrict__ wg_acc, double *__restrict__ sums)
 {
-    __shared__ double part[kWavesPerBlock][kWave];
+    __shared__ double part[kReduceWaves][kWave];
     const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave;
     const int idx = blockIdx.x * kWave + lane;   // s*K + k
     const int s = idx / kTileSlots, k = idx % kTileSlots;
-    const int per = (B + kWavesPerBlock - 1) / kWavesPerBlock;
+    const int per = (B + kReduceWaves - 1) / kReduceWaves;
     const int q0 = wv * per, q1 = (q0 + per < B) ? q0 + per : B;
     const double *p = wg_acc + (int64_t)s * B * kTileSlots + k;
     double a = 0.0;
@@ -1354,7 +1356,7 @@ __global__ __launch_bounds__(kBlock) void k_hot_reduce(int B, const double *__re
     if (wv == 0) {
         double t = part[0][lane];
 #pragma unroll
-        for (int m = 1; m < kWavesPerBlock; ++m) t += part[m][lane];
+        for (int m = 1; m < kReduceWaves; ++m) t += part[m][lane];
         sums[idx] = t;
     }
 }
@@ -1388,7 +1390,7 @@ static int launch_hot_tiles(tron_dataset *ds, const CsrPlan &A, const double *x,
     }
     {
         ProfScope ps(ds, SLOT_SPMV_TILE_REDUCE, st);
-        hipLaunchKernelGGL(k_hot_reduce, dim3(kTileSlices * kTileSlots / kWave), dim3(kBlock), 0, st, H.blocks_per_slice,
+        hipLaunchKernelGGL(k_hot_reduce, dim3(kTileSlices * kTileSlots / kWave), dim3(kReduceWaves * kWave), 0, st, H.blocks_per_slice,
                            H.wg_acc, H.sums);
         TRON_HIP(hipGetLastError());
     }
