@@ -118,6 +118,7 @@ static int alloc_common(tron_dataset *ds)
     // the stream has drained, without a copy operation between the last kernel and the host's wait.
     TRON_HIP(hipHostMalloc(reinterpret_cast<void **>(&ds->scal_host), sizeof(double) * kScalars, hipHostMallocMapped));
     TRON_HIP(hipHostGetDevicePointer(reinterpret_cast<void **>(&ds->scal_dev), ds->scal_host, 0));
+    TRON_HIP(hipMalloc(reinterpret_cast<void **>(&ds->scal_copy), sizeof(double) * kScalars));
     ds->vec_grid_n = vec_grid_for(ds->n);
     ds->vec_grid_d = vec_grid_for(ds->d);
     return TRON_OK;
@@ -169,7 +170,7 @@ void tron_dataset_destroy(tron_dataset *ds)
     ds->fwd.release();
     ds->bwd.release();
     hipFree(ds->y); hipFree(ds->y8); hipFree(ds->z); hipFree(ds->zhat); hipFree(ds->Dbuf[0]); hipFree(ds->Dbuf[1]);
-    hipFree(ds->partials); hipFree(ds->row_partials); hipFree(ds->unit_scale);
+    hipFree(ds->partials); hipFree(ds->row_partials); hipFree(ds->unit_scale); hipFree(ds->scal_copy);
     if (ds->scal_host) hipHostFree(ds->scal_host);
     for (double *p : ds->sv) hipFree(p);
     ds->prof.destroy();

@@ -253,6 +253,7 @@ struct tron_dataset {
     int64_t partials_len = 0;
     double *scal_host = nullptr; // kScalars pinned host scalars, mapped into the device's address space
     double *scal_dev = nullptr;  // the device address of scal_host (kernels write the scalars there)
+    double *scal_copy = nullptr; // the same scalars in device memory, for kernels that continue from them without the host
     int dense_grid = 0;          // workgroups of the dense kernels
     int vec_grid_n = 0, vec_grid_d = 0;  // workgroups of elementwise kernels over n / d
 
@@ -287,8 +288,16 @@ int loss_terms(tron_dataset *ds, int loss, const double *z, double *zhat, double
 int read_scalars(tron_dataset *ds, int count);  // stream sync; then scal_host[0..count) holds what the kernels wrote
 // CG vector kernels (see solver.hip); M = diagonal preconditioner or null
 int cg_init(tron_dataset *ds, const double *g, const double *M, double *s, double *r, double *p);  // M: slot0 = g.(g/M); returns #partials
-int cg_step(tron_dataset *ds, double alpha, const double *p, const double *Hp, const double *M, double *s, double *r);  // slot0 = r.r | r.(r/M)
-int cg_dir(tron_dataset *ds, double beta, const double *r, const double *s, const double *M, double *p);  // slots: p.p, s.p, s.s (M-weighted)
+// What the CG step kernel needs to form the step length itself from the device copy of the scalars (slot 0 = p.Hp,
+// slots 1..3 = p.p, s.p, s.s unless `first`): alpha = rr / p.Hp, or the step to the trust-region boundary if
+// |s + alpha p| >= delta.  The kernel leaves the step taken in scalar 4 and whether it went to the boundary in scalar 5.
+struct CgStepCtl {
+    double rr, delta;
+    int first;      // first iteration: s = 0 and p.p = rr
+};
+int cg_step(tron_dataset *ds, const CgStepCtl &ctl, const double *p, const double *Hp, const double *M, double *s, double *r);  // slot0 = r.r | r.(r/M)
+// beta = (scalar 0 of the device copy) / rr_old
+int cg_dir(tron_dataset *ds, double rr_old, const double *r, const double *s, const double *M, double *p);  // slots: p.p, s.p, s.s (M-weighted)
 int trial_point(tron_dataset *ds, const double *w, const double *s, const double *g, const double *r, const double *M,
                 double *wnew);  // wnew = w+s; slots: g.s, s.r, s.s | s.Ms
 int probe_read(const double *src, int64_t count, int reps, hipStream_t st, double *ms, double *checksum);

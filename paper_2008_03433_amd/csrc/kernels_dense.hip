@@ -201,7 +201,7 @@ __global__ __launch_bounds__(kBlock) void k_dense_columns(int64_t d, int grid, c
 __global__ __launch_bounds__(kBlock) void k_dense_scalars(int64_t d, int nloss, const double *__restrict__ loss_partials,
                                                           const double *__restrict__ active_partials,
                                                           const double *__restrict__ w, const double *__restrict__ colprod,
-                                                          double *__restrict__ scal)
+                                                          double *__restrict__ scal, double *__restrict__ scal_copy)
 {
     __shared__ double lds[kWavesPerBlock];
     double a = 0.0, b = 0.0, c = 0.0, e = 0.0;
@@ -225,6 +225,7 @@ __global__ __launch_bounds__(kBlock) void k_dense_scalars(int64_t d, int nloss, 
             scal[3] = e;
         } else {
             scal[0] = c;
+            scal_copy[0] = c;   // p.Hp: the CG step kernel continues from it
         }
     }
 }
@@ -367,7 +368,7 @@ int dense_hv(tron_dataset *ds, double C, int Dslot, const double *v, double *Hv)
     const int cg = (int)((ds->d + kWavesPerBlock - 1) / kWavesPerBlock);
     hipLaunchKernelGGL(k_dense_columns, dim3(cg), dim3(kBlock), 0, ds->stream, ds->d, grid, ds->partials, v, C, Hv, v, colprod);
     hipLaunchKernelGGL(k_dense_scalars, dim3(1), dim3(kBlock), 0, ds->stream, ds->d, 0, (const double *)nullptr,
-                       (const double *)nullptr, (const double *)nullptr, colprod, ds->scal_dev);
+                       (const double *)nullptr, (const double *)nullptr, colprod, ds->scal_dev, ds->scal_copy);
     TRON_HIP(hipGetLastError());
     return TRON_OK;
 }
@@ -408,7 +409,7 @@ int dense_fun_grad(tron_dataset *ds, int loss, double C, const double *w, int Ds
     hipLaunchKernelGGL(k_dense_columns, dim3(cg), dim3(kBlock), 0, ds->stream, ds->d, grid, ds->partials, w, C, g,
                        (const double *)nullptr, colprod);
     hipLaunchKernelGGL(k_dense_scalars, dim3(1), dim3(kBlock), 0, ds->stream, ds->d, grid, loss_partials, active_partials, w, colprod,
-                       ds->scal_dev);
+                       ds->scal_dev, ds->scal_copy);
     TRON_HIP(hipGetLastError());
     return TRON_OK;
 }

@@ -7,9 +7,10 @@
 namespace tron {
 
 // ------------------------------------------------------------------ second stage
-// scal[first + s] = sum_{b < count} partials[s*stride + b]
+// scal[first + s] = sum_{b < count} partials[s*stride + b]; scal is the host's copy (mapped pinned memory), scal_copy the
+// device's
 __global__ __launch_bounds__(kBlock) void k_reduce_final(const double *__restrict__ partials, int count, int stride,
-                                                         double *__restrict__ scal, int first)
+                                                         double *__restrict__ scal, double *__restrict__ scal_copy, int first)
 {
     __shared__ double lds[kWavesPerBlock];
     const int s = blockIdx.x;
@@ -17,14 +18,17 @@ __global__ __launch_bounds__(kBlock) void k_reduce_final(const double *__restric
     double acc = 0.0;
     for (int b = threadIdx.x; b < count; b += kBlock) acc += p[b];
     acc = block_sum(acc, lds);
-    if (threadIdx.x == 0) scal[first + s] = acc;
+    if (threadIdx.x == 0) {
+        scal[first + s] = acc;
+        scal_copy[first + s] = acc;
+    }
 }
 
 int reduce_final(tron_dataset *ds, int nslots, int count, int stride, int first_scalar)
 {
     ProfScope ps(ds, SLOT_REDUCE_FINAL);
     hipLaunchKernelGGL(k_reduce_final, dim3(nslots), dim3(kBlock), 0, ds->stream, ds->partials, count, stride,
-                       ds->scal_dev, first_scalar);
+                       ds->scal_dev, ds->scal_copy, first_scalar);
     TRON_HIP(hipGetLastError());
     return TRON_OK;
 }
@@ -154,13 +158,37 @@ int cg_init(tron_dataset *ds, const double *g, const double *M, double *s, doubl
     return gr;
 }
 
-// s += alpha p;  r -= alpha Hp;  partial slot 0 = r.r (PRE: r.(r / M))
+// The step length of a CG iteration from the device copy of the scalars (see CgStepCtl), in the operations and the
+// order the host used to take (no contraction into fused multiply-adds), the same in every thread.
+__device__ __forceinline__ double cg_step_length(const CgStepCtl &c, const double *__restrict__ sc, bool &boundary)
+{
+    const double pHp = sc[0];
+    const double pp = c.first ? c.rr : sc[1], sp = c.first ? 0.0 : sc[2], ss = c.first ? 0.0 : sc[3];
+    const double alpha = c.rr / pHp;
+    // |s + alpha p|^2 from the three dot products kept alongside the vectors
+    const double len2 = __dadd_rn(ss, __dmul_rn(alpha, __dadd_rn(__dmul_rn(2.0, sp), __dmul_rn(alpha, pp))));
+    boundary = sqrt(len2) >= c.delta;
+    if (!boundary) return alpha;
+    const double gap = __dadd_rn(__dmul_rn(c.delta, c.delta), -ss);
+    const double rad = sqrt(__dadd_rn(__dmul_rn(sp, sp), __dmul_rn(pp, gap)));
+    return (sp >= 0.0) ? gap / __dadd_rn(sp, rad) : __dadd_rn(rad, -sp) / pp;
+}
+
+// s += a p;  r -= a Hp with a = the step length above;  partial slot 0 = r.r (PRE: r.(r / M));  scalars 4, 5 = a,
+// whether the step went to the boundary
 template <bool PRE>
-__global__ __launch_bounds__(kBlock) void k_cg_step(int64_t d, double alpha, const double *__restrict__ p,
+__global__ __launch_bounds__(kBlock) void k_cg_step(int64_t d, CgStepCtl ctl, const double *__restrict__ sc, const double *__restrict__ p,
                                                     const double *__restrict__ Hp, const double *__restrict__ M,
-                                                    double *__restrict__ s, double *__restrict__ r, double *__restrict__ partials)
+                                                    double *__restrict__ s, double *__restrict__ r, double *__restrict__ partials,
+                                                    double *__restrict__ scal)
 {
     __shared__ double lds[kWavesPerBlock];
+    bool boundary;
+    const double alpha = cg_step_length(ctl, sc, boundary);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        scal[4] = alpha;
+        scal[5] = boundary ? 1.0 : 0.0;
+    }
     double acc = 0.0;
     for (int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x; j < d; j += (int64_t)gridDim.x * kBlock) {
         s[j] = fma(alpha, p[j], s[j]);
@@ -172,23 +200,25 @@ __global__ __launch_bounds__(kBlock) void k_cg_step(int64_t d, double alpha, con
     if (threadIdx.x == 0) partials[blockIdx.x] = acc;
 }
 
-int cg_step(tron_dataset *ds, double alpha, const double *p, const double *Hp, const double *M, double *s, double *r)
+int cg_step(tron_dataset *ds, const CgStepCtl &ctl, const double *p, const double *Hp, const double *M, double *s, double *r)
 {
     ProfScope ps(ds, SLOT_CG_VEC);
     const int g = vec_grid(ds->d);
-    if (M) hipLaunchKernelGGL(k_cg_step<true>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, alpha, p, Hp, M, s, r, ds->partials);
-    else hipLaunchKernelGGL(k_cg_step<false>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, alpha, p, Hp, M, s, r, ds->partials);
+    if (M) hipLaunchKernelGGL(k_cg_step<true>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, ctl, ds->scal_copy, p, Hp, M, s, r, ds->partials, ds->scal_dev);
+    else hipLaunchKernelGGL(k_cg_step<false>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, ctl, ds->scal_copy, p, Hp, M, s, r, ds->partials, ds->scal_dev);
     TRON_HIP(hipGetLastError());
     return g;
 }
 
-// p = r + beta p (PRE: r / M + beta p);  partial slots: 0 = p.p, 1 = s.p, 2 = s.s (PRE: M-weighted)
+// p = r + beta p (PRE: r / M + beta p) with beta = (scalar 0 of the device copy: the new r.r) / rr_old;
+// partial slots: 0 = p.p, 1 = s.p, 2 = s.s (PRE: M-weighted)
 template <bool PRE>
-__global__ __launch_bounds__(kBlock) void k_cg_dir(int64_t d, double beta, const double *__restrict__ r,
+__global__ __launch_bounds__(kBlock) void k_cg_dir(int64_t d, double rr_old, const double *__restrict__ sc, const double *__restrict__ r,
                                                    const double *__restrict__ s, const double *__restrict__ M,
                                                    double *__restrict__ p, double *__restrict__ partials, int stride)
 {
     __shared__ double lds[kWavesPerBlock];
+    const double beta = sc[0] / rr_old;
     double pp = 0.0, sp = 0.0, ss = 0.0;
     for (int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x; j < d; j += (int64_t)gridDim.x * kBlock) {
         const double m = PRE ? M[j] : 1.0;
@@ -213,12 +243,12 @@ __global__ __launch_bounds__(kBlock) void k_cg_dir(int64_t d, double beta, const
     if (threadIdx.x == 0) partials[2 * stride + blockIdx.x] = ss;
 }
 
-int cg_dir(tron_dataset *ds, double beta, const double *r, const double *s, const double *M, double *p)
+int cg_dir(tron_dataset *ds, double rr_old, const double *r, const double *s, const double *M, double *p)
 {
     ProfScope ps(ds, SLOT_CG_VEC);
     const int g = vec_grid(ds->d);
-    if (M) hipLaunchKernelGGL(k_cg_dir<true>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, beta, r, s, M, p, ds->partials, kMaxGrid);
-    else hipLaunchKernelGGL(k_cg_dir<false>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, beta, r, s, M, p, ds->partials, kMaxGrid);
+    if (M) hipLaunchKernelGGL(k_cg_dir<true>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, rr_old, ds->scal_copy, r, s, M, p, ds->partials, kMaxGrid);
+    else hipLaunchKernelGGL(k_cg_dir<false>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, rr_old, ds->scal_copy, r, s, M, p, ds->partials, kMaxGrid);
     TRON_HIP(hipGetLastError());
     return g;
 }

@@ -85,46 +85,35 @@ int eval_f(tron_dataset *ds, const tron_params &P, const double *w, int Dslot, d
 //   the boundary along p and stop;  s += alpha p, r -= alpha Hp, beta = r'.r'/r.r, p = r + beta p.
 // With a diagonal preconditioner M (not null): z = r / M replaces r in p and in the dot products r.r, and the lengths
 // are M-norms (the iteration is plain CG in the variables M^(1/2) s); gscaled = sqrt(g.M^-1 g) takes the place of |g|.
+// One wait per iteration: the step kernel forms alpha (or the step to the boundary) from the scalars the device keeps,
+// the direction kernel forms beta, and the host reads the new r.r and the boundary flag once both are enqueued.  The
+// direction update of the last iteration is therefore computed for nothing (p is not needed again).
 int cg_solve(tron_dataset *ds, const tron_params &P, const double *M, double delta, double gscaled, int *n_hv, int *on_boundary)
 {
     double *g = ds->sv[V_G], *s = ds->sv[V_S], *r = ds->sv[V_R], *p = ds->sv[V_P], *Hp = ds->sv[V_HP];
     TRON_TRY(cg_init(ds, g, M, s, r, p));
-    double rr = gscaled * gscaled, pp = rr, sp = 0.0, ss = 0.0;   // p = z = -g / M at the start: p.Mp = r.z
+    double rr = gscaled * gscaled;   // p = z = -g / M at the start: p.Mp = r.z
     int it = 0;
     *on_boundary = 0;
     while (it < P.max_cg) {
         if (std::sqrt(rr) <= P.cg_xi * gscaled) break;
-        TRON_TRY(hv_enqueue(ds, P.C, p, Hp));
-        TRON_TRY(read_scalars(ds, 4));  // p.Hp, and p.p, s.p, s.s left by the preceding direction update
-        const double pHp = ds->scal_host[0];
-        if (it > 0) {
-            pp = ds->scal_host[1];
-            sp = ds->scal_host[2];
-            ss = ds->scal_host[3];
-        }
+        TRON_TRY(hv_enqueue(ds, P.C, p, Hp));   // scalar 0 = p.Hp; scalars 1..3 = p.p, s.p, s.s of the direction update before
+        const CgStepCtl ctl{rr, delta, it == 0 ? 1 : 0};
         ++it;
-        const double alpha = rr / pHp;
-        // |s + alpha p|^2 from the three dot products kept alongside the vectors
-        const double len2 = ss + alpha * (2.0 * sp + alpha * pp);
-        if (std::sqrt(len2) >= delta) {
-            const double gap = delta * delta - ss;
-            const double rad = std::sqrt(sp * sp + pp * gap);
-            const double tau = (sp >= 0.0) ? gap / (sp + rad) : (rad - sp) / pp;
-            TRON_TRY(cg_step(ds, tau, p, Hp, M, s, r));
+        const int g1 = cg_step(ds, ctl, p, Hp, M, s, r);
+        TRON_TRY(g1);
+        TRON_TRY(reduce_final(ds, 1, g1, 0, 0));   // scalar 0 = the new r.r
+        if (it < P.max_cg) {
+            const int g2 = cg_dir(ds, rr, r, s, M, p);
+            TRON_TRY(g2);
+            TRON_TRY(reduce_final(ds, 3, g2, kMaxGrid, 1));
+        }
+        TRON_TRY(read_scalars(ds, 6));
+        if (ds->scal_host[5] != 0.0) {
             *on_boundary = 1;
             break;
         }
-        const int g1 = cg_step(ds, alpha, p, Hp, M, s, r);
-        TRON_TRY(g1);
-        TRON_TRY(reduce_final(ds, 1, g1, 0, 0));
-        TRON_TRY(read_scalars(ds, 1));
-        const double rr_new = ds->scal_host[0];
-        const double beta = rr_new / rr;
-        rr = rr_new;
-        if (std::sqrt(rr) <= P.cg_xi * gscaled || it >= P.max_cg) break;  // p is not needed again
-        const int g2 = cg_dir(ds, beta, r, s, M, p);
-        TRON_TRY(g2);
-        TRON_TRY(reduce_final(ds, 3, g2, kMaxGrid, 1));  // scalars 1..3 = p.p, s.p, s.s, read with the next p.Hp
+        rr = ds->scal_host[0];
     }
     *n_hv = it;
     return TRON_OK;
