@@ -111,6 +111,10 @@ struct Profiler {
 constexpr int kColParts = 8;            // column ranges, one per XCD
 constexpr int kMaxParts = kColParts + 1;   // + the head partition (see CsrPlan::head)
 constexpr int kHotSlots = 4096;   // LDS table entries per workgroup (32 KiB)
+// The head partition kept as sorted slices has one table for a workgroup of 16 wavefronts, one workgroup per CU:
+// 16384 entries (128 KiB).  Its place in hot_ids / hot_x is behind the P range tables, which stay kHotSlots apart.
+constexpr int kSellSlots = 16384;
+constexpr int kSellBlock = 1024;
 
 // Hot-row tiles of the transposed product  out[j] += sum_i val * x[i]  (j = row of the plan, i = column).
 // The rows with the most entries (up to kTileSlices * kTileSlots of them) are taken out of the CSR layout and
@@ -166,7 +170,7 @@ struct SellHead {
     int nwaves = 0;               // wavefronts the slices were dealt to (= 4 x workgroups of the kernel)
     int nslices = 0;
     int64_t *wave_off = nullptr;     // device, nwaves + 1: first group of each wavefront's stream in data
-    uint16_t *data = nullptr;     // device: groups (headers and slots; kHotSlots = the padding slot, whose table entry is 0)
+    uint16_t *data = nullptr;     // device: groups (headers and slots; kSellSlots = the padding slot, whose table entry is 0)
     double *sums = nullptr;       // device, rows: in sorted order
     int32_t *pos = nullptr;       // device, rows: where the sum of a row is
     void release();
@@ -209,8 +213,9 @@ struct CsrPlan {
     int part_nhot[kMaxParts] = {0};      // LDS-resident columns of partition x
     int max_chunks = 0;                  // max over the column ranges
     int range_slots = 0;                 // LDS table entries used by the column ranges (<= kHotSlots)
-    int32_t *hot_ids = nullptr;          // device, (P+1)*kHotSlots column ids of the LDS tables (null: no LDS table)
-    double *hot_x = nullptr;             // device, (P+1)*kHotSlots: the gather vector at those columns, refreshed every call
+    int head_slots = 0;                  // LDS table entries of the head partition (kHotSlots, or kSellSlots as sorted slices)
+    int32_t *hot_ids = nullptr;          // device, P*kHotSlots + head_slots column ids of the LDS tables (null: no LDS table)
+    double *hot_x = nullptr;             // device, as many: the gather vector at those columns, refreshed every call
     int64_t nseg_total = 0;              // segments (= partial sums) of the plan
     int64_t ngroups = 0;                 // ceil(rows / 64)
     GroupBase *group_base = nullptr;     // device, ngroups records

@@ -142,15 +142,18 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
         std::vector<int32_t> slot_of, hot_ids;
         std::vector<std::pair<int64_t, int32_t>> cand;
         int64_t head_nnz = 0;
+        // unit plans keep the head partition as sorted slices (SellHead) instead of chunks, with a larger table
+        const bool want_sell = A.unit && g_tuning.csr_sell != 0;
+        A.head_slots = want_sell ? kSellSlots : kHotSlots;
         if (hot) {
             A.range_slots = (int)std::min<int64_t>(kHotSlots, std::max<int64_t>(2, g_tuning.csr_range_slots / 2 * 2));
             slot_of.assign((size_t)cols, -1);
-            hot_ids.assign((size_t)(P + 1) * kHotSlots, 0);
+            hot_ids.assign((size_t)P * kHotSlots + A.head_slots, 0);
         }
         if (hot && g_tuning.csr_head) {
             for (int64_t j = 0; j < cols; ++j)
                 if (colcount[j + 1] >= kHotMinCount) cand.emplace_back(-colcount[j + 1], (int32_t)j);
-            const size_t keep = std::min<size_t>(cand.size(), kHotSlots);
+            const size_t keep = std::min<size_t>(cand.size(), (size_t)A.head_slots);
             std::partial_sort(cand.begin(), cand.begin() + keep, cand.end());
             for (size_t k = 0; k < keep; ++k) head_nnz -= cand[k].first;
             if (head_nnz * 4 >= A.nnz) {
@@ -165,8 +168,7 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
                 }
             }
         }
-        // unit plans keep the head partition as sorted slices (SellHead) instead of chunks
-        const bool sell = A.unit && A.head >= 0 && g_tuning.csr_sell != 0;
+        const bool sell = want_sell && A.head >= 0;
         const int NP = (A.head >= 0 && !sell) ? P + 1 : P;   // chunked partitions in all
         const int64_t range_nnz = A.nnz - ((A.head >= 0) ? head_nnz : 0);
         // column ranges with equal nonzero counts (head columns excluded): bound[x] = first column of range x
@@ -348,7 +350,7 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
                 while ((groups - wave_off[w]) % kSellAhead) null_groups.push_back(groups++);
             }
             wave_off[S.nwaves] = groups;
-            std::vector<uint16_t> data((size_t)std::max<int64_t>(groups, 1) * kWave * 8, (uint16_t)kHotSlots);
+            std::vector<uint16_t> data((size_t)std::max<int64_t>(groups, 1) * kWave * 8, (uint16_t)kSellSlots);
             for (int64_t gpad : null_groups)
                 for (int l = 0; l < kWave; ++l) {
                     const int32_t hdr[4] = {-1, 0, 0, 0};   // a header of a slice without groups
@@ -911,18 +913,18 @@ __device__ __forceinline__ int64_t uniform64(int64_t v)
     return (int64_t)(((uint64_t)hi << 32) | lo);
 }
 
-__global__ __launch_bounds__(kBlock) void k_head_sell(int nwaves, const int64_t *__restrict__ wave_off, const uint16_t *__restrict__ data,
-                                                     const double *__restrict__ hot_x, double *__restrict__ sums)
+__global__ __launch_bounds__(kSellBlock) void k_head_sell(int nwaves, const int64_t *__restrict__ wave_off, const uint16_t *__restrict__ data,
+                                                         const double *__restrict__ hot_x, double *__restrict__ sums)
 {
-    __shared__ __align__(16) double table[kHotSlots + 2];
+    __shared__ __align__(16) double table[kSellSlots + 2];
     {
         const double2 *__restrict__ src = reinterpret_cast<const double2 *>(hot_x);
-        for (int k = threadIdx.x; k < kHotSlots / 2; k += kBlock) reinterpret_cast<double2 *>(table)[k] = src[k];
-        if (threadIdx.x == 0) table[kHotSlots] = 0.0;   // the padding slot
+        for (int k = threadIdx.x; k < kSellSlots / 2; k += kSellBlock) reinterpret_cast<double2 *>(table)[k] = src[k];
+        if (threadIdx.x == 0) table[kSellSlots] = 0.0;   // the padding slot
         __syncthreads();
     }
     const int lane = threadIdx.x & (kWave - 1);
-    const int w = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+    const int w = blockIdx.x * (kSellBlock / kWave) + threadIdx.x / kWave;
     if (w >= nwaves) return;
     // everything that steers the loop is kept in scalar registers: a branch on a vector condition would make the compiler
     // wait for every load in flight where the paths join
@@ -1631,7 +1633,7 @@ static int launch_partials(tron_dataset *ds, const CsrPlan &A, int slot, const d
     const PartArgs pa = part_args(A);
     if (A.hot_ids) {
         ProfScope ps(ds, SLOT_SPMV_GATHER);
-        const int nh = (A.P + 1) * kHotSlots;
+        const int nh = A.P * kHotSlots + A.head_slots;
         hipLaunchKernelGGL(k_gather_hot, dim3((nh + kBlock - 1) / kBlock), dim3(kBlock), 0, ds->stream, nh, A.hot_ids, x, A.hot_x);
         TRON_HIP(hipGetLastError());
     }
@@ -1640,7 +1642,7 @@ static int launch_partials(tron_dataset *ds, const CsrPlan &A, int slot, const d
         const int grid = std::max(1, std::min(A.part_nchunks[A.head], (int)g_tuning.csr_hot_blocks_per_part * kColParts));
         if (A.sell.on) {
             const SellHead &S = A.sell;
-            hipLaunchKernelGGL(k_head_sell, dim3(S.nwaves / kWavesPerBlock), dim3(kBlock), 0, ds->stream, S.nwaves, S.wave_off, S.data,
+            hipLaunchKernelGGL(k_head_sell, dim3((S.nwaves + kSellBlock / kWave - 1) / (kSellBlock / kWave)), dim3(kSellBlock), 0, ds->stream, S.nwaves, S.wave_off, S.data,
                                A.hot_x + (size_t)A.head * kHotSlots, S.sums);
         } else if (A.unit)
             hipLaunchKernelGGL(k_csr_head_unit, dim3(grid), dim3(kBlock), kHotSlots * sizeof(double), ds->stream, head_args(A),
