@@ -284,7 +284,8 @@ TRON_API int tron_probe_read_bandwidth(const double *src_dev, int64_t count, int
  *   "csr_tiles" (0/1): hot-row tiles for the transposed product;
  *   "csr_unit" (0/1): layouts without a value stream when every instance's entries share one value;
  *   "csr_sell" (0/1), "csr_sell_blocks" (1..4096): such a layout keeps its head partition as sorted slices of 64 rows,
- *                one row per lane (0: as chunks like the other partitions); workgroups of that kernel;
+ *                one row per lane, over the 16384 most frequent columns (0: as chunks like the other partitions, over
+ *                4096 columns); a quarter of the number of wavefronts the slices are dealt to;
  *   "csr_hot_blocks_per_part", "csr_range_blocks_per_part", "csr_blocks_per_part",
  *   "csr_tile_blocks_per_slice": persistent workgroups of the head, table, table-less and tile kernels.
  * "dense_device_driver" (-1/0/1): tron_solve on a dense matrix with d <= 32 and no preconditioner runs its trust-region and
