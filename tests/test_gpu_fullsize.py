@@ -27,6 +27,20 @@ def c3():
 def test_config3_full_calls(c3, rng):
     assert c3.n == 2_000_000 and c3.d == 3_000_000 and c3.nnz > 100_000_000
     check_calls(c3, LOSS_LR, c3.C, rng, w_scale=1.0, n_hv=1)
+    # every sum of the full-size layouts (sorted slices, tiles with LDS accumulators, partitions) is built in a fixed
+    # order: repeated calls agree bit for bit
+    import paper_2008_03433_amd as tron
+    torch = torch_mod()
+    ds = tron.Dataset.from_problem(c3)
+    w = torch.tensor(rng.standard_normal(c3.d), dtype=torch.float64, device="cuda")
+    v = torch.tensor(rng.standard_normal(c3.d), dtype=torch.float64, device="cuda")
+    out = [torch.empty_like(w) for _ in range(4)]
+    f1 = ds.fun_grad(LOSS_LR, c3.C, w, out[0])
+    ds.hv(c3.C, v, out[1])
+    f2 = ds.fun_grad(LOSS_LR, c3.C, w, out[2])
+    ds.hv(c3.C, v, out[3])
+    ds.close()
+    assert f1 == f2 and torch.equal(out[0], out[2]) and torch.equal(out[1], out[3])
 
 
 def test_config3_full_solve(c3):
