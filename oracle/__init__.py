@@ -56,10 +56,19 @@ class _Result(ctypes.Structure):
 _libs = {}
 
 
-def _L(plain_fp64: bool = False):
+def build_variant(out_so: str, src: str = _SRC, extra_flags=()) -> str:
+    """Compile a copy of the oracle source (e.g. one with a planted mistake, for the tests that show the pins
+    catch it) into out_so with the flags of build()."""
+    cmd = ["gcc", "-O2", "-fPIC", "-shared", "-fvisibility=hidden", "-ffp-contract=off", *extra_flags, "-o", out_so, src, "-lm"]
+    subprocess.check_call(cmd)
+    return out_so
+
+
+def _L(plain_fp64=False):
+    """plain_fp64: False = the oracle, True = its fp64-accumulator twin, a path = a library made by build_variant."""
     if plain_fp64 not in _libs:
         build()
-        lib = ctypes.CDLL(_SO_F64 if plain_fp64 else _SO)
+        lib = ctypes.CDLL(plain_fp64 if isinstance(plain_fp64, str) else (_SO_F64 if plain_fp64 else _SO))
         P, dbl, vp, ci = ctypes.POINTER, ctypes.c_double, ctypes.c_void_p, ctypes.c_int
         lib.orc_fun.argtypes = [P(_Data), ci, dbl, vp, P(dbl), vp, vp, vp]
         lib.orc_grad.argtypes = [P(_Data), dbl, vp, vp, vp]
@@ -98,9 +107,10 @@ class SolveResult:
 class Oracle:
     """One dataset (CSR or dense row-major) bound to the oracle routines."""
 
-    def __init__(self, *, n: int, d: int, y, rowptr=None, col=None, val=None, X=None, plain_fp64: bool = False):
+    def __init__(self, *, n: int, d: int, y, rowptr=None, col=None, val=None, X=None, plain_fp64=False):
         self.n, self.d = int(n), int(d)
-        self._plain = bool(plain_fp64)   # sums in fp64 instead of long double (rounding-sensitivity experiments only)
+        # True: sums in fp64 instead of long double (rounding-sensitivity experiments only); a path: a build_variant library
+        self._plain = plain_fp64 if isinstance(plain_fp64, str) else bool(plain_fp64)
         self.y = _f64(y)
         assert self.y.shape == (self.n,)
         if X is not None:

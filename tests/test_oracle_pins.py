@@ -644,3 +644,19 @@ def test_fold_solutions_are_stationary_for_the_masked_full_problem(rng, loss):
         assert np.linalg.norm(g) <= 1e-9 * res.gnorm0 * (1 + 1e-6)
         w_ref, _ = _newton_minimise(X[rows], y[rows], loss, C)
         np.testing.assert_allclose(res.w, w_ref, rtol=0, atol=1e-7 * max(1.0, np.abs(w_ref).max()))
+
+
+# ----------------------------------------------------------------------------
+# memory safety: every routine once under the address and undefined-behaviour sanitizers
+# ----------------------------------------------------------------------------
+def test_oracle_runs_clean_under_sanitizers(tmp_path):
+    import os
+    import subprocess
+    here = os.path.dirname(os.path.abspath(orc.__file__))
+    exe = str(tmp_path / "oracle_sanitize")
+    subprocess.check_call(["gcc", "-g", "-O1", "-ffp-contract=off", "-fsanitize=address,undefined",
+                           "-fno-sanitize-recover=all", "-static-libasan", "-o", exe,
+                           os.path.join(here, "sanitize_main.c"), "-lm"])
+    run = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert run.returncode == 0, run.stdout + run.stderr
+    assert "oracle sanitize run ok" in run.stdout
