@@ -131,6 +131,23 @@ TRON_API int tron_fun_grad(tron_dataset *ds, int loss, double C, const double *w
 TRON_API int tron_hv(tron_dataset *ds, double C, const double *v_dev, double *Hv_dev, double *vHv_host);
 
 /*
+ * tron_hv for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same product, same kernels and same results as tron_hv on a dense handle, but the
+ * kernels' work space (per-workgroup column sums, column products, the curvature scalar) is a static device array of
+ * TRON_HV_STATIC_MAX_DOUBLES doubles (2 MiB, held by every GPU the library runs on until the process ends) instead of
+ * the handle's allocation, and the call itself allocates nothing and never synchronises: it only enqueues on the
+ * handle's stream.  vHv_dev: DEVICE pointer to one double that receives v.Hv, or NULL.
+ * Dense handles only.  TRON_EINVAL when d * (workgroups of the dense kernels, at most 2048; tron_dataset_stat
+ * "dense_grid") + d + 1 exceeds TRON_HV_STATIC_MAX_DOUBLES (any n for d <= 127), when the handle is sparse, or when
+ * the current device is not the handle's; TRON_ESTATE if no D is cached.
+ * All calls on one GPU share the one array: calls that overlap in time on the same GPU (different streams or
+ * threads) race; calls on one stream are ordered and safe.  The array keeps the last call's contents; no call relies
+ * on them.
+ */
+#define TRON_HV_STATIC_MAX_DOUBLES 262144
+TRON_API int tron_hv_static(tron_dataset *ds, double C, const double *v_dev, double *Hv_dev, double *vHv_dev);
+
+/*
  * Diagonal of the Hessian at the w of the last tron_fun_grad (Appendix B: H = I + C X^T D X):
  *   hd_j = 1 + C sum_i D_i x_ij^2.
  * hd_dev: device pointer, d doubles.  Synchronises the stream.  TRON_ESTATE if no D is cached.

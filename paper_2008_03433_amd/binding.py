@@ -51,6 +51,7 @@ _SIGNATURES = {
     "tron_dataset_stat": (_int, [_vp, ctypes.c_char_p, ctypes.POINTER(_i64)]),
     "tron_fun_grad": (_int, [_vp, _int, _dbl, _vp, ctypes.POINTER(_dbl), _vp]),
     "tron_hv": (_int, [_vp, _dbl, _vp, _vp, ctypes.POINTER(_dbl)]),
+    "tron_hv_static": (_int, [_vp, _dbl, _vp, _vp, _vp]),
     "tron_solve": (_int, [_vp, ctypes.POINTER(_Params), _vp, ctypes.POINTER(_Result)]),
     "tron_hess_diag": (_int, [_vp, _dbl, _vp]),
     "tron_batch_create": (_int, [_vp, _int, _vp, _int, ctypes.POINTER(_vp)]),
@@ -188,6 +189,11 @@ def tron_hv(ds, C, v, Hv, want_vHv=True) -> Optional[float]:
         return s.value
     _check(load_library().tron_hv(ds, C, _ptr(v), _ptr(Hv), None))
     return None
+
+
+def tron_hv_static(ds, C, v, Hv, vHv=None) -> None:
+    """tron_hv without any allocation (dense handles): enqueues only; vHv is a CUDA tensor of one double, or None."""
+    _check(load_library().tron_hv_static(ds, C, _ptr(v), _ptr(Hv), _ptr(vHv)))
 
 
 def tron_hess_diag(ds, C, hd) -> None:
@@ -336,6 +342,9 @@ class Dataset:
 
     def hv(self, C, v, Hv, want_vHv=True):
         return tron_hv(self.handle, C, v, Hv, want_vHv)
+
+    def hv_static(self, C, v, Hv, vHv=None):
+        return tron_hv_static(self.handle, C, v, Hv, vHv)
 
     def hess_diag(self, C, hd):
         return tron_hess_diag(self.handle, C, hd)

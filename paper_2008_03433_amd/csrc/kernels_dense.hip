@@ -17,6 +17,8 @@
 // Workgroup partial column sums go to `partials[col * grid + block]`; a second kernel adds them in a
 // fixed order (no atomics) and applies  out = add + C * sum  together with the dot products the
 // trust-region driver needs.
+#include <cmath>
+
 #include "dense_tile.h"
 
 namespace tron {
@@ -234,13 +236,13 @@ __global__ __launch_bounds__(kBlock) void k_dense_scalars(int64_t d, int nloss, 
 constexpr double kSkipBelow = 0.95;   // active fraction under which the Hessian-vector pass skips the inactive rows
 
 template <int E, int L>
-int launch_hv(tron_dataset *ds, const void *D, bool mask, bool skip, const double *v)
+int launch_hv(tron_dataset *ds, const void *D, bool mask, bool skip, const double *v, double *partials)
 {
     constexpr int U = pick_U(E, L);
     const bool vec = (E % 2 == 0) && (ds->d % 2 == 0);
     const int grid = ds->dense_grid;
 #define TRON_HV(V, M, G, S) \
-    hipLaunchKernelGGL((k_dense_hv<E, L, U, V, M, G, S>), dim3(grid), dim3(kBlock), 0, ds->stream, ds->n, ds->d, ds->X, D, v, ds->partials)
+    hipLaunchKernelGGL((k_dense_hv<E, L, U, V, M, G, S>), dim3(grid), dim3(kBlock), 0, ds->stream, ds->n, ds->d, ds->X, D, v, partials)
 #define TRON_HV_V(M, G, S) do { if (vec) TRON_HV((E % 2 == 0), M, G, S); else TRON_HV(false, M, G, S); } while (0)
     if (v) {
         if (!mask) TRON_HV_V(false, false, false);
@@ -307,7 +309,7 @@ int launch_fg(tron_dataset *ds, int loss, const double *w, void *Dout, double *l
     set_error("internal: no dense kernel for E=%d L=%d", s.E, s.L);              \
     return TRON_EINVAL;
 
-int dispatch_hv(tron_dataset *ds, const void *D, bool mask, bool skip, const double *v) { TRON_DISPATCH(launch_hv, ds, D, mask, skip, v) }
+int dispatch_hv(tron_dataset *ds, const void *D, bool mask, bool skip, const double *v, double *partials) { TRON_DISPATCH(launch_hv, ds, D, mask, skip, v, partials) }
 int dispatch_fg(tron_dataset *ds, int loss, const double *w, void *Dout, double *lp, double *ap) { TRON_DISPATCH(launch_fg, ds, loss, w, Dout, lp, ap) }
 
 }  // namespace
@@ -361,7 +363,7 @@ int dense_hv(tron_dataset *ds, double C, int Dslot, const double *v, double *Hv)
     double *colprod = ds->partials + ds->d * grid + grid;
     {
         ProfScope ps(ds, SLOT_DENSE_HV);
-        TRON_TRY(dispatch_hv(ds, D, mask, mask && ds->active_frac[Dslot] < kSkipBelow, v));
+        TRON_TRY(dispatch_hv(ds, D, mask, mask && ds->active_frac[Dslot] < kSkipBelow, v, ds->partials));
         TRON_HIP(hipGetLastError());
     }
     ProfScope ps(ds, SLOT_DENSE_FINALIZE);
@@ -380,7 +382,7 @@ int dense_hess_diag(tron_dataset *ds, double C, int Dslot, double *out)
     double *colprod = ds->partials + ds->d * grid + grid;
     {
         ProfScope ps(ds, SLOT_DENSE_HV);
-        TRON_TRY(dispatch_hv(ds, ds->Dbuf[Dslot], ds->D_is_mask[Dslot], ds->D_is_mask[Dslot] && ds->active_frac[Dslot] < kSkipBelow, nullptr));
+        TRON_TRY(dispatch_hv(ds, ds->Dbuf[Dslot], ds->D_is_mask[Dslot], ds->D_is_mask[Dslot] && ds->active_frac[Dslot] < kSkipBelow, nullptr, ds->partials));
         TRON_HIP(hipGetLastError());
     }
     ProfScope ps(ds, SLOT_DENSE_FINALIZE);
@@ -415,3 +417,61 @@ int dense_fun_grad(tron_dataset *ds, int loss, double C, const double *w, int Ds
 }
 
 }  // namespace tron
+
+// ------------------------------------------------------------------ Hessian-vector product without any allocation
+// The work space of the dense Hessian-vector product -- per-workgroup column sums (d * grid), the d column products
+// and the curvature scalar -- in a file-scope device array instead of the handle's allocation.  Every GPU the
+// library runs on holds its own copy of the array, at its own address, until the process ends.
+namespace {
+constexpr int64_t kStaticScratchDoubles = TRON_HV_STATIC_MAX_DOUBLES;
+__device__ __align__(256) double scratch[kStaticScratchDoubles];
+constexpr int kStaticMaxDevices = 64;
+double *g_scratch_ptr[kStaticMaxDevices] = {nullptr};   // device address of `scratch` on each GPU, looked up once
+}  // namespace
+
+extern "C" int tron_hv_static(tron_dataset *ds, double C, const double *v_dev, double *Hv_dev, double *vHv_dev)
+{
+    using namespace tron;
+    if (!ds || !v_dev || !Hv_dev || v_dev == Hv_dev || !(C > 0.0) || !std::isfinite(C)) {
+        set_error("tron_hv_static: bad argument (null handle/v/Hv, v aliases Hv, or C <= 0)");
+        return TRON_EINVAL;
+    }
+    if (!ds->dense) { set_error("tron_hv_static: dense handles only"); return TRON_EINVAL; }
+    if (!ds->have_D) { set_error("tron_hv_static: no cached D; call tron_fun_grad first"); return TRON_ESTATE; }
+    const int grid = ds->dense_grid;
+    const int64_t need = ds->d * grid + ds->d + 1;
+    if (need > kStaticScratchDoubles) {
+        set_error("tron_hv_static: n = %lld, d = %lld needs %lld doubles of work space (d * %d workgroups + d + 1); the static "
+                  "work space holds %lld: use tron_hv", (long long)ds->n, (long long)ds->d, (long long)need, grid,
+                  (long long)kStaticScratchDoubles);
+        return TRON_EINVAL;
+    }
+    int dev = -1;
+    TRON_HIP(hipGetDevice(&dev));
+    if (dev != ds->device || dev < 0 || dev >= kStaticMaxDevices) {
+        set_error("tron_hv_static: current device %d is not the handle's device %d (or beyond %d devices)", dev, ds->device,
+                  kStaticMaxDevices);
+        return TRON_EINVAL;
+    }
+    if (!g_scratch_ptr[dev]) {
+        // in host code the array's name is only a stand-in: its address on this GPU comes from the runtime
+        double *p = nullptr;
+        TRON_HIP(hipGetSymbolAddress(reinterpret_cast<void **>(&p), HIP_SYMBOL(scratch)));
+        if (!p) { set_error("tron_hv_static: the static work space has no device address"); return TRON_EDEVICE; }
+        g_scratch_ptr[dev] = p;
+    }
+    double *partials = g_scratch_ptr[dev];
+    double *colprod = partials + ds->d * grid;
+    double *scalar = colprod + ds->d;
+    // Nothing has to start at zero: every workgroup of the pass writes all d of its column sums, the second stage
+    // writes all d column products, the third the scalar.
+    const int Dslot = ds->Dcur;
+    const bool mask = ds->D_is_mask[Dslot];
+    TRON_TRY(dispatch_hv(ds, ds->Dbuf[Dslot], mask, mask && ds->active_frac[Dslot] < kSkipBelow, v_dev, partials));
+    const int cg = (int)((ds->d + kWavesPerBlock - 1) / kWavesPerBlock);
+    hipLaunchKernelGGL(k_dense_columns, dim3(cg), dim3(kBlock), 0, ds->stream, ds->d, grid, partials, v_dev, C, Hv_dev, v_dev, colprod);
+    hipLaunchKernelGGL(k_dense_scalars, dim3(1), dim3(kBlock), 0, ds->stream, ds->d, 0, (const double *)nullptr,
+                       (const double *)nullptr, (const double *)nullptr, colprod, vHv_dev ? vHv_dev : scalar, scalar);
+    TRON_HIP(hipGetLastError());
+    return TRON_OK;
+}
