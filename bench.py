@@ -28,15 +28,21 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 
-# library profiler slot -> (kernel name in rocprofv3 output, profiles/ file that holds its byte counters)
+# (workload, library profiler slot) -> (kernel name in rocprofv3 output, profiles/ file that holds its byte counters).
+# The counters were read on exactly that workload at full size; any other run reports traffic = null.
 ROCPROF_NAMES = {
-    "dense_hv": ("k_dense_hv<6, 4, 4, true, true, false, false>", "dense_hv_fun_grad_c5.md"),
-    "dense_fun_grad": ("k_dense_fun_grad<6, 4, 4, true, 1>", "dense_hv_fun_grad_c5.md"),
+    ("c5", "dense_hv"): ("k_dense_hv<6, 4, 4, true, true, false, false>", "dense_hv_fun_grad_c5.md"),
+    ("c5", "dense_fun_grad"): ("k_dense_fun_grad<6, 4, 4, true, 1>", "dense_hv_fun_grad_c5.md"),
     # config 3 has one value per instance: its layouts keep no value stream and run the "unit" kernels
-    "spmv_head": ("k_head_sell", "csr_spmv_c3.md"),
-    "spmv_fwd": ("k_csr_spmv_part<true, false, false, true>", "csr_spmv_c3.md"),
-    "spmv_bwd": ("k_csr_spmv_part<false, false, false, true>", "csr_spmv_c3.md"),
-    "spmv_tiles": ("k_hot_tiles_unit", "csr_spmv_c3.md"),
+    ("c3", "spmv_head"): ("k_head_sell", "csr_spmv_c3.md"),
+    ("c3", "spmv_fwd"): ("k_csr_spmv_part<true, false, false, true>", "csr_spmv_c3.md"),
+    ("c3", "spmv_bwd"): ("k_csr_spmv_part<false, false, false, true>", "csr_spmv_c3.md"),
+    ("c3", "spmv_tiles"): ("k_hot_tiles_unit", "csr_spmv_c3.md"),
+    # the same matrix with the general layout forced (csr_unit = 0: 32-bit / 16-bit indices + fp64 values)
+    ("c3_values", "spmv_head"): ("k_csr_spmv_part<true, true, false, false>", "csr_spmv_c3_values.md"),
+    ("c3_values", "spmv_fwd"): ("k_csr_spmv_part<true, false, false, false>", "csr_spmv_c3_values.md"),
+    ("c3_values", "spmv_bwd"): ("k_csr_spmv_part<false, false, false, false>", "csr_spmv_c3_values.md"),
+    ("c3_values", "spmv_tiles"): ("k_hot_tiles<false>", "csr_spmv_c3_values.md"),
 }
 
 
@@ -92,38 +98,56 @@ def upload(tron, workload):
     return tron.Dataset.from_problem(workload)
 
 
-def algorithmic_bytes(ds, stat, kernel: str) -> float:
-    """Bytes the method has to move per launch of the named kernel: 12 B per nonzero (int32 column + fp64 value),
-    8 B per row pointer / vector element touched; the fused dense pass reads X once."""
-    n, d, nnz = ds.n, ds.d, ds.nnz
+def format_bytes(ds, stat, kernel: str) -> float:
+    """Bytes one launch of the named kernel has to move in the format the handle actually stores (the library's own
+    count: index / value streams, flag bits, tables, every needed vector element once, partial sums and results
+    written).  This is the numerator of every reported HBM fraction: the kernel cannot move fewer bytes, so the
+    fraction cannot exceed 1."""
+    key = {"dense_hv": "hv_bytes", "dense_fun_grad": "fun_grad_bytes", "spmv_head": "fwd_bytes_head",
+           "spmv_fwd": "fwd_bytes_ranges", "spmv_tiles": "bwd_bytes_tiles", "spmv_bwd": "bwd_bytes_ranges",
+           "spmv_gather": "fwd_bytes_gather", "spmv_tile_reduce": "bwd_bytes_tile_reduce"}.get(kernel)
+    if kernel == "spmv_combine":   # two launches per call (forward with D, transposed with the addend): their mean
+        return 0.5 * (stat("fwd_bytes_combine") + 8.0 * ds.n + stat("bwd_bytes_combine") + 8.0 * ds.d)
+    if key is None:
+        raise KeyError(kernel)
+    v = float(stat(key))
+    if v <= 0.0:
+        raise KeyError(kernel)
+    return v
+
+
+def work_bytes(ds, stat, kernel: str) -> float:
+    """The format-independent count of the method's description: 12 B per nonzero (int32 column + fp64 value) and 8 B
+    per vector element touched; X once for the fused dense pass.  Reported as a rate of work done ("work_GB/s"), never
+    as an HBM fraction: layouts without a value stream move fewer bytes than this."""
+    n, d = ds.n, ds.d
     if kernel == "dense_hv":
-        return 8.0 * n * d + 8.0 * n                       # X once + D
+        return 8.0 * n * d + 8.0 * n
     if kernel == "dense_fun_grad":
-        return 8.0 * n * d + 16.0 * n                      # X once + y read + D written
-    # Sparse kernels: 12 B per nonzero they process, 8 B per element of the vector they gather from and of the
-    # row sums they write (their shares add up to the 24 nnz + O(n + d) of one Hv call).
-    if kernel == "spmv_head":                              # head partition of X: LDS-table gathers only
+        return 8.0 * n * d + 16.0 * n
+    if kernel == "spmv_head":
         return 12.0 * stat("fwd_head_nnz") + 8.0 * n
-    if kernel == "spmv_fwd":                               # the rest of X (all of it when there is no head partition)
+    if kernel == "spmv_fwd":
         return 12.0 * (stat("fwd_csr_nnz") - stat("fwd_head_nnz")) + 8.0 * d + 8.0 * n
-    if kernel == "spmv_tiles":                             # hot rows of the transposed copy
+    if kernel == "spmv_tiles":
         return 12.0 * stat("bwd_tile_nnz") + 8.0 * n
-    if kernel == "spmv_bwd":                               # the rest of the transposed copy
+    if kernel == "spmv_bwd":
         return 12.0 * stat("bwd_csr_nnz") + 8.0 * n + 8.0 * d
     raise KeyError(kernel)
 
 
-def hv_call_bytes(ds) -> float:
+def hv_work_bytes(ds) -> float:
     if ds.dense:
         return 8.0 * ds.n * ds.d + 8.0 * ds.n
     return 24.0 * ds.nnz + 32.0 * ds.n + 32.0 * ds.d
 
 
-def measured_traffic(slot: str):
-    """HBM-side bytes per launch from the committed rocprofv3 counter summaries (FETCH_SIZE + WRITE_SIZE, scaled)."""
-    if slot not in ROCPROF_NAMES:
+def measured_traffic(profile_key, slot: str):
+    """HBM-side bytes per launch from the committed rocprofv3 counter summaries (FETCH_SIZE + WRITE_SIZE, scaled);
+    None unless this run is the workload the summary was taken on."""
+    if profile_key is None or (profile_key, slot) not in ROCPROF_NAMES:
         return None
-    kname, fname = ROCPROF_NAMES[slot]
+    kname, fname = ROCPROF_NAMES[(profile_key, slot)]
     path = os.path.join(ROOT, "profiles", fname)
     if not os.path.exists(path):
         return None
@@ -141,8 +165,26 @@ def measured_traffic(slot: str):
     return None
 
 
-def cpu_baseline(workload, loss, C, budget_s: float = 15.0):
-    """The CPU oracle timed on this host, one thread, on a bounded sample of the same workload."""
+def pin_to_one_core():
+    """Pins this process to one of the cores it may run on (the oracle is single-threaded; pinning keeps it from
+    migrating).  Returns (core, previous affinity) -- restore with os.sched_setaffinity(0, previous)."""
+    prev = os.sched_getaffinity(0)
+    core = max(prev)   # away from core 0, where the runtime's helper threads tend to sit
+    os.sched_setaffinity(0, {core})
+    return core, prev
+
+
+def cpu_baseline(workload, loss, C, eps=None, budget_s: float = 15.0, full_solve: bool = False):
+    """The CPU oracle timed on this host, one thread pinned to one core, on a bounded sample of the same workload;
+    with full_solve also one complete oracle solve (config 3: about half a minute)."""
+    core, prev = pin_to_one_core()
+    try:
+        return _cpu_baseline(workload, loss, C, eps, budget_s, full_solve, core)
+    finally:
+        os.sched_setaffinity(0, prev)
+
+
+def _cpu_baseline(workload, loss, C, eps, budget_s, full_solve, core):
     import numpy as np
     import datagen as dg
     from oracle import Oracle
@@ -177,12 +219,24 @@ def cpu_baseline(workload, loss, C, budget_s: float = 15.0):
                 break
     except OSError:
         pass
-    return {
-        "value": scale / med, "unit": "Hv/s", "cores": 1, "kind": "oracle", "host_cpu": cpu_model, "host_nproc": os.cpu_count(),
+    out = {
+        "value": scale / med, "unit": "Hv/s", "cores": 1, "pinned_to_core": core, "kind": "oracle", "host_cpu": cpu_model,
+        "host_nproc": os.cpu_count(),
         "sample": f"{len(times)} oracle Hv calls, {sample}; median {med:.3f} s per sampled call; "
                   f"one fun+grad took {t_fg:.3f} s",
         "fun_grad_per_s": scale / t_fg,
     }
+    if full_solve and scale == 1.0:
+        log("  oracle: one full solve")
+        t0 = time.perf_counter()
+        ref = o.tron(loss, C, eps)
+        t_solve = time.perf_counter() - t0
+        out["solve"] = {"seconds": t_solve, "outer_iters": ref.outer_iters, "cg_iters": ref.cg_iters_total, "f": ref.f,
+                        "converged": ref.converged, "hv_per_s_over_the_solve": ref.n_hv / t_solve}
+        out["sample"] += f"; one full oracle solve took {t_solve:.1f} s"
+    else:
+        out["solve"] = None   # the sample is a part of the matrix: no whole solve is timed
+    return out
 
 
 def run_workload(args, wname: str) -> dict:
@@ -247,6 +301,7 @@ def run_workload(args, wname: str) -> dict:
     Hv = torch.empty_like(v)
     w.zero_()
     ds.fun_grad(loss, C, w, g)
+    hv_fmt, fg_fmt = float(stat("hv_bytes")), float(stat("fun_grad_bytes"))   # for the D cached now (w = 0: every row active)
     for _ in range(3):
         ds.hv(C, v, Hv, want_vHv=False)
     torch.cuda.synchronize()
@@ -280,28 +335,56 @@ def run_workload(args, wname: str) -> dict:
 
     kernels = {k: {"ms": r["ms"] / r["calls"], "calls_per_hv": r["calls"] / args.hv_reps} for k, r in prof_hv.items()}
     kernels_fg = {k: {"ms": r["ms"] / r["calls"], "calls_per_fun_grad": r["calls"] / fg_reps} for k, r in prof_fg.items()}
-    big = [k for k in kernels if k in ("dense_hv", "spmv_head", "spmv_fwd", "spmv_bwd", "spmv_tiles")]
-    dominant = max(big, key=lambda k: kernels[k]["ms"])
-    dom_ms = kernels[dominant]["ms"]
-    dom_bytes = algorithmic_bytes(ds, stat, dominant)
-    achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(dominant),
-                "ms_per_launch": dom_ms, "algorithmic_bytes_per_launch": dom_bytes}
-    if not ds.dense and stat("unit_values"):
-        roofline["note"] = ("algorithmic bytes count 12 B per nonzero (int32 column + fp64 value); every instance of this matrix has "
-                            "one value for all its entries, so the layouts keep no value stream and the kernel moves fewer bytes than "
-                            "that (traffic): it is bound by issue and latency, not by HBM, and frac can exceed 1")
-    def with_rates(table):
+    # HBM fractions are computed from the bytes the stored format makes the kernel move (library count, read while the
+    # D of the timed calls is cached); the format-independent 12 B / nonzero count is reported beside them as a rate of
+    # work ("work_GB/s"), which can exceed the peak for layouts without a value stream and is never called a fraction.
+    profile_key = None
+    if args.scale == 1.0 and wname in ("c3", "c5"):
+        profile_key = wname if (ds.dense or stat("unit_values")) else "c3_values"
+
+    def kernel_roofline(k, ms, table_name):
+        fb = format_bytes(ds, stat, k) if k != "dense_hv" else hv_fmt
+        if k == "dense_fun_grad":
+            fb = fg_fmt
+        rec = {"kernel": k, "in": table_name, "bound": "hbm", "achieved": fb / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+               "frac": fb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": measured_traffic(profile_key, k), "ms_per_launch": ms,
+               "format_bytes_per_launch": fb}
+        try:
+            rec["work_GB/s"] = work_bytes(ds, stat, k) / (ms * 1e-3) / 1e9
+        except KeyError:
+            pass
+        return rec
+
+    def with_rates(table, table_name):
         outk = {}
         for k, rec in table.items():
             outk[k] = dict(rec)
             try:
-                gbs = algorithmic_bytes(ds, stat, k) / (rec["ms"] * 1e-3) / 1e9
-                outk[k].update({"GB/s": gbs, "frac": gbs / HBM_PEAK_GBS})
+                r = kernel_roofline(k, rec["ms"], table_name)
+                outk[k].update({"GB/s": r["achieved"], "frac": r["frac"], "format_bytes": r["format_bytes_per_launch"]})
+                if "work_GB/s" in r:
+                    outk[k]["work_GB/s"] = r["work_GB/s"]
             except KeyError:
                 pass
         return outk
+
+    big = [k for k in kernels if k in ("dense_hv", "spmv_head", "spmv_fwd", "spmv_bwd", "spmv_tiles")]
+    dominant = max(big, key=lambda k: kernels[k]["ms"])
+    roofline = kernel_roofline(dominant, kernels[dominant]["ms"], "kernels_hv")
+    roofline["workload"] = name
+    # every other large kernel of the two calls, and the calls as a whole
+    roofline["also"] = [dict(kernel_roofline(k, kernels[k]["ms"], "kernels_hv"), workload=name) for k in big if k != dominant]
+    roofline["also"] += [dict(kernel_roofline(k, kernels_fg[k]["ms"], "kernels_fun_grad"), workload=name)
+                         for k in kernels_fg if k in ("dense_fun_grad",)]
+    roofline["also"].append({"kernel": "one tron_hv call (all its kernels)", "workload": name, "bound": "hbm",
+                             "achieved": hv_fmt / hv_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                             "frac": hv_fmt / hv_s / 1e9 / HBM_PEAK_GBS, "ms_per_launch": hv_s * 1e3,
+                             "format_bytes_per_launch": hv_fmt, "work_GB/s": hv_work_bytes(ds) / hv_s / 1e9, "traffic": None})
+    if not ds.dense:
+        roofline["note"] = ("frac = bytes the kernel must move in the stored format / time / 8 TB/s." +
+                            (" Every instance of this matrix has one value for all its entries, so the layouts keep no value stream "
+                             "(2-4 B per nonzero): the head-partition and tile kernels are bound by LDS gathers and instruction issue, "
+                             "the range kernels by L2 requests, not by HBM bytes." if stat("unit_values") else ""))
 
     out = {
         "metric": "Hessian-vector products/sec (sustained over full TRON solves) + % HBM peak; end-to-end TRON solve seconds",
@@ -317,12 +400,14 @@ def run_workload(args, wname: str) -> dict:
         "solve_preconditioned": {"precond_blend": 0.01, "seconds": pcg_s, "outer_iters": pres.outer_iters,
                                  "cg_iters": pres.cg_iters_total, "n_hv": pres.n_hv, "f": pres.f, "gnorm": pres.gnorm,
                                  "converged": pres.converged},
-        "hv_call": {"per_s": 1.0 / hv_s, "ms": hv_s * 1e3, "GB/s": hv_call_bytes(ds) / hv_s / 1e9,
-                    "frac_hbm_peak": hv_call_bytes(ds) / hv_s / 1e9 / HBM_PEAK_GBS, "algorithmic_bytes": hv_call_bytes(ds),
+        "hv_call": {"per_s": 1.0 / hv_s, "ms": hv_s * 1e3, "GB/s": hv_fmt / hv_s / 1e9,
+                    "frac_hbm_peak": hv_fmt / hv_s / 1e9 / HBM_PEAK_GBS, "format_bytes": hv_fmt,
+                    "work_bytes": hv_work_bytes(ds), "work_GB/s": hv_work_bytes(ds) / hv_s / 1e9,
                     "event_ms_median": hv_each[len(hv_each) // 2], "event_ms_min": hv_each[0]},
-        "fun_grad_call": {"per_s": 1.0 / fg_s, "ms": fg_s * 1e3},
-        "kernels_hv": with_rates(kernels),
-        "kernels_fun_grad": with_rates(kernels_fg),
+        "fun_grad_call": {"per_s": 1.0 / fg_s, "ms": fg_s * 1e3, "format_bytes": fg_fmt, "GB/s": fg_fmt / fg_s / 1e9,
+                          "frac_hbm_peak": fg_fmt / fg_s / 1e9 / HBM_PEAK_GBS},
+        "kernels_hv": with_rates(kernels, "kernels_hv"),
+        "kernels_fun_grad": with_rates(kernels_fg, "kernels_fun_grad"),
         "roofline": roofline,
     }
     if not ds.dense:
@@ -330,7 +415,7 @@ def run_workload(args, wname: str) -> dict:
                                              "bwd_tile_nnz", "bwd_tile_rows", "bwd_tiles", "unit_values")}
     if not args.no_cpu_baseline:
         log("timing the CPU oracle (one thread, bounded sample)")
-        out["cpu_baseline"] = cpu_baseline(workload, loss, C)
+        out["cpu_baseline"] = cpu_baseline(workload, loss, C, eps, full_solve=(wname == "c3"))
     else:
         out["cpu_baseline"] = None
     ds.close()
@@ -344,7 +429,8 @@ def small_config(args, wname: str) -> dict:
     sub = run_workload(argparse.Namespace(**{**vars(args), "no_cpu_baseline": True, "steps": 5, "warmup": 1}), wname)
     out = {"config": sub["config"]["workload"], "solve_ms": sub["ms_per_step"], "solve_min_ms": sub["solve"]["min_seconds"] * 1e3,
            "outer_iters": sub["solve"]["outer_iters"], "cg_iters": sub["solve"]["cg_iters"], "f": sub["solve"]["f"],
-           "hv_ms": sub["hv_call"]["ms"], "hv_effective_GB/s": sub["hv_call"]["GB/s"], "hv_frac_hbm_peak": sub["hv_call"]["frac_hbm_peak"],
+           "hv_ms": sub["hv_call"]["ms"], "hv_format_GB/s": sub["hv_call"]["GB/s"], "hv_frac_hbm_peak": sub["hv_call"]["frac_hbm_peak"],
+           "hv_work_GB/s": sub["hv_call"]["work_GB/s"],
            "fun_grad_ms": sub["fun_grad_call"]["ms"], "solve_preconditioned": sub["solve_preconditioned"],
            "kernels_hv": sub["kernels_hv"], "cpu_baseline": None}
     if not args.no_cpu_baseline:
@@ -554,6 +640,10 @@ def main() -> int:
         sub = run_workload(args, also)
         keep = ("value", "unit", "ms_per_step", "config", "solve", "solve_preconditioned", "hv_call", "fun_grad_call", "kernels_hv", "kernels_fun_grad", "roofline", "cpu_baseline")
         out["also"] = {also: {k: sub[k] for k in keep}}
+        # the second workload's rooflines travel inside the primary roofline object as well
+        extra = dict(sub["roofline"])
+        out["roofline"]["also"].append({k: v for k, v in extra.items() if k != "also"})
+        out["roofline"]["also"] += extra.get("also", [])
     if args.workload == "c3" and args.scale == 1.0 and args.also is None:
         out["others"] = {w: small_config(args, w) for w in ("c1", "c2", "c4")}
         # the other loss / storage mixes (GPU only: their oracle solves take minutes)
@@ -565,7 +655,10 @@ def main() -> int:
         try:
             sub = run_workload(argparse.Namespace(**{**vars(args), "no_cpu_baseline": True, "steps": 2, "warmup": 1}), "c3")
             out["c3_with_value_stream"] = {"hv_call": sub["hv_call"], "solve_ms": sub["ms_per_step"], "kernels_hv": sub["kernels_hv"],
-                                           "layout": sub["layout"]}
+                                           "layout": sub["layout"], "roofline": sub["roofline"]}
+            for r in [sub["roofline"]] + sub["roofline"].get("also", []):
+                out["roofline"]["also"].append(dict({k: v for k, v in r.items() if k != "also"},
+                                                    workload=sub["config"]["workload"] + " with the value stream (csr_unit = 0)"))
         finally:
             tron.tron_tuning_set("csr_unit", 1)
         out["cross_validation"] = cross_validation_configs()

@@ -73,14 +73,16 @@ TRON_API int tron_dataset_create_csr(int64_t n, int64_t d, const int64_t *rowptr
                                      const double *val, const double *y, int mem, void *hip_stream,
                                      tron_dataset **out);
 
-/* Dense input: X row-major n*d fp64 with leading dimension d, y fp64[n] in {+1,-1}. */
+/* Dense input: X row-major n*d fp64 with leading dimension d (finite), y fp64[n] exactly +1.0 or -1.0; host or device
+ * pointers per mem, checked either way (device input by a kernel): TRON_EINVAL and nothing created otherwise. */
 TRON_API int tron_dataset_create_dense(int64_t n, int64_t d, const double *X_rowmajor, const double *y, int mem,
                                        void *hip_stream, tron_dataset **out);
 
 /*
  * Dense dataset filled in row chunks (for matrices too large to stage on the host at once):
  * create_dense_empty allocates n*d on the device with undefined contents; write_rows copies
- * nrows rows starting at row0 (X_chunk row-major nrows*d, y_chunk nrows; host or device per mem).
+ * nrows rows starting at row0 (X_chunk row-major nrows*d, y_chunk nrows; host or device per mem).  A chunk with a
+ * label other than +1 / -1 or a non-finite entry returns TRON_EINVAL and writes nothing.
  * Every row must be written once before the first compute call; this is not checked.
  */
 TRON_API int tron_dataset_create_dense_empty(int64_t n, int64_t d, void *hip_stream, tron_dataset **out);
@@ -102,6 +104,14 @@ TRON_API int tron_dataset_shape(const tron_dataset *ds, int64_t *n, int64_t *d, 
  *   "fwd_lds_columns"          columns served from LDS tables in the forward pass
  *   "dense_grid"               workgroups of the dense kernels
  *   "unit_values"              1 when the sparse layouts keep no values (every instance's entries share one value)
+ *   "fwd_bytes_gather", "fwd_bytes_head", "fwd_bytes_ranges", "fwd_bytes_combine",
+ *   "bwd_bytes_tiles", "bwd_bytes_tile_reduce", "bwd_bytes_ranges", "bwd_bytes_combine"
+ *                              bytes one launch of that kernel of the forward / transposed product has to move in the
+ *                              format the handle stores (index and value streams, flag bits, tables, each needed vector
+ *                              element once, partial sums and results written); 0 for dense handles and absent parts
+ *   "hv_bytes", "fun_grad_bytes"  the same for a whole tron_hv / tron_fun_grad call with the currently cached D (dense:
+ *                              X once -- only the active rows when the pass skips the others -- plus D or the
+ *                              active-set bits); these are the denominators of the reported HBM fractions
  * Unknown names return TRON_EINVAL.
  */
 TRON_API int tron_dataset_stat(const tron_dataset *ds, const char *name, int64_t *value);

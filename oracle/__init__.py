@@ -53,6 +53,8 @@ class _Result(ctypes.Structure):
                 ("n_grad", ctypes.c_int), ("n_hv", ctypes.c_int), ("converged", ctypes.c_int)]
 
 
+_PROGRESS_FN = ctypes.CFUNCTYPE(None, ctypes.POINTER(TraceRec))
+
 _libs = {}
 
 
@@ -78,6 +80,8 @@ def _L(plain_fp64=False):
         lib.orc_hess_diag.argtypes = [P(_Data), dbl, vp, vp]
         lib.orc_pcg.argtypes = [P(_Data), dbl, vp, vp, vp, dbl, dbl, ci, vp, vp, P(ci), P(ci)]
         lib.orc_tron_pcg.argtypes = [P(_Data), ci, dbl, dbl, ci, ci, dbl, dbl, vp, P(_Result), P(TraceRec), ci, P(ci)]
+        lib.orc_set_progress.argtypes = [_PROGRESS_FN]
+        lib.orc_set_progress.restype = None
         for f in (lib.orc_fun, lib.orc_grad, lib.orc_hv, lib.orc_cg, lib.orc_tron, lib.orc_hess_diag, lib.orc_pcg, lib.orc_tron_pcg):
             f.restype = ci
         _libs[plain_fp64] = lib
@@ -205,8 +209,18 @@ class Oracle:
         return s, r, nhv.value, bool(onb.value)
 
     def tron(self, loss: int, C: float, eps: float, w0=None, max_outer: int = 1000, max_cg: int = 1000,
-             xi: float = 0.1, trace_cap: int = 1024, precond_blend=None) -> SolveResult:
-        """precond_blend = None: plain CG; a number a in (0, 1]: CG preconditioned by (1-a) I + a diag(H)."""
+             xi: float = 0.1, trace_cap: int = 1024, precond_blend=None, progress=None) -> SolveResult:
+        """precond_blend = None: plain CG; a number a in (0, 1]: CG preconditioned by (1-a) I + a diag(H).
+        progress: called with the record (a dict) of every finished outer iteration, for long solves."""
+        lib = _L(self._plain)
+        cb = _PROGRESS_FN(lambda rec: progress({k: getattr(rec.contents, k) for k, _ in TraceRec._fields_})) if progress else None
+        lib.orc_set_progress(cb if cb else _PROGRESS_FN())
+        try:
+            return self._tron(loss, C, eps, w0, max_outer, max_cg, xi, trace_cap, precond_blend)
+        finally:
+            lib.orc_set_progress(_PROGRESS_FN())
+
+    def _tron(self, loss, C, eps, w0, max_outer, max_cg, xi, trace_cap, precond_blend) -> SolveResult:
         w = np.zeros(self.d) if w0 is None else _f64(w0).copy()
         res = _Result()
         trace = (TraceRec * trace_cap)()

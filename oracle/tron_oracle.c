@@ -387,6 +387,12 @@ typedef struct {
     int outer_iters, cg_iters_total, n_fun, n_grad, n_hv, converged;
 } orc_result;
 
+/* Optional observer, called with the record of every finished outer iteration (a long solve can report where it
+ * is); it sees the values and changes nothing. */
+typedef void (*orc_progress_fn)(const orc_trace_rec *);
+static orc_progress_fn progress_fn = NULL;
+ORC_API void orc_set_progress(orc_progress_fn fn) { progress_fn = fn; }
+
 /*
  * Algorithm 1 with the blanks filled in as follows (the paper names sigma_0 only):
  *   - Delta_0 = |grad f(w_0)|;
@@ -487,10 +493,10 @@ static int tron_impl(const orc_data *A, int loss, double C, double eps, int max_
             }
         }
         res->outer_iters = k;
-        if (trace && tl < trace_cap) {
-            orc_trace_rec *t = &trace[tl++];
-            t->iter = k; t->cg_iters = ncg; t->accepted = accepted; t->on_boundary = onb;
-            t->f = f; t->gnorm = gnorm; t->delta = delta; t->ared = ared; t->pred = pred; t->snorm = snorm;
+        {
+            const orc_trace_rec rec = { k, ncg, accepted, onb, f, gnorm, delta, ared, pred, snorm };
+            if (trace && tl < trace_cap) trace[tl++] = rec;
+            if (progress_fn) progress_fn(&rec);
         }
         if (accepted && gnorm <= eps * res->gnorm0) { status = 0; res->converged = 1; break; }
         if (pred <= 0.0 || (noise && gnorm >= gnorm_before)) break;

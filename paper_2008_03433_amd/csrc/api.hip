@@ -357,6 +357,12 @@ int tron_dataset_write_rows(tron_dataset *ds, int64_t row0, int64_t nrows, const
         TRON_TRY(check_labels(y_chunk, nrows));
         for (int64_t k = 0; k < nrows * ds->d; ++k)
             if (!std::isfinite(X_chunk[k])) { set_error("X has a non-finite entry in row %lld", (long long)(row0 + k / ds->d)); return TRON_EINVAL; }
+    } else {
+        // the same checks on the device, before anything is copied
+        int what = 0;
+        TRON_TRY(dense_validate_device(ds, nrows, X_chunk, y_chunk, &what));
+        if (what == 1) { set_error("a label in rows [%lld, %lld) is not +1 or -1", (long long)row0, (long long)(row0 + nrows)); return TRON_EINVAL; }
+        if (what == 2) { set_error("X has a non-finite entry in rows [%lld, %lld)", (long long)row0, (long long)(row0 + nrows)); return TRON_EINVAL; }
     }
     const hipMemcpyKind kind = (mem == TRON_MEM_HOST) ? hipMemcpyHostToDevice : hipMemcpyDeviceToDevice;
     TRON_HIP(hipMemcpyAsync(ds->X + row0 * ds->d, X_chunk, sizeof(double) * (size_t)nrows * (size_t)ds->d, kind, ds->stream));
@@ -399,7 +405,28 @@ int tron_dataset_shape(const tron_dataset *ds, int64_t *n, int64_t *d, int64_t *
 int tron_dataset_stat(const tron_dataset *ds, const char *name, int64_t *value)
 {
     if (!ds || !name || !value) { set_error("tron_dataset_stat: null argument"); return TRON_EINVAL; }
+    // bytes per launch in the stored format (see PlanBytes); the Hessian-vector call adds the vectors of the call itself
+    PlanBytes fb{0, 0, 0, 0, 0, 0}, bb{0, 0, 0, 0, 0, 0};
+    int64_t hv_bytes = 0, fun_grad_bytes = 0;
+    if (ds->dense) {
+        // X once (the active rows only when the pass skips the others), D or the active-set bits / bytes, per-workgroup sums
+        const int slot = ds->Dcur;
+        const bool mask = ds->have_D && ds->D_is_mask[slot];
+        const double frac = (mask && ds->active_frac[slot] < 0.95) ? ds->active_frac[slot] : 1.0;
+        const int64_t dbytes = !mask ? 8 * ds->n : (ds->d <= 32 ? ds->n / 8 : ds->n);
+        hv_bytes = (int64_t)(8.0 * frac * (double)ds->n * (double)ds->d) + dbytes + 8 * ds->d * ds->dense_grid;
+        fun_grad_bytes = 8 * ds->n * ds->d + ds->n /* labels */ + dbytes + 8 * ds->d * ds->dense_grid;
+    } else {
+        fb = plan_bytes(ds->fwd);
+        bb = plan_bytes(ds->bwd);
+        hv_bytes = fb.gather + fb.head + fb.ranges + fb.combine + 8 * ds->n /* D */ +
+                   bb.tiles + bb.tile_reduce + bb.ranges + bb.combine + 8 * ds->d /* v as addend */;
+        fun_grad_bytes = hv_bytes + 8 * ds->n /* y */ + 8 * ds->n /* zhat and D both written */;
+    }
     struct { const char *k; int64_t v; } tab[] = {
+        {"fwd_bytes_gather", fb.gather}, {"fwd_bytes_head", fb.head}, {"fwd_bytes_ranges", fb.ranges}, {"fwd_bytes_combine", fb.combine},
+        {"bwd_bytes_tiles", bb.tiles}, {"bwd_bytes_tile_reduce", bb.tile_reduce}, {"bwd_bytes_ranges", bb.ranges},
+        {"bwd_bytes_combine", bb.combine}, {"hv_bytes", hv_bytes}, {"fun_grad_bytes", fun_grad_bytes},
         {"fwd_parts", ds->dense ? 0 : ds->fwd.P},
         {"bwd_parts", ds->dense ? 0 : ds->bwd.P},
         {"fwd_csr_nnz", ds->dense ? 0 : ds->fwd.nnz},

@@ -136,6 +136,8 @@ struct HotTiles {
     int64_t tile0[kTileSlices] = {0};    // first tile of slice s
     int64_t ntiles[kTileSlices] = {0};
     int blocks_per_slice = 0;            // persistent workgroups per slice
+    int64_t nseg_padded = 0;             // entries of seg_slot (every tile's block padded to a multiple of 8)
+    int64_t span_total = 0;              // sum over the tiles of the columns they span (what the kernels copy into LDS)
     double *val = nullptr;               // device, ntiles_total * kChunk (zero padded); null for a unit plan
     uint16_t *iloc = nullptr;            // device, ntiles_total * kChunk: column minus the tile's first column
     uint8_t *flags = nullptr;            // device, ntiles_total * 256: bit e of byte t = entry 8t + e of the tile is the last of its segment
@@ -169,6 +171,8 @@ struct SellHead {
     bool on = false;
     int nwaves = 0;               // wavefronts the slices were dealt to (= 4 x workgroups of the kernel)
     int nslices = 0;
+    int64_t ngroups = 0;          // groups of 64 x 16 bytes in data (headers, slots and padding)
+    int64_t nrows_with_entries = 0;
     int64_t *wave_off = nullptr;     // device, nwaves + 1: first group of each wavefront's stream in data
     uint16_t *data = nullptr;     // device: groups (headers and slots; kSellSlots = the padding slot, whose table entry is 0)
     double *sums = nullptr;       // device, rows: in sorted order
@@ -217,6 +221,7 @@ struct CsrPlan {
     int32_t *hot_ids = nullptr;          // device, P*kHotSlots + head_slots column ids of the LDS tables (null: no LDS table)
     double *hot_x = nullptr;             // device, as many: the gather vector at those columns, refreshed every call
     int64_t nseg_total = 0;              // segments (= partial sums) of the plan
+    int64_t cold_cols = 0;               // columns with entries that no LDS table serves (P > 1): what the gathers must fetch
     int64_t ngroups = 0;                 // ceil(rows / 64)
     GroupBase *group_base = nullptr;     // device, ngroups records
     int4 *chunk_tab = nullptr;           // device, per chunk: {first owned segment (partition-relative), number of owned
@@ -332,6 +337,19 @@ int spmv_scale(tron_dataset *ds, const CsrPlan &A, int slot, const double *x, co
 int spmv_axpy(tron_dataset *ds, const CsrPlan &A, int slot, const double *x, const double *add, double alpha,
               bool dot_self, double *out, bool square = false, bool x_prescaled = false);
 
+// Bytes one launch of each kernel of a product with plan A has to move in the format A stores (what the byte counters
+// of the memory system would read for a launch without any wasted traffic): the streams it reads once, the vector
+// elements it must fetch at least once, and what it writes.  Zero for parts the plan does not have.
+struct PlanBytes {
+    int64_t gather;        // k_gather_hot: ids, the gathered elements, the table copy
+    int64_t head;          // head partition (sorted slices or chunks)
+    int64_t ranges;        // the column ranges (or the single chunk kernel of an unpartitioned plan)
+    int64_t tiles;         // hot-row tiles incl. the workgroup accumulators
+    int64_t tile_reduce;
+    int64_t combine;       // partial sums in, row vector(s) in, result out
+};
+PlanBytes plan_bytes(const CsrPlan &A);
+
 // ---- kernels_dense.hip
 bool dense_supported(int64_t d);
 int dense_grid_for(int64_t n, int64_t d);
@@ -341,6 +359,7 @@ int64_t dense_partials_needed(int64_t n, int64_t d);
 // (the caller reads the four scalars and records scalars[3] / n in active_frac[Dslot])
 int dense_fun_grad(tron_dataset *ds, int loss, double C, const double *w, int Dslot, double *g);
 int dense_labels_from_device(tron_dataset *ds, int64_t row0, int64_t m, const double *y_dev);
+int dense_validate_device(tron_dataset *ds, int64_t m, const double *X_dev, const double *y_dev, int *what);
 // Hv = v + C X^T (D (X v)); scalars[0] = v.Hv
 int dense_hv(tron_dataset *ds, double C, int Dslot, const double *v, double *Hv);
 

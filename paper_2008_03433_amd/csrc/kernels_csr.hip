@@ -204,6 +204,8 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
                 }
             }
         }
+        for (int64_t j = 0; j < cols; ++j)   // head columns have count 0 here
+            if (colcount[j + 1] > colcount[j] && !(hot && slot_of[j] >= 0)) A.cold_cols++;
         std::vector<int64_t>().swap(colcount);
         // per-(partition,row) entry counts -> offsets; non-empty pairs are the segments
         std::vector<int32_t> rp32((size_t)NP * (rows + 1), 0);
@@ -350,6 +352,8 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
                 while ((groups - wave_off[w]) % kSellAhead) null_groups.push_back(groups++);
             }
             wave_off[S.nwaves] = groups;
+            S.ngroups = groups;
+            for (int64_t r = 0; r < rows; ++r) S.nrows_with_entries += cnt[r] > 0;
             std::vector<uint16_t> data((size_t)std::max<int64_t>(groups, 1) * kWave * 8, (uint16_t)kSellSlots);
             for (int64_t gpad : null_groups)
                 for (int l = 0; l < kWave; ++l) {
@@ -1049,6 +1053,9 @@ int hot_tiles_build(CsrPlan &A, const int64_t *t_rowptr, const int32_t *t_col, c
         nseg += (int64_t)sslot[s].size();
     }
     H.ntiles_total = ntiles;
+    H.nseg_padded = nseg;
+    for (int s = 0; s < kTileSlices; ++s)
+        for (const int4 &h : hdrs[s]) H.span_total += h.z;
     if (ntiles == 0) return TRON_OK;
     if (nseg > 0x7ffffff0 || ntiles > 0x7ffffff0 / kChunk * 1024) { set_error("hot tiles too large"); return TRON_EINVAL; }
     if (!unit) TRON_HIP(hipMalloc(reinterpret_cast<void **>(&H.val), sizeof(double) * ntiles * kChunk));
@@ -1753,6 +1760,48 @@ int spmv_axpy(tron_dataset *ds, const CsrPlan &A, int slot, const double *x, con
         hipLaunchKernelGGL(k_combine_axpy<false>, dim3(g), dim3(kBlock), 0, ds->stream, A.rows, partial_ref(ds, A), add, alpha, out, ds->partials, hot);
     TRON_HIP(hipGetLastError());
     return g;
+}
+
+// ------------------------------------------------------------------ byte accounting (see PlanBytes)
+PlanBytes plan_bytes(const CsrPlan &A)
+{
+    PlanBytes b{0, 0, 0, 0, 0, 0};
+    const int64_t vbytes = A.unit ? 0 : 8;   // value stream per stored entry
+    if (A.P == 1) {
+        // plain CSR in chunks: columns and values once, row offsets, the gathered vector and the result once each
+        b.ranges = A.nnz * (4 + 8) + 8 * (A.rows + 1) + 4 * ((int64_t)A.nblocks + 1) + 8 * A.cols + 8 * A.rows;
+        return b;
+    }
+    const int64_t per_chunk = kBlock /* flag bits */ + (int64_t)sizeof(int4) /* table entry */ + 8 /* carry */;
+    int64_t nseg_head = 0;
+    if (A.hot_ids) {
+        const int64_t nh = (int64_t)A.P * kHotSlots + A.head_slots;
+        b.gather = nh * (4 + 8 + 8);
+    }
+    if (A.sell.on) {
+        b.head = A.sell.ngroups * kWave * 16 + 8 * ((int64_t)A.sell.nwaves + 1) + 8 * (int64_t)kSellSlots + 8 * A.sell.nrows_with_entries;
+    } else if (A.head >= 0) {
+        const int h = A.head;
+        nseg_head = A.nseg_total - A.part_seg0[h];
+        b.head = (int64_t)A.part_nchunks[h] * (kChunk * (2 + vbytes) + per_chunk) + 8 * (int64_t)kHotSlots + 8 * nseg_head;
+    }
+    int64_t range_chunks = 0;
+    for (int x = 0; x < A.P; ++x) range_chunks += A.part_nchunks[x];
+    const int64_t nseg_ranges = A.nseg_total - nseg_head;
+    b.ranges = range_chunks * (kChunk * (4 + vbytes) + per_chunk) + 8 * nseg_ranges + 8 * A.cold_cols +
+               (A.hot_ids ? 8 * (int64_t)A.P * A.range_slots : 0);
+    if (A.hot.ntiles_total > 0) {
+        const HotTiles &H = A.hot;
+        const int64_t acc = 8 * (int64_t)kTileSlices * H.blocks_per_slice * kTileSlots;
+        b.tiles = H.ntiles_total * (kChunk * (2 + vbytes) + kBlock + (int64_t)sizeof(int4)) + 2 * H.nseg_padded + 8 * H.span_total + acc;
+        b.tile_reduce = acc + 8 * (int64_t)kTileSlices * kTileSlots;
+    }
+    // combine: every partial sum once, the row mask, the group table, the result; plus what the plan's extras need per row
+    b.combine = 8 * A.nseg_total + 2 * A.rows + (int64_t)sizeof(GroupBase) * A.ngroups + 8 * A.rows;
+    if (A.sell.on) b.combine += (8 + 4) * A.rows;                        // sorted sums through the position array
+    if (A.hot.ntiles_total > 0) b.combine += 4 * A.rows + 8 * (int64_t)A.hot.nhot;   // slot of each row, sums of the hot rows
+    if (A.row_scale) b.combine += 8 * A.rows;
+    return b;
 }
 
 }  // namespace tron

@@ -320,6 +320,35 @@ __global__ __launch_bounds__(kBlock) void k_labels_to_int8(int64_t m, const doub
         y8[i] = (y[i] > 0.0) ? 1 : -1;
 }
 
+// Input check for rows handed over in device memory: flag[0] = 1 when a label is not exactly +1 or -1, flag[1] = 1 when
+// an entry of X is not finite (every offending thread stores the same value).
+__global__ __launch_bounds__(kBlock) void k_dense_validate(int64_t m, int64_t count, const double *__restrict__ X,
+                                                           const double *__restrict__ y, double *__restrict__ flag)
+{
+    const int64_t t0 = (int64_t)blockIdx.x * kBlock + threadIdx.x, stride = (int64_t)gridDim.x * kBlock;
+    bool bad_y = false, bad_x = false;
+    for (int64_t i = t0; i < m; i += stride) bad_y |= !(y[i] == 1.0 || y[i] == -1.0);
+    for (int64_t k = t0; k < count; k += stride) bad_x |= !isfinite(X[k]);
+    if (bad_y) flag[0] = 1.0;
+    if (bad_x) flag[1] = 1.0;
+}
+
+// what: 0 = fine, 1 = a label is not +1 / -1, 2 = a matrix entry is not finite.  Synchronises the stream.
+int dense_validate_device(tron_dataset *ds, int64_t m, const double *X_dev, const double *y_dev, int *what)
+{
+    double *flag_host = ds->scal_host + kScalars - 2;   // the last two scalar slots: written by no other kernel
+    flag_host[0] = 0.0;
+    flag_host[1] = 0.0;
+    int64_t g = (m * ds->d + kBlock * 8 - 1) / (kBlock * 8);
+    if (g < 1) g = 1;
+    if (g > kMaxGrid) g = kMaxGrid;
+    hipLaunchKernelGGL(k_dense_validate, dim3((int)g), dim3(kBlock), 0, ds->stream, m, m * ds->d, X_dev, y_dev, ds->scal_dev + kScalars - 2);
+    TRON_HIP(hipGetLastError());
+    TRON_HIP(hipStreamSynchronize(ds->stream));
+    *what = flag_host[0] != 0.0 ? 1 : (flag_host[1] != 0.0 ? 2 : 0);
+    return TRON_OK;
+}
+
 int dense_labels_from_device(tron_dataset *ds, int64_t row0, int64_t m, const double *y_dev)
 {
     int64_t g = (m + kBlock - 1) / kBlock;

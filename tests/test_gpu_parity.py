@@ -419,6 +419,38 @@ def test_invalid_inputs_are_rejected(rng):
         tron.tron_dataset_create_dense(2, 600, np.zeros((2, 600)), y)
 
 
+def test_invalid_dense_input_in_device_memory_is_rejected(rng):
+    """Rows handed over as device pointers get the checks host input gets: labels exactly +1 / -1, finite entries."""
+    import paper_2008_03433_amd as tron
+    torch = torch_mod()
+    n, d = 5000, 7
+    X = rng.standard_normal((n, d))
+    y = np.where(rng.random(n) < 0.5, 1.0, -1.0)
+    for bad_y in (0.0, 0.5, 2.0, np.nan, -np.inf):
+        yy = y.copy(); yy[n - 3] = bad_y
+        with pytest.raises(tron.TronError) as e:
+            tron.tron_dataset_create_dense(n, d, dev(X), dev(yy))
+        assert e.value.code == -1 and "label" in str(e.value)
+    for bad_x in (np.nan, np.inf, -np.inf):
+        XX = X.copy(); XX[n - 1, d - 1] = bad_x
+        with pytest.raises(tron.TronError) as e:
+            tron.tron_dataset_create_dense(n, d, dev(XX), dev(y))
+        assert e.value.code == -1 and "finite" in str(e.value)
+    # a rejected chunk leaves the rows already written alone; a good chunk still goes through afterwards
+    h = tron.tron_dataset_create_dense_empty(n, d)
+    try:
+        tron.tron_dataset_write_rows(h, 0, n, dev(X), dev(y))
+        yy = y[:100].copy(); yy[5] = 0.0
+        with pytest.raises(tron.TronError):
+            tron.tron_dataset_write_rows(h, 0, 100, dev(np.zeros((100, d))), dev(yy))
+        w = dev(0.1 * rng.standard_normal(d))
+        f = tron.tron_fun_grad(h, LOSS_LR, 1.0, w, None)
+        f_o, _, _ = __import__("oracle").Oracle(n=n, d=d, y=y, X=X).fun_grad(LOSS_LR, 1.0, w.cpu().numpy())
+        assert abs(f - f_o) <= 1e-10 * abs(f_o)
+    finally:
+        tron.tron_dataset_destroy(h)
+
+
 # ------------------------------------------------------------------ full solves
 def test_solve_config1():
     p = dg.config1()

@@ -7,6 +7,30 @@ from oracle import Oracle
 REL = 1e-10  # per-call parity gate (fp64), norm-wise
 
 
+def progress_reporter(capsys, label):
+    """Returns a callback for Oracle.tron(progress=...): one line per finished outer iteration of a long oracle solve,
+    printed past pytest's capture and appended to gpurun_out/test_progress.log, so that a watcher of the run's output
+    sees the solve advance."""
+    import os
+    import sys
+    import time
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    t0 = time.time()
+
+    def report(rec):
+        line = (f"[{label}] oracle outer iteration {rec['iter']}: {rec['cg_iters']} CG steps, f = {rec['f']:.10g}, "
+                f"|g| = {rec['gnorm']:.3e} ({time.time() - t0:.0f} s)")
+        with capsys.disabled():
+            print(line, file=sys.stderr, flush=True)
+        try:
+            os.makedirs(os.path.join(root, "gpurun_out"), exist_ok=True)
+            with open(os.path.join(root, "gpurun_out", "test_progress.log"), "a") as fh:
+                fh.write(line + "\n")
+        except OSError:
+            pass
+    return report
+
+
 def torch_mod():
     import torch
     return torch
