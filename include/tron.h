@@ -103,6 +103,7 @@ TRON_API int tron_dataset_shape(const tron_dataset *ds, int64_t *n, int64_t *d, 
  *   "bwd_tile_nnz", "bwd_tile_rows", "bwd_tiles"  nonzeros, features and tiles of the hot-row tiles
  *   "fwd_lds_columns"          columns served from LDS tables in the forward pass
  *   "dense_grid"               workgroups of the dense kernels
+ *   "dense_compact_rows"       rows of the compacted copy of the active rows the next tron_hv would run over (0: none)
  *   "unit_values"              1 when the sparse layouts keep no values (every instance's entries share one value)
  *   "fwd_bytes_gather", "fwd_bytes_head", "fwd_bytes_ranges", "fwd_bytes_combine",
  *   "bwd_bytes_tiles", "bwd_bytes_tile_reduce", "bwd_bytes_ranges", "bwd_bytes_combine"
@@ -315,6 +316,11 @@ TRON_API int tron_probe_read_bandwidth(const double *src_dev, int64_t count, int
  *                4096 columns); a quarter of the number of wavefronts the slices are dealt to;
  *   "csr_hot_blocks_per_part", "csr_range_blocks_per_part", "csr_blocks_per_part",
  *   "csr_tile_blocks_per_slice": persistent workgroups of the head, table, table-less and tile kernels.
+ * "dense_compact" (-1/0/1): L2-SVM on a dense matrix with d <= 32: Hessian-vector products run over a compacted copy of the
+ *   active rows, X_I of Section 5 of the paper, built on the device (up to n*d more doubles of device memory): 0 never (the
+ *   pass over X skips inactive rows instead), 1 whenever some rows are inactive (tron_fun_grad then builds the copy for the
+ *   tron_hv calls that follow), -1 (default) inside tron_solve when at most 60% of the rows are active and the last inner
+ *   solve took at least ten products.  Read at call time, not at creation.
  * "dense_device_driver" (-1/0/1): tron_solve on a dense matrix with d <= 32 and no preconditioner runs its trust-region and
  *   CG steps on the device (as tron_batch_solve does): 0 never, 1 always, -1 (default) for the L2-SVM on matrices up to 1 GB.
  * "batch_grid" (0..4096): workgroups of the multi-problem pass (0 = as many as are resident at once).

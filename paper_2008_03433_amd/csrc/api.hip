@@ -33,7 +33,7 @@ int hip_fail(hipError_t e, const char *what, const char *file, int line)
 // ------------------------------------------------------------------ profiler
 const char *const kSlotNames[SLOT_COUNT] = {
     "spmv_fwd", "spmv_bwd", "spmv_head", "spmv_tiles", "spmv_tile_reduce", "spmv_gather", "spmv_fixup", "spmv_combine", "loss_terms",
-    "dense_fun_grad", "dense_hv", "dense_finalize", "dot", "reduce_final", "cg_vec", "batch_pass", "batch_advance"};
+    "dense_fun_grad", "dense_hv", "dense_finalize", "dense_compact", "dot", "reduce_final", "cg_vec", "batch_pass", "batch_advance"};
 
 int Profiler::begin(int slot, hipStream_t st)
 {
@@ -166,6 +166,7 @@ void tron_dataset_destroy(tron_dataset *ds)
     if (!ds) return;
     hipStreamSynchronize(ds->stream);
     dense_device_release(ds);
+    dense_compact_release(ds);
     hipFree(ds->X);
     ds->fwd.release();
     ds->bwd.release();
@@ -415,6 +416,8 @@ int tron_dataset_stat(const tron_dataset *ds, const char *name, int64_t *value)
         const double frac = (mask && ds->active_frac[slot] < 0.95) ? ds->active_frac[slot] : 1.0;
         const int64_t dbytes = !mask ? 8 * ds->n : (ds->d <= 32 ? ds->n / 8 : ds->n);
         hv_bytes = (int64_t)(8.0 * frac * (double)ds->n * (double)ds->d) + dbytes + 8 * ds->d * ds->dense_grid;
+        if (ds->have_D && ds->hat_slot == slot)   // the pass runs over the compacted copy
+            hv_bytes = 8 * ds->hat_rows * ds->d + ds->hat_rows / 8 + 8 * ds->d * dense_grid_for(ds->hat_rows, ds->d);
         fun_grad_bytes = 8 * ds->n * ds->d + ds->n /* labels */ + dbytes + 8 * ds->d * ds->dense_grid;
     } else {
         fb = plan_bytes(ds->fwd);
@@ -437,6 +440,7 @@ int tron_dataset_stat(const tron_dataset *ds, const char *name, int64_t *value)
         {"bwd_tiles", ds->dense ? 0 : ds->bwd.hot.ntiles_total},
         {"fwd_lds_columns", ds->dense ? 0 : [&] { int64_t t = 0; for (int x = 0; x < kMaxParts; ++x) t += ds->fwd.part_nhot[x]; return t; }()},
         {"dense_grid", ds->dense_grid},
+        {"dense_compact_rows", (ds->dense && ds->have_D && ds->hat_slot == ds->Dcur) ? ds->hat_rows : 0},
         {"unit_values", (!ds->dense && ds->fwd.unit) ? 1 : 0},
     };
     for (auto &e : tab)
@@ -456,7 +460,10 @@ int tron_fun_grad(tron_dataset *ds, int loss, double C, const double *w_dev, dou
         TRON_TRY(dense_fun_grad(ds, loss, C, w_dev, slot, g_dev));
         TRON_TRY(read_scalars(ds, 4));
         ds->active_frac[slot] = ds->scal_host[3] / (double)ds->n;
+        ds->active_count[slot] = (int64_t)ds->scal_host[3];
         *f_host = 0.5 * ds->scal_host[1] + C * ds->scal_host[0];
+        // stand-alone calls: the compacted copy of the active rows only when the knob forces it
+        if (g_tuning.dense_compact > 0 && dense_compact_wanted(ds, slot, 0)) TRON_TRY(dense_compact_build(ds, slot));
     } else {
         TRON_TRY(fun_eval(ds, loss, C, w_dev, slot, f_host));
         if (g_dev) {
@@ -564,6 +571,10 @@ int tron_tuning_set(const char *name, int64_t value)
     }
     if (name && strcmp(name, "csr_unit") == 0 && (value == 0 || value == 1)) {
         g_tuning.csr_unit = value;
+        return TRON_OK;
+    }
+    if (name && strcmp(name, "dense_compact") == 0 && value >= -1 && value <= 1) {
+        g_tuning.dense_compact = value;
         return TRON_OK;
     }
     if (name && strcmp(name, "dense_device_driver") == 0 && value >= -1 && value <= 1) {

@@ -41,6 +41,8 @@ struct Tuning {
     int64_t csr_sell_blocks = 1024;   // workgroups of the sorted-slice head kernel
     int64_t csr_sell = 1;    // unit plans: the head partition as sorted slices of 64 rows, one row per lane (0 = as chunks)
     int64_t csr_unit = 1;    // partitioned layouts: drop the value stream when every row of X holds one repeated value (0 = off)
+    int64_t dense_compact = -1;         // dense L2-SVM: Hessian-vector products on a compacted copy of the active rows:
+                                        //   0 never, 1 whenever rows are inactive, -1 automatic (see dense_compact_wanted)
     int64_t dense_device_driver = -1;   // tron_solve on dense d <= 32 without preconditioner driven from the device:
                                         //   0 never, 1 always, -1 automatic (the L2-SVM on matrices up to 1 GB)
     int64_t batch_grid = 0;  // workgroups of the multi-problem pass: 0 = as many as are resident at once
@@ -69,6 +71,7 @@ enum Slot {
     SLOT_DENSE_FUN_GRAD,   // fused dense z / loss / D / X^T zhat
     SLOT_DENSE_HV,         // fused dense X^T (D (X v))
     SLOT_DENSE_FINALIZE,   // column sums of per-workgroup partials
+    SLOT_DENSE_COMPACT,    // compacted copy of the active rows
     SLOT_DOT,              // dot products / norms (first stage)
     SLOT_REDUCE_FINAL,     // second reduction stage -> scalars
     SLOT_CG_VEC,           // CG vector updates
@@ -269,6 +272,15 @@ struct tron_dataset {
 
     double *unit_scale = nullptr;  // sparse, unit plans: r (n), the value shared by the entries of instance i
 
+    // dense L2-SVM: compacted copy of the active rows of D buffer `hat_slot` (-1: none), see dense_compact_build
+    double *Xhat = nullptr;          // hat_cap rows x d
+    int64_t hat_cap = 0, hat_rows = 0;
+    uint64_t *hat_bits = nullptr;    // hat_cap / 64 + 1 words: the all-active set of the compacted copy
+    int64_t *tile_off = nullptr;     // ceil(n / 64) + 1: active rows before each 64-row tile
+    int64_t *scan_blocks = nullptr;  // partial sums of the scan over the tiles
+    int hat_slot = -1;
+    int64_t active_count[2] = {0, 0};   // rows with D != 0 in each buffer
+
     tron_batch *self_batch = nullptr;   // dense: one problem over all rows, for solves driven from the device
 
     // solver vectors (d each), allocated on first tron_solve
@@ -365,6 +377,13 @@ int dense_hv(tron_dataset *ds, double C, int Dslot, const double *v, double *Hv)
 
 // out = 1 + C diag(X^T D X)
 int dense_hess_diag(tron_dataset *ds, double C, int Dslot, double *out);
+// X_hat = the rows of X that are active in Dbuf[Dslot] (the compacted copy of Section 5 of the paper), built on the device;
+// dense_hv then runs over it.  Needs the active set as bit words (L2-SVM, d <= 32) and active_count[Dslot].  Enqueue only
+// (allocates, and therefore synchronises, when the copy has to grow).
+int dense_compact_build(tron_dataset *ds, int Dslot);
+// whether the knob asks for the copy, given how many Hessian-vector products the last inner solve took
+bool dense_compact_wanted(const tron_dataset *ds, int Dslot, int recent_cg_iters);
+void dense_compact_release(tron_dataset *ds);
 
 // ---- batch.hip
 int dense_device_solve(tron_dataset *ds, const tron_params &P, double *w_dev, tron_result *res);

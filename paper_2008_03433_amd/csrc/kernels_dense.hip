@@ -232,17 +232,102 @@ __global__ __launch_bounds__(kBlock) void k_dense_scalars(int64_t d, int nloss, 
     }
 }
 
+// Both second-stage kernels in one launch, for d <= kFinishMaxD: a single workgroup of 16 wavefronts; wavefront w adds the
+// per-workgroup partial sums of columns w, w + 16, ... (sixteen loads per lane in flight at a time, added in index
+// order), then the workgroup adds the column products and the other scalars.  Same outputs as k_dense_columns followed
+// by k_dense_scalars; the launch and the wait between the two are saved, which is a third of a Hessian-vector call on a
+// matrix of a million rows.
+constexpr int kFinishMaxD = 64;
+constexpr int kFinishWaves = 16;
+__global__ __launch_bounds__(kFinishWaves * kWave) void k_dense_finish(int64_t d, int grid, const double *__restrict__ partials,
+                                                                       const double *__restrict__ add, double C, double *__restrict__ out,
+                                                                       const double *__restrict__ dotw, int nloss,
+                                                                       const double *__restrict__ loss_partials,
+                                                                       const double *__restrict__ active_partials,
+                                                                       const double *__restrict__ w, double *__restrict__ scal,
+                                                                       double *__restrict__ scal_copy)
+{
+    __shared__ double colprod[kFinishMaxD];
+    __shared__ double red[4][kFinishWaves];
+    const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave;
+    for (int c = wv; c < d; c += kFinishWaves) {
+        const double *p = partials + (int64_t)c * grid;
+        double s = 0.0;
+        for (int b0 = 0; b0 < grid; b0 += 16 * kWave) {
+            double t[16];
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                const int b = b0 + k * kWave + lane;
+                t[k] = (b < grid) ? p[b] : 0.0;
+            }
+#pragma unroll
+            for (int k = 0; k < 16; ++k) s += t[k];
+        }
+        s = wave_sum(s);
+        if (lane == 0) {
+            const double o = fma(C, s, add ? add[c] : 1.0);
+            if (out) out[c] = o;
+            colprod[c] = o * (dotw ? dotw[c] : o);
+        }
+    }
+    double a = 0.0, e = 0.0, ww = 0.0;
+    for (int i = threadIdx.x; i < nloss; i += kFinishWaves * kWave) {
+        a += loss_partials[i];
+        e += active_partials[i];
+    }
+    if (w && threadIdx.x < d) ww = w[threadIdx.x] * w[threadIdx.x];
+    __syncthreads();
+    double cp = (threadIdx.x < d) ? colprod[threadIdx.x] : 0.0;   // d <= 64: all in wavefront 0
+    a = wave_sum(a); e = wave_sum(e); ww = wave_sum(ww); cp = wave_sum(cp);
+    if (lane == 0) { red[0][wv] = a; red[1][wv] = e; red[2][wv] = ww; red[3][wv] = cp; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double ta = 0.0, te = 0.0, tw = 0.0, tc = 0.0;
+#pragma unroll
+        for (int k = 0; k < kFinishWaves; ++k) { ta += red[0][k]; te += red[1][k]; tw += red[2][k]; tc += red[3][k]; }
+        if (nloss > 0) {
+            scal[0] = ta;
+            scal[1] = tw;
+            scal[2] = tc;
+            scal[3] = te;
+        } else {
+            scal[0] = tc;
+            scal_copy[0] = tc;   // p.Hp: the CG step kernel continues from it
+        }
+    }
+}
+
 // ------------------------------------------------------------------ dispatch
 constexpr double kSkipBelow = 0.95;   // active fraction under which the Hessian-vector pass skips the inactive rows
 
+// What a Hessian-vector pass runs over: the matrix itself with D of one buffer, or the compacted copy of its active rows
+// (then every row is active: the bit words are all ones).
+struct HvInput {
+    const double *X;
+    int64_t n;
+    const void *D;
+    bool mask, skip;
+    int grid;
+};
+
+HvInput hv_input(const tron_dataset *ds, int Dslot)
+{
+    if (ds->hat_slot == Dslot && ds->Xhat)
+        return HvInput{ds->Xhat, ds->hat_rows, ds->hat_bits, true, false, dense_grid_for(ds->hat_rows, ds->d)};
+    const bool mask = ds->D_is_mask[Dslot];
+    return HvInput{ds->X, ds->n, ds->Dbuf[Dslot], mask, mask && ds->active_frac[Dslot] < kSkipBelow, ds->dense_grid};
+}
+
 template <int E, int L>
-int launch_hv(tron_dataset *ds, const void *D, bool mask, bool skip, const double *v, double *partials)
+int launch_hv(tron_dataset *ds, const HvInput &in, const double *v, double *partials)
 {
     constexpr int U = pick_U(E, L);
     const bool vec = (E % 2 == 0) && (ds->d % 2 == 0);
-    const int grid = ds->dense_grid;
+    const int grid = in.grid;
+    const void *D = in.D;
+    const bool mask = in.mask, skip = in.skip;
 #define TRON_HV(V, M, G, S) \
-    hipLaunchKernelGGL((k_dense_hv<E, L, U, V, M, G, S>), dim3(grid), dim3(kBlock), 0, ds->stream, ds->n, ds->d, ds->X, D, v, partials)
+    hipLaunchKernelGGL((k_dense_hv<E, L, U, V, M, G, S>), dim3(grid), dim3(kBlock), 0, ds->stream, in.n, ds->d, in.X, D, v, partials)
 #define TRON_HV_V(M, G, S) do { if (vec) TRON_HV((E % 2 == 0), M, G, S); else TRON_HV(false, M, G, S); } while (0)
     if (v) {
         if (!mask) TRON_HV_V(false, false, false);
@@ -309,7 +394,7 @@ int launch_fg(tron_dataset *ds, int loss, const double *w, void *Dout, double *l
     set_error("internal: no dense kernel for E=%d L=%d", s.E, s.L);              \
     return TRON_EINVAL;
 
-int dispatch_hv(tron_dataset *ds, const void *D, bool mask, bool skip, const double *v, double *partials) { TRON_DISPATCH(launch_hv, ds, D, mask, skip, v, partials) }
+int dispatch_hv(tron_dataset *ds, const HvInput &in, const double *v, double *partials) { TRON_DISPATCH(launch_hv, ds, in, v, partials) }
 int dispatch_fg(tron_dataset *ds, int loss, const double *w, void *Dout, double *lp, double *ap) { TRON_DISPATCH(launch_fg, ds, loss, w, Dout, lp, ap) }
 
 }  // namespace
@@ -358,6 +443,173 @@ int dense_labels_from_device(tron_dataset *ds, int64_t row0, int64_t m, const do
     return TRON_OK;
 }
 
+// ------------------------------------------------------------------ compacted copy of the active rows
+// Section 5 of the paper keeps X_hat = X_{I,:} in device memory so that its matrix-vector products touch active rows
+// only.  Here the copy is optional (the Hessian-vector pass over X skips inactive rows by itself): it pays when many
+// products follow at one iterate with a small active set, because a pass over contiguous rows streams faster than one
+// that picks 192-byte rows out of X.  Built on the device from the bit words the function/gradient pass left:
+//   1. active rows before every 64-row tile: popcounts, scanned in three steps (per workgroup, over the workgroups, back);
+//   2. every wavefront copies the active rows of its tiles to their places in X_hat (reads of inactive rows are not issued);
+//   3. the active set of the copy is all ones.
+constexpr int kScanPer = 4;                                   // tiles per thread in the scan
+constexpr int kScanTile = kBlock * kScanPer;                  // tiles per workgroup
+
+__global__ __launch_bounds__(kBlock) void k_active_block_sums(int64_t ntiles, const uint64_t *__restrict__ bits, int64_t *__restrict__ block_sums)
+{
+    __shared__ double lds[kWavesPerBlock];
+    const int64_t t0 = (int64_t)blockIdx.x * kScanTile + threadIdx.x * kScanPer;
+    int c = 0;
+#pragma unroll
+    for (int k = 0; k < kScanPer; ++k)
+        if (t0 + k < ntiles) c += __popcll(bits[t0 + k]);
+    const double s = block_sum((double)c, lds);   // exact: at most 2^18 per workgroup
+    if (threadIdx.x == 0) block_sums[blockIdx.x] = (int64_t)s;
+}
+
+// exclusive scan of the workgroup sums, in place, by one workgroup (thread t owns a contiguous run of them)
+__global__ __launch_bounds__(kBlock) void k_active_scan_blocks(int nblocks, int64_t *__restrict__ block_sums)
+{
+    __shared__ int64_t run[kBlock];
+    const int per = (nblocks + kBlock - 1) / kBlock;
+    const int b0 = threadIdx.x * per, b1 = (b0 + per < nblocks) ? b0 + per : nblocks;
+    int64_t s = 0;
+    for (int b = b0; b < b1; ++b) s += block_sums[b];
+    run[threadIdx.x] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int64_t acc = 0;
+        for (int t = 0; t < kBlock; ++t) { const int64_t v = run[t]; run[t] = acc; acc += v; }
+    }
+    __syncthreads();
+    int64_t acc = run[threadIdx.x];
+    for (int b = b0; b < b1; ++b) { const int64_t v = block_sums[b]; block_sums[b] = acc; acc += v; }
+}
+
+__global__ __launch_bounds__(kBlock) void k_active_tile_offsets(int64_t ntiles, const uint64_t *__restrict__ bits,
+                                                                const int64_t *__restrict__ block_sums, int64_t *__restrict__ tile_off)
+{
+    __shared__ int wave_tot[kWavesPerBlock];
+    const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave;
+    const int64_t t0 = (int64_t)blockIdx.x * kScanTile + threadIdx.x * kScanPer;
+    int c[kScanPer], mine = 0;
+#pragma unroll
+    for (int k = 0; k < kScanPer; ++k) {
+        c[k] = (t0 + k < ntiles) ? __popcll(bits[t0 + k]) : 0;
+        mine += c[k];
+    }
+    const int incl = wave_scan_add(mine);
+    if (lane == kWave - 1) wave_tot[wv] = incl;
+    __syncthreads();
+    int before = 0;
+    for (int w = 0; w < wv; ++w) before += wave_tot[w];
+    int64_t off = block_sums[blockIdx.x] + before + incl - mine;
+#pragma unroll
+    for (int k = 0; k < kScanPer; ++k) {
+        if (t0 + k < ntiles) tile_off[t0 + k] = off;
+        off += c[k];
+    }
+}
+
+// VEC: d is even, rows are moved in 16-byte pieces
+template <bool VEC>
+__global__ __launch_bounds__(kBlock) void k_compact_rows(int64_t n, int d, uint64_t inv_d, const double *__restrict__ X,
+                                                         const uint64_t *__restrict__ bits, const int64_t *__restrict__ tile_off,
+                                                         double *__restrict__ Xhat)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t ntiles = (n + kWave - 1) / kWave;
+    const int64_t nwaves = (int64_t)gridDim.x * kWavesPerBlock;
+    constexpr int W = VEC ? 2 : 1;
+    for (int64_t tile = (int64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave; tile < ntiles; tile += nwaves) {
+        const uint64_t b = bits[tile];   // rows past n are never set
+        if (b == 0) continue;
+        const double *src = X + tile * kWave * d;
+        double *dst = Xhat + tile_off[tile] * d;
+        const int total = kWave * d;
+        for (int e = lane * W; e < total; e += kWave * W) {
+            const int row = (int)(((uint64_t)e * inv_d) >> 32);   // e / d, exact for e < 64 * 32 (inv_d = ceil(2^32 / d))
+            if ((b >> row) & 1u) {
+                const int rank = __popcll(b & ((1ull << row) - 1ull));
+                const int col = e - row * d;
+                if (VEC) *reinterpret_cast<double2 *>(dst + rank * d + col) = *reinterpret_cast<const double2 *>(src + e);
+                else dst[rank * d + col] = src[e];
+            }
+        }
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void k_all_active_bits(int64_t rows, uint64_t *__restrict__ bits)
+{
+    const int64_t words = (rows + kWave - 1) / kWave;
+    for (int64_t t = (int64_t)blockIdx.x * kBlock + threadIdx.x; t < words; t += (int64_t)gridDim.x * kBlock) {
+        const int64_t left = rows - t * kWave;
+        bits[t] = (left >= kWave) ? ~0ull : ((1ull << left) - 1ull);
+    }
+}
+
+bool dense_compact_wanted(const tron_dataset *ds, int Dslot, int recent_cg_iters)
+{
+    if (!ds->dense || ds->d > 32 || !ds->D_is_mask[Dslot] || g_tuning.dense_compact == 0) return false;
+    if (ds->active_count[Dslot] <= 0 || ds->active_frac[Dslot] >= kSkipBelow) return false;
+    if (g_tuning.dense_compact > 0) return true;
+    // Building the copy costs about as much as 2.5 products over it and a product over it saves about a quarter of the
+    // row-skipping one: worth it from about ten products per iterate on, with no more than 60% of the rows active.
+    return ds->active_frac[Dslot] <= 0.6 && recent_cg_iters >= 10;
+}
+
+int dense_compact_build(tron_dataset *ds, int Dslot)
+{
+    if (!ds->dense || ds->d > 32 || !ds->D_is_mask[Dslot]) { set_error("internal: no bit-word active set to compact"); return TRON_EINVAL; }
+    const int64_t rows = ds->active_count[Dslot];
+    const int64_t ntiles = (ds->n + kWave - 1) / kWave;
+    const int nblocks = (int)((ntiles + kScanTile - 1) / kScanTile);
+    ds->hat_slot = -1;
+    if (!ds->tile_off) {
+        TRON_HIP(hipMalloc(reinterpret_cast<void **>(&ds->tile_off), sizeof(int64_t) * (size_t)(ntiles + 1)));
+        TRON_HIP(hipMalloc(reinterpret_cast<void **>(&ds->scan_blocks), sizeof(int64_t) * (size_t)(nblocks + 1)));
+    }
+    if (rows > ds->hat_cap) {
+        // grow with some room, so that a slowly growing active set does not reallocate at every iterate
+        TRON_HIP(hipStreamSynchronize(ds->stream));
+        hipFree(ds->Xhat); hipFree(ds->hat_bits);
+        ds->Xhat = nullptr; ds->hat_bits = nullptr; ds->hat_cap = 0;
+        int64_t cap = rows + rows / 8 + 1024;
+        if (cap > ds->n) cap = ds->n;
+        TRON_HIP(hipMalloc(reinterpret_cast<void **>(&ds->Xhat), sizeof(double) * (size_t)cap * (size_t)ds->d));
+        TRON_HIP(hipMalloc(reinterpret_cast<void **>(&ds->hat_bits), sizeof(uint64_t) * (size_t)(cap / kWave + 1)));
+        ds->hat_cap = cap;
+    }
+    ProfScope ps(ds, SLOT_DENSE_COMPACT);
+    const uint64_t *bits = static_cast<const uint64_t *>(static_cast<const void *>(ds->Dbuf[Dslot]));
+    hipLaunchKernelGGL(k_active_block_sums, dim3(nblocks), dim3(kBlock), 0, ds->stream, ntiles, bits, ds->scan_blocks);
+    hipLaunchKernelGGL(k_active_scan_blocks, dim3(1), dim3(kBlock), 0, ds->stream, nblocks, ds->scan_blocks);
+    hipLaunchKernelGGL(k_active_tile_offsets, dim3(nblocks), dim3(kBlock), 0, ds->stream, ntiles, bits, ds->scan_blocks, ds->tile_off);
+    int64_t g = (ntiles + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (g > kMaxGrid) g = kMaxGrid;
+    const uint64_t inv_d = ((1ull << 32) + (uint64_t)ds->d - 1) / (uint64_t)ds->d;
+    if (ds->d % 2 == 0)
+        hipLaunchKernelGGL(k_compact_rows<true>, dim3((int)g), dim3(kBlock), 0, ds->stream, ds->n, (int)ds->d, inv_d, ds->X, bits, ds->tile_off, ds->Xhat);
+    else
+        hipLaunchKernelGGL(k_compact_rows<false>, dim3((int)g), dim3(kBlock), 0, ds->stream, ds->n, (int)ds->d, inv_d, ds->X, bits, ds->tile_off, ds->Xhat);
+    const int64_t words = (rows + kWave - 1) / kWave;
+    int64_t gb = (words + kBlock - 1) / kBlock;
+    if (gb < 1) gb = 1;
+    if (gb > kMaxGrid) gb = kMaxGrid;
+    hipLaunchKernelGGL(k_all_active_bits, dim3((int)gb), dim3(kBlock), 0, ds->stream, rows, ds->hat_bits);
+    TRON_HIP(hipGetLastError());
+    ds->hat_rows = rows;
+    ds->hat_slot = Dslot;
+    return TRON_OK;
+}
+
+void dense_compact_release(tron_dataset *ds)
+{
+    hipFree(ds->Xhat); hipFree(ds->hat_bits); hipFree(ds->tile_off); hipFree(ds->scan_blocks);
+    ds->Xhat = nullptr; ds->hat_bits = nullptr; ds->tile_off = nullptr; ds->scan_blocks = nullptr;
+    ds->hat_cap = ds->hat_rows = 0;
+    ds->hat_slot = -1;
+}
+
 bool dense_supported(int64_t d)
 {
     Shape s;
@@ -386,20 +638,24 @@ int64_t dense_partials_needed(int64_t n, int64_t d)
 
 int dense_hv(tron_dataset *ds, double C, int Dslot, const double *v, double *Hv)
 {
-    const void *D = ds->Dbuf[Dslot];
-    const bool mask = ds->D_is_mask[Dslot];
-    const int grid = ds->dense_grid;
-    double *colprod = ds->partials + ds->d * grid + grid;
+    const HvInput in = hv_input(ds, Dslot);
+    const int grid = in.grid;
+    double *colprod = ds->partials + ds->d * ds->dense_grid + ds->dense_grid;
     {
         ProfScope ps(ds, SLOT_DENSE_HV);
-        TRON_TRY(dispatch_hv(ds, D, mask, mask && ds->active_frac[Dslot] < kSkipBelow, v, ds->partials));
+        TRON_TRY(dispatch_hv(ds, in, v, ds->partials));
         TRON_HIP(hipGetLastError());
     }
     ProfScope ps(ds, SLOT_DENSE_FINALIZE);
-    const int cg = (int)((ds->d + kWavesPerBlock - 1) / kWavesPerBlock);
-    hipLaunchKernelGGL(k_dense_columns, dim3(cg), dim3(kBlock), 0, ds->stream, ds->d, grid, ds->partials, v, C, Hv, v, colprod);
-    hipLaunchKernelGGL(k_dense_scalars, dim3(1), dim3(kBlock), 0, ds->stream, ds->d, 0, (const double *)nullptr,
-                       (const double *)nullptr, (const double *)nullptr, colprod, ds->scal_dev, ds->scal_copy);
+    if (ds->d <= kFinishMaxD) {
+        hipLaunchKernelGGL(k_dense_finish, dim3(1), dim3(kFinishWaves * kWave), 0, ds->stream, ds->d, grid, ds->partials, v, C, Hv, v, 0,
+                           (const double *)nullptr, (const double *)nullptr, (const double *)nullptr, ds->scal_dev, ds->scal_copy);
+    } else {
+        const int cg = (int)((ds->d + kWavesPerBlock - 1) / kWavesPerBlock);
+        hipLaunchKernelGGL(k_dense_columns, dim3(cg), dim3(kBlock), 0, ds->stream, ds->d, grid, ds->partials, v, C, Hv, v, colprod);
+        hipLaunchKernelGGL(k_dense_scalars, dim3(1), dim3(kBlock), 0, ds->stream, ds->d, 0, (const double *)nullptr,
+                           (const double *)nullptr, (const double *)nullptr, colprod, ds->scal_dev, ds->scal_copy);
+    }
     TRON_HIP(hipGetLastError());
     return TRON_OK;
 }
@@ -407,11 +663,12 @@ int dense_hv(tron_dataset *ds, double C, int Dslot, const double *v, double *Hv)
 // out = 1 + C diag(X^T D X): the same pass as dense_hv with squared entries
 int dense_hess_diag(tron_dataset *ds, double C, int Dslot, double *out)
 {
-    const int grid = ds->dense_grid;
-    double *colprod = ds->partials + ds->d * grid + grid;
+    const HvInput in = hv_input(ds, Dslot);
+    const int grid = in.grid;
+    double *colprod = ds->partials + ds->d * ds->dense_grid + ds->dense_grid;
     {
         ProfScope ps(ds, SLOT_DENSE_HV);
-        TRON_TRY(dispatch_hv(ds, ds->Dbuf[Dslot], ds->D_is_mask[Dslot], ds->D_is_mask[Dslot] && ds->active_frac[Dslot] < kSkipBelow, nullptr, ds->partials));
+        TRON_TRY(dispatch_hv(ds, in, nullptr, ds->partials));
         TRON_HIP(hipGetLastError());
     }
     ProfScope ps(ds, SLOT_DENSE_FINALIZE);
@@ -425,6 +682,7 @@ int dense_hess_diag(tron_dataset *ds, double C, int Dslot, double *out)
 int dense_fun_grad(tron_dataset *ds, int loss, double C, const double *w, int Dslot, double *g)
 {
     void *Dout = ds->Dbuf[Dslot];
+    if (ds->hat_slot == Dslot) ds->hat_slot = -1;   // the compacted copy belonged to the D that is overwritten now
     ds->D_is_mask[Dslot] = (loss == TRON_LOSS_L2SVM);
     const int grid = ds->dense_grid;
     double *loss_partials = ds->partials + ds->d * grid;
@@ -436,11 +694,16 @@ int dense_fun_grad(tron_dataset *ds, int loss, double C, const double *w, int Ds
         TRON_HIP(hipGetLastError());
     }
     ProfScope ps(ds, SLOT_DENSE_FINALIZE);
-    const int cg = (int)((ds->d + kWavesPerBlock - 1) / kWavesPerBlock);
-    hipLaunchKernelGGL(k_dense_columns, dim3(cg), dim3(kBlock), 0, ds->stream, ds->d, grid, ds->partials, w, C, g,
-                       (const double *)nullptr, colprod);
-    hipLaunchKernelGGL(k_dense_scalars, dim3(1), dim3(kBlock), 0, ds->stream, ds->d, grid, loss_partials, active_partials, w, colprod,
-                       ds->scal_dev, ds->scal_copy);
+    if (ds->d <= kFinishMaxD) {
+        hipLaunchKernelGGL(k_dense_finish, dim3(1), dim3(kFinishWaves * kWave), 0, ds->stream, ds->d, grid, ds->partials, w, C, g,
+                           (const double *)nullptr, grid, loss_partials, active_partials, w, ds->scal_dev, ds->scal_copy);
+    } else {
+        const int cg = (int)((ds->d + kWavesPerBlock - 1) / kWavesPerBlock);
+        hipLaunchKernelGGL(k_dense_columns, dim3(cg), dim3(kBlock), 0, ds->stream, ds->d, grid, ds->partials, w, C, g,
+                           (const double *)nullptr, colprod);
+        hipLaunchKernelGGL(k_dense_scalars, dim3(1), dim3(kBlock), 0, ds->stream, ds->d, grid, loss_partials, active_partials, w, colprod,
+                           ds->scal_dev, ds->scal_copy);
+    }
     TRON_HIP(hipGetLastError());
     return TRON_OK;
 }
@@ -467,7 +730,9 @@ extern "C" int tron_hv_static(tron_dataset *ds, double C, const double *v_dev, d
     }
     if (!ds->dense) { set_error("tron_hv_static: dense handles only"); return TRON_EINVAL; }
     if (!ds->have_D) { set_error("tron_hv_static: no cached D; call tron_fun_grad first"); return TRON_ESTATE; }
-    const int grid = ds->dense_grid;
+    const int Dslot = ds->Dcur;
+    const HvInput in = hv_input(ds, Dslot);
+    const int grid = in.grid;
     const int64_t need = ds->d * grid + ds->d + 1;
     if (need > kStaticScratchDoubles) {
         set_error("tron_hv_static: n = %lld, d = %lld needs %lld doubles of work space (d * %d workgroups + d + 1); the static "
@@ -494,13 +759,16 @@ extern "C" int tron_hv_static(tron_dataset *ds, double C, const double *v_dev, d
     double *scalar = colprod + ds->d;
     // Nothing has to start at zero: every workgroup of the pass writes all d of its column sums, the second stage
     // writes all d column products, the third the scalar.
-    const int Dslot = ds->Dcur;
-    const bool mask = ds->D_is_mask[Dslot];
-    TRON_TRY(dispatch_hv(ds, ds->Dbuf[Dslot], mask, mask && ds->active_frac[Dslot] < kSkipBelow, v_dev, partials));
-    const int cg = (int)((ds->d + kWavesPerBlock - 1) / kWavesPerBlock);
-    hipLaunchKernelGGL(k_dense_columns, dim3(cg), dim3(kBlock), 0, ds->stream, ds->d, grid, partials, v_dev, C, Hv_dev, v_dev, colprod);
-    hipLaunchKernelGGL(k_dense_scalars, dim3(1), dim3(kBlock), 0, ds->stream, ds->d, 0, (const double *)nullptr,
-                       (const double *)nullptr, (const double *)nullptr, colprod, vHv_dev ? vHv_dev : scalar, scalar);
+    TRON_TRY(dispatch_hv(ds, in, v_dev, partials));
+    if (ds->d <= kFinishMaxD) {
+        hipLaunchKernelGGL(k_dense_finish, dim3(1), dim3(kFinishWaves * kWave), 0, ds->stream, ds->d, grid, partials, v_dev, C, Hv_dev, v_dev, 0,
+                           (const double *)nullptr, (const double *)nullptr, (const double *)nullptr, vHv_dev ? vHv_dev : scalar, scalar);
+    } else {
+        const int cg = (int)((ds->d + kWavesPerBlock - 1) / kWavesPerBlock);
+        hipLaunchKernelGGL(k_dense_columns, dim3(cg), dim3(kBlock), 0, ds->stream, ds->d, grid, partials, v_dev, C, Hv_dev, v_dev, colprod);
+        hipLaunchKernelGGL(k_dense_scalars, dim3(1), dim3(kBlock), 0, ds->stream, ds->d, 0, (const double *)nullptr,
+                           (const double *)nullptr, (const double *)nullptr, colprod, vHv_dev ? vHv_dev : scalar, scalar);
+    }
     TRON_HIP(hipGetLastError());
     return TRON_OK;
 }

@@ -73,6 +73,7 @@ int eval_f(tron_dataset *ds, const tron_params &P, const double *w, int Dslot, d
         TRON_TRY(dense_fun_grad(ds, P.loss, P.C, w, Dslot, gout));
         TRON_TRY(read_scalars(ds, 4));
         ds->active_frac[Dslot] = ds->scal_host[3] / (double)ds->n;
+        ds->active_count[Dslot] = (int64_t)ds->scal_host[3];
         *f = 0.5 * ds->scal_host[1] + P.C * ds->scal_host[0];
         *gnorm_dense = std::sqrt(ds->scal_host[2]);
         return TRON_OK;
@@ -195,6 +196,8 @@ extern "C" int tron_solve(tron_dataset *ds, const tron_params *params, double *w
     ds->have_D = true;
     res->n_fun++;
     res->n_grad++;
+    // L2-SVM with a small active set (a warm start far along): Hessian-vector products over a compacted copy of the active rows
+    if (ds->dense && dense_compact_wanted(ds, ds->Dcur, g_tuning.dense_compact > 0 ? 0 : P.max_cg)) TRON_TRY(dense_compact_build(ds, ds->Dcur));
     if (res->gnorm0 == 0.0) res->gnorm0 = gnorm;
     // gscaled: the length of the gradient the inner solver measures its residual against (|g|, or sqrt(g.M^-1 g))
     double gscaled = gnorm;
@@ -238,6 +241,9 @@ extern "C" int tron_solve(tron_dataset *ds, const tron_params *params, double *w
             gnorm = gnorm_new;
             gscaled = gnorm;
             res->n_grad++;
+            // the active set changed with the iterate: rebuild the compacted copy if it is worth having (judged by the
+            // number of products the inner solve just took)
+            if (ds->dense && gnorm > P.eps * res->gnorm0 && dense_compact_wanted(ds, ds->Dcur, ncg)) TRON_TRY(dense_compact_build(ds, ds->Dcur));
             if (precond && gnorm > P.eps * res->gnorm0) TRON_TRY(build_preconditioner(ds, P, ds->Dcur, g, M, &gscaled));
         }
         res->outer_iters = k;
