@@ -98,6 +98,8 @@ TRON_API int tron_dataset_shape(const tron_dataset *ds, int64_t *n, int64_t *d, 
 /*
  * Layout statistics of a handle (what the library built from the input), by name:
  *   "fwd_parts", "bwd_parts"   column partitions of the forward / transposed CSR layouts (0 for dense)
+ *   "fwd_segmented", "bwd_segmented"  1 when that layout stores row segments + flag bits (every partitioned layout, and
+ *                              unpartitioned ones whose chunks mix long and short rows), 0 for plain CSR
  *   "fwd_csr_nnz", "bwd_csr_nnz"  nonzeros held in those CSR layouts
  *   "fwd_head_nnz"             of fwd_csr_nnz, the nonzeros of the head partition (the most frequent columns)
  *   "bwd_tile_nnz", "bwd_tile_rows", "bwd_tiles"  nonzeros, features and tiles of the hot-row tiles
@@ -305,6 +307,9 @@ TRON_API int tron_probe_read_bandwidth(const double *src_dev, int64_t count, int
  * floating-point summation order.
  *   "csr_parts": column partitions of the two CSR layouts: 0 = automatic (8 when the gathered
  *                vector would not stay resident in one L2, else 1), 1 = never partition, 8 = always.
+ *   "csr_segmented" (-1/0/1): unpartitioned layouts as row segments + flag bits (summed by scans) instead of plain CSR
+ *                (one lane group per row): 0 never, 1 always, -1 (default) when some chunk of the plain layout would
+ *                leave a single thread a row of about a hundred entries or more.
  * Partitioned layouts only:
  *   "csr_hot" (0/1): LDS tables of frequent columns in the forward layout;
  *   "csr_head" (0/1): a head partition for the most frequent columns of the whole matrix (needs csr_hot);

@@ -307,8 +307,8 @@ int tron_dataset_create_csr(int64_t n, int64_t d, const int64_t *rowptr, const i
     }
     if (rc >= 0) {
         int64_t need = 0;
-        if (ds->fwd.P > 1) need = std::max<int64_t>(need, ds->fwd.nseg_total);   // one partial sum per segment
-        if (ds->bwd.P > 1) need = std::max<int64_t>(need, ds->bwd.nseg_total);
+        if (!ds->fwd.plain) need = std::max<int64_t>(need, ds->fwd.nseg_total);   // one partial sum per segment
+        if (!ds->bwd.plain) need = std::max<int64_t>(need, ds->bwd.nseg_total);
         if (need > 0) {
             hipError_t e = hipMalloc(reinterpret_cast<void **>(&ds->row_partials), sizeof(double) * need);
             if (e != hipSuccess) rc = hip_fail(e, "allocate row partials", __FILE__, __LINE__);
@@ -432,6 +432,8 @@ int tron_dataset_stat(const tron_dataset *ds, const char *name, int64_t *value)
         {"bwd_bytes_combine", bb.combine}, {"hv_bytes", hv_bytes}, {"fun_grad_bytes", fun_grad_bytes},
         {"fwd_parts", ds->dense ? 0 : ds->fwd.P},
         {"bwd_parts", ds->dense ? 0 : ds->bwd.P},
+        {"fwd_segmented", (ds->dense || ds->fwd.plain) ? 0 : 1},
+        {"bwd_segmented", (ds->dense || ds->bwd.plain) ? 0 : 1},
         {"fwd_csr_nnz", ds->dense ? 0 : ds->fwd.nnz},
         {"fwd_head_nnz", (ds->dense || ds->fwd.head < 0) ? 0 : ds->fwd.part_nnz[ds->fwd.head]},
         {"bwd_csr_nnz", ds->dense ? 0 : ds->bwd.nnz},
@@ -567,6 +569,10 @@ int tron_tuning_set(const char *name, int64_t value)
     }
     if (name && strcmp(name, "csr_sell_blocks") == 0 && value >= 1 && value <= 4096) {
         g_tuning.csr_sell_blocks = value;
+        return TRON_OK;
+    }
+    if (name && strcmp(name, "csr_segmented") == 0 && value >= -1 && value <= 1) {
+        g_tuning.csr_segmented = value;
         return TRON_OK;
     }
     if (name && strcmp(name, "csr_unit") == 0 && (value == 0 || value == 1)) {

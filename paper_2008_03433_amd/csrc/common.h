@@ -40,6 +40,8 @@ struct Tuning {
     int64_t csr_tile_blocks_per_slice = 0;   // persistent workgroups per slice of hot rows (0 = automatic: 96, or 160 for unit plans)
     int64_t csr_sell_blocks = 1024;   // workgroups of the sorted-slice head kernel
     int64_t csr_sell = 1;    // unit plans: the head partition as sorted slices of 64 rows, one row per lane (0 = as chunks)
+    int64_t csr_segmented = -1;  // unpartitioned layouts as segments + flag bits instead of plain CSR: 0 never, 1 always, -1 when a
+                             //   chunk of the plain layout would leave one thread a long row (see csr_plan_build)
     int64_t csr_unit = 1;    // partitioned layouts: drop the value stream when every row of X holds one repeated value (0 = off)
     int64_t dense_compact = -1;         // dense L2-SVM: Hessian-vector products on a compacted copy of the active rows:
                                         //   0 never, 1 whenever rows are inactive, -1 automatic (see dense_compact_wanted)
@@ -101,7 +103,8 @@ struct Profiler {
 // rows that *start* inside a chunk; a row that continues into later chunks receives the remainder
 // through `carry` and the fix-up list.
 //
-// P == 1 (small matrices): plain CSR, one workgroup per chunk, epilogue applied directly.
+// P == 1 (small matrices): plain CSR, one workgroup per chunk, epilogue applied directly -- or, when long and short rows
+// share chunks, the segment layout of the partitioned case with a single range.
 //
 // P == 8 (the gathered vector would not stay resident in one L2): the column space is cut into 8
 // contiguous ranges with equal nonzero counts and the nonzeros are stored range-major: partition x
@@ -188,6 +191,9 @@ struct CsrPlan {
     SellHead sell;                       // optional (head partition of a unit plan)
     HotTiles hot;                        // optional (transposed orientation of large matrices)
     int P = 1;                           // number of column ranges (1 = unpartitioned)
+    bool plain = true;                   // P == 1 stored as plain CSR (row offsets, one workgroup per chunk, epilogue applied directly);
+                                         //   false: the segment layout below (always for P > 1; for P == 1 when rows of very
+                                         //   different lengths share chunks, which the plain kernel handles badly)
     int head = -1;                       // P, when partition P holds the entries of the matrix' most frequent columns
                                          //   (whole rows, every entry served from one LDS table, 16-bit slots in col16); else -1
     int32_t *col = nullptr;              // device, (padded) nnz of the ranges; with an LDS table, hot columns are stored as ~slot

@@ -118,10 +118,34 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
         parts = (cols * (int64_t)sizeof(double) > kGatherBytesForPartitioning && A.nnz >= kMinNnzForPartitioning) ? kColParts : 1;
     if (parts > kColParts) parts = kColParts;
     A.P = parts;
+    A.plain = (parts == 1);
     std::vector<int32_t> row_lo, fix_row, fix_part, fix_b0, fix_cnt;
 
     if (A.unit && A.P == 1) { set_error("internal: unit plan without partitions"); return TRON_EINVAL; }
-    if (A.P == 1) {
+    if (A.plain && g_tuning.csr_segmented != 0) {
+        // The plain kernel gives a chunk's rows groups of g = 256 / (rows starting in the chunk) lanes, one thread per row
+        // when there are more than 128: a row of hundreds of entries among many short ones (the middle of a Zipf
+        // distribution, in the transposed copy) then keeps one thread adding for tens of microseconds.  Count, per chunk,
+        // the additions the busiest thread would make; beyond 96 the segment layout (scans, no per-row loops) is used.
+        bool segmented = g_tuning.csr_segmented > 0;
+        int64_t r = 0;
+        const int64_t nchunks = (A.nnz + kChunk - 1) / kChunk;
+        for (int64_t c = 0; c < nchunks && !segmented; ++c) {
+            const int64_t start = c * kChunk, end = std::min<int64_t>(A.nnz, start + kChunk);
+            while (r < rows && h_rowptr[r] < start) ++r;
+            int64_t nrows = 0, longest = 0;
+            for (int64_t q = r; q < rows && h_rowptr[q] < end; ++q) {
+                ++nrows;
+                longest = std::max<int64_t>(longest, std::min<int64_t>(h_rowptr[q + 1], end) - h_rowptr[q]);
+            }
+            int64_t g = 1;
+            while (g < kWave && nrows * (g * 2) <= kBlock) g *= 2;
+            if ((longest + g - 1) / g > 96) segmented = true;
+        }
+        if (segmented) A.plain = false;
+    }
+    hot = hot && A.P > 1;   // LDS tables belong to the column ranges of large matrices
+    if (A.plain) {
         const int64_t nb64 = std::max<int64_t>(1, (A.nnz + kChunk - 1) / kChunk);
         if (nb64 > 0x7ffffff0) { set_error("matrix too large: %lld chunks", (long long)nb64); return TRON_EINVAL; }
         A.nblocks = (int)nb64;
@@ -207,26 +231,39 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
         for (int64_t j = 0; j < cols; ++j)   // head columns have count 0 here
             if (colcount[j + 1] > colcount[j] && !(hot && slot_of[j] >= 0)) A.cold_cols++;
         std::vector<int64_t>().swap(colcount);
-        // per-(partition,row) entry counts -> offsets; non-empty pairs are the segments
-        std::vector<int32_t> rp32((size_t)NP * (rows + 1), 0);
+        // per-(partition,row) entry counts -> offsets; non-empty pairs are the segments.  A segment that would straddle a
+        // chunk boundary is moved to the start of the next chunk (the gap it leaves is padding that reaches no sum), so
+        // that a chunk never continues a row of the chunk before and no carry / fix-up pass is needed; only a segment
+        // longer than a whole chunk is still split.
+        std::vector<int32_t> rp32((size_t)NP * (rows + 1), 0);    // start of (x, r) relative to the partition
+        std::vector<int32_t> len32((size_t)NP * rows, 0);         // its number of entries
         for (int64_t r = 0; r < rows; ++r)
             for (int64_t k = h_rowptr[r]; k < h_rowptr[r + 1]; ++k)
-                if (part_of[h_col[k]] < NP) rp32[(size_t)part_of[h_col[k]] * (rows + 1) + r + 1]++;
+                if (part_of[h_col[k]] < NP) len32[(size_t)part_of[h_col[k]] * rows + r]++;
         std::vector<uint16_t> mask((size_t)rows, 0);
         int64_t pos = 0, nseg_total = 0;
         int chunk = 0;
         A.max_chunks = 0;
         for (int x = 0; x < NP; ++x) {
             int32_t *rp = rp32.data() + (size_t)x * (rows + 1);
-            int64_t nseg = 0;
+            const int32_t *ln = len32.data() + (size_t)x * rows;
+            int64_t nseg = 0, at = 0;
             for (int64_t r = 0; r < rows; ++r) {
-                if (rp[r + 1] > 0) { mask[r] |= (uint16_t)(1u << x); ++nseg; }
-                rp[r + 1] += rp[r];
+                const int64_t len = ln[r];
+                if (len > 0) {
+                    mask[r] |= (uint16_t)(1u << x);
+                    ++nseg;
+                    if (len <= kChunk && at % kChunk + len > kChunk) at = (at / kChunk + 1) * kChunk;
+                }
+                rp[r] = (int32_t)at;
+                at += len;
+                if (at > 0x7ffffff0) { set_error("partition too large for 32-bit offsets"); return TRON_EINVAL; }
             }
+            rp[rows] = (int32_t)at;
             A.part_base[x] = pos;
             A.part_seg0[x] = nseg_total;
             A.part_chunk0[x] = chunk;
-            A.part_nchunks[x] = (int)std::max<int64_t>(1, (A.part_nnz[x] + kChunk - 1) / kChunk);
+            A.part_nchunks[x] = (int)std::max<int64_t>(1, (at + kChunk - 1) / kChunk);
             if (x < P) A.max_chunks = std::max(A.max_chunks, A.part_nchunks[x]);
             chunk += A.part_nchunks[x];
             pos += (int64_t)A.part_nchunks[x] * kChunk;
@@ -255,6 +292,7 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
         std::vector<uint8_t> flags((size_t)chunk * kBlock, 0);   // per chunk: one bit per entry, set on the last entry of a segment
         for (int x = 0; x < NP; ++x) {
             const int32_t *rp = rp32.data() + (size_t)x * (rows + 1);
+            const int32_t *ln = len32.data() + (size_t)x * rows;
             const int nch = A.part_nchunks[x];
             // the segments of this partition, in row order, with start/end positions relative to the partition
             int64_t m = 0;               // segment counter (partition-relative)
@@ -268,7 +306,7 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
                 t = make_int4(next_first_seg, 0, (int)off, 0);
             };
             for (int64_t r = 0; r < rows; ++r) {
-                const int64_t rs = rp[r], re = rp[r + 1];
+                const int64_t rs = rp[r], re = rs + ln[r];
                 if (re == rs) continue;
                 while (rs >= (int64_t)(c + 1) * kChunk) close_chunk((int)m, rs);   // this segment starts in a later chunk
                 seg_row[A.part_seg0[x] + m] = (int32_t)r;
@@ -287,7 +325,7 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
                 }
                 ++m;
             }
-            while (c < nch - 1) close_chunk((int)m, (int64_t)A.part_nnz[x]);
+            while (c < nch - 1) close_chunk((int)m, (int64_t)rp[rows]);
             tab[A.part_chunk0[x] + c] = t;
         }
         // first_off of a chunk inside or at the end of a split row: the chunk-relative end of that row
@@ -427,7 +465,7 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
     A.nfix = (int)fix_row.size();
     A.fix_max_cnt = 0;
     for (int32_t c : fix_cnt) A.fix_max_cnt = std::max(A.fix_max_cnt, (int)c);
-    if (A.P == 1) TRON_TRY(upload(&A.row_lo, row_lo.data(), row_lo.size(), st));
+    if (A.plain) TRON_TRY(upload(&A.row_lo, row_lo.data(), row_lo.size(), st));
     TRON_TRY(upload(&A.fix_row, fix_row.data(), fix_row.size(), st));
     TRON_TRY(upload(&A.fix_part, fix_part.data(), fix_part.size(), st));
     TRON_TRY(upload(&A.fix_b0, fix_b0.data(), fix_b0.size(), st));
@@ -530,6 +568,35 @@ __device__ __forceinline__ void chunk_body(double *prod, const double *table, in
     if (nrows <= 0) return;
     int g = 1;
     while (g < kWave && nrows * (g * 2) <= kBlock) g *= 2;
+    if (g == 1 && nrows > kBlock) {
+        // Many short rows (the tail of a Zipf-distributed transposed copy: a thousand rows of one or two entries in a
+        // chunk): one thread per row, and the row offsets of eight passes are fetched together -- a pass that waited
+        // for its own two offsets first cost a memory round trip each, eight or more per chunk.
+        constexpr int kBatch = 8;
+        for (int base = 0; base < nrows; base += kBatch * kBlock) {
+            int64_t rs[kBatch], re[kBatch];
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) {
+                const int ri = base + j * kBlock + tid;
+                const int64_t r = (int64_t)lo + (ri < nrows ? ri : nrows - 1);
+                rs[j] = (int64_t)rp[r];
+                re[j] = (int64_t)rp[r + 1];
+            }
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) {
+                const int ri = base + j * kBlock + tid;
+                if (ri < nrows) {
+                    const int64_t r = (int64_t)lo + ri;
+                    const int k0 = (int)(rs[j] - start);
+                    const int k1 = (int)(((re[j] < end) ? re[j] : end) - start);
+                    double s = 0.0;
+                    for (int k = k0; k < k1; ++k) s += prod[k];
+                    yout[r] = epilogue<EPI>(s, r, aux, alpha);
+                }
+            }
+        }
+        return;
+    }
     const int sub = tid & (g - 1);
     const int rows_per_pass = kBlock / g;
     for (int base = 0; base < nrows; base += rows_per_pass) {
@@ -1662,7 +1729,8 @@ static int launch_partials(tron_dataset *ds, const CsrPlan &A, int slot, const d
     {
         ProfScope ps(ds, slot);
         const int want = (int)(A.hot_ids ? g_tuning.csr_range_blocks_per_part : g_tuning.csr_blocks_per_part);
-        const int per_part = std::max(1, std::min(A.max_chunks, want));
+        // a single range (small matrices) gets the workgroups that eight ranges would share
+        const int per_part = std::max(1, std::min(A.max_chunks, A.P == 1 ? want * kColParts : want));
         if (A.hot_ids && A.unit)
             hipLaunchKernelGGL((k_csr_spmv_part<true, false, false, true>), dim3(per_part * A.P), dim3(kBlock), A.range_slots * sizeof(double), ds->stream,
                                pa, A.rows, part_ptrs(ds, A), x);
@@ -1687,7 +1755,7 @@ static int launch_partials(tron_dataset *ds, const CsrPlan &A, int slot, const d
 int spmv_loss(tron_dataset *ds, const CsrPlan &A, int slot, int loss, const double *x, double *zwork, double *zhat, double *D,
               const double *post)
 {
-    if (A.P == 1) {
+    if (A.plain) {
         if (post) { set_error("internal: post-scaling on an unpartitioned plan"); return TRON_EINVAL; }
         TRON_TRY(launch_plain<EPI_PLAIN>(ds, A, slot, x, zwork, nullptr, 0.0));
         return loss_terms(ds, loss, zwork, zhat, D);
@@ -1705,7 +1773,7 @@ int spmv_loss(tron_dataset *ds, const CsrPlan &A, int slot, int loss, const doub
 
 int spmv_scale(tron_dataset *ds, const CsrPlan &A, int slot, const double *x, const double *scale, double *out, const double *post)
 {
-    if (A.P == 1) {
+    if (A.plain) {
         if (post) { set_error("internal: post-scaling on an unpartitioned plan"); return TRON_EINVAL; }
         return launch_plain<EPI_SCALE>(ds, A, slot, x, out, scale, 0.0);
     }
@@ -1740,7 +1808,7 @@ int spmv_axpy(tron_dataset *ds, const CsrPlan &A, int slot, const double *x, con
         set_error("internal: pre-scaled vector for a plan without column scale");
         return TRON_EINVAL;
     }
-    if (A.P == 1) {
+    if (A.plain) {
         TRON_TRY(launch_plain<EPI_AXPY>(ds, A, slot, x, out, add, alpha, square));
         if (!add) return 0;
         return dot_partials(ds, A.rows, out, dot_self ? out : add, nullptr, nullptr, nullptr, nullptr);
@@ -1767,7 +1835,7 @@ PlanBytes plan_bytes(const CsrPlan &A)
 {
     PlanBytes b{0, 0, 0, 0, 0, 0};
     const int64_t vbytes = A.unit ? 0 : 8;   // value stream per stored entry
-    if (A.P == 1) {
+    if (A.plain) {
         // plain CSR in chunks: columns and values once, row offsets, the gathered vector and the result once each
         b.ranges = A.nnz * (4 + 8) + 8 * (A.rows + 1) + 4 * ((int64_t)A.nblocks + 1) + 8 * A.cols + 8 * A.rows;
         return b;

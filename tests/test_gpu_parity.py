@@ -141,6 +141,44 @@ def test_csr_partitioned_layout(rng, loss, force_partitions):
     check_calls(p, loss, 1.0, rng, n_hv=1)
 
 
+@pytest.mark.parametrize("segmented", [0, 1, -1])
+@pytest.mark.parametrize("loss", [LOSS_LR, LOSS_L2SVM])
+def test_csr_unpartitioned_layouts(rng, loss, segmented):
+    """Small matrices: plain CSR (one lane group per row) or row segments with flag bits (scans) in a single range; the
+    automatic choice takes the second for the Zipf-skewed transposed copy of config 2 and the first for config 1."""
+    import paper_2008_03433_amd as tron
+    tron.tron_tuning_set("csr_segmented", segmented)
+    try:
+        for p, expect_bwd in ((dg.config1(), 0), (dg.config2(), 1)):
+            if segmented == -1:
+                ds = tron.Dataset.from_problem(p)
+                got = (tron.tron_dataset_stat(ds.handle, "fwd_segmented"), tron.tron_dataset_stat(ds.handle, "bwd_segmented"))
+                ds.close()
+                assert got[1] == expect_bwd, (p.name, got)
+            check_calls(p, loss, 1.0, rng, w_scale=1.0, n_hv=1)
+        n, d = 3000, 5000
+        X = rng.standard_normal((n, d)) * (rng.random((n, d)) < 0.002)
+        X[5] = rng.standard_normal(d)          # rows and columns longer than a chunk
+        X[:, 17] = rng.standard_normal(n)
+        X[100:140] = 0.0
+        X[:, 2000:2600] = 0.0
+        X[n - 1] = 0.0
+        X[:, d - 1] = 0.0
+        y = np.where(rng.random(n) < 0.5, 1.0, -1.0)
+        check_calls(_csr_from_dense(X, y), loss, 0.5, rng, w_scale=0.2, n_hv=1)
+        X = rng.standard_normal((50, 3))
+        check_calls(_csr_from_dense(X, np.where(rng.random(50) < 0.5, 1.0, -1.0)), loss, 1.0, rng, n_hv=1)
+        e = SparseProblem("empty", 3, 4, np.zeros(4, dtype=np.int64), np.zeros(0, dtype=np.int32), np.zeros(0),
+                          np.array([1.0, -1.0, 1.0]))
+        check_calls(e, loss, 1.0, rng, n_hv=1)
+        if segmented == 1:
+            p = dg.config2()
+            compare_solves(p, p.loss, p.C, p.eps)
+            compare_solves(p, p.loss, p.C, p.eps, precond_blend=0.01)
+    finally:
+        tron.tron_tuning_set("csr_segmented", -1)
+
+
 @pytest.mark.parametrize("knobs", [{"csr_head": 0}, {"csr_hot": 0}, {"csr_tiles": 0}, {"csr_range_slots": 64}, {"csr_unit": 0}, {"csr_sell": 0},
                                    {"csr_sell_blocks": 1},
                                    {"csr_unit": 0, "csr_head": 0, "csr_tiles": 0},
