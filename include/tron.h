@@ -321,6 +321,10 @@ TRON_API int tron_probe_read_bandwidth(const double *src_dev, int64_t count, int
  *                4096 columns); a quarter of the number of wavefronts the slices are dealt to;
  *   "csr_hot_blocks_per_part", "csr_range_blocks_per_part", "csr_blocks_per_part",
  *   "csr_tile_blocks_per_slice": persistent workgroups of the head, table, table-less and tile kernels.
+ * "fuse_reductions" (-1/0/1), read at every call: the second stage of every two-stage reduction (sum of the
+ *   per-workgroup partial sums) is done by the workgroup of the producing kernel that finishes last (found through a ticket
+ *   counter; the sums themselves are added in a fixed order, so results do not change) instead of by a launch of its own:
+ *   0 never, 1 always, -1 (default) for launches of up to 32 workgroups (vectors of up to 32768 elements).
  * "dense_compact" (-1/0/1): L2-SVM on a dense matrix with d <= 32: Hessian-vector products run over a compacted copy of the
  *   active rows, X_I of Section 5 of the paper, built on the device (up to n*d more doubles of device memory): 0 never (the
  *   pass over X skips inactive rows instead), 1 whenever some rows are inactive (tron_fun_grad then builds the copy for the

@@ -119,6 +119,8 @@ static int alloc_common(tron_dataset *ds)
     TRON_HIP(hipHostMalloc(reinterpret_cast<void **>(&ds->scal_host), sizeof(double) * kScalars, hipHostMallocMapped));
     TRON_HIP(hipHostGetDevicePointer(reinterpret_cast<void **>(&ds->scal_dev), ds->scal_host, 0));
     TRON_HIP(hipMalloc(reinterpret_cast<void **>(&ds->scal_copy), sizeof(double) * kScalars));
+    TRON_HIP(hipMalloc(reinterpret_cast<void **>(&ds->ticket), 64));
+    TRON_HIP(hipMemset(ds->ticket, 0, 64));
     ds->vec_grid_n = vec_grid_for(ds->n);
     ds->vec_grid_d = vec_grid_for(ds->d);
     return TRON_OK;
@@ -171,7 +173,7 @@ void tron_dataset_destroy(tron_dataset *ds)
     ds->fwd.release();
     ds->bwd.release();
     hipFree(ds->y); hipFree(ds->y8); hipFree(ds->z); hipFree(ds->zhat); hipFree(ds->Dbuf[0]); hipFree(ds->Dbuf[1]);
-    hipFree(ds->partials); hipFree(ds->row_partials); hipFree(ds->unit_scale); hipFree(ds->scal_copy);
+    hipFree(ds->partials); hipFree(ds->row_partials); hipFree(ds->unit_scale); hipFree(ds->scal_copy); hipFree(ds->ticket);
     if (ds->scal_host) hipHostFree(ds->scal_host);
     for (double *p : ds->sv) hipFree(p);
     ds->prof.destroy();
@@ -577,6 +579,10 @@ int tron_tuning_set(const char *name, int64_t value)
     }
     if (name && strcmp(name, "csr_unit") == 0 && (value == 0 || value == 1)) {
         g_tuning.csr_unit = value;
+        return TRON_OK;
+    }
+    if (name && strcmp(name, "fuse_reductions") == 0 && value >= -1 && value <= 1) {
+        g_tuning.fuse_reductions = value;
         return TRON_OK;
     }
     if (name && strcmp(name, "dense_compact") == 0 && value >= -1 && value <= 1) {

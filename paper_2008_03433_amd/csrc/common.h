@@ -45,6 +45,8 @@ struct Tuning {
     int64_t csr_unit = 1;    // partitioned layouts: drop the value stream when every row of X holds one repeated value (0 = off)
     int64_t dense_compact = -1;         // dense L2-SVM: Hessian-vector products on a compacted copy of the active rows:
                                         //   0 never, 1 whenever rows are inactive, -1 automatic (see dense_compact_wanted)
+    int64_t fuse_reductions = -1;  // second reduction stage inside the producing kernel (last workgroup): 0 never, 1 always,
+                                   //   -1 automatic (launches of few workgroups, where the extra launch costs more than it does)
     int64_t dense_device_driver = -1;   // tron_solve on dense d <= 32 without preconditioner driven from the device:
                                         //   0 never, 1 always, -1 automatic (the L2-SVM on matrices up to 1 GB)
     int64_t batch_grid = 0;  // workgroups of the multi-problem pass: 0 = as many as are resident at once
@@ -273,6 +275,8 @@ struct tron_dataset {
     double *scal_host = nullptr; // kScalars pinned host scalars, mapped into the device's address space
     double *scal_dev = nullptr;  // the device address of scal_host (kernels write the scalars there)
     double *scal_copy = nullptr; // the same scalars in device memory, for kernels that continue from them without the host
+    unsigned *ticket = nullptr;  // counter of finished workgroups for reductions completed inside the producing kernel (zero between kernels)
+    bool finish_done = false;    // the last producing kernel did: the next reduce_final call is a no-op
     int dense_grid = 0;          // workgroups of the dense kernels
     int vec_grid_n = 0, vec_grid_d = 0;  // workgroups of elementwise kernels over n / d
 
@@ -297,6 +301,19 @@ struct tron_dataset {
 
 namespace tron {
 
+// Where the kernel that produces first-stage partial sums puts the finished sums when it adds them itself (the workgroup
+// that finishes last does it, see finish_partials): scalar slots first, first + 1, ... of both copies.  ticket == null:
+// a separate k_reduce_final launch adds them.
+struct Finish {
+    unsigned *ticket;
+    double *scal, *scal_copy;
+    int first;
+};
+// The Finish for a producing kernel of `grid` workgroups whose sums go to scalars first_scalar...: with a ticket when
+// the launch is small enough for that to pay (then the reduce_final call that follows does nothing), without otherwise or
+// when first_scalar < 0.
+Finish finish_for(tron_dataset *ds, int first_scalar, int grid);
+
 // RAII bracket used by the launch helpers
 struct ProfScope {
     tron_dataset *ds; int idx;
@@ -310,12 +327,13 @@ struct ProfScope {
 // out_scal[s] = sum of partials[s*stride .. s*stride+count) for s < nslots (second stage)
 int reduce_final(tron_dataset *ds, int nslots, int count, int stride, int first_scalar);
 // partial sums of a.b (and optionally c.e, f.h) into partial slots 0..k-1; returns #partials per slot
+// `first` (here and below): scalar slot the finished sums go to when the kernel completes the reduction itself (see Finish)
 int dot_partials(tron_dataset *ds, int64_t m, const double *a0, const double *b0, const double *a1, const double *b1,
-                 const double *a2, const double *b2);
-int loss_terms(tron_dataset *ds, int loss, const double *z, double *zhat, double *D);  // partial slot 0 = sum loss
+                 const double *a2, const double *b2, int first = -1);
+int loss_terms(tron_dataset *ds, int loss, const double *z, double *zhat, double *D, int first = -1);  // partial slot 0 = sum loss
 int read_scalars(tron_dataset *ds, int count);  // stream sync; then scal_host[0..count) holds what the kernels wrote
 // CG vector kernels (see solver.hip); M = diagonal preconditioner or null
-int cg_init(tron_dataset *ds, const double *g, const double *M, double *s, double *r, double *p);  // M: slot0 = g.(g/M); returns #partials
+int cg_init(tron_dataset *ds, const double *g, const double *M, double *s, double *r, double *p, int first = -1);  // M: slot0 = g.(g/M); returns #partials
 // What the CG step kernel needs to form the step length itself from the device copy of the scalars (slot 0 = p.Hp,
 // slots 1..3 = p.p, s.p, s.s unless `first`): alpha = rr / p.Hp, or the step to the trust-region boundary if
 // |s + alpha p| >= delta.  The kernel leaves the step taken in scalar 4 and whether it went to the boundary in scalar 5.
@@ -323,11 +341,11 @@ struct CgStepCtl {
     double rr, delta;
     int first;      // first iteration: s = 0 and p.p = rr
 };
-int cg_step(tron_dataset *ds, const CgStepCtl &ctl, const double *p, const double *Hp, const double *M, double *s, double *r);  // slot0 = r.r | r.(r/M)
+int cg_step(tron_dataset *ds, const CgStepCtl &ctl, const double *p, const double *Hp, const double *M, double *s, double *r, int first = -1);  // slot0 = r.r | r.(r/M)
 // beta = (scalar 0 of the device copy) / rr_old
-int cg_dir(tron_dataset *ds, double rr_old, const double *r, const double *s, const double *M, double *p);  // slots: p.p, s.p, s.s (M-weighted)
+int cg_dir(tron_dataset *ds, double rr_old, const double *r, const double *s, const double *M, double *p, int first = -1);  // slots: p.p, s.p, s.s (M-weighted)
 int trial_point(tron_dataset *ds, const double *w, const double *s, const double *g, const double *r, const double *M,
-                double *wnew);  // wnew = w+s; slots: g.s, s.r, s.s | s.Ms
+                double *wnew, int first = -1);  // wnew = w+s; slots: g.s, s.r, s.s | s.Ms
 int probe_read(const double *src, int64_t count, int reps, hipStream_t st, double *ms, double *checksum);
 int probe_copy(double *dst, const double *src, int64_t count, int reps, hipStream_t st, double *ms);
 
@@ -349,11 +367,11 @@ int hot_tiles_build(CsrPlan &A, const int64_t *t_rowptr, const int32_t *t_col, c
 //   elementwise -- the column scale of the unit plan that will gather from it (then passed with x_prescaled = true)
 // Each returns the number of first-stage partials in slot 0 (0 if none), or a negative error.
 int spmv_loss(tron_dataset *ds, const CsrPlan &A, int slot, int loss, const double *x, double *zwork, double *zhat, double *D,
-              const double *post = nullptr);
+              const double *post = nullptr, int first = -1);
 int spmv_scale(tron_dataset *ds, const CsrPlan &A, int slot, const double *x, const double *scale, double *out,
                const double *post = nullptr);
 int spmv_axpy(tron_dataset *ds, const CsrPlan &A, int slot, const double *x, const double *add, double alpha,
-              bool dot_self, double *out, bool square = false, bool x_prescaled = false);
+              bool dot_self, double *out, bool square = false, bool x_prescaled = false, int first = -1);
 
 // Bytes one launch of each kernel of a product with plan A has to move in the format A stores (what the byte counters
 // of the memory system would read for a launch without any wasted traffic): the streams it reads once, the vector

@@ -131,6 +131,38 @@ __device__ __forceinline__ double block_sum(double v, double *lds)
     return t;
 }
 
+// Second reduction stage inside the producing kernel (see Finish in common.h).  Every thread of every workgroup calls it
+// after thread 0 has written the workgroup's partial sums (NSLOTS of them, `stride` apart).  The workgroup that draws
+// the last ticket adds the partial sums of all workgroups -- in the order and with the arithmetic of k_reduce_final, so
+// the result does not depend on which workgroup that is -- writes the scalars and clears the counter for the next
+// kernel on the stream.  The counter is the only thing touched atomically; no sum goes through an atomic.
+template <int NSLOTS>
+__device__ __forceinline__ void finish_partials(const Finish &f, const double *partials, int stride, double *lds)
+{
+    if (!f.ticket) return;
+    __shared__ int is_last;
+    if (threadIdx.x == 0) {
+        __threadfence();   // the partial sums above are visible device-wide before the ticket is
+        is_last = (atomicAdd(f.ticket, 1u) == gridDim.x - 1) ? 1 : 0;
+    }
+    __syncthreads();
+    if (!is_last) return;
+    __threadfence();       // and the other workgroups' partial sums are visible here
+    const int count = (int)gridDim.x;
+#pragma unroll
+    for (int s = 0; s < NSLOTS; ++s) {
+        const double *p = partials + (int64_t)s * stride;
+        double acc = 0.0;
+        for (int b = threadIdx.x; b < count; b += kBlock) acc += __builtin_nontemporal_load(p + b);
+        acc = block_sum(acc, lds);
+        if (threadIdx.x == 0) {
+            f.scal[f.first + s] = acc;
+            f.scal_copy[f.first + s] = acc;
+        }
+    }
+    if (threadIdx.x == 0) *f.ticket = 0u;
+}
+
 // Per-instance terms at margin z with label y (Table 1 and Appendix E of the paper):
 //   logistic:  t = y z, h = 1/(1+exp(-t));  alpha = log(1+exp(-t)),  zhat = (h-1) y,  D = h (1-h)
 //   L2-SVM:    m = 1 - y z;  active iff m > 0;  alpha = max(0,m)^2,  zhat = 2 (z-y) [active],  D = 2 [active]

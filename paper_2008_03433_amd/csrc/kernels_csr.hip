@@ -1572,7 +1572,7 @@ __device__ __forceinline__ double sum_parts(const PartialRef &P, int64_t G, int6
 template <int LOSS>
 __global__ __launch_bounds__(kBlock) void k_combine_loss(int64_t n, PartialRef P, const double *__restrict__ y,
                                                          double *__restrict__ zhat, double *__restrict__ D, double *__restrict__ red,
-                                                         const double *__restrict__ post)
+                                                         const double *__restrict__ post, Finish fin)
 {
     __shared__ double lds[kWavesPerBlock];
     double acc = 0.0;
@@ -1588,6 +1588,7 @@ __global__ __launch_bounds__(kBlock) void k_combine_loss(int64_t n, PartialRef P
     }
     acc = block_sum(acc, lds);
     if (threadIdx.x == 0) red[blockIdx.x] = acc;
+    finish_partials<1>(fin, red, 0, lds);
 }
 
 // out = scale .* sum of partials
@@ -1606,7 +1607,7 @@ __global__ __launch_bounds__(kBlock) void k_combine_scale(int64_t rows, PartialR
 // out = add + alpha * sum of partials (add == null: add 1); partial slot 0 = out . (SELF ? out : add)
 template <bool SELF>
 __global__ __launch_bounds__(kBlock) void k_combine_axpy(int64_t rows, PartialRef P, const double *__restrict__ add, double alpha,
-                                                         double *__restrict__ out, double *__restrict__ red, HotRef hot)
+                                                         double *__restrict__ out, double *__restrict__ red, HotRef hot, Finish fin)
 {
     __shared__ double lds[kWavesPerBlock];
     double acc = 0.0;
@@ -1621,6 +1622,7 @@ __global__ __launch_bounds__(kBlock) void k_combine_axpy(int64_t rows, PartialRe
     }
     acc = block_sum(acc, lds);
     if (threadIdx.x == 0) red[blockIdx.x] = acc;
+    finish_partials<1>(fin, red, 0, lds);
 }
 
 // ------------------------------------------------------------------ launchers
@@ -1753,20 +1755,21 @@ static int launch_partials(tron_dataset *ds, const CsrPlan &A, int slot, const d
 }
 
 int spmv_loss(tron_dataset *ds, const CsrPlan &A, int slot, int loss, const double *x, double *zwork, double *zhat, double *D,
-              const double *post)
+              const double *post, int first)
 {
     if (A.plain) {
         if (post) { set_error("internal: post-scaling on an unpartitioned plan"); return TRON_EINVAL; }
         TRON_TRY(launch_plain<EPI_PLAIN>(ds, A, slot, x, zwork, nullptr, 0.0));
-        return loss_terms(ds, loss, zwork, zhat, D);
+        return loss_terms(ds, loss, zwork, zhat, D, first);
     }
     TRON_TRY(launch_partials(ds, A, slot, x));
     ProfScope ps(ds, SLOT_SPMV_COMBINE);
     const int g = vec_grid(A.rows);
+    const Finish fin = finish_for(ds, first, g);
     if (loss == TRON_LOSS_LR)
-        hipLaunchKernelGGL(k_combine_loss<TRON_LOSS_LR>, dim3(g), dim3(kBlock), 0, ds->stream, A.rows, partial_ref(ds, A), ds->y, zhat, D, ds->partials, post);
+        hipLaunchKernelGGL(k_combine_loss<TRON_LOSS_LR>, dim3(g), dim3(kBlock), 0, ds->stream, A.rows, partial_ref(ds, A), ds->y, zhat, D, ds->partials, post, fin);
     else
-        hipLaunchKernelGGL(k_combine_loss<TRON_LOSS_L2SVM>, dim3(g), dim3(kBlock), 0, ds->stream, A.rows, partial_ref(ds, A), ds->y, zhat, D, ds->partials, post);
+        hipLaunchKernelGGL(k_combine_loss<TRON_LOSS_L2SVM>, dim3(g), dim3(kBlock), 0, ds->stream, A.rows, partial_ref(ds, A), ds->y, zhat, D, ds->partials, post, fin);
     TRON_HIP(hipGetLastError());
     return g;
 }
@@ -1795,7 +1798,7 @@ __global__ __launch_bounds__(kBlock) void k_prescale(int64_t m, const double *__
 }
 
 int spmv_axpy(tron_dataset *ds, const CsrPlan &A, int slot, const double *x, const double *add, double alpha, bool dot_self,
-              double *out, bool square, bool x_prescaled)
+              double *out, bool square, bool x_prescaled, int first)
 {
     if (square && A.hot_ids) { set_error("internal: squared product on a layout with LDS tables"); return TRON_EINVAL; }
     if (A.unit && A.col_scale && !x_prescaled) {
@@ -1811,7 +1814,7 @@ int spmv_axpy(tron_dataset *ds, const CsrPlan &A, int slot, const double *x, con
     if (A.plain) {
         TRON_TRY(launch_plain<EPI_AXPY>(ds, A, slot, x, out, add, alpha, square));
         if (!add) return 0;
-        return dot_partials(ds, A.rows, out, dot_self ? out : add, nullptr, nullptr, nullptr, nullptr);
+        return dot_partials(ds, A.rows, out, dot_self ? out : add, nullptr, nullptr, nullptr, nullptr, first);
     }
     HotRef hot{nullptr, nullptr};
     if (A.hot.ntiles_total > 0) {
@@ -1822,10 +1825,11 @@ int spmv_axpy(tron_dataset *ds, const CsrPlan &A, int slot, const double *x, con
     TRON_TRY(launch_partials(ds, A, slot, x, square));
     ProfScope ps(ds, SLOT_SPMV_COMBINE);
     const int g = vec_grid(A.rows);
+    const Finish fin = finish_for(ds, add ? first : -1, g);
     if (dot_self)
-        hipLaunchKernelGGL(k_combine_axpy<true>, dim3(g), dim3(kBlock), 0, ds->stream, A.rows, partial_ref(ds, A), add, alpha, out, ds->partials, hot);
+        hipLaunchKernelGGL(k_combine_axpy<true>, dim3(g), dim3(kBlock), 0, ds->stream, A.rows, partial_ref(ds, A), add, alpha, out, ds->partials, hot, fin);
     else
-        hipLaunchKernelGGL(k_combine_axpy<false>, dim3(g), dim3(kBlock), 0, ds->stream, A.rows, partial_ref(ds, A), add, alpha, out, ds->partials, hot);
+        hipLaunchKernelGGL(k_combine_axpy<false>, dim3(g), dim3(kBlock), 0, ds->stream, A.rows, partial_ref(ds, A), add, alpha, out, ds->partials, hot, fin);
     TRON_HIP(hipGetLastError());
     return g;
 }

@@ -24,8 +24,25 @@ __global__ __launch_bounds__(kBlock) void k_reduce_final(const double *__restric
     }
 }
 
+// Automatic rule: only launches of up to kFuseMaxGrid workgroups complete their own reduction.  Every workgroup pays a
+// device-wide fence and a ticket (a few microseconds, overlapped only if there are few of them); measured: with 5
+// workgroups a solve of the smallest sparse configuration takes 0.42 instead of 0.49 ms, with 47 nothing is gained, with
+// 2048 a combine kernel takes 65 instead of 36 us.
+constexpr int kFuseMaxGrid = 32;
+Finish finish_for(tron_dataset *ds, int first_scalar, int grid)
+{
+    const bool fuse = ds->ticket && first_scalar >= 0 &&
+                      (g_tuning.fuse_reductions > 0 || (g_tuning.fuse_reductions < 0 && grid <= kFuseMaxGrid));
+    ds->finish_done = fuse;
+    return Finish{fuse ? ds->ticket : nullptr, ds->scal_dev, ds->scal_copy, first_scalar};
+}
+
 int reduce_final(tron_dataset *ds, int nslots, int count, int stride, int first_scalar)
 {
+    if (ds->finish_done) {   // the kernel that produced the partial sums has added them already
+        ds->finish_done = false;
+        return TRON_OK;
+    }
     ProfScope ps(ds, SLOT_REDUCE_FINAL);
     hipLaunchKernelGGL(k_reduce_final, dim3(nslots), dim3(kBlock), 0, ds->stream, ds->partials, count, stride,
                        ds->scal_dev, ds->scal_copy, first_scalar);
@@ -53,7 +70,7 @@ template <int K>
 __global__ __launch_bounds__(kBlock) void k_dots(int64_t m, const double *__restrict__ a0, const double *__restrict__ b0,
                                                  const double *__restrict__ a1, const double *__restrict__ b1,
                                                  const double *__restrict__ a2, const double *__restrict__ b2,
-                                                 double *__restrict__ partials, int stride)
+                                                 double *__restrict__ partials, int stride, Finish fin)
 {
     __shared__ double lds[kWavesPerBlock];
     double s0 = 0.0, s1 = 0.0, s2 = 0.0;
@@ -72,19 +89,21 @@ __global__ __launch_bounds__(kBlock) void k_dots(int64_t m, const double *__rest
         s2 = block_sum(s2, lds);
         if (threadIdx.x == 0) partials[2 * stride + blockIdx.x] = s2;
     }
+    finish_partials<K>(fin, partials, stride, lds);
 }
 
 int dot_partials(tron_dataset *ds, int64_t m, const double *a0, const double *b0, const double *a1, const double *b1,
-                 const double *a2, const double *b2)
+                 const double *a2, const double *b2, int first)
 {
     ProfScope ps(ds, SLOT_DOT);
     const int g = vec_grid(m);
+    const Finish fin = finish_for(ds, first, g);
     if (a2)
-        hipLaunchKernelGGL(k_dots<3>, dim3(g), dim3(kBlock), 0, ds->stream, m, a0, b0, a1, b1, a2, b2, ds->partials, kMaxGrid);
+        hipLaunchKernelGGL(k_dots<3>, dim3(g), dim3(kBlock), 0, ds->stream, m, a0, b0, a1, b1, a2, b2, ds->partials, kMaxGrid, fin);
     else if (a1)
-        hipLaunchKernelGGL(k_dots<2>, dim3(g), dim3(kBlock), 0, ds->stream, m, a0, b0, a1, b1, a2, b2, ds->partials, kMaxGrid);
+        hipLaunchKernelGGL(k_dots<2>, dim3(g), dim3(kBlock), 0, ds->stream, m, a0, b0, a1, b1, a2, b2, ds->partials, kMaxGrid, fin);
     else
-        hipLaunchKernelGGL(k_dots<1>, dim3(g), dim3(kBlock), 0, ds->stream, m, a0, b0, a1, b1, a2, b2, ds->partials, kMaxGrid);
+        hipLaunchKernelGGL(k_dots<1>, dim3(g), dim3(kBlock), 0, ds->stream, m, a0, b0, a1, b1, a2, b2, ds->partials, kMaxGrid, fin);
     TRON_HIP(hipGetLastError());
     return g;
 }
@@ -94,7 +113,7 @@ int dot_partials(tron_dataset *ds, int64_t m, const double *a0, const double *b0
 template <int LOSS>
 __global__ __launch_bounds__(kBlock) void k_loss_terms(int64_t n, const double *__restrict__ z, const double *__restrict__ y,
                                                        double *__restrict__ zhat, double *__restrict__ D,
-                                                       double *__restrict__ partials)
+                                                       double *__restrict__ partials, Finish fin)
 {
     __shared__ double lds[kWavesPerBlock];
     double acc = 0.0;
@@ -107,16 +126,18 @@ __global__ __launch_bounds__(kBlock) void k_loss_terms(int64_t n, const double *
     }
     acc = block_sum(acc, lds);
     if (threadIdx.x == 0) partials[blockIdx.x] = acc;
+    finish_partials<1>(fin, partials, 0, lds);
 }
 
-int loss_terms(tron_dataset *ds, int loss, const double *z, double *zhat, double *D)
+int loss_terms(tron_dataset *ds, int loss, const double *z, double *zhat, double *D, int first)
 {
     ProfScope ps(ds, SLOT_LOSS_TERMS);
     const int g = vec_grid(ds->n);
+    const Finish fin = finish_for(ds, first, g);
     if (loss == TRON_LOSS_LR)
-        hipLaunchKernelGGL(k_loss_terms<TRON_LOSS_LR>, dim3(g), dim3(kBlock), 0, ds->stream, ds->n, z, ds->y, zhat, D, ds->partials);
+        hipLaunchKernelGGL(k_loss_terms<TRON_LOSS_LR>, dim3(g), dim3(kBlock), 0, ds->stream, ds->n, z, ds->y, zhat, D, ds->partials, fin);
     else
-        hipLaunchKernelGGL(k_loss_terms<TRON_LOSS_L2SVM>, dim3(g), dim3(kBlock), 0, ds->stream, ds->n, z, ds->y, zhat, D, ds->partials);
+        hipLaunchKernelGGL(k_loss_terms<TRON_LOSS_L2SVM>, dim3(g), dim3(kBlock), 0, ds->stream, ds->n, z, ds->y, zhat, D, ds->partials, fin);
     TRON_HIP(hipGetLastError());
     return g;
 }
@@ -130,7 +151,7 @@ int loss_terms(tron_dataset *ds, int loss, const double *z, double *zhat, double
 template <bool PRE>
 __global__ __launch_bounds__(kBlock) void k_cg_init(int64_t d, const double *__restrict__ g, const double *__restrict__ M,
                                                     double *__restrict__ s, double *__restrict__ r, double *__restrict__ p,
-                                                    double *__restrict__ partials)
+                                                    double *__restrict__ partials, Finish fin)
 {
     __shared__ double lds[kWavesPerBlock];
     double acc = 0.0;
@@ -145,15 +166,17 @@ __global__ __launch_bounds__(kBlock) void k_cg_init(int64_t d, const double *__r
     if (PRE) {
         acc = block_sum(acc, lds);
         if (threadIdx.x == 0) partials[blockIdx.x] = acc;
+        finish_partials<1>(fin, partials, 0, lds);
     }
 }
 
-int cg_init(tron_dataset *ds, const double *g, const double *M, double *s, double *r, double *p)
+int cg_init(tron_dataset *ds, const double *g, const double *M, double *s, double *r, double *p, int first)
 {
     ProfScope ps(ds, SLOT_CG_VEC);
     const int gr = vec_grid(ds->d);
-    if (M) hipLaunchKernelGGL(k_cg_init<true>, dim3(gr), dim3(kBlock), 0, ds->stream, ds->d, g, M, s, r, p, ds->partials);
-    else hipLaunchKernelGGL(k_cg_init<false>, dim3(gr), dim3(kBlock), 0, ds->stream, ds->d, g, M, s, r, p, ds->partials);
+    const Finish fin = finish_for(ds, M ? first : -1, gr);   // without M the kernel produces no sum
+    if (M) hipLaunchKernelGGL(k_cg_init<true>, dim3(gr), dim3(kBlock), 0, ds->stream, ds->d, g, M, s, r, p, ds->partials, fin);
+    else hipLaunchKernelGGL(k_cg_init<false>, dim3(gr), dim3(kBlock), 0, ds->stream, ds->d, g, M, s, r, p, ds->partials, fin);
     TRON_HIP(hipGetLastError());
     return gr;
 }
@@ -180,7 +203,7 @@ template <bool PRE>
 __global__ __launch_bounds__(kBlock) void k_cg_step(int64_t d, CgStepCtl ctl, const double *__restrict__ sc, const double *__restrict__ p,
                                                     const double *__restrict__ Hp, const double *__restrict__ M,
                                                     double *__restrict__ s, double *__restrict__ r, double *__restrict__ partials,
-                                                    double *__restrict__ scal)
+                                                    double *__restrict__ scal, Finish fin)
 {
     __shared__ double lds[kWavesPerBlock];
     bool boundary;
@@ -198,14 +221,16 @@ __global__ __launch_bounds__(kBlock) void k_cg_step(int64_t d, CgStepCtl ctl, co
     }
     acc = block_sum(acc, lds);
     if (threadIdx.x == 0) partials[blockIdx.x] = acc;
+    finish_partials<1>(fin, partials, 0, lds);
 }
 
-int cg_step(tron_dataset *ds, const CgStepCtl &ctl, const double *p, const double *Hp, const double *M, double *s, double *r)
+int cg_step(tron_dataset *ds, const CgStepCtl &ctl, const double *p, const double *Hp, const double *M, double *s, double *r, int first)
 {
     ProfScope ps(ds, SLOT_CG_VEC);
     const int g = vec_grid(ds->d);
-    if (M) hipLaunchKernelGGL(k_cg_step<true>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, ctl, ds->scal_copy, p, Hp, M, s, r, ds->partials, ds->scal_dev);
-    else hipLaunchKernelGGL(k_cg_step<false>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, ctl, ds->scal_copy, p, Hp, M, s, r, ds->partials, ds->scal_dev);
+    const Finish fin = finish_for(ds, first, g);
+    if (M) hipLaunchKernelGGL(k_cg_step<true>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, ctl, ds->scal_copy, p, Hp, M, s, r, ds->partials, ds->scal_dev, fin);
+    else hipLaunchKernelGGL(k_cg_step<false>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, ctl, ds->scal_copy, p, Hp, M, s, r, ds->partials, ds->scal_dev, fin);
     TRON_HIP(hipGetLastError());
     return g;
 }
@@ -215,7 +240,7 @@ int cg_step(tron_dataset *ds, const CgStepCtl &ctl, const double *p, const doubl
 template <bool PRE>
 __global__ __launch_bounds__(kBlock) void k_cg_dir(int64_t d, double rr_old, const double *__restrict__ sc, const double *__restrict__ r,
                                                    const double *__restrict__ s, const double *__restrict__ M,
-                                                   double *__restrict__ p, double *__restrict__ partials, int stride)
+                                                   double *__restrict__ p, double *__restrict__ partials, int stride, Finish fin)
 {
     __shared__ double lds[kWavesPerBlock];
     const double beta = sc[0] / rr_old;
@@ -241,14 +266,16 @@ __global__ __launch_bounds__(kBlock) void k_cg_dir(int64_t d, double rr_old, con
     if (threadIdx.x == 0) partials[stride + blockIdx.x] = sp;
     ss = block_sum(ss, lds);
     if (threadIdx.x == 0) partials[2 * stride + blockIdx.x] = ss;
+    finish_partials<3>(fin, partials, stride, lds);
 }
 
-int cg_dir(tron_dataset *ds, double rr_old, const double *r, const double *s, const double *M, double *p)
+int cg_dir(tron_dataset *ds, double rr_old, const double *r, const double *s, const double *M, double *p, int first)
 {
     ProfScope ps(ds, SLOT_CG_VEC);
     const int g = vec_grid(ds->d);
-    if (M) hipLaunchKernelGGL(k_cg_dir<true>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, rr_old, ds->scal_copy, r, s, M, p, ds->partials, kMaxGrid);
-    else hipLaunchKernelGGL(k_cg_dir<false>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, rr_old, ds->scal_copy, r, s, M, p, ds->partials, kMaxGrid);
+    const Finish fin = finish_for(ds, first, g);
+    if (M) hipLaunchKernelGGL(k_cg_dir<true>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, rr_old, ds->scal_copy, r, s, M, p, ds->partials, kMaxGrid, fin);
+    else hipLaunchKernelGGL(k_cg_dir<false>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, rr_old, ds->scal_copy, r, s, M, p, ds->partials, kMaxGrid, fin);
     TRON_HIP(hipGetLastError());
     return g;
 }
@@ -258,7 +285,7 @@ template <bool PRE>
 __global__ __launch_bounds__(kBlock) void k_trial_point(int64_t d, const double *__restrict__ w, const double *__restrict__ s,
                                                         const double *__restrict__ g, const double *__restrict__ r,
                                                         const double *__restrict__ M, double *__restrict__ wnew,
-                                                        double *__restrict__ partials, int stride)
+                                                        double *__restrict__ partials, int stride, Finish fin)
 {
     __shared__ double lds[kWavesPerBlock];
     double gs = 0.0, sr = 0.0, ss = 0.0;
@@ -275,15 +302,17 @@ __global__ __launch_bounds__(kBlock) void k_trial_point(int64_t d, const double 
     if (threadIdx.x == 0) partials[stride + blockIdx.x] = sr;
     ss = block_sum(ss, lds);
     if (threadIdx.x == 0) partials[2 * stride + blockIdx.x] = ss;
+    finish_partials<3>(fin, partials, stride, lds);
 }
 
 int trial_point(tron_dataset *ds, const double *w, const double *s, const double *g, const double *r, const double *M,
-                double *wnew)
+                double *wnew, int first)
 {
     ProfScope ps(ds, SLOT_CG_VEC);
     const int gr = vec_grid(ds->d);
-    if (M) hipLaunchKernelGGL(k_trial_point<true>, dim3(gr), dim3(kBlock), 0, ds->stream, ds->d, w, s, g, r, M, wnew, ds->partials, kMaxGrid);
-    else hipLaunchKernelGGL(k_trial_point<false>, dim3(gr), dim3(kBlock), 0, ds->stream, ds->d, w, s, g, r, M, wnew, ds->partials, kMaxGrid);
+    const Finish fin = finish_for(ds, first, gr);
+    if (M) hipLaunchKernelGGL(k_trial_point<true>, dim3(gr), dim3(kBlock), 0, ds->stream, ds->d, w, s, g, r, M, wnew, ds->partials, kMaxGrid, fin);
+    else hipLaunchKernelGGL(k_trial_point<false>, dim3(gr), dim3(kBlock), 0, ds->stream, ds->d, w, s, g, r, M, wnew, ds->partials, kMaxGrid, fin);
     TRON_HIP(hipGetLastError());
     return gr;
 }

@@ -13,10 +13,10 @@ namespace tron {
 int fun_eval(tron_dataset *ds, int loss, double C, const double *w, int Dslot, double *f_out)
 {
     // with unit plans zhat is stored already multiplied by the instances' values, as the transposed plan gathers it
-    const int gl = spmv_loss(ds, ds->fwd, SLOT_SPMV_FWD, loss, w, ds->z, ds->zhat, ds->Dbuf[Dslot], ds->bwd.col_scale);
+    const int gl = spmv_loss(ds, ds->fwd, SLOT_SPMV_FWD, loss, w, ds->z, ds->zhat, ds->Dbuf[Dslot], ds->bwd.col_scale, 0);
     TRON_TRY(gl);
     TRON_TRY(reduce_final(ds, 1, gl, 0, 0));
-    const int gw = dot_partials(ds, ds->d, w, w, nullptr, nullptr, nullptr, nullptr);
+    const int gw = dot_partials(ds, ds->d, w, w, nullptr, nullptr, nullptr, nullptr, 1);
     TRON_TRY(gw);
     TRON_TRY(reduce_final(ds, 1, gw, 0, 1));
     TRON_TRY(read_scalars(ds, 2));
@@ -27,7 +27,7 @@ int fun_eval(tron_dataset *ds, int loss, double C, const double *w, int Dslot, d
 // g = w + C X^T zhat (zhat from the preceding fun_eval) and |g|
 int grad_eval(tron_dataset *ds, double C, const double *w, double *g, double *gnorm_out)
 {
-    const int gg = spmv_axpy(ds, ds->bwd, SLOT_SPMV_BWD, ds->zhat, w, C, true, g, false, ds->bwd.col_scale != nullptr);
+    const int gg = spmv_axpy(ds, ds->bwd, SLOT_SPMV_BWD, ds->zhat, w, C, true, g, false, ds->bwd.col_scale != nullptr, 0);
     TRON_TRY(gg);
     TRON_TRY(reduce_final(ds, 1, gg, 0, 0));
     TRON_TRY(read_scalars(ds, 1));
@@ -41,7 +41,7 @@ int hv_enqueue(tron_dataset *ds, double C, const double *v, double *Hv)
     if (ds->dense) return dense_hv(ds, C, ds->Dcur, v, Hv);
     const double *D = ds->Dbuf[ds->Dcur];
     TRON_TRY(spmv_scale(ds, ds->fwd, SLOT_SPMV_FWD, v, D, ds->z, ds->bwd.col_scale));   // a1 = D (X v)
-    const int g = spmv_axpy(ds, ds->bwd, SLOT_SPMV_BWD, ds->z, v, C, false, Hv, false, ds->bwd.col_scale != nullptr);  // Hv = v + C X^T a1
+    const int g = spmv_axpy(ds, ds->bwd, SLOT_SPMV_BWD, ds->z, v, C, false, Hv, false, ds->bwd.col_scale != nullptr, 0);  // Hv = v + C X^T a1
     TRON_TRY(g);
     TRON_TRY(reduce_final(ds, 1, g, 0, 0));
     return TRON_OK;
@@ -101,11 +101,11 @@ int cg_solve(tron_dataset *ds, const tron_params &P, const double *M, double del
         TRON_TRY(hv_enqueue(ds, P.C, p, Hp));   // scalar 0 = p.Hp; scalars 1..3 = p.p, s.p, s.s of the direction update before
         const CgStepCtl ctl{rr, delta, it == 0 ? 1 : 0};
         ++it;
-        const int g1 = cg_step(ds, ctl, p, Hp, M, s, r);
+        const int g1 = cg_step(ds, ctl, p, Hp, M, s, r, 0);
         TRON_TRY(g1);
         TRON_TRY(reduce_final(ds, 1, g1, 0, 0));   // scalar 0 = the new r.r
         if (it < P.max_cg) {
-            const int g2 = cg_dir(ds, rr, r, s, M, p);
+            const int g2 = cg_dir(ds, rr, r, s, M, p, 1);
             TRON_TRY(g2);
             TRON_TRY(reduce_final(ds, 3, g2, kMaxGrid, 1));
         }
@@ -125,7 +125,7 @@ int build_preconditioner(tron_dataset *ds, const tron_params &P, int Dslot, cons
 {
     TRON_TRY(hess_diag_enqueue(ds, P.precond_blend * P.C, Dslot, M));   // 1 + blend C sum D x^2
     // g.(g / M) with the CG start-up kernel (s, r, p are scratch here: the inner solver initialises them again)
-    const int gr = cg_init(ds, g, M, ds->sv[V_S], ds->sv[V_R], ds->sv[V_P]);
+    const int gr = cg_init(ds, g, M, ds->sv[V_S], ds->sv[V_R], ds->sv[V_P], 0);
     TRON_TRY(gr);
     TRON_TRY(reduce_final(ds, 1, gr, 0, 0));
     TRON_TRY(read_scalars(ds, 1));
@@ -174,7 +174,7 @@ extern "C" int tron_solve(tron_dataset *ds, const tron_params *params, double *w
 
     // |grad f(0)|: the reference of the stopping test.  When w0 = 0 it is the first gradient itself.
     {
-        const int gz = dot_partials(ds, ds->d, w, w, nullptr, nullptr, nullptr, nullptr);
+        const int gz = dot_partials(ds, ds->d, w, w, nullptr, nullptr, nullptr, nullptr, 0);
         TRON_TRY(gz);
         TRON_TRY(reduce_final(ds, 1, gz, 0, 0));
         TRON_TRY(read_scalars(ds, 1));
@@ -212,7 +212,7 @@ extern "C" int tron_solve(tron_dataset *ds, const tron_params *params, double *w
         res->n_hv += ncg;
         res->cg_iters_total += ncg;
         // trial point and the model reduction  pred = -q(s) = -1/2 (g.s - s.r)
-        const int gt = trial_point(ds, w, s, g, r, M, wnew);
+        const int gt = trial_point(ds, w, s, g, r, M, wnew, 0);
         TRON_TRY(gt);
         TRON_TRY(reduce_final(ds, 3, gt, kMaxGrid, 0));
         TRON_TRY(read_scalars(ds, 3));

@@ -501,6 +501,34 @@ def test_solve_config2():
     assert res.cg_iters_total > 10
 
 
+@pytest.mark.parametrize("fuse", [0, 1])
+def test_reductions_finished_in_kernel_or_by_a_launch_agree_bit_for_bit(rng, fuse):
+    """The second stage of the reductions -- inside the producing kernel (last workgroup) or as a launch of its own -- adds
+    the same partial sums in the same order: identical scalars, identical trajectories."""
+    import paper_2008_03433_amd as tron
+    torch = torch_mod()
+    out = {}
+    for knob in (fuse, 1 - fuse):
+        tron.tron_tuning_set("fuse_reductions", knob)
+        try:
+            for p in (dg.config2(), dg.config4(n=50_000)):
+                tron.tron_tuning_set("dense_device_driver", 0)
+                ds = tron.Dataset.from_problem(p)
+                w = torch.zeros(p.d, dtype=torch.float64, device="cuda")
+                res = ds.solve(p.loss, p.C, 1e-4, w, precond_blend=0.01 if fuse else 0.0)
+                v = torch.ones(p.d, dtype=torch.float64, device="cuda"); Hv = torch.empty_like(v)
+                vHv = ds.hv(p.C, v, Hv)
+                f = ds.fun_grad(p.loss, p.C, w, Hv)
+                ds.close()
+                out.setdefault(p.name, []).append((res.f, res.gnorm, res.cg_iters_total, [t["f"] for t in res.trace], vHv, f,
+                                                   w.cpu().numpy().tobytes()))
+        finally:
+            tron.tron_tuning_set("fuse_reductions", -1)
+            tron.tron_tuning_set("dense_device_driver", -1)
+    for name, (a, b) in out.items():
+        assert a == b, name
+
+
 def test_solve_config2_svm_loss():
     # Off-config stress: H = I + X^T X has a well separated top eigenvalue (~2e3, the Zipf head feature), so CG
     # iterates are sensitive to rounding (plain-fp64 numpy CG departs from the long-double oracle by ~4e-7 in s
