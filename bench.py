@@ -547,6 +547,19 @@ def cross_validation(X, y, label: str, folds: int = 3, Cs=(0.1, 1.0), eps: float
     fg_pass_ms = prof_fg["batch_pass"]["ms"] / prof_fg["batch_pass"]["calls"]
     advance_ms = prof_hv["batch_advance"]["ms"] / prof_hv["batch_advance"]["calls"]
     batch_f = [r.f for r in res]
+    # the same rounds for the logistic loss (fp64 D per row and problem instead of one bit; the function/gradient round
+    # evaluates exp / log1p per row and problem)
+    b.fun_grad(dg.LOSS_LR, C_list, W, None)
+    tron.tron_profile_enable(ds.handle, True)
+    for _ in range(10):
+        b.hv(C_list, V, HV, want_vHv=False)
+    lr_hv = tron.tron_profile_read(ds.handle)
+    for _ in range(5):
+        b.fun_grad(dg.LOSS_LR, C_list, W, None)
+    lr_fg = tron.tron_profile_read(ds.handle)
+    tron.tron_profile_enable(ds.handle, False)
+    lr_hv_pass_ms = lr_hv["batch_pass"]["ms"] / lr_hv["batch_pass"]["calls"]
+    lr_fg_pass_ms = lr_fg["batch_pass"]["ms"] / lr_fg["batch_pass"]["calls"]
     b.close()
     ds.close()
     # one problem at a time on compacted copies
@@ -580,7 +593,8 @@ def cross_validation(X, y, label: str, folds: int = 3, Cs=(0.1, 1.0), eps: float
     agree = max(abs(batch_f[k] - fk) / abs(fk) for k, fk in seq_f)
     return {"workload": label, "n": n, "d": d, "folds": folds, "C": list(Cs), "problems": K, "loss": "l2svm", "eps": eps,
             "batched": {"solve_ms": best * 1e3, "rounds": rounds, "hv_pass_ms": hv_pass_ms, "fun_grad_pass_ms": fg_pass_ms,
-                        "advance_ms": advance_ms, "hv_per_second_all_problems": K / ((hv_pass_ms + advance_ms) * 1e-3),
+                        "advance_ms": advance_ms, "logistic_hv_pass_ms": lr_hv_pass_ms, "logistic_fun_grad_pass_ms": lr_fg_pass_ms,
+                        "hv_per_second_all_problems": K / ((hv_pass_ms + advance_ms) * 1e-3),
                         "X_read_GB/s": 8.0 * n * d / (hv_pass_ms * 1e-3) / 1e9,
                         "outer_iters": [r.outer_iters for r in res], "cg_iters": [r.cg_iters_total for r in res],
                         "converged": all(r.converged for r in res)},

@@ -229,7 +229,7 @@ TRON_API int tron_solve(tron_dataset *ds, const tron_params *params, double *w_d
  * CG, the function/gradient pass for those at a trial point -- so X is read once per round, not once
  * per problem.  Problem k is exactly the problem of Section 3 over the instances {i : bit k of
  * member[i] is set}: the rows outside it contribute nothing to f, g or Hv.
- * Dense handles with d <= TRON_BATCH_MAX_D only.
+ * Dense handles with d <= TRON_BATCH_MAX_D only (sparse handles and wider matrices: one tron_solve per problem).
  * ------------------------------------------------------------------------------------------ */
 typedef struct tron_batch tron_batch; /* opaque: membership bits, per-problem D, solver state, work space */
 
@@ -264,8 +264,10 @@ TRON_API int tron_batch_hv(tron_batch *b, const double *C_host, const double *V_
 
 /*
  * tron_solve for every problem, in lock-step rounds of one pass over X each.  params: loss, eps,
- * max_outer, max_cg, cg_xi apply to every problem; params->C is ignored (C_host[k] is problem k's C);
- * params->precond_blend must be 0.  W_dev: K*d doubles, in: starting points, out: final iterates.
+ * max_outer, max_cg, cg_xi, precond_blend apply to every problem; params->C is ignored (C_host[k] is problem k's C).
+ * With precond_blend > 0 every problem runs the preconditioned inner solver described for tron_solve; the Hessian
+ * diagonal of a problem's new iterate takes one more pass over X (a round of its own, shared with whatever the other
+ * problems have pending).  W_dev: K*d doubles, in: starting points, out: final iterates.
  * res_host: K results, each with its own trace / trace_cap set before the call.  Every problem follows
  * the rules stated for tron_solve; the whole trust-region and CG logic runs on the device (the vectors
  * have d <= 32 entries), the host only learns which problems are still running.

@@ -264,10 +264,10 @@ def tron_batch_hv(b, C, V, HV, want_vHv=True) -> Optional[List[float]]:
     return list(s) if want_vHv else None
 
 
-def tron_batch_solve(b, loss, C, eps, W, max_outer=1000, max_cg=1000, cg_xi=0.1, trace_cap=1024) -> List[SolveResult]:
+def tron_batch_solve(b, loss, C, eps, W, max_outer=1000, max_cg=1000, cg_xi=0.1, trace_cap=1024, precond_blend=0.0) -> List[SolveResult]:
     """Solves the K problems in place on the CUDA tensor W (K*d doubles); one SolveResult per problem."""
     K = len(C)
-    params = _Params(loss, 0.0, eps, max_outer, max_cg, cg_xi, 0.0)
+    params = _Params(loss, 0.0, eps, max_outer, max_cg, cg_xi, precond_blend)
     traces = [(TraceRec * max(trace_cap, 1))() for _ in range(K)]
     res = (_Result * K)()
     for k in range(K):

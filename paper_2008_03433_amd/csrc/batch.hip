@@ -23,8 +23,8 @@ constexpr int kBatchMax = TRON_BATCH_MAX;
 constexpr int kVecPad = TRON_BATCH_MAX_D;   // doubles per stored vector
 static_assert(kVecPad <= kWave, "one lane per vector entry");
 
-enum { MODE_IDLE = 0, MODE_HV = 1, MODE_FG = 2 };
-enum { PH_DONE = 0, PH_ONESHOT, PH_REF, PH_START, PH_CG, PH_TRIAL };
+enum { MODE_IDLE = 0, MODE_HV = 1, MODE_FG = 2, MODE_DIAG = 3 };   // MODE_DIAG: column sums of D_i x_ij^2 (the Hessian diagonal)
+enum { PH_DONE = 0, PH_ONESHOT, PH_REF, PH_START, PH_CG, PH_TRIAL, PH_DIAG0, PH_DIAG };
 enum { BEGIN_SOLVE = 0, BEGIN_FG, BEGIN_HV };
 
 // request of the next pass: written by the begin / advance kernels, read by the pass
@@ -37,17 +37,20 @@ struct BatchCtl {
 struct ProbScalars {
     int32_t phase, status, converged, outer, cg_total, n_fun, n_grad, n_hv, cg_it, onb, dcur, trace_len;
     double C, f, gnorm, gnorm0, delta, rr, pred, snorm, out_scal;
+    double gscaled;   // what the inner solver measures its residual against: |g|, or sqrt(g.M^-1 g) with a preconditioner
 };
 
 // solver state of one problem (device memory)
 struct ProbState {
     ProbScalars sc;
     double w[kVecPad], wnew[kVecPad], g[kVecPad], s[kVecPad], r[kVecPad], p[kVecPad], out[kVecPad];
+    double M[kVecPad];   // diagonal preconditioner (1 - a) I + a diag(H) of the current iterate (used when blend > 0)
 };
 
 struct SolveParams {
     int loss, max_outer, max_cg, trace_cap;
     double eps, xi;
+    double blend;   // 0: plain CG; a in (0, 1]: CG preconditioned by M = (1 - a) I + a diag(H), rebuilt at every accepted iterate
 };
 
 struct BatchC { double v[kBatchMax]; };
@@ -111,7 +114,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass(int64_t n, int64_t d, 
     ConstWords words[KT];
 #pragma unroll
     for (int k = 0; k < KT; ++k) {
-        if (mode[k] == MODE_HV && svm) words[k] = (ConstWords)(Dbits_in + ((int64_t)k * 2 + dslot[k]) * ntiles);
+        if ((mode[k] == MODE_HV || mode[k] == MODE_DIAG) && svm) words[k] = (ConstWords)(Dbits_in + ((int64_t)k * 2 + dslot[k]) * ntiles);
         else words[k] = (ConstWords)(member + (int64_t)k * ntiles);
     }
     double acc[KT][E];
@@ -151,7 +154,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass(int64_t n, int64_t d, 
 #pragma unroll
                 for (int k = 0; k < KT; ++k) {
                     Drow[k] = 0.0;
-                    if (mode[k] == MODE_HV && wk[k] != 0 && row0 + lane < n)
+                    if ((mode[k] == MODE_HV || mode[k] == MODE_DIAG) && wk[k] != 0 && row0 + lane < n)
                         Drow[k] = Dval[((int64_t)k * 2 + dslot[k]) * n + row0 + lane];   // zero outside the problem's rows
                 }
             }
@@ -163,6 +166,27 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass(int64_t n, int64_t d, 
             for (int k = 0; k < KT; ++k) {
                 if (mode[k] == MODE_IDLE || wk[k] == 0) continue;   // uniform
                 double vk[E], t[U], c[U];
+                if (mode[k] == MODE_DIAG) {
+                    // sum_i D_i x_ij^2: the row coefficient is D itself, the entries are squared
+                    if (svm) {
+                        const uint32_t lo = (uint32_t)wk[k], hi = (uint32_t)(wk[k] >> 32);
+#pragma unroll
+                        for (int u = 0; u < U; ++u) {
+                            uint32_t half;
+                            if (T::RW == kWave) half = (lane < 32) ? lo : hi;
+                            else half = (u * T::RW < 32) ? lo : hi;
+                            c[u] = (half & rowbit[u]) ? 2.0 : 0.0;
+                        }
+                    } else {
+                        T::from_row_owner(Drow[k], lane, c);
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+#pragma unroll
+                        for (int e = 0; e < E; ++e) acc[k][e] = fma(c[u] * x[u][e], x[u][e], acc[k][e]);
+                    }
+                    continue;
+                }
 #pragma unroll
                 for (int e = 0; e < E; ++e) vk[e] = lvec[k][qoff + e];
                 T::row_dots(x, vk, t);
@@ -255,29 +279,31 @@ struct Request {
     double vec;   // this lane's entry of the vector
 };
 
-// Start of the truncated CG iteration at the current iterate: s = 0, r = p = -g; the first product is H p.
-__device__ __forceinline__ Request cg_begin(ProbState &S, ProbScalars &sc, int j, bool in, double g)
+// Start of the truncated CG iteration at the current iterate: s = 0, r = -g, p = r (preconditioned: p = r / M, and the
+// residual is measured by r.M^-1 r); the first product is H p.  m: this lane's entry of M, 1 without a preconditioner.
+__device__ __forceinline__ Request cg_begin(ProbState &S, ProbScalars &sc, int j, bool in, double g, double m)
 {
+    const double p0 = -g / m;
     if (in) {
         S.s[j] = 0.0;
         S.r[j] = -g;
-        S.p[j] = -g;
+        S.p[j] = p0;
     }
-    sc.rr = sc.gnorm * sc.gnorm;
+    sc.rr = sc.gscaled * sc.gscaled;
     sc.cg_it = 0;
     sc.onb = 0;
     sc.phase = PH_CG;
-    return Request{MODE_HV, sc.dcur, -g};
+    return Request{MODE_HV, sc.dcur, p0};
 }
 
 // End of the inner iteration: trial point w + s and the model's reduction pred = -q(s) = -1/2 (g.s - s.r);
 // the next pass evaluates f and the gradient there, D going to the problem's other buffer.
-__device__ __forceinline__ Request cg_end(ProbState &S, ProbScalars &sc, int j, bool in, double s, double r)
+__device__ __forceinline__ Request cg_end(ProbState &S, ProbScalars &sc, int j, bool in, double s, double r, double m)
 {
     const double w = in ? S.w[j] : 0.0, g = in ? S.g[j] : 0.0;
     const double wnew = w + s;
     const double gs = dot64(g, s), sr = dot64(s, r);
-    sc.snorm = sqrt(dot64(s, s));
+    sc.snorm = sqrt(dot64(m * s, s));   // the length the radius rules use: the M-norm of the iteration
     sc.pred = -0.5 * (gs - sr);
     if (in) S.wnew[j] = wnew;
     sc.phase = PH_TRIAL;
@@ -324,8 +350,19 @@ __global__ __launch_bounds__(kAdvanceBlock) void k_batch_advance(int64_t d, int 
     const double o = in ? fma(C, cs[j], u) : 0.0;   // entry j of  v + C X^T(D(Xv))  or of  w + C X^T zhat
     Request next{MODE_IDLE, sc.dcur, 0.0};
     const double eta0 = 1e-4, eta1 = 0.25, eta2 = 0.75, sig2 = 0.5, sig3 = 4.0;
+    const bool precond = P.blend > 0.0;
+    // this lane's entry of the preconditioner; 1 without one (and past d), which leaves every product below unchanged
+    double m = (precond && in && sc.phase != PH_ONESHOT) ? S.M[j] : 1.0;
 
-    if (mode == MODE_HV) {
+    if (mode == MODE_DIAG) {
+        // cs[j] = sum_i D_i x_ij^2 at the current iterate: M = (1 - a) + a (1 + C cs) = 1 + a C cs, then the inner solve starts
+        m = in ? fma(P.blend * C, cs[j], 1.0) : 1.0;
+        if (in) S.M[j] = m;
+        const double g = in ? S.g[j] : 0.0;
+        sc.gscaled = sqrt(dot64(g, g / m));
+        if (sc.phase == PH_DIAG0) sc.delta = sc.gscaled;   // Delta_0 = sqrt(g.M^-1 g)
+        next = cg_begin(S, sc, j, in, g, m);
+    } else if (mode == MODE_HV) {
         const double pHp = dot64(u, o);
         if (sc.phase == PH_ONESHOT) {
             if (in) S.out[j] = o;
@@ -337,7 +374,7 @@ __global__ __launch_bounds__(kAdvanceBlock) void k_batch_advance(int64_t d, int 
             sc.n_hv += 1;
             sc.cg_total += 1;
             const double alpha = sc.rr / pHp;
-            const double pp = dot64(u, u), sp = dot64(s, u), ss = dot64(s, s);
+            const double pp = dot64(m * u, u), sp = dot64(m * s, u), ss = dot64(m * s, s);
             bool end = false;
             if (sqrt(ss + alpha * (2.0 * sp + alpha * pp)) >= sc.delta) {
                 // to the boundary along p
@@ -351,13 +388,14 @@ __global__ __launch_bounds__(kAdvanceBlock) void k_batch_advance(int64_t d, int 
             } else {
                 s = fma(alpha, u, s);
                 r = fma(-alpha, o, r);
-                const double rr_new = dot64(r, r);
+                const double zr = r / m;
+                const double rr_new = dot64(r, zr);
                 const double beta = rr_new / sc.rr;
                 sc.rr = rr_new;
-                if (sqrt(rr_new) <= P.xi * sc.gnorm || sc.cg_it >= P.max_cg) {
+                if (sqrt(rr_new) <= P.xi * sc.gscaled || sc.cg_it >= P.max_cg) {
                     end = true;
                 } else {
-                    const double p = fma(beta, u, r);
+                    const double p = fma(beta, u, zr);
                     if (in) S.p[j] = p;
                     next = Request{MODE_HV, sc.dcur, p};
                 }
@@ -366,7 +404,7 @@ __global__ __launch_bounds__(kAdvanceBlock) void k_batch_advance(int64_t d, int 
                 S.s[j] = s;
                 S.r[j] = r;
             }
-            if (end) next = cg_end(S, sc, j, in, s, r);
+            if (end) next = cg_end(S, sc, j, in, s, r, m);
         }
     } else {   // MODE_FG: u is the point, o the gradient there
         const double f = 0.5 * dot64(u, u) + C * cs[d];
@@ -390,8 +428,12 @@ __global__ __launch_bounds__(kAdvanceBlock) void k_batch_advance(int64_t d, int 
             sc.n_grad += 1;
             if (sc.gnorm0 == 0.0) sc.gnorm0 = gn;
             sc.delta = gn;
+            sc.gscaled = gn;
             if (gn <= P.eps * sc.gnorm0) finish(sc, TRON_OK);
-            else next = cg_begin(S, sc, j, in, o);
+            else if (precond) {   // the Hessian diagonal at this iterate first
+                sc.phase = PH_DIAG0;
+                next = Request{MODE_DIAG, sc.dcur, 0.0};
+            } else next = cg_begin(S, sc, j, in, o, 1.0);
         } else {   // PH_TRIAL
             sc.n_fun += 1;
             const double ared = sc.f - f;
@@ -412,6 +454,7 @@ __global__ __launch_bounds__(kAdvanceBlock) void k_batch_advance(int64_t d, int 
                 sc.dcur = 1 - sc.dcur;   // the Hessian now uses D at the accepted point
                 sc.f = f;
                 sc.gnorm = gn;
+                sc.gscaled = gn;
                 sc.n_grad += 1;
             }
             sc.outer += 1;
@@ -426,7 +469,10 @@ __global__ __launch_bounds__(kAdvanceBlock) void k_batch_advance(int64_t d, int 
             if (accepted && sc.gnorm <= P.eps * sc.gnorm0) finish(sc, TRON_OK);
             else if (sc.pred <= 0.0 || (noise && sc.gnorm >= gnorm_before)) finish(sc, TRON_EMAXITER);
             else if (sc.outer >= P.max_outer) finish(sc, TRON_EMAXITER);
-            else next = cg_begin(S, sc, j, in, g);
+            else if (precond && accepted) {   // the iterate moved: its Hessian diagonal, then the inner solve
+                sc.phase = PH_DIAG;
+                next = Request{MODE_DIAG, sc.dcur, 0.0};
+            } else next = cg_begin(S, sc, j, in, g, m);   // after a rejected step M and sqrt(g.M^-1 g) still hold
         }
     }
     if (lane < kVecPad) ctl->vec[k][lane] = in ? next.vec : 0.0;
@@ -454,7 +500,7 @@ __global__ __launch_bounds__(kWave) void k_batch_begin(int what, int64_t d, cons
         sc.status = TRON_EMAXITER;
         sc.converged = sc.outer = sc.cg_total = sc.n_fun = sc.n_grad = sc.n_hv = sc.cg_it = sc.onb = sc.trace_len = 0;
         sc.dcur = 0;
-        sc.f = sc.gnorm = sc.gnorm0 = sc.delta = sc.rr = sc.pred = sc.snorm = sc.out_scal = 0.0;
+        sc.f = sc.gnorm = sc.gnorm0 = sc.delta = sc.rr = sc.pred = sc.snorm = sc.out_scal = sc.gscaled = 0.0;
         if (in) S.w[lane] = x;
         const bool nonzero = __ballot(x != 0.0) != 0;
         sc.phase = nonzero ? PH_REF : PH_START;
@@ -749,9 +795,9 @@ extern "C" int tron_batch_solve(tron_batch *b, const tron_params *params, const 
     if (!b || !params || !C_host || !W_dev || !res) { set_error("tron_batch_solve: null argument"); return TRON_EINVAL; }
     const tron_params &Q = *params;
     if ((Q.loss != TRON_LOSS_LR && Q.loss != TRON_LOSS_L2SVM) || bad_C(b, C_host) || !(Q.eps > 0.0) || Q.max_outer < 1 ||
-        Q.max_cg < 1 || !(Q.cg_xi > 0.0) || !(Q.cg_xi < 1.0) || Q.precond_blend != 0.0) {
+        Q.max_cg < 1 || !(Q.cg_xi > 0.0) || !(Q.cg_xi < 1.0) || !(Q.precond_blend >= 0.0) || !(Q.precond_blend <= 1.0)) {
         set_error("tron_batch_solve: bad parameter (loss, every C > 0, eps > 0, max_outer >= 1, max_cg >= 1, 0 < cg_xi < 1, "
-                  "precond_blend = 0)");
+                  "0 <= precond_blend <= 1)");
         return TRON_EINVAL;
     }
     int cap = 0;
@@ -768,12 +814,12 @@ extern "C" int tron_batch_solve(tron_batch *b, const tron_params *params, const 
         TRON_HIP(hipMalloc(reinterpret_cast<void **>(&b->trace), sizeof(tron_trace_rec) * (size_t)b->K * (size_t)cap));
         b->trace_cap = cap;
     }
-    SolveParams P{Q.loss, Q.max_outer, Q.max_cg, cap, Q.eps, Q.cg_xi};
+    SolveParams P{Q.loss, Q.max_outer, Q.max_cg, cap, Q.eps, Q.cg_xi, Q.precond_blend};
     b->D_loss = -1;
     TRON_TRY(launch_begin(b, BEGIN_SOLVE, W_dev, C_host));
-    // A problem needs at most 2 + max_outer (max_cg + 1) rounds.  The host looks at the modes every `poll` rounds; a
+    // A problem needs at most 3 + max_outer (max_cg + 2) rounds (one more per iterate with a preconditioner).  The host looks at the modes every `poll` rounds; a
     // pass that finds every problem idle returns at once.
-    const int64_t round_cap = 2 + (int64_t)Q.max_outer * ((int64_t)Q.max_cg + 1);
+    const int64_t round_cap = 3 + (int64_t)Q.max_outer * ((int64_t)Q.max_cg + 2);
     const double pass_bytes = (double)ds->n * (double)ds->d * 8.0;
     const int poll = pass_bytes < 4e8 ? 4 : 1;
     bool live = true;

@@ -166,6 +166,42 @@ def test_batch_solve_matches_the_oracle(rng, loss, n, d, K):
     _compare_batch_solve(rng, X, y, member, K, loss, Cs, 1e-6)
 
 
+@pytest.mark.parametrize("loss", [LOSS_LR, LOSS_L2SVM])
+@pytest.mark.parametrize("blend", [0.01, 1.0])
+def test_batch_solve_with_the_diagonal_preconditioner(rng, loss, blend):
+    """Every problem preconditioned by M = (1 - a) I + a diag(H) of its own rows and iterate: same trajectories as the
+    oracle's preconditioned solve of each fold.  Columns on very different scales make the diagonal matter."""
+    n, d, K = 9000, 20, 5
+    X, y = _dense(rng, n, d)
+    X = X * np.logspace(-0.7, 0.7, d)[None, :]
+    member = _cv_members(rng, n, K)
+    Cs = [0.05, 0.5, 0.05, 0.5, 5.0]
+    res = _compare_batch_solve(rng, X, y, member, K, loss, Cs, 1e-4, precond_blend=blend)
+    assert all(r.converged for r in res)
+    # the preconditioner is worth having on this matrix: fewer Hessian-vector products in total than plain CG takes
+    # (plain CG on these badly scaled columns is sensitive to rounding, so its trajectory is not compared step by step)
+    torch = torch_mod()
+    ds = tron.Dataset.from_dense(X, y)
+    b = tron.Batch(ds, K, member)
+    plain = b.solve(loss, Cs, 1e-4, torch.zeros((K, d), dtype=torch.float64, device="cuda"))
+    b.close()
+    ds.close()
+    assert all(r.converged for r in plain)
+    assert sum(r.n_hv for r in res) < sum(r.n_hv for r in plain)
+
+
+def test_batch_solve_preconditioned_from_a_far_start(rng):
+    """Rejected steps and boundary exits with the M-norm trust region, several problems at once."""
+    n, d, K = 2000, 16, 3
+    X = 3.0 * rng.standard_normal((n, d)) * (rng.random((n, d)) < 0.3)
+    y = np.where(rng.random(n) < 0.5, 1.0, -1.0)
+    member = _cv_members(rng, n, K)
+    W0 = 3.0 * rng.standard_normal((K, d))
+    res = _compare_batch_solve(rng, X, y, member, K, LOSS_LR, [50.0, 20.0, 50.0], 1e-4, W0=W0, precond_blend=0.01)
+    assert sum(1 - t["accepted"] for r in res for t in r.trace) >= 3
+    assert sum(t["on_boundary"] for r in res for t in r.trace) >= 3
+
+
 def test_batch_solve_problems_finish_at_different_rounds(rng):
     """Very different C: some problems stop after one or two outer iterations while others keep running."""
     n, d, K = 8000, 24, 4
