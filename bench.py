@@ -152,13 +152,27 @@ def measured_traffic(profile_key, slot: str):
     if not os.path.exists(path):
         return None
     in_traffic = False
+    column = None   # index of the "traffic GB" cell (older summaries: fetched + written)
     for line in open(path):
         if line.startswith("## "):
             in_traffic = "traffic" in line
-        if in_traffic and line.startswith(f"| `{kname}` |"):
-            cells = [c.strip() for c in line.strip().strip("|").split("|")]
+            column = None
+        if not in_traffic or not line.startswith("|"):
+            continue
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if cells and cells[0] == "kernel":
+            column = cells.index("traffic GB") if "traffic GB" in cells else None
+            fetched = cells.index("fetched GB") if "fetched GB" in cells else (cells.index("fetched GB (scaled)") if "fetched GB (scaled)" in cells else None)
+            written = cells.index("written GB") if "written GB" in cells else (cells.index("written GB (scaled)") if "written GB (scaled)" in cells else None)
+            continue
+        if cells and cells[0] == f"`{kname}`":
             try:
-                total = (float(cells[2]) + float(cells[4])) * 1e9
+                if column is not None:
+                    total = float(cells[column]) * 1e9
+                elif fetched is not None and written is not None:
+                    total = (float(cells[fetched]) + float(cells[written])) * 1e9
+                else:
+                    return None
             except (ValueError, IndexError):
                 return None
             return total if total > 0.0 else None    # a row of zeros: the kernel was not in that profile
