@@ -597,6 +597,10 @@ int tron_tuning_set(const char *name, int64_t value)
         g_tuning.batch_grid = value;
         return TRON_OK;
     }
+    if (name && strcmp(name, "batch_mfma") == 0 && value >= -1 && value <= 1) {
+        g_tuning.batch_mfma = value;
+        return TRON_OK;
+    }
     set_error("tron_tuning_set: unknown knob or value out of range");
     return TRON_EINVAL;
 }

@@ -250,6 +250,319 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass(int64_t n, int64_t d, 
     }
 }
 
+// ------------------------------------------------------------------ the pass over X on the matrix units
+// With several problems the pass is two skinny matrix products per tile of 64 rows: Z = X V (64 x d by d x K) and
+// G += X^T C (d x 64 by 64 x K), C = the row coefficients formed from Z.  This kernel runs them as fp64 matrix
+// instructions (16 x 16 x 4: A 16 x 4, B 4 x 16, result 16 x 16; lane l holds A[l % 16][l / 16], B[l / 16][l % 16] and, in
+// its result register v, the element [4 v + l / 16][l % 16]) with the problems as the 16 result columns:
+//   * a wavefront copies its tile of X into LDS exactly as it lies in memory (16-byte pieces, the loads of the next tile
+//     in flight during the work on the current one; rows that concern no problem are not read);
+//   * Z: per 16 rows and 4 columns of X one instruction, A read from LDS, B = V kept in registers;
+//   * lane (g = l / 16, p = l % 16) then holds Z of problem p at rows 4 v + g of every 16-row group.  Hessian rounds form
+//     C in place: the L2-SVM selects by the bit of the active-set word (factor 2 folded into V), the logistic loss
+//     multiplies by D, staged through LDS from a coalesced load.  Function/gradient rounds pass Z through LDS to the
+//     row-per-lane layout, where the per-row terms run once per row and problem, lane i owning row i (loss sums, new D
+//     or active-set words exactly as in k_batch_pass), and take zhat back the same way;
+//   * G: the result rows are the columns of X (two instructions for d > 16); the four rows 4 v + g, g = 0..3, that the
+//     lanes hold in register v are the summation index, so C is used where it lies.  A = X[row][column] read from LDS
+//     along a row: conflict-free.  Problems asking for the Hessian diagonal use the same instructions with A squared and
+//     C = D.
+// Results go to the same partials array, in the same layout, as k_batch_pass writes: the steps after the pass do not
+// know which kernel ran.  Sums are formed in a fixed order (the instruction's, then tiles in order, wavefronts 0..3).
+typedef double mfma4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ void wave_lds_fence()
+{
+    // LDS operations of one wavefront complete in the order issued; this keeps the compiler from reordering them
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+// the 64-bit value of lane `src` (per-lane index)
+__device__ __forceinline__ uint64_t lane_value(uint64_t v, int src)
+{
+    const int lo = __builtin_amdgcn_ds_bpermute(src * 4, (int)(uint32_t)v);
+    const int hi = __builtin_amdgcn_ds_bpermute(src * 4, (int)(uint32_t)(v >> 32));
+    return ((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo;
+}
+
+constexpr int kExRow = kWave + 1;   // doubles per problem in the exchange area (padded against bank conflicts)
+__host__ __device__ constexpr int mfma_wave_doubles(int d, int KT) { return kWave * d + 4 + KT * kExRow + ((KT * kExRow) & 1); }
+
+template <bool VEC, int DMAX, int KT, int LOSS>
+__global__ __launch_bounds__(kBlock, 2) void k_batch_pass_mfma(int64_t n, int64_t d, const double *__restrict__ X,
+                                                            const int8_t *__restrict__ y,
+                                                            const BatchCtl *__restrict__ ctl, const uint64_t *__restrict__ member,
+                                                            const uint64_t *__restrict__ Dbits_in, uint64_t *Dbits_out,
+                                                            double *Dval, int64_t ntiles, double *__restrict__ partials)
+{
+    static_assert(KT <= 16 && KT <= kBatchMax, "one result column per problem");
+    constexpr bool svm = LOSS == TRON_LOSS_L2SVM;
+    static_assert(DMAX % 4 == 0 && DMAX <= kVecPad, "d <= DMAX, in steps of the instruction's four columns");
+    constexpr int PW = VEC ? 2 : 1;                 // doubles per piece
+    constexpr int NP = DMAX / PW;                   // pieces per lane and tile at most (a tile is 64 d doubles)
+    constexpr int SL = kWave / KT;                  // tiles whose new active-set words a lane group holds before they are stored
+    extern __shared__ double dyn[];
+    __shared__ double lds_red[kWavesPerBlock];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int D = (int)d;
+    int mode[KT], dslot[KT];
+    bool any = false, any_fg = false, any_hv = false, any_diag = false, any_mul = false, any_exd = false;
+#pragma unroll
+    for (int k = 0; k < KT; ++k) {
+        mode[k] = ctl->mode[k];
+        dslot[k] = ctl->dslot[k];
+        any |= mode[k] != MODE_IDLE;
+        any_fg |= mode[k] == MODE_FG;
+        any_hv |= mode[k] == MODE_HV;
+        any_diag |= mode[k] == MODE_DIAG;
+        any_mul |= mode[k] == MODE_FG || mode[k] == MODE_HV;
+        any_exd |= !svm && (mode[k] == MODE_HV || mode[k] == MODE_DIAG);
+    }
+    if (!any) return;
+    const int xs_len = kWave * D + 4;
+    double *Xs = dyn + (size_t)wv * mfma_wave_doubles(D, KT);   // the tile as it lies in memory, 4 doubles of slack
+    double *Ex = Xs + xs_len;                                    // [problem][row] exchange area
+    for (int i = lane; i < mfma_wave_doubles(D, KT); i += kWave) Xs[i] = 0.0;
+    // this lane in the matrix layouts: g = summation index / row block, p = problem (result column) or row / column of X
+    const int p = lane & 15, g = lane >> 4;
+    const bool pk = p < KT;
+    const int modeM = pk ? ctl->mode[pk ? p : 0] : MODE_IDLE;
+    const bool exM = modeM == MODE_FG || (!svm && (modeM == MODE_HV || modeM == MODE_DIAG));   // C comes out of the exchange area
+    const int KD = (D + 3) / 4;
+    double Vop[DMAX / 4];
+#pragma unroll
+    for (int kk = 0; kk < DMAX / 4; ++kk) {
+        const int f = 4 * kk + g;
+        const bool use = f < D && (modeM == MODE_HV || modeM == MODE_FG);
+        const double scale = (svm && modeM == MODE_HV) ? 2.0 : 1.0;
+        Vop[kk] = use ? scale * ctl->vec[pk ? p : 0][f] : 0.0;
+    }
+    // lane k < KT fetches the word of problem k: its active set (L2-SVM Hessian / diagonal) or its members
+    const uint64_t *plane = nullptr;
+    if (lane < KT) {
+        const int m = ctl->mode[lane < KT ? lane : 0];
+        if ((m == MODE_HV || m == MODE_DIAG) && svm) plane = Dbits_in + ((int64_t)lane * 2 + ctl->dslot[lane < KT ? lane : 0]) * ntiles;
+        else if (m != MODE_IDLE) plane = member + (int64_t)lane * ntiles;
+    }
+    const int64_t nwaves = (int64_t)gridDim.x * kWavesPerBlock;
+    const int64_t wave_id = (int64_t)blockIdx.x * kWavesPerBlock + wv;
+    const int64_t per_wave = (ntiles + nwaves - 1) / nwaves;
+    const int64_t first = wave_id * per_wave;
+    const int64_t last = (first + per_wave < ntiles) ? first + per_wave : ntiles;
+    const int np = D / PW;                                   // pieces per lane: 64 d / PW pieces over 64 lanes
+    const uint64_t inv_d = (0x100000000ull + (uint64_t)D - 1) / (uint64_t)D;   // row of element e < 2048: (e inv_d) >> 32 (2^32 itself for d = 1)
+
+    double xr[NP][PW];
+    double loss[KT];
+    uint64_t held = 0;   // lane SL k + j: the new active-set word of problem k for the j-th tile since the last store
+#pragma unroll
+    for (int k = 0; k < KT; ++k) loss[k] = 0.0;
+    mfma4 G1 = {0.0, 0.0, 0.0, 0.0}, G2 = {0.0, 0.0, 0.0, 0.0};
+
+    // loads of a tile into xr (rows outside `rows` or past n are left out: their registers are not written to LDS either)
+    auto fetch = [&](int64_t tile, uint64_t rows) {
+        const int64_t row0 = tile * kWave;
+        const double *base = X + row0 * d;
+#pragma unroll
+        for (int it = 0; it < NP; ++it) {
+            if (it < np) {
+                const uint32_t e = (uint32_t)(it * kWave + lane) * PW;
+                const uint32_t row = (uint32_t)(((uint64_t)e * inv_d) >> 32);
+                const bool take = ((rows >> row) & 1u) && row0 + row < n;
+                if constexpr (VEC) {
+                    double2 t = make_double2(0.0, 0.0);
+                    if (take) t = *reinterpret_cast<const double2 *>(base + e);
+                    xr[it][0] = t.x;
+                    xr[it][1] = t.y;
+                } else {
+                    xr[it][0] = take ? base[e] : 0.0;
+                }
+            }
+        }
+    };
+    auto to_lds = [&](int64_t tile, uint64_t rows) {
+        const int64_t row0 = tile * kWave;
+#pragma unroll
+        for (int it = 0; it < NP; ++it) {
+            if (it < np) {
+                const uint32_t e = (uint32_t)(it * kWave + lane) * PW;
+                const uint32_t row = (uint32_t)(((uint64_t)e * inv_d) >> 32);
+                const bool take = ((rows >> row) & 1u) && row0 + row < n;
+                if (take) {
+                    if constexpr (VEC) *reinterpret_cast<double2 *>(Xs + e) = make_double2(xr[it][0], xr[it][1]);
+                    else Xs[e] = xr[it][0];
+                }
+            }
+        }
+    };
+
+    // words of the current tile (w0), the next (w1) and the one after (loaded in the loop); their scalar copies
+    uint64_t w0 = 0, w1 = 0;
+    if (plane && first < last) w0 = plane[first];
+    if (plane && first + 1 < last) w1 = plane[first + 1];
+    uint64_t wk[KT], rows_cur = 0;
+#pragma unroll
+    for (int k = 0; k < KT; ++k) {
+        wk[k] = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(w0 >> 32), k) << 32) | (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)w0, k);
+        rows_cur |= wk[k];
+    }
+    double ycur = 1.0;
+    if (first < last && rows_cur != 0) {
+        fetch(first, rows_cur);
+        if (any_fg && first * kWave + lane < n) ycur = (double)y[first * kWave + lane];
+    }
+    int it_tile = 0;
+    for (int64_t tile = first; tile < last; ++tile, ++it_tile) {
+        const int slotl = it_tile & (SL - 1);
+        const int64_t row0 = tile * kWave;
+        const uint64_t w2 = (plane && tile + 2 < last) ? plane[tile + 2] : 0;
+        uint64_t wkn[KT], rows_next = 0;
+#pragma unroll
+        for (int k = 0; k < KT; ++k) {
+            wkn[k] = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(w1 >> 32), k) << 32) | (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)w1, k);
+            rows_next |= wkn[k];
+        }
+        if (rows_cur != 0) to_lds(tile, rows_cur);
+        double ynext = 1.0;
+        if (tile + 1 < last && rows_next != 0) {
+            fetch(tile + 1, rows_next);
+            if (any_fg && row0 + kWave + lane < n) ynext = (double)y[row0 + kWave + lane];
+        }
+        if (rows_cur != 0) {
+            // logistic D of the problems in a Hessian / diagonal round, lane i taking row i
+            if (any_exd) {
+#pragma unroll
+                for (int k = 0; k < KT; ++k) {
+                    if (svm || !(mode[k] == MODE_HV || mode[k] == MODE_DIAG)) continue;   // uniform
+                    double Dv = 0.0;
+                    if (wk[k] != 0 && row0 + lane < n) Dv = Dval[((int64_t)k * 2 + dslot[k]) * n + row0 + lane];   // zero outside the problem's rows
+                    Ex[k * kExRow + lane] = Dv;
+                }
+            }
+            wave_lds_fence();
+            // Z = X V for rows 16 s .. 16 s + 15
+            auto z_of = [&](int s) {
+                mfma4 z = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+                for (int kk = 0; kk < DMAX / 4; ++kk) {
+                    if (kk < KD) {
+                        const double a = Xs[(16 * s + p) * D + 4 * kk + g];
+                        z = __builtin_amdgcn_mfma_f64_16x16x4f64(a, Vop[kk], z, 0, 0, 0);
+                    }
+                }
+                return z;
+            };
+            if (any_fg) {
+#pragma unroll 1
+                for (int s = 0; s < 4; ++s) {
+                    const mfma4 z = z_of(s);
+                    if (modeM == MODE_FG) {
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) Ex[p * kExRow + 16 * s + 4 * v + g] = z[v];
+                    }
+                }
+                wave_lds_fence();
+#pragma unroll
+                for (int k = 0; k < KT; ++k) {
+                    if (mode[k] != MODE_FG) continue;   // uniform
+                    double zhat = 0.0;
+                    if (wk[k] != 0) {
+                        const double z = Ex[k * kExRow + lane];
+                        const bool mine = (wk[k] >> lane) & 1u;
+                        double alpha, Di;
+                        loss_terms_dev<LOSS>(z, ycur, alpha, zhat, Di);
+                        if (!mine) { alpha = 0.0; zhat = 0.0; Di = 0.0; }
+                        loss[k] += alpha;
+                        if (svm) {
+                            const uint64_t nb = __ballot(Di != 0.0);
+                            if (lane == SL * k + slotl) held = nb;
+                        } else if (mine) {
+                            Dval[((int64_t)k * 2 + dslot[k]) * n + row0 + lane] = Di;
+                        }
+                    } else if (svm && lane == SL * k + slotl) {
+                        held = 0;
+                    }
+                    Ex[k * kExRow + lane] = zhat;
+                }
+                wave_lds_fence();
+            }
+            // the word of this lane's problem
+            uint64_t wordM = 0;
+            if (svm) wordM = lane_value(w0, p);
+            // G += X^T C, 16 rows at a time (Z of a Hessian round is formed again here rather than kept)
+#pragma unroll 1
+            for (int s = 0; s < 4; ++s) {
+                mfma4 z = {0.0, 0.0, 0.0, 0.0};
+                if (any_hv) z = z_of(s);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int r = 16 * s + 4 * v + g;
+                    const double e = (exM && pk) ? Ex[p * kExRow + r] : 0.0;
+                    const bool bit = (wordM >> r) & 1u;
+                    double c, cd;
+                    if (svm) {
+                        c = (modeM == MODE_HV) ? (bit ? z[v] : 0.0) : ((modeM == MODE_FG) ? e : 0.0);
+                        cd = (modeM == MODE_DIAG && bit) ? 2.0 : 0.0;
+                    } else {
+                        c = (modeM == MODE_HV) ? e * z[v] : ((modeM == MODE_FG) ? e : 0.0);
+                        cd = (modeM == MODE_DIAG) ? e : 0.0;
+                    }
+                    const double a1 = (p < D) ? Xs[r * D + p] : 0.0;
+                    const double a2 = (16 + p < D) ? Xs[r * D + 16 + p] : 0.0;
+                    if (any_mul) {
+                        G1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, c, G1, 0, 0, 0);
+                        if (DMAX > 16 && D > 16) G2 = __builtin_amdgcn_mfma_f64_16x16x4f64(a2, c, G2, 0, 0, 0);
+                    }
+                    if (any_diag) {
+                        G1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a1 * a1, cd, G1, 0, 0, 0);
+                        if (DMAX > 16 && D > 16) G2 = __builtin_amdgcn_mfma_f64_16x16x4f64(a2 * a2, cd, G2, 0, 0, 0);
+                    }
+                }
+            }
+            wave_lds_fence();   // the next tile is written over this one
+        }
+        if (svm && any_fg && (slotl == SL - 1 || tile + 1 == last)) {
+            // lane SL k + j stores the word of problem k for tile (tile - slotl + j): SL consecutive words per problem
+            const int k = lane / SL, j = lane % SL;
+            const int mk = ctl->mode[k < KT ? k : 0];
+            if (mk == MODE_FG && j <= slotl) Dbits_out[((int64_t)k * 2 + ctl->dslot[k < KT ? k : 0]) * ntiles + (tile - slotl) + j] = held;
+            held = 0;
+        }
+        w0 = w1;
+        w1 = w2;
+        rows_cur = rows_next;
+        ycur = ynext;
+#pragma unroll
+        for (int k = 0; k < KT; ++k) wk[k] = wkn[k];
+    }
+    // wavefronts 0..3 added in order; result register v of lane (g, p) is column 4 v + g (G1) / 16 + 4 v + g (G2) of problem p
+    __syncthreads();
+    double *Gs = dyn;   // [wavefront][column 0..31][problem 0..15]
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        Gs[((wv * 32) + 4 * v + g) * 16 + p] = G1[v];
+        Gs[((wv * 32) + 16 + 4 * v + g) * 16 + p] = G2[v];
+    }
+    __syncthreads();
+    const int64_t cols = d + 1;
+    for (int i = threadIdx.x; i < KT * D; i += kBlock) {
+        const int k = i / D, col = i % D;
+        if (ctl->mode[k] == MODE_IDLE) continue;
+        double t = 0.0;
+#pragma unroll
+        for (int w = 0; w < kWavesPerBlock; ++w) t += Gs[((w * 32) + col) * 16 + k];
+        partials[((int64_t)k * cols + col) * gridDim.x + blockIdx.x] = t;
+    }
+#pragma unroll
+    for (int k = 0; k < KT; ++k) {
+        if (mode[k] == MODE_IDLE) continue;   // uniform over the workgroup
+        const double ls = block_sum(loss[k], lds_red);
+        if (threadIdx.x == 0) partials[((int64_t)k * cols + d) * gridDim.x + blockIdx.x] = ls;
+    }
+}
+
 // ------------------------------------------------------------------ membership words
 // planes[k][tile] bit i = bit k of member[tile*64 + i] (member == null: every row belongs to every problem); rows past n
 // give zero bits.  bad[0] is set when a word has a bit at or above K.
@@ -565,6 +878,22 @@ PassPair pass_for_shape(const Shape &s, bool vec)
     }
 }
 
+template <int DMAX, int KT>
+PassPair mfma_pass_pair(bool vec)
+{
+    if (vec) return {{k_batch_pass_mfma<true, DMAX, KT, TRON_LOSS_LR>, k_batch_pass_mfma<true, DMAX, KT, TRON_LOSS_L2SVM>}};
+    return {{k_batch_pass_mfma<false, DMAX, KT, TRON_LOSS_LR>, k_batch_pass_mfma<false, DMAX, KT, TRON_LOSS_L2SVM>}};
+}
+
+template <int KT>
+PassPair mfma_pass_for(int64_t d)
+{
+    const bool vec = d % 2 == 0;
+    if (d <= 16) return mfma_pass_pair<16, KT>(vec);
+    if (d <= 24) return mfma_pass_pair<24, KT>(vec);
+    return mfma_pass_pair<32, KT>(vec);
+}
+
 }  // namespace
 }  // namespace tron
 
@@ -585,6 +914,7 @@ struct tron_batch {
     double *partials = nullptr;           // K x (d+1) x grid
     int grid = 0;
     tron::PassPair pass{{nullptr, nullptr}};
+    size_t pass_lds = 0;                  // dynamic LDS of the pass kernel (the matrix-unit pass; 0 otherwise)
     int D_loss = -1;                      // loss whose D the buffers hold (-1: none)
 };
 
@@ -603,7 +933,8 @@ int launch_pass(tron_batch *b, int loss)
     uint64_t *Dout = b->Dbits;
     double *Dval = b->Dval, *partials = b->partials;
     void *args[] = {&n, &d, &X, &y, &ctl, &member, &Din, &Dout, &Dval, &ntiles, &partials};
-    TRON_HIP(hipLaunchKernel(reinterpret_cast<const void *>(b->pass.fn[loss == TRON_LOSS_L2SVM ? 1 : 0]), dim3(b->grid), dim3(kBlock), args, 0, ds->stream));
+    TRON_HIP(hipLaunchKernel(reinterpret_cast<const void *>(b->pass.fn[loss == TRON_LOSS_L2SVM ? 1 : 0]), dim3(b->grid), dim3(kBlock), args, b->pass_lds,
+                             ds->stream));
     return TRON_OK;
 }
 
@@ -705,10 +1036,18 @@ static int batch_create_impl(tron_dataset *ds, int K, const uint32_t *member, in
     auto fail = [&](int rc) { tron_batch_destroy(b); return rc; };
 #define TRON_B(expr) do { hipError_t e__ = (expr); if (e__ != hipSuccess) return fail(hip_fail(e__, #expr, __FILE__, __LINE__)); } while (0)
     if (!b->pass.fn[0]) { set_error("tron_batch_create: internal: no kernel for E=%d L=%d", s.E, s.L); return fail(TRON_EINVAL); }
+    if (g_tuning.batch_mfma > 0) {
+        // the pass as matrix instructions, eight problem columns: the tile of X and the exchange area of every wavefront in LDS
+        b->KT = 8;
+        b->pass = mfma_pass_for<8>(d);
+        b->pass_lds = sizeof(double) * kWavesPerBlock * (size_t)mfma_wave_doubles((int)d, 8);
+        for (int l = 0; l < 2; ++l)
+            TRON_B(hipFuncSetAttribute(reinterpret_cast<const void *>(b->pass.fn[l]), hipFuncAttributeMaxDynamicSharedMemorySize, (int)b->pass_lds));
+    }
     // resident workgroups of the pass: all of them hold their accumulators for the whole pass
     int per_cu = 0, per_cu_lr = 0, cus = 0;
-    TRON_B(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(b->pass.fn[1]), kBlock, 0));
-    TRON_B(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_lr, reinterpret_cast<const void *>(b->pass.fn[0]), kBlock, 0));
+    TRON_B(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(b->pass.fn[1]), kBlock, b->pass_lds));
+    TRON_B(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_lr, reinterpret_cast<const void *>(b->pass.fn[0]), kBlock, b->pass_lds));
     if (per_cu_lr > per_cu) per_cu = per_cu_lr;
     TRON_B(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, ds->device));
     int64_t grid = (int64_t)cus * (per_cu < 1 ? 1 : per_cu);

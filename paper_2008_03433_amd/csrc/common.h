@@ -50,6 +50,7 @@ struct Tuning {
     int64_t dense_device_driver = -1;   // tron_solve on dense d <= 32 without preconditioner driven from the device:
                                         //   0 never, 1 always, -1 automatic (the L2-SVM on matrices up to 1 GB)
     int64_t batch_grid = 0;  // workgroups of the multi-problem pass: 0 = as many as are resident at once
+    int64_t batch_mfma = -1; // multi-problem pass on the matrix units: 1 = yes, 0 = no, -1 = the library decides
 };
 extern Tuning g_tuning;
 

@@ -16,6 +16,15 @@ def rng():
     return np.random.default_rng(20080343)
 
 
+@pytest.fixture(autouse=True, params=["vector_units", "matrix_units"])
+def pass_kernel(request):
+    """Every test of this file runs with both kernels of the pass over X: the one on the vector units and the one that
+    forms the two skinny products with fp64 matrix instructions."""
+    tron.tron_tuning_set("batch_mfma", 1 if request.param == "matrix_units" else 0)
+    yield request.param
+    tron.tron_tuning_set("batch_mfma", -1)
+
+
 def _dense(rng, n, d, sep=0.6):
     mu = rng.standard_normal(d)
     mu *= sep / np.linalg.norm(mu)
