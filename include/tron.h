@@ -230,10 +230,13 @@ TRON_API int tron_solve(tron_dataset *ds, const tron_params *params, double *w_d
  * per problem.  Problem k is exactly the problem of Section 3 over the instances {i : bit k of
  * member[i] is set}: the rows outside it contribute nothing to f, g or Hv.
  * Dense handles with d <= TRON_BATCH_MAX_D only (sparse handles and wider matrices: one tron_solve per problem).
+ * Per tile of 64 instances the pass is two skinny matrix products (64 x d by d x K, and d x 64 by 64 x K).  Up to
+ * eight problems they run on the vector units; nine to sixteen problems (or knob "batch_mfma" = 1) run them as fp64
+ * matrix instructions with the problems as the sixteen result columns.  Same results up to summation order.
  * ------------------------------------------------------------------------------------------ */
 typedef struct tron_batch tron_batch; /* opaque: membership bits, per-problem D, solver state, work space */
 
-#define TRON_BATCH_MAX 8
+#define TRON_BATCH_MAX 16
 #define TRON_BATCH_MAX_D 32
 
 /*
@@ -335,6 +338,8 @@ TRON_API int tron_probe_read_bandwidth(const double *src_dev, int64_t count, int
  * "dense_device_driver" (-1/0/1): tron_solve on a dense matrix with d <= 32 and no preconditioner runs its trust-region and
  *   CG steps on the device (as tron_batch_solve does): 0 never, 1 always, -1 (default) for the L2-SVM on matrices up to 1 GB.
  * "batch_grid" (0..4096): workgroups of the multi-problem pass (0 = as many as are resident at once).
+ * "batch_mfma" (-1/0/1): batches created afterwards run the multi-problem pass on the fp64 matrix units (1), or on the
+ *                vector units where those can hold the batch, i.e. up to eight problems (0, and the default -1).
  * Unknown names or values return TRON_EINVAL.
  */
 TRON_API int tron_tuning_set(const char *name, int64_t value);

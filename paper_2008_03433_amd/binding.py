@@ -229,7 +229,7 @@ def tron_solve(ds, loss, C, eps, w, max_outer=1000, max_cg=1000, cg_xi=0.1, trac
                        res.n_hv, bool(res.converged), rc, recs)
 
 
-BATCH_MAX = 8
+BATCH_MAX = 16
 BATCH_MAX_D = 32
 
 

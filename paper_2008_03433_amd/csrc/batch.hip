@@ -71,7 +71,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass(int64_t n, int64_t d, 
                                                        const int8_t *__restrict__ y,
                                                        const BatchCtl *__restrict__ ctl, const uint64_t *__restrict__ member,
                                                        const uint64_t *__restrict__ Dbits_in, uint64_t *Dbits_out,
-                                                       double *Dval, int64_t ntiles, double *__restrict__ partials)
+                                                       double *Dval, int64_t ntiles, double *__restrict__ partials, int /* K: unused here */)
 {
     using T = Tile<E, L, U, VEC>;
     static_assert(T::RT == kWave, "one 64-bit word per tile");
@@ -287,14 +287,15 @@ __device__ __forceinline__ uint64_t lane_value(uint64_t v, int src)
 }
 
 constexpr int kExRow = kWave + 1;   // doubles per problem in the exchange area (padded against bank conflicts)
-__host__ __device__ constexpr int mfma_wave_doubles(int d, int KT) { return kWave * d + 4 + KT * kExRow + ((KT * kExRow) & 1); }
+// doubles of LDS per wavefront: the tile (dmax columns, 16 doubles of slack) and K rows of the exchange area
+__host__ __device__ constexpr int mfma_wave_doubles(int dmax, int K) { return kWave * dmax + 16 + K * kExRow + ((K * kExRow) & 1); }
 
 template <bool VEC, int DMAX, int KT, int LOSS>
 __global__ __launch_bounds__(kBlock, 2) void k_batch_pass_mfma(int64_t n, int64_t d, const double *__restrict__ X,
                                                             const int8_t *__restrict__ y,
                                                             const BatchCtl *__restrict__ ctl, const uint64_t *__restrict__ member,
                                                             const uint64_t *__restrict__ Dbits_in, uint64_t *Dbits_out,
-                                                            double *Dval, int64_t ntiles, double *__restrict__ partials)
+                                                            double *Dval, int64_t ntiles, double *__restrict__ partials, int K)
 {
     static_assert(KT <= 16 && KT <= kBatchMax, "one result column per problem");
     constexpr bool svm = LOSS == TRON_LOSS_L2SVM;
@@ -321,16 +322,17 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass_mfma(int64_t n, int64_
         any_exd |= !svm && (mode[k] == MODE_HV || mode[k] == MODE_DIAG);
     }
     if (!any) return;
-    const int xs_len = kWave * D + 4;
-    double *Xs = dyn + (size_t)wv * mfma_wave_doubles(D, KT);   // the tile as it lies in memory, 4 doubles of slack
-    double *Ex = Xs + xs_len;                                    // [problem][row] exchange area
-    for (int i = lane; i < mfma_wave_doubles(D, KT); i += kWave) Xs[i] = 0.0;
+    // The tile as it lies in memory (64 d doubles); the area is sized for DMAX columns so that every lane can copy its
+    // NP pieces without asking whether they belong to the tile (those past 64 d are fetched from the first bytes of X).
+    constexpr int xs_len = kWave * DMAX + 16;
+    double *Xs = dyn + (size_t)wv * mfma_wave_doubles(DMAX, K);
+    double *Ex = Xs + xs_len;                                    // [problem 0..K-1][row] exchange area
+    for (int i = lane; i < mfma_wave_doubles(DMAX, K); i += kWave) Xs[i] = 0.0;
     // this lane in the matrix layouts: g = summation index / row block, p = problem (result column) or row / column of X
     const int p = lane & 15, g = lane >> 4;
-    const bool pk = p < KT;
+    const bool pk = p < K;   // K <= KT
     const int modeM = pk ? ctl->mode[pk ? p : 0] : MODE_IDLE;
     const bool exM = modeM == MODE_FG || (!svm && (modeM == MODE_HV || modeM == MODE_DIAG));   // C comes out of the exchange area
-    const int KD = (D + 3) / 4;
     double Vop[DMAX / 4];
 #pragma unroll
     for (int kk = 0; kk < DMAX / 4; ++kk) {
@@ -351,7 +353,6 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass_mfma(int64_t n, int64_
     const int64_t per_wave = (ntiles + nwaves - 1) / nwaves;
     const int64_t first = wave_id * per_wave;
     const int64_t last = (first + per_wave < ntiles) ? first + per_wave : ntiles;
-    const int np = D / PW;                                   // pieces per lane: 64 d / PW pieces over 64 lanes
     const uint64_t inv_d = (0x100000000ull + (uint64_t)D - 1) / (uint64_t)D;   // row of element e < 2048: (e inv_d) >> 32 (2^32 itself for d = 1)
 
     double xr[NP][PW];
@@ -361,74 +362,78 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass_mfma(int64_t n, int64_
     for (int k = 0; k < KT; ++k) loss[k] = 0.0;
     mfma4 G1 = {0.0, 0.0, 0.0, 0.0}, G2 = {0.0, 0.0, 0.0, 0.0};
 
-    // loads of a tile into xr (rows outside `rows` or past n are left out: their registers are not written to LDS either)
+    // Loads of a tile into xr, then xr into LDS.  No load sits behind a branch on a per-lane condition (the compiler would
+    // wait for every load in flight where such paths join): a piece of a row that concerns no problem, or past the end, is
+    // fetched from the first bytes of X instead -- one cached line for all of them -- and copied like the others; its row
+    // coefficient is zero in every problem and X is finite, so what lies there does not matter.
     auto fetch = [&](int64_t tile, uint64_t rows) {
         const int64_t row0 = tile * kWave;
         const double *base = X + row0 * d;
 #pragma unroll
         for (int it = 0; it < NP; ++it) {
-            if (it < np) {
-                const uint32_t e = (uint32_t)(it * kWave + lane) * PW;
-                const uint32_t row = (uint32_t)(((uint64_t)e * inv_d) >> 32);
-                const bool take = ((rows >> row) & 1u) && row0 + row < n;
-                if constexpr (VEC) {
-                    double2 t = make_double2(0.0, 0.0);
-                    if (take) t = *reinterpret_cast<const double2 *>(base + e);
-                    xr[it][0] = t.x;
-                    xr[it][1] = t.y;
-                } else {
-                    xr[it][0] = take ? base[e] : 0.0;
-                }
+            const uint32_t e = (uint32_t)(it * kWave + lane) * PW;
+            const uint32_t row = (uint32_t)(((uint64_t)e * inv_d) >> 32);   // >= 64 past the tile
+            const bool take = row < (uint32_t)kWave && ((rows >> (row & 63u)) & 1u) && row0 + row < n;
+            const double *src = take ? base + e : X;
+            if constexpr (VEC) {
+                const double2 t = *reinterpret_cast<const double2 *>(src);
+                xr[it][0] = t.x;
+                xr[it][1] = t.y;
+            } else {
+                xr[it][0] = *src;
             }
         }
     };
-    auto to_lds = [&](int64_t tile, uint64_t rows) {
-        const int64_t row0 = tile * kWave;
+    auto to_lds = [&]() {
 #pragma unroll
         for (int it = 0; it < NP; ++it) {
-            if (it < np) {
-                const uint32_t e = (uint32_t)(it * kWave + lane) * PW;
-                const uint32_t row = (uint32_t)(((uint64_t)e * inv_d) >> 32);
-                const bool take = ((rows >> row) & 1u) && row0 + row < n;
-                if (take) {
-                    if constexpr (VEC) *reinterpret_cast<double2 *>(Xs + e) = make_double2(xr[it][0], xr[it][1]);
-                    else Xs[e] = xr[it][0];
-                }
-            }
+            const uint32_t e = (uint32_t)(it * kWave + lane) * PW;
+            if constexpr (VEC) *reinterpret_cast<double2 *>(Xs + e) = make_double2(xr[it][0], xr[it][1]);
+            else Xs[e] = xr[it][0];
         }
+    };
+    const uint64_t *plane_c = plane ? plane : member;   // a valid address for the lanes that fetch no word
+    // raw loads (clamped addresses); what they are worth is decided where they are used, so that nothing waits for them early
+    auto word_raw = [&](int64_t tile) { return plane_c[tile < last ? tile : last - 1]; };
+    auto word_ok = [&](int64_t tile) { return plane != nullptr && tile < last; };
+    auto label_raw = [&](int64_t tile) {
+        const int64_t i = tile * kWave + lane;
+        return (int)y[i < n ? i : n - 1];   // rows past n belong to no problem: their label is never used
     };
 
     // words of the current tile (w0), the next (w1) and the one after (loaded in the loop); their scalar copies
     uint64_t w0 = 0, w1 = 0;
-    if (plane && first < last) w0 = plane[first];
-    if (plane && first + 1 < last) w1 = plane[first + 1];
+    if (first < last) {   // the same for the whole wavefront
+        w0 = word_ok(first) ? word_raw(first) : 0ull;
+        w1 = word_ok(first + 1) ? word_raw(first + 1) : 0ull;
+    }
     uint64_t wk[KT], rows_cur = 0;
 #pragma unroll
     for (int k = 0; k < KT; ++k) {
         wk[k] = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(w0 >> 32), k) << 32) | (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)w0, k);
         rows_cur |= wk[k];
     }
-    double ycur = 1.0;
+    int ycur = 1;   // the labels travel with the tile: asked for with its loads, first touched after they have all arrived
     if (first < last && rows_cur != 0) {
+        if (any_fg) ycur = label_raw(first);
         fetch(first, rows_cur);
-        if (any_fg && first * kWave + lane < n) ycur = (double)y[first * kWave + lane];
     }
     int it_tile = 0;
     for (int64_t tile = first; tile < last; ++tile, ++it_tile) {
         const int slotl = it_tile & (SL - 1);
         const int64_t row0 = tile * kWave;
-        const uint64_t w2 = (plane && tile + 2 < last) ? plane[tile + 2] : 0;
+        const uint64_t w2 = word_raw(tile + 2);
         uint64_t wkn[KT], rows_next = 0;
 #pragma unroll
         for (int k = 0; k < KT; ++k) {
             wkn[k] = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(w1 >> 32), k) << 32) | (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)w1, k);
             rows_next |= wkn[k];
         }
-        if (rows_cur != 0) to_lds(tile, rows_cur);
-        double ynext = 1.0;
+        if (rows_cur != 0) to_lds();
+        int ynext = 1;
         if (tile + 1 < last && rows_next != 0) {
+            if (any_fg) ynext = label_raw(tile + 1);
             fetch(tile + 1, rows_next);
-            if (any_fg && row0 + kWave + lane < n) ynext = (double)y[row0 + kWave + lane];
         }
         if (rows_cur != 0) {
             // logistic D of the problems in a Hessian / diagonal round, lane i taking row i
@@ -436,9 +441,9 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass_mfma(int64_t n, int64_
 #pragma unroll
                 for (int k = 0; k < KT; ++k) {
                     if (svm || !(mode[k] == MODE_HV || mode[k] == MODE_DIAG)) continue;   // uniform
-                    double Dv = 0.0;
-                    if (wk[k] != 0 && row0 + lane < n) Dv = Dval[((int64_t)k * 2 + dslot[k]) * n + row0 + lane];   // zero outside the problem's rows
-                    Ex[k * kExRow + lane] = Dv;
+                    const int64_t i = row0 + lane;
+                    const double Dv = Dval[((int64_t)k * 2 + dslot[k]) * n + (i < n ? i : n - 1)];   // zero outside the problem's rows
+                    Ex[k * kExRow + lane] = (i < n) ? Dv : 0.0;
                 }
             }
             wave_lds_fence();
@@ -446,11 +451,9 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass_mfma(int64_t n, int64_
             auto z_of = [&](int s) {
                 mfma4 z = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-                for (int kk = 0; kk < DMAX / 4; ++kk) {
-                    if (kk < KD) {
-                        const double a = Xs[(16 * s + p) * D + 4 * kk + g];
-                        z = __builtin_amdgcn_mfma_f64_16x16x4f64(a, Vop[kk], z, 0, 0, 0);
-                    }
+                for (int kk = 0; kk < DMAX / 4; ++kk) {   // columns past d: V is zero there and what A reads is finite
+                    const double a = Xs[(16 * s + p) * D + 4 * kk + g];
+                    z = __builtin_amdgcn_mfma_f64_16x16x4f64(a, Vop[kk], z, 0, 0, 0);
                 }
                 return z;
             };
@@ -464,6 +467,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass_mfma(int64_t n, int64_
                     }
                 }
                 wave_lds_fence();
+                const double yrow = (double)ycur;
 #pragma unroll
                 for (int k = 0; k < KT; ++k) {
                     if (mode[k] != MODE_FG) continue;   // uniform
@@ -472,7 +476,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass_mfma(int64_t n, int64_
                         const double z = Ex[k * kExRow + lane];
                         const bool mine = (wk[k] >> lane) & 1u;
                         double alpha, Di;
-                        loss_terms_dev<LOSS>(z, ycur, alpha, zhat, Di);
+                        loss_terms_dev<LOSS>(z, yrow, alpha, zhat, Di);
                         if (!mine) { alpha = 0.0; zhat = 0.0; Di = 0.0; }
                         loss[k] += alpha;
                         if (svm) {
@@ -496,10 +500,19 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass_mfma(int64_t n, int64_
             for (int s = 0; s < 4; ++s) {
                 mfma4 z = {0.0, 0.0, 0.0, 0.0};
                 if (any_hv) z = z_of(s);
+                // every LDS read of the 16 rows first (none behind a per-lane condition), then the selects and the products
+                double ev[4], a1v[4], a2v[4];
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     const int r = 16 * s + 4 * v + g;
-                    const double e = (exM && pk) ? Ex[p * kExRow + r] : 0.0;
+                    ev[v] = Ex[(pk ? p : 0) * kExRow + r];
+                    a1v[v] = Xs[r * D + p];
+                    a2v[v] = (DMAX > 16) ? Xs[r * D + 16 + p] : 0.0;   // past d: finite, masked below
+                }
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int r = 16 * s + 4 * v + g;
+                    const double e = (exM && pk) ? ev[v] : 0.0;
                     const bool bit = (wordM >> r) & 1u;
                     double c, cd;
                     if (svm) {
@@ -509,15 +522,15 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass_mfma(int64_t n, int64_
                         c = (modeM == MODE_HV) ? e * z[v] : ((modeM == MODE_FG) ? e : 0.0);
                         cd = (modeM == MODE_DIAG) ? e : 0.0;
                     }
-                    const double a1 = (p < D) ? Xs[r * D + p] : 0.0;
-                    const double a2 = (16 + p < D) ? Xs[r * D + 16 + p] : 0.0;
+                    const double a1 = (p < D) ? a1v[v] : 0.0;
+                    const double a2 = (16 + p < D) ? a2v[v] : 0.0;
                     if (any_mul) {
                         G1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, c, G1, 0, 0, 0);
-                        if (DMAX > 16 && D > 16) G2 = __builtin_amdgcn_mfma_f64_16x16x4f64(a2, c, G2, 0, 0, 0);
+                        if (DMAX > 16) G2 = __builtin_amdgcn_mfma_f64_16x16x4f64(a2, c, G2, 0, 0, 0);
                     }
                     if (any_diag) {
                         G1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a1 * a1, cd, G1, 0, 0, 0);
-                        if (DMAX > 16 && D > 16) G2 = __builtin_amdgcn_mfma_f64_16x16x4f64(a2 * a2, cd, G2, 0, 0, 0);
+                        if (DMAX > 16) G2 = __builtin_amdgcn_mfma_f64_16x16x4f64(a2 * a2, cd, G2, 0, 0, 0);
                     }
                 }
             }
@@ -531,8 +544,9 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass_mfma(int64_t n, int64_
             held = 0;
         }
         w0 = w1;
-        w1 = w2;
+        w1 = word_ok(tile + 2) ? w2 : 0ull;
         rows_cur = rows_next;
+        asm volatile("" : "+v"(ynext));   // nothing of the next tile's loads is touched before this point
         ycur = ynext;
 #pragma unroll
         for (int k = 0; k < KT; ++k) wk[k] = wkn[k];
@@ -840,7 +854,7 @@ __global__ __launch_bounds__(kWave) void k_batch_store(int which, int64_t d, con
 
 // ------------------------------------------------------------------ kernel choice
 using PassFn = void (*)(int64_t, int64_t, const double *, const int8_t *, const BatchCtl *, const uint64_t *,
-                        const uint64_t *, uint64_t *, double *, int64_t, double *);
+                        const uint64_t *, uint64_t *, double *, int64_t, double *, int);
 
 struct PassPair { PassFn fn[2]; };   // by loss
 
@@ -932,7 +946,8 @@ int launch_pass(tron_batch *b, int loss)
     const uint64_t *member = b->member, *Din = b->Dbits;
     uint64_t *Dout = b->Dbits;
     double *Dval = b->Dval, *partials = b->partials;
-    void *args[] = {&n, &d, &X, &y, &ctl, &member, &Din, &Dout, &Dval, &ntiles, &partials};
+    int K = b->K;
+    void *args[] = {&n, &d, &X, &y, &ctl, &member, &Din, &Dout, &Dval, &ntiles, &partials, &K};
     TRON_HIP(hipLaunchKernel(reinterpret_cast<const void *>(b->pass.fn[loss == TRON_LOSS_L2SVM ? 1 : 0]), dim3(b->grid), dim3(kBlock), args, b->pass_lds,
                              ds->stream));
     return TRON_OK;
@@ -1032,15 +1047,17 @@ static int batch_create_impl(tron_dataset *ds, int K, const uint32_t *member, in
     b->KT = (K <= 4) ? 4 : 8;
     b->ntiles = (n + kWave - 1) / kWave;
     const bool vec = (s.E % 2 == 0) && (d % 2 == 0);
+    // up to 8 problems: the pass on the vector units (4 or 8 problem slots); more: the matrix units (below)
     b->pass = (b->KT == 4) ? pass_for_shape<4>(s, vec) : pass_for_shape<8>(s, vec);
     auto fail = [&](int rc) { tron_batch_destroy(b); return rc; };
 #define TRON_B(expr) do { hipError_t e__ = (expr); if (e__ != hipSuccess) return fail(hip_fail(e__, #expr, __FILE__, __LINE__)); } while (0)
     if (!b->pass.fn[0]) { set_error("tron_batch_create: internal: no kernel for E=%d L=%d", s.E, s.L); return fail(TRON_EINVAL); }
-    if (g_tuning.batch_mfma > 0) {
-        // the pass as matrix instructions, eight problem columns: the tile of X and the exchange area of every wavefront in LDS
-        b->KT = 8;
-        b->pass = mfma_pass_for<8>(d);
-        b->pass_lds = sizeof(double) * kWavesPerBlock * (size_t)mfma_wave_doubles((int)d, 8);
+    if (g_tuning.batch_mfma > 0 || K > 8) {
+        // the pass as matrix instructions, 8 or 16 problem columns: the tile of X and the exchange area of every wavefront in LDS
+        b->KT = (K <= 8) ? 8 : 16;
+        b->pass = (b->KT == 8) ? mfma_pass_for<8>(d) : mfma_pass_for<16>(d);
+        b->pass_lds = sizeof(double) * kWavesPerBlock * (size_t)mfma_wave_doubles(d <= 16 ? 16 : (d <= 24 ? 24 : 32), K);
+        if (b->pass_lds < sizeof(double) * kWavesPerBlock * 32 * 16) b->pass_lds = sizeof(double) * kWavesPerBlock * 32 * 16;   // the final sums of the four wavefronts
         for (int l = 0; l < 2; ++l)
             TRON_B(hipFuncSetAttribute(reinterpret_cast<const void *>(b->pass.fn[l]), hipFuncAttributeMaxDynamicSharedMemorySize, (int)b->pass_lds));
     }

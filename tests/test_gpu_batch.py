@@ -86,7 +86,9 @@ def _check_calls(rng, X, y, member, K, loss, Cs, n_hv=2):
 @pytest.mark.parametrize("loss", [LOSS_LR, LOSS_L2SVM])
 @pytest.mark.parametrize("n,d,K", [(1000, 24, 3), (4133, 24, 8), (70000, 18, 6), (5000, 7, 2), (3000, 32, 5), (300, 1, 1),
                                    (20011, 13, 4), (64, 24, 8), (63, 5, 7), (2000, 32, 8), (1500, 28, 7), (900, 9, 8),
-                                   (700, 3, 6), (1200, 16, 5), (6000, 23, 3)])
+                                   (700, 3, 6), (1200, 16, 5), (6000, 23, 3),
+                                   # more than eight problems: always the pass on the matrix units
+                                   (5000, 24, 12), (3000, 18, 16), (2000, 32, 9), (1000, 7, 16), (4133, 24, 16), (700, 31, 11)])
 def test_batch_calls_match_the_oracle(rng, loss, n, d, K):
     X, y = _dense(rng, n, d)
     member = _cv_members(rng, n, K)
@@ -165,7 +167,7 @@ def _compare_batch_solve(rng, X, y, member, K, loss, Cs, eps, W0=None, **kw):
 
 
 @pytest.mark.parametrize("loss", [LOSS_LR, LOSS_L2SVM])
-@pytest.mark.parametrize("n,d,K", [(3000, 24, 3), (20000, 18, 6), (5000, 24, 8), (777, 5, 1)])
+@pytest.mark.parametrize("n,d,K", [(3000, 24, 3), (20000, 18, 6), (5000, 24, 8), (777, 5, 1), (6000, 24, 12), (2500, 18, 16)])
 def test_batch_solve_matches_the_oracle(rng, loss, n, d, K):
     X, y = _dense(rng, n, d)
     member = _cv_members(rng, n, K)
@@ -304,7 +306,7 @@ def test_batch_argument_errors(rng):
         with pytest.raises(tron.TronError):
             tron.Batch(ds, 0, member)
         with pytest.raises(tron.TronError):
-            tron.Batch(ds, 9, member)
+            tron.Batch(ds, 17, member)
         bad = member.copy()
         bad[17] = 4
         with pytest.raises(tron.TronError):
