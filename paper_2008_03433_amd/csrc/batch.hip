@@ -287,8 +287,9 @@ __device__ __forceinline__ uint64_t lane_value(uint64_t v, int src)
 }
 
 constexpr int kExRow = kWave + 1;   // doubles per problem in the exchange area (padded against bank conflicts)
-// doubles of LDS per wavefront: the tile (dmax columns, 16 doubles of slack) and K rows of the exchange area
-__host__ __device__ constexpr int mfma_wave_doubles(int dmax, int K) { return kWave * dmax + 16 + K * kExRow + ((K * kExRow) & 1); }
+// doubles of LDS per wavefront: the tile (rows padded to at most dmax + 2 doubles, 16 doubles of slack) and K rows of the
+// exchange area
+__host__ __device__ constexpr int mfma_wave_doubles(int dmax, int K) { return kWave * (dmax + 2) + 16 + K * kExRow + ((K * kExRow) & 1); }
 
 template <bool VEC, int DMAX, int KT, int LOSS>
 __global__ __launch_bounds__(kBlock, 2) void k_batch_pass_mfma(int64_t n, int64_t d, const double *__restrict__ X,
@@ -322,9 +323,11 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass_mfma(int64_t n, int64_
         any_exd |= !svm && (mode[k] == MODE_HV || mode[k] == MODE_DIAG);
     }
     if (!any) return;
-    // The tile as it lies in memory (64 d doubles); the area is sized for DMAX columns so that every lane can copy its
-    // NP pieces without asking whether they belong to the tile (those past 64 d are fetched from the first bytes of X).
-    constexpr int xs_len = kWave * DMAX + 16;
+    // The tile in LDS: row r at r S, S = the first length >= d whose rows start in different banks for 16 consecutive rows
+    // (16-byte pieces: S = 2 mod 4; 8-byte pieces: S odd).  Every lane copies NP pieces per tile; those past the tile
+    // (d < DMAX) are fetched from the first bytes of X and land in the slack behind the tile.
+    constexpr int xs_len = kWave * (DMAX + 2) + 16;
+    const int S = VEC ? D + ((6 - D % 4) % 4) : (D | 1);
     double *Xs = dyn + (size_t)wv * mfma_wave_doubles(DMAX, K);
     double *Ex = Xs + xs_len;                                    // [problem 0..K-1][row] exchange area
     for (int i = lane; i < mfma_wave_doubles(DMAX, K); i += kWave) Xs[i] = 0.0;
@@ -354,6 +357,15 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass_mfma(int64_t n, int64_
     const int64_t first = wave_id * per_wave;
     const int64_t last = (first + per_wave < ntiles) ? first + per_wave : ntiles;
     const uint64_t inv_d = (0x100000000ull + (uint64_t)D - 1) / (uint64_t)D;   // row of element e < 2048: (e inv_d) >> 32 (2^32 itself for d = 1)
+    // per piece of this lane, fixed for the whole pass: its row in the tile (64 = past the tile) and where it goes in LDS
+    uint32_t prow[NP], plds[NP];
+#pragma unroll
+    for (int it = 0; it < NP; ++it) {
+        const uint32_t e = (uint32_t)(it * kWave + lane) * PW;
+        const uint32_t row = (uint32_t)(((uint64_t)e * inv_d) >> 32);
+        prow[it] = row < (uint32_t)kWave ? row : (uint32_t)kWave;
+        plds[it] = row < (uint32_t)kWave ? row * (uint32_t)S + (e - row * (uint32_t)D) : (uint32_t)(xs_len - 2);
+    }
 
     double xr[NP][PW];
     double loss[KT];
@@ -369,11 +381,13 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass_mfma(int64_t n, int64_
     auto fetch = [&](int64_t tile, uint64_t rows) {
         const int64_t row0 = tile * kWave;
         const double *base = X + row0 * d;
+        const bool full = rows == ~0ull && row0 + kWave <= n;   // the same for every lane: no per-row questions
 #pragma unroll
         for (int it = 0; it < NP; ++it) {
             const uint32_t e = (uint32_t)(it * kWave + lane) * PW;
-            const uint32_t row = (uint32_t)(((uint64_t)e * inv_d) >> 32);   // >= 64 past the tile
-            const bool take = row < (uint32_t)kWave && ((rows >> (row & 63u)) & 1u) && row0 + row < n;
+            const uint32_t row = prow[it];
+            bool take = row < (uint32_t)kWave;
+            if (!full) take = take && ((rows >> (row & 63u)) & 1u) && row0 + row < n;
             const double *src = take ? base + e : X;
             if constexpr (VEC) {
                 const double2 t = *reinterpret_cast<const double2 *>(src);
@@ -387,9 +401,8 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass_mfma(int64_t n, int64_
     auto to_lds = [&]() {
 #pragma unroll
         for (int it = 0; it < NP; ++it) {
-            const uint32_t e = (uint32_t)(it * kWave + lane) * PW;
-            if constexpr (VEC) *reinterpret_cast<double2 *>(Xs + e) = make_double2(xr[it][0], xr[it][1]);
-            else Xs[e] = xr[it][0];
+            if constexpr (VEC) *reinterpret_cast<double2 *>(Xs + plds[it]) = make_double2(xr[it][0], xr[it][1]);
+            else Xs[plds[it]] = xr[it][0];
         }
     };
     const uint64_t *plane_c = plane ? plane : member;   // a valid address for the lanes that fetch no word
@@ -452,7 +465,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass_mfma(int64_t n, int64_
                 mfma4 z = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
                 for (int kk = 0; kk < DMAX / 4; ++kk) {   // columns past d: V is zero there and what A reads is finite
-                    const double a = Xs[(16 * s + p) * D + 4 * kk + g];
+                    const double a = Xs[(16 * s + p) * S + 4 * kk + g];
                     z = __builtin_amdgcn_mfma_f64_16x16x4f64(a, Vop[kk], z, 0, 0, 0);
                 }
                 return z;
@@ -500,37 +513,34 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass_mfma(int64_t n, int64_
             for (int s = 0; s < 4; ++s) {
                 mfma4 z = {0.0, 0.0, 0.0, 0.0};
                 if (any_hv) z = z_of(s);
-                // every LDS read of the 16 rows first (none behind a per-lane condition), then the selects and the products
+                // every LDS read of the 16 rows first (none behind a per-lane condition), then the selects and the products.
+                // Columns of X past d give result rows that nobody reads: A is used as it lies in LDS.
                 double ev[4], a1v[4], a2v[4];
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     const int r = 16 * s + 4 * v + g;
                     ev[v] = Ex[(pk ? p : 0) * kExRow + r];
-                    a1v[v] = Xs[r * D + p];
-                    a2v[v] = (DMAX > 16) ? Xs[r * D + 16 + p] : 0.0;   // past d: finite, masked below
+                    a1v[v] = Xs[r * S + p];
+                    a2v[v] = (DMAX > 16) ? Xs[r * S + 16 + p] : 0.0;
                 }
+                const uint32_t bits = (uint32_t)(wordM >> (16 * s + g));   // bit 4 v: row 16 s + 4 v + g
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    const int r = 16 * s + 4 * v + g;
                     const double e = (exM && pk) ? ev[v] : 0.0;
-                    const bool bit = (wordM >> r) & 1u;
-                    double c, cd;
-                    if (svm) {
-                        c = (modeM == MODE_HV) ? (bit ? z[v] : 0.0) : ((modeM == MODE_FG) ? e : 0.0);
-                        cd = (modeM == MODE_DIAG && bit) ? 2.0 : 0.0;
-                    } else {
-                        c = (modeM == MODE_HV) ? e * z[v] : ((modeM == MODE_FG) ? e : 0.0);
-                        cd = (modeM == MODE_DIAG) ? e : 0.0;
-                    }
-                    const double a1 = (p < D) ? a1v[v] : 0.0;
-                    const double a2 = (16 + p < D) ? a2v[v] : 0.0;
+                    const bool bit = (bits >> (4 * v)) & 1u;
+                    double c;
+                    if (svm) c = (modeM == MODE_HV) ? (bit ? z[v] : 0.0) : ((modeM == MODE_FG) ? e : 0.0);
+                    else c = (modeM == MODE_HV) ? e * z[v] : ((modeM == MODE_FG) ? e : 0.0);
                     if (any_mul) {
-                        G1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, c, G1, 0, 0, 0);
-                        if (DMAX > 16) G2 = __builtin_amdgcn_mfma_f64_16x16x4f64(a2, c, G2, 0, 0, 0);
+                        G1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a1v[v], c, G1, 0, 0, 0);
+                        if (DMAX > 16) G2 = __builtin_amdgcn_mfma_f64_16x16x4f64(a2v[v], c, G2, 0, 0, 0);
                     }
                     if (any_diag) {
-                        G1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a1 * a1, cd, G1, 0, 0, 0);
-                        if (DMAX > 16) G2 = __builtin_amdgcn_mfma_f64_16x16x4f64(a2 * a2, cd, G2, 0, 0, 0);
+                        double cd;
+                        if (svm) cd = (modeM == MODE_DIAG && bit) ? 2.0 : 0.0;
+                        else cd = (modeM == MODE_DIAG) ? e : 0.0;
+                        G1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a1v[v] * a1v[v], cd, G1, 0, 0, 0);
+                        if (DMAX > 16) G2 = __builtin_amdgcn_mfma_f64_16x16x4f64(a2v[v] * a2v[v], cd, G2, 0, 0, 0);
                     }
                 }
             }
