@@ -100,6 +100,22 @@ def test_config3_full_solve_against_the_oracle(c3, capsys):
         ds.close()
 
 
+@pytest.mark.parametrize("device_driver", [0, 1])
+def test_config4_full_solve_against_the_oracle(device_driver):
+    """Config 4 in full (1M x 24, L2-SVM): the whole solve against the oracle's, driven from the host and from the device."""
+    import paper_2008_03433_amd as tron
+    from util import compare_solves
+    p = dg.config4()
+    assert p.n == 1_000_000 and p.d == 24
+    tron.tron_tuning_set("dense_device_driver", device_driver)
+    try:
+        res, ref = compare_solves(p, p.loss, p.C, p.eps)
+        assert res.converged
+        compare_solves(p, p.loss, p.C, 1e-6)
+    finally:
+        tron.tron_tuning_set("dense_device_driver", -1)
+
+
 def test_dense_20m_solves_against_the_oracle():
     """20M x 24 rows of the config-5 generator (3.84 GB: the host-driven path with thousands of tiles per wavefront):
     whole solves against the oracle, single-problem and through the multi-problem calls."""
@@ -193,28 +209,34 @@ def test_config5_full_size_sampled_rows(rng, loss):
         Cs = [0.1, 0.3, C]
         W = np.stack([w, -0.5 * w, w])
         V = np.stack([v, v[::-1].copy(), v])
-        b = tron.tron_batch_create(h, 3, member)
-        try:
-            del member
-            W_d, V_d = dev(W), dev(V)
-            G_d, HV_d = torch.empty_like(W_d), torch.empty_like(V_d)
-            fb = tron.tron_batch_fun_grad(b, loss, Cs, W_d, G_d)
-            vHvb = tron.tron_batch_hv(b, Cs, V_d, HV_d)
-            G, HV = G_d.cpu().numpy(), HV_d.cpu().numpy()
-            for k in range(3):
-                ok = o.restrict(rows_k[k])
-                f_k, g_k, D_k = ok.fun_grad(loss, Cs[k], W[k])
-                assert_scalar_close(fb[k], f_k + Cs[k] * zero_rows_k[k] * loss0, what=f"batch f[{k}]")
-                assert_vec_close(G[k], g_k, what=f"batch g[{k}]")
-                Hv_k = ok.hv(Cs[k], D_k, V[k])
-                assert_vec_close(HV[k], Hv_k, what=f"batch Hv[{k}]")
-                assert_scalar_close(vHvb[k], float(V[k] @ Hv_k), what=f"batch v.Hv[{k}]")
-            # problem 2 sees what the single-problem calls saw
-            assert_scalar_close(fb[2], f, rel=1e-13, what="batch f against tron_fun_grad")
-            assert_vec_close(G[2], g.cpu().numpy(), rel=1e-12, what="batch g against tron_fun_grad")
-            assert_vec_close(HV[2], Hv.cpu().numpy(), rel=1e-12, what="batch Hv against tron_hv")
-        finally:
-            tron.tron_batch_destroy(b)
+        # once with the pass on the vector units, once on the fp64 matrix units
+        for matrix_units in (0, 1):
+            tron.tron_tuning_set("batch_mfma", matrix_units)
+            try:
+                b = tron.tron_batch_create(h, 3, member)
+            finally:
+                tron.tron_tuning_set("batch_mfma", -1)
+            try:
+                W_d, V_d = dev(W), dev(V)
+                G_d, HV_d = torch.empty_like(W_d), torch.empty_like(V_d)
+                fb = tron.tron_batch_fun_grad(b, loss, Cs, W_d, G_d)
+                vHvb = tron.tron_batch_hv(b, Cs, V_d, HV_d)
+                G, HV = G_d.cpu().numpy(), HV_d.cpu().numpy()
+                for k in range(3):
+                    ok = o.restrict(rows_k[k])
+                    f_k, g_k, D_k = ok.fun_grad(loss, Cs[k], W[k])
+                    assert_scalar_close(fb[k], f_k + Cs[k] * zero_rows_k[k] * loss0, what=f"batch f[{k}]")
+                    assert_vec_close(G[k], g_k, what=f"batch g[{k}]")
+                    Hv_k = ok.hv(Cs[k], D_k, V[k])
+                    assert_vec_close(HV[k], Hv_k, what=f"batch Hv[{k}]")
+                    assert_scalar_close(vHvb[k], float(V[k] @ Hv_k), what=f"batch v.Hv[{k}]")
+                # problem 2 sees what the single-problem calls saw
+                assert_scalar_close(fb[2], f, rel=1e-13, what="batch f against tron_fun_grad")
+                assert_vec_close(G[2], g.cpu().numpy(), rel=1e-12, what="batch g against tron_fun_grad")
+                assert_vec_close(HV[2], Hv.cpu().numpy(), rel=1e-12, what="batch Hv against tron_hv")
+            finally:
+                tron.tron_batch_destroy(b)
+        del member
     finally:
         tron.tron_dataset_destroy(h)
 
