@@ -4,7 +4,9 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <exception>
 #include <new>
+#include <thread>
 
 #include "common.h"
 
@@ -282,13 +284,42 @@ int tron_dataset_create_csr(int64_t n, int64_t d, const int64_t *rowptr, const i
         if (!unit) t_val.resize((size_t)t_nnz);
         cursor.assign(t_rowptr.begin(), t_rowptr.end() - 1);
     } catch (const std::bad_alloc &) { set_error("out of host memory building the transposed copy"); return TRON_ENOMEM; }
-    for (int64_t i = 0; i < n; ++i)
-        for (int64_t k = h_rowptr[i]; k < h_rowptr[i + 1]; ++k) {
-            if (nhot && slot_code[h_col[k]] >= 0) continue;
-            const int64_t pos = cursor[h_col[k]]++;
-            t_col[pos] = (int32_t)i;
-            if (!unit) t_val[pos] = h_val[k];
+    {
+        // One host thread per range of features (equal shares of the copy's entries): every thread walks the whole matrix
+        // and places the entries of its own features, so the instances stay in ascending order inside a feature and no
+        // two threads touch the same cursor.
+        unsigned T = std::max(1u, std::min(8u, std::thread::hardware_concurrency()));
+        if (t_nnz < (1 << 20)) T = 1;
+        std::vector<int64_t> bound(T + 1, d);
+        bound[0] = 0;
+        for (unsigned t = 1; t < T; ++t)
+            bound[t] = std::lower_bound(t_rowptr.begin(), t_rowptr.end(), t_nnz / T * t) - t_rowptr.begin();
+        for (unsigned t = 1; t <= T; ++t) bound[t] = std::min<int64_t>(d, std::max(bound[t], bound[t - 1]));
+        bound[T] = d;
+        auto place = [&](int64_t c0, int64_t c1) {
+            if (c0 >= c1) return;
+            for (int64_t i = 0; i < n; ++i)
+                for (int64_t k = h_rowptr[i]; k < h_rowptr[i + 1]; ++k) {
+                    const int64_t c = h_col[k];
+                    if (c < c0) continue;
+                    if (c >= c1) break;   // columns ascend inside a row
+                    if (nhot && slot_code[c] >= 0) continue;
+                    const int64_t pos = cursor[c]++;
+                    t_col[pos] = (int32_t)i;
+                    if (!unit) t_val[pos] = h_val[k];
+                }
+        };
+        std::vector<std::thread> workers;
+        unsigned started = 0;
+        try {
+            for (unsigned t = 1; t < T; ++t) { workers.emplace_back(place, bound[t], bound[t + 1]); ++started; }
+        } catch (const std::exception &) {
+            // no more threads to be had: the remaining ranges run below
         }
+        place(bound[0], bound[1]);
+        for (unsigned t = 1 + started; t < T; ++t) place(bound[t], bound[t + 1]);
+        for (std::thread &w : workers) w.join();
+    }
 
     tron_dataset *ds = new (std::nothrow) tron_dataset();
     if (!ds) { set_error("out of host memory"); return TRON_ENOMEM; }

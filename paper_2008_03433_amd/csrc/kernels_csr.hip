@@ -24,6 +24,8 @@
 // reductions.
 #include <algorithm>
 #include <cstring>
+#include <exception>
+#include <thread>
 
 #include "device_util.h"
 
@@ -105,6 +107,30 @@ static void plan_chunks(const RP *rp, int64_t rows, int64_t nnz_x, int nchunks, 
         }
     }
     (void)nnz_x;
+}
+
+// fn(first, last) over [0, n) cut into equal ranges, one host thread per range (at most eight; small n: the caller's
+// thread alone).  fn must not throw and must write only what belongs to its own range.
+template <class F>
+static void parallel_ranges(int64_t n, F &&fn)
+{
+    unsigned T = std::thread::hardware_concurrency();
+    T = std::max(1u, std::min(8u, T));
+    if (n < (1 << 16)) T = 1;
+    const int64_t per = (n + T - 1) / T;
+    std::vector<std::thread> workers;
+    unsigned started = 0;
+    try {
+        for (unsigned t = 1; t < T; ++t) {
+            workers.emplace_back(fn, std::min<int64_t>(n, (int64_t)t * per), std::min<int64_t>(n, (int64_t)(t + 1) * per));
+            ++started;
+        }
+    } catch (const std::exception &) {
+        // no more threads to be had: the remaining ranges run below
+    }
+    fn((int64_t)0, std::min<int64_t>(n, per));
+    for (unsigned t = 1 + started; t < T; ++t) fn(std::min<int64_t>(n, (int64_t)t * per), std::min<int64_t>(n, (int64_t)(t + 1) * per));
+    for (std::thread &w : workers) w.join();
 }
 
 int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowptr, const int32_t *h_col,
@@ -237,9 +263,22 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
         // longer than a whole chunk is still split.
         std::vector<int32_t> rp32((size_t)NP * (rows + 1), 0);    // start of (x, r) relative to the partition
         std::vector<int32_t> len32((size_t)NP * rows, 0);         // its number of entries
-        for (int64_t r = 0; r < rows; ++r)
-            for (int64_t k = h_rowptr[r]; k < h_rowptr[r + 1]; ++k)
-                if (part_of[h_col[k]] < NP) len32[(size_t)part_of[h_col[k]] * rows + r]++;
+        std::vector<int32_t> head_cnt(sell ? (size_t)rows : 0, 0);   // entries of the row in a head kept as sorted slices
+        // one table for the passes over the entries below: partition in the upper half, LDS slot + 1 (0: none) in the lower
+        std::vector<int32_t> code_of((size_t)cols);
+        for (int64_t j = 0; j < cols; ++j) code_of[j] = ((int32_t)part_of[j] << 16) | ((hot && slot_of[j] >= 0) ? slot_of[j] + 1 : 0);
+        parallel_ranges(rows, [&](int64_t r0, int64_t r1) {
+            for (int64_t r = r0; r < r1; ++r)
+                for (int64_t k = h_rowptr[r]; k < h_rowptr[r + 1]; ++k) {
+                    const int x = code_of[h_col[k]] >> 16;
+                    if (x < NP) len32[(size_t)x * rows + r]++;
+                    else if (sell && x == P) head_cnt[r]++;
+                }
+        });
+        // a head kept as sorted slices: the slots of a row's head entries, row after row (filled with the ranges below)
+        std::vector<int64_t> head_off(sell ? (size_t)rows + 1 : 0, 0);
+        for (int64_t r = 0; sell && r < rows; ++r) head_off[r + 1] = head_off[r] + head_cnt[r];
+        std::vector<uint16_t> head_slot(sell ? (size_t)head_off[rows] : 0);
         std::vector<uint16_t> mask((size_t)rows, 0);
         int64_t pos = 0, nseg_total = 0;
         int chunk = 0;
@@ -274,18 +313,24 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
         // entries partition-major; inside a row the entries of one range are contiguous and stay ordered
         std::vector<int32_t> pcol((size_t)pos, 0);
         std::vector<double> pval(A.unit ? 0 : (size_t)pos, 0.0);
-        {
-            std::vector<int64_t> cursor(NP);
-            for (int64_t r = 0; r < rows; ++r) {
+        parallel_ranges(rows, [&](int64_t r0, int64_t r1) {   // a row's places belong to that row alone
+            int64_t cursor[kMaxParts + 1];
+            for (int64_t r = r0; r < r1; ++r) {
                 for (int x = 0; x < NP; ++x) cursor[x] = A.part_base[x] + rp32[(size_t)x * (rows + 1) + r];
+                int64_t hq = sell ? head_off[r] : 0;
                 for (int64_t k = h_rowptr[r]; k < h_rowptr[r + 1]; ++k) {
-                    if (part_of[h_col[k]] >= NP) continue;   // head entries of a plan with sorted slices
-                    const int64_t q = cursor[part_of[h_col[k]]]++;
-                    pcol[q] = (hot && slot_of[h_col[k]] >= 0) ? ~slot_of[h_col[k]] : h_col[k];   // the head's become 16-bit slots below
+                    const int32_t code = code_of[h_col[k]];
+                    const int x = code >> 16, slot1 = code & 0xffff;
+                    if (x >= NP) {   // head entries of a plan with sorted slices
+                        if (sell && x == P) head_slot[hq++] = (uint16_t)(slot1 - 1);
+                        continue;
+                    }
+                    const int64_t q = cursor[x]++;
+                    pcol[q] = slot1 ? ~(slot1 - 1) : h_col[k];   // the head's become 16-bit slots below
                     if (!A.unit) pval[q] = h_val[k];
                 }
             }
-        }
+        });
         // segment tables
         std::vector<int32_t> seg_row((size_t)std::max<int64_t>(nseg_total, 1));
         std::vector<int4> tab((size_t)chunk);
@@ -337,10 +382,7 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
         }
         if (sell) {
             // ---- sorted slices of the head partition
-            std::vector<int32_t> cnt((size_t)rows, 0);
-            for (int64_t r = 0; r < rows; ++r)
-                for (int64_t k = h_rowptr[r]; k < h_rowptr[r + 1]; ++k)
-                    if (part_of[h_col[k]] == P) cnt[r]++;
+            const std::vector<int32_t> &cnt = head_cnt;   // counted with the segment lengths above
             struct Slice { int32_t len8; int64_t first; };   // first: position of its 64 rows in `order`
             std::vector<int32_t> order((size_t)rows);
             std::vector<Slice> slices;
@@ -398,7 +440,8 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
                     const int32_t hdr[4] = {-1, 0, 0, 0};   // a header of a slice without groups
                     std::memcpy(&data[((size_t)gpad * kWave + l) * 8], hdr, sizeof(hdr));
                 }
-            for (size_t p = 0; p < slices.size(); ++p) {
+            parallel_ranges((int64_t)slices.size(), [&](int64_t p0, int64_t p1) {   // a slice's groups belong to it alone
+            for (int64_t p = p0; p < p1; ++p) {
                 const Slice &sc = slices[stored[p]];
                 const int64_t w1 = std::min<int64_t>(rows, (sc.first / kSellWindow + 1) * (int64_t)kSellWindow);
                 for (int l = 0; l < kWave; ++l) {
@@ -407,17 +450,14 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
                     const int32_t r = (pos < w1) ? order[pos] : -1;
                     if (r >= 0 && cnt[r] > 0) {
                         hdr[0] = (int32_t)pos;   // sums are kept in sorted order
-                        int j = 0;
-                        for (int64_t k = h_rowptr[r]; k < h_rowptr[r + 1]; ++k) {
-                            if (part_of[h_col[k]] != P) continue;
-                            // entry j of the row: group 1 + j / 8 of the slice, lane l, place j % 8
-                            data[((size_t)(goff[p] + 1 + j / 8) * kWave + l) * 8 + j % 8] = (uint16_t)slot_of[h_col[k]];
-                            ++j;
-                        }
+                        // entry j of the row: group 1 + j / 8 of the slice, lane l, place j % 8
+                        const uint16_t *hs = head_slot.data() + head_off[r];
+                        for (int j = 0; j < cnt[r]; ++j) data[((size_t)(goff[p] + 1 + j / 8) * kWave + l) * 8 + j % 8] = hs[j];
                     }
                     std::memcpy(&data[((size_t)goff[p] * kWave + l) * 8], hdr, sizeof(hdr));
                 }
             }
+            });
             {
                 std::vector<int32_t> pos_of((size_t)rows);
                 for (int64_t q = 0; q < rows; ++q) pos_of[order[q]] = (int32_t)q;
@@ -1063,11 +1103,21 @@ int hot_tiles_build(CsrPlan &A, const int64_t *t_rowptr, const int32_t *t_col, c
     std::vector<uint16_t> sslot[kTileSlices];
     std::vector<int4> hdrs[kTileSlices];
 
+    std::vector<Entry> sorted[kTileSlices];
+    std::vector<int32_t> slot_at[kTileSlices];
     auto close_tile = [&](int s) {
         std::vector<Entry> &e = cur[s];
         if (e.empty()) return;
-        // by slot; the entries of a slot keep their column order
-        std::stable_sort(e.begin(), e.end(), [](const Entry &a, const Entry &b) { return a.slot < b.slot; });
+        // by slot; the entries of a slot keep their column order (counting sort)
+        {
+            std::vector<int32_t> &at = slot_at[s];
+            at.assign((size_t)kTileSlots + 1, 0);
+            for (const Entry &x : e) at[(size_t)x.slot + 1]++;
+            for (int q = 0; q < kTileSlots; ++q) at[(size_t)q + 1] += at[(size_t)q];
+            sorted[s].resize(e.size());
+            for (const Entry &x : e) sorted[s][(size_t)at[x.slot]++] = x;
+            e.swap(sorted[s]);
+        }
         int4 h = make_int4((int)base[s], 0, 0, (int)sslot[s].size());
         const size_t off = tiloc[s].size();
         if (!unit) tval[s].resize(off + kChunk, 0.0);
@@ -1090,25 +1140,63 @@ int hot_tiles_build(CsrPlan &A, const int64_t *t_rowptr, const int32_t *t_col, c
 
     // the kernels gather from a copy of the tile's columns in LDS: a tile spans at most kTileWindow of them
     const int64_t span = kTileWindow;
-    int cnt[kTileSlices];
-    for (int64_t i = 0; i < A.cols; ++i) {
-        for (int s = 0; s < kTileSlices; ++s) cnt[s] = 0;
-        for (int64_t k = t_rowptr[i]; k < t_rowptr[i + 1]; ++k) {
+    // The slices are independent of each other (own features, own tiles): one host thread per slice walks the matrix
+    // and keeps the entries of its slice.
+    int64_t slice_nnz[kTileSlices] = {0};
+    bool slice_failed[kTileSlices] = {false};
+    // the code of every entry's feature (slice and slot; kNoCode: not in the tiles), looked up once, so that the slice
+    // threads stream through 16-bit codes instead of each looking every feature up again
+    static_assert(kTileSlices * kTileSlots < 0xffff, "entry codes are 16 bits");
+    constexpr uint16_t kNoCode = 0xffff;
+    std::vector<uint16_t> ecode;
+    try {
+        ecode.resize((size_t)t_rowptr[A.cols]);
+    } catch (const std::exception &) { set_error("out of host memory building the hot-row tiles"); return TRON_ENOMEM; }
+    parallel_ranges(A.cols, [&](int64_t i0, int64_t i1) {
+        for (int64_t k = t_rowptr[i0]; k < t_rowptr[i1]; ++k) {
             const int32_t code = slot_code[t_col[k]];
-            if (code >= 0) cnt[code / kTileSlots]++;
+            ecode[k] = code >= 0 ? (uint16_t)code : kNoCode;
         }
-        for (int s = 0; s < kTileSlices; ++s) {
-            if (!cnt[s]) continue;
-            if ((int)cur[s].size() + cnt[s] > kChunk || (!cur[s].empty() && i - base[s] >= span)) close_tile(s);
-            if (cur[s].empty()) base[s] = i;
+    });
+    auto build_slice = [&](int s) {
+        try {
+            int64_t nnz = 0;
+            for (int64_t i = 0; i < A.cols; ++i) {
+                int cnt = 0;
+                for (int64_t k = t_rowptr[i]; k < t_rowptr[i + 1]; ++k)
+                    if (ecode[k] != kNoCode && ecode[k] / kTileSlots == s) ++cnt;
+                if (!cnt) continue;
+                if ((int)cur[s].size() + cnt > kChunk || (!cur[s].empty() && i - base[s] >= span)) close_tile(s);
+                if (cur[s].empty()) base[s] = i;
+                for (int64_t k = t_rowptr[i]; k < t_rowptr[i + 1]; ++k) {
+                    const int code = ecode[k];
+                    if (code == kNoCode || code / kTileSlots != s) continue;
+                    ++nnz;
+                    cur[s].push_back({(uint16_t)(code % kTileSlots), (uint16_t)(i - base[s]), unit ? 1.0 : t_val[k]});
+                }
+            }
+            close_tile(s);
+            slice_nnz[s] = nnz;
+        } catch (const std::exception &) {
+            slice_failed[s] = true;
         }
-        for (int64_t k = t_rowptr[i]; k < t_rowptr[i + 1]; ++k) {
-            const int32_t code = slot_code[t_col[k]];
-            if (code >= 0) H.nnz++;
-            if (code >= 0) cur[code / kTileSlots].push_back({(uint16_t)(code % kTileSlots), (uint16_t)(i - base[code / kTileSlots]), unit ? 1.0 : t_val[k]});
+    };
+    {
+        std::vector<std::thread> workers;
+        try {
+            for (int s = 1; s < kTileSlices; ++s) workers.emplace_back(build_slice, s);
+        } catch (const std::exception &) {
+            // fewer threads than slices could be started: the rest run here
         }
+        const int started = (int)workers.size();
+        build_slice(0);
+        for (int s = 1 + started; s < kTileSlices; ++s) build_slice(s);
+        for (std::thread &t : workers) t.join();
     }
-    for (int s = 0; s < kTileSlices; ++s) close_tile(s);
+    for (int s = 0; s < kTileSlices; ++s) {
+        if (slice_failed[s]) { set_error("out of host memory building the hot-row tiles"); return TRON_ENOMEM; }
+        H.nnz += slice_nnz[s];
+    }
 
     // concatenate the slices; segment offsets become global
     int64_t ntiles = 0, nseg = 0;
