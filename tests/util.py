@@ -1,16 +1,19 @@
 """Helpers shared by the GPU parity tests."""
+import os
+
 import numpy as np
 
 import paper_2008_03433_amd as tron
 from oracle import Oracle
 
 REL = 1e-10  # per-call parity gate (fp64), norm-wise
+PROGRESS_DIR = os.environ.get("TRON_TEST_PROGRESS_DIR", "gpurun_out")   # relative to the repository root
 
 
 def progress_reporter(capsys, label):
     """Returns a callback for Oracle.tron(progress=...): one line per finished outer iteration of a long oracle solve,
-    printed past pytest's capture and appended to gpurun_out/test_progress.log, so that a watcher of the run's output
-    sees the solve advance."""
+    printed past pytest's capture and appended to a log file in the run's output folder (PROGRESS_DIR), so that whoever
+    watches the run sees the solve advance."""
     import os
     import sys
     import time
@@ -23,8 +26,8 @@ def progress_reporter(capsys, label):
         with capsys.disabled():
             print(line, file=sys.stderr, flush=True)
         try:
-            os.makedirs(os.path.join(root, "gpurun_out"), exist_ok=True)
-            with open(os.path.join(root, "gpurun_out", "test_progress.log"), "a") as fh:
+            os.makedirs(os.path.join(root, PROGRESS_DIR), exist_ok=True)
+            with open(os.path.join(root, PROGRESS_DIR, "test_progress.log"), "a") as fh:
                 fh.write(line + "\n")
         except OSError:
             pass
