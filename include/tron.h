@@ -326,6 +326,9 @@ TRON_API int tron_probe_read_bandwidth(const double *src_dev, int64_t count, int
  *                4096 columns); a quarter of the number of wavefronts the slices are dealt to;
  *   "csr_hot_blocks_per_part", "csr_range_blocks_per_part", "csr_blocks_per_part",
  *   "csr_tile_blocks_per_slice": persistent workgroups of the head, table, table-less and tile kernels.
+ * "cg_speculate" (-1/0/1), read at every solve: the host-driven CG loop enqueues the kernels of iteration k + 1 before it
+ *                has read the scalars of iteration k (1), or only after (0); -1: ahead when a Hessian-vector product moves
+ *                at most 64 MB.  Same iterates either way: the kernels of an iteration that turns out not to exist change nothing.
  * "fuse_reductions" (-1/0/1), read at every call: the second stage of every two-stage reduction (sum of the
  *   per-workgroup partial sums) is done by the workgroup of the producing kernel that finishes last (found through a ticket
  *   counter; the sums themselves are added in a fixed order, so results do not change) instead of by a launch of its own:

@@ -178,6 +178,8 @@ void tron_dataset_destroy(tron_dataset *ds)
     hipFree(ds->partials); hipFree(ds->row_partials); hipFree(ds->unit_scale); hipFree(ds->scal_copy); hipFree(ds->ticket);
     if (ds->scal_host) hipHostFree(ds->scal_host);
     for (double *p : ds->sv) hipFree(p);
+    for (hipEvent_t e : ds->cg_event)
+        if (e) hipEventDestroy(e);
     ds->prof.destroy();
     delete ds;
 }
@@ -610,6 +612,10 @@ int tron_tuning_set(const char *name, int64_t value)
     }
     if (name && strcmp(name, "csr_unit") == 0 && (value == 0 || value == 1)) {
         g_tuning.csr_unit = value;
+        return TRON_OK;
+    }
+    if (name && strcmp(name, "cg_speculate") == 0 && value >= -1 && value <= 1) {
+        g_tuning.cg_speculate = value;
         return TRON_OK;
     }
     if (name && strcmp(name, "fuse_reductions") == 0 && value >= -1 && value <= 1) {

@@ -45,6 +45,8 @@ struct Tuning {
     int64_t csr_unit = 1;    // partitioned layouts: drop the value stream when every row of X holds one repeated value (0 = off)
     int64_t dense_compact = -1;         // dense L2-SVM: Hessian-vector products on a compacted copy of the active rows:
                                         //   0 never, 1 whenever rows are inactive, -1 automatic (see dense_compact_wanted)
+    int64_t cg_speculate = -1;  // enqueue CG iteration k + 1 before the host has read iteration k's scalars: 0 never, 1 always,
+                                // -1 when a Hessian-vector product is cheap (a wasted one costs less than the waits saved)
     int64_t fuse_reductions = -1;  // second reduction stage inside the producing kernel (last workgroup): 0 never, 1 always,
                                    //   -1 automatic (launches of few workgroups, where the extra launch costs more than it does)
     int64_t dense_device_driver = -1;   // tron_solve on dense d <= 32 without preconditioner driven from the device:
@@ -296,6 +298,7 @@ struct tron_dataset {
 
     // solver vectors (d each), allocated on first tron_solve
     double *sv[9] = {nullptr};
+    hipEvent_t cg_event[2] = {nullptr, nullptr};   // end of a CG iteration's kernels, by iteration parity
 
     tron::Profiler prof;
 };
@@ -334,17 +337,25 @@ int dot_partials(tron_dataset *ds, int64_t m, const double *a0, const double *b0
 int loss_terms(tron_dataset *ds, int loss, const double *z, double *zhat, double *D, int first = -1);  // partial slot 0 = sum loss
 int read_scalars(tron_dataset *ds, int count);  // stream sync; then scal_host[0..count) holds what the kernels wrote
 // CG vector kernels (see solver.hip); M = diagonal preconditioner or null
-int cg_init(tron_dataset *ds, const double *g, const double *M, double *s, double *r, double *p, int first = -1);  // M: slot0 = g.(g/M); returns #partials
+// The scalars a CG run keeps on the device between its kernels, by iteration parity (iteration it reads r.r from
+// kScalRR + it % 2 and its reduction leaves the new r.r in kScalRR + (it + 1) % 2; whether iteration it stepped to the
+// trust-region boundary is in kScalFlag + it % 2).  Two slots each, so that the kernels of iteration it + 1 can be
+// enqueued before the host has read what iteration it left.
+constexpr int kScalRR = 6, kScalFlag = 8;
+// rr0 >= 0: also starts a CG run (scalar kScalRR = rr0, both flags cleared)
+int cg_init(tron_dataset *ds, const double *g, const double *M, double *s, double *r, double *p, int first = -1, double rr0 = -1.0);  // M: slot0 = g.(g/M); returns #partials
 // What the CG step kernel needs to form the step length itself from the device copy of the scalars (slot 0 = p.Hp,
-// slots 1..3 = p.p, s.p, s.s unless `first`): alpha = rr / p.Hp, or the step to the trust-region boundary if
-// |s + alpha p| >= delta.  The kernel leaves the step taken in scalar 4 and whether it went to the boundary in scalar 5.
+// slots 1..3 = p.p, s.p, s.s unless it == 0, r.r as above): alpha = rr / p.Hp, or the step to the trust-region boundary
+// if |s + alpha p| >= delta.  The kernel leaves the step taken in scalar 4 and the boundary flag in its slot.
+// An iteration that was enqueued ahead although the run had ended -- the iteration before it went to the boundary, or
+// left sqrt(r.r) <= tol -- changes nothing: both kernels test for that themselves, with the host's own comparison.
 struct CgStepCtl {
-    double rr, delta;
-    int first;      // first iteration: s = 0 and p.p = rr
+    double tol, delta;   // tol = xi times the length of the gradient the run started from
+    int it;              // iteration number, from 0 (then s = 0 and p.p = r.r)
 };
-int cg_step(tron_dataset *ds, const CgStepCtl &ctl, const double *p, const double *Hp, const double *M, double *s, double *r, int first = -1);  // slot0 = r.r | r.(r/M)
-// beta = (scalar 0 of the device copy) / rr_old
-int cg_dir(tron_dataset *ds, double rr_old, const double *r, const double *s, const double *M, double *p, int first = -1);  // slots: p.p, s.p, s.s (M-weighted)
+int cg_step(tron_dataset *ds, const CgStepCtl &ctl, const double *p, const double *Hp, const double *M, double *s, double *r);  // r.r | r.(r/M) to its slot
+// beta = (new r.r) / (old r.r), both from the device copy
+int cg_dir(tron_dataset *ds, const CgStepCtl &ctl, const double *r, const double *s, const double *M, double *p, int first = -1);  // slots: p.p, s.p, s.s (M-weighted)
 int trial_point(tron_dataset *ds, const double *w, const double *s, const double *g, const double *r, const double *M,
                 double *wnew, int first = -1);  // wnew = w+s; slots: g.s, s.r, s.s | s.Ms
 int probe_read(const double *src, int64_t count, int reps, hipStream_t st, double *ms, double *checksum);

@@ -151,9 +151,18 @@ int loss_terms(tron_dataset *ds, int loss, const double *z, double *zhat, double
 template <bool PRE>
 __global__ __launch_bounds__(kBlock) void k_cg_init(int64_t d, const double *__restrict__ g, const double *__restrict__ M,
                                                     double *__restrict__ s, double *__restrict__ r, double *__restrict__ p,
-                                                    double *__restrict__ partials, Finish fin)
+                                                    double *__restrict__ partials, Finish fin, double rr0, double *__restrict__ scal,
+                                                    double *__restrict__ scal_copy)
 {
     __shared__ double lds[kWavesPerBlock];
+    if (rr0 >= 0.0 && blockIdx.x == 0 && threadIdx.x == 0) {
+        scal[kScalRR] = rr0;
+        scal_copy[kScalRR] = rr0;
+        for (int q = 0; q < 2; ++q) {
+            scal[kScalFlag + q] = 0.0;
+            scal_copy[kScalFlag + q] = 0.0;
+        }
+    }
     double acc = 0.0;
     for (int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x; j < d; j += (int64_t)gridDim.x * kBlock) {
         const double t = -g[j];
@@ -170,24 +179,34 @@ __global__ __launch_bounds__(kBlock) void k_cg_init(int64_t d, const double *__r
     }
 }
 
-int cg_init(tron_dataset *ds, const double *g, const double *M, double *s, double *r, double *p, int first)
+int cg_init(tron_dataset *ds, const double *g, const double *M, double *s, double *r, double *p, int first, double rr0)
 {
     ProfScope ps(ds, SLOT_CG_VEC);
     const int gr = vec_grid(ds->d);
     const Finish fin = finish_for(ds, M ? first : -1, gr);   // without M the kernel produces no sum
-    if (M) hipLaunchKernelGGL(k_cg_init<true>, dim3(gr), dim3(kBlock), 0, ds->stream, ds->d, g, M, s, r, p, ds->partials, fin);
-    else hipLaunchKernelGGL(k_cg_init<false>, dim3(gr), dim3(kBlock), 0, ds->stream, ds->d, g, M, s, r, p, ds->partials, fin);
+    if (M) hipLaunchKernelGGL(k_cg_init<true>, dim3(gr), dim3(kBlock), 0, ds->stream, ds->d, g, M, s, r, p, ds->partials, fin, rr0, ds->scal_dev, ds->scal_copy);
+    else hipLaunchKernelGGL(k_cg_init<false>, dim3(gr), dim3(kBlock), 0, ds->stream, ds->d, g, M, s, r, p, ds->partials, fin, rr0, ds->scal_dev, ds->scal_copy);
     TRON_HIP(hipGetLastError());
     return gr;
+}
+
+// Whether the CG run had ended before iteration c.it: the iteration before went to the boundary or left
+// sqrt(r.r) <= tol (the comparison the host makes).  The same in every thread of the launch.
+__device__ __forceinline__ bool cg_run_ended(const CgStepCtl &c, const double *__restrict__ sc)
+{
+    if (c.it == 0) return false;
+    return sc[kScalFlag + ((c.it - 1) & 1)] != 0.0 || sqrt(sc[kScalRR + (c.it & 1)]) <= c.tol;
 }
 
 // The step length of a CG iteration from the device copy of the scalars (see CgStepCtl), in the operations and the
 // order the host used to take (no contraction into fused multiply-adds), the same in every thread.
 __device__ __forceinline__ double cg_step_length(const CgStepCtl &c, const double *__restrict__ sc, bool &boundary)
 {
+    const bool first = c.it == 0;
+    const double rr = sc[kScalRR + (c.it & 1)];
     const double pHp = sc[0];
-    const double pp = c.first ? c.rr : sc[1], sp = c.first ? 0.0 : sc[2], ss = c.first ? 0.0 : sc[3];
-    const double alpha = c.rr / pHp;
+    const double pp = first ? rr : sc[1], sp = first ? 0.0 : sc[2], ss = first ? 0.0 : sc[3];
+    const double alpha = rr / pHp;
     // |s + alpha p|^2 from the three dot products kept alongside the vectors
     const double len2 = __dadd_rn(ss, __dmul_rn(alpha, __dadd_rn(__dmul_rn(2.0, sp), __dmul_rn(alpha, pp))));
     boundary = sqrt(len2) >= c.delta;
@@ -197,20 +216,22 @@ __device__ __forceinline__ double cg_step_length(const CgStepCtl &c, const doubl
     return (sp >= 0.0) ? gap / __dadd_rn(sp, rad) : __dadd_rn(rad, -sp) / pp;
 }
 
-// s += a p;  r -= a Hp with a = the step length above;  partial slot 0 = r.r (PRE: r.(r / M));  scalars 4, 5 = a,
-// whether the step went to the boundary
+// s += a p;  r -= a Hp with a = the step length above;  partial slot 0 = r.r (PRE: r.(r / M));  scalar 4 = a, the
+// iteration's flag slot = whether the step went to the boundary.  Nothing at all if the run had ended.
 template <bool PRE>
 __global__ __launch_bounds__(kBlock) void k_cg_step(int64_t d, CgStepCtl ctl, const double *__restrict__ sc, const double *__restrict__ p,
                                                     const double *__restrict__ Hp, const double *__restrict__ M,
                                                     double *__restrict__ s, double *__restrict__ r, double *__restrict__ partials,
-                                                    double *__restrict__ scal, Finish fin)
+                                                    double *__restrict__ scal, double *__restrict__ scal_copy, Finish fin)
 {
     __shared__ double lds[kWavesPerBlock];
+    if (cg_run_ended(ctl, sc)) return;
     bool boundary;
     const double alpha = cg_step_length(ctl, sc, boundary);
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         scal[4] = alpha;
-        scal[5] = boundary ? 1.0 : 0.0;
+        scal[kScalFlag + (ctl.it & 1)] = boundary ? 1.0 : 0.0;
+        scal_copy[kScalFlag + (ctl.it & 1)] = boundary ? 1.0 : 0.0;   // read by the kernels after this one only
     }
     double acc = 0.0;
     for (int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x; j < d; j += (int64_t)gridDim.x * kBlock) {
@@ -224,26 +245,28 @@ __global__ __launch_bounds__(kBlock) void k_cg_step(int64_t d, CgStepCtl ctl, co
     finish_partials<1>(fin, partials, 0, lds);
 }
 
-int cg_step(tron_dataset *ds, const CgStepCtl &ctl, const double *p, const double *Hp, const double *M, double *s, double *r, int first)
+int cg_step(tron_dataset *ds, const CgStepCtl &ctl, const double *p, const double *Hp, const double *M, double *s, double *r)
 {
     ProfScope ps(ds, SLOT_CG_VEC);
     const int g = vec_grid(ds->d);
-    const Finish fin = finish_for(ds, first, g);
-    if (M) hipLaunchKernelGGL(k_cg_step<true>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, ctl, ds->scal_copy, p, Hp, M, s, r, ds->partials, ds->scal_dev, fin);
-    else hipLaunchKernelGGL(k_cg_step<false>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, ctl, ds->scal_copy, p, Hp, M, s, r, ds->partials, ds->scal_dev, fin);
+    const Finish fin = finish_for(ds, kScalRR + ((ctl.it + 1) & 1), g);
+    if (M) hipLaunchKernelGGL(k_cg_step<true>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, ctl, ds->scal_copy, p, Hp, M, s, r, ds->partials, ds->scal_dev, ds->scal_copy, fin);
+    else hipLaunchKernelGGL(k_cg_step<false>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, ctl, ds->scal_copy, p, Hp, M, s, r, ds->partials, ds->scal_dev, ds->scal_copy, fin);
     TRON_HIP(hipGetLastError());
     return g;
 }
 
-// p = r + beta p (PRE: r / M + beta p) with beta = (scalar 0 of the device copy: the new r.r) / rr_old;
-// partial slots: 0 = p.p, 1 = s.p, 2 = s.s (PRE: M-weighted)
+// p = r + beta p (PRE: r / M + beta p) with beta = (the new r.r) / (the old r.r), both from the device copy;
+// partial slots: 0 = p.p, 1 = s.p, 2 = s.s (PRE: M-weighted).  Nothing at all if the run ended with this iteration.
 template <bool PRE>
-__global__ __launch_bounds__(kBlock) void k_cg_dir(int64_t d, double rr_old, const double *__restrict__ sc, const double *__restrict__ r,
+__global__ __launch_bounds__(kBlock) void k_cg_dir(int64_t d, CgStepCtl ctl, const double *__restrict__ sc, const double *__restrict__ r,
                                                    const double *__restrict__ s, const double *__restrict__ M,
                                                    double *__restrict__ p, double *__restrict__ partials, int stride, Finish fin)
 {
     __shared__ double lds[kWavesPerBlock];
-    const double beta = sc[0] / rr_old;
+    const double rr_old = sc[kScalRR + (ctl.it & 1)], rr_new = sc[kScalRR + ((ctl.it + 1) & 1)];
+    if (cg_run_ended(ctl, sc) || sc[kScalFlag + (ctl.it & 1)] != 0.0 || sqrt(rr_new) <= ctl.tol) return;
+    const double beta = rr_new / rr_old;
     double pp = 0.0, sp = 0.0, ss = 0.0;
     for (int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x; j < d; j += (int64_t)gridDim.x * kBlock) {
         const double m = PRE ? M[j] : 1.0;
@@ -269,13 +292,13 @@ __global__ __launch_bounds__(kBlock) void k_cg_dir(int64_t d, double rr_old, con
     finish_partials<3>(fin, partials, stride, lds);
 }
 
-int cg_dir(tron_dataset *ds, double rr_old, const double *r, const double *s, const double *M, double *p, int first)
+int cg_dir(tron_dataset *ds, const CgStepCtl &ctl, const double *r, const double *s, const double *M, double *p, int first)
 {
     ProfScope ps(ds, SLOT_CG_VEC);
     const int g = vec_grid(ds->d);
     const Finish fin = finish_for(ds, first, g);
-    if (M) hipLaunchKernelGGL(k_cg_dir<true>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, rr_old, ds->scal_copy, r, s, M, p, ds->partials, kMaxGrid, fin);
-    else hipLaunchKernelGGL(k_cg_dir<false>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, rr_old, ds->scal_copy, r, s, M, p, ds->partials, kMaxGrid, fin);
+    if (M) hipLaunchKernelGGL(k_cg_dir<true>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, ctl, ds->scal_copy, r, s, M, p, ds->partials, kMaxGrid, fin);
+    else hipLaunchKernelGGL(k_cg_dir<false>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, ctl, ds->scal_copy, r, s, M, p, ds->partials, kMaxGrid, fin);
     TRON_HIP(hipGetLastError());
     return g;
 }

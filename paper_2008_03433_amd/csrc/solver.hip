@@ -87,36 +87,51 @@ int eval_f(tron_dataset *ds, const tron_params &P, const double *w, int Dslot, d
 // With a diagonal preconditioner M (not null): z = r / M replaces r in p and in the dot products r.r, and the lengths
 // are M-norms (the iteration is plain CG in the variables M^(1/2) s); gscaled = sqrt(g.M^-1 g) takes the place of |g|.
 // One wait per iteration: the step kernel forms alpha (or the step to the boundary) from the scalars the device keeps,
-// the direction kernel forms beta, and the host reads the new r.r and the boundary flag once both are enqueued.  The
-// direction update of the last iteration is therefore computed for nothing (p is not needed again).
+// the direction kernel forms beta, and the host reads the new r.r and the boundary flag of iteration k once its kernels
+// have run.  Where a product is cheap the kernels of iteration k + 1 are enqueued before that wait, so the device never
+// idles while the host decides; if iteration k turns out to be the last, those kernels find that out by themselves and
+// leave s and r alone (see CgStepCtl) -- one product computed for nothing per run, against one idle gap per iteration.
 int cg_solve(tron_dataset *ds, const tron_params &P, const double *M, double delta, double gscaled, int *n_hv, int *on_boundary)
 {
     double *g = ds->sv[V_G], *s = ds->sv[V_S], *r = ds->sv[V_R], *p = ds->sv[V_P], *Hp = ds->sv[V_HP];
-    TRON_TRY(cg_init(ds, g, M, s, r, p));
-    double rr = gscaled * gscaled;   // p = z = -g / M at the start: p.Mp = r.z
-    int it = 0;
+    const double rr0 = gscaled * gscaled;   // p = z = -g / M at the start: p.Mp = r.z
+    const double tol = P.cg_xi * gscaled;
     *on_boundary = 0;
-    while (it < P.max_cg) {
-        if (std::sqrt(rr) <= P.cg_xi * gscaled) break;
+    *n_hv = 0;
+    for (hipEvent_t &e : ds->cg_event)
+        if (!e) TRON_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    TRON_TRY(cg_init(ds, g, M, s, r, p, -1, rr0));
+    if (std::sqrt(rr0) <= tol) return TRON_OK;
+    const double hv_bytes = ds->dense ? 8.0 * (double)ds->n * (double)ds->d : 24.0 * (double)ds->fwd.nnz;
+    const bool ahead = g_tuning.cg_speculate > 0 || (g_tuning.cg_speculate < 0 && hv_bytes <= 64e6);
+    auto enqueue = [&](int it) -> int {
         TRON_TRY(hv_enqueue(ds, P.C, p, Hp));   // scalar 0 = p.Hp; scalars 1..3 = p.p, s.p, s.s of the direction update before
-        const CgStepCtl ctl{rr, delta, it == 0 ? 1 : 0};
-        ++it;
-        const int g1 = cg_step(ds, ctl, p, Hp, M, s, r, 0);
+        const CgStepCtl ctl{tol, delta, it};
+        const int g1 = cg_step(ds, ctl, p, Hp, M, s, r);
         TRON_TRY(g1);
-        TRON_TRY(reduce_final(ds, 1, g1, 0, 0));   // scalar 0 = the new r.r
-        if (it < P.max_cg) {
-            const int g2 = cg_dir(ds, rr, r, s, M, p, 1);
+        TRON_TRY(reduce_final(ds, 1, g1, 0, kScalRR + ((it + 1) & 1)));   // the new r.r
+        if (it + 1 < P.max_cg) {
+            const int g2 = cg_dir(ds, ctl, r, s, M, p, 1);
             TRON_TRY(g2);
             TRON_TRY(reduce_final(ds, 3, g2, kMaxGrid, 1));
         }
-        TRON_TRY(read_scalars(ds, 6));
-        if (ds->scal_host[5] != 0.0) {
+        TRON_HIP(hipEventRecord(ds->cg_event[it & 1], ds->stream));
+        return TRON_OK;
+    };
+    TRON_TRY(enqueue(0));
+    for (int it = 0;; ++it) {
+        const bool more = it + 1 < P.max_cg;
+        if (ahead && more) TRON_TRY(enqueue(it + 1));
+        TRON_HIP(hipEventSynchronize(ds->cg_event[it & 1]));
+        *n_hv = it + 1;
+        if (ds->scal_host[kScalFlag + (it & 1)] != 0.0) {
             *on_boundary = 1;
             break;
         }
-        rr = ds->scal_host[0];
+        const double rr = ds->scal_host[kScalRR + ((it + 1) & 1)];
+        if (!more || std::sqrt(rr) <= tol) break;
+        if (!ahead) TRON_TRY(enqueue(it + 1));
     }
-    *n_hv = it;
     return TRON_OK;
 }
 

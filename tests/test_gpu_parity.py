@@ -595,6 +595,39 @@ def test_solve_hits_trust_region_boundary(rng):
         assert sum(1 - t["accepted"] for t in ref.trace) >= 5
 
 
+@pytest.mark.parametrize("ahead", [0, 1])
+def test_cg_iterations_enqueued_ahead_or_one_by_one_take_the_same_path(rng, ahead):
+    """The host-driven CG loop either waits for an iteration's scalars before enqueuing the next iteration, or enqueues
+    one iteration ahead and lets the kernels of an iteration that turns out not to exist leave the vectors alone.  Runs
+    that end by the residual test, on the trust-region boundary, at the iteration cap, with and without the
+    preconditioner, sparse and dense: the oracle's trajectory either way."""
+    import paper_2008_03433_amd as tron
+    tron.tron_tuning_set("cg_speculate", ahead)
+    tron.tron_tuning_set("dense_device_driver", 0)
+    try:
+        p = dg.config1()
+        compare_solves(p, p.loss, p.C, p.eps)
+        p = dg.config2()
+        compare_solves(p, p.loss, p.C, p.eps)
+        compare_solves(p, p.loss, p.C, 1e-4, precond_blend=0.01)
+        compare_solves(p, p.loss, p.C, 1e-3, max_cg=3)       # every run cut at three iterations
+        compare_solves(p, p.loss, p.C, 1e-3, max_cg=1)
+        q = _dense(rng, 5000, 18)
+        compare_solves(q, LOSS_LR, 2.0, 1e-6)
+        compare_solves(q, LOSS_L2SVM, 0.5, 1e-6, precond_blend=0.5)
+        far = np.random.default_rng(5)
+        n, d = 2000, 40
+        X = 3.0 * far.standard_normal((n, d)) * (far.random((n, d)) < 0.3)
+        y = np.where(far.random(n) < 0.5, 1.0, -1.0)
+        w0 = 3.0 * far.standard_normal(d)
+        for pb in (_csr_from_dense(X, y), DenseProblem("far", n, d, X, y)):
+            res, ref = compare_solves(pb, LOSS_LR, 50.0, 1e-4, w0=w0)
+            assert sum(t["on_boundary"] for t in ref.trace) >= 5
+    finally:
+        tron.tron_tuning_set("cg_speculate", -1)
+        tron.tron_tuning_set("dense_device_driver", -1)
+
+
 def test_solve_warm_start_and_iteration_cap(rng, dense_driver):
     torch = torch_mod()
     import paper_2008_03433_amd as tron
