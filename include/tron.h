@@ -341,6 +341,8 @@ TRON_API int tron_probe_read_bandwidth(const double *src_dev, int64_t count, int
  * "dense_device_driver" (-1/0/1): tron_solve on a dense matrix with d <= 32 and no preconditioner runs its trust-region and
  *   CG steps on the device (as tron_batch_solve does): 0 never, 1 always, -1 (default) for the L2-SVM on matrices up to 1 GB.
  * "batch_grid" (0..4096): workgroups of the multi-problem pass (0 = as many as are resident at once).
+ * "batch_mfma_rows" (0/32/64): rows of X a wavefront of the matrix-unit pass keeps in LDS at a time (0: 64 where two
+ *                workgroups per CU still fit, else 32).
  * "batch_mfma" (-1/0/1): batches created afterwards run the multi-problem pass on the fp64 matrix units (1), or on the
  *                vector units where those can hold the batch, i.e. up to eight problems (0, and the default -1).
  * Unknown names or values return TRON_EINVAL.

@@ -286,12 +286,14 @@ __device__ __forceinline__ uint64_t lane_value(uint64_t v, int src)
     return ((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo;
 }
 
-constexpr int kExRow = kWave + 1;   // doubles per problem in the exchange area (padded against bank conflicts)
-// doubles of LDS per wavefront: the tile (rows padded to at most dmax + 2 doubles, 16 doubles of slack) and K rows of the
-// exchange area
-__host__ __device__ constexpr int mfma_wave_doubles(int dmax, int K) { return kWave * (dmax + 2) + 16 + K * kExRow + ((K * kExRow) & 1); }
+// doubles of LDS per wavefront: a unit of RT rows of X (rows padded to at most dmax + 2 doubles, 16 doubles of slack) and
+// K rows of RT + 1 doubles of the exchange area
+__host__ __device__ constexpr int mfma_wave_doubles(int dmax, int K, int rt) { return rt * (dmax + 2) + 16 + K * (rt + 1) + ((K * (rt + 1)) & 1); }
 
-template <bool VEC, int DMAX, int KT, int LOSS>
+// RT = rows of X a wavefront keeps in LDS at a time: a whole 64-row tile, or half of one (smaller LDS footprint and
+// fewer registers for the loads in flight, so more wavefronts per SIMD to cover the dependent chains of matrix
+// instructions; the row-per-lane steps then serve 64 / RT problems side by side).
+template <bool VEC, int DMAX, int KT, int LOSS, int RT>
 __global__ __launch_bounds__(kBlock, 2) void k_batch_pass_mfma(int64_t n, int64_t d, const double *__restrict__ X,
                                                             const int8_t *__restrict__ y,
                                                             const BatchCtl *__restrict__ ctl, const uint64_t *__restrict__ member,
@@ -299,11 +301,17 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass_mfma(int64_t n, int64_
                                                             double *Dval, int64_t ntiles, double *__restrict__ partials, int K)
 {
     static_assert(KT <= 16 && KT <= kBatchMax, "one result column per problem");
+    static_assert(RT == 32 || RT == 64, "a tile or half a tile");
     constexpr bool svm = LOSS == TRON_LOSS_L2SVM;
     static_assert(DMAX % 4 == 0 && DMAX <= kVecPad, "d <= DMAX, in steps of the instruction's four columns");
     constexpr int PW = VEC ? 2 : 1;                 // doubles per piece
-    constexpr int NP = DMAX / PW;                   // pieces per lane and tile at most (a tile is 64 d doubles)
+    constexpr int NH = kWave / RT;                  // units per tile
+    constexpr int NS = RT / 16;                     // groups of 16 rows per unit
+    constexpr int PP = kWave / RT;                  // problems side by side in the row-per-lane layout
+    constexpr int NP = RT * DMAX / PW / kWave;      // pieces per lane and unit at most (a unit is RT d doubles)
+    static_assert(RT * DMAX / PW % kWave == 0 && KT % PP == 0, "whole pieces per lane; whole groups of problems");
     constexpr int SL = kWave / KT;                  // tiles whose new active-set words a lane group holds before they are stored
+    constexpr int kExRow = RT + 1;                  // doubles per problem in the exchange area (padded against bank conflicts)
     extern __shared__ double dyn[];
     __shared__ double lds_red[kWavesPerBlock];
     const int lane = threadIdx.x & (kWave - 1);
@@ -323,19 +331,21 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass_mfma(int64_t n, int64_
         any_exd |= !svm && (mode[k] == MODE_HV || mode[k] == MODE_DIAG);
     }
     if (!any) return;
-    // The tile in LDS: row r at r S, S = the first length >= d whose rows start in different banks for 16 consecutive rows
-    // (16-byte pieces: S = 2 mod 4; 8-byte pieces: S odd).  Every lane copies NP pieces per tile; those past the tile
-    // (d < DMAX) are fetched from the first bytes of X and land in the slack behind the tile.
-    constexpr int xs_len = kWave * (DMAX + 2) + 16;
+    // The unit in LDS: row r at r S, S = the first length >= d whose rows start in different banks for 16 consecutive rows
+    // (16-byte pieces: S = 2 mod 4; 8-byte pieces: S odd).  Every lane copies NP pieces per unit; those past the unit
+    // (d < DMAX) are fetched from the first bytes of X and land in the slack behind it.
+    constexpr int xs_len = RT * (DMAX + 2) + 16;
     const int S = VEC ? D + ((6 - D % 4) % 4) : (D | 1);
-    double *Xs = dyn + (size_t)wv * mfma_wave_doubles(DMAX, K);
+    double *Xs = dyn + (size_t)wv * mfma_wave_doubles(DMAX, K, RT);
     double *Ex = Xs + xs_len;                                    // [problem 0..K-1][row] exchange area
-    for (int i = lane; i < mfma_wave_doubles(DMAX, K); i += kWave) Xs[i] = 0.0;
+    for (int i = lane; i < mfma_wave_doubles(DMAX, K, RT); i += kWave) Xs[i] = 0.0;
     // this lane in the matrix layouts: g = summation index / row block, p = problem (result column) or row / column of X
     const int p = lane & 15, g = lane >> 4;
     const bool pk = p < K;   // K <= KT
     const int modeM = pk ? ctl->mode[pk ? p : 0] : MODE_IDLE;
     const bool exM = modeM == MODE_FG || (!svm && (modeM == MODE_HV || modeM == MODE_DIAG));   // C comes out of the exchange area
+    // ... and in the row-per-lane layout: row rowl of the unit, problem sub of a group of PP problems
+    const int rowl = lane & (RT - 1), sub = lane / RT;
     double Vop[DMAX / 4];
 #pragma unroll
     for (int kk = 0; kk < DMAX / 4; ++kk) {
@@ -357,14 +367,14 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass_mfma(int64_t n, int64_
     const int64_t first = wave_id * per_wave;
     const int64_t last = (first + per_wave < ntiles) ? first + per_wave : ntiles;
     const uint64_t inv_d = (0x100000000ull + (uint64_t)D - 1) / (uint64_t)D;   // row of element e < 2048: (e inv_d) >> 32 (2^32 itself for d = 1)
-    // per piece of this lane, fixed for the whole pass: its row in the tile (64 = past the tile) and where it goes in LDS
+    // per piece of this lane, fixed for the whole pass: its row in the unit (RT = past the unit) and where it goes in LDS
     uint32_t prow[NP], plds[NP];
 #pragma unroll
     for (int it = 0; it < NP; ++it) {
         const uint32_t e = (uint32_t)(it * kWave + lane) * PW;
         const uint32_t row = (uint32_t)(((uint64_t)e * inv_d) >> 32);
-        prow[it] = row < (uint32_t)kWave ? row : (uint32_t)kWave;
-        plds[it] = row < (uint32_t)kWave ? row * (uint32_t)S + (e - row * (uint32_t)D) : (uint32_t)(xs_len - 2);
+        prow[it] = row < (uint32_t)RT ? row : (uint32_t)RT;
+        plds[it] = row < (uint32_t)RT ? row * (uint32_t)S + (e - row * (uint32_t)D) : (uint32_t)(xs_len - 2);
     }
 
     double xr[NP][PW];
@@ -374,20 +384,22 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass_mfma(int64_t n, int64_
     for (int k = 0; k < KT; ++k) loss[k] = 0.0;
     mfma4 G1 = {0.0, 0.0, 0.0, 0.0}, G2 = {0.0, 0.0, 0.0, 0.0};
 
-    // Loads of a tile into xr, then xr into LDS.  No load sits behind a branch on a per-lane condition (the compiler would
+    // the rows of unit h of a tile that concern some problem
+    auto unit_rows = [&](uint64_t rows, int h) -> uint64_t { return RT == kWave ? rows : ((rows >> (RT * h)) & 0xffffffffull); };
+    // Loads of a unit into xr, then xr into LDS.  No load sits behind a branch on a per-lane condition (the compiler would
     // wait for every load in flight where such paths join): a piece of a row that concerns no problem, or past the end, is
     // fetched from the first bytes of X instead -- one cached line for all of them -- and copied like the others; its row
     // coefficient is zero in every problem and X is finite, so what lies there does not matter.
-    auto fetch = [&](int64_t tile, uint64_t rows) {
-        const int64_t row0 = tile * kWave;
+    auto fetch = [&](int64_t tile, int h, uint64_t urows) {
+        const int64_t row0 = tile * kWave + RT * h;
         const double *base = X + row0 * d;
-        const bool full = rows == ~0ull && row0 + kWave <= n;   // the same for every lane: no per-row questions
+        const bool full = urows == (RT == kWave ? ~0ull : 0xffffffffull) && row0 + RT <= n;   // the same for every lane: no per-row questions
 #pragma unroll
         for (int it = 0; it < NP; ++it) {
             const uint32_t e = (uint32_t)(it * kWave + lane) * PW;
             const uint32_t row = prow[it];
-            bool take = row < (uint32_t)kWave;
-            if (!full) take = take && ((rows >> (row & 63u)) & 1u) && row0 + row < n;
+            bool take = row < (uint32_t)RT;
+            if (!full) take = take && ((urows >> (row & (RT - 1))) & 1u) && row0 + row < n;
             const double *src = take ? base + e : X;
             if constexpr (VEC) {
                 const double2 t = *reinterpret_cast<const double2 *>(src);
@@ -409,10 +421,14 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass_mfma(int64_t n, int64_
     // raw loads (clamped addresses); what they are worth is decided where they are used, so that nothing waits for them early
     auto word_raw = [&](int64_t tile) { return plane_c[tile < last ? tile : last - 1]; };
     auto word_ok = [&](int64_t tile) { return plane != nullptr && tile < last; };
-    auto label_raw = [&](int64_t tile) {
-        const int64_t i = tile * kWave + lane;
+    auto label_raw = [&](int64_t tile, int h) {
+        const int64_t i = tile * kWave + RT * h + rowl;
         return (int)y[i < n ? i : n - 1];   // rows past n belong to no problem: their label is never used
     };
+    // a value that is the same within each group of RT lanes: x[sub] of PP values that are the same for every lane
+    auto by_sub_i = [&](const int *x) { return (PP == 1 || sub == 0) ? x[0] : x[PP - 1]; };
+    auto by_sub_u = [&](const uint64_t *x) { return (PP == 1 || sub == 0) ? x[0] : x[PP - 1]; };
+    static_assert(PP <= 2, "by_sub picks between two");
 
     // words of the current tile (w0), the next (w1) and the one after (loaded in the loop); their scalar copies
     uint64_t w0 = 0, w1 = 0;
@@ -426,15 +442,14 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass_mfma(int64_t n, int64_
         wk[k] = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(w0 >> 32), k) << 32) | (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)w0, k);
         rows_cur |= wk[k];
     }
-    int ycur = 1;   // the labels travel with the tile: asked for with its loads, first touched after they have all arrived
-    if (first < last && rows_cur != 0) {
-        if (any_fg) ycur = label_raw(first);
-        fetch(first, rows_cur);
+    int ycur = 1;   // the labels travel with the unit: asked for with its loads, first touched after they have all arrived
+    if (first < last && unit_rows(rows_cur, 0) != 0) {
+        if (any_fg) ycur = label_raw(first, 0);
+        fetch(first, 0, unit_rows(rows_cur, 0));
     }
     int it_tile = 0;
     for (int64_t tile = first; tile < last; ++tile, ++it_tile) {
         const int slotl = it_tile & (SL - 1);
-        const int64_t row0 = tile * kWave;
         const uint64_t w2 = word_raw(tile + 2);
         uint64_t wkn[KT], rows_next = 0;
 #pragma unroll
@@ -442,109 +457,145 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass_mfma(int64_t n, int64_
             wkn[k] = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(w1 >> 32), k) << 32) | (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)w1, k);
             rows_next |= wkn[k];
         }
-        if (rows_cur != 0) to_lds();
-        int ynext = 1;
-        if (tile + 1 < last && rows_next != 0) {
-            if (any_fg) ynext = label_raw(tile + 1);
-            fetch(tile + 1, rows_next);
-        }
-        if (rows_cur != 0) {
-            // logistic D of the problems in a Hessian / diagonal round, lane i taking row i
-            if (any_exd) {
-#pragma unroll
-                for (int k = 0; k < KT; ++k) {
-                    if (svm || !(mode[k] == MODE_HV || mode[k] == MODE_DIAG)) continue;   // uniform
-                    const int64_t i = row0 + lane;
-                    const double Dv = Dval[((int64_t)k * 2 + dslot[k]) * n + (i < n ? i : n - 1)];   // zero outside the problem's rows
-                    Ex[k * kExRow + lane] = (i < n) ? Dv : 0.0;
+        // the word of this lane's problem
+        uint64_t wordM = 0;
+        if (svm) wordM = lane_value(w0, p);
+#pragma unroll 1
+        for (int h = 0; h < NH; ++h) {
+            const int64_t row0 = tile * kWave + RT * h;
+            const uint64_t urows = unit_rows(rows_cur, h);
+            if (urows != 0) to_lds();
+            // the loads of the unit after this one
+            int ynext = 1;
+            {
+                const bool same_tile = h + 1 < NH;
+                const int64_t nt = same_tile ? tile : tile + 1;
+                const int nh = same_tile ? h + 1 : 0;
+                const uint64_t nrows = unit_rows(same_tile ? rows_cur : rows_next, nh);
+                if (nt < last && nrows != 0) {
+                    if (any_fg) ynext = label_raw(nt, nh);
+                    fetch(nt, nh, nrows);
                 }
             }
-            wave_lds_fence();
-            // Z = X V for rows 16 s .. 16 s + 15
-            auto z_of = [&](int s) {
-                mfma4 z = {0.0, 0.0, 0.0, 0.0};
+            if (urows != 0) {
+                // logistic D of the problems in a Hessian / diagonal round, row-per-lane, PP problems side by side
+                if (any_exd) {
 #pragma unroll
-                for (int kk = 0; kk < DMAX / 4; ++kk) {   // columns past d: V is zero there and what A reads is finite
-                    const double a = Xs[(16 * s + p) * S + 4 * kk + g];
-                    z = __builtin_amdgcn_mfma_f64_16x16x4f64(a, Vop[kk], z, 0, 0, 0);
-                }
-                return z;
-            };
-            if (any_fg) {
-#pragma unroll 1
-                for (int s = 0; s < 4; ++s) {
-                    const mfma4 z = z_of(s);
-                    if (modeM == MODE_FG) {
+                    for (int k = 0; k < KT; k += PP) {
+                        bool some = false;
+                        int mk[PP], dk[PP];
 #pragma unroll
-                        for (int v = 0; v < 4; ++v) Ex[p * kExRow + 16 * s + 4 * v + g] = z[v];
+                        for (int j = 0; j < PP; ++j) {
+                            mk[j] = mode[k + j];
+                            dk[j] = dslot[k + j];
+                            some |= mk[j] == MODE_HV || mk[j] == MODE_DIAG;
+                        }
+                        if (svm || !some) continue;   // uniform
+                        const int mK = by_sub_i(mk), dK = by_sub_i(dk);
+                        const int kk = k + sub;
+                        const int64_t i = row0 + rowl;
+                        const double Dv = Dval[((int64_t)(kk < K ? kk : 0) * 2 + dK) * n + (i < n ? i : n - 1)];   // zero outside the problem's rows
+                        if ((mK == MODE_HV || mK == MODE_DIAG) && kk < K) Ex[kk * kExRow + rowl] = (i < n) ? Dv : 0.0;
                     }
                 }
                 wave_lds_fence();
-                const double yrow = (double)ycur;
+                // Z = X V for rows 16 s .. 16 s + 15 of the unit
+                auto z_of = [&](int s) {
+                    mfma4 z = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-                for (int k = 0; k < KT; ++k) {
-                    if (mode[k] != MODE_FG) continue;   // uniform
-                    double zhat = 0.0;
-                    if (wk[k] != 0) {
-                        const double z = Ex[k * kExRow + lane];
-                        const bool mine = (wk[k] >> lane) & 1u;
-                        double alpha, Di;
+                    for (int kk = 0; kk < DMAX / 4; ++kk) {   // columns past d: V is zero there and what A reads is finite
+                        const double a = Xs[(16 * s + p) * S + 4 * kk + g];
+                        z = __builtin_amdgcn_mfma_f64_16x16x4f64(a, Vop[kk], z, 0, 0, 0);
+                    }
+                    return z;
+                };
+                if (any_fg) {
+#pragma unroll 1
+                    for (int s = 0; s < NS; ++s) {
+                        const mfma4 z = z_of(s);
+                        if (modeM == MODE_FG) {
+#pragma unroll
+                            for (int v = 0; v < 4; ++v) Ex[p * kExRow + 16 * s + 4 * v + g] = z[v];
+                        }
+                    }
+                    wave_lds_fence();
+                    const double yrow = (double)ycur;
+#pragma unroll
+                    for (int k = 0; k < KT; k += PP) {
+                        bool some = false;
+                        int mk[PP], dk[PP];
+                        uint64_t wq[PP];
+#pragma unroll
+                        for (int j = 0; j < PP; ++j) {
+                            mk[j] = mode[k + j];
+                            dk[j] = dslot[k + j];
+                            wq[j] = wk[k + j];
+                            some |= mk[j] == MODE_FG;
+                        }
+                        if (!some) continue;   // uniform
+                        const int kk = k + sub;
+                        const bool act = by_sub_i(mk) == MODE_FG && kk < K;
+                        const double z = Ex[(kk < K ? kk : 0) * kExRow + rowl];
+                        const bool mine = act && ((by_sub_u(wq) >> (RT * h + rowl)) & 1u);
+                        double alpha, zhat, Di;
                         loss_terms_dev<LOSS>(z, yrow, alpha, zhat, Di);
                         if (!mine) { alpha = 0.0; zhat = 0.0; Di = 0.0; }
-                        loss[k] += alpha;
+#pragma unroll
+                        for (int j = 0; j < PP; ++j) loss[k + j] += (sub == j) ? alpha : 0.0;
                         if (svm) {
                             const uint64_t nb = __ballot(Di != 0.0);
-                            if (lane == SL * k + slotl) held = nb;
+#pragma unroll
+                            for (int j = 0; j < PP; ++j) {
+                                const uint64_t part = RT == kWave ? nb : ((nb >> (RT * j)) & 0xffffffffull);
+                                if (lane == SL * (k + j) + slotl) held |= part << (RT * h);
+                            }
                         } else if (mine) {
-                            Dval[((int64_t)k * 2 + dslot[k]) * n + row0 + lane] = Di;
+                            Dval[((int64_t)kk * 2 + by_sub_i(dk)) * n + row0 + rowl] = Di;
                         }
-                    } else if (svm && lane == SL * k + slotl) {
-                        held = 0;
+                        if (act) Ex[kk * kExRow + rowl] = zhat;
                     }
-                    Ex[k * kExRow + lane] = zhat;
+                    wave_lds_fence();
                 }
-                wave_lds_fence();
-            }
-            // the word of this lane's problem
-            uint64_t wordM = 0;
-            if (svm) wordM = lane_value(w0, p);
-            // G += X^T C, 16 rows at a time (Z of a Hessian round is formed again here rather than kept)
+                // G += X^T C, 16 rows at a time (Z of a Hessian round is formed again here rather than kept)
 #pragma unroll 1
-            for (int s = 0; s < 4; ++s) {
-                mfma4 z = {0.0, 0.0, 0.0, 0.0};
-                if (any_hv) z = z_of(s);
-                // every LDS read of the 16 rows first (none behind a per-lane condition), then the selects and the products.
-                // Columns of X past d give result rows that nobody reads: A is used as it lies in LDS.
-                double ev[4], a1v[4], a2v[4];
+                for (int s = 0; s < NS; ++s) {
+                    mfma4 z = {0.0, 0.0, 0.0, 0.0};
+                    if (any_hv) z = z_of(s);
+                    // every LDS read of the 16 rows first (none behind a per-lane condition), then the selects and the products.
+                    // Columns of X past d give result rows that nobody reads: A is used as it lies in LDS.
+                    double ev[4], a1v[4], a2v[4];
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int r = 16 * s + 4 * v + g;
-                    ev[v] = Ex[(pk ? p : 0) * kExRow + r];
-                    a1v[v] = Xs[r * S + p];
-                    a2v[v] = (DMAX > 16) ? Xs[r * S + 16 + p] : 0.0;
-                }
-                const uint32_t bits = (uint32_t)(wordM >> (16 * s + g));   // bit 4 v: row 16 s + 4 v + g
+                    for (int v = 0; v < 4; ++v) {
+                        const int r = 16 * s + 4 * v + g;
+                        ev[v] = Ex[(pk ? p : 0) * kExRow + r];
+                        a1v[v] = Xs[r * S + p];
+                        a2v[v] = (DMAX > 16) ? Xs[r * S + 16 + p] : 0.0;
+                    }
+                    const uint32_t bits = (uint32_t)(wordM >> (RT * h + 16 * s + g));   // bit 4 v: row 16 s + 4 v + g of the unit
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const double e = (exM && pk) ? ev[v] : 0.0;
-                    const bool bit = (bits >> (4 * v)) & 1u;
-                    double c;
-                    if (svm) c = (modeM == MODE_HV) ? (bit ? z[v] : 0.0) : ((modeM == MODE_FG) ? e : 0.0);
-                    else c = (modeM == MODE_HV) ? e * z[v] : ((modeM == MODE_FG) ? e : 0.0);
-                    if (any_mul) {
-                        G1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a1v[v], c, G1, 0, 0, 0);
-                        if (DMAX > 16) G2 = __builtin_amdgcn_mfma_f64_16x16x4f64(a2v[v], c, G2, 0, 0, 0);
-                    }
-                    if (any_diag) {
-                        double cd;
-                        if (svm) cd = (modeM == MODE_DIAG && bit) ? 2.0 : 0.0;
-                        else cd = (modeM == MODE_DIAG) ? e : 0.0;
-                        G1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a1v[v] * a1v[v], cd, G1, 0, 0, 0);
-                        if (DMAX > 16) G2 = __builtin_amdgcn_mfma_f64_16x16x4f64(a2v[v] * a2v[v], cd, G2, 0, 0, 0);
+                    for (int v = 0; v < 4; ++v) {
+                        const double e = (exM && pk) ? ev[v] : 0.0;
+                        const bool bit = (bits >> (4 * v)) & 1u;
+                        double c;
+                        if (svm) c = (modeM == MODE_HV) ? (bit ? z[v] : 0.0) : ((modeM == MODE_FG) ? e : 0.0);
+                        else c = (modeM == MODE_HV) ? e * z[v] : ((modeM == MODE_FG) ? e : 0.0);
+                        if (any_mul) {
+                            G1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a1v[v], c, G1, 0, 0, 0);
+                            if (DMAX > 16) G2 = __builtin_amdgcn_mfma_f64_16x16x4f64(a2v[v], c, G2, 0, 0, 0);
+                        }
+                        if (any_diag) {
+                            double cd;
+                            if (svm) cd = (modeM == MODE_DIAG && bit) ? 2.0 : 0.0;
+                            else cd = (modeM == MODE_DIAG) ? e : 0.0;
+                            G1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a1v[v] * a1v[v], cd, G1, 0, 0, 0);
+                            if (DMAX > 16) G2 = __builtin_amdgcn_mfma_f64_16x16x4f64(a2v[v] * a2v[v], cd, G2, 0, 0, 0);
+                        }
                     }
                 }
+                wave_lds_fence();   // the next unit is written over this one
             }
-            wave_lds_fence();   // the next tile is written over this one
+            asm volatile("" : "+v"(ynext));   // nothing of the next unit's loads is touched before this point
+            ycur = ynext;
         }
         if (svm && any_fg && (slotl == SL - 1 || tile + 1 == last)) {
             // lane SL k + j stores the word of problem k for tile (tile - slotl + j): SL consecutive words per problem
@@ -556,8 +607,6 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass_mfma(int64_t n, int64_
         w0 = w1;
         w1 = word_ok(tile + 2) ? w2 : 0ull;
         rows_cur = rows_next;
-        asm volatile("" : "+v"(ynext));   // nothing of the next tile's loads is touched before this point
-        ycur = ynext;
 #pragma unroll
         for (int k = 0; k < KT; ++k) wk[k] = wkn[k];
     }
@@ -902,20 +951,20 @@ PassPair pass_for_shape(const Shape &s, bool vec)
     }
 }
 
-template <int DMAX, int KT>
+template <int DMAX, int KT, int RT>
 PassPair mfma_pass_pair(bool vec)
 {
-    if (vec) return {{k_batch_pass_mfma<true, DMAX, KT, TRON_LOSS_LR>, k_batch_pass_mfma<true, DMAX, KT, TRON_LOSS_L2SVM>}};
-    return {{k_batch_pass_mfma<false, DMAX, KT, TRON_LOSS_LR>, k_batch_pass_mfma<false, DMAX, KT, TRON_LOSS_L2SVM>}};
+    if (vec) return {{k_batch_pass_mfma<true, DMAX, KT, TRON_LOSS_LR, RT>, k_batch_pass_mfma<true, DMAX, KT, TRON_LOSS_L2SVM, RT>}};
+    return {{k_batch_pass_mfma<false, DMAX, KT, TRON_LOSS_LR, RT>, k_batch_pass_mfma<false, DMAX, KT, TRON_LOSS_L2SVM, RT>}};
 }
 
-template <int KT>
+template <int KT, int RT>
 PassPair mfma_pass_for(int64_t d)
 {
     const bool vec = d % 2 == 0;
-    if (d <= 16) return mfma_pass_pair<16, KT>(vec);
-    if (d <= 24) return mfma_pass_pair<24, KT>(vec);
-    return mfma_pass_pair<32, KT>(vec);
+    if (d <= 16) return mfma_pass_pair<16, KT, RT>(vec);
+    if (d <= 24) return mfma_pass_pair<24, KT, RT>(vec);
+    return mfma_pass_pair<32, KT, RT>(vec);
 }
 
 }  // namespace
@@ -1065,8 +1114,14 @@ static int batch_create_impl(tron_dataset *ds, int K, const uint32_t *member, in
     if (g_tuning.batch_mfma > 0 || K > 8) {
         // the pass as matrix instructions, 8 or 16 problem columns: the tile of X and the exchange area of every wavefront in LDS
         b->KT = (K <= 8) ? 8 : 16;
-        b->pass = (b->KT == 8) ? mfma_pass_for<8>(d) : mfma_pass_for<16>(d);
-        b->pass_lds = sizeof(double) * kWavesPerBlock * (size_t)mfma_wave_doubles(d <= 16 ? 16 : (d <= 24 ? 24 : 32), K);
+        // whole 64-row tiles in LDS where two workgroups per CU still fit (measured faster there: the loads of the next
+        // tile are asked for a whole tile ahead), half tiles otherwise
+        const int dmax = d <= 16 ? 16 : (d <= 24 ? 24 : 32);
+        const size_t lds64 = sizeof(double) * kWavesPerBlock * (size_t)mfma_wave_doubles(dmax, K, 64);
+        const int rt = g_tuning.batch_mfma_rows != 0 ? (int)g_tuning.batch_mfma_rows : (lds64 <= 80 * 1024 ? 64 : 32);
+        if (rt == 64) b->pass = (b->KT == 8) ? mfma_pass_for<8, 64>(d) : mfma_pass_for<16, 64>(d);
+        else b->pass = (b->KT == 8) ? mfma_pass_for<8, 32>(d) : mfma_pass_for<16, 32>(d);
+        b->pass_lds = sizeof(double) * kWavesPerBlock * (size_t)mfma_wave_doubles(dmax, K, rt);
         if (b->pass_lds < sizeof(double) * kWavesPerBlock * 32 * 16) b->pass_lds = sizeof(double) * kWavesPerBlock * 32 * 16;   // the final sums of the four wavefronts
         for (int l = 0; l < 2; ++l)
             TRON_B(hipFuncSetAttribute(reinterpret_cast<const void *>(b->pass.fn[l]), hipFuncAttributeMaxDynamicSharedMemorySize, (int)b->pass_lds));
