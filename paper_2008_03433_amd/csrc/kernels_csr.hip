@@ -172,15 +172,41 @@ int csr_plan_build(CsrPlan &A, int64_t rows, int64_t cols, const int64_t *h_rowp
     }
     hot = hot && A.P > 1;   // LDS tables belong to the column ranges of large matrices
     if (A.plain) {
-        const int64_t nb64 = std::max<int64_t>(1, (A.nnz + kChunk - 1) / kChunk);
+        // A row that fits into a chunk never straddles a chunk boundary: one that would is moved to the start of the next
+        // chunk.  The gap it leaves is counted to the row before, filled with zeros at that row's last column (they add
+        // 0 times an entry of the vector the row reads anyway).  Only rows longer than a chunk are still completed by the
+        // fix-up kernel; for matrices of short rows that launch disappears.
+        std::vector<int64_t> rp((size_t)rows + 1);
+        int64_t at = 0;
+        for (int64_t r = 0; r < rows; ++r) {
+            const int64_t len = h_rowptr[r + 1] - h_rowptr[r];
+            if (len > 0 && len <= kChunk && at % kChunk + len > kChunk) at = (at / kChunk + 1) * kChunk;
+            rp[r] = at;
+            at += len;
+        }
+        rp[rows] = at;
+        const int64_t stored = at;
+        std::vector<int32_t> pcol((size_t)stored);
+        std::vector<double> pval((size_t)stored);
+        {
+            int64_t filled = 0;
+            int32_t last_col = 0;
+            for (int64_t r = 0; r < rows; ++r) {
+                for (; filled < rp[r]; ++filled) { pcol[filled] = last_col; pval[filled] = 0.0; }
+                for (int64_t k = h_rowptr[r]; k < h_rowptr[r + 1]; ++k, ++filled) { pcol[filled] = h_col[k]; pval[filled] = h_val[k]; }
+                if (h_rowptr[r + 1] > h_rowptr[r]) last_col = h_col[h_rowptr[r + 1] - 1];
+            }
+        }
+        const int64_t nb64 = std::max<int64_t>(1, (stored + kChunk - 1) / kChunk);
         if (nb64 > 0x7ffffff0) { set_error("matrix too large: %lld chunks", (long long)nb64); return TRON_EINVAL; }
         A.nblocks = (int)nb64;
-        A.part_base[0] = 0; A.part_nnz[0] = A.nnz; A.part_chunk0[0] = 0; A.part_nchunks[0] = A.nblocks;
+        A.part_base[0] = 0; A.part_nnz[0] = stored; A.part_chunk0[0] = 0; A.part_nchunks[0] = A.nblocks;
         A.max_chunks = A.nblocks;
-        plan_chunks(h_rowptr, rows, A.nnz, A.nblocks, 0, 0, row_lo, fix_row, fix_part, fix_b0, fix_cnt);
-        TRON_TRY(upload(&A.rowptr, h_rowptr, (size_t)rows + 1, st));
-        TRON_TRY(upload(&A.col, h_col, (size_t)A.nnz, st));
-        TRON_TRY(upload(&A.val, h_val, (size_t)A.nnz, st));
+        plan_chunks(rp.data(), rows, stored, A.nblocks, 0, 0, row_lo, fix_row, fix_part, fix_b0, fix_cnt);
+        TRON_TRY(upload(&A.rowptr, rp.data(), (size_t)rows + 1, st));
+        TRON_TRY(upload(&A.col, pcol.data(), (size_t)stored, st));
+        TRON_TRY(upload(&A.val, pval.data(), (size_t)stored, st));
+        TRON_HIP(hipStreamSynchronize(st));   // the staging vectors go out of scope
     } else {
         const int P = A.P;
         std::vector<int64_t> colcount((size_t)cols + 1, 0);
@@ -1729,10 +1755,10 @@ static int launch_plain(tron_dataset *ds, const CsrPlan &A, int slot, const doub
     {
         ProfScope ps(ds, slot);
         if (square)
-            hipLaunchKernelGGL((k_csr_spmv<EPI, true>), dim3(A.nblocks), dim3(kBlock), 0, ds->stream, A.nnz, A.rowptr, A.col, A.val,
+            hipLaunchKernelGGL((k_csr_spmv<EPI, true>), dim3(A.nblocks), dim3(kBlock), 0, ds->stream, A.part_nnz[0], A.rowptr, A.col, A.val,
                                A.row_lo, x, yout, aux, alpha, A.carry);
         else
-            hipLaunchKernelGGL((k_csr_spmv<EPI, false>), dim3(A.nblocks), dim3(kBlock), 0, ds->stream, A.nnz, A.rowptr, A.col, A.val,
+            hipLaunchKernelGGL((k_csr_spmv<EPI, false>), dim3(A.nblocks), dim3(kBlock), 0, ds->stream, A.part_nnz[0], A.rowptr, A.col, A.val,
                                A.row_lo, x, yout, aux, alpha, A.carry);
         TRON_HIP(hipGetLastError());
     }
@@ -1929,7 +1955,7 @@ PlanBytes plan_bytes(const CsrPlan &A)
     const int64_t vbytes = A.unit ? 0 : 8;   // value stream per stored entry
     if (A.plain) {
         // plain CSR in chunks: columns and values once, row offsets, the gathered vector and the result once each
-        b.ranges = A.nnz * (4 + 8) + 8 * (A.rows + 1) + 4 * ((int64_t)A.nblocks + 1) + 8 * A.cols + 8 * A.rows;
+        b.ranges = A.part_nnz[0] * (4 + 8) + 8 * (A.rows + 1) + 4 * ((int64_t)A.nblocks + 1) + 8 * A.cols + 8 * A.rows;
         return b;
     }
     const int64_t per_chunk = kBlock /* flag bits */ + (int64_t)sizeof(int4) /* table entry */ + 8 /* carry */;
