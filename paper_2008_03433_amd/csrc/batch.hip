@@ -1,9 +1,10 @@
 // Several problems of Section 3 of the paper over one resident dense matrix: the cross-validation setting of
 // Section 2.1 (three folds, nested cross-validation inside each), where the problems differ only in the instances
 // they train on and in C.  The problems advance in lock-step rounds.  A round is
-//   1. one pass over X (k_batch_pass) that serves every problem's pending request -- X^T (D (X v)) for a problem inside
-//      its CG iteration, or z = X w / loss / D / X^T zhat for one at a trial point (Table 1) -- so that an element of X
-//      read from HBM is used by all of them;
+//   1. one pass over X (k_batch_pass on the vector units, up to eight problems; k_batch_pass_mfma on the fp64 matrix
+//      units, up to sixteen) that serves every problem's pending request -- X^T (D (X v)) for a problem inside its CG
+//      iteration, or z = X w / loss / D / X^T zhat for one at a trial point (Table 1) -- so that an element of X read
+//      from HBM is used by all of them;
 //   2. one small kernel (k_batch_advance) that adds up the pass's per-workgroup partial sums and then runs, for every
 //      problem, the step of Algorithm 1 / of the truncated CG iteration that was waiting for the product, and posts
 //      the problem's next request.
