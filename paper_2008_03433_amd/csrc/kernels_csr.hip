@@ -6,10 +6,11 @@
 // features give the transposed copy rows of length ~n next to millions of length 0/1): a workgroup
 // streams one chunk of kChunk nonzeros with 16-byte non-temporal loads that cover whole cache lines,
 // multiplies them by the gathered vector entries and parks the products in LDS; the sums of the row
-// pieces ("segments") of the chunk come out of a segmented scan (see chunk_runs).  A row that runs past
-// the end of its chunk receives the rest from the `carry` of the following chunks in a small fix-up
-// kernel, in a fixed order -- nothing is ever added in an order that depends on timing, so results are
-// bit-reproducible (the one atomic instruction in use, the LDS add of the unit tile kernel, has a fixed order too).
+// pieces ("segments") of the chunk come out of a segmented scan (see chunk_runs).  Rows and segments that fit
+// into a chunk are stored so that they never cross a chunk boundary; one longer than a chunk receives the rest
+// from the `carry` of the following chunks in a small fix-up kernel, in a fixed order -- nothing is ever added in
+// an order that depends on timing, so results are bit-reproducible (the one atomic instruction in use, the LDS
+// add of the unit tile kernel, has a fixed order too).
 //
 // The gathers decide the speed.  A gather that misses the vector L1 costs an L2 request of its own, and
 // a CU keeps only ~100 of them in flight; one that misses L2 as well pulls a 64-byte sector for 8 useful
