@@ -329,6 +329,8 @@ TRON_API int tron_probe_read_bandwidth(const double *src_dev, int64_t count, int
  * "cg_speculate" (-1/0/1), read at every solve: the host-driven CG loop enqueues the kernels of iteration k + 1 before it
  *                has read the scalars of iteration k (1), or only after (0); -1: ahead when a Hessian-vector product moves
  *                at most 64 MB.  Same iterates either way: the kernels of an iteration that turns out not to exist change nothing.
+ *                Under the same setting the outer loop forms the sparse gradient at a trial point before it knows whether
+ *                the step is accepted (a rejected step leaves it unused; n_grad counts accepted steps' gradients only).
  * "fuse_reductions" (-1/0/1), read at every call: the second stage of every two-stage reduction (sum of the
  *   per-workgroup partial sums) is done by the workgroup of the producing kernel that finishes last (found through a ticket
  *   counter; the sums themselves are added in a fixed order, so results do not change) instead of by a launch of its own:

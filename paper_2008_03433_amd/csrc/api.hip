@@ -180,6 +180,7 @@ void tron_dataset_destroy(tron_dataset *ds)
     for (double *p : ds->sv) hipFree(p);
     for (hipEvent_t e : ds->cg_event)
         if (e) hipEventDestroy(e);
+    hipFree(ds->cg_partials);
     ds->prof.destroy();
     delete ds;
 }

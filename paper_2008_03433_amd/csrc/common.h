@@ -300,6 +300,7 @@ struct tron_dataset {
     // solver vectors (d each), allocated on first tron_solve
     double *sv[9] = {nullptr};
     hipEvent_t cg_event[2] = {nullptr, nullptr};   // end of a CG iteration's kernels, by iteration parity
+    double *cg_partials = nullptr;   // kCgRegions x kMaxGrid: per-workgroup sums that the next CG kernel adds up itself
 
     tron::Profiler prof;
 };
@@ -343,6 +344,12 @@ int read_scalars(tron_dataset *ds, int count);  // stream sync; then scal_host[0
 // trust-region boundary is in kScalFlag + it % 2).  Two slots each, so that the kernels of iteration it + 1 can be
 // enqueued before the host has read what iteration it left.
 constexpr int kScalRR = 6, kScalFlag = 8;
+// The step and direction kernels leave per-workgroup partial sums in regions of cg_partials, kMaxGrid doubles each.  With
+// at most kCgDirectGrid workgroups the consumer adds them up itself (every workgroup, in the order of the second-stage
+// kernel, so all get the same bits), which saves the two launches that would do nothing else; above that every workgroup
+// re-reading every partial sum costs more than those launches, and the second-stage kernel runs in between.
+enum { CGP_RR = 0, CGP_PP, CGP_SP, CGP_SS, kCgRegions };
+constexpr int kCgDirectGrid = 512;
 // rr0 >= 0: also starts a CG run (scalar kScalRR = rr0, both flags cleared)
 int cg_init(tron_dataset *ds, const double *g, const double *M, double *s, double *r, double *p, int first = -1, double rr0 = -1.0);  // M: slot0 = g.(g/M); returns #partials
 // What the CG step kernel needs to form the step length itself from the device copy of the scalars (slot 0 = p.Hp,
@@ -354,9 +361,15 @@ struct CgStepCtl {
     double tol, delta;   // tol = xi times the length of the gradient the run started from
     int it;              // iteration number, from 0 (then s = 0 and p.p = r.r)
 };
-int cg_step(tron_dataset *ds, const CgStepCtl &ctl, const double *p, const double *Hp, const double *M, double *s, double *r);  // r.r | r.(r/M) to its slot
-// beta = (new r.r) / (old r.r), both from the device copy
-int cg_dir(tron_dataset *ds, const CgStepCtl &ctl, const double *r, const double *s, const double *M, double *p, int first = -1);  // slots: p.p, s.p, s.s (M-weighted)
+// n_dir: workgroups of the direction kernel before (its partial sums of p.p, s.p, s.s; unused when it == 0), 0 = take the
+// sums from scalars 1..3.  Returns its own number of workgroups: the partial sums of r.r | r.(r/M) in region CGP_RR.
+int cg_step(tron_dataset *ds, const CgStepCtl &ctl, int n_dir, const double *p, const double *Hp, const double *M, double *s, double *r);
+// n_step: workgroups of the step kernel before: adds up the new r.r and leaves it in its scalar slot (host and device copy);
+// 0 = the slot holds it already.  beta = (new r.r) / (old r.r); partial sums of p.p, s.p, s.s (M-weighted) in their regions.
+// Returns its number of workgroups.
+int cg_dir(tron_dataset *ds, const CgStepCtl &ctl, int n_step, const double *r, const double *s, const double *M, double *p);
+// the second stage as a launch of its own, for `count` partial sums in each of nregions regions of cg_partials from `region` on
+int reduce_cg_regions(tron_dataset *ds, int region, int nregions, int count, int first_scalar);
 int trial_point(tron_dataset *ds, const double *w, const double *s, const double *g, const double *r, const double *M,
                 double *wnew, int first = -1);  // wnew = w+s; slots: g.s, s.r, s.s | s.Ms
 int probe_read(const double *src, int64_t count, int reps, hipStream_t st, double *ms, double *checksum);
@@ -427,7 +440,9 @@ int dense_device_solve(tron_dataset *ds, const tron_params &P, double *w_dev, tr
 void dense_device_release(tron_dataset *ds);
 
 // ---- solver.hip
+int fun_enqueue(tron_dataset *ds, int loss, const double *w, int Dslot);                        // scalars[0]=sum of loss terms, [1]=w.w, no sync
 int fun_eval(tron_dataset *ds, int loss, double C, const double *w, int Dslot, double *f_out);  // syncs
+int grad_enqueue(tron_dataset *ds, double C, const double *w, double *g, int scalar);           // scalars[scalar]=g.g, no sync
 // out = 1 + C sum_i D_i x_ij^2 with D = Dbuf[Dslot] (the diagonal of the Hessian; C scaled by the caller for a blend). Enqueue only.
 int hess_diag_enqueue(tron_dataset *ds, double C, int Dslot, double *out);
 int grad_eval(tron_dataset *ds, double C, const double *w, double *g, double *gnorm_out);        // syncs

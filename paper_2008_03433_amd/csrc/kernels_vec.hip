@@ -50,6 +50,15 @@ int reduce_final(tron_dataset *ds, int nslots, int count, int stride, int first_
     return TRON_OK;
 }
 
+int reduce_cg_regions(tron_dataset *ds, int region, int nregions, int count, int first_scalar)
+{
+    ProfScope ps(ds, SLOT_REDUCE_FINAL);
+    hipLaunchKernelGGL(k_reduce_final, dim3(nregions), dim3(kBlock), 0, ds->stream, ds->cg_partials + (size_t)region * kMaxGrid, count, kMaxGrid,
+                       ds->scal_dev, ds->scal_copy, first_scalar);
+    TRON_HIP(hipGetLastError());
+    return TRON_OK;
+}
+
 int read_scalars(tron_dataset *ds, int count)
 {
     (void)count;   // scal_dev is the device address of scal_host: the kernels have written the scalars in place
@@ -200,12 +209,11 @@ __device__ __forceinline__ bool cg_run_ended(const CgStepCtl &c, const double *_
 
 // The step length of a CG iteration from the device copy of the scalars (see CgStepCtl), in the operations and the
 // order the host used to take (no contraction into fused multiply-adds), the same in every thread.
-__device__ __forceinline__ double cg_step_length(const CgStepCtl &c, const double *__restrict__ sc, bool &boundary)
+__device__ __forceinline__ double cg_step_length(const CgStepCtl &c, const double *__restrict__ sc, double pp, double sp, double ss, bool &boundary)
 {
-    const bool first = c.it == 0;
     const double rr = sc[kScalRR + (c.it & 1)];
     const double pHp = sc[0];
-    const double pp = first ? rr : sc[1], sp = first ? 0.0 : sc[2], ss = first ? 0.0 : sc[3];
+    if (c.it == 0) { pp = rr; sp = 0.0; ss = 0.0; }
     const double alpha = rr / pHp;
     // |s + alpha p|^2 from the three dot products kept alongside the vectors
     const double len2 = __dadd_rn(ss, __dmul_rn(alpha, __dadd_rn(__dmul_rn(2.0, sp), __dmul_rn(alpha, pp))));
@@ -216,18 +224,48 @@ __device__ __forceinline__ double cg_step_length(const CgStepCtl &c, const doubl
     return (sp >= 0.0) ? gap / __dadd_rn(sp, rad) : __dadd_rn(rad, -sp) / pp;
 }
 
-// s += a p;  r -= a Hp with a = the step length above;  partial slot 0 = r.r (PRE: r.(r / M));  scalar 4 = a, the
-// iteration's flag slot = whether the step went to the boundary.  Nothing at all if the run had ended.
+// The sum of `count` <= kCgDirectGrid per-workgroup partial sums with the order and arithmetic of k_reduce_final, formed
+// by every wavefront on its own: each lane plays its thread of each of that kernel's wavefronts in turn.  No barrier, no
+// LDS, and the loads of several such sums can be in flight together.
+static_assert(kCgDirectGrid <= 2 * kBlock, "two partial sums per thread of the second-stage kernel at most");
+__device__ __forceinline__ double sum_of_partials(const double *__restrict__ p, int count)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    double a[kWavesPerBlock];
+#pragma unroll
+    for (int w = 0; w < kWavesPerBlock; ++w) {
+        const int b = w * kWave + lane;
+        const double x = p[b < count ? b : 0], y = p[b + kBlock < count ? b + kBlock : 0];
+        a[w] = (0.0 + (b < count ? x : 0.0)) + (b + kBlock < count ? y : 0.0);
+    }
+    double t = 0.0;
+#pragma unroll
+    for (int w = 0; w < kWavesPerBlock; ++w) t += wave_sum(a[w]);
+    return t;
+}
+
+// s += a p;  r -= a Hp with a = the step length above;  region CGP_RR = partial sums of r.r (PRE: r.(r / M));  scalar 4 = a,
+// the iteration's flag slot = whether the step went to the boundary.  Nothing at all if the run had ended.
 template <bool PRE>
-__global__ __launch_bounds__(kBlock) void k_cg_step(int64_t d, CgStepCtl ctl, const double *__restrict__ sc, const double *__restrict__ p,
+__global__ __launch_bounds__(kBlock) void k_cg_step(int64_t d, CgStepCtl ctl, int n_dir, const double *__restrict__ sc, const double *__restrict__ p,
                                                     const double *__restrict__ Hp, const double *__restrict__ M,
-                                                    double *__restrict__ s, double *__restrict__ r, double *__restrict__ partials,
-                                                    double *__restrict__ scal, double *__restrict__ scal_copy, Finish fin)
+                                                    double *__restrict__ s, double *__restrict__ r, double *__restrict__ cgp,
+                                                    double *__restrict__ scal, double *__restrict__ scal_copy)
 {
     __shared__ double lds[kWavesPerBlock];
     if (cg_run_ended(ctl, sc)) return;
+    double pp = 0.0, sp = 0.0, ss = 0.0;
+    if (ctl.it > 0 && n_dir > 0) {   // what the direction kernel before left, one partial sum per workgroup
+        pp = sum_of_partials(cgp + (size_t)CGP_PP * kMaxGrid, n_dir);
+        sp = sum_of_partials(cgp + (size_t)CGP_SP * kMaxGrid, n_dir);
+        ss = sum_of_partials(cgp + (size_t)CGP_SS * kMaxGrid, n_dir);
+    } else if (ctl.it > 0) {   // added up by a launch in between
+        pp = sc[1];
+        sp = sc[2];
+        ss = sc[3];
+    }
     bool boundary;
-    const double alpha = cg_step_length(ctl, sc, boundary);
+    const double alpha = cg_step_length(ctl, sc, pp, sp, ss, boundary);
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         scal[4] = alpha;
         scal[kScalFlag + (ctl.it & 1)] = boundary ? 1.0 : 0.0;
@@ -241,31 +279,38 @@ __global__ __launch_bounds__(kBlock) void k_cg_step(int64_t d, CgStepCtl ctl, co
         acc += rj * (PRE ? rj / M[j] : rj);
     }
     acc = block_sum(acc, lds);
-    if (threadIdx.x == 0) partials[blockIdx.x] = acc;
-    finish_partials<1>(fin, partials, 0, lds);
+    if (threadIdx.x == 0) cgp[(size_t)CGP_RR * kMaxGrid + blockIdx.x] = acc;
 }
 
-int cg_step(tron_dataset *ds, const CgStepCtl &ctl, const double *p, const double *Hp, const double *M, double *s, double *r)
+int cg_step(tron_dataset *ds, const CgStepCtl &ctl, int n_dir, const double *p, const double *Hp, const double *M, double *s, double *r)
 {
     ProfScope ps(ds, SLOT_CG_VEC);
     const int g = vec_grid(ds->d);
-    const Finish fin = finish_for(ds, kScalRR + ((ctl.it + 1) & 1), g);
-    if (M) hipLaunchKernelGGL(k_cg_step<true>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, ctl, ds->scal_copy, p, Hp, M, s, r, ds->partials, ds->scal_dev, ds->scal_copy, fin);
-    else hipLaunchKernelGGL(k_cg_step<false>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, ctl, ds->scal_copy, p, Hp, M, s, r, ds->partials, ds->scal_dev, ds->scal_copy, fin);
+    if (M) hipLaunchKernelGGL(k_cg_step<true>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, ctl, n_dir, ds->scal_copy, p, Hp, M, s, r, ds->cg_partials, ds->scal_dev, ds->scal_copy);
+    else hipLaunchKernelGGL(k_cg_step<false>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, ctl, n_dir, ds->scal_copy, p, Hp, M, s, r, ds->cg_partials, ds->scal_dev, ds->scal_copy);
     TRON_HIP(hipGetLastError());
     return g;
 }
 
-// p = r + beta p (PRE: r / M + beta p) with beta = (the new r.r) / (the old r.r), both from the device copy;
-// partial slots: 0 = p.p, 1 = s.p, 2 = s.s (PRE: M-weighted).  Nothing at all if the run ended with this iteration.
+// p = r + beta p (PRE: r / M + beta p) with beta = (the new r.r) / (the old r.r): the new one is added up here from the
+// step kernel's partial sums and left in its scalar slot for the host and the next step; regions CGP_PP, CGP_SP, CGP_SS =
+// partial sums of p.p, s.p, s.s (PRE: M-weighted).  Nothing at all if the run had ended before this iteration; only the
+// new r.r if it ends with it.
 template <bool PRE>
-__global__ __launch_bounds__(kBlock) void k_cg_dir(int64_t d, CgStepCtl ctl, const double *__restrict__ sc, const double *__restrict__ r,
+__global__ __launch_bounds__(kBlock) void k_cg_dir(int64_t d, CgStepCtl ctl, int n_step, const double *__restrict__ sc, const double *__restrict__ r,
                                                    const double *__restrict__ s, const double *__restrict__ M,
-                                                   double *__restrict__ p, double *__restrict__ partials, int stride, Finish fin)
+                                                   double *__restrict__ p, double *__restrict__ cgp, double *__restrict__ scal,
+                                                   double *__restrict__ scal_copy)
 {
     __shared__ double lds[kWavesPerBlock];
-    const double rr_old = sc[kScalRR + (ctl.it & 1)], rr_new = sc[kScalRR + ((ctl.it + 1) & 1)];
-    if (cg_run_ended(ctl, sc) || sc[kScalFlag + (ctl.it & 1)] != 0.0 || sqrt(rr_new) <= ctl.tol) return;
+    if (cg_run_ended(ctl, sc)) return;
+    const double rr_old = sc[kScalRR + (ctl.it & 1)];
+    const double rr_new = n_step > 0 ? sum_of_partials(cgp + (size_t)CGP_RR * kMaxGrid, n_step) : sc[kScalRR + ((ctl.it + 1) & 1)];
+    if (n_step > 0 && blockIdx.x == 0 && threadIdx.x == 0) {   // read by the kernels after this one only (this one reads the other slot)
+        scal[kScalRR + ((ctl.it + 1) & 1)] = rr_new;
+        scal_copy[kScalRR + ((ctl.it + 1) & 1)] = rr_new;
+    }
+    if (sc[kScalFlag + (ctl.it & 1)] != 0.0 || sqrt(rr_new) <= ctl.tol) return;
     const double beta = rr_new / rr_old;
     double pp = 0.0, sp = 0.0, ss = 0.0;
     for (int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x; j < d; j += (int64_t)gridDim.x * kBlock) {
@@ -284,21 +329,19 @@ __global__ __launch_bounds__(kBlock) void k_cg_dir(int64_t d, CgStepCtl ctl, con
         }
     }
     pp = block_sum(pp, lds);
-    if (threadIdx.x == 0) partials[blockIdx.x] = pp;
+    if (threadIdx.x == 0) cgp[(size_t)CGP_PP * kMaxGrid + blockIdx.x] = pp;
     sp = block_sum(sp, lds);
-    if (threadIdx.x == 0) partials[stride + blockIdx.x] = sp;
+    if (threadIdx.x == 0) cgp[(size_t)CGP_SP * kMaxGrid + blockIdx.x] = sp;
     ss = block_sum(ss, lds);
-    if (threadIdx.x == 0) partials[2 * stride + blockIdx.x] = ss;
-    finish_partials<3>(fin, partials, stride, lds);
+    if (threadIdx.x == 0) cgp[(size_t)CGP_SS * kMaxGrid + blockIdx.x] = ss;
 }
 
-int cg_dir(tron_dataset *ds, const CgStepCtl &ctl, const double *r, const double *s, const double *M, double *p, int first)
+int cg_dir(tron_dataset *ds, const CgStepCtl &ctl, int n_step, const double *r, const double *s, const double *M, double *p)
 {
     ProfScope ps(ds, SLOT_CG_VEC);
     const int g = vec_grid(ds->d);
-    const Finish fin = finish_for(ds, first, g);
-    if (M) hipLaunchKernelGGL(k_cg_dir<true>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, ctl, ds->scal_copy, r, s, M, p, ds->partials, kMaxGrid, fin);
-    else hipLaunchKernelGGL(k_cg_dir<false>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, ctl, ds->scal_copy, r, s, M, p, ds->partials, kMaxGrid, fin);
+    if (M) hipLaunchKernelGGL(k_cg_dir<true>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, ctl, n_step, ds->scal_copy, r, s, M, p, ds->cg_partials, ds->scal_dev, ds->scal_copy);
+    else hipLaunchKernelGGL(k_cg_dir<false>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, ctl, n_step, ds->scal_copy, r, s, M, p, ds->cg_partials, ds->scal_dev, ds->scal_copy);
     TRON_HIP(hipGetLastError());
     return g;
 }

@@ -10,7 +10,7 @@ namespace tron {
 
 // f(w) for the sparse layout: z = X w, loss terms (zhat, D into Dbuf[Dslot]), f = 1/2 w.w + C sum loss.
 // The dense layout computes the same together with the gradient sums in one fused pass.
-int fun_eval(tron_dataset *ds, int loss, double C, const double *w, int Dslot, double *f_out)
+int fun_enqueue(tron_dataset *ds, int loss, const double *w, int Dslot)   // scalar 0 = sum of the loss terms, scalar 1 = w.w
 {
     // with unit plans zhat is stored already multiplied by the instances' values, as the transposed plan gathers it
     const int gl = spmv_loss(ds, ds->fwd, SLOT_SPMV_FWD, loss, w, ds->z, ds->zhat, ds->Dbuf[Dslot], ds->bwd.col_scale, 0);
@@ -19,17 +19,29 @@ int fun_eval(tron_dataset *ds, int loss, double C, const double *w, int Dslot, d
     const int gw = dot_partials(ds, ds->d, w, w, nullptr, nullptr, nullptr, nullptr, 1);
     TRON_TRY(gw);
     TRON_TRY(reduce_final(ds, 1, gw, 0, 1));
+    return TRON_OK;
+}
+
+int fun_eval(tron_dataset *ds, int loss, double C, const double *w, int Dslot, double *f_out)
+{
+    TRON_TRY(fun_enqueue(ds, loss, w, Dslot));
     TRON_TRY(read_scalars(ds, 2));
     *f_out = 0.5 * ds->scal_host[1] + C * ds->scal_host[0];
     return TRON_OK;
 }
 
-// g = w + C X^T zhat (zhat from the preceding fun_eval) and |g|
+// g = w + C X^T zhat (zhat from the preceding fun_enqueue); scalar `scalar` = g.g
+int grad_enqueue(tron_dataset *ds, double C, const double *w, double *g, int scalar)
+{
+    const int gg = spmv_axpy(ds, ds->bwd, SLOT_SPMV_BWD, ds->zhat, w, C, true, g, false, ds->bwd.col_scale != nullptr, scalar);
+    TRON_TRY(gg);
+    TRON_TRY(reduce_final(ds, 1, gg, 0, scalar));
+    return TRON_OK;
+}
+
 int grad_eval(tron_dataset *ds, double C, const double *w, double *g, double *gnorm_out)
 {
-    const int gg = spmv_axpy(ds, ds->bwd, SLOT_SPMV_BWD, ds->zhat, w, C, true, g, false, ds->bwd.col_scale != nullptr, 0);
-    TRON_TRY(gg);
-    TRON_TRY(reduce_final(ds, 1, gg, 0, 0));
+    TRON_TRY(grad_enqueue(ds, C, w, g, 0));
     TRON_TRY(read_scalars(ds, 1));
     *gnorm_out = std::sqrt(ds->scal_host[0]);
     return TRON_OK;
@@ -63,22 +75,41 @@ int ensure_solver_vectors(tron_dataset *ds, bool precond)
 {
     for (int k = 0; k < V_COUNT; ++k)
         if (!ds->sv[k] && (k != V_M || precond)) TRON_HIP(hipMalloc(reinterpret_cast<void **>(&ds->sv[k]), sizeof(double) * ds->d));
+    if (!ds->cg_partials) TRON_HIP(hipMalloc(reinterpret_cast<void **>(&ds->cg_partials), sizeof(double) * kCgRegions * kMaxGrid));
     return TRON_OK;
 }
 
-// f and (dense: also the gradient, into gout) at w; D goes to Dbuf[Dslot]
-int eval_f(tron_dataset *ds, const tron_params &P, const double *w, int Dslot, double *gout, double *f, double *gnorm_dense)
+// Scalar slots of the outer loop, apart from 0..3 of the evaluation: what one wait of the host brings back together.
+constexpr int kScalGG = 2;      // g.g of the sparse gradient (the dense pass leaves it there as well)
+constexpr int kScalTrial = 10;  // g.s, s.r, s.s of the trial point
+constexpr int kScalW0 = 13;     // w0.w0
+
+// Whether a product with X is cheap enough to be spent on a guess (kernels enqueued before the host knows that their
+// result is wanted), as against one idle gap of the device per wait of the host.
+bool products_cheap(const tron_dataset *ds)
 {
+    const double hv_bytes = ds->dense ? 8.0 * (double)ds->n * (double)ds->d : 24.0 * (double)ds->fwd.nnz;
+    return hv_bytes <= 64e6;
+}
+
+// f at w, D into Dbuf[Dslot], and -- dense always, sparse if with_grad -- the gradient into gout.  Enqueue only.
+int eval_enqueue(tron_dataset *ds, const tron_params &P, const double *w, int Dslot, double *gout, bool with_grad)
+{
+    if (ds->dense) return dense_fun_grad(ds, P.loss, P.C, w, Dslot, gout);
+    TRON_TRY(fun_enqueue(ds, P.loss, w, Dslot));
+    if (with_grad) TRON_TRY(grad_enqueue(ds, P.C, w, gout, kScalGG));
+    return TRON_OK;
+}
+
+// What eval_enqueue's kernels left, after a wait; *gnorm only where the gradient was formed.
+void eval_result(tron_dataset *ds, const tron_params &P, int Dslot, bool with_grad, double *f, double *gnorm)
+{
+    *f = 0.5 * ds->scal_host[1] + P.C * ds->scal_host[0];
     if (ds->dense) {
-        TRON_TRY(dense_fun_grad(ds, P.loss, P.C, w, Dslot, gout));
-        TRON_TRY(read_scalars(ds, 4));
         ds->active_frac[Dslot] = ds->scal_host[3] / (double)ds->n;
         ds->active_count[Dslot] = (int64_t)ds->scal_host[3];
-        *f = 0.5 * ds->scal_host[1] + P.C * ds->scal_host[0];
-        *gnorm_dense = std::sqrt(ds->scal_host[2]);
-        return TRON_OK;
     }
-    return fun_eval(ds, P.loss, P.C, w, Dslot, f);
+    if (ds->dense || with_grad) *gnorm = std::sqrt(ds->scal_host[kScalGG]);
 }
 
 // Steihaug-Toint truncated CG on q(s) = g.s + 1/2 s.H s inside |s| <= delta.
@@ -102,18 +133,21 @@ int cg_solve(tron_dataset *ds, const tron_params &P, const double *M, double del
         if (!e) TRON_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
     TRON_TRY(cg_init(ds, g, M, s, r, p, -1, rr0));
     if (std::sqrt(rr0) <= tol) return TRON_OK;
-    const double hv_bytes = ds->dense ? 8.0 * (double)ds->n * (double)ds->d : 24.0 * (double)ds->fwd.nnz;
-    const bool ahead = g_tuning.cg_speculate > 0 || (g_tuning.cg_speculate < 0 && hv_bytes <= 64e6);
+    const bool ahead = g_tuning.cg_speculate > 0 || (g_tuning.cg_speculate < 0 && products_cheap(ds));
+    int n_dir = 0;   // workgroups of the direction kernel enqueued last
     auto enqueue = [&](int it) -> int {
-        TRON_TRY(hv_enqueue(ds, P.C, p, Hp));   // scalar 0 = p.Hp; scalars 1..3 = p.p, s.p, s.s of the direction update before
+        TRON_TRY(hv_enqueue(ds, P.C, p, Hp));   // scalar 0 = p.Hp
         const CgStepCtl ctl{tol, delta, it};
-        const int g1 = cg_step(ds, ctl, p, Hp, M, s, r);
+        const int g1 = cg_step(ds, ctl, n_dir, p, Hp, M, s, r);
         TRON_TRY(g1);
-        TRON_TRY(reduce_final(ds, 1, g1, 0, kScalRR + ((it + 1) & 1)));   // the new r.r
-        if (it + 1 < P.max_cg) {
-            const int g2 = cg_dir(ds, ctl, r, s, M, p, 1);
+        const bool direct = g1 <= kCgDirectGrid;   // the consumer adds up the partial sums itself
+        const bool last = it + 1 >= P.max_cg;      // the last iteration allowed: no direction after it
+        if (!direct || last) TRON_TRY(reduce_cg_regions(ds, CGP_RR, 1, g1, kScalRR + ((it + 1) & 1)));
+        if (!last) {
+            const int g2 = cg_dir(ds, ctl, direct ? g1 : 0, r, s, M, p);
             TRON_TRY(g2);
-            TRON_TRY(reduce_final(ds, 3, g2, kMaxGrid, 1));
+            if (!direct) TRON_TRY(reduce_cg_regions(ds, CGP_PP, 3, g2, 1));
+            n_dir = direct ? g2 : 0;
         }
         TRON_HIP(hipEventRecord(ds->cg_event[it & 1], ds->stream));
         return TRON_OK;
@@ -187,30 +221,33 @@ extern "C" int tron_solve(tron_dataset *ds, const tron_params *params, double *w
     double *s = ds->sv[V_S], *r = ds->sv[V_R];
     TRON_HIP(hipMemcpyAsync(w, w_dev, dbytes, hipMemcpyDeviceToDevice, ds->stream));
 
-    // |grad f(0)|: the reference of the stopping test.  When w0 = 0 it is the first gradient itself.
-    {
-        const int gz = dot_partials(ds, ds->d, w, w, nullptr, nullptr, nullptr, nullptr, 0);
-        TRON_TRY(gz);
-        TRON_TRY(reduce_final(ds, 1, gz, 0, 0));
-        TRON_TRY(read_scalars(ds, 1));
-        if (ds->scal_host[0] != 0.0) {
-            double f0, gn0 = 0.0;
-            TRON_HIP(hipMemsetAsync(wnew, 0, dbytes, ds->stream));
-            TRON_TRY(eval_f(ds, P, wnew, 0, gnew, &f0, &gn0));
-            if (!ds->dense) TRON_TRY(grad_eval(ds, P.C, wnew, gnew, &gn0));
-            res->gnorm0 = gn0;
-            res->n_fun++;
-            res->n_grad++;
-        }
-    }
+    // f and the gradient at w0, and whether w0 = 0, behind one wait
     ds->Dcur = 0;
     ds->have_D = false;
     double f, gnorm = 0.0;
-    TRON_TRY(eval_f(ds, P, w, ds->Dcur, g, &f, &gnorm));
-    if (!ds->dense) TRON_TRY(grad_eval(ds, P.C, w, g, &gnorm));
+    {
+        const int gz = dot_partials(ds, ds->d, w, w, nullptr, nullptr, nullptr, nullptr, kScalW0);
+        TRON_TRY(gz);
+        TRON_TRY(reduce_final(ds, 1, gz, 0, kScalW0));
+    }
+    TRON_TRY(eval_enqueue(ds, P, w, ds->Dcur, g, true));
+    TRON_TRY(read_scalars(ds, kScalars));
+    eval_result(ds, P, ds->Dcur, true, &f, &gnorm);
     ds->have_D = true;
     res->n_fun++;
     res->n_grad++;
+    // |grad f(0)|: the reference of the stopping test.  When w0 = 0 it is the first gradient itself; otherwise one more
+    // evaluation, whose D goes to the buffer of the trial points.
+    if (ds->scal_host[kScalW0] != 0.0) {
+        double f0, gn0 = 0.0;
+        TRON_HIP(hipMemsetAsync(wnew, 0, dbytes, ds->stream));
+        TRON_TRY(eval_enqueue(ds, P, wnew, 1 - ds->Dcur, gnew, true));
+        TRON_TRY(read_scalars(ds, kScalars));
+        eval_result(ds, P, 1 - ds->Dcur, true, &f0, &gn0);
+        res->gnorm0 = gn0;
+        res->n_fun++;
+        res->n_grad++;
+    }
     // L2-SVM with a small active set (a warm start far along): Hessian-vector products over a compacted copy of the active rows
     if (ds->dense && dense_compact_wanted(ds, ds->Dcur, g_tuning.dense_compact > 0 ? 0 : P.max_cg)) TRON_TRY(dense_compact_build(ds, ds->Dcur));
     if (res->gnorm0 == 0.0) res->gnorm0 = gnorm;
@@ -226,17 +263,21 @@ extern "C" int tron_solve(tron_dataset *ds, const tron_params *params, double *w
         TRON_TRY(cg_solve(ds, P, M, delta, gscaled, &ncg, &onb));
         res->n_hv += ncg;
         res->cg_iters_total += ncg;
-        // trial point and the model reduction  pred = -q(s) = -1/2 (g.s - s.r)
-        const int gt = trial_point(ds, w, s, g, r, M, wnew, 0);
+        // The trial point, the model reduction  pred = -q(s) = -1/2 (g.s - s.r)  and f at the trial point behind one wait.
+        // Where products are cheap the sparse gradient at the trial point is formed on the guess that the step will be
+        // accepted (a rejected step leaves it unused; n_grad counts the gradients of accepted steps either way).
+        const int gt = trial_point(ds, w, s, g, r, M, wnew, kScalTrial);
         TRON_TRY(gt);
-        TRON_TRY(reduce_final(ds, 3, gt, kMaxGrid, 0));
-        TRON_TRY(read_scalars(ds, 3));
-        const double gs = ds->scal_host[0], sr = ds->scal_host[1];
-        const double snorm = std::sqrt(ds->scal_host[2]);
+        TRON_TRY(reduce_final(ds, 3, gt, kMaxGrid, kScalTrial));
+        const int trial_slot = 1 - ds->Dcur;   // D of the trial point goes to the other buffer
+        const bool grad_ahead = !ds->dense && g_tuning.cg_speculate != 0 && (g_tuning.cg_speculate > 0 || products_cheap(ds));
+        TRON_TRY(eval_enqueue(ds, P, wnew, trial_slot, gnew, grad_ahead));
+        TRON_TRY(read_scalars(ds, kScalars));
+        const double gs = ds->scal_host[kScalTrial], sr = ds->scal_host[kScalTrial + 1];
+        const double snorm = std::sqrt(ds->scal_host[kScalTrial + 2]);
         const double pred = -0.5 * (gs - sr);
         double fnew, gnorm_new = 0.0;
-        const int trial_slot = 1 - ds->Dcur;
-        TRON_TRY(eval_f(ds, P, wnew, trial_slot, gnew, &fnew, &gnorm_new));  // D of the trial point goes to the other buffer
+        eval_result(ds, P, trial_slot, grad_ahead, &fnew, &gnorm_new);
         res->n_fun++;
         const double ared = f - fnew;
         const bool noise = std::fabs(ared) <= 1e-12 * std::fabs(f) && pred <= 1e-12 * std::fabs(f);
@@ -248,7 +289,7 @@ extern "C" int tron_solve(tron_dataset *ds, const tron_params *params, double *w
         int accepted = 0;
         if (sigma > eta0) {
             accepted = 1;
-            if (!ds->dense) TRON_TRY(grad_eval(ds, P.C, wnew, gnew, &gnorm_new));
+            if (!ds->dense && !grad_ahead) TRON_TRY(grad_eval(ds, P.C, wnew, gnew, &gnorm_new));
             std::swap(w, wnew);
             std::swap(g, gnew);
             ds->Dcur = trial_slot;   // the Hessian now uses D at the accepted point
