@@ -335,6 +335,8 @@ TRON_API int tron_probe_read_bandwidth(const double *src_dev, int64_t count, int
  *   per-workgroup partial sums) is done by the workgroup of the producing kernel that finishes last (found through a ticket
  *   counter; the sums themselves are added in a fixed order, so results do not change) instead of by a launch of its own:
  *   0 never, 1 always, -1 (default) for launches of up to 32 workgroups (vectors of up to 32768 elements).
+ *   (The step and direction kernels of the CG loop are outside this setting: with up to 512 workgroups each adds up the
+ *   other's partial sums itself, in that same order; above, a launch does it.)
  * "dense_compact" (-1/0/1): L2-SVM on a dense matrix with d <= 32: Hessian-vector products run over a compacted copy of the
  *   active rows, X_I of Section 5 of the paper, built on the device (up to n*d more doubles of device memory): 0 never (the
  *   pass over X skips inactive rows instead), 1 whenever some rows are inactive (tron_fun_grad then builds the copy for the
