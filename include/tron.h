@@ -347,6 +347,10 @@ TRON_API int tron_probe_read_bandwidth(const double *src_dev, int64_t count, int
  * "batch_grid" (0..4096): workgroups of the multi-problem pass (0 = as many as are resident at once).
  * "batch_mfma_rows" (0/32/64): rows of X a wavefront of the matrix-unit pass keeps in LDS at a time (0: 64 where two
  *                workgroups per CU still fit, else 32).
+ * "batch_lean" (0/1, default 1): batches created afterwards run a round of the matrix-unit pass in which no problem asks
+ *                for function and gradient (the Hessian-vector calls; inside tron_batch_solve the rounds right after the
+ *                host has looked at the problems' requests) with a kernel compiled without the per-row steps of such
+ *                requests: fewer registers and less LDS per wavefront (half tiles unless "batch_mfma_rows" says otherwise).
  * "batch_mfma" (-1/0/1): batches created afterwards run the multi-problem pass on the fp64 matrix units (1), or on the
  *                vector units where those can hold the batch, i.e. up to eight problems (0, and the default -1).
  * Unknown names or values return TRON_EINVAL.

@@ -639,6 +639,10 @@ int tron_tuning_set(const char *name, int64_t value)
         g_tuning.batch_mfma_rows = value;
         return TRON_OK;
     }
+    if (name && strcmp(name, "batch_lean") == 0 && value >= 0 && value <= 1) {
+        g_tuning.batch_lean = value;
+        return TRON_OK;
+    }
     if (name && strcmp(name, "batch_mfma") == 0 && value >= -1 && value <= 1) {
         g_tuning.batch_mfma = value;
         return TRON_OK;

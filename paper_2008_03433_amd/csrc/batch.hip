@@ -294,8 +294,11 @@ __host__ __device__ constexpr int mfma_wave_doubles(int dmax, int K, int rt) { r
 // RT = rows of X a wavefront keeps in LDS at a time: a whole 64-row tile, or half of one (smaller LDS footprint and
 // fewer registers for the loads in flight, so more wavefronts per SIMD to cover the dependent chains of matrix
 // instructions; the row-per-lane steps then serve 64 / RT problems side by side).
-template <bool VEC, int DMAX, int KT, int LOSS, int RT>
-__global__ __launch_bounds__(kBlock, 2) void k_batch_pass_mfma(int64_t n, int64_t d, const double *__restrict__ X,
+// FG = false: a pass in which no problem asks for function and gradient (the host knows the modes of the round).  The
+// per-row steps, the labels, the loss sums and the new active-set words are compiled out, and the L2-SVM needs no
+// exchange area: fewer registers and less LDS per wavefront, so more wavefronts per SIMD.
+template <bool VEC, int DMAX, int KT, int LOSS, int RT, bool FG>
+__global__ __launch_bounds__(kBlock, FG ? 2 : 3) void k_batch_pass_mfma(int64_t n, int64_t d, const double *__restrict__ X,
                                                             const int8_t *__restrict__ y,
                                                             const BatchCtl *__restrict__ ctl, const uint64_t *__restrict__ member,
                                                             const uint64_t *__restrict__ Dbits_in, uint64_t *Dbits_out,
@@ -328,30 +331,33 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass_mfma(int64_t n, int64_
         any_fg |= mode[k] == MODE_FG;
         any_hv |= mode[k] == MODE_HV;
         any_diag |= mode[k] == MODE_DIAG;
-        any_mul |= mode[k] == MODE_FG || mode[k] == MODE_HV;
+        any_mul |= (FG && mode[k] == MODE_FG) || mode[k] == MODE_HV;
         any_exd |= !svm && (mode[k] == MODE_HV || mode[k] == MODE_DIAG);
     }
+    any_fg = FG && any_fg;
     if (!any) return;
     // The unit in LDS: row r at r S, S = the first length >= d whose rows start in different banks for 16 consecutive rows
     // (16-byte pieces: S = 2 mod 4; 8-byte pieces: S odd).  Every lane copies NP pieces per unit; those past the unit
     // (d < DMAX) are fetched from the first bytes of X and land in the slack behind it.
     constexpr int xs_len = RT * (DMAX + 2) + 16;
     const int S = VEC ? D + ((6 - D % 4) % 4) : (D | 1);
-    double *Xs = dyn + (size_t)wv * mfma_wave_doubles(DMAX, K, RT);
+    constexpr bool kHasEx = FG || !svm;                          // otherwise C is formed where Z lies
+    const int kex = kHasEx ? K : 0;
+    double *Xs = dyn + (size_t)wv * mfma_wave_doubles(DMAX, kex, RT);
     double *Ex = Xs + xs_len;                                    // [problem 0..K-1][row] exchange area
-    for (int i = lane; i < mfma_wave_doubles(DMAX, K, RT); i += kWave) Xs[i] = 0.0;
+    for (int i = lane; i < mfma_wave_doubles(DMAX, kex, RT); i += kWave) Xs[i] = 0.0;
     // this lane in the matrix layouts: g = summation index / row block, p = problem (result column) or row / column of X
     const int p = lane & 15, g = lane >> 4;
     const bool pk = p < K;   // K <= KT
     const int modeM = pk ? ctl->mode[pk ? p : 0] : MODE_IDLE;
-    const bool exM = modeM == MODE_FG || (!svm && (modeM == MODE_HV || modeM == MODE_DIAG));   // C comes out of the exchange area
+    const bool exM = (FG && modeM == MODE_FG) || (!svm && (modeM == MODE_HV || modeM == MODE_DIAG));   // C comes out of the exchange area
     // ... and in the row-per-lane layout: row rowl of the unit, problem sub of a group of PP problems
     const int rowl = lane & (RT - 1), sub = lane / RT;
     double Vop[DMAX / 4];
 #pragma unroll
     for (int kk = 0; kk < DMAX / 4; ++kk) {
         const int f = 4 * kk + g;
-        const bool use = f < D && (modeM == MODE_HV || modeM == MODE_FG);
+        const bool use = f < D && (modeM == MODE_HV || (FG && modeM == MODE_FG));
         const double scale = (svm && modeM == MODE_HV) ? 2.0 : 1.0;
         Vop[kk] = use ? scale * ctl->vec[pk ? p : 0][f] : 0.0;
     }
@@ -568,7 +574,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass_mfma(int64_t n, int64_
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
                         const int r = 16 * s + 4 * v + g;
-                        ev[v] = Ex[(pk ? p : 0) * kExRow + r];
+                        ev[v] = kHasEx ? Ex[(pk ? p : 0) * kExRow + r] : 0.0;
                         a1v[v] = Xs[r * S + p];
                         a2v[v] = (DMAX > 16) ? Xs[r * S + 16 + p] : 0.0;
                     }
@@ -578,8 +584,8 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass_mfma(int64_t n, int64_
                         const double e = (exM && pk) ? ev[v] : 0.0;
                         const bool bit = (bits >> (4 * v)) & 1u;
                         double c;
-                        if (svm) c = (modeM == MODE_HV) ? (bit ? z[v] : 0.0) : ((modeM == MODE_FG) ? e : 0.0);
-                        else c = (modeM == MODE_HV) ? e * z[v] : ((modeM == MODE_FG) ? e : 0.0);
+                        if (svm) c = (modeM == MODE_HV) ? (bit ? z[v] : 0.0) : ((FG && modeM == MODE_FG) ? e : 0.0);
+                        else c = (modeM == MODE_HV) ? e * z[v] : ((FG && modeM == MODE_FG) ? e : 0.0);
                         if (any_mul) {
                             G1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a1v[v], c, G1, 0, 0, 0);
                             if (DMAX > 16) G2 = __builtin_amdgcn_mfma_f64_16x16x4f64(a2v[v], c, G2, 0, 0, 0);
@@ -632,7 +638,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass_mfma(int64_t n, int64_
 #pragma unroll
     for (int k = 0; k < KT; ++k) {
         if (mode[k] == MODE_IDLE) continue;   // uniform over the workgroup
-        const double ls = block_sum(loss[k], lds_red);
+        const double ls = FG ? block_sum(loss[k], lds_red) : 0.0;
         if (threadIdx.x == 0) partials[((int64_t)k * cols + d) * gridDim.x + blockIdx.x] = ls;
     }
 }
@@ -952,20 +958,27 @@ PassPair pass_for_shape(const Shape &s, bool vec)
     }
 }
 
-template <int DMAX, int KT, int RT>
+template <int DMAX, int KT, int RT, bool FG>
 PassPair mfma_pass_pair(bool vec)
 {
-    if (vec) return {{k_batch_pass_mfma<true, DMAX, KT, TRON_LOSS_LR, RT>, k_batch_pass_mfma<true, DMAX, KT, TRON_LOSS_L2SVM, RT>}};
-    return {{k_batch_pass_mfma<false, DMAX, KT, TRON_LOSS_LR, RT>, k_batch_pass_mfma<false, DMAX, KT, TRON_LOSS_L2SVM, RT>}};
+    if (vec) return {{k_batch_pass_mfma<true, DMAX, KT, TRON_LOSS_LR, RT, FG>, k_batch_pass_mfma<true, DMAX, KT, TRON_LOSS_L2SVM, RT, FG>}};
+    return {{k_batch_pass_mfma<false, DMAX, KT, TRON_LOSS_LR, RT, FG>, k_batch_pass_mfma<false, DMAX, KT, TRON_LOSS_L2SVM, RT, FG>}};
 }
 
-template <int KT, int RT>
+template <int KT, int RT, bool FG>
 PassPair mfma_pass_for(int64_t d)
 {
     const bool vec = d % 2 == 0;
-    if (d <= 16) return mfma_pass_pair<16, KT, RT>(vec);
-    if (d <= 24) return mfma_pass_pair<24, KT, RT>(vec);
-    return mfma_pass_pair<32, KT, RT>(vec);
+    if (d <= 16) return mfma_pass_pair<16, KT, RT, FG>(vec);
+    if (d <= 24) return mfma_pass_pair<24, KT, RT, FG>(vec);
+    return mfma_pass_pair<32, KT, RT, FG>(vec);
+}
+
+template <bool FG>
+PassPair mfma_pass_select(int KT, int rt, int64_t d)
+{
+    if (rt == 64) return (KT == 8) ? mfma_pass_for<8, 64, FG>(d) : mfma_pass_for<16, 64, FG>(d);
+    return (KT == 8) ? mfma_pass_for<8, 32, FG>(d) : mfma_pass_for<16, 32, FG>(d);
 }
 
 }  // namespace
@@ -989,16 +1002,28 @@ struct tron_batch {
     int grid = 0;
     tron::PassPair pass{{nullptr, nullptr}};
     size_t pass_lds = 0;                  // dynamic LDS of the pass kernel (the matrix-unit pass; 0 otherwise)
+    // the matrix-unit pass for rounds in which no problem asks for function and gradient (null: none), with its own
+    // dynamic LDS and number of resident workgroups per loss; grid_used = the workgroups of the pass launched last
+    tron::PassPair pass_nofg{{nullptr, nullptr}};
+    size_t pass_nofg_lds[2] = {0, 0};
+    int grid_nofg[2] = {0, 0};
+    int grid_used = 0;
     int D_loss = -1;                      // loss whose D the buffers hold (-1: none)
 };
 
 namespace tron {
 namespace {
 
-int launch_pass(tron_batch *b, int loss)
+// no_fg: the caller knows that no problem is in MODE_FG in this round
+int launch_pass(tron_batch *b, int loss, bool no_fg = false)
 {
     tron_dataset *ds = b->ds;
     ProfScope ps(ds, SLOT_BATCH_PASS);
+    const int li = loss == TRON_LOSS_L2SVM ? 1 : 0;
+    const bool lean = no_fg && b->pass_nofg.fn[li] != nullptr;
+    const PassFn fn = lean ? b->pass_nofg.fn[li] : b->pass.fn[li];
+    const size_t lds = lean ? b->pass_nofg_lds[li] : b->pass_lds;
+    b->grid_used = lean ? b->grid_nofg[li] : b->grid;
     int64_t n = ds->n, d = ds->d, ntiles = b->ntiles;
     const double *X = ds->X;
     const int8_t *y = ds->y8;
@@ -1008,8 +1033,7 @@ int launch_pass(tron_batch *b, int loss)
     double *Dval = b->Dval, *partials = b->partials;
     int K = b->K;
     void *args[] = {&n, &d, &X, &y, &ctl, &member, &Din, &Dout, &Dval, &ntiles, &partials, &K};
-    TRON_HIP(hipLaunchKernel(reinterpret_cast<const void *>(b->pass.fn[loss == TRON_LOSS_L2SVM ? 1 : 0]), dim3(b->grid), dim3(kBlock), args, b->pass_lds,
-                             ds->stream));
+    TRON_HIP(hipLaunchKernel(reinterpret_cast<const void *>(fn), dim3(b->grid_used), dim3(kBlock), args, lds, ds->stream));
     return TRON_OK;
 }
 
@@ -1017,7 +1041,7 @@ int launch_advance(tron_batch *b, const SolveParams &P)
 {
     tron_dataset *ds = b->ds;
     ProfScope ps(ds, SLOT_BATCH_ADVANCE);
-    hipLaunchKernelGGL(k_batch_advance, dim3(b->K), dim3(kAdvanceBlock), 0, ds->stream, ds->d, b->grid, b->partials, b->ctl, b->st, P,
+    hipLaunchKernelGGL(k_batch_advance, dim3(b->K), dim3(kAdvanceBlock), 0, ds->stream, ds->d, b->grid_used, b->partials, b->ctl, b->st, P,
                        P.trace_cap > 0 ? b->trace : nullptr);
     TRON_HIP(hipGetLastError());
     return TRON_OK;
@@ -1058,7 +1082,7 @@ int one_shot(tron_batch *b, int what, int loss, const double *C_host, const doub
     SolveParams P{};
     P.loss = loss;
     TRON_TRY(launch_begin(b, what, IN, C_host));
-    TRON_TRY(launch_pass(b, loss));
+    TRON_TRY(launch_pass(b, loss, what == BEGIN_HV));
     TRON_TRY(launch_advance(b, P));
     if (OUT) {
         hipLaunchKernelGGL(k_batch_store, dim3(b->K), dim3(kWave), 0, ds->stream, 1, ds->d, b->st, OUT);
@@ -1120,12 +1144,24 @@ static int batch_create_impl(tron_dataset *ds, int K, const uint32_t *member, in
         const int dmax = d <= 16 ? 16 : (d <= 24 ? 24 : 32);
         const size_t lds64 = sizeof(double) * kWavesPerBlock * (size_t)mfma_wave_doubles(dmax, K, 64);
         const int rt = g_tuning.batch_mfma_rows != 0 ? (int)g_tuning.batch_mfma_rows : (lds64 <= 80 * 1024 ? 64 : 32);
-        if (rt == 64) b->pass = (b->KT == 8) ? mfma_pass_for<8, 64>(d) : mfma_pass_for<16, 64>(d);
-        else b->pass = (b->KT == 8) ? mfma_pass_for<8, 32>(d) : mfma_pass_for<16, 32>(d);
+        b->pass = mfma_pass_select<true>(b->KT, rt, d);
+        const size_t floor_lds = sizeof(double) * kWavesPerBlock * 32 * 16;   // the final sums of the four wavefronts
         b->pass_lds = sizeof(double) * kWavesPerBlock * (size_t)mfma_wave_doubles(dmax, K, rt);
-        if (b->pass_lds < sizeof(double) * kWavesPerBlock * 32 * 16) b->pass_lds = sizeof(double) * kWavesPerBlock * 32 * 16;   // the final sums of the four wavefronts
+        if (b->pass_lds < floor_lds) b->pass_lds = floor_lds;
         for (int l = 0; l < 2; ++l)
             TRON_B(hipFuncSetAttribute(reinterpret_cast<const void *>(b->pass.fn[l]), hipFuncAttributeMaxDynamicSharedMemorySize, (int)b->pass_lds));
+        if (g_tuning.batch_lean != 0) {
+            // rounds without function / gradient requests (the L2-SVM then keeps no exchange area): half tiles, three or
+            // four wavefronts per SIMD
+            const int rt_lean = g_tuning.batch_mfma_rows != 0 ? (int)g_tuning.batch_mfma_rows : 32;
+            b->pass_nofg = mfma_pass_select<false>(b->KT, rt_lean, d);
+            for (int l = 0; l < 2; ++l) {
+                b->pass_nofg_lds[l] = sizeof(double) * kWavesPerBlock * (size_t)mfma_wave_doubles(dmax, l == 1 ? 0 : K, rt_lean);
+                if (b->pass_nofg_lds[l] < floor_lds) b->pass_nofg_lds[l] = floor_lds;
+                TRON_B(hipFuncSetAttribute(reinterpret_cast<const void *>(b->pass_nofg.fn[l]), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)b->pass_nofg_lds[l]));
+            }
+        }
     }
     // resident workgroups of the pass: all of them hold their accumulators for the whole pass
     int per_cu = 0, per_cu_lr = 0, cus = 0;
@@ -1139,11 +1175,23 @@ static int batch_create_impl(tron_dataset *ds, int K, const uint32_t *member, in
     if (grid > by_tiles) grid = by_tiles;
     if (grid < 1) grid = 1;
     b->grid = (int)grid;
+    b->grid_used = b->grid;
+    int64_t grid_max = grid;
+    for (int l = 0; l < 2 && b->pass_nofg.fn[l]; ++l) {
+        int pc = 0;
+        TRON_B(hipOccupancyMaxActiveBlocksPerMultiprocessor(&pc, reinterpret_cast<const void *>(b->pass_nofg.fn[l]), kBlock, b->pass_nofg_lds[l]));
+        int64_t gl = (int64_t)cus * (pc < 1 ? 1 : pc);
+        if (g_tuning.batch_grid > 0) gl = g_tuning.batch_grid;
+        if (gl > by_tiles) gl = by_tiles;
+        if (gl < 1) gl = 1;
+        b->grid_nofg[l] = (int)gl;
+        if (gl > grid_max) grid_max = gl;
+    }
     TRON_B(hipMalloc(reinterpret_cast<void **>(&b->member), sizeof(uint64_t) * (size_t)K * (size_t)b->ntiles));
     TRON_B(hipMalloc(reinterpret_cast<void **>(&b->Dbits), sizeof(uint64_t) * 2 * (size_t)K * (size_t)b->ntiles));
     TRON_B(hipMalloc(reinterpret_cast<void **>(&b->ctl), sizeof(BatchCtl)));
     TRON_B(hipMalloc(reinterpret_cast<void **>(&b->st), sizeof(ProbState) * kBatchMax));
-    TRON_B(hipMalloc(reinterpret_cast<void **>(&b->partials), sizeof(double) * (size_t)K * (size_t)(d + 1) * (size_t)b->grid));
+    TRON_B(hipMalloc(reinterpret_cast<void **>(&b->partials), sizeof(double) * (size_t)K * (size_t)(d + 1) * (size_t)grid_max));
     TRON_B(hipHostMalloc(reinterpret_cast<void **>(&b->st_host), sizeof(ProbState) * kBatchMax, hipHostMallocDefault));
     TRON_B(hipHostMalloc(reinterpret_cast<void **>(&b->mode_host), sizeof(int32_t) * (kBatchMax + 1), hipHostMallocDefault));
     TRON_B(hipMemsetAsync(b->ctl, 0, sizeof(BatchCtl), ds->stream));
@@ -1245,15 +1293,20 @@ extern "C" int tron_batch_solve(tron_batch *b, const tron_params *params, const 
     const double pass_bytes = (double)ds->n * (double)ds->d * 8.0;
     const int poll = pass_bytes < 4e8 ? 4 : 1;
     bool live = true;
+    bool no_fg = false;   // known only right after the host has looked: the first round of a group of `poll`
     for (int64_t round = 0; live && round < round_cap + poll; round += poll) {
         for (int i = 0; i < poll; ++i) {
-            TRON_TRY(launch_pass(b, Q.loss));
+            TRON_TRY(launch_pass(b, Q.loss, i == 0 && no_fg));
             TRON_TRY(launch_advance(b, P));
         }
         TRON_HIP(hipMemcpyAsync(b->mode_host, b->ctl->mode, sizeof(int32_t) * kBatchMax, hipMemcpyDeviceToHost, ds->stream));
         TRON_HIP(hipStreamSynchronize(ds->stream));
         live = false;
-        for (int k = 0; k < b->K; ++k) live |= b->mode_host[k] != MODE_IDLE;
+        no_fg = true;
+        for (int k = 0; k < b->K; ++k) {
+            live |= b->mode_host[k] != MODE_IDLE;
+            no_fg = no_fg && b->mode_host[k] != MODE_FG;
+        }
     }
     if (live) { set_error("tron_batch_solve: internal: problems still running after the round limit"); return TRON_ESTATE; }
     hipLaunchKernelGGL(k_batch_store, dim3(b->K), dim3(kWave), 0, ds->stream, 0, ds->d, b->st, W_dev);

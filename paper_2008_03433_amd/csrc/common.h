@@ -53,6 +53,7 @@ struct Tuning {
                                         //   0 never, 1 always, -1 automatic (the L2-SVM on matrices up to 1 GB)
     int64_t batch_grid = 0;  // workgroups of the multi-problem pass: 0 = as many as are resident at once
     int64_t batch_mfma = -1; // multi-problem pass on the matrix units: 1 = yes, 0 = no, -1 = the library decides
+    int64_t batch_lean = 1;         // matrix-unit pass: rounds without function / gradient requests run a kernel compiled without those steps
     int64_t batch_mfma_rows = 0;    // rows of X a wavefront of that pass keeps in LDS at a time: 32 or 64; 0 = by LDS footprint
 };
 extern Tuning g_tuning;

@@ -16,15 +16,18 @@ def rng():
     return np.random.default_rng(20080343)
 
 
-@pytest.fixture(autouse=True, params=["vector_units", "matrix_units_64_rows", "matrix_units_32_rows"])
+@pytest.fixture(autouse=True, params=["vector_units", "matrix_units_64_rows", "matrix_units_32_rows", "matrix_units_one_kernel"])
 def pass_kernel(request):
     """Every test of this file runs with the kernels of the pass over X: the one on the vector units and the one that
-    forms the two skinny products with fp64 matrix instructions, a wavefront holding a whole 64-row tile or half of one."""
+    forms the two skinny products with fp64 matrix instructions, a wavefront holding a whole 64-row tile or half of one;
+    rounds without function / gradient requests with the kernel compiled for them, or (one_kernel) with the general one."""
     tron.tron_tuning_set("batch_mfma", 0 if request.param == "vector_units" else 1)
-    tron.tron_tuning_set("batch_mfma_rows", 32 if request.param.endswith("32_rows") else 64)
+    tron.tron_tuning_set("batch_mfma_rows", {"matrix_units_64_rows": 64, "matrix_units_32_rows": 32}.get(request.param, 0))
+    tron.tron_tuning_set("batch_lean", 0 if request.param == "matrix_units_one_kernel" else 1)
     yield request.param
     tron.tron_tuning_set("batch_mfma", -1)
     tron.tron_tuning_set("batch_mfma_rows", 0)
+    tron.tron_tuning_set("batch_lean", 1)
 
 
 def _dense(rng, n, d, sep=0.6):
