@@ -606,7 +606,9 @@ def cross_validation(X, y, label: str, folds: int = 3, Cs=(0.1, 1.0), eps: float
         torch.cuda.empty_cache()
     agree = max(abs(batch_f[k] - fk) / abs(fk) for k, fk in seq_f)
     return {"workload": label, "n": n, "d": d, "folds": folds, "C": list(Cs), "problems": K, "loss": "l2svm", "eps": eps,
-            "pass_kernel": "fp64 matrix instructions" if K > 8 else "vector units",
+            # the library's rule per loss: the matrix units from eight problems on (L2-SVM), from five (logistic)
+            "pass_kernel": "fp64 matrix instructions" if K >= 8 else "vector units",
+            "logistic_pass_kernel": "fp64 matrix instructions" if K >= 5 else "vector units",
             "batched": {"solve_ms": best * 1e3, "rounds": rounds, "hv_pass_ms": hv_pass_ms, "fun_grad_pass_ms": fg_pass_ms,
                         "advance_ms": advance_ms, "logistic_hv_pass_ms": lr_hv_pass_ms, "logistic_fun_grad_pass_ms": lr_fg_pass_ms,
                         "hv_per_second_all_problems": K / ((hv_pass_ms + advance_ms) * 1e-3),

@@ -230,9 +230,10 @@ TRON_API int tron_solve(tron_dataset *ds, const tron_params *params, double *w_d
  * per problem.  Problem k is exactly the problem of Section 3 over the instances {i : bit k of
  * member[i] is set}: the rows outside it contribute nothing to f, g or Hv.
  * Dense handles with d <= TRON_BATCH_MAX_D only (sparse handles and wider matrices: one tron_solve per problem).
- * Per tile of 64 instances the pass is two skinny matrix products (64 x d by d x K, and d x 64 by 64 x K).  Up to
- * eight problems they run on the vector units; nine to sixteen problems (or knob "batch_mfma" = 1) run them as fp64
- * matrix instructions with the problems as the sixteen result columns.  Same results up to summation order.
+ * Per tile of 64 instances the pass is two skinny matrix products (64 x d by d x K, and d x 64 by 64 x K).  They run
+ * on the vector units, or as fp64 matrix instructions with the problems as the sixteen result columns: always above
+ * eight problems, below that per loss where measured faster (L2-SVM: eight problems, logistic loss: five and more);
+ * knob "batch_mfma".  Same results up to summation order.
  * ------------------------------------------------------------------------------------------ */
 typedef struct tron_batch tron_batch; /* opaque: membership bits, per-problem D, solver state, work space */
 
@@ -345,14 +346,15 @@ TRON_API int tron_probe_read_bandwidth(const double *src_dev, int64_t count, int
  * "dense_device_driver" (-1/0/1): tron_solve on a dense matrix with d <= 32 and no preconditioner runs its trust-region and
  *   CG steps on the device (as tron_batch_solve does): 0 never, 1 always, -1 (default) for the L2-SVM on matrices up to 1 GB.
  * "batch_grid" (0..4096): workgroups of the multi-problem pass (0 = as many as are resident at once).
- * "batch_mfma_rows" (0/32/64): rows of X a wavefront of the matrix-unit pass keeps in LDS at a time (0: 64 where two
- *                workgroups per CU still fit, else 32).
+ * "batch_mfma_rows" (0/32/64): rows of X a wavefront of the matrix-unit pass keeps in LDS at a time (0: 32, except 64
+ *                in the L2-SVM's rounds without function / gradient requests).
  * "batch_lean" (0/1, default 1): batches created afterwards run a round of the matrix-unit pass in which no problem asks
  *                for function and gradient (the Hessian-vector calls; inside tron_batch_solve the rounds right after the
- *                host has looked at the problems' requests) with a kernel compiled without the per-row steps of such
- *                requests: fewer registers and less LDS per wavefront (half tiles unless "batch_mfma_rows" says otherwise).
+ *                host has looked at the problems' requests) with a kernel compiled without the loss terms of such
+ *                requests: fewer registers, so more wavefronts per SIMD.
  * "batch_mfma" (-1/0/1): batches created afterwards run the multi-problem pass on the fp64 matrix units (1), or on the
- *                vector units where those can hold the batch, i.e. up to eight problems (0, and the default -1).
+ *                vector units where those can hold the batch, i.e. up to eight problems (0); -1 (default): per loss,
+ *                the matrix units from eight problems on for the L2-SVM and from five on for the logistic loss.
  * Unknown names or values return TRON_EINVAL.
  */
 TRON_API int tron_tuning_set(const char *name, int64_t value);

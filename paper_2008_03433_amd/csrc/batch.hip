@@ -259,11 +259,17 @@ __global__ __launch_bounds__(kBlock, 2) void k_batch_pass(int64_t n, int64_t d, 
 //   * a wavefront copies its tile of X into LDS exactly as it lies in memory (16-byte pieces, the loads of the next tile
 //     in flight during the work on the current one; rows that concern no problem are not read);
 //   * Z: per 16 rows and 4 columns of X one instruction, A read from LDS, B = V kept in registers;
-//   * lane (g = l / 16, p = l % 16) then holds Z of problem p at rows 4 v + g of every 16-row group.  Hessian rounds form
-//     C in place: the L2-SVM selects by the bit of the active-set word (factor 2 folded into V), the logistic loss
-//     multiplies by D, staged through LDS from a coalesced load.  Function/gradient rounds pass Z through LDS to the
-//     row-per-lane layout, where the per-row terms run once per row and problem, lane i owning row i (loss sums, new D
-//     or active-set words exactly as in k_batch_pass), and take zhat back the same way;
+//   * lane (g = l / 16, p = l % 16) then holds Z of problem p at rows 4 v + g of every 16-row group, and C is formed where
+//     Z lies.  Hessian rounds: the L2-SVM selects by the bit of the active-set word (factor 2 folded into V), the
+//     logistic loss multiplies by D, which each lane loads for its own elements (four consecutive rows of a problem
+//     per instruction and group of lanes; the four instructions of a 16-row step use up whole lines).  Function/gradient rounds of the
+//     L2-SVM: the lane evaluates the loss terms of its own sixteen (row, problem) elements per tile (the same
+//     per-element function as k_batch_pass; labels and membership come as bits of two 64-bit words per tile), keeps one
+//     loss sum -- its problem's -- and its rows' bits of the new active-set word, which the four lanes of a problem put
+//     together once per tile.  The logistic terms (an exponential, a logarithm and a division each) cost more than
+//     everything else in the pass, so they are evaluated once per row and problem that asks -- not for the sixteen
+//     result columns: Z goes through an LDS exchange area to a row-per-lane layout, where the new D is stored as
+//     64 consecutive rows of a problem, and zhat comes back the same way;
 //   * G: the result rows are the columns of X (two instructions for d > 16); the four rows 4 v + g, g = 0..3, that the
 //     lanes hold in register v are the summation index, so C is used where it lies.  A = X[row][column] read from LDS
 //     along a row: conflict-free.  Problems asking for the Hessian diagonal use the same instructions with A squared and
@@ -287,16 +293,17 @@ __device__ __forceinline__ uint64_t lane_value(uint64_t v, int src)
     return ((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo;
 }
 
-// doubles of LDS per wavefront: a unit of RT rows of X (rows padded to at most dmax + 2 doubles, 16 doubles of slack) and
-// K rows of RT + 1 doubles of the exchange area
-__host__ __device__ constexpr int mfma_wave_doubles(int dmax, int K, int rt) { return rt * (dmax + 2) + 16 + K * (rt + 1) + ((K * (rt + 1)) & 1); }
+// doubles of LDS per wavefront: a unit of RT rows of X (rows padded to at most dmax + 2 doubles, 16 doubles of slack) and,
+// where logistic function / gradient requests are served (kex = K, otherwise 0), the exchange area: kex rows of RT + 1
+// doubles for Z and zhat by problem and row
+__host__ __device__ constexpr int mfma_wave_doubles(int dmax, int kex, int rt) { return rt * (dmax + 2) + 16 + ((kex * (rt + 1) + 1) & ~1); }
 
 // RT = rows of X a wavefront keeps in LDS at a time: a whole 64-row tile, or half of one (smaller LDS footprint and
 // fewer registers for the loads in flight, so more wavefronts per SIMD to cover the dependent chains of matrix
 // instructions; the row-per-lane steps then serve 64 / RT problems side by side).
 // FG = false: a pass in which no problem asks for function and gradient (the host knows the modes of the round).  The
-// per-row steps, the labels, the loss sums and the new active-set words are compiled out, and the L2-SVM needs no
-// exchange area: fewer registers and less LDS per wavefront, so more wavefronts per SIMD.
+// per-element loss terms, the labels, the loss sums and the new active-set words are compiled out: fewer registers, so
+// more wavefronts per SIMD.
 template <bool VEC, int DMAX, int KT, int LOSS, int RT, bool FG>
 __global__ __launch_bounds__(kBlock, FG ? 2 : 3) void k_batch_pass_mfma(int64_t n, int64_t d, const double *__restrict__ X,
                                                             const int8_t *__restrict__ y,
@@ -311,11 +318,11 @@ __global__ __launch_bounds__(kBlock, FG ? 2 : 3) void k_batch_pass_mfma(int64_t 
     constexpr int PW = VEC ? 2 : 1;                 // doubles per piece
     constexpr int NH = kWave / RT;                  // units per tile
     constexpr int NS = RT / 16;                     // groups of 16 rows per unit
-    constexpr int PP = kWave / RT;                  // problems side by side in the row-per-lane layout
     constexpr int NP = RT * DMAX / PW / kWave;      // pieces per lane and unit at most (a unit is RT d doubles)
+    constexpr int PP = kWave / RT;                  // problems side by side in the row-per-lane layout
     static_assert(RT * DMAX / PW % kWave == 0 && KT % PP == 0, "whole pieces per lane; whole groups of problems");
-    constexpr int SL = kWave / KT;                  // tiles whose new active-set words a lane group holds before they are stored
     constexpr int kExRow = RT + 1;                  // doubles per problem in the exchange area (padded against bank conflicts)
+    constexpr bool kHasEx = FG && !svm;             // logistic function / gradient requests go through the exchange area
     extern __shared__ double dyn[];
     __shared__ double lds_red[kWavesPerBlock];
     const int lane = threadIdx.x & (kWave - 1);
@@ -341,18 +348,19 @@ __global__ __launch_bounds__(kBlock, FG ? 2 : 3) void k_batch_pass_mfma(int64_t 
     // (d < DMAX) are fetched from the first bytes of X and land in the slack behind it.
     constexpr int xs_len = RT * (DMAX + 2) + 16;
     const int S = VEC ? D + ((6 - D % 4) % 4) : (D | 1);
-    constexpr bool kHasEx = FG || !svm;                          // otherwise C is formed where Z lies
     const int kex = kHasEx ? K : 0;
     double *Xs = dyn + (size_t)wv * mfma_wave_doubles(DMAX, kex, RT);
-    double *Ex = Xs + xs_len;                                    // [problem 0..K-1][row] exchange area
+    double *Ex = Xs + xs_len;                                    // [problem][row of the unit]: Z, then zhat
     for (int i = lane; i < mfma_wave_doubles(DMAX, kex, RT); i += kWave) Xs[i] = 0.0;
     // this lane in the matrix layouts: g = summation index / row block, p = problem (result column) or row / column of X
     const int p = lane & 15, g = lane >> 4;
     const bool pk = p < K;   // K <= KT
     const int modeM = pk ? ctl->mode[pk ? p : 0] : MODE_IDLE;
-    const bool exM = (FG && modeM == MODE_FG) || (!svm && (modeM == MODE_HV || modeM == MODE_DIAG));   // C comes out of the exchange area
-    // ... and in the row-per-lane layout: row rowl of the unit, problem sub of a group of PP problems
-    const int rowl = lane & (RT - 1), sub = lane / RT;
+    const int dslotM = pk ? ctl->dslot[pk ? p : 0] : 0;
+    const bool exM = !svm && (modeM == MODE_HV || modeM == MODE_DIAG);   // this lane's problem reads its D
+    const int rowl = lane & (RT - 1), sub = lane / RT;   // row-per-lane layout: row of the unit, problem of a group of PP
+    // logistic D of this lane's problem in the slot it reads; lanes without such a problem stay at the start of the array
+    const double *const DvalM = (!svm && pk) ? Dval + ((int64_t)p * 2 + dslotM) * n : Dval;
     double Vop[DMAX / 4];
 #pragma unroll
     for (int kk = 0; kk < DMAX / 4; ++kk) {
@@ -385,10 +393,11 @@ __global__ __launch_bounds__(kBlock, FG ? 2 : 3) void k_batch_pass_mfma(int64_t 
     }
 
     double xr[NP][PW];
-    double loss[KT];
-    uint64_t held = 0;   // lane SL k + j: the new active-set word of problem k for the j-th tile since the last store
+    double lossM = 0.0;   // L2-SVM: loss terms of this lane's rows of its problem
+    double lossK[KT];     // logistic: loss terms of this lane's row, by problem
 #pragma unroll
-    for (int k = 0; k < KT; ++k) loss[k] = 0.0;
+    for (int k = 0; k < KT; ++k) lossK[k] = 0.0;
+    uint64_t nbM = 0;     // this lane's rows' bits of its problem's new active-set word for the current tile
     mfma4 G1 = {0.0, 0.0, 0.0, 0.0}, G2 = {0.0, 0.0, 0.0, 0.0};
 
     // the rows of unit h of a tile that concern some problem
@@ -454,9 +463,7 @@ __global__ __launch_bounds__(kBlock, FG ? 2 : 3) void k_batch_pass_mfma(int64_t 
         if (any_fg) ycur = label_raw(first, 0);
         fetch(first, 0, unit_rows(rows_cur, 0));
     }
-    int it_tile = 0;
-    for (int64_t tile = first; tile < last; ++tile, ++it_tile) {
-        const int slotl = it_tile & (SL - 1);
+    for (int64_t tile = first; tile < last; ++tile) {
         const uint64_t w2 = word_raw(tile + 2);
         uint64_t wkn[KT], rows_next = 0;
 #pragma unroll
@@ -466,10 +473,9 @@ __global__ __launch_bounds__(kBlock, FG ? 2 : 3) void k_batch_pass_mfma(int64_t 
         }
         // the word of this lane's problem
         uint64_t wordM = 0;
-        if (svm) wordM = lane_value(w0, p);
+        if (svm || any_fg) wordM = lane_value(w0, p);
 #pragma unroll 1
         for (int h = 0; h < NH; ++h) {
-            const int64_t row0 = tile * kWave + RT * h;
             const uint64_t urows = unit_rows(rows_cur, h);
             if (urows != 0) to_lds();
             // the loads of the unit after this one
@@ -485,26 +491,6 @@ __global__ __launch_bounds__(kBlock, FG ? 2 : 3) void k_batch_pass_mfma(int64_t 
                 }
             }
             if (urows != 0) {
-                // logistic D of the problems in a Hessian / diagonal round, row-per-lane, PP problems side by side
-                if (any_exd) {
-#pragma unroll
-                    for (int k = 0; k < KT; k += PP) {
-                        bool some = false;
-                        int mk[PP], dk[PP];
-#pragma unroll
-                        for (int j = 0; j < PP; ++j) {
-                            mk[j] = mode[k + j];
-                            dk[j] = dslot[k + j];
-                            some |= mk[j] == MODE_HV || mk[j] == MODE_DIAG;
-                        }
-                        if (svm || !some) continue;   // uniform
-                        const int mK = by_sub_i(mk), dK = by_sub_i(dk);
-                        const int kk = k + sub;
-                        const int64_t i = row0 + rowl;
-                        const double Dv = Dval[((int64_t)(kk < K ? kk : 0) * 2 + dK) * n + (i < n ? i : n - 1)];   // zero outside the problem's rows
-                        if ((mK == MODE_HV || mK == MODE_DIAG) && kk < K) Ex[kk * kExRow + rowl] = (i < n) ? Dv : 0.0;
-                    }
-                }
                 wave_lds_fence();
                 // Z = X V for rows 16 s .. 16 s + 15 of the unit
                 auto z_of = [&](int s) {
@@ -516,7 +502,9 @@ __global__ __launch_bounds__(kBlock, FG ? 2 : 3) void k_batch_pass_mfma(int64_t 
                     }
                     return z;
                 };
-                if (any_fg) {
+                if (kHasEx && any_fg) {
+                    // logistic function / gradient requests: Z to the row-per-lane layout, the terms once per row and
+                    // problem that asks (D stored from there), zhat back
 #pragma unroll 1
                     for (int s = 0; s < NS; ++s) {
                         const mfma4 z = z_of(s);
@@ -548,44 +536,62 @@ __global__ __launch_bounds__(kBlock, FG ? 2 : 3) void k_batch_pass_mfma(int64_t 
                         loss_terms_dev<LOSS>(z, yrow, alpha, zhat, Di);
                         if (!mine) { alpha = 0.0; zhat = 0.0; Di = 0.0; }
 #pragma unroll
-                        for (int j = 0; j < PP; ++j) loss[k + j] += (sub == j) ? alpha : 0.0;
-                        if (svm) {
-                            const uint64_t nb = __ballot(Di != 0.0);
-#pragma unroll
-                            for (int j = 0; j < PP; ++j) {
-                                const uint64_t part = RT == kWave ? nb : ((nb >> (RT * j)) & 0xffffffffull);
-                                if (lane == SL * (k + j) + slotl) held |= part << (RT * h);
-                            }
-                        } else if (mine) {
-                            Dval[((int64_t)kk * 2 + by_sub_i(dk)) * n + row0 + rowl] = Di;
-                        }
+                        for (int j = 0; j < PP; ++j) lossK[k + j] += (sub == j) ? alpha : 0.0;
+                        if (mine) Dval[((int64_t)kk * 2 + by_sub_i(dk)) * n + tile * kWave + RT * h + rowl] = Di;
                         if (act) Ex[kk * kExRow + rowl] = zhat;
                     }
                     wave_lds_fence();
                 }
-                // G += X^T C, 16 rows at a time (Z of a Hessian round is formed again here rather than kept)
+                // labels of the unit's rows as a word (the same in every lane)
+                const uint64_t yword = (svm && any_fg) ? __ballot(ycur > 0) : 0ull;
+                // G += X^T C, 16 rows at a time
 #pragma unroll 1
                 for (int s = 0; s < NS; ++s) {
+                    // logistic D of the lane's four elements, asked for before the products that form Z (zero outside the
+                    // problem's rows: never written there); no load sits behind a per-lane branch
+                    double ev[4] = {0.0, 0.0, 0.0, 0.0};
+                    bool evok[4] = {false, false, false, false};
+                    if (any_exd) {   // uniform
+                        const int64_t r0 = tile * kWave + RT * h + 16 * s + g;
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            evok[v] = exM && r0 + 4 * v < n;
+                            ev[v] = *(evok[v] ? DvalM + r0 + 4 * v : Dval);
+                        }
+                    }
                     mfma4 z = {0.0, 0.0, 0.0, 0.0};
-                    if (any_hv) z = z_of(s);
+                    if (any_hv || (svm && any_fg)) z = z_of(s);
                     // every LDS read of the 16 rows first (none behind a per-lane condition), then the selects and the products.
                     // Columns of X past d give result rows that nobody reads: A is used as it lies in LDS.
-                    double ev[4], a1v[4], a2v[4];
+                    double a1v[4], a2v[4], ex[4];
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
                         const int r = 16 * s + 4 * v + g;
-                        ev[v] = kHasEx ? Ex[(pk ? p : 0) * kExRow + r] : 0.0;
+                        ex[v] = kHasEx ? Ex[(pk ? p : 0) * kExRow + r] : 0.0;   // zhat of a logistic function / gradient request
                         a1v[v] = Xs[r * S + p];
                         a2v[v] = (DMAX > 16) ? Xs[r * S + 16 + p] : 0.0;
                     }
                     const uint32_t bits = (uint32_t)(wordM >> (RT * h + 16 * s + g));   // bit 4 v: row 16 s + 4 v + g of the unit
+                    const uint32_t ybits = (uint32_t)(yword >> (16 * s + g));            // the same rows' labels
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
-                        const double e = (exM && pk) ? ev[v] : 0.0;
+                        const double e = evok[v] ? ev[v] : 0.0;
                         const bool bit = (bits >> (4 * v)) & 1u;
+                        double cfg = 0.0;   // zhat of a function / gradient request
+                        if (kHasEx) cfg = (modeM == MODE_FG) ? ex[v] : 0.0;
+                        if (svm && any_fg) {   // uniform
+                            const double yv = ((ybits >> (4 * v)) & 1u) ? 1.0 : -1.0;
+                            double alpha, zhat, Di;
+                            loss_terms_dev<LOSS>(z[v], yv, alpha, zhat, Di);
+                            const bool mine = modeM == MODE_FG && bit;   // a row of this lane's problem (rows past n have no bit)
+                            lossM += mine ? alpha : 0.0;
+                            cfg = mine ? zhat : 0.0;
+                            const int rt = RT * h + 16 * s + 4 * v + g;   // the row in its tile
+                            nbM |= (uint64_t)(mine && Di != 0.0) << rt;
+                        }
                         double c;
-                        if (svm) c = (modeM == MODE_HV) ? (bit ? z[v] : 0.0) : ((FG && modeM == MODE_FG) ? e : 0.0);
-                        else c = (modeM == MODE_HV) ? e * z[v] : ((FG && modeM == MODE_FG) ? e : 0.0);
+                        if (svm) c = (modeM == MODE_HV) ? (bit ? z[v] : 0.0) : cfg;
+                        else c = (modeM == MODE_HV) ? e * z[v] : cfg;
                         if (any_mul) {
                             G1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a1v[v], c, G1, 0, 0, 0);
                             if (DMAX > 16) G2 = __builtin_amdgcn_mfma_f64_16x16x4f64(a2v[v], c, G2, 0, 0, 0);
@@ -604,12 +610,12 @@ __global__ __launch_bounds__(kBlock, FG ? 2 : 3) void k_batch_pass_mfma(int64_t 
             asm volatile("" : "+v"(ynext));   // nothing of the next unit's loads is touched before this point
             ycur = ynext;
         }
-        if (svm && any_fg && (slotl == SL - 1 || tile + 1 == last)) {
-            // lane SL k + j stores the word of problem k for tile (tile - slotl + j): SL consecutive words per problem
-            const int k = lane / SL, j = lane % SL;
-            const int mk = ctl->mode[k < KT ? k : 0];
-            if (mk == MODE_FG && j <= slotl) Dbits_out[((int64_t)k * 2 + ctl->dslot[k < KT ? k : 0]) * ntiles + (tile - slotl) + j] = held;
-            held = 0;
+        if (svm && any_fg) {
+            // the four lanes of a problem hold disjoint rows' bits of its new word; a tile without rows still gets its zero
+            uint64_t word = nbM | lane_value(nbM, lane ^ 16);
+            word |= lane_value(word, lane ^ 32);
+            if (g == 0 && modeM == MODE_FG) Dbits_out[((int64_t)p * 2 + dslotM) * ntiles + tile] = word;
+            nbM = 0;
         }
         w0 = w1;
         w1 = word_ok(tile + 2) ? w2 : 0ull;
@@ -638,7 +644,7 @@ __global__ __launch_bounds__(kBlock, FG ? 2 : 3) void k_batch_pass_mfma(int64_t 
 #pragma unroll
     for (int k = 0; k < KT; ++k) {
         if (mode[k] == MODE_IDLE) continue;   // uniform over the workgroup
-        const double ls = FG ? block_sum(loss[k], lds_red) : 0.0;
+        const double ls = FG ? block_sum(svm ? (p == k ? lossM : 0.0) : lossK[k], lds_red) : 0.0;
         if (threadIdx.x == 0) partials[((int64_t)k * cols + d) * gridDim.x + blockIdx.x] = ls;
     }
 }
@@ -999,14 +1005,15 @@ struct tron_batch {
     tron_trace_rec *trace = nullptr;      // device, K * trace_cap
     int trace_cap = 0;
     double *partials = nullptr;           // K x (d+1) x grid
-    int grid = 0;
     tron::PassPair pass{{nullptr, nullptr}};
-    size_t pass_lds = 0;                  // dynamic LDS of the pass kernel (the matrix-unit pass; 0 otherwise)
+    size_t pass_lds[2] = {0, 0};          // dynamic LDS of the pass kernel per loss (the matrix-unit pass; 0 otherwise)
     // the matrix-unit pass for rounds in which no problem asks for function and gradient (null: none), with its own
     // dynamic LDS and number of resident workgroups per loss; grid_used = the workgroups of the pass launched last
     tron::PassPair pass_nofg{{nullptr, nullptr}};
     size_t pass_nofg_lds[2] = {0, 0};
     int grid_nofg[2] = {0, 0};
+    int grid_pass[2] = {0, 0};            // workgroups of pass.fn per loss
+    bool on_matrix_units[2] = {false, false};   // per loss: pass.fn is the matrix-unit kernel
     int grid_used = 0;
     int D_loss = -1;                      // loss whose D the buffers hold (-1: none)
 };
@@ -1022,8 +1029,8 @@ int launch_pass(tron_batch *b, int loss, bool no_fg = false)
     const int li = loss == TRON_LOSS_L2SVM ? 1 : 0;
     const bool lean = no_fg && b->pass_nofg.fn[li] != nullptr;
     const PassFn fn = lean ? b->pass_nofg.fn[li] : b->pass.fn[li];
-    const size_t lds = lean ? b->pass_nofg_lds[li] : b->pass_lds;
-    b->grid_used = lean ? b->grid_nofg[li] : b->grid;
+    const size_t lds = lean ? b->pass_nofg_lds[li] : b->pass_lds[li];
+    b->grid_used = lean ? b->grid_nofg[li] : b->grid_pass[li];
     int64_t n = ds->n, d = ds->d, ntiles = b->ntiles;
     const double *X = ds->X;
     const int8_t *y = ds->y8;
@@ -1131,62 +1138,67 @@ static int batch_create_impl(tron_dataset *ds, int K, const uint32_t *member, in
     b->KT = (K <= 4) ? 4 : 8;
     b->ntiles = (n + kWave - 1) / kWave;
     const bool vec = (s.E % 2 == 0) && (d % 2 == 0);
-    // up to 8 problems: the pass on the vector units (4 or 8 problem slots); more: the matrix units (below)
+    // up to 8 problems: the pass on the vector units (4 or 8 problem slots), unless the matrix units take it (below)
     b->pass = (b->KT == 4) ? pass_for_shape<4>(s, vec) : pass_for_shape<8>(s, vec);
     auto fail = [&](int rc) { tron_batch_destroy(b); return rc; };
 #define TRON_B(expr) do { hipError_t e__ = (expr); if (e__ != hipSuccess) return fail(hip_fail(e__, #expr, __FILE__, __LINE__)); } while (0)
     if (!b->pass.fn[0]) { set_error("tron_batch_create: internal: no kernel for E=%d L=%d", s.E, s.L); return fail(TRON_EINVAL); }
-    if (g_tuning.batch_mfma > 0 || K > 8) {
-        // the pass as matrix instructions, 8 or 16 problem columns: the tile of X and the exchange area of every wavefront in LDS
-        b->KT = (K <= 8) ? 8 : 16;
-        // whole 64-row tiles in LDS where two workgroups per CU still fit (measured faster there: the loads of the next
-        // tile are asked for a whole tile ahead), half tiles otherwise
-        const int dmax = d <= 16 ? 16 : (d <= 24 ? 24 : 32);
-        const size_t lds64 = sizeof(double) * kWavesPerBlock * (size_t)mfma_wave_doubles(dmax, K, 64);
-        const int rt = g_tuning.batch_mfma_rows != 0 ? (int)g_tuning.batch_mfma_rows : (lds64 <= 80 * 1024 ? 64 : 32);
-        b->pass = mfma_pass_select<true>(b->KT, rt, d);
-        const size_t floor_lds = sizeof(double) * kWavesPerBlock * 32 * 16;   // the final sums of the four wavefronts
-        b->pass_lds = sizeof(double) * kWavesPerBlock * (size_t)mfma_wave_doubles(dmax, K, rt);
-        if (b->pass_lds < floor_lds) b->pass_lds = floor_lds;
-        for (int l = 0; l < 2; ++l)
-            TRON_B(hipFuncSetAttribute(reinterpret_cast<const void *>(b->pass.fn[l]), hipFuncAttributeMaxDynamicSharedMemorySize, (int)b->pass_lds));
+    // The pass as matrix instructions (8 or 16 problem columns; the tile of X of every wavefront in LDS, and where logistic
+    // function / gradient requests are served the exchange area), chosen per loss: above eight problems always; otherwise
+    // where it is the faster one (measured at 20M x 24: the L2-SVM from eight problems on, the logistic loss -- whose
+    // vector kernel evaluates every problem's terms in every lane and spills -- from five).
+    const int mfma_from[2] = {5, 8};   // logistic, L2-SVM
+    const int dmax = d <= 16 ? 16 : (d <= 24 ? 24 : 32);
+    const size_t floor_lds = sizeof(double) * kWavesPerBlock * 32 * 16;   // the final sums of the four wavefronts
+    const int KTm = (K <= 8) ? 8 : 16;
+    for (int l = 0; l < 2; ++l) {
+        b->on_matrix_units[l] = K > 8 || g_tuning.batch_mfma > 0 || (g_tuning.batch_mfma < 0 && K >= mfma_from[l]);
+        if (!b->on_matrix_units[l]) continue;
+        // half tiles (measured: as fast or faster than whole tiles for both losses, 3 to 12% at 12 problems)
+        const int rt = g_tuning.batch_mfma_rows != 0 ? (int)g_tuning.batch_mfma_rows : 32;
+        b->pass.fn[l] = mfma_pass_select<true>(KTm, rt, d).fn[l];
+        b->pass_lds[l] = sizeof(double) * kWavesPerBlock * (size_t)mfma_wave_doubles(dmax, l == 0 ? K : 0, rt);
+        if (b->pass_lds[l] < floor_lds) b->pass_lds[l] = floor_lds;
+        TRON_B(hipFuncSetAttribute(reinterpret_cast<const void *>(b->pass.fn[l]), hipFuncAttributeMaxDynamicSharedMemorySize, (int)b->pass_lds[l]));
         if (g_tuning.batch_lean != 0) {
-            // rounds without function / gradient requests (the L2-SVM then keeps no exchange area): half tiles, three or
-            // four wavefronts per SIMD
-            const int rt_lean = g_tuning.batch_mfma_rows != 0 ? (int)g_tuning.batch_mfma_rows : 32;
-            b->pass_nofg = mfma_pass_select<false>(b->KT, rt_lean, d);
-            for (int l = 0; l < 2; ++l) {
-                b->pass_nofg_lds[l] = sizeof(double) * kWavesPerBlock * (size_t)mfma_wave_doubles(dmax, l == 1 ? 0 : K, rt_lean);
-                if (b->pass_nofg_lds[l] < floor_lds) b->pass_nofg_lds[l] = floor_lds;
-                TRON_B(hipFuncSetAttribute(reinterpret_cast<const void *>(b->pass_nofg.fn[l]), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)b->pass_nofg_lds[l]));
-            }
+            // rounds without function / gradient requests: three or four wavefronts per SIMD; whole tiles for the L2-SVM,
+            // half tiles for the logistic loss (measured: 3% either way)
+            const int rt_lean = g_tuning.batch_mfma_rows != 0 ? (int)g_tuning.batch_mfma_rows : (l == 1 ? 64 : 32);
+            b->pass_nofg.fn[l] = mfma_pass_select<false>(KTm, rt_lean, d).fn[l];
+            b->pass_nofg_lds[l] = sizeof(double) * kWavesPerBlock * (size_t)mfma_wave_doubles(dmax, 0, rt_lean);
+            if (b->pass_nofg_lds[l] < floor_lds) b->pass_nofg_lds[l] = floor_lds;
+            TRON_B(hipFuncSetAttribute(reinterpret_cast<const void *>(b->pass_nofg.fn[l]), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)b->pass_nofg_lds[l]));
         }
     }
-    // resident workgroups of the pass: all of them hold their accumulators for the whole pass
-    int per_cu = 0, per_cu_lr = 0, cus = 0;
-    TRON_B(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(b->pass.fn[1]), kBlock, b->pass_lds));
-    TRON_B(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_lr, reinterpret_cast<const void *>(b->pass.fn[0]), kBlock, b->pass_lds));
-    if (per_cu_lr > per_cu) per_cu = per_cu_lr;
+    // resident workgroups of a pass: all of them hold their accumulators for the whole pass
+    int cus = 0;
     TRON_B(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, ds->device));
-    int64_t grid = (int64_t)cus * (per_cu < 1 ? 1 : per_cu);
-    if (g_tuning.batch_grid > 0) grid = g_tuning.batch_grid;
     const int64_t by_tiles = (b->ntiles + kWavesPerBlock - 1) / kWavesPerBlock;
-    if (grid > by_tiles) grid = by_tiles;
-    if (grid < 1) grid = 1;
-    b->grid = (int)grid;
-    b->grid_used = b->grid;
-    int64_t grid_max = grid;
-    for (int l = 0; l < 2 && b->pass_nofg.fn[l]; ++l) {
+    auto resident = [&](PassFn fn, size_t lds, int *out) -> int {
         int pc = 0;
-        TRON_B(hipOccupancyMaxActiveBlocksPerMultiprocessor(&pc, reinterpret_cast<const void *>(b->pass_nofg.fn[l]), kBlock, b->pass_nofg_lds[l]));
+        const hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&pc, reinterpret_cast<const void *>(fn), kBlock, lds);
+        if (e != hipSuccess) return hip_fail(e, "hipOccupancyMaxActiveBlocksPerMultiprocessor", __FILE__, __LINE__);
         int64_t gl = (int64_t)cus * (pc < 1 ? 1 : pc);
         if (g_tuning.batch_grid > 0) gl = g_tuning.batch_grid;
         if (gl > by_tiles) gl = by_tiles;
         if (gl < 1) gl = 1;
-        b->grid_nofg[l] = (int)gl;
-        if (gl > grid_max) grid_max = gl;
+        *out = (int)gl;
+        return TRON_OK;
+    };
+    int64_t grid_max = 1;
+    for (int l = 0; l < 2; ++l) {
+        int rc = resident(b->pass.fn[l], b->pass_lds[l], &b->grid_pass[l]);
+        if (rc == TRON_OK && b->pass_nofg.fn[l]) rc = resident(b->pass_nofg.fn[l], b->pass_nofg_lds[l], &b->grid_nofg[l]);
+        if (rc != TRON_OK) return fail(rc);
+        if (b->grid_pass[l] > grid_max) grid_max = b->grid_pass[l];
+        if (b->grid_nofg[l] > grid_max) grid_max = b->grid_nofg[l];
     }
+    if (!b->on_matrix_units[0] && !b->on_matrix_units[1]) {
+        // the two vector kernels share one grid (the larger residency), as they always have
+        b->grid_pass[0] = b->grid_pass[1] = (int)grid_max;
+    }
+    b->grid_used = b->grid_pass[1];
     TRON_B(hipMalloc(reinterpret_cast<void **>(&b->member), sizeof(uint64_t) * (size_t)K * (size_t)b->ntiles));
     TRON_B(hipMalloc(reinterpret_cast<void **>(&b->Dbits), sizeof(uint64_t) * 2 * (size_t)K * (size_t)b->ntiles));
     TRON_B(hipMalloc(reinterpret_cast<void **>(&b->ctl), sizeof(BatchCtl)));
