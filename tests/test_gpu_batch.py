@@ -16,12 +16,14 @@ def rng():
     return np.random.default_rng(20080343)
 
 
-@pytest.fixture(autouse=True, params=["vector_units", "matrix_units_64_rows", "matrix_units_32_rows", "matrix_units_one_kernel"])
+@pytest.fixture(autouse=True, params=["library_default", "vector_units", "matrix_units_64_rows", "matrix_units_32_rows",
+                                      "matrix_units_one_kernel"])
 def pass_kernel(request):
     """Every test of this file runs with the kernels of the pass over X: the one on the vector units and the one that
     forms the two skinny products with fp64 matrix instructions, a wavefront holding a whole 64-row tile or half of one;
-    rounds without function / gradient requests with the kernel compiled for them, or (one_kernel) with the general one."""
-    tron.tron_tuning_set("batch_mfma", 0 if request.param == "vector_units" else 1)
+    rounds without function / gradient requests with the kernel compiled for them, or (one_kernel) with the general one;
+    and with the library's own choice, which depends on the number of problems and the loss."""
+    tron.tron_tuning_set("batch_mfma", {"library_default": -1, "vector_units": 0}.get(request.param, 1))
     tron.tron_tuning_set("batch_mfma_rows", {"matrix_units_64_rows": 64, "matrix_units_32_rows": 32}.get(request.param, 0))
     tron.tron_tuning_set("batch_lean", 0 if request.param == "matrix_units_one_kernel" else 1)
     yield request.param
