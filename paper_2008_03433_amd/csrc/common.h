@@ -363,8 +363,10 @@ struct CgStepCtl {
     int it;              // iteration number, from 0 (then s = 0 and p.p = r.r)
 };
 // n_dir: workgroups of the direction kernel before (its partial sums of p.p, s.p, s.s; unused when it == 0), 0 = take the
-// sums from scalars 1..3.  Returns its own number of workgroups: the partial sums of r.r | r.(r/M) in region CGP_RR.
-int cg_step(tron_dataset *ds, const CgStepCtl &ctl, int n_dir, const double *p, const double *Hp, const double *M, double *s, double *r);
+// sums from scalars 1..3.  n_php: partial sums of p.Hp at the start of ds->partials, 0 = take p.Hp from scalar 0.
+// Returns its own number of workgroups: the partial sums of r.r | r.(r/M) in region CGP_RR.
+int cg_step(tron_dataset *ds, const CgStepCtl &ctl, int n_dir, int n_php, const double *p, const double *Hp, const double *M, double *s, double *r);
+int vec_workgroups(int64_t m);   // workgroups of the vector kernels (and of the sparse combine kernels) over m elements
 // n_step: workgroups of the step kernel before: adds up the new r.r and leaves it in its scalar slot (host and device copy);
 // 0 = the slot holds it already.  beta = (new r.r) / (old r.r); partial sums of p.p, s.p, s.s (M-weighted) in their regions.
 // Returns its number of workgroups.
@@ -447,6 +449,6 @@ int grad_enqueue(tron_dataset *ds, double C, const double *w, double *g, int sca
 // out = 1 + C sum_i D_i x_ij^2 with D = Dbuf[Dslot] (the diagonal of the Hessian; C scaled by the caller for a blend). Enqueue only.
 int hess_diag_enqueue(tron_dataset *ds, double C, int Dslot, double *out);
 int grad_eval(tron_dataset *ds, double C, const double *w, double *g, double *gnorm_out);        // syncs
-int hv_enqueue(tron_dataset *ds, double C, const double *v, double *Hv);                         // scalars[0]=v.Hv, no sync
+int hv_enqueue(tron_dataset *ds, double C, const double *v, double *Hv, int *vhv_partials = nullptr);   // scalars[0]=v.Hv, no sync
 
 }  // namespace tron

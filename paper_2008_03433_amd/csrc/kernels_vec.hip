@@ -209,10 +209,9 @@ __device__ __forceinline__ bool cg_run_ended(const CgStepCtl &c, const double *_
 
 // The step length of a CG iteration from the device copy of the scalars (see CgStepCtl), in the operations and the
 // order the host used to take (no contraction into fused multiply-adds), the same in every thread.
-__device__ __forceinline__ double cg_step_length(const CgStepCtl &c, const double *__restrict__ sc, double pp, double sp, double ss, bool &boundary)
+__device__ __forceinline__ double cg_step_length(const CgStepCtl &c, const double *__restrict__ sc, double pHp, double pp, double sp, double ss, bool &boundary)
 {
     const double rr = sc[kScalRR + (c.it & 1)];
-    const double pHp = sc[0];
     if (c.it == 0) { pp = rr; sp = 0.0; ss = 0.0; }
     const double alpha = rr / pHp;
     // |s + alpha p|^2 from the three dot products kept alongside the vectors
@@ -247,7 +246,7 @@ __device__ __forceinline__ double sum_of_partials(const double *__restrict__ p, 
 // s += a p;  r -= a Hp with a = the step length above;  region CGP_RR = partial sums of r.r (PRE: r.(r / M));  scalar 4 = a,
 // the iteration's flag slot = whether the step went to the boundary.  Nothing at all if the run had ended.
 template <bool PRE>
-__global__ __launch_bounds__(kBlock) void k_cg_step(int64_t d, CgStepCtl ctl, int n_dir, const double *__restrict__ sc, const double *__restrict__ p,
+__global__ __launch_bounds__(kBlock) void k_cg_step(int64_t d, CgStepCtl ctl, int n_dir, int n_php, const double *__restrict__ php, const double *__restrict__ sc, const double *__restrict__ p,
                                                     const double *__restrict__ Hp, const double *__restrict__ M,
                                                     double *__restrict__ s, double *__restrict__ r, double *__restrict__ cgp,
                                                     double *__restrict__ scal, double *__restrict__ scal_copy)
@@ -264,8 +263,9 @@ __global__ __launch_bounds__(kBlock) void k_cg_step(int64_t d, CgStepCtl ctl, in
         sp = sc[2];
         ss = sc[3];
     }
+    const double pHp = n_php > 0 ? sum_of_partials(php, n_php) : sc[0];   // left by the product's last kernel, or added up by a launch
     bool boundary;
-    const double alpha = cg_step_length(ctl, sc, pp, sp, ss, boundary);
+    const double alpha = cg_step_length(ctl, sc, pHp, pp, sp, ss, boundary);
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         scal[4] = alpha;
         scal[kScalFlag + (ctl.it & 1)] = boundary ? 1.0 : 0.0;
@@ -282,12 +282,14 @@ __global__ __launch_bounds__(kBlock) void k_cg_step(int64_t d, CgStepCtl ctl, in
     if (threadIdx.x == 0) cgp[(size_t)CGP_RR * kMaxGrid + blockIdx.x] = acc;
 }
 
-int cg_step(tron_dataset *ds, const CgStepCtl &ctl, int n_dir, const double *p, const double *Hp, const double *M, double *s, double *r)
+int vec_workgroups(int64_t m) { return vec_grid(m); }
+
+int cg_step(tron_dataset *ds, const CgStepCtl &ctl, int n_dir, int n_php, const double *p, const double *Hp, const double *M, double *s, double *r)
 {
     ProfScope ps(ds, SLOT_CG_VEC);
     const int g = vec_grid(ds->d);
-    if (M) hipLaunchKernelGGL(k_cg_step<true>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, ctl, n_dir, ds->scal_copy, p, Hp, M, s, r, ds->cg_partials, ds->scal_dev, ds->scal_copy);
-    else hipLaunchKernelGGL(k_cg_step<false>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, ctl, n_dir, ds->scal_copy, p, Hp, M, s, r, ds->cg_partials, ds->scal_dev, ds->scal_copy);
+    if (M) hipLaunchKernelGGL(k_cg_step<true>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, ctl, n_dir, n_php, ds->partials, ds->scal_copy, p, Hp, M, s, r, ds->cg_partials, ds->scal_dev, ds->scal_copy);
+    else hipLaunchKernelGGL(k_cg_step<false>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, ctl, n_dir, n_php, ds->partials, ds->scal_copy, p, Hp, M, s, r, ds->cg_partials, ds->scal_dev, ds->scal_copy);
     TRON_HIP(hipGetLastError());
     return g;
 }

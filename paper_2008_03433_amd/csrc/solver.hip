@@ -48,13 +48,22 @@ int grad_eval(tron_dataset *ds, double C, const double *w, double *g, double *gn
 }
 
 // Hv = v + C X^T (D (X v)) with D = Dbuf[Dcur]; scal_dev[0] = v.Hv.  Enqueue only.
-int hv_enqueue(tron_dataset *ds, double C, const double *v, double *Hv)
+// vhv_partials not null: a caller whose next kernel can add up the per-workgroup partial sums of v.Hv itself (they lie at
+// the start of ds->partials); where there are few enough of them their number comes back there and scalar 0 is not
+// formed, otherwise 0 comes back and scalar 0 is.
+int hv_enqueue(tron_dataset *ds, double C, const double *v, double *Hv, int *vhv_partials)
 {
+    if (vhv_partials) *vhv_partials = 0;
     if (ds->dense) return dense_hv(ds, C, ds->Dcur, v, Hv);
     const double *D = ds->Dbuf[ds->Dcur];
     TRON_TRY(spmv_scale(ds, ds->fwd, SLOT_SPMV_FWD, v, D, ds->z, ds->bwd.col_scale));   // a1 = D (X v)
-    const int g = spmv_axpy(ds, ds->bwd, SLOT_SPMV_BWD, ds->z, v, C, false, Hv, false, ds->bwd.col_scale != nullptr, 0);  // Hv = v + C X^T a1
+    const bool direct = vhv_partials && vec_workgroups(ds->d) <= kCgDirectGrid;
+    const int g = spmv_axpy(ds, ds->bwd, SLOT_SPMV_BWD, ds->z, v, C, false, Hv, false, ds->bwd.col_scale != nullptr, direct ? -1 : 0);  // Hv = v + C X^T a1
     TRON_TRY(g);
+    if (direct && g <= kCgDirectGrid) {
+        *vhv_partials = g;
+        return TRON_OK;
+    }
     TRON_TRY(reduce_final(ds, 1, g, 0, 0));
     return TRON_OK;
 }
@@ -136,9 +145,10 @@ int cg_solve(tron_dataset *ds, const tron_params &P, const double *M, double del
     const bool ahead = g_tuning.cg_speculate > 0 || (g_tuning.cg_speculate < 0 && products_cheap(ds));
     int n_dir = 0;   // workgroups of the direction kernel enqueued last
     auto enqueue = [&](int it) -> int {
-        TRON_TRY(hv_enqueue(ds, P.C, p, Hp));   // scalar 0 = p.Hp
+        int n_php = 0;   // per-workgroup partial sums of p.Hp left for the step kernel (0: the sum is in scalar 0)
+        TRON_TRY(hv_enqueue(ds, P.C, p, Hp, &n_php));
         const CgStepCtl ctl{tol, delta, it};
-        const int g1 = cg_step(ds, ctl, n_dir, p, Hp, M, s, r);
+        const int g1 = cg_step(ds, ctl, n_dir, n_php, p, Hp, M, s, r);
         TRON_TRY(g1);
         const bool direct = g1 <= kCgDirectGrid;   // the consumer adds up the partial sums itself
         const bool last = it + 1 >= P.max_cg;      // the last iteration allowed: no direction after it
