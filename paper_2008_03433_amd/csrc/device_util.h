@@ -164,7 +164,7 @@ __device__ __forceinline__ void finish_partials(const Finish &f, const double *p
 }
 
 // log(1 + e) for 0 <= e <= 1, as 2 atanh(u) with u = e / (2 + e) <= 1/3: the odd series in u up to u^31 (the first
-// term left out is below 1e-17 of the sum).  Within 2 ulp of the exact value (4.2e-16 relative at worst over 2.6M
+// term left out is below 2e-17 of the sum).  Within 2 ulp of the exact value (4.2e-16 relative at worst over 2.6M
 // arguments e = exp(-t), t in [0, 600], against extended precision on the host; the library's general-argument routine:
 // 1.2e-16) at about a third of that routine's instructions -- in the multi-problem logistic function/gradient pass, which
 // evaluates it once per row and problem, the general routine alone took a quarter of the time.
