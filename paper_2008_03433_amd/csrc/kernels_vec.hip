@@ -284,10 +284,18 @@ __global__ __launch_bounds__(kBlock) void k_cg_step(int64_t d, CgStepCtl ctl, in
 
 int vec_workgroups(int64_t m) { return vec_grid(m); }
 
+// The step and direction kernels run with at most kCgDirectGrid workgroups, so that each can add up the other's partial
+// sums itself whatever d is (longer loops per thread instead of more workgroups).
+static inline int cg_grid(int64_t m)
+{
+    const int g = vec_grid(m);
+    return g < kCgDirectGrid ? g : kCgDirectGrid;
+}
+
 int cg_step(tron_dataset *ds, const CgStepCtl &ctl, int n_dir, int n_php, const double *p, const double *Hp, const double *M, double *s, double *r)
 {
     ProfScope ps(ds, SLOT_CG_VEC);
-    const int g = vec_grid(ds->d);
+    const int g = cg_grid(ds->d);
     if (M) hipLaunchKernelGGL(k_cg_step<true>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, ctl, n_dir, n_php, ds->partials, ds->scal_copy, p, Hp, M, s, r, ds->cg_partials, ds->scal_dev, ds->scal_copy);
     else hipLaunchKernelGGL(k_cg_step<false>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, ctl, n_dir, n_php, ds->partials, ds->scal_copy, p, Hp, M, s, r, ds->cg_partials, ds->scal_dev, ds->scal_copy);
     TRON_HIP(hipGetLastError());
@@ -341,7 +349,7 @@ __global__ __launch_bounds__(kBlock) void k_cg_dir(int64_t d, CgStepCtl ctl, int
 int cg_dir(tron_dataset *ds, const CgStepCtl &ctl, int n_step, const double *r, const double *s, const double *M, double *p)
 {
     ProfScope ps(ds, SLOT_CG_VEC);
-    const int g = vec_grid(ds->d);
+    const int g = cg_grid(ds->d);
     if (M) hipLaunchKernelGGL(k_cg_dir<true>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, ctl, n_step, ds->scal_copy, r, s, M, p, ds->cg_partials, ds->scal_dev, ds->scal_copy);
     else hipLaunchKernelGGL(k_cg_dir<false>, dim3(g), dim3(kBlock), 0, ds->stream, ds->d, ctl, n_step, ds->scal_copy, r, s, M, p, ds->cg_partials, ds->scal_dev, ds->scal_copy);
     TRON_HIP(hipGetLastError());
